@@ -1,0 +1,222 @@
+/*
+ * fb.h -- C ABI of the MI355X forward-backward / LF-MMI library (libfb_amd.so).
+ *
+ * The library computes, on one gfx950 GPU and in the log semifield of the
+ * paper (Semiring-algebra section, Eq. 8-12: a (+) b = log(e^a + e^b),
+ * a (x) b = a + b, zero = -inf, one = 0):
+ *
+ *   fb_alpha         alpha_n = v_n o (T^t alpha_{n-1})                 Eq. 13
+ *   fb_beta          beta_n  = T (beta_{n+1} o v_{n+1})                Eq. 14
+ *   fb_posteriors    p(z_n | x) = alpha_n beta_n / sum_z alpha_N(z)    Eq. 15
+ *   lfmmi_loss_grad  L = log p(X|G_num) - log p(X|G_den), dL/dphi      Eq. 16-17
+ *
+ * for a batch of sequences (Dealing-with-batches section).  All logs are
+ * natural.  Frames and states are numbered from 0.
+ *
+ * Model.  A graph has K states and E arcs (src -> dst, log-weight logw); only
+ * arcs that are not the semiring zero are stored.  State k emits through pdf
+ * pdf[k] in [0, D): v_n[k] = emis[b][n][pdf[k]].  alpha_0 = init (x) v_0 (the
+ * first state emits the first frame, so T frames use T-1 arcs),
+ * beta_{T-1} = final, log Z = (+)-sum_k alpha_{T-1}[k] (x) final[k].
+ * -inf is a legal value of init, final, logw and emis; NaN and +inf are not.
+ * Parallel arcs are kept apart (their weights (+)-add).
+ *
+ * Two kinds of graph:
+ *   shared  one graph used by every sequence of the batch (the denominator
+ *           graph; the paper replicates it on the block diagonal, here it is
+ *           stored once);
+ *   packed  n_seq graphs concatenated block-diagonally, sequence b owning the
+ *           states [state_off[b], state_off[b+1]) (numerator graphs).
+ *
+ * Pointers.  Unless a comment says "host", every array argument of a compute
+ * call is a DEVICE pointer owned by the caller; the library neither allocates
+ * nor frees nor synchronises in a compute call, it only enqueues kernels on
+ * `stream` (a hipStream_t, NULL = the default stream).  Inputs are read-only.
+ * Outputs are overwritten in full unless stated.
+ *
+ * Layouts (row-major, last index fastest):
+ *   emis, pdf_post, grad   float [B][N][D]
+ *   lengths                int32 [B]; sequence b has lengths[b] real frames,
+ *                          the rest of its N frames is padding and is ignored.
+ *                          A length is clamped to [0, N]; a sequence of length
+ *                          0 is skipped (log Z = -inf, zero posteriors, no
+ *                          contribution to the loss).
+ *   alpha, beta, state_post
+ *       shared graph       float [B][N][K]
+ *       packed graphs      float [N][K]   (K = all states of all sequences;
+ *                                          sequence b fills its own columns)
+ *   alpha_off, beta_off    float [B][N]
+ *   logz                   double [B]
+ *
+ * Normalised storage.  Stored alpha/beta rows are shifted so that single
+ * precision keeps its resolution on long sequences:
+ *   true alpha_n[k] = alpha[..n..][k] + sum_{m <= n} alpha_off[b][m]
+ *   true beta_n[k]  = beta[..n..][k]  + sum_{m >= n} beta_off[b][m]
+ * (sum the offsets in double).  The shifts cancel in Eq. 15, so posteriors do
+ * not depend on them.  Rows of padded frames hold -inf (alpha, beta) or 0
+ * (offsets, posteriors, grad).
+ *
+ * Errors.  Every call returns FB_OK (0) or a negative code and never throws;
+ * fb_last_error() gives a thread-local description of the last failure.
+ * Kernel launches are asynchronous: an error inside a kernel surfaces at the
+ * caller's next synchronisation.  A sequence with no complete path has
+ * log Z = -inf and zero posteriors / gradient -- that is not an error.
+ */
+#ifndef FB_AMD_H
+#define FB_AMD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fb_graph fb_graph; /* opaque; owns host and device copies of its layouts */
+typedef void *fb_stream;          /* hipStream_t */
+
+enum {
+    FB_OK = 0,
+    FB_EINVAL = -1,      /* malformed argument (see each call)                       */
+    FB_ENOMEM = -2,      /* host or device allocation failed                         */
+    FB_EHIP = -3,        /* a HIP runtime call failed (no device, launch error, ...) */
+    FB_EUNSUPPORTED = -4 /* valid input beyond a documented limit of the kernels     */
+};
+
+/* fb_graph_create flags */
+enum {
+    FB_GRAPH_HOST_ONLY = 1 /* build and keep the layouts on the host only: no GPU is touched;
+                              the handle serves fb_graph_layout* but no compute call */
+};
+
+/* Arrays that fb_graph_layout can copy out (graph-layout step; integer work, one
+ * well-defined answer).  "in" = arcs stably sorted by destination (what T^t of
+ * Eq. 13 gathers), "out" = arcs stably sorted by source (T of Eq. 14); "stable"
+ * = ties keep ascending original arc index.  *_PERM[i] is the original index
+ * of the i-th sorted arc; *_W the weights permuted, never altered. */
+enum {
+    FB_IN_PTR = 0,     /* int32 [K+1]  arcs entering state j are IN_*[ptr[j] .. ptr[j+1])  */
+    FB_IN_SRC = 1,     /* int32 [E]                                                          */
+    FB_IN_W = 2,       /* float [E]                                                          */
+    FB_IN_PERM = 3,    /* int32 [E]                                                          */
+    FB_OUT_PTR = 4,    /* int32 [K+1]  arcs leaving state i are OUT_*[ptr[i] .. ptr[i+1])   */
+    FB_OUT_DST = 5,    /* int32 [E]                                                          */
+    FB_OUT_W = 6,      /* float [E]                                                          */
+    FB_OUT_PERM = 7,   /* int32 [E]                                                          */
+    FB_PDF_PTR = 8,    /* int32 [D+1]  states tied to pdf d are PDF_STATES[ptr[d] .. ptr[d+1]) */
+    FB_PDF_STATES = 9  /* int32 [K]    states stably sorted by pdf id                        */
+};
+
+/*
+ * Build a graph (graph-layout step; Matrix-based-implementation section: T[i][j]
+ * is the weight of arc i -> j, stored sparsely).
+ *   src, dst, logw  host, [E], arcs in any order
+ *   pdf, init, final host, [K]
+ *   D               number of pdfs (columns of emis)
+ *   n_seq, state_off  n_seq = 0 and NULL: shared graph.  n_seq = B > 0 and host
+ *                   int32 [B+1]: packed graphs, state_off[0] = 0, non-decreasing,
+ *                   state_off[B] = K, every graph non-empty.
+ * The arrays are copied; the caller may free them on return.
+ * FB_EINVAL: NULL pointer, K <= 0, E < 0, D <= 0, an arc endpoint outside [0,K),
+ *   a pdf id outside [0,D), a NaN or +inf weight / init / final, bad state_off,
+ *   an arc joining two packed graphs.  FB_EUNSUPPORTED: a (sub-)graph too large
+ *   for the on-chip state vector (see fb_limits).  FB_EHIP / FB_ENOMEM: upload failed.
+ */
+int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, const int32_t *dst,
+                    const float *logw, const int32_t *pdf, const float *init, const float *final_,
+                    int32_t D, int32_t n_seq, const int32_t *state_off, uint32_t flags);
+
+/* Free a graph and its device memory.  NULL is allowed.  The caller must have
+ * synchronised every stream that still uses it. */
+int fb_graph_destroy(fb_graph *g);
+
+/* Number of elements of layout array `which`, or a negative error code. */
+int64_t fb_graph_layout_size(const fb_graph *g, int which);
+
+/* Copy layout array `which` to host_out (host pointer); bytes must be exactly
+ * 4 * fb_graph_layout_size().  FB_EINVAL otherwise. */
+int fb_graph_layout(const fb_graph *g, int which, void *host_out, size_t bytes);
+
+/*
+ * Diagnostic, host only: apply the static work plan the kernels walk for this
+ * graph, on the host and in double precision, to a vector x (host).
+ *   which = 0  forward plan:  y[j] = (+)-sum over arcs entering j of (w (x) x[src]), log2 units
+ *   which = 1  backward plan: y[i] = (+)-sum over arcs leaving i of (w (x) x[dst]), log2 units
+ *   which = 2  pdf plan:      y[d] = sum of x over the states tied to pdf d (ordinary sum)
+ * sub: 0 for a shared graph, the sequence index for packed graphs; x and y use
+ * the sub-graph's local state numbering (y: pdf ids for which = 2; entries
+ * without a row keep their value).  Weights are the graph's log-weights times
+ * log2(e), rounded to float.  Lets a CPU-only test check the scheduling logic.
+ */
+int fb_graph_schedule_apply_host(const fb_graph *g, int which, int32_t sub, const double *x, double *y);
+
+/* Host-side check of a host copy of lengths: FB_EINVAL if NULL, B <= 0, N <= 0
+ * or any length is outside [1, N].  (The compute calls themselves only see the
+ * device copy and clamp.) */
+int fb_check_lengths(const int32_t *lengths_host, int32_t B, int32_t N);
+
+/*
+ * Forward recursion, Eq. 13, for every sequence of the batch.
+ *   alpha      out, nullable (then only the offsets and log Z are produced)
+ *   alpha_off  out, float [B][N], nullable
+ *   logz       out, double [B], nullable: log Z_b = (+)-sum_k alpha_{T-1}[k] (x) final[k]
+ * FB_EINVAL: g NULL or host-only, emis / lengths NULL, B/N/D <= 0, D != the graph's D,
+ *   packed graph with B != n_seq.  FB_EUNSUPPORTED: K and D together exceed the
+ *   on-chip memory of a compute unit (fb_limits).
+ */
+int fb_alpha(const fb_graph *g, const float *emis, const int32_t *lengths, int32_t B, int32_t N, int32_t D,
+             float *alpha, float *alpha_off, double *logz, fb_stream stream);
+
+/*
+ * Backward recursion, Eq. 14 (with v_{n+1}, as in the scalar Eq. 3).
+ *   beta, beta_off  out, nullable, as for fb_alpha
+ *   logz            out, nullable: log Z_b evaluated at the first frame,
+ *                   (+)-sum_k init[k] (x) v_0[k] (x) beta_0[k]; equals fb_alpha's up to rounding
+ * Errors as fb_alpha.
+ */
+int fb_beta(const fb_graph *g, const float *emis, const int32_t *lengths, int32_t B, int32_t N, int32_t D,
+            float *beta, float *beta_off, double *logz, fb_stream stream);
+
+/*
+ * State and pdf posteriors, Eq. 15, from the normalised alpha and beta of
+ * fb_alpha / fb_beta (the offsets are not needed: they cancel).
+ *   state_post  out, nullable: gamma[.][n][k] = exp(alpha_n[k] (x) beta_n[k] (/) log Z)
+ *   pdf_post    out, nullable: rho[b][n][d] = sum of gamma over the states tied to pdf d
+ * The normaliser is evaluated on each frame as (+)-sum_k alpha_n[k] (x) beta_n[k],
+ * which equals log Z for every n, so rounding accumulated along the recursion
+ * cancels.  Padded frames get 0.  Errors as fb_alpha (alpha, beta, lengths must
+ * not be NULL; at least one output must be given).
+ */
+int fb_posteriors(const fb_graph *g, const float *alpha, const float *beta, const int32_t *lengths,
+                  int32_t B, int32_t N, int32_t D, float *state_post, float *pdf_post, fb_stream stream);
+
+/* Bytes of device workspace lfmmi_loss_grad needs for these sizes (0 on bad arguments). */
+size_t fb_lfmmi_workspace_bytes(const fb_graph *den, const fb_graph *num, int32_t B, int32_t N, int32_t D);
+
+/*
+ * LF-MMI objective and its derivative w.r.t. the network output (Eq. 16-17):
+ *   loss  = sum_b ( log Z_num[b] - log Z_den[b] )          (no sign flip, no averaging)
+ *   grad[b][n][d] = rho_num[b][n][d] - rho_den[b][n][d]    (0 on padded frames)
+ *   den   shared graph, num packed graphs with n_seq = B, both built with this D
+ *   loss  out, device double [1]; logz_num, logz_den out, device double [B], nullable
+ *   ws    device scratch of at least fb_lfmmi_workspace_bytes(), 256-byte aligned;
+ *         its contents are undefined before and after the call
+ * FB_EINVAL: as fb_alpha, or ws too small / NULL, den packed, num shared.
+ */
+int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths,
+                    int32_t B, int32_t N, int32_t D, double *loss, double *logz_num, double *logz_den,
+                    float *grad, void *ws, size_t ws_bytes, fb_stream stream);
+
+/* Limits of the kernels for a graph / batch shape: the largest number of states
+ * one (sub-)graph may have so that its state vectors and one emission row of D
+ * pdfs fit in the 160 KB of on-chip memory of a gfx950 compute unit.
+ * shared != 0: shared-graph kernels; 0: packed-graph kernels. */
+int32_t fb_limits_max_states(int32_t D, int shared);
+
+const char *fb_strerror(int code);
+const char *fb_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FB_AMD_H */

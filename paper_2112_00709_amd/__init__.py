@@ -1,0 +1,242 @@
+"""Python binding of libfb_amd.so (include/fb.h): argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; PyTorch is used for
+device memory and the current stream, nothing else.  There is no CPU fallback:
+if the shared library is missing or a call fails, an exception is raised.
+
+The functions carry the names of the C entry points:
+``fb_graph_create``, ``fb_graph_layout``, ``fb_alpha``, ``fb_beta``,
+``fb_posteriors``, ``lfmmi_loss_grad``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfb_amd.so")
+
+FB_OK, FB_EINVAL, FB_ENOMEM, FB_EHIP, FB_EUNSUPPORTED = 0, -1, -2, -3, -4
+FB_GRAPH_HOST_ONLY = 1
+LAYOUT = {"in_ptr": 0, "in_src": 1, "in_w": 2, "in_perm": 3, "out_ptr": 4, "out_dst": 5, "out_w": 6,
+          "out_perm": 7, "pdf_ptr": 8, "pdf_states": 9}
+
+# every symbol include/fb.h declares
+SYMBOLS = ["fb_graph_create", "fb_graph_destroy", "fb_graph_layout_size", "fb_graph_layout", "fb_check_lengths",
+           "fb_alpha", "fb_beta", "fb_posteriors", "fb_lfmmi_workspace_bytes", "lfmmi_loss_grad",
+           "fb_limits_max_states", "fb_strerror", "fb_last_error", "fb_graph_schedule_apply_host"]
+
+
+class FBError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libfb_amd error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the built library (fails loudly when it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, u32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32, ctypes.c_size_t
+        L.fb_graph_create.argtypes = [ctypes.POINTER(vp), i32, i64, vp, vp, vp, vp, vp, vp, i32, i32, vp, u32]
+        L.fb_graph_create.restype = ctypes.c_int
+        L.fb_graph_destroy.argtypes = [vp]
+        L.fb_graph_destroy.restype = ctypes.c_int
+        L.fb_graph_layout_size.argtypes = [vp, ctypes.c_int]
+        L.fb_graph_layout_size.restype = i64
+        L.fb_graph_layout.argtypes = [vp, ctypes.c_int, vp, sz]
+        L.fb_graph_layout.restype = ctypes.c_int
+        L.fb_graph_schedule_apply_host.argtypes = [vp, ctypes.c_int, i32, vp, vp]
+        L.fb_graph_schedule_apply_host.restype = ctypes.c_int
+        L.fb_check_lengths.argtypes = [vp, i32, i32]
+        L.fb_check_lengths.restype = ctypes.c_int
+        L.fb_alpha.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp]
+        L.fb_alpha.restype = ctypes.c_int
+        L.fb_beta.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp]
+        L.fb_beta.restype = ctypes.c_int
+        L.fb_posteriors.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp]
+        L.fb_posteriors.restype = ctypes.c_int
+        L.fb_lfmmi_workspace_bytes.argtypes = [vp, vp, i32, i32, i32]
+        L.fb_lfmmi_workspace_bytes.restype = sz
+        L.lfmmi_loss_grad.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.lfmmi_loss_grad.restype = ctypes.c_int
+        L.fb_limits_max_states.argtypes = [i32, ctypes.c_int]
+        L.fb_limits_max_states.restype = i32
+        L.fb_strerror.argtypes = [ctypes.c_int]
+        L.fb_strerror.restype = ctypes.c_char_p
+        L.fb_last_error.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != FB_OK:
+        raise FBError(rc, (lib().fb_last_error() or b"").decode() or lib().fb_strerror(rc).decode())
+
+
+def _np(a, dtype):
+    return None if a is None else np.ascontiguousarray(a, dtype=dtype)
+
+
+def _hp(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+class Graph:
+    """Owner of an ``fb_graph*``."""
+
+    def __init__(self, handle, K, E, D, n_seq, host_only):
+        self._h, self.K, self.E, self.D, self.n_seq, self.host_only = handle, K, E, D, n_seq, host_only
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise ValueError("graph already destroyed")
+        return self._h
+
+    @property
+    def shared(self) -> bool:
+        return self.n_seq == 0
+
+    def destroy(self) -> None:
+        if self._h is not None:
+            h, self._h = self._h, None
+            _check(lib().fb_graph_destroy(h))
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def fb_graph_create(K, src, dst, logw, pdf, init, final, D, state_off=None, host_only=False) -> Graph:
+    src, dst, logw = _np(src, np.int32), _np(dst, np.int32), _np(logw, np.float32)
+    pdf, init, final = _np(pdf, np.int32), _np(init, np.float32), _np(final, np.float32)
+    state_off = _np(state_off, np.int32)
+    E = 0 if src is None else int(src.shape[0])
+    n_seq = 0 if state_off is None else int(state_off.shape[0]) - 1
+    h = ctypes.c_void_p()
+    _check(lib().fb_graph_create(ctypes.byref(h), int(K), E, _hp(src), _hp(dst), _hp(logw), _hp(pdf), _hp(init),
+                                 _hp(final), int(D), n_seq, _hp(state_off), FB_GRAPH_HOST_ONLY if host_only else 0))
+    return Graph(h, int(K), E, int(D), n_seq, host_only)
+
+
+def graph_from(g, D: int, host_only: bool = False) -> Graph:
+    """Build from an object with fields K, src, dst, logw, pdf, init, final, state_off."""
+    return fb_graph_create(g.K, g.src, g.dst, g.logw, g.pdf, g.init, g.final, D, g.state_off, host_only)
+
+
+def fb_graph_layout(g: Graph, name: str) -> np.ndarray:
+    which = LAYOUT[name]
+    n = lib().fb_graph_layout_size(g.handle, which)
+    if n < 0:
+        _check(int(n))
+    out = np.empty(int(n), dtype=np.float32 if name.endswith("_w") else np.int32)
+    _check(lib().fb_graph_layout(g.handle, which, _hp(out), out.nbytes))
+    return out
+
+
+def fb_graph_schedule_apply_host(g: Graph, which: int, sub: int, x: np.ndarray, y: np.ndarray) -> np.ndarray:
+    x = _np(x, np.float64)
+    assert y.dtype == np.float64 and y.flags.c_contiguous
+    _check(lib().fb_graph_schedule_apply_host(g.handle, which, sub, _hp(x), _hp(y)))
+    return y
+
+
+def fb_check_lengths(lengths, N: int) -> None:
+    lengths = _np(lengths, np.int32)
+    _check(lib().fb_check_lengths(_hp(lengths), int(lengths.shape[0]), int(N)))
+
+
+def fb_limits_max_states(D: int, shared: bool) -> int:
+    return int(lib().fb_limits_max_states(int(D), 1 if shared else 0))
+
+
+# ----------------------------------------------------------------- device calls
+
+def _torch():
+    import torch
+    return torch
+
+
+def _dp(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(_torch().cuda.current_stream().cuda_stream)
+
+
+def _dev_inputs(emis, lengths):
+    torch = _torch()
+    if not (emis.is_cuda and emis.dtype == torch.float32 and emis.is_contiguous() and emis.dim() == 3):
+        raise ValueError("emis must be a contiguous float32 CUDA tensor [B, N, D]")
+    if not (lengths.is_cuda and lengths.dtype == torch.int32 and lengths.is_contiguous()
+            and lengths.shape == (emis.shape[0],)):
+        raise ValueError("lengths must be a contiguous int32 CUDA tensor [B]")
+    return tuple(int(s) for s in emis.shape)
+
+
+def _vec_shape(g: Graph, B: int, N: int):
+    return (B, N, g.K) if g.shared else (N, g.K)
+
+
+def _recursion(fn, g: Graph, emis, lengths, want_vectors: bool):
+    torch = _torch()
+    B, N, D = _dev_inputs(emis, lengths)
+    vec = torch.empty(_vec_shape(g, B, N), dtype=torch.float32, device=emis.device) if want_vectors else None
+    off = torch.empty((B, N), dtype=torch.float32, device=emis.device)
+    logz = torch.empty((B,), dtype=torch.float64, device=emis.device)
+    _check(fn(g.handle, _dp(emis), _dp(lengths), B, N, D, _dp(vec), _dp(off), _dp(logz), _stream()))
+    return vec, off, logz
+
+
+def fb_alpha(g: Graph, emis, lengths, want_vectors: bool = True):
+    """-> (alpha, alpha_off [B,N], logz [B]); alpha is [B,N,K] (shared) or [N,K] (packed)."""
+    return _recursion(lib().fb_alpha, g, emis, lengths, want_vectors)
+
+
+def fb_beta(g: Graph, emis, lengths, want_vectors: bool = True):
+    """-> (beta, beta_off [B,N], logz [B])."""
+    return _recursion(lib().fb_beta, g, emis, lengths, want_vectors)
+
+
+def fb_posteriors(g: Graph, alpha, beta, lengths, B: int, N: int, want_state: bool = True, want_pdf: bool = True):
+    """-> (state_post like alpha, pdf_post [B,N,D])."""
+    torch = _torch()
+    state = torch.empty_like(alpha) if want_state else None
+    pdfp = torch.empty((B, N, g.D), dtype=torch.float32, device=alpha.device) if want_pdf else None
+    _check(lib().fb_posteriors(g.handle, _dp(alpha), _dp(beta), _dp(lengths), B, N, g.D, _dp(state), _dp(pdfp), _stream()))
+    return state, pdfp
+
+
+def fb_lfmmi_workspace_bytes(den: Graph, num: Graph, B: int, N: int, D: int) -> int:
+    return int(lib().fb_lfmmi_workspace_bytes(den.handle, num.handle, B, N, D))
+
+
+def lfmmi_loss_grad(den: Graph, num: Graph, emis, lengths, ws=None, grad=None):
+    """-> (loss [1] float64, logz_num [B], logz_den [B], grad [B,N,D]), all on the device.
+    ``ws`` (uint8 CUDA tensor of fb_lfmmi_workspace_bytes) and ``grad`` may be passed in for reuse."""
+    torch = _torch()
+    B, N, D = _dev_inputs(emis, lengths)
+    need = fb_lfmmi_workspace_bytes(den, num, B, N, D)
+    if ws is None:
+        ws = torch.empty((need,), dtype=torch.uint8, device=emis.device)
+    if grad is None:
+        grad = torch.empty((B, N, D), dtype=torch.float32, device=emis.device)
+    loss = torch.empty((1,), dtype=torch.float64, device=emis.device)
+    zn = torch.empty((B,), dtype=torch.float64, device=emis.device)
+    zd = torch.empty((B,), dtype=torch.float64, device=emis.device)
+    _check(lib().lfmmi_loss_grad(den.handle, num.handle, _dp(emis), _dp(lengths), B, N, D, _dp(loss), _dp(zn), _dp(zd),
+                                 _dp(grad), _dp(ws), int(ws.numel()), _stream()))
+    return loss, zn, zd, grad

@@ -1,0 +1,183 @@
+// The compute entry points of the C ABI: argument checks and kernel launches.
+#include <algorithm>
+
+#include "fb_internal.h"
+
+using namespace fb;
+
+namespace {
+
+constexpr float kLn2f = 0.69314718055994530942f;
+constexpr float kLog2ef = 1.44269504088896340736f;
+
+int check_common(const char *who, const fb_graph *g, const void *p1, const void *p2, int32_t B, int32_t N, int32_t D)
+{
+    const std::string w(who);
+    if (!g) return fail(FB_EINVAL, w + ": graph is NULL");
+    if (g->host_only) return fail(FB_EINVAL, w + ": graph was created with FB_GRAPH_HOST_ONLY");
+    if (!p1 || !p2) return fail(FB_EINVAL, w + ": NULL input array");
+    if (B <= 0 || N <= 0 || D <= 0) return fail(FB_EINVAL, w + ": B, N and D must be positive");
+    if (D != g->D) return fail(FB_EINVAL, w + ": D differs from the graph's D");
+    if (g->n_seq > 0 && B != g->n_seq) return fail(FB_EINVAL, w + ": B differs from the number of packed graphs");
+    return FB_OK;
+}
+
+RecDir make_dir(const fb_graph *g, bool backward, float *out, float *off, double *logz, float out_scale,
+                bool fill_pad = true)
+{
+    RecDir r{};
+    r.sched = backward ? g->bwd : g->fwd;
+    r.bound = backward ? g->d_final2 : g->d_init2;
+    r.obound = backward ? g->d_init2 : g->d_final2;
+    r.out = out;
+    r.off = off;
+    r.logz = logz;
+    r.out_scale = out_scale;
+    r.backward = backward ? 1 : 0;
+    r.fill_pad = fill_pad ? 1 : 0;
+    return r;
+}
+
+int run_recursion(const fb_graph *g, const float *emis, const int32_t *lengths, int32_t B, int32_t N, int32_t D,
+                  const RecDir *dirs, int n_dir, fb_stream stream)
+{
+    RecParams p{};
+    bool any_bwd = false;
+    for (int i = 0; i < n_dir; ++i) {
+        p.dir[i] = dirs[i];
+        any_bwd = any_bwd || dirs[i].backward;
+    }
+    p.n_dir = n_dir;
+    p.pdf = g->d_pdf;
+    p.emis = emis;
+    p.lengths = lengths;
+    p.B = B; p.N = N; p.D = D;
+    p.shared = g->n_seq == 0;
+    p.Ktot = g->K;
+    p.Kcap = g->max_sub_K;
+    p.Pcap = std::max(g->h_fwd.max_part, g->h_bwd.max_part);
+    p.Ecap = p.shared ? D : g->max_sub_K;
+    p.any_backward = any_bwd;
+    const size_t lds = recursion_lds_bytes(p.Kcap, p.Pcap, p.Ecap, any_bwd);
+    if (lds > kLdsBytes) return fail(FB_EUNSUPPORTED, "state vectors and emission rows exceed the on-chip memory");
+    return launch_recursion(g->nw, p, lds, stream);
+}
+
+PostGraph make_post(const fb_graph *g, const float *a, const float *b, float in_scale, float *state_post)
+{
+    PostGraph q{};
+    q.pdfs = g->pdfs;
+    q.sub = g->pdfs.sub;
+    q.a = a;
+    q.b = b;
+    q.in_scale = in_scale;
+    q.shared = g->n_seq == 0;
+    q.Ktot = g->K;
+    q.state_post = state_post;
+    return q;
+}
+
+int run_posteriors(const PostGraph *gs, const fb_graph *const *graphs, int n_graph, const int32_t *lengths, int32_t B,
+                   int32_t N, int32_t D, float *pdf_out, fb_stream stream)
+{
+    PostParams p{};
+    p.n_graph = n_graph;
+    for (int i = 0; i < n_graph; ++i) {
+        p.g[i] = gs[i];
+        p.Kcap = std::max(p.Kcap, graphs[i]->max_sub_K);
+        p.Pcap = std::max(p.Pcap, graphs[i]->h_pdf.max_part);
+    }
+    p.lengths = lengths;
+    p.B = B; p.N = N; p.D = D;
+    p.pdf_out = pdf_out;
+    p.frames_per_block = 4;
+    const size_t lds = posterior_lds_bytes(p.Kcap, p.Pcap, D);
+    if (lds > kLdsBytes) return fail(FB_EUNSUPPORTED, "state vector and pdf row exceed the on-chip memory");
+    return launch_posteriors(p, lds, stream);
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+}  // namespace
+
+extern "C" {
+
+int fb_alpha(const fb_graph *g, const float *emis, const int32_t *lengths, int32_t B, int32_t N, int32_t D, float *alpha,
+             float *alpha_off, double *logz, fb_stream stream)
+{
+    int rc = check_common("fb_alpha", g, emis, lengths, B, N, D);
+    if (rc) return rc;
+    const RecDir d = make_dir(g, false, alpha, alpha_off, logz, kLn2f);
+    return run_recursion(g, emis, lengths, B, N, D, &d, 1, stream);
+}
+
+int fb_beta(const fb_graph *g, const float *emis, const int32_t *lengths, int32_t B, int32_t N, int32_t D, float *beta,
+            float *beta_off, double *logz, fb_stream stream)
+{
+    int rc = check_common("fb_beta", g, emis, lengths, B, N, D);
+    if (rc) return rc;
+    const RecDir d = make_dir(g, true, beta, beta_off, logz, kLn2f);
+    return run_recursion(g, emis, lengths, B, N, D, &d, 1, stream);
+}
+
+int fb_posteriors(const fb_graph *g, const float *alpha, const float *beta, const int32_t *lengths, int32_t B, int32_t N,
+                  int32_t D, float *state_post, float *pdf_post, fb_stream stream)
+{
+    int rc = check_common("fb_posteriors", g, alpha, beta, B, N, D);
+    if (rc) return rc;
+    if (!lengths) return fail(FB_EINVAL, "fb_posteriors: lengths is NULL");
+    if (!state_post && !pdf_post) return fail(FB_EINVAL, "fb_posteriors: no output requested");
+    const PostGraph q = make_post(g, alpha, beta, kLog2ef, state_post);
+    return run_posteriors(&q, &g, 1, lengths, B, N, D, pdf_post, stream);
+}
+
+size_t fb_lfmmi_workspace_bytes(const fb_graph *den, const fb_graph *num, int32_t B, int32_t N, int32_t D)
+{
+    if (!den || !num || B <= 0 || N <= 0 || D <= 0) return 0;
+    const size_t den_vec = align256((size_t)B * N * den->K * sizeof(float));
+    const size_t num_vec = align256((size_t)N * num->K * sizeof(float));
+    const size_t z = align256((size_t)B * sizeof(double));
+    return 2 * den_vec + 2 * num_vec + 2 * z;
+}
+
+int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths, int32_t B,
+                    int32_t N, int32_t D, double *loss, double *logz_num, double *logz_den, float *grad, void *ws,
+                    size_t ws_bytes, fb_stream stream)
+{
+    int rc = check_common("lfmmi_loss_grad", den, emis, lengths, B, N, D);
+    if (rc) return rc;
+    if ((rc = check_common("lfmmi_loss_grad", num, emis, lengths, B, N, D))) return rc;
+    if (den->n_seq != 0) return fail(FB_EINVAL, "lfmmi_loss_grad: the denominator graph must be shared");
+    if (num->n_seq == 0) return fail(FB_EINVAL, "lfmmi_loss_grad: the numerator graphs must be packed");
+    if (!loss || !grad) return fail(FB_EINVAL, "lfmmi_loss_grad: loss or grad is NULL");
+    const size_t need = fb_lfmmi_workspace_bytes(den, num, B, N, D);
+    if (!ws || ws_bytes < need) return fail(FB_EINVAL, "lfmmi_loss_grad: workspace missing or too small");
+    if (((uintptr_t)ws & 255) != 0) return fail(FB_EINVAL, "lfmmi_loss_grad: workspace must be 256-byte aligned");
+
+    // workspace: forward and backward vectors of both graphs in log2 units, log Z when the caller keeps none
+    char *w = (char *)ws;
+    const size_t den_vec = align256((size_t)B * N * den->K * sizeof(float));
+    const size_t num_vec = align256((size_t)N * num->K * sizeof(float));
+    float *den_a = (float *)w; w += den_vec;
+    float *den_b = (float *)w; w += den_vec;
+    float *num_a = (float *)w; w += num_vec;
+    float *num_b = (float *)w; w += num_vec;
+    double *zn = logz_num ? logz_num : (double *)w; w += align256((size_t)B * sizeof(double));
+    double *zd = logz_den ? logz_den : (double *)w;
+
+    // both recursions of a graph run side by side in one launch
+    RecDir dn[2] = {make_dir(num, false, num_a, nullptr, zn, 1.0f, false),
+                    make_dir(num, true, num_b, nullptr, nullptr, 1.0f, false)};
+    if ((rc = run_recursion(num, emis, lengths, B, N, D, dn, 2, stream))) return rc;
+    RecDir dd[2] = {make_dir(den, false, den_a, nullptr, zd, 1.0f, false),
+                    make_dir(den, true, den_b, nullptr, nullptr, 1.0f, false)};
+    if ((rc = run_recursion(den, emis, lengths, B, N, D, dd, 2, stream))) return rc;
+
+    // Eq. 17: numerator pdf posteriors minus denominator pdf posteriors
+    const PostGraph q[2] = {make_post(num, num_a, num_b, 1.0f, nullptr), make_post(den, den_a, den_b, 1.0f, nullptr)};
+    const fb_graph *gs[2] = {num, den};
+    if ((rc = run_posteriors(q, gs, 2, lengths, B, N, D, grad, stream))) return rc;
+    return launch_loss(zn, zd, lengths, B, loss, stream);
+}
+
+}  // extern "C"

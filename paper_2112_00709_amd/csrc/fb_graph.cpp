@@ -1,0 +1,341 @@
+// Graph handle: validation, the graph-layout step (stable sorts by destination,
+// by source and by pdf), the kernel schedules built from those layouts, upload.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+#include "fb_internal.h"
+
+namespace fb {
+
+static thread_local std::string g_err;
+
+void set_error(const std::string &msg) { g_err = msg; }
+
+int fail(int code, const std::string &msg)
+{
+    g_err = msg;
+    return code;
+}
+
+namespace {
+
+constexpr double kLog2e = 1.4426950408889634074;
+
+// ptr/perm of the stable ascending order of keys in [0, n_keys): counting sort,
+// scanning the input left to right, so ties keep their original order.
+void stable_group(const int32_t *keys, int64_t n, int32_t n_keys, std::vector<int32_t> &ptr, std::vector<int32_t> &perm)
+{
+    ptr.assign((size_t)n_keys + 1, 0);
+    for (int64_t i = 0; i < n; ++i) ++ptr[(size_t)keys[i] + 1];
+    for (int32_t k = 0; k < n_keys; ++k) ptr[k + 1] += ptr[k];
+    perm.resize((size_t)n);
+    std::vector<int32_t> at(ptr.begin(), ptr.end() - 1);
+    for (int64_t i = 0; i < n; ++i) perm[(size_t)at[keys[i]]++] = (int32_t)i;
+}
+
+float to_log2(float x) { return (float)((double)x * kLog2e); }   // -inf stays -inf
+
+template <class T>
+int upload(fb_graph *g, const std::vector<T> &h, const T **dev)
+{
+    *dev = nullptr;
+    if (h.empty()) return FB_OK;
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, h.size() * sizeof(T));
+    if (e != hipSuccess)
+        return fail(e == hipErrorOutOfMemory ? FB_ENOMEM : FB_EHIP, std::string("hipMalloc: ") + hipGetErrorString(e));
+    g->allocs.push_back(p);
+    e = hipMemcpy(p, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return fail(FB_EHIP, std::string("hipMemcpy: ") + hipGetErrorString(e));
+    *dev = (const T *)p;
+    return FB_OK;
+}
+
+int upload_sell(fb_graph *g, const SellHost &h, SellDev &d)
+{
+    int rc;
+    if ((rc = upload(g, h.sub, &d.sub))) return rc;
+    if ((rc = upload(g, h.wave_ptr, &d.wave_ptr))) return rc;
+    if ((rc = upload(g, h.slice_trip, &d.slice_trip))) return rc;
+    if ((rc = upload(g, h.slice_arc, &d.slice_arc))) return rc;
+    if ((rc = upload(g, h.row_out, &d.row_out))) return rc;
+    if ((rc = upload(g, h.row_vidx, &d.row_vidx))) return rc;
+    if ((rc = upload(g, h.arcs, &d.arcs))) return rc;
+    return FB_OK;
+}
+
+}  // namespace
+
+size_t recursion_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t Ecap, bool any_backward)
+{
+    return ((size_t)Kcap * (any_backward ? 4 : 2) + (size_t)Pcap + 2 * (size_t)Ecap) * 4 + kLdsReserve;
+}
+
+size_t posterior_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t D)
+{
+    return ((size_t)Kcap + (size_t)Pcap + (size_t)D) * 4 + kLdsReserve;
+}
+
+}  // namespace fb
+
+using namespace fb;
+
+extern "C" {
+
+const char *fb_last_error(void) { return g_err.c_str(); }
+
+const char *fb_strerror(int code)
+{
+    switch (code) {
+    case FB_OK: return "success";
+    case FB_EINVAL: return "invalid argument";
+    case FB_ENOMEM: return "out of memory";
+    case FB_EHIP: return "HIP runtime error";
+    case FB_EUNSUPPORTED: return "input exceeds a limit of the kernels";
+    default: return "unknown error code";
+    }
+}
+
+int32_t fb_limits_max_states(int32_t D, int shared)
+{
+    if (D <= 0) return 0;
+    // backward recursion: four state vectors, partial slots (allow K/8), two emission rows
+    // (D entries for a shared graph, one per state for packed graphs)
+    const double avail = (double)kLdsBytes - (double)kLdsReserve - (shared ? 8.0 * D : 0.0);
+    const double per_state = 4.0 * (4.0 + 0.125 + (shared ? 0.0 : 2.0));
+    const double k = avail / per_state;
+    return k < 1 ? 0 : (int32_t)k;
+}
+
+int fb_check_lengths(const int32_t *lengths_host, int32_t B, int32_t N)
+{
+    if (!lengths_host || B <= 0 || N <= 0) return fail(FB_EINVAL, "fb_check_lengths: NULL lengths or B, N <= 0");
+    for (int32_t b = 0; b < B; ++b)
+        if (lengths_host[b] < 1 || lengths_host[b] > N)
+            return fail(FB_EINVAL, "length of sequence " + std::to_string(b) + " = " + std::to_string(lengths_host[b]) +
+                                       " is outside [1, " + std::to_string(N) + "]");
+    return FB_OK;
+}
+
+int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, const int32_t *dst, const float *logw,
+                    const int32_t *pdf, const float *init, const float *final_, int32_t D, int32_t n_seq,
+                    const int32_t *state_off, uint32_t flags)
+{
+    if (!out) return fail(FB_EINVAL, "fb_graph_create: out is NULL");
+    *out = nullptr;
+    if (K <= 0 || E < 0 || D <= 0) return fail(FB_EINVAL, "fb_graph_create: K <= 0, E < 0 or D <= 0");
+    if (E > INT32_MAX / 2) return fail(FB_EUNSUPPORTED, "fb_graph_create: more than 2^30 arcs");
+    if ((E > 0 && (!src || !dst || !logw)) || !pdf || !init || !final_)
+        return fail(FB_EINVAL, "fb_graph_create: NULL array");
+    if (n_seq < 0 || (n_seq > 0) != (state_off != nullptr))
+        return fail(FB_EINVAL, "fb_graph_create: n_seq and state_off must be given together");
+    for (int64_t e = 0; e < E; ++e) {
+        if (src[e] < 0 || src[e] >= K || dst[e] < 0 || dst[e] >= K)
+            return fail(FB_EINVAL, "arc " + std::to_string(e) + " has an endpoint outside [0, K)");
+        if (std::isnan(logw[e]) || logw[e] == INFINITY)
+            return fail(FB_EINVAL, "arc " + std::to_string(e) + " has a NaN or +inf weight");
+    }
+    for (int32_t k = 0; k < K; ++k) {
+        if (pdf[k] < 0 || pdf[k] >= D) return fail(FB_EINVAL, "pdf id of state " + std::to_string(k) + " outside [0, D)");
+        if (std::isnan(init[k]) || init[k] == INFINITY || std::isnan(final_[k]) || final_[k] == INFINITY)
+            return fail(FB_EINVAL, "init/final of state " + std::to_string(k) + " is NaN or +inf");
+    }
+    std::vector<int32_t> seq_of;   // packed: sequence of every state
+    if (n_seq > 0) {
+        if (state_off[0] != 0 || state_off[n_seq] != K) return fail(FB_EINVAL, "state_off must run from 0 to K");
+        seq_of.resize((size_t)K);
+        for (int32_t b = 0; b < n_seq; ++b) {
+            if (state_off[b + 1] <= state_off[b]) return fail(FB_EINVAL, "state_off must increase (no empty graph)");
+            if (state_off[b + 1] > K) return fail(FB_EINVAL, "state_off beyond K");
+            for (int32_t k = state_off[b]; k < state_off[b + 1]; ++k) seq_of[(size_t)k] = b;
+        }
+        for (int64_t e = 0; e < E; ++e)
+            if (seq_of[(size_t)src[e]] != seq_of[(size_t)dst[e]])
+                return fail(FB_EINVAL, "arc " + std::to_string(e) + " joins two packed graphs");
+    }
+
+    fb_graph *g = new (std::nothrow) fb_graph;
+    if (!g) return fail(FB_ENOMEM, "fb_graph_create: host allocation failed");
+    int rc = FB_OK;
+    try {
+        g->K = K; g->E = E; g->D = D; g->n_seq = n_seq;
+        g->host_only = (flags & FB_GRAPH_HOST_ONLY) != 0;
+        if (n_seq > 0) g->state_off.assign(state_off, state_off + n_seq + 1);
+
+        // ---- graph-layout step: integer work, weights only permuted
+        HostLayout &L = g->lay;
+        stable_group(dst, E, K, L.in_ptr, L.in_perm);
+        stable_group(src, E, K, L.out_ptr, L.out_perm);
+        stable_group(pdf, K, D, L.pdf_ptr, L.pdf_states);
+        L.in_src.resize((size_t)E); L.in_w.resize((size_t)E); L.out_dst.resize((size_t)E); L.out_w.resize((size_t)E);
+        for (int64_t i = 0; i < E; ++i) {
+            L.in_src[(size_t)i] = src[L.in_perm[(size_t)i]];
+            L.in_w[(size_t)i] = logw[L.in_perm[(size_t)i]];
+            L.out_dst[(size_t)i] = dst[L.out_perm[(size_t)i]];
+            L.out_w[(size_t)i] = logw[L.out_perm[(size_t)i]];
+        }
+
+        // ---- schedules
+        const int32_t n_sub = n_seq > 0 ? n_seq : 1;
+        int64_t max_sub_E = 0;
+        for (int32_t s = 0; s < n_sub; ++s) {
+            const int32_t k0 = n_seq > 0 ? state_off[s] : 0, k1 = n_seq > 0 ? state_off[s + 1] : K;
+            g->max_sub_K = std::max(g->max_sub_K, k1 - k0);
+            max_sub_E = std::max<int64_t>(max_sub_E, (int64_t)L.in_ptr[k1] - L.in_ptr[k0]);
+        }
+        g->nw = (max_sub_E >= 4096 || g->max_sub_K > 1024) ? kNWShared : kNWSmall;
+        g->h_fwd.nw = g->h_bwd.nw = g->nw;
+        g->h_pdf.nw = kNWSmall;   // the posterior kernel always runs four waves
+
+        std::vector<int64_t> ptr;
+        std::vector<int32_t> col, rid, vid;
+        std::vector<float> w;
+        for (int32_t s = 0; s < n_sub; ++s) {
+            const int32_t k0 = n_seq > 0 ? state_off[s] : 0, k1 = n_seq > 0 ? state_off[s + 1] : K, Ks = k1 - k0;
+            rid.resize((size_t)Ks); vid.resize((size_t)Ks);
+            for (int32_t k = 0; k < Ks; ++k) { rid[k] = k; vid[k] = n_seq > 0 ? k : pdf[k0 + k]; }
+            for (int dir = 0; dir < 2; ++dir) {
+                const std::vector<int32_t> &p = dir ? L.out_ptr : L.in_ptr, &other = dir ? L.out_dst : L.in_src;
+                const std::vector<float> &ww = dir ? L.out_w : L.in_w;
+                ptr.assign((size_t)Ks + 1, 0);
+                const int64_t e0 = p[k0], e1 = p[k1];
+                col.resize((size_t)(e1 - e0)); w.resize((size_t)(e1 - e0));
+                for (int32_t k = 0; k <= Ks; ++k) ptr[k] = (int64_t)p[k0 + k] - e0;
+                for (int64_t e = e0; e < e1; ++e) {
+                    col[(size_t)(e - e0)] = other[(size_t)e] - k0;
+                    w[(size_t)(e - e0)] = to_log2(ww[(size_t)e]);
+                }
+                sell_append(dir ? g->h_bwd : g->h_fwd, k0, Ks, Ks, ptr.data(), col.data(), w.data(), rid.data(),
+                            vid.data(), -INFINITY, 0.0f);
+            }
+            // states -> pdfs, ordinary sums: one row per pdf (every pdf for a shared graph, the
+            // pdfs the sub-graph uses for packed graphs), listing the states tied to it
+            std::vector<int32_t> prow, pcol;
+            std::vector<int64_t> pptr{0};
+            if (n_seq == 0) {
+                for (int32_t d = 0; d < D; ++d) {
+                    prow.push_back(d);
+                    for (int32_t i = L.pdf_ptr[d]; i < L.pdf_ptr[d + 1]; ++i) pcol.push_back(L.pdf_states[(size_t)i]);
+                    pptr.push_back((int64_t)pcol.size());
+                }
+            } else {
+                std::vector<int32_t> order((size_t)Ks);
+                std::iota(order.begin(), order.end(), 0);
+                std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return pdf[k0 + a] < pdf[k0 + b]; });
+                for (size_t i = 0; i < order.size(); ++i) {
+                    if (i == 0 || pdf[k0 + order[i]] != pdf[k0 + order[i - 1]]) {
+                        if (i) pptr.push_back((int64_t)pcol.size());
+                        prow.push_back(pdf[k0 + order[i]]);
+                    }
+                    pcol.push_back(order[i]);
+                }
+                pptr.push_back((int64_t)pcol.size());
+            }
+            std::vector<float> ones(pcol.size(), 1.0f);
+            sell_append(g->h_pdf, k0, Ks, (int32_t)prow.size(), pptr.data(), pcol.data(), ones.data(), prow.data(),
+                        nullptr, 0.0f, 1.0f);
+        }
+        {   // nothing a kernel will index may leave its array
+            std::string why;
+            const int32_t nv = n_seq > 0 ? -1 : D;
+            if (!sell_in_bounds(g->h_fwd, -1, nv, why) || !sell_in_bounds(g->h_bwd, -1, nv, why) ||
+                !sell_in_bounds(g->h_pdf, D, 1, why))
+                rc = fail(FB_EHIP, "internal error: schedule out of bounds (" + why + ")");
+        }
+        const int32_t Pcap = std::max(g->h_fwd.max_part, g->h_bwd.max_part);
+        const int32_t Ecap = n_seq > 0 ? g->max_sub_K : D;
+        if (rc == FB_OK && (recursion_lds_bytes(g->max_sub_K, Pcap, Ecap, true) > kLdsBytes ||
+            posterior_lds_bytes(g->max_sub_K, g->h_pdf.max_part, D) > kLdsBytes)) {
+            rc = fail(FB_EUNSUPPORTED, "graph too large: " + std::to_string(g->max_sub_K) + " states, " +
+                                           std::to_string(Pcap) + " partial slots and " + std::to_string(Ecap) +
+                                           " emission entries do not fit the on-chip memory of a compute unit");
+        }
+
+        // ---- upload
+        if (rc == FB_OK && !g->host_only) {
+            std::vector<float> i2((size_t)K), f2((size_t)K);
+            for (int32_t k = 0; k < K; ++k) { i2[k] = to_log2(init[k]); f2[k] = to_log2(final_[k]); }
+            std::vector<int32_t> hp(pdf, pdf + K);
+            const int32_t *dp = nullptr; const float *di = nullptr, *df = nullptr;
+            if (!(rc = upload(g, hp, &dp)) && !(rc = upload(g, i2, &di)) && !(rc = upload(g, f2, &df)) &&
+                !(rc = upload_sell(g, g->h_fwd, g->fwd)) && !(rc = upload_sell(g, g->h_bwd, g->bwd)))
+                rc = upload_sell(g, g->h_pdf, g->pdfs);
+            g->d_pdf = const_cast<int32_t *>(dp); g->d_init2 = const_cast<float *>(di); g->d_final2 = const_cast<float *>(df);
+        }
+    } catch (const std::bad_alloc &) {
+        rc = fail(FB_ENOMEM, "fb_graph_create: host allocation failed");
+    }
+    if (rc != FB_OK) {
+        const std::string keep = fb_last_error();
+        fb_graph_destroy(g);
+        set_error(keep);
+        return rc;
+    }
+    *out = g;
+    return FB_OK;
+}
+
+int fb_graph_destroy(fb_graph *g)
+{
+    if (!g) return FB_OK;
+    int rc = FB_OK;
+    for (void *p : g->allocs)
+        if (hipFree(p) != hipSuccess) rc = FB_EHIP;
+    delete g;
+    return rc == FB_OK ? FB_OK : fail(FB_EHIP, "hipFree failed");
+}
+
+static const void *layout_array(const fb_graph *g, int which, int64_t *n)
+{
+    const HostLayout &L = g->lay;
+    switch (which) {
+    case FB_IN_PTR: *n = (int64_t)L.in_ptr.size(); return L.in_ptr.data();
+    case FB_IN_SRC: *n = (int64_t)L.in_src.size(); return L.in_src.data();
+    case FB_IN_W: *n = (int64_t)L.in_w.size(); return L.in_w.data();
+    case FB_IN_PERM: *n = (int64_t)L.in_perm.size(); return L.in_perm.data();
+    case FB_OUT_PTR: *n = (int64_t)L.out_ptr.size(); return L.out_ptr.data();
+    case FB_OUT_DST: *n = (int64_t)L.out_dst.size(); return L.out_dst.data();
+    case FB_OUT_W: *n = (int64_t)L.out_w.size(); return L.out_w.data();
+    case FB_OUT_PERM: *n = (int64_t)L.out_perm.size(); return L.out_perm.data();
+    case FB_PDF_PTR: *n = (int64_t)L.pdf_ptr.size(); return L.pdf_ptr.data();
+    case FB_PDF_STATES: *n = (int64_t)L.pdf_states.size(); return L.pdf_states.data();
+    default: *n = -1; return nullptr;
+    }
+}
+
+int fb_graph_schedule_apply_host(const fb_graph *g, int which, int32_t sub, const double *x, double *y)
+{
+    if (!g || !x || !y) return fail(FB_EINVAL, "fb_graph_schedule_apply_host: NULL argument");
+    const SellHost *S = which == 0 ? &g->h_fwd : which == 1 ? &g->h_bwd : which == 2 ? &g->h_pdf : nullptr;
+    if (!S || sub < 0 || (size_t)sub >= S->sub.size())
+        return fail(FB_EINVAL, "fb_graph_schedule_apply_host: unknown schedule or sub-graph");
+    sell_apply_host(*S, sub, which != 2, x, y);
+    return FB_OK;
+}
+
+int64_t fb_graph_layout_size(const fb_graph *g, int which)
+{
+    if (!g) return fail(FB_EINVAL, "fb_graph_layout_size: NULL graph");
+    int64_t n;
+    layout_array(g, which, &n);
+    if (n < 0) return fail(FB_EINVAL, "fb_graph_layout_size: unknown array");
+    return n;
+}
+
+int fb_graph_layout(const fb_graph *g, int which, void *host_out, size_t bytes)
+{
+    if (!g || !host_out) return fail(FB_EINVAL, "fb_graph_layout: NULL argument");
+    int64_t n;
+    const void *p = layout_array(g, which, &n);
+    if (n < 0) return fail(FB_EINVAL, "fb_graph_layout: unknown array");
+    if (bytes != (size_t)n * 4) return fail(FB_EINVAL, "fb_graph_layout: bytes must be 4 * fb_graph_layout_size()");
+    if (n) std::memcpy(host_out, p, bytes);
+    return FB_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,148 @@
+// Internal declarations shared by the host code and the kernels of libfb_amd.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "../../include/fb.h"
+
+namespace fb {
+
+constexpr int kWave = 64;            // gfx950 wavefront
+constexpr int kNWShared = 16;        // waves per workgroup, large (sub-)graphs
+constexpr int kNWSmall = 4;          // waves per workgroup, small (sub-)graphs
+constexpr int kChunk = 32;           // longest arc list one lane walks; longer rows are split
+constexpr size_t kLdsBytes = 160 * 1024;
+constexpr size_t kLdsReserve = 1024; // reduction slots etc.
+
+// One (src, weight) pair of a row of a sparse semiring matrix, as the kernels read it.
+struct Arc {
+    int32_t src;   // index into the vector the row gathers from
+    float w;       // weight (log2 units in the log semiring; 1 / 0 in the plain-sum use)
+};
+
+// Part of a schedule that belongs to one (sub-)graph.
+struct SubDesc {
+    int32_t k0;         // first state of the sub-graph in the global numbering
+    int32_t K;          // its number of states
+    int32_t n_levels;   // passes over the rows: 1 + the depth of row splitting
+    int32_t n_part;     // partial-result slots used by split rows
+    int32_t wave_ptr0;  // where its [(n_levels * nw) + 1] slice ranges start in wave_ptr
+    int32_t pad_[3];
+};
+
+// Row-split sliced-ELL schedule of a sparse matrix-vector product, host side.
+// Rows are grouped 64 to a slice (one row per lane), a slice is padded to its
+// longest row, rows longer than kChunk are split into partial rows that a later
+// level combines, and slices are dealt to the nw waves of a workgroup so that
+// every wave has about the same number of arc visits.
+struct SellHost {
+    int nw = 0;
+    std::vector<SubDesc> sub;
+    std::vector<int32_t> wave_ptr;    // slice ranges per (sub, level, wave)
+    std::vector<int32_t> slice_trip;  // arcs each lane of the slice walks
+    std::vector<int64_t> slice_arc;   // first arc of the slice in `arcs`
+    std::vector<int32_t> row_out;     // [n_slices*64]: >=0 final row id, -1 idle lane, <=-2 partial slot -2-o
+    std::vector<int32_t> row_vidx;    // [n_slices*64]: index of the row's emission in the staged emission vector
+    std::vector<Arc> arcs;            // slice-major, then step, then lane
+    int32_t max_part = 0;
+};
+
+// Device copy of a SellHost.
+struct SellDev {
+    const SubDesc *sub = nullptr;
+    const int32_t *wave_ptr = nullptr;
+    const int32_t *slice_trip = nullptr;
+    const int64_t *slice_arc = nullptr;
+    const int32_t *row_out = nullptr;
+    const int32_t *row_vidx = nullptr;
+    const Arc *arcs = nullptr;
+};
+
+// rows [0, n_rows) of a CSR-like matrix: entries ptr[r]..ptr[r+1] with column col[] and weight w[].
+// Appends one sub-schedule to `out`.
+void sell_append(SellHost &out, int32_t k0, int32_t K, int32_t n_rows, const int64_t *ptr, const int32_t *col,
+                 const float *w, const int32_t *row_out_id, const int32_t *row_vidx_id, float pad_w, float one_w);
+
+bool sell_in_bounds(const SellHost &S, int32_t n_out, int32_t n_vidx, std::string &why);
+void sell_apply_host(const SellHost &S, int32_t sub, bool log_semiring, const double *x, double *y);
+
+struct HostLayout {                   // the graph-layout step, kept for fb_graph_layout
+    std::vector<int32_t> in_ptr, in_src, in_perm, out_ptr, out_dst, out_perm, pdf_ptr, pdf_states;
+    std::vector<float> in_w, out_w;
+};
+
+}  // namespace fb
+
+struct fb_graph {
+    int32_t K = 0, D = 0, n_seq = 0;  // n_seq == 0: shared
+    int64_t E = 0;
+    int nw = 0;                       // waves per workgroup its schedules were built for
+    int32_t max_sub_K = 0;
+    bool host_only = false;
+    fb::HostLayout lay;
+    std::vector<int32_t> state_off;   // packed only
+    fb::SellHost h_fwd, h_bwd, h_pdf; // host schedules (kept for size queries)
+    // device
+    fb::SellDev fwd, bwd, pdfs;
+    int32_t *d_pdf = nullptr;         // [K]
+    float *d_init2 = nullptr;         // [K] init * log2(e)
+    float *d_final2 = nullptr;        // [K] final * log2(e)
+    std::vector<void *> allocs;       // everything to hipFree
+};
+
+namespace fb {
+
+void set_error(const std::string &msg);
+int fail(int code, const std::string &msg);
+
+struct RecDir {
+    SellDev sched;
+    const float *bound;    // start weights of this direction (init2 forward, final2 backward)
+    const float *obound;   // end weights, for log Z
+    float *out;            // normalised vectors, nullable
+    float *off;            // [B][N] offsets, nullable
+    double *logz;          // [B], nullable
+    float out_scale;       // ln 2 for natural-log output, 1 to keep log2 units
+    int backward;
+    int fill_pad;          // write -inf / 0 into the rows of padded frames
+};
+
+struct RecParams {
+    RecDir dir[2];
+    int n_dir;
+    const int32_t *pdf;
+    const float *emis;
+    const int32_t *lengths;
+    int32_t B, N, D, shared, Ktot;
+    int32_t Kcap, Pcap, Ecap, any_backward;
+};
+
+struct PostGraph {
+    SellDev pdfs;          // plain-sum schedule states -> pdfs
+    const SubDesc *sub;    // same as pdfs.sub
+    const float *a, *b;    // normalised forward / backward vectors
+    float in_scale;        // log2(e) if a, b are natural logs, 1 if log2 units
+    int32_t shared, Ktot;
+    float *state_post;     // nullable
+};
+
+struct PostParams {
+    PostGraph g[2];        // g[0] contributes +, g[1] contributes - (absent if n_graph == 1)
+    int n_graph;
+    const int32_t *lengths;
+    int32_t B, N, D;
+    float *pdf_out;        // [B][N][D], nullable
+    int32_t Kcap, Pcap, frames_per_block;
+};
+
+int launch_recursion(int nw, const RecParams &p, size_t lds_bytes, void *stream);
+int launch_posteriors(const PostParams &p, size_t lds_bytes, void *stream);
+int launch_loss(const double *logz_num, const double *logz_den, const int32_t *lengths, int32_t B, double *loss,
+                void *stream);
+size_t recursion_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t Ecap, bool any_backward);
+size_t posterior_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t D);
+
+}  // namespace fb

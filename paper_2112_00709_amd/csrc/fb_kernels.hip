@@ -1,0 +1,454 @@
+// gfx950 kernels of libfb_amd: the alpha / beta recursions (Eq. 13-14), the
+// posteriors (Eq. 15) with their accumulation over tied states, and the LF-MMI
+// objective (Eq. 16).
+//
+// Work decomposition.  Sequences of a batch are independent (the batched
+// transition matrix is block diagonal), while the frames of one sequence are
+// strictly sequential.  One workgroup therefore owns one (sequence, direction)
+// pair for the whole time loop and keeps that sequence's state vector in LDS:
+// a time step needs workgroup barriers only, never a grid-wide one, and the
+// forward and backward recursions of a batch run side by side in one launch.
+// Within a step the sparse product is walked one matrix row per lane along a
+// static row-split sliced-ELL schedule (fb_sell.cpp); the arcs stream from L2,
+// the gathered vector comes from LDS.
+//
+// Arithmetic.  Internally logs are base 2 (weights and emissions are scaled by
+// log2 e once), so the semiring sum is v_exp_f32 / v_log_f32 with no
+// multiplications.  A row's (+)-sum is evaluated in one pass with a running
+// maximum: one exponential per arc, one logarithm per row.  The state vector is
+// kept normalised: every step subtracts the previous step's maximum, the
+// subtracted amounts are the offsets handed back to the caller and their sum is
+// accumulated in double for log Z.
+#include <hip/hip_runtime.h>
+
+#include "fb_internal.h"
+
+namespace fb {
+
+namespace {
+
+constexpr float kNegBig = -1.0e30f;   // stands for "no finite term yet"; values below it count as semiring zero
+constexpr float kLog2e = 1.44269504088896340736f;
+constexpr double kLn2 = 0.69314718055994530942;
+constexpr int kEPT = 4;               // emission elements a thread prefetches per frame
+
+__device__ __forceinline__ float fexp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float flog2(float x) { return __builtin_amdgcn_logf(x); }
+
+// running (+)-sum in base 2: value = m + log2(s)
+__device__ __forceinline__ void lse_add(float &m, float &s, float x)
+{
+    const float d = x - m;
+    const float e = fexp2(-fabsf(d));
+    s = d > 0.0f ? fmaf(s, e, 1.0f) : s + e;
+    m = fmaxf(m, x);
+}
+
+__device__ __forceinline__ void lse_merge(float &m, float &s, float m2, float s2)
+{
+    const float M = fmaxf(m, m2);
+    s = s * fexp2(m - M) + s2 * fexp2(m2 - M);
+    m = M;
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// One level of a log-semiring schedule for this wave: every lane walks its row.
+template <class Fin>
+__device__ __forceinline__ void sell_log_level(const SellDev &S, int wp, const float *vbase, float *part, int lane, Fin fin)
+{
+    const int s0 = S.wave_ptr[wp], s1 = S.wave_ptr[wp + 1];
+    for (int s = s0; s < s1; ++s) {
+        const int trip = S.slice_trip[s];
+        const Arc *ap = S.arcs + S.slice_arc[s] + lane;
+        float m = kNegBig, sum = 0.0f;
+        int it = 0;
+        for (; it + 4 <= trip; it += 4) {
+            const Arc a0 = ap[0], a1 = ap[kWave], a2 = ap[2 * kWave], a3 = ap[3 * kWave];
+            ap += 4 * kWave;
+            const float x0 = vbase[a0.src] + a0.w, x1 = vbase[a1.src] + a1.w;
+            const float x2 = vbase[a2.src] + a2.w, x3 = vbase[a3.src] + a3.w;
+            lse_add(m, sum, x0);
+            lse_add(m, sum, x1);
+            lse_add(m, sum, x2);
+            lse_add(m, sum, x3);
+        }
+        for (; it < trip; ++it) {
+            const Arc a = ap[0];
+            ap += kWave;
+            lse_add(m, sum, vbase[a.src] + a.w);
+        }
+        const float val = m + flog2(sum);   // sum == 0 -> -inf
+        const int o = S.row_out[s * kWave + lane];
+        if (o >= 0)
+            fin(o, S.row_vidx[s * kWave + lane], val);
+        else if (o < -1)
+            part[-2 - o] = val;
+    }
+}
+
+// One level of a plain-sum schedule (posterior accumulation over tied states).
+template <class Fin>
+__device__ __forceinline__ void sell_sum_level(const SellDev &S, int wp, const float *vbase, float *part, int lane, Fin fin)
+{
+    const int s0 = S.wave_ptr[wp], s1 = S.wave_ptr[wp + 1];
+    for (int s = s0; s < s1; ++s) {
+        const int trip = S.slice_trip[s];
+        const Arc *ap = S.arcs + S.slice_arc[s] + lane;
+        float acc = 0.0f;
+        for (int it = 0; it < trip; ++it) {
+            const Arc a = ap[0];
+            ap += kWave;
+            acc = fmaf(a.w, vbase[a.src], acc);
+        }
+        const int o = S.row_out[s * kWave + lane];
+        if (o >= 0)
+            fin(o, acc);
+        else if (o < -1)
+            part[-2 - o] = acc;
+    }
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// alpha / beta recursion.  grid = B * n_dir workgroups of NW waves; workgroup
+// (b, which) runs direction dir[which] of sequence b over all its frames.
+//
+// With x_n the vector kept in LDS, both directions are the same recursion on a
+// matrix and its transpose:
+//   forward   x_n = alpha_n              = v_n o (+)_{in(j)}  (w (x) x_{n-1}[src])
+//   backward  x_n = beta_n (x) v_n       = v_n o (+)_{out(i)} (w (x) x_{n+1}[dst])
+// and beta_n itself is the row sum before v_n is applied.
+// ---------------------------------------------------------------------------
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P)
+{
+    extern __shared__ float lds[];
+    constexpr int NT = NW * kWave;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int b = blockIdx.x % P.B;
+    const RecDir &R = P.dir[blockIdx.x / P.B];
+    const SellDev &S = R.sched;
+    const bool bwd = R.backward != 0;
+    const SubDesc sd = S.sub[P.shared ? 0 : b];
+    const int K = sd.K, k0 = sd.k0, L = sd.n_levels;
+    const int T = min(max(P.lengths[b], 0), P.N);
+    const int nE = P.shared ? P.D : K;           // entries of a staged emission vector
+
+    float *xb = lds;                             // x, two buffers of Kcap
+    float *bh = xb + 2 * P.Kcap;                 // beta before v is applied, two buffers (backward only)
+    float *part = bh + (P.any_backward ? 2 * P.Kcap : 0);
+    float *er = part + P.Pcap;                   // staged emissions (log2 units), two buffers of Ecap
+    float *red = er + 2 * P.Ecap;                // [2][NW] step maxima, then scratch for the last reduction
+
+    const float *em_seq = P.emis + (size_t)b * P.N * P.D;
+    float *out_seq = nullptr;
+    size_t out_ld = 0;
+    if (R.out) {
+        out_seq = P.shared ? R.out + (size_t)b * P.N * K : R.out + k0;
+        out_ld = P.shared ? (size_t)K : (size_t)P.Ktot;
+    }
+    float *off_seq = R.off ? R.off + (size_t)b * P.N : nullptr;
+    auto frame = [&](int i) { return bwd ? T - 1 - i : i; };
+
+    if (T > 0) {
+        // which element of an emission row each staged entry comes from
+        int eidx[kEPT];
+#pragma unroll
+        for (int j = 0; j < kEPT; ++j) {
+            const int e = tid + j * NT;
+            eidx[j] = e < nE ? (P.shared ? e : P.pdf[k0 + e]) : 0;
+        }
+        auto stage_tail = [&](const float *row, float *dst) {   // entries beyond the prefetch registers
+            for (int e = kEPT * NT + tid; e < nE; e += NT) dst[e] = row[P.shared ? e : P.pdf[k0 + e]] * kLog2e;
+        };
+        auto stage_direct = [&](int f, float *dst) {
+            const float *row = em_seq + (size_t)f * P.D;
+#pragma unroll
+            for (int j = 0; j < kEPT; ++j) {
+                const int e = tid + j * NT;
+                if (e < nE) dst[e] = row[eidx[j]] * kLog2e;
+            }
+            stage_tail(row, dst);
+        };
+        float ereg[kEPT];
+        auto prefetch = [&](int f) {
+            const float *row = em_seq + (size_t)f * P.D;
+#pragma unroll
+            for (int j = 0; j < kEPT; ++j) ereg[j] = (tid + j * NT < nE) ? row[eidx[j]] : 0.0f;
+        };
+        auto commit = [&](int f, float *dst) {
+#pragma unroll
+            for (int j = 0; j < kEPT; ++j) {
+                const int e = tid + j * NT;
+                if (e < nE) dst[e] = ereg[j] * kLog2e;
+            }
+            if (nE > kEPT * NT) stage_tail(em_seq + (size_t)f * P.D, dst);
+        };
+
+        // ---- first frame of this direction: x = start weight (x) v
+        stage_direct(frame(0), er);
+        if (T > 1) stage_direct(frame(1), er + P.Ecap);
+        __syncthreads();
+        float wmax = -INFINITY;
+        for (int k = tid; k < K; k += NT) {
+            const float s = R.bound[k0 + k];
+            const float x = s + er[P.shared ? P.pdf[k0 + k] : k];
+            xb[k] = x;
+            if (bwd) bh[k] = s;
+            wmax = fmaxf(wmax, x);
+        }
+        wmax = wave_max(wmax);
+        if (lane == 0) red[wave] = wmax;
+        if (T > 2) prefetch(frame(2));
+        if (off_seq && tid == 0) off_seq[frame(0)] = 0.0f;
+        __syncthreads();
+
+        double csum = 0.0;
+        for (int i = 1; i < T; ++i) {
+            const int cur = (i - 1) & 1, nxt = i & 1;
+            const float *xc = xb + cur * P.Kcap;
+            float *xn = xb + nxt * P.Kcap;
+            float *bn = bh + nxt * P.Kcap;
+            const float *ern = er + nxt * P.Ecap;
+            float M = red[cur * NW];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) M = fmaxf(M, red[cur * NW + w]);
+            const float c = (M == -INFINITY) ? 0.0f : M;
+            csum += (double)c;
+            if (off_seq && tid == 0) off_seq[frame(i)] = c * R.out_scale;
+            if (out_seq) {   // vector of the previous step, now final, goes out coalesced
+                float *orow = out_seq + (size_t)frame(i - 1) * out_ld;
+                const float *srcv = bwd ? bh + cur * P.Kcap : xc;
+                for (int k = tid; k < K; k += NT) orow[k] = srcv[k] * R.out_scale;
+            }
+            wmax = -INFINITY;
+            auto fin = [&](int o, int vi, float val) {
+                const float pre = val - c;
+                const float x = pre + ern[vi];
+                xn[o] = x;
+                if (bwd) bn[o] = pre;
+                wmax = fmaxf(wmax, x);
+            };
+            for (int l = 0; l < L; ++l) {
+                sell_log_level(S, sd.wave_ptr0 + l * NW + wave, l == 0 ? xc : part, part, lane, fin);
+                if (l + 1 < L) __syncthreads();
+            }
+            // emissions two frames ahead: the row loaded during the last step goes to LDS,
+            // the next row starts its trip from HBM
+            if (i + 1 < T) commit(frame(i + 1), er + cur * P.Ecap);
+            if (i + 2 < T) prefetch(frame(i + 2));
+            wmax = wave_max(wmax);
+            if (lane == 0) red[nxt * NW + wave] = wmax;
+            __syncthreads();
+        }
+
+        // ---- last frame: write it out, close log Z with the end weights
+        const int last = (T - 1) & 1;
+        const float *xl = xb + last * P.Kcap;
+        if (out_seq) {
+            float *orow = out_seq + (size_t)frame(T - 1) * out_ld;
+            const float *srcv = bwd ? bh + last * P.Kcap : xl;
+            for (int k = tid; k < K; k += NT) orow[k] = srcv[k] * R.out_scale;
+        }
+        if (R.logz) {
+            float m = kNegBig, s = 0.0f;
+            for (int k = tid; k < K; k += NT) lse_add(m, s, xl[k] + R.obound[k0 + k]);
+#pragma unroll
+            for (int o = 32; o >= 1; o >>= 1) lse_merge(m, s, __shfl_xor(m, o, 64), __shfl_xor(s, o, 64));
+            float *rm = red + 2 * NW, *rs = rm + NW;
+            if (lane == 0) { rm[wave] = m; rs[wave] = s; }
+            __syncthreads();
+            if (tid == 0) {
+                m = rm[0]; s = rs[0];
+                for (int w = 1; w < NW; ++w) lse_merge(m, s, rm[w], rs[w]);
+                const float r = m + flog2(s);
+                R.logz[b] = (csum + (double)r) * kLn2;
+            }
+        }
+    } else if (R.logz && tid == 0) {
+        R.logz[b] = -INFINITY;
+    }
+
+    // ---- padded frames
+    if (out_seq && R.fill_pad)
+        for (int f = T; f < P.N; ++f) {
+            float *orow = out_seq + (size_t)f * out_ld;
+            for (int k = tid; k < K; k += NT) orow[k] = -INFINITY;
+        }
+    if (off_seq)
+        for (int f = T + tid; f < P.N; f += NT) off_seq[f] = 0.0f;
+}
+
+// ---------------------------------------------------------------------------
+// Posteriors (Eq. 15) of one or two graphs and their accumulation into pdf
+// posteriors; with two graphs the second is subtracted (Eq. 17).  grid =
+// (ceil(N / frames_per_block), B), 256 threads.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fb_posterior_kernel(const PostParams P)
+{
+    extern __shared__ float lds[];
+    constexpr int NW = kNWSmall, NT = NW * kWave;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int b = blockIdx.y;
+    const int T = min(max(P.lengths[b], 0), P.N);
+    float *tb = lds;                 // per-state values of the frame
+    float *part = tb + P.Kcap;
+    float *rho = part + P.Pcap;      // [D]
+    float *red = rho + P.D;          // [NW]
+
+    for (int fi = 0; fi < P.frames_per_block; ++fi) {
+        const int n = blockIdx.x * P.frames_per_block + fi;
+        if (n >= P.N) break;
+        float *prow = P.pdf_out ? P.pdf_out + ((size_t)b * P.N + n) * P.D : nullptr;
+        if (n >= T) {   // padded frame: zeros
+            if (prow)
+                for (int d = tid; d < P.D; d += NT) prow[d] = 0.0f;
+            for (int gi = 0; gi < P.n_graph; ++gi) {
+                const PostGraph &G = P.g[gi];
+                if (!G.state_post) continue;
+                const SubDesc sd = G.sub[G.shared ? 0 : b];
+                float *srow = G.shared ? G.state_post + ((size_t)b * P.N + n) * sd.K
+                                       : G.state_post + (size_t)n * G.Ktot + sd.k0;
+                for (int k = tid; k < sd.K; k += NT) srow[k] = 0.0f;
+            }
+            continue;
+        }
+        for (int d = tid; d < P.D; d += NT) rho[d] = 0.0f;
+        for (int gi = 0; gi < P.n_graph; ++gi) {
+            const PostGraph &G = P.g[gi];
+            const SubDesc sd = G.sub[G.shared ? 0 : b];
+            const int K = sd.K;
+            const size_t at = G.shared ? ((size_t)b * P.N + n) * K : (size_t)n * G.Ktot + sd.k0;
+            const float *arow = G.a + at, *brow = G.b + at;
+            // log posterior up to the frame's normaliser, its maximum
+            float mx = -INFINITY;
+            for (int k = tid; k < K; k += NT) {
+                const float t = (arow[k] + brow[k]) * G.in_scale;
+                tb[k] = t;
+                mx = fmaxf(mx, t);
+            }
+            mx = wave_max(mx);
+            if (lane == 0) red[wave] = mx;
+            __syncthreads();
+            mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+            __syncthreads();
+            float sum = 0.0f;
+            if (mx != -INFINITY)
+                for (int k = tid; k < K; k += NT) {
+                    const float e = fexp2(tb[k] - mx);
+                    tb[k] = e;
+                    sum += e;
+                }
+            else
+                for (int k = tid; k < K; k += NT) tb[k] = 0.0f;
+            sum = wave_sum(sum);
+            if (lane == 0) red[wave] = sum;
+            __syncthreads();
+            sum = (red[0] + red[1]) + (red[2] + red[3]);
+            const float inv = sum > 0.0f ? 1.0f / sum : 0.0f;
+            float *srow = G.state_post ? G.state_post + at : nullptr;
+            for (int k = tid; k < K; k += NT) {
+                const float gma = tb[k] * inv;
+                tb[k] = gma;
+                if (srow) srow[k] = gma;
+            }
+            __syncthreads();
+            if (prow) {
+                const float sign = gi == 0 ? 1.0f : -1.0f;
+                auto fin = [&](int o, float v) { rho[o] += sign * v; };
+                for (int l = 0; l < sd.n_levels; ++l) {
+                    sell_sum_level(G.pdfs, sd.wave_ptr0 + l * NW + wave, l == 0 ? tb : part, part, lane, fin);
+                    __syncthreads();
+                }
+            }
+        }
+        if (prow)
+            for (int d = tid; d < P.D; d += NT) prow[d] = rho[d];
+        __syncthreads();
+    }
+}
+
+// loss = sum_b (log Z_num[b] - log Z_den[b]) over the sequences that have frames (Eq. 16),
+// summed in double in a fixed order.
+__global__ __launch_bounds__(256) void fb_loss_kernel(const double *zn, const double *zd, const int32_t *lengths, int32_t B,
+                                                      double *loss)
+{
+    __shared__ double acc[256];
+    double a = 0.0;
+    for (int b = threadIdx.x; b < B; b += 256)
+        if (lengths[b] > 0) a += zn[b] - zd[b];
+    acc[threadIdx.x] = a;
+    __syncthreads();
+    for (int s = 128; s >= 1; s >>= 1) {
+        if ((int)threadIdx.x < s) acc[threadIdx.x] += acc[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *loss = acc[0];
+}
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+static int check_launch(const char *what)
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(FB_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+    return FB_OK;
+}
+
+template <class Kern>
+static int allow_lds(Kern kern, size_t bytes)
+{
+    if (bytes <= 64 * 1024) return FB_OK;
+    const hipError_t e =
+        hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) return fail(FB_EHIP, std::string("hipFuncSetAttribute(LDS size): ") + hipGetErrorString(e));
+    return FB_OK;
+}
+
+int launch_recursion(int nw, const RecParams &p, size_t lds_bytes, void *stream)
+{
+    const dim3 grid((unsigned)(p.B * p.n_dir));
+    int rc;
+    if (nw == kNWShared) {
+        if ((rc = allow_lds(fb_recursion_kernel<kNWShared>, lds_bytes))) return rc;
+        hipLaunchKernelGGL(fb_recursion_kernel<kNWShared>, grid, dim3(kNWShared * kWave), lds_bytes, (hipStream_t)stream, p);
+    } else {
+        if ((rc = allow_lds(fb_recursion_kernel<kNWSmall>, lds_bytes))) return rc;
+        hipLaunchKernelGGL(fb_recursion_kernel<kNWSmall>, grid, dim3(kNWSmall * kWave), lds_bytes, (hipStream_t)stream, p);
+    }
+    return check_launch("recursion kernel launch");
+}
+
+int launch_posteriors(const PostParams &p, size_t lds_bytes, void *stream)
+{
+    const dim3 grid((unsigned)((p.N + p.frames_per_block - 1) / p.frames_per_block), (unsigned)p.B);
+    int rc;
+    if ((rc = allow_lds(fb_posterior_kernel, lds_bytes))) return rc;
+    hipLaunchKernelGGL(fb_posterior_kernel, grid, dim3(256), lds_bytes, (hipStream_t)stream, p);
+    return check_launch("posterior kernel launch");
+}
+
+int launch_loss(const double *zn, const double *zd, const int32_t *lengths, int32_t B, double *loss, void *stream)
+{
+    hipLaunchKernelGGL(fb_loss_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, zn, zd, lengths, B, loss);
+    return check_launch("loss kernel launch");
+}
+
+}  // namespace fb

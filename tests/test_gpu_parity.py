@@ -1,0 +1,314 @@
+"""Parity of the HIP path (through the C ABI) against the fp64 CPU oracle.
+
+Tolerances (stated by the benchmark spec): log Z 1e-4 relative; posteriors and gradients
+1e-5 absolute; the integer graph layout bit-exact.  Stored alpha / beta rows are
+normalised, so they are compared after adding back the offsets (1e-4 relative)
+and, more sharply, row by row relative to the row maximum.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from oracle import layout as olayout
+
+pytestmark = pytest.mark.gpu
+
+TOL_LOGZ_REL = 1e-4
+TOL_POST_ABS = 1e-5
+
+
+def say(msg):
+    print(f"[gpu-case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def fb():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2112_00709_amd as lib
+    lib.lib()                       # fails loudly if the HIP library is not built
+    return lib
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def gpu_forward_backward(fb, g, D, emis, lengths):
+    """alpha/beta reconstructed per sequence (float64), gamma, rho, logz from the GPU library."""
+    import torch
+    G = fb.graph_from(g, D)
+    e, l = dev(emis), dev(lengths.astype(np.int32))
+    B, N, _ = emis.shape
+    a, aoff, za = fb.fb_alpha(G, e, l)
+    b, boff, zb = fb.fb_beta(G, e, l)
+    gam, rho = fb.fb_posteriors(G, a, b, l, B, N)
+    torch.cuda.synchronize()
+    out = dict(alpha=host(a), beta=host(b), aoff=host(aoff).astype(np.float64), boff=host(boff).astype(np.float64),
+               logz=host(za), logz_b=host(zb), gamma=host(gam), rho=host(rho))
+    G.destroy()
+    return out
+
+
+def seq_view(g, arr, b, T):
+    """Rows of sequence b from a [B,N,K] (shared) or [N,K] (packed) array."""
+    if g.packed:
+        return arr[:T, g.state_off[b]:g.state_off[b + 1]]
+    return arr[b, :T]
+
+
+def check_log_rows(got_norm, off_cum, want, what):
+    """got_norm: float32 normalised rows [T,K]; off_cum: [T] cumulative offsets; want: oracle rows (float64)."""
+    got = got_norm.astype(np.float64) + off_cum[:, None]
+    inf_w = np.isneginf(want)
+    assert np.array_equal(np.isneginf(got_norm), inf_w), f"{what}: -inf pattern differs"
+    fin = ~inf_w
+    err = np.abs(got[fin] - want[fin])
+    assert np.all(err <= TOL_LOGZ_REL * np.maximum(1.0, np.abs(want[fin]))), f"{what}: max err {err.max()}"
+    # shape of each row relative to its maximum (what posteriors depend on)
+    for n in range(want.shape[0]):
+        if not fin[n].any():
+            continue
+        gw = want[n][fin[n]] - want[n][fin[n]].max()
+        gg = got_norm[n][fin[n]].astype(np.float64) - got_norm[n][fin[n]].astype(np.float64).max()
+        assert np.all(np.abs(gw - gg) <= 2e-5 * (1.0 + np.abs(gw))), f"{what}: frame {n} row shape"
+
+
+def compare_fb(fb, g, D, emis, lengths, sel=None, name=""):
+    B = emis.shape[0]
+    sel = list(range(B)) if sel is None else list(sel)
+    say(f"{name}: oracle on {len(sel)} of {B} sequences")
+    ref = oracle.forward_backward(g, emis, lengths, sel=sel)
+    say(f"{name}: fb_alpha / fb_beta / fb_posteriors B={B} N={emis.shape[1]} D={D} K={g.K} E={g.E}")
+    out = gpu_forward_backward(fb, g, D, emis, lengths)
+    for i, b in enumerate(sel):
+        T = int(lengths[b])
+        wz = ref.logz[i]
+        for z in (out["logz"][b], out["logz_b"][b]):
+            if np.isneginf(wz):
+                assert np.isneginf(z)
+            else:
+                assert abs(z - wz) <= TOL_LOGZ_REL * max(1.0, abs(wz)), f"{name} b={b}: logZ {z} vs {wz}"
+        if np.isneginf(wz):
+            assert np.all(seq_view(g, out["gamma"], b, T) == 0) and np.all(out["rho"][b] == 0)
+            continue
+        check_log_rows(seq_view(g, out["alpha"], b, T), np.cumsum(out["aoff"][b, :T]), ref.alpha[i], f"{name} alpha b={b}")
+        check_log_rows(seq_view(g, out["beta"], b, T), np.cumsum(out["boff"][b, :T][::-1])[::-1], ref.beta[i],
+                       f"{name} beta b={b}")
+        dg = np.abs(seq_view(g, out["gamma"], b, T) - ref.gamma[i]).max()
+        dr = np.abs(out["rho"][b] - ref.rho[i]).max()
+        assert dg <= TOL_POST_ABS, f"{name} b={b}: state posterior err {dg}"
+        assert dr <= TOL_POST_ABS, f"{name} b={b}: pdf posterior err {dr}"
+    # padded frames, every sequence
+    N = emis.shape[1]
+    for b in range(B):
+        T = int(lengths[b])
+        if T < N:
+            assert np.all(out["rho"][b, T:] == 0)
+            pad = out["gamma"][T:, g.state_off[b]:g.state_off[b + 1]] if g.packed else out["gamma"][b, T:]
+            assert np.all(pad == 0)
+            assert np.all(out["aoff"][b, T:] == 0) and np.all(out["boff"][b, T:] == 0)
+            pa = out["alpha"][T:, g.state_off[b]:g.state_off[b + 1]] if g.packed else out["alpha"][b, T:]
+            assert np.all(np.isneginf(pa))
+    return out
+
+
+def compare_lfmmi(fb, w, sel=None, name=""):
+    import torch
+    B = w.B
+    sel = list(range(B)) if sel is None else list(sel)
+    say(f"{name}: oracle LF-MMI on {len(sel)} of {B} sequences")
+    ref = oracle.lfmmi(w.den, w.num, w.emis, w.lengths, sel=sel)
+    say(f"{name}: lfmmi_loss_grad B={B} N={w.N} D={w.D} Kden={w.den.K} Knum={w.num.K}")
+    Gd, Gn = fb.graph_from(w.den, w.D), fb.graph_from(w.num, w.D)
+    loss, zn, zd, grad = fb.lfmmi_loss_grad(Gd, Gn, dev(w.emis), dev(w.lengths.astype(np.int32)))
+    torch.cuda.synchronize()
+    loss, zn, zd = float(host(loss)[0]), host(zn), host(zd)
+    for i, b in enumerate(sel):
+        assert abs(zn[b] - ref.logz_num[i]) <= TOL_LOGZ_REL * max(1.0, abs(ref.logz_num[i]))
+        assert abs(zd[b] - ref.logz_den[i]) <= TOL_LOGZ_REL * max(1.0, abs(ref.logz_den[i]))
+        gb = host(grad[b])
+        err = np.abs(gb - ref.grad[i]).max()
+        assert err <= TOL_POST_ABS, f"{name} b={b}: grad err {err}"
+    assert abs(loss - float(np.sum(zn - zd))) <= 1e-9 * max(1.0, float(np.sum(np.abs(zn) + np.abs(zd))))
+    if len(sel) == B:
+        assert abs(loss - ref.loss) <= TOL_LOGZ_REL * float(np.sum(np.abs(ref.logz_num) + np.abs(ref.logz_den)))
+    # properties that hold at any size: rows of real frames sum to 0, padded rows are 0
+    rows = host(grad.sum(dim=2))
+    absrows = host(grad.abs().sum(dim=2))
+    for b in range(B):
+        T = int(w.lengths[b])
+        assert np.all(np.abs(rows[b, :T]) <= 2e-4)
+        assert np.all(absrows[b, T:] == 0)
+        assert np.all(absrows[b, :T] > 0)
+    Gd.destroy(); Gn.destroy()
+    return loss
+
+
+# ------------------------------------------------------------------ layout on the device build
+
+def test_layout_bit_exact_from_device_graph(fb):
+    w = wl.config3(B=1, N=2)
+    say("layout: config3 graph, device build")
+    G = fb.graph_from(w.den, w.D)
+    ref = olayout.graph_layout(w.den.K, w.D, w.den.src, w.den.dst, w.den.logw, w.den.pdf)
+    for name, want in ref.items():
+        assert np.array_equal(fb.fb_graph_layout(G, name).view(np.int32), want.view(np.int32)), name
+    G.destroy()
+
+
+# ------------------------------------------------------------------ the five configurations
+
+def test_config1(fb):
+    w = wl.config1()
+    compare_fb(fb, w.den, w.D, w.emis, w.lengths, name="config1")
+
+
+def test_config2(fb):
+    w = wl.config2()
+    compare_fb(fb, w.num, w.D, w.emis, w.lengths, name="config2")
+
+
+def test_config3_full(fb):
+    w = wl.config3()
+    out = compare_fb(fb, w.den, w.D, w.emis, w.lengths, sel=range(0, 64, 4), name="config3")
+    np.testing.assert_allclose(out["rho"].sum(axis=2), 1.0, atol=2e-5)      # every sequence, every frame
+
+
+def test_config4_scaled(fb):
+    """Full 6000-state hub graph (rows split over three levels), small ragged batch."""
+    w = wl.config4(B=6, Nmin=20, Nmax=60)
+    compare_fb(fb, w.den, w.D, w.emis, w.lengths, name="config4-scaled")
+
+
+def test_config5_scaled(fb):
+    w = wl.config5(B=6, Lmin=5, Lmax=15)
+    compare_lfmmi(fb, w, name="config5-scaled")
+    compare_fb(fb, w.num, w.D, w.emis, w.lengths, name="config5-scaled numerator")
+
+
+def test_config4_full_size_sampled(fb):
+    w = wl.config4()
+    order = np.argsort(w.lengths)
+    sel = [int(order[0]), int(order[len(order) // 2]), int(order[-1])]
+    out = compare_fb(fb, w.den, w.D, w.emis, w.lengths, sel=sel, name="config4-full")
+    for b in range(w.B):
+        T = int(w.lengths[b])
+        np.testing.assert_allclose(out["rho"][b, :T].sum(axis=1), 1.0, atol=5e-5)
+        np.testing.assert_allclose(out["gamma"][b, :T].sum(axis=1), 1.0, atol=5e-5)
+    ok = np.isfinite(out["logz"]) & (np.abs(out["logz"] - out["logz_b"]) <= TOL_LOGZ_REL * np.abs(out["logz"]))
+    assert ok.all()                                                  # forward and backward agree on log Z
+
+
+def test_config5_full_size_sampled(fb):
+    w = wl.config5()
+    order = np.argsort(w.lengths)
+    sel = [int(order[0]), int(order[len(order) // 3]), int(order[-1])]
+    compare_lfmmi(fb, w, sel=sel, name="config5-full")
+
+
+# ------------------------------------------------------------------ edge cases
+
+def test_single_frame_and_single_state(fb):
+    g = wl.Graph(1, np.array([0], np.int32), np.array([0], np.int32), np.array([-0.25], np.float32),
+                 np.array([2], np.int32), np.array([-0.5], np.float32), np.array([-1.0], np.float32))
+    emis = np.random.default_rng(1).normal(size=(3, 4, 5)).astype(np.float32)
+    compare_fb(fb, g, 5, emis, np.array([1, 4, 2], np.int32), name="one-state graph, lengths 1/4/2")
+
+
+def test_ragged_batch_with_fully_padded_tail(fb):
+    w = wl.config3(K=500, B=5, N=12, D=30)
+    lengths = np.array([12, 1, 7, 9, 3], np.int32)
+    emis = np.concatenate([w.emis, np.full((5, 3, 30), np.nan, np.float32)], axis=1)     # padding must never be read into results
+    compare_fb(fb, w.den, 30, emis, lengths, name="ragged + NaN padding")
+
+
+def test_infeasible_and_semiring_zero_inputs(fb):
+    rng = np.random.default_rng(3)
+    g = wl.chain_graphs(rng, np.array([2, 3, 2]), 11)                 # 6, 9, 6 states
+    lengths = np.array([6, 8, 9], np.int32)                           # second chain cannot finish: log Z = -inf
+    emis = rng.normal(size=(3, 9, 11)).astype(np.float32)
+    emis[2, 4, :] = -np.inf                                           # a frame nobody can emit: log Z = -inf
+    out = compare_fb(fb, g, 11, emis, lengths, name="infeasible chains")
+    assert np.isneginf(out["logz"][1]) and np.isneginf(out["logz"][2]) and np.isfinite(out["logz"][0])
+    assert not np.isnan(out["rho"]).any() and not np.isnan(out["gamma"]).any()
+    g2 = wl.tiny_graph(9, 6, 4)                                       # -inf init/final entries, sourceless states
+    e2 = rng.normal(size=(2, 7, 4)).astype(np.float32)
+    e2[0, 3, 1] = -np.inf
+    compare_fb(fb, g2, 4, e2, np.array([7, 5], np.int32), name="tiny graph with -inf entries")
+
+
+def test_zero_length_sequence_is_skipped(fb):
+    import torch
+    w = wl.config5(K=200, B=4, Lmin=2, Lmax=4, D=40)
+    lengths = w.lengths.copy(); lengths[1] = 0
+    Gd, Gn = fb.graph_from(w.den, w.D), fb.graph_from(w.num, w.D)
+    say("zero-length sequence: lfmmi_loss_grad")
+    loss, zn, zd, grad = fb.lfmmi_loss_grad(Gd, Gn, dev(w.emis), dev(lengths))
+    torch.cuda.synchronize()
+    keep = [0, 2, 3]
+    ref = oracle.lfmmi(w.den, w.num, w.emis, w.lengths, sel=keep)
+    assert abs(float(host(loss)[0]) - ref.loss) <= TOL_LOGZ_REL * float(np.sum(np.abs(ref.logz_num) + np.abs(ref.logz_den)))
+    assert np.all(host(grad[1]) == 0) and np.isneginf(host(zn)[1]) and np.isneginf(host(zd)[1])
+    np.testing.assert_allclose(host(grad)[keep], ref.grad, atol=TOL_POST_ABS)
+    Gd.destroy(); Gn.destroy()
+
+
+def test_shared_graph_equals_its_packed_replication(fb):
+    """Block-diagonal batching: the same graph replicated as packed graphs gives the same posteriors."""
+    rng = np.random.default_rng(8)
+    g = wl.random_graph(rng, 70, 9, mean_extra_deg=3.0)
+    B, N = 3, 10
+    emis = rng.normal(size=(B, N, 9)).astype(np.float32)
+    lengths = np.array([10, 4, 7], np.int32)
+    rep = wl.Graph(B * g.K, np.concatenate([g.src + b * g.K for b in range(B)]).astype(np.int32),
+                   np.concatenate([g.dst + b * g.K for b in range(B)]).astype(np.int32), np.tile(g.logw, B),
+                   np.tile(g.pdf, B), np.tile(g.init, B), np.tile(g.final, B),
+                   state_off=(np.arange(B + 1) * g.K).astype(np.int32))
+    say("shared vs packed replication")
+    a = gpu_forward_backward(fb, g, 9, emis, lengths)
+    p = gpu_forward_backward(fb, rep, 9, emis, lengths)
+    np.testing.assert_allclose(a["rho"], p["rho"], atol=2e-6)
+    np.testing.assert_allclose(a["logz"], p["logz"], rtol=1e-6)
+    for b in range(B):
+        np.testing.assert_allclose(a["gamma"][b, :lengths[b]], p["gamma"][:lengths[b], b * g.K:(b + 1) * g.K], atol=2e-6)
+
+
+def test_results_are_deterministic(fb):
+    import torch
+    w = wl.config5(K=800, B=5, Lmin=3, Lmax=8, D=120)
+    Gd, Gn = fb.graph_from(w.den, w.D), fb.graph_from(w.num, w.D)
+    e, l = dev(w.emis), dev(w.lengths)
+    say("determinism: two lfmmi_loss_grad calls")
+    r1 = fb.lfmmi_loss_grad(Gd, Gn, e, l)
+    r2 = fb.lfmmi_loss_grad(Gd, Gn, e, l)
+    torch.cuda.synchronize()
+    for x, y in zip(r1, r2):
+        assert torch.equal(x, y)
+    Gd.destroy(); Gn.destroy()
+
+
+def test_device_call_argument_errors(fb):
+    w = wl.config2(B=3)
+    G = fb.graph_from(w.num, w.D)
+    e, l = dev(w.emis), dev(w.lengths)
+    with pytest.raises(fb.FBError) as err:
+        fb.fb_alpha(G, e[:2].contiguous(), l[:2].contiguous())          # B differs from the number of packed graphs
+    assert err.value.code == fb.FB_EINVAL
+    Gs = fb.graph_from(wl.config1().den, 16)
+    with pytest.raises(fb.FBError) as err:
+        fb.fb_alpha(Gs, e, l)                                           # D mismatch
+    assert err.value.code == fb.FB_EINVAL
+    with pytest.raises(fb.FBError) as err:
+        fb.lfmmi_loss_grad(G, G, e, l)                                  # den must be shared
+    assert err.value.code == fb.FB_EINVAL
+    G.destroy(); Gs.destroy()

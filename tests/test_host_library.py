@@ -1,0 +1,191 @@
+"""Host-side logic of libfb_amd, no GPU: the library loads and exports every
+symbol of include/fb.h, argument errors are reported as codes, the graph layout
+(integer work) is bit-exact against the oracle's stable sorts, and the static
+work plan the kernels walk computes the same sparse products as a direct
+evaluation."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2112_00709_amd as fb
+import workloads as wl
+from oracle import layout as olayout
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    if not os.path.exists(fb.LIB_PATH):
+        from paper_2112_00709_amd import build
+        build.build_library()
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "fb.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(\w+)\s*\(", header)) - {"defined", "__cplusplus"}
+    declared = {d for d in declared if d.startswith(("fb_", "lfmmi_"))}
+    assert declared == set(fb.SYMBOLS)
+    L = fb.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def _host_graph(g, D):
+    return fb.graph_from(g, D, host_only=True)
+
+
+@pytest.mark.parametrize("case", ["config1", "chains", "zipf"])
+def test_graph_layout_bit_exact(case):
+    if case == "config1":
+        w = wl.config1(); g = w.den
+    elif case == "chains":
+        w = wl.config2(B=5); g = w.num
+    else:
+        w = wl.config4(K=1500, B=2, Nmin=3, Nmax=4, D=200); g = w.den
+    h = _host_graph(g, w.D)
+    ref = olayout.graph_layout(g.K, w.D, g.src, g.dst, g.logw, g.pdf)
+    for name, want in ref.items():
+        got = fb.fb_graph_layout(h, name)
+        assert got.dtype == want.dtype and got.shape == want.shape, name
+        assert np.array_equal(got.view(np.int32), want.view(np.int32)), name     # bit-exact, weights included
+    h.destroy()
+
+
+def _direct_product(K, rows, cols, w2, x):
+    """y[r] = log2-sum-exp2 over entries (r, c) of w2 + x[c], in double."""
+    y = np.full(K, -np.inf)
+    t = w2 + x[cols]
+    for r in range(K):
+        sel = t[rows == r]
+        if sel.size and np.max(sel) > -np.inf:
+            m = np.max(sel)
+            y[r] = m + np.log2(np.sum(np.exp2(sel - m)))
+    return y
+
+
+@pytest.mark.parametrize("case", ["zipf_hubs", "uniform", "chains"])
+def test_kernel_schedule_computes_the_sparse_products(case):
+    rng = np.random.default_rng(5)
+    if case == "zipf_hubs":          # hub rows are split over several levels
+        w = wl.config4(K=900, B=2, Nmin=3, Nmax=4, D=64); g = w.den
+    elif case == "uniform":
+        w = wl.config3(K=300, B=2, N=3, D=20); g = w.den
+    else:
+        w = wl.config2(B=4); g = w.num
+    h = _host_graph(g, w.D)
+    off = g.state_off if g.packed else np.array([0, g.K])
+    w2 = (g.logw.astype(np.float64) * np.log2(np.e)).astype(np.float32).astype(np.float64)
+    for sub in range(len(off) - 1):
+        k0, k1 = int(off[sub]), int(off[sub + 1])
+        Ks = k1 - k0
+        x = rng.normal(size=Ks) * 5
+        x[rng.integers(0, Ks)] = -np.inf
+        inside = (g.src >= k0) & (g.src < k1)
+        src, dst, ww = g.src[inside] - k0, g.dst[inside] - k0, w2[inside]
+        for which, rows, cols in ((0, dst, src), (1, src, dst)):
+            y = fb.fb_graph_schedule_apply_host(h, which, sub, x, np.full(Ks, 123.0))
+            want = _direct_product(Ks, rows, cols, ww, x)
+            fin = np.isfinite(want)
+            assert np.array_equal(np.isneginf(y), np.isneginf(want))
+            np.testing.assert_allclose(y[fin], want[fin], rtol=0, atol=1e-9)
+        gam = rng.random(Ks)
+        y = fb.fb_graph_schedule_apply_host(h, 2, sub, gam, np.zeros(w.D))
+        want = np.bincount(g.pdf[k0:k1], weights=gam, minlength=w.D)
+        np.testing.assert_allclose(y, want, atol=1e-12)
+    h.destroy()
+
+
+def test_hub_graph_really_has_split_rows():
+    w = wl.config4(K=900, B=2, Nmin=3, Nmax=4, D=64)
+    assert np.bincount(w.den.dst, minlength=900).max() > 32 * 32     # at least three levels
+
+
+def _raises(code, fn, *a, **k):
+    with pytest.raises(fb.FBError) as e:
+        fn(*a, **k)
+    assert e.value.code == code, str(e.value)
+    assert str(e.value)
+
+
+def test_graph_create_argument_errors():
+    g = wl.config1().den
+    ok = dict(K=g.K, src=g.src, dst=g.dst, logw=g.logw, pdf=g.pdf, init=g.init, final=g.final, D=16, host_only=True)
+
+    def make(**kw):
+        a = dict(ok); a.update(kw)
+        fb.fb_graph_create(**a).destroy()
+
+    make()
+    _raises(fb.FB_EINVAL, make, K=0)
+    _raises(fb.FB_EINVAL, make, D=0)
+    bad = g.dst.copy(); bad[3] = 16
+    _raises(fb.FB_EINVAL, make, dst=bad)
+    bad = g.src.copy(); bad[0] = -1
+    _raises(fb.FB_EINVAL, make, src=bad)
+    bad = g.pdf.copy(); bad[5] = 16
+    _raises(fb.FB_EINVAL, make, pdf=bad)
+    _raises(fb.FB_EINVAL, make, D=15)
+    for val in (np.nan, np.inf):
+        bad = g.logw.copy(); bad[7] = val
+        _raises(fb.FB_EINVAL, make, logw=bad)
+        bad = g.init.copy(); bad[2] = val
+        _raises(fb.FB_EINVAL, make, init=bad)
+        bad = g.final.copy(); bad[2] = val
+        _raises(fb.FB_EINVAL, make, final=bad)
+    ninf = g.logw.copy(); ninf[7] = -np.inf          # the semiring zero is a legal weight
+    make(logw=ninf)
+    # packed graphs
+    c = wl.config2(B=3).num
+    okp = dict(K=c.K, src=c.src, dst=c.dst, logw=c.logw, pdf=c.pdf, init=c.init, final=c.final, D=84,
+               state_off=c.state_off, host_only=True)
+    fb.fb_graph_create(**okp).destroy()
+    so = c.state_off.copy(); so[1], so[2] = so[2], so[1]
+    _raises(fb.FB_EINVAL, lambda: fb.fb_graph_create(**dict(okp, state_off=so)))
+    so = c.state_off.copy(); so[-1] -= 1
+    _raises(fb.FB_EINVAL, lambda: fb.fb_graph_create(**dict(okp, state_off=so)))
+    so = c.state_off.copy(); so[1] += 1               # the arc into the moved state now crosses two graphs
+    _raises(fb.FB_EINVAL, lambda: fb.fb_graph_create(**dict(okp, state_off=so)))
+    L = fb.lib()
+    assert L.fb_graph_create(None, 1, 0, None, None, None, None, None, None, 1, 0, None, 1) == fb.FB_EINVAL
+    h = ctypes.c_void_p()
+    assert L.fb_graph_create(ctypes.byref(h), 4, 0, None, None, None, None, None, None, 1, 0, None, 1) == fb.FB_EINVAL
+
+
+def test_too_large_graph_is_unsupported_not_a_crash():
+    K = fb.fb_limits_max_states(84, True) * 2
+    z = np.zeros(K, np.float32)
+    _raises(fb.FB_EUNSUPPORTED, fb.fb_graph_create, K, np.arange(K) % K, (np.arange(K) + 1) % K, z,
+            np.zeros(K, np.int32), z, z, 84, host_only=True)
+    assert fb.fb_limits_max_states(84, True) > 6000 and fb.fb_limits_max_states(3000, True) > 6000
+    assert fb.fb_limits_max_states(3000, False) > 450
+
+
+def test_compute_calls_reject_bad_arguments_without_a_gpu():
+    g = wl.config1().den
+    h = _host_graph(g, 16)
+    L = fb.lib()
+    one = ctypes.c_void_p(256)      # never dereferenced: the checks come first
+    assert L.fb_alpha(None, one, one, 1, 50, 16, None, None, None, None) == fb.FB_EINVAL
+    assert L.fb_alpha(h.handle, one, one, 1, 50, 16, None, None, None, None) == fb.FB_EINVAL     # host-only graph
+    assert b"HOST_ONLY" in L.fb_last_error()
+    assert L.fb_beta(h.handle, None, one, 1, 50, 16, None, None, None, None) == fb.FB_EINVAL
+    assert L.fb_posteriors(h.handle, one, one, None, 1, 50, 16, one, one, None) == fb.FB_EINVAL
+    assert L.lfmmi_loss_grad(h.handle, h.handle, one, one, 1, 50, 16, one, None, None, one, one, 1 << 30, None) == fb.FB_EINVAL
+    assert L.fb_lfmmi_workspace_bytes(None, None, 1, 1, 1) == 0
+    assert L.fb_graph_layout(h.handle, 99, one, 4) == fb.FB_EINVAL
+    assert L.fb_graph_layout(h.handle, 0, one, 3) == fb.FB_EINVAL
+    assert L.fb_graph_layout_size(h.handle, 99) == fb.FB_EINVAL
+    assert L.fb_graph_destroy(None) == fb.FB_OK
+    assert L.fb_strerror(fb.FB_EUNSUPPORTED) and L.fb_strerror(12345)
+    h.destroy()
+
+
+def test_check_lengths():
+    fb.fb_check_lengths(np.array([1, 5, 3]), 5)
+    _raises(fb.FB_EINVAL, fb.fb_check_lengths, np.array([1, 6, 3]), 5)
+    _raises(fb.FB_EINVAL, fb.fb_check_lengths, np.array([0, 2]), 5)
