@@ -1,0 +1,151 @@
+"""Benchmark of the LF-MMI hot path on one MI355X.
+
+A step is one lfmmi_loss_grad call on configuration 5 (the largest workload:
+the 6000-state / ~60k-arc Zipf denominator graph shared by B=128 utterances,
+128 packed numerator chains, D=3000, N_b = round(3.6 L_b) frames): numerator
+and denominator alpha and beta recursions, log Z, state and pdf posteriors,
+objective and gradient.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line: throughput in log-semiring arc-updates/s
+(2 * sum_b N_b * E_b, real frames, denominator + numerator arcs), ms per batch,
+the memory roofline of the dominant kernel (the denominator recursion launch,
+timed live with HIP events on the launching stream) and the fp64 CPU oracle
+timed on this machine's host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
+
+# HBM bytes per denominator-recursion launch on configuration 5 from rocprofv3 --pmc
+# (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on a plain copy kernel);
+# see profiles/.  None until measured for the workload being run.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, choices=[5], help="workload (configuration 5 is the benchmark)")
+    ap.add_argument("--cpu-sample", type=int, default=0, help="sequences the CPU oracle is timed on (0 = 2 per thread)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (sequences are independent, so the batch would be "
+              "split across GPUs with one 8-byte all-reduce of the loss; no multi-GPU path is built).", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2112_00709_amd as fb
+    import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    fb.lib()
+    torch.cuda.set_device(0)
+
+    t_gen = time.time()
+    w = wl.config5()
+    log(f"[bench] config5 generated in {time.time() - t_gen:.1f}s: B={w.B} N={w.N} D={w.D} "
+        f"den K={w.den.K} E={w.den.E}; num K={w.num.K} E={w.num.E}; frames={int(w.lengths.sum())}")
+    t0 = time.time()
+    den, num = fb.graph_from(w.den, w.D), fb.graph_from(w.num, w.D)
+    log(f"[bench] graph layout + schedules + upload: {time.time() - t0:.3f}s (not part of a step)")
+    emis = torch.from_numpy(w.emis).cuda()
+    lengths = torch.from_numpy(w.lengths).cuda()
+    ws = torch.empty((fb.fb_lfmmi_workspace_bytes(den, num, w.B, w.N, w.D),), dtype=torch.uint8, device="cuda")
+    grad = torch.empty((w.B, w.N, w.D), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+
+    def step():
+        return fb.lfmmi_loss_grad(den, num, emis, lengths, ws=ws, grad=grad)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out = step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    loss = float(out[0].item())
+
+    # stage times with HIP events recorded by the library on the launching stream
+    fb.fb_profile_enable(True)
+    stages = []
+    for _ in range(max(3, min(args.steps, 10))):
+        step()
+        stages.append(fb.fb_profile_read())
+    fb.fb_profile_enable(False)
+    stage_ms = {k: float(np.mean([s[k] for s in stages])) for k in stages[0]}
+
+    upd_den, upd_num = w.arc_updates(w.den), w.arc_updates(w.num)
+    arc_updates = upd_den + upd_num
+    frames = int(w.lengths.sum())
+    d_used = int(np.unique(w.den.pdf).size)
+    # algorithmic bytes of the denominator recursion launch: per real frame and direction,
+    # the emission entries the graph uses are read once and the state vector is written once
+    algo_bytes = frames * 2 * (4 * d_used + 4 * w.den.K)
+    achieved = algo_bytes / (stage_ms["den_recursion"] * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get("config5")
+    result = {
+        "metric": "log-semiring arc-updates/sec (B*N*E*2) + LF-MMI loss+grad ms/batch",
+        "value": arc_updates / (ms_per_step * 1e-3),
+        "unit": "arc-updates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "config5: LF-MMI loss+grad, Zipf denominator K=6000 E~60k shared by B=128, "
+                               "128 packed numerator chains, D=3000, N_b=round(3.6 L_b)",
+                   "B": w.B, "N_max": w.N, "frames": frames, "D": w.D,
+                   "den_states": w.den.K, "den_arcs": w.den.E, "num_states": w.num.K, "num_arcs": w.num.E},
+        "lfmmi_ms_per_batch": ms_per_step,
+        "arc_updates_per_step": arc_updates,
+        "arc_updates_padded": 2 * w.B * w.N * w.den.E,
+        "stage_ms": stage_ms,
+        "loss": loss,
+        "roofline": {"kernel": "fb_recursion_kernel<16> (denominator alpha+beta, one launch)",
+                     "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "algorithmic_bytes": algo_bytes, "launch_ms": stage_ms["den_recursion"]},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = oracle.num_threads()
+        ns = args.cpu_sample or min(w.B, 2 * threads)
+        order = np.argsort(w.lengths, kind="stable")
+        sel = np.sort(order[np.linspace(0, w.B - 1, ns).round().astype(int)])
+        sample_updates = int(2 * np.sum(w.lengths[sel].astype(np.int64) * (w.den.E + w.num.arcs_per_seq(w.B)[sel])))
+        t0 = time.perf_counter()
+        oracle.lfmmi(w.den, w.num, w.emis, w.lengths, sel=sel)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {
+            "value": sample_updates / dt, "unit": "arc-updates/s", "cores": int(min(threads, ns)), "kind": "oracle",
+            "sample": f"{ns} of {w.B} utterances of config5 spread over the length range "
+                      f"({sample_updates} arc-updates, {dt:.1f} s, fp64, OpenMP over utterances)"}
+    print(json.dumps(result), flush=True)
+    den.destroy(); num.destroy()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

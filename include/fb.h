@@ -56,6 +56,16 @@
  * not depend on them.  Rows of padded frames hold -inf (alpha, beta) or 0
  * (offsets, posteriors, grad).
  *
+ * Precision.  Exponentials and logarithms are single precision everywhere.
+ * The normalised state vector of the recursions is carried either in single or
+ * in double precision.  A single-precision log value x carries a rounding error
+ * of about 3e-8 * |x| per time step, so single carriers are accurate when the
+ * states that matter for the posterior lie within a few tens of the frame's
+ * best state (densely connected graphs such as the denominator); in long
+ * left-to-right chains a state can matter while its alpha is far below the
+ * frame's best, and double carriers keep the 1e-5 posterior accuracy there.
+ * The alpha / beta arrays of fb_alpha / fb_beta are float in both cases.
+ *
  * Errors.  Every call returns FB_OK (0) or a negative code and never throws;
  * fb_last_error() gives a thread-local description of the last failure.
  * Kernel launches are asynchronous: an error inside a kernel surfaces at the
@@ -85,8 +95,12 @@ enum {
 
 /* fb_graph_create flags */
 enum {
-    FB_GRAPH_HOST_ONLY = 1 /* build and keep the layouts on the host only: no GPU is touched;
-                              the handle serves fb_graph_layout* but no compute call */
+    FB_GRAPH_HOST_ONLY = 1, /* build and keep the layouts on the host only: no GPU is touched;
+                               the handle serves fb_graph_layout* but no compute call */
+    FB_GRAPH_WIDE_STATE = 2, /* carry the state vectors in double (see "Precision" below) */
+    FB_GRAPH_NARROW_STATE = 4 /* carry them in single; with neither flag the library chooses:
+                               double for small (sub-)graphs (< 4096 arcs and <= 1024 states each),
+                               single otherwise */
 };
 
 /* Arrays that fb_graph_layout can copy out (graph-layout step; integer work, one
@@ -212,6 +226,19 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
  * pdfs fit in the 160 KB of on-chip memory of a gfx950 compute unit.
  * shared != 0: shared-graph kernels; 0: packed-graph kernels. */
 int32_t fb_limits_max_states(int32_t D, int shared);
+
+/*
+ * Stage timing of lfmmi_loss_grad, for benchmarks.  fb_profile_enable(1) creates
+ * five HIP events (the only allocation; not allowed while a stream is being
+ * captured); while enabled, lfmmi_loss_grad records one before and after each of
+ * its four kernel launches on the caller's stream.  fb_profile_read waits for the
+ * last recorded event and returns the milliseconds of the latest call's stages:
+ * ms[0] numerator recursions, ms[1] denominator recursions, ms[2] posteriors and
+ * gradient, ms[3] objective.  FB_EINVAL if profiling is off, ms is NULL (host
+ * pointer) or no call was recorded.  fb_profile_enable(0) destroys the events.
+ */
+int fb_profile_enable(int on);
+int fb_profile_read(float *ms);
 
 const char *fb_strerror(int code);
 const char *fb_last_error(void);

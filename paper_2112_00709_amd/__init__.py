@@ -20,14 +20,15 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfb_amd.so")
 
 FB_OK, FB_EINVAL, FB_ENOMEM, FB_EHIP, FB_EUNSUPPORTED = 0, -1, -2, -3, -4
-FB_GRAPH_HOST_ONLY = 1
+FB_GRAPH_HOST_ONLY, FB_GRAPH_WIDE_STATE, FB_GRAPH_NARROW_STATE = 1, 2, 4
 LAYOUT = {"in_ptr": 0, "in_src": 1, "in_w": 2, "in_perm": 3, "out_ptr": 4, "out_dst": 5, "out_w": 6,
           "out_perm": 7, "pdf_ptr": 8, "pdf_states": 9}
 
 # every symbol include/fb.h declares
 SYMBOLS = ["fb_graph_create", "fb_graph_destroy", "fb_graph_layout_size", "fb_graph_layout", "fb_check_lengths",
            "fb_alpha", "fb_beta", "fb_posteriors", "fb_lfmmi_workspace_bytes", "lfmmi_loss_grad",
-           "fb_limits_max_states", "fb_strerror", "fb_last_error", "fb_graph_schedule_apply_host"]
+           "fb_limits_max_states", "fb_strerror", "fb_last_error", "fb_graph_schedule_apply_host",
+           "fb_profile_enable", "fb_profile_read"]
 
 
 class FBError(RuntimeError):
@@ -71,6 +72,10 @@ def lib() -> ctypes.CDLL:
         L.lfmmi_loss_grad.restype = ctypes.c_int
         L.fb_limits_max_states.argtypes = [i32, ctypes.c_int]
         L.fb_limits_max_states.restype = i32
+        L.fb_profile_enable.argtypes = [ctypes.c_int]
+        L.fb_profile_enable.restype = ctypes.c_int
+        L.fb_profile_read.argtypes = [vp]
+        L.fb_profile_read.restype = ctypes.c_int
         L.fb_strerror.argtypes = [ctypes.c_int]
         L.fb_strerror.restype = ctypes.c_char_p
         L.fb_last_error.restype = ctypes.c_char_p
@@ -119,7 +124,9 @@ class Graph:
             pass
 
 
-def fb_graph_create(K, src, dst, logw, pdf, init, final, D, state_off=None, host_only=False) -> Graph:
+def fb_graph_create(K, src, dst, logw, pdf, init, final, D, state_off=None, host_only=False, state="auto") -> Graph:
+    """state: 'auto', 'wide' (double carriers) or 'narrow' (single carriers)."""
+    flags = (FB_GRAPH_HOST_ONLY if host_only else 0) | {"auto": 0, "wide": FB_GRAPH_WIDE_STATE, "narrow": FB_GRAPH_NARROW_STATE}[state]
     src, dst, logw = _np(src, np.int32), _np(dst, np.int32), _np(logw, np.float32)
     pdf, init, final = _np(pdf, np.int32), _np(init, np.float32), _np(final, np.float32)
     state_off = _np(state_off, np.int32)
@@ -127,13 +134,13 @@ def fb_graph_create(K, src, dst, logw, pdf, init, final, D, state_off=None, host
     n_seq = 0 if state_off is None else int(state_off.shape[0]) - 1
     h = ctypes.c_void_p()
     _check(lib().fb_graph_create(ctypes.byref(h), int(K), E, _hp(src), _hp(dst), _hp(logw), _hp(pdf), _hp(init),
-                                 _hp(final), int(D), n_seq, _hp(state_off), FB_GRAPH_HOST_ONLY if host_only else 0))
+                                 _hp(final), int(D), n_seq, _hp(state_off), flags))
     return Graph(h, int(K), E, int(D), n_seq, host_only)
 
 
-def graph_from(g, D: int, host_only: bool = False) -> Graph:
+def graph_from(g, D: int, host_only: bool = False, state: str = "auto") -> Graph:
     """Build from an object with fields K, src, dst, logw, pdf, init, final, state_off."""
-    return fb_graph_create(g.K, g.src, g.dst, g.logw, g.pdf, g.init, g.final, D, g.state_off, host_only)
+    return fb_graph_create(g.K, g.src, g.dst, g.logw, g.pdf, g.init, g.final, D, g.state_off, host_only, state)
 
 
 def fb_graph_layout(g: Graph, name: str) -> np.ndarray:
@@ -156,6 +163,17 @@ def fb_graph_schedule_apply_host(g: Graph, which: int, sub: int, x: np.ndarray, 
 def fb_check_lengths(lengths, N: int) -> None:
     lengths = _np(lengths, np.int32)
     _check(lib().fb_check_lengths(_hp(lengths), int(lengths.shape[0]), int(N)))
+
+
+def fb_profile_enable(on: bool) -> None:
+    _check(lib().fb_profile_enable(1 if on else 0))
+
+
+def fb_profile_read() -> dict:
+    """Milliseconds of the stages of the latest lfmmi_loss_grad call (waits for it)."""
+    ms = (ctypes.c_float * 4)()
+    _check(lib().fb_profile_read(ctypes.cast(ms, ctypes.c_void_p)))
+    return {"num_recursion": ms[0], "den_recursion": ms[1], "posteriors_grad": ms[2], "loss": ms[3]}
 
 
 def fb_limits_max_states(D: int, shared: bool) -> int:

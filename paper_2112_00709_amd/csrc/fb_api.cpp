@@ -1,4 +1,6 @@
 // The compute entry points of the C ABI: argument checks and kernel launches.
+#include <hip/hip_runtime_api.h>
+
 #include <algorithm>
 
 #include "fb_internal.h"
@@ -22,14 +24,15 @@ int check_common(const char *who, const fb_graph *g, const void *p1, const void 
     return FB_OK;
 }
 
-RecDir make_dir(const fb_graph *g, bool backward, float *out, float *off, double *logz, float out_scale,
-                bool fill_pad = true)
+RecDir make_dir(const fb_graph *g, bool backward, void *out, bool out_carrier, float *off, double *logz,
+                float out_scale, bool fill_pad)
 {
     RecDir r{};
     r.sched = backward ? g->bwd : g->fwd;
     r.bound = backward ? g->d_final2 : g->d_init2;
     r.obound = backward ? g->d_init2 : g->d_final2;
     r.out = out;
+    r.out_carrier = out_carrier ? 1 : 0;
     r.off = off;
     r.logz = logz;
     r.out_scale = out_scale;
@@ -58,14 +61,15 @@ int run_recursion(const fb_graph *g, const float *emis, const int32_t *lengths, 
     p.Pcap = std::max(g->h_fwd.max_part, g->h_bwd.max_part);
     p.Ecap = p.shared ? D : g->max_sub_K;
     p.any_backward = any_bwd;
-    const size_t lds = recursion_lds_bytes(p.Kcap, p.Pcap, p.Ecap, any_bwd);
+    const size_t lds = recursion_lds_bytes(p.Kcap, p.Pcap, p.Ecap, any_bwd, g->f64);
     if (lds > kLdsBytes) return fail(FB_EUNSUPPORTED, "state vectors and emission rows exceed the on-chip memory");
-    return launch_recursion(g->nw, p, lds, stream);
+    return launch_recursion(g->nw, g->f64, p, lds, stream);
 }
 
-PostGraph make_post(const fb_graph *g, const float *a, const float *b, float in_scale, float *state_post)
+PostGraph make_post(const fb_graph *g, const void *a, const void *b, bool f64, float in_scale, float *state_post)
 {
     PostGraph q{};
+    q.f64 = f64 ? 1 : 0;
     q.pdfs = g->pdfs;
     q.sub = g->pdfs.sub;
     q.a = a;
@@ -85,20 +89,64 @@ int run_posteriors(const PostGraph *gs, const fb_graph *const *graphs, int n_gra
     for (int i = 0; i < n_graph; ++i) {
         p.g[i] = gs[i];
         p.Kcap = std::max(p.Kcap, graphs[i]->max_sub_K);
+        if (gs[i].f64) p.Kcap64 = std::max(p.Kcap64, graphs[i]->max_sub_K);
         p.Pcap = std::max(p.Pcap, graphs[i]->h_pdf.max_part);
     }
     p.lengths = lengths;
     p.B = B; p.N = N; p.D = D;
     p.pdf_out = pdf_out;
     p.frames_per_block = 4;
-    const size_t lds = posterior_lds_bytes(p.Kcap, p.Pcap, D);
+    const size_t lds = 64 + (size_t)p.Kcap64 * 8 + ((size_t)p.Kcap + p.Pcap + D) * 4 + kLdsReserve;
     if (lds > kLdsBytes) return fail(FB_EUNSUPPORTED, "state vector and pdf row exceed the on-chip memory");
     return launch_posteriors(p, lds, stream);
 }
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// stage timing of lfmmi_loss_grad (fb_profile_enable / fb_profile_read)
+struct Profile {
+    bool on = false, recorded = false;
+    hipEvent_t ev[5] = {};
+} g_prof;
+
+void mark(int i, fb_stream stream)
+{
+    if (g_prof.on) (void)hipEventRecord(g_prof.ev[i], (hipStream_t)stream);
+}
+
 }  // namespace
+
+extern "C" {
+
+int fb_profile_enable(int on)
+{
+    if (on && !g_prof.on) {
+        for (int i = 0; i < 5; ++i)
+            if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) {
+                for (int j = 0; j < i; ++j) (void)hipEventDestroy(g_prof.ev[j]);
+                return fail(FB_EHIP, "fb_profile_enable: hipEventCreate failed");
+            }
+        g_prof.on = true;
+        g_prof.recorded = false;
+    } else if (!on && g_prof.on) {
+        for (int i = 0; i < 5; ++i) (void)hipEventDestroy(g_prof.ev[i]);
+        g_prof.on = false;
+        g_prof.recorded = false;
+    }
+    return FB_OK;
+}
+
+int fb_profile_read(float *ms)
+{
+    if (!g_prof.on || !g_prof.recorded || !ms) return fail(FB_EINVAL, "fb_profile_read: nothing recorded");
+    if (hipEventSynchronize(g_prof.ev[4]) != hipSuccess) return fail(FB_EHIP, "fb_profile_read: hipEventSynchronize failed");
+    for (int i = 0; i < 4; ++i)
+        if (hipEventElapsedTime(&ms[i], g_prof.ev[i], g_prof.ev[i + 1]) != hipSuccess)
+            return fail(FB_EHIP, "fb_profile_read: hipEventElapsedTime failed");
+    return FB_OK;
+}
+
+}  // extern "C"
 
 extern "C" {
 
@@ -107,7 +155,7 @@ int fb_alpha(const fb_graph *g, const float *emis, const int32_t *lengths, int32
 {
     int rc = check_common("fb_alpha", g, emis, lengths, B, N, D);
     if (rc) return rc;
-    const RecDir d = make_dir(g, false, alpha, alpha_off, logz, kLn2f);
+    const RecDir d = make_dir(g, false, alpha, false, alpha_off, logz, kLn2f, true);
     return run_recursion(g, emis, lengths, B, N, D, &d, 1, stream);
 }
 
@@ -116,7 +164,7 @@ int fb_beta(const fb_graph *g, const float *emis, const int32_t *lengths, int32_
 {
     int rc = check_common("fb_beta", g, emis, lengths, B, N, D);
     if (rc) return rc;
-    const RecDir d = make_dir(g, true, beta, beta_off, logz, kLn2f);
+    const RecDir d = make_dir(g, true, beta, false, beta_off, logz, kLn2f, true);
     return run_recursion(g, emis, lengths, B, N, D, &d, 1, stream);
 }
 
@@ -127,15 +175,15 @@ int fb_posteriors(const fb_graph *g, const float *alpha, const float *beta, cons
     if (rc) return rc;
     if (!lengths) return fail(FB_EINVAL, "fb_posteriors: lengths is NULL");
     if (!state_post && !pdf_post) return fail(FB_EINVAL, "fb_posteriors: no output requested");
-    const PostGraph q = make_post(g, alpha, beta, kLog2ef, state_post);
+    const PostGraph q = make_post(g, alpha, beta, false, kLog2ef, state_post);
     return run_posteriors(&q, &g, 1, lengths, B, N, D, pdf_post, stream);
 }
 
 size_t fb_lfmmi_workspace_bytes(const fb_graph *den, const fb_graph *num, int32_t B, int32_t N, int32_t D)
 {
     if (!den || !num || B <= 0 || N <= 0 || D <= 0) return 0;
-    const size_t den_vec = align256((size_t)B * N * den->K * sizeof(float));
-    const size_t num_vec = align256((size_t)N * num->K * sizeof(float));
+    const size_t den_vec = align256((size_t)B * N * den->K * (den->f64 ? 8 : 4));
+    const size_t num_vec = align256((size_t)N * num->K * (num->f64 ? 8 : 4));
     const size_t z = align256((size_t)B * sizeof(double));
     return 2 * den_vec + 2 * num_vec + 2 * z;
 }
@@ -156,28 +204,36 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
 
     // workspace: forward and backward vectors of both graphs in log2 units, log Z when the caller keeps none
     char *w = (char *)ws;
-    const size_t den_vec = align256((size_t)B * N * den->K * sizeof(float));
-    const size_t num_vec = align256((size_t)N * num->K * sizeof(float));
-    float *den_a = (float *)w; w += den_vec;
-    float *den_b = (float *)w; w += den_vec;
-    float *num_a = (float *)w; w += num_vec;
-    float *num_b = (float *)w; w += num_vec;
+    const size_t den_vec = align256((size_t)B * N * den->K * (den->f64 ? 8 : 4));
+    const size_t num_vec = align256((size_t)N * num->K * (num->f64 ? 8 : 4));
+    void *den_a = w; w += den_vec;
+    void *den_b = w; w += den_vec;
+    void *num_a = w; w += num_vec;
+    void *num_b = w; w += num_vec;
     double *zn = logz_num ? logz_num : (double *)w; w += align256((size_t)B * sizeof(double));
     double *zd = logz_den ? logz_den : (double *)w;
 
     // both recursions of a graph run side by side in one launch
-    RecDir dn[2] = {make_dir(num, false, num_a, nullptr, zn, 1.0f, false),
-                    make_dir(num, true, num_b, nullptr, nullptr, 1.0f, false)};
+    RecDir dn[2] = {make_dir(num, false, num_a, true, nullptr, zn, 1.0f, false),
+                    make_dir(num, true, num_b, true, nullptr, nullptr, 1.0f, false)};
+    mark(0, stream);
     if ((rc = run_recursion(num, emis, lengths, B, N, D, dn, 2, stream))) return rc;
-    RecDir dd[2] = {make_dir(den, false, den_a, nullptr, zd, 1.0f, false),
-                    make_dir(den, true, den_b, nullptr, nullptr, 1.0f, false)};
+    mark(1, stream);
+    RecDir dd[2] = {make_dir(den, false, den_a, true, nullptr, zd, 1.0f, false),
+                    make_dir(den, true, den_b, true, nullptr, nullptr, 1.0f, false)};
     if ((rc = run_recursion(den, emis, lengths, B, N, D, dd, 2, stream))) return rc;
+    mark(2, stream);
 
     // Eq. 17: numerator pdf posteriors minus denominator pdf posteriors
-    const PostGraph q[2] = {make_post(num, num_a, num_b, 1.0f, nullptr), make_post(den, den_a, den_b, 1.0f, nullptr)};
+    const PostGraph q[2] = {make_post(num, num_a, num_b, num->f64, 1.0f, nullptr),
+                            make_post(den, den_a, den_b, den->f64, 1.0f, nullptr)};
     const fb_graph *gs[2] = {num, den};
     if ((rc = run_posteriors(q, gs, 2, lengths, B, N, D, grad, stream))) return rc;
-    return launch_loss(zn, zd, lengths, B, loss, stream);
+    mark(3, stream);
+    rc = launch_loss(zn, zd, lengths, B, loss, stream);
+    mark(4, stream);
+    if (g_prof.on && rc == FB_OK) g_prof.recorded = true;
+    return rc;
 }
 
 }  // extern "C"

@@ -71,14 +71,14 @@ int upload_sell(fb_graph *g, const SellHost &h, SellDev &d)
 
 }  // namespace
 
-size_t recursion_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t Ecap, bool any_backward)
+size_t recursion_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t Ecap, bool any_backward, bool f64)
 {
-    return ((size_t)Kcap * (any_backward ? 4 : 2) + (size_t)Pcap + 2 * (size_t)Ecap) * 4 + kLdsReserve;
+    return ((size_t)Kcap * (any_backward ? 4 : 2) + (size_t)Pcap + 2 * (size_t)Ecap) * (f64 ? 8 : 4) + kLdsReserve;
 }
 
-size_t posterior_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t D)
+size_t posterior_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t D, bool f64)
 {
-    return ((size_t)Kcap + (size_t)Pcap + (size_t)D) * 4 + kLdsReserve;
+    return 64 + (f64 ? (size_t)Kcap * 8 : 0) + ((size_t)Kcap + (size_t)Pcap + (size_t)D) * 4 + kLdsReserve;
 }
 
 }  // namespace fb
@@ -132,6 +132,8 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
     if (E > INT32_MAX / 2) return fail(FB_EUNSUPPORTED, "fb_graph_create: more than 2^30 arcs");
     if ((E > 0 && (!src || !dst || !logw)) || !pdf || !init || !final_)
         return fail(FB_EINVAL, "fb_graph_create: NULL array");
+    if ((flags & FB_GRAPH_WIDE_STATE) && (flags & FB_GRAPH_NARROW_STATE))
+        return fail(FB_EINVAL, "fb_graph_create: FB_GRAPH_WIDE_STATE and FB_GRAPH_NARROW_STATE exclude each other");
     if (n_seq < 0 || (n_seq > 0) != (state_off != nullptr))
         return fail(FB_EINVAL, "fb_graph_create: n_seq and state_off must be given together");
     for (int64_t e = 0; e < E; ++e) {
@@ -189,6 +191,7 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
             max_sub_E = std::max<int64_t>(max_sub_E, (int64_t)L.in_ptr[k1] - L.in_ptr[k0]);
         }
         g->nw = (max_sub_E >= 4096 || g->max_sub_K > 1024) ? kNWShared : kNWSmall;
+        g->f64 = (flags & FB_GRAPH_WIDE_STATE) ? true : (flags & FB_GRAPH_NARROW_STATE) ? false : g->nw == kNWSmall;
         g->h_fwd.nw = g->h_bwd.nw = g->nw;
         g->h_pdf.nw = kNWSmall;   // the posterior kernel always runs four waves
 
@@ -249,8 +252,8 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
         }
         const int32_t Pcap = std::max(g->h_fwd.max_part, g->h_bwd.max_part);
         const int32_t Ecap = n_seq > 0 ? g->max_sub_K : D;
-        if (rc == FB_OK && (recursion_lds_bytes(g->max_sub_K, Pcap, Ecap, true) > kLdsBytes ||
-            posterior_lds_bytes(g->max_sub_K, g->h_pdf.max_part, D) > kLdsBytes)) {
+        if (rc == FB_OK && (recursion_lds_bytes(g->max_sub_K, Pcap, Ecap, true, g->f64) > kLdsBytes ||
+            posterior_lds_bytes(g->max_sub_K, g->h_pdf.max_part, D, g->f64) > kLdsBytes)) {
             rc = fail(FB_EUNSUPPORTED, "graph too large: " + std::to_string(g->max_sub_K) + " states, " +
                                            std::to_string(Pcap) + " partial slots and " + std::to_string(Ecap) +
                                            " emission entries do not fit the on-chip memory of a compute unit");

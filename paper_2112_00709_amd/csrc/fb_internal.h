@@ -82,6 +82,7 @@ struct fb_graph {
     int nw = 0;                       // waves per workgroup its schedules were built for
     int32_t max_sub_K = 0;
     bool host_only = false;
+    bool f64 = false;                 // state vectors carried in double (exponentials stay single)
     fb::HostLayout lay;
     std::vector<int32_t> state_off;   // packed only
     fb::SellHost h_fwd, h_bwd, h_pdf; // host schedules (kept for size queries)
@@ -102,7 +103,8 @@ struct RecDir {
     SellDev sched;
     const float *bound;    // start weights of this direction (init2 forward, final2 backward)
     const float *obound;   // end weights, for log Z
-    float *out;            // normalised vectors, nullable
+    void *out;             // normalised vectors, nullable: float, or the carrier type if out_carrier
+    int out_carrier;       // out holds carrier-type values (workspace), not float
     float *off;            // [B][N] offsets, nullable
     double *logz;          // [B], nullable
     float out_scale;       // ln 2 for natural-log output, 1 to keep log2 units
@@ -123,7 +125,8 @@ struct RecParams {
 struct PostGraph {
     SellDev pdfs;          // plain-sum schedule states -> pdfs
     const SubDesc *sub;    // same as pdfs.sub
-    const float *a, *b;    // normalised forward / backward vectors
+    const void *a, *b;     // normalised forward / backward vectors, float or double
+    int f64;               // a, b are double
     float in_scale;        // log2(e) if a, b are natural logs, 1 if log2 units
     int32_t shared, Ktot;
     float *state_post;     // nullable
@@ -135,14 +138,14 @@ struct PostParams {
     const int32_t *lengths;
     int32_t B, N, D;
     float *pdf_out;        // [B][N][D], nullable
-    int32_t Kcap, Pcap, frames_per_block;
+    int32_t Kcap, Kcap64, Pcap, frames_per_block;   // Kcap64: largest double-carrier (sub-)graph
 };
 
-int launch_recursion(int nw, const RecParams &p, size_t lds_bytes, void *stream);
+int launch_recursion(int nw, bool f64, const RecParams &p, size_t lds_bytes, void *stream);
 int launch_posteriors(const PostParams &p, size_t lds_bytes, void *stream);
 int launch_loss(const double *logz_num, const double *logz_den, const int32_t *lengths, int32_t B, double *loss,
                 void *stream);
-size_t recursion_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t Ecap, bool any_backward);
-size_t posterior_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t D);
+size_t recursion_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t Ecap, bool any_backward, bool f64);
+size_t posterior_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t D, bool f64);
 
 }  // namespace fb

@@ -18,7 +18,9 @@
 // maximum: one exponential per arc, one logarithm per row.  The state vector is
 // kept normalised: every step subtracts the previous step's maximum, the
 // subtracted amounts are the offsets handed back to the caller and their sum is
-// accumulated in double for log Z.
+// accumulated in double for log Z.  The vector's element type ("carrier") is
+// float or double; exponentials and logarithms are single precision either way
+// (they act on differences to the running maximum, which are small).
 #include <hip/hip_runtime.h>
 
 #include "fb_internal.h"
@@ -28,33 +30,39 @@ namespace fb {
 namespace {
 
 constexpr float kNegBig = -1.0e30f;   // stands for "no finite term yet"; values below it count as semiring zero
-constexpr float kLog2e = 1.44269504088896340736f;
+constexpr double kLog2e = 1.4426950408889634074;
 constexpr double kLn2 = 0.69314718055994530942;
 constexpr int kEPT = 4;               // emission elements a thread prefetches per frame
 
 __device__ __forceinline__ float fexp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float flog2(float x) { return __builtin_amdgcn_logf(x); }
 
-// running (+)-sum in base 2: value = m + log2(s)
-__device__ __forceinline__ void lse_add(float &m, float &s, float x)
+// running (+)-sum in base 2: value = m + log2(s); m in the carrier type, s single
+template <class T>
+__device__ __forceinline__ void lse_add(T &m, float &s, T x)
 {
-    const float d = x - m;
+    const float d = (float)(x - m);
     const float e = fexp2(-fabsf(d));
     s = d > 0.0f ? fmaf(s, e, 1.0f) : s + e;
-    m = fmaxf(m, x);
+    m = x > m ? x : m;
 }
 
-__device__ __forceinline__ void lse_merge(float &m, float &s, float m2, float s2)
+template <class T>
+__device__ __forceinline__ void lse_merge(T &m, float &s, T m2, float s2)
 {
-    const float M = fmaxf(m, m2);
-    s = s * fexp2(m - M) + s2 * fexp2(m2 - M);
+    const T M = m2 > m ? m2 : m;
+    s = s * fexp2((float)(m - M)) + s2 * fexp2((float)(m2 - M));
     m = M;
 }
 
-__device__ __forceinline__ float wave_max(float v)
+template <class T>
+__device__ __forceinline__ T wave_max(T v)
 {
 #pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    for (int o = 32; o >= 1; o >>= 1) {
+        const T u = __shfl_xor(v, o, 64);
+        v = u > v ? u : v;
+    }
     return v;
 }
 
@@ -66,20 +74,21 @@ __device__ __forceinline__ float wave_sum(float v)
 }
 
 // One level of a log-semiring schedule for this wave: every lane walks its row.
-template <class Fin>
-__device__ __forceinline__ void sell_log_level(const SellDev &S, int wp, const float *vbase, float *part, int lane, Fin fin)
+template <class T, class Fin>
+__device__ __forceinline__ void sell_log_level(const SellDev &S, int wp, const T *vbase, T *part, int lane, Fin fin)
 {
     const int s0 = S.wave_ptr[wp], s1 = S.wave_ptr[wp + 1];
     for (int s = s0; s < s1; ++s) {
         const int trip = S.slice_trip[s];
         const Arc *ap = S.arcs + S.slice_arc[s] + lane;
-        float m = kNegBig, sum = 0.0f;
+        T m = (T)kNegBig;
+        float sum = 0.0f;
         int it = 0;
         for (; it + 4 <= trip; it += 4) {
             const Arc a0 = ap[0], a1 = ap[kWave], a2 = ap[2 * kWave], a3 = ap[3 * kWave];
             ap += 4 * kWave;
-            const float x0 = vbase[a0.src] + a0.w, x1 = vbase[a1.src] + a1.w;
-            const float x2 = vbase[a2.src] + a2.w, x3 = vbase[a3.src] + a3.w;
+            const T x0 = vbase[a0.src] + (T)a0.w, x1 = vbase[a1.src] + (T)a1.w;
+            const T x2 = vbase[a2.src] + (T)a2.w, x3 = vbase[a3.src] + (T)a3.w;
             lse_add(m, sum, x0);
             lse_add(m, sum, x1);
             lse_add(m, sum, x2);
@@ -88,9 +97,9 @@ __device__ __forceinline__ void sell_log_level(const SellDev &S, int wp, const f
         for (; it < trip; ++it) {
             const Arc a = ap[0];
             ap += kWave;
-            lse_add(m, sum, vbase[a.src] + a.w);
+            lse_add(m, sum, vbase[a.src] + (T)a.w);
         }
-        const float val = m + flog2(sum);   // sum == 0 -> -inf
+        const T val = m + (T)flog2(sum);   // sum == 0 -> -inf
         const int o = S.row_out[s * kWave + lane];
         if (o >= 0)
             fin(o, S.row_vidx[s * kWave + lane], val);
@@ -132,12 +141,14 @@ __device__ __forceinline__ void sell_sum_level(const SellDev &S, int wp, const f
 //   forward   x_n = alpha_n              = v_n o (+)_{in(j)}  (w (x) x_{n-1}[src])
 //   backward  x_n = beta_n (x) v_n       = v_n o (+)_{out(i)} (w (x) x_{n+1}[dst])
 // and beta_n itself is the row sum before v_n is applied.
+// T: carrier type of the vectors (float or double).
 // ---------------------------------------------------------------------------
-template <int NW>
+template <int NW, class T>
 __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P)
 {
-    extern __shared__ float lds[];
+    extern __shared__ double lds_raw[];
     constexpr int NT = NW * kWave;
+    const T kNegInf = (T)(-INFINITY);
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int b = blockIdx.x % P.B;
@@ -146,26 +157,33 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
     const bool bwd = R.backward != 0;
     const SubDesc sd = S.sub[P.shared ? 0 : b];
     const int K = sd.K, k0 = sd.k0, L = sd.n_levels;
-    const int T = min(max(P.lengths[b], 0), P.N);
+    const int Tn = min(max(P.lengths[b], 0), P.N);
     const int nE = P.shared ? P.D : K;           // entries of a staged emission vector
 
-    float *xb = lds;                             // x, two buffers of Kcap
-    float *bh = xb + 2 * P.Kcap;                 // beta before v is applied, two buffers (backward only)
-    float *part = bh + (P.any_backward ? 2 * P.Kcap : 0);
-    float *er = part + P.Pcap;                   // staged emissions (log2 units), two buffers of Ecap
-    float *red = er + 2 * P.Ecap;                // [2][NW] step maxima, then scratch for the last reduction
+    T *xb = (T *)lds_raw;                        // x, two buffers of Kcap
+    T *bh = xb + 2 * P.Kcap;                     // beta before v is applied, two buffers (backward only)
+    T *part = bh + (P.any_backward ? 2 * P.Kcap : 0);
+    T *er = part + P.Pcap;                       // staged emissions (log2 units), two buffers of Ecap
+    T *red = er + 2 * P.Ecap;                    // [2][NW] step maxima, then scratch for the last reduction
 
     const float *em_seq = P.emis + (size_t)b * P.N * P.D;
-    float *out_seq = nullptr;
-    size_t out_ld = 0;
-    if (R.out) {
-        out_seq = P.shared ? R.out + (size_t)b * P.N * K : R.out + k0;
-        out_ld = P.shared ? (size_t)K : (size_t)P.Ktot;
-    }
+    const size_t out_ld = P.shared ? (size_t)K : (size_t)P.Ktot;
+    const size_t out_at = P.shared ? (size_t)b * P.N * K : (size_t)k0;
+    float *out_f = (R.out && !R.out_carrier) ? (float *)R.out + out_at : nullptr;
+    T *out_t = (R.out && R.out_carrier) ? (T *)R.out + out_at : nullptr;
     float *off_seq = R.off ? R.off + (size_t)b * P.N : nullptr;
-    auto frame = [&](int i) { return bwd ? T - 1 - i : i; };
+    auto frame = [&](int i) { return bwd ? Tn - 1 - i : i; };
+    auto write_row = [&](int f, const T *srcv) {   // coalesced copy of a finished vector to global memory
+        if (out_f) {
+            float *orow = out_f + (size_t)f * out_ld;
+            for (int k = tid; k < K; k += NT) orow[k] = (float)srcv[k] * R.out_scale;
+        } else if (out_t) {
+            T *orow = out_t + (size_t)f * out_ld;
+            for (int k = tid; k < K; k += NT) orow[k] = srcv[k];
+        }
+    };
 
-    if (T > 0) {
+    if (Tn > 0) {
         // which element of an emission row each staged entry comes from
         int eidx[kEPT];
 #pragma unroll
@@ -173,15 +191,16 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
             const int e = tid + j * NT;
             eidx[j] = e < nE ? (P.shared ? e : P.pdf[k0 + e]) : 0;
         }
-        auto stage_tail = [&](const float *row, float *dst) {   // entries beyond the prefetch registers
-            for (int e = kEPT * NT + tid; e < nE; e += NT) dst[e] = row[P.shared ? e : P.pdf[k0 + e]] * kLog2e;
+        auto scaled = [](float v) { return (T)((T)v * (T)kLog2e); };
+        auto stage_tail = [&](const float *row, T *dst) {   // entries beyond the prefetch registers
+            for (int e = kEPT * NT + tid; e < nE; e += NT) dst[e] = scaled(row[P.shared ? e : P.pdf[k0 + e]]);
         };
-        auto stage_direct = [&](int f, float *dst) {
+        auto stage_direct = [&](int f, T *dst) {
             const float *row = em_seq + (size_t)f * P.D;
 #pragma unroll
             for (int j = 0; j < kEPT; ++j) {
                 const int e = tid + j * NT;
-                if (e < nE) dst[e] = row[eidx[j]] * kLog2e;
+                if (e < nE) dst[e] = scaled(row[eidx[j]]);
             }
             stage_tail(row, dst);
         };
@@ -191,93 +210,85 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
 #pragma unroll
             for (int j = 0; j < kEPT; ++j) ereg[j] = (tid + j * NT < nE) ? row[eidx[j]] : 0.0f;
         };
-        auto commit = [&](int f, float *dst) {
+        auto commit = [&](int f, T *dst) {
 #pragma unroll
             for (int j = 0; j < kEPT; ++j) {
                 const int e = tid + j * NT;
-                if (e < nE) dst[e] = ereg[j] * kLog2e;
+                if (e < nE) dst[e] = scaled(ereg[j]);
             }
             if (nE > kEPT * NT) stage_tail(em_seq + (size_t)f * P.D, dst);
         };
 
         // ---- first frame of this direction: x = start weight (x) v
         stage_direct(frame(0), er);
-        if (T > 1) stage_direct(frame(1), er + P.Ecap);
+        if (Tn > 1) stage_direct(frame(1), er + P.Ecap);
         __syncthreads();
-        float wmax = -INFINITY;
+        T wmax = kNegInf;
         for (int k = tid; k < K; k += NT) {
-            const float s = R.bound[k0 + k];
-            const float x = s + er[P.shared ? P.pdf[k0 + k] : k];
+            const T s = (T)R.bound[k0 + k];
+            const T x = s + er[P.shared ? P.pdf[k0 + k] : k];
             xb[k] = x;
             if (bwd) bh[k] = s;
-            wmax = fmaxf(wmax, x);
+            wmax = x > wmax ? x : wmax;
         }
         wmax = wave_max(wmax);
         if (lane == 0) red[wave] = wmax;
-        if (T > 2) prefetch(frame(2));
+        if (Tn > 2) prefetch(frame(2));
         if (off_seq && tid == 0) off_seq[frame(0)] = 0.0f;
         __syncthreads();
 
         double csum = 0.0;
-        for (int i = 1; i < T; ++i) {
+        for (int i = 1; i < Tn; ++i) {
             const int cur = (i - 1) & 1, nxt = i & 1;
-            const float *xc = xb + cur * P.Kcap;
-            float *xn = xb + nxt * P.Kcap;
-            float *bn = bh + nxt * P.Kcap;
-            const float *ern = er + nxt * P.Ecap;
-            float M = red[cur * NW];
+            const T *xc = xb + cur * P.Kcap;
+            T *xn = xb + nxt * P.Kcap;
+            T *bn = bh + nxt * P.Kcap;
+            const T *ern = er + nxt * P.Ecap;
+            T M = red[cur * NW];
 #pragma unroll
-            for (int w = 1; w < NW; ++w) M = fmaxf(M, red[cur * NW + w]);
-            const float c = (M == -INFINITY) ? 0.0f : M;
+            for (int w = 1; w < NW; ++w) M = red[cur * NW + w] > M ? red[cur * NW + w] : M;
+            const T c = (M == kNegInf) ? (T)0 : M;
             csum += (double)c;
-            if (off_seq && tid == 0) off_seq[frame(i)] = c * R.out_scale;
-            if (out_seq) {   // vector of the previous step, now final, goes out coalesced
-                float *orow = out_seq + (size_t)frame(i - 1) * out_ld;
-                const float *srcv = bwd ? bh + cur * P.Kcap : xc;
-                for (int k = tid; k < K; k += NT) orow[k] = srcv[k] * R.out_scale;
-            }
-            wmax = -INFINITY;
-            auto fin = [&](int o, int vi, float val) {
-                const float pre = val - c;
-                const float x = pre + ern[vi];
+            if (off_seq && tid == 0) off_seq[frame(i)] = (float)c * R.out_scale;
+            write_row(frame(i - 1), bwd ? bh + cur * P.Kcap : xc);   // the previous step's vector is final now
+            wmax = kNegInf;
+            auto fin = [&](int o, int vi, T val) {
+                const T pre = val - c;
+                const T x = pre + ern[vi];
                 xn[o] = x;
                 if (bwd) bn[o] = pre;
-                wmax = fmaxf(wmax, x);
+                wmax = x > wmax ? x : wmax;
             };
             for (int l = 0; l < L; ++l) {
-                sell_log_level(S, sd.wave_ptr0 + l * NW + wave, l == 0 ? xc : part, part, lane, fin);
+                sell_log_level<T>(S, sd.wave_ptr0 + l * NW + wave, l == 0 ? xc : part, part, lane, fin);
                 if (l + 1 < L) __syncthreads();
             }
             // emissions two frames ahead: the row loaded during the last step goes to LDS,
             // the next row starts its trip from HBM
-            if (i + 1 < T) commit(frame(i + 1), er + cur * P.Ecap);
-            if (i + 2 < T) prefetch(frame(i + 2));
+            if (i + 1 < Tn) commit(frame(i + 1), er + cur * P.Ecap);
+            if (i + 2 < Tn) prefetch(frame(i + 2));
             wmax = wave_max(wmax);
             if (lane == 0) red[nxt * NW + wave] = wmax;
             __syncthreads();
         }
 
         // ---- last frame: write it out, close log Z with the end weights
-        const int last = (T - 1) & 1;
-        const float *xl = xb + last * P.Kcap;
-        if (out_seq) {
-            float *orow = out_seq + (size_t)frame(T - 1) * out_ld;
-            const float *srcv = bwd ? bh + last * P.Kcap : xl;
-            for (int k = tid; k < K; k += NT) orow[k] = srcv[k] * R.out_scale;
-        }
+        const int last = (Tn - 1) & 1;
+        const T *xl = xb + last * P.Kcap;
+        write_row(frame(Tn - 1), bwd ? bh + last * P.Kcap : xl);
         if (R.logz) {
-            float m = kNegBig, s = 0.0f;
-            for (int k = tid; k < K; k += NT) lse_add(m, s, xl[k] + R.obound[k0 + k]);
+            T m = (T)kNegBig;
+            float s = 0.0f;
+            for (int k = tid; k < K; k += NT) lse_add(m, s, xl[k] + (T)R.obound[k0 + k]);
 #pragma unroll
-            for (int o = 32; o >= 1; o >>= 1) lse_merge(m, s, __shfl_xor(m, o, 64), __shfl_xor(s, o, 64));
-            float *rm = red + 2 * NW, *rs = rm + NW;
-            if (lane == 0) { rm[wave] = m; rs[wave] = s; }
+            for (int o = 32; o >= 1; o >>= 1) lse_merge(m, s, (T)__shfl_xor(m, o, 64), __shfl_xor(s, o, 64));
+            T *rm = red + 2 * NW, *rs = rm + NW;
+            if (lane == 0) { rm[wave] = m; rs[wave] = (T)s; }
             __syncthreads();
             if (tid == 0) {
-                m = rm[0]; s = rs[0];
-                for (int w = 1; w < NW; ++w) lse_merge(m, s, rm[w], rs[w]);
-                const float r = m + flog2(s);
-                R.logz[b] = (csum + (double)r) * kLn2;
+                m = rm[0]; s = (float)rs[0];
+                for (int w = 1; w < NW; ++w) lse_merge(m, s, rm[w], (float)rs[w]);
+                R.logz[b] = (csum + (double)m + (double)flog2(s)) * kLn2;
             }
         }
     } else if (R.logz && tid == 0) {
@@ -285,13 +296,15 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
     }
 
     // ---- padded frames
-    if (out_seq && R.fill_pad)
-        for (int f = T; f < P.N; ++f) {
-            float *orow = out_seq + (size_t)f * out_ld;
-            for (int k = tid; k < K; k += NT) orow[k] = -INFINITY;
-        }
-    if (off_seq)
-        for (int f = T + tid; f < P.N; f += NT) off_seq[f] = 0.0f;
+    if (R.fill_pad) {
+        if (out_f)
+            for (int f = Tn; f < P.N; ++f) {
+                float *orow = out_f + (size_t)f * out_ld;
+                for (int k = tid; k < K; k += NT) orow[k] = -INFINITY;
+            }
+        if (off_seq)
+            for (int f = Tn + tid; f < P.N; f += NT) off_seq[f] = 0.0f;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -299,18 +312,65 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
 // posteriors; with two graphs the second is subtracted (Eq. 17).  grid =
 // (ceil(N / frames_per_block), B), 256 threads.
 // ---------------------------------------------------------------------------
+namespace {
+
+// gamma of one frame of one graph into tb[0..K): softmax over the states of
+// (a + b) * in_scale, in base 2.  IT: element type of a and b.
+template <class IT>
+__device__ __forceinline__ void frame_posteriors(const IT *arow, const IT *brow, IT in_scale, int K, float *tb,
+                                                 IT *stage, float *red, float *srow, int tid, int lane, int wave)
+{
+    constexpr int NT = kNWSmall * kWave;
+    IT mx = (IT)(-INFINITY);
+    for (int k = tid; k < K; k += NT) {
+        const IT t = (arow[k] + brow[k]) * in_scale;
+        stage[k] = t;
+        mx = t > mx ? t : mx;
+    }
+    mx = wave_max(mx);
+    IT *redt = (IT *)red;
+    if (lane == 0) redt[wave] = mx;
+    __syncthreads();
+    mx = redt[0];
+    for (int w = 1; w < kNWSmall; ++w) mx = redt[w] > mx ? redt[w] : mx;
+    __syncthreads();
+    float sum = 0.0f;
+    if (mx != (IT)(-INFINITY))
+        for (int k = tid; k < K; k += NT) {
+            const float e = fexp2((float)(stage[k] - mx));
+            tb[k] = e;      // tb may alias stage when IT is float: same index, read before write
+            sum += e;
+        }
+    else
+        for (int k = tid; k < K; k += NT) tb[k] = 0.0f;
+    sum = wave_sum(sum);
+    if (lane == 0) red[wave] = sum;
+    __syncthreads();
+    sum = (red[0] + red[1]) + (red[2] + red[3]);
+    const float inv = sum > 0.0f ? 1.0f / sum : 0.0f;
+    for (int k = tid; k < K; k += NT) {
+        const float gma = tb[k] * inv;
+        tb[k] = gma;
+        if (srow) srow[k] = gma;
+    }
+    __syncthreads();
+}
+
+}  // namespace
+
 __global__ __launch_bounds__(256) void fb_posterior_kernel(const PostParams P)
 {
-    extern __shared__ float lds[];
+    extern __shared__ double lds_raw[];
     constexpr int NW = kNWSmall, NT = NW * kWave;
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int b = blockIdx.y;
     const int T = min(max(P.lengths[b], 0), P.N);
-    float *tb = lds;                 // per-state values of the frame
+    float *red = (float *)lds_raw;                  // reduction slots: NW doubles or floats
+    double *stage64 = lds_raw + 8;                  // [Kcap64] log posteriors of a double-carrier graph
+    float *tb = (float *)(stage64 + P.Kcap64);      // [Kcap] per-state values of the frame
     float *part = tb + P.Kcap;
-    float *rho = part + P.Pcap;      // [D]
-    float *red = rho + P.D;          // [NW]
+    float *rho = part + P.Pcap;                     // [D]
 
     for (int fi = 0; fi < P.frames_per_block; ++fi) {
         const int n = blockIdx.x * P.frames_per_block + fi;
@@ -335,40 +395,13 @@ __global__ __launch_bounds__(256) void fb_posterior_kernel(const PostParams P)
             const SubDesc sd = G.sub[G.shared ? 0 : b];
             const int K = sd.K;
             const size_t at = G.shared ? ((size_t)b * P.N + n) * K : (size_t)n * G.Ktot + sd.k0;
-            const float *arow = G.a + at, *brow = G.b + at;
-            // log posterior up to the frame's normaliser, its maximum
-            float mx = -INFINITY;
-            for (int k = tid; k < K; k += NT) {
-                const float t = (arow[k] + brow[k]) * G.in_scale;
-                tb[k] = t;
-                mx = fmaxf(mx, t);
-            }
-            mx = wave_max(mx);
-            if (lane == 0) red[wave] = mx;
-            __syncthreads();
-            mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-            __syncthreads();
-            float sum = 0.0f;
-            if (mx != -INFINITY)
-                for (int k = tid; k < K; k += NT) {
-                    const float e = fexp2(tb[k] - mx);
-                    tb[k] = e;
-                    sum += e;
-                }
-            else
-                for (int k = tid; k < K; k += NT) tb[k] = 0.0f;
-            sum = wave_sum(sum);
-            if (lane == 0) red[wave] = sum;
-            __syncthreads();
-            sum = (red[0] + red[1]) + (red[2] + red[3]);
-            const float inv = sum > 0.0f ? 1.0f / sum : 0.0f;
             float *srow = G.state_post ? G.state_post + at : nullptr;
-            for (int k = tid; k < K; k += NT) {
-                const float gma = tb[k] * inv;
-                tb[k] = gma;
-                if (srow) srow[k] = gma;
-            }
-            __syncthreads();
+            if (G.f64)
+                frame_posteriors<double>((const double *)G.a + at, (const double *)G.b + at, (double)G.in_scale, K, tb,
+                                         stage64, red, srow, tid, lane, wave);
+            else
+                frame_posteriors<float>((const float *)G.a + at, (const float *)G.b + at, G.in_scale, K, tb, tb, red,
+                                        srow, tid, lane, wave);
             if (prow) {
                 const float sign = gi == 0 ? 1.0f : -1.0f;
                 auto fin = [&](int o, float v) { rho[o] += sign * v; };
@@ -413,34 +446,33 @@ static int check_launch(const char *what)
 }
 
 template <class Kern>
-static int allow_lds(Kern kern, size_t bytes)
+static int launch_rec(Kern kern, int nw, const RecParams &p, size_t lds_bytes, void *stream)
 {
-    if (bytes <= 64 * 1024) return FB_OK;
-    const hipError_t e =
-        hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-    if (e != hipSuccess) return fail(FB_EHIP, std::string("hipFuncSetAttribute(LDS size): ") + hipGetErrorString(e));
-    return FB_OK;
+    if (lds_bytes > 64 * 1024) {
+        const hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return fail(FB_EHIP, std::string("hipFuncSetAttribute(LDS size): ") + hipGetErrorString(e));
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)(p.B * p.n_dir)), dim3(nw * kWave), lds_bytes, (hipStream_t)stream, p);
+    return check_launch("recursion kernel launch");
 }
 
-int launch_recursion(int nw, const RecParams &p, size_t lds_bytes, void *stream)
+int launch_recursion(int nw, bool f64, const RecParams &p, size_t lds_bytes, void *stream)
 {
-    const dim3 grid((unsigned)(p.B * p.n_dir));
-    int rc;
-    if (nw == kNWShared) {
-        if ((rc = allow_lds(fb_recursion_kernel<kNWShared>, lds_bytes))) return rc;
-        hipLaunchKernelGGL(fb_recursion_kernel<kNWShared>, grid, dim3(kNWShared * kWave), lds_bytes, (hipStream_t)stream, p);
-    } else {
-        if ((rc = allow_lds(fb_recursion_kernel<kNWSmall>, lds_bytes))) return rc;
-        hipLaunchKernelGGL(fb_recursion_kernel<kNWSmall>, grid, dim3(kNWSmall * kWave), lds_bytes, (hipStream_t)stream, p);
-    }
-    return check_launch("recursion kernel launch");
+    if (nw == kNWShared)
+        return f64 ? launch_rec(fb_recursion_kernel<kNWShared, double>, nw, p, lds_bytes, stream)
+                   : launch_rec(fb_recursion_kernel<kNWShared, float>, nw, p, lds_bytes, stream);
+    return f64 ? launch_rec(fb_recursion_kernel<kNWSmall, double>, nw, p, lds_bytes, stream)
+               : launch_rec(fb_recursion_kernel<kNWSmall, float>, nw, p, lds_bytes, stream);
 }
 
 int launch_posteriors(const PostParams &p, size_t lds_bytes, void *stream)
 {
     const dim3 grid((unsigned)((p.N + p.frames_per_block - 1) / p.frames_per_block), (unsigned)p.B);
-    int rc;
-    if ((rc = allow_lds(fb_posterior_kernel, lds_bytes))) return rc;
+    if (lds_bytes > 64 * 1024) {
+        const hipError_t e =
+            hipFuncSetAttribute((const void *)fb_posterior_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return fail(FB_EHIP, std::string("hipFuncSetAttribute(LDS size): ") + hipGetErrorString(e));
+    }
     hipLaunchKernelGGL(fb_posterior_kernel, grid, dim3(256), lds_bytes, (hipStream_t)stream, p);
     return check_launch("posterior kernel launch");
 }
