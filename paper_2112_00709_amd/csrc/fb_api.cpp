@@ -61,7 +61,7 @@ int run_recursion(const fb_graph *g, const float *emis, const int32_t *lengths, 
     p.Pcap = std::max(g->h_fwd.max_part, g->h_bwd.max_part);
     p.Ecap = p.shared ? D : g->max_sub_K;
     p.any_backward = any_bwd;
-    const size_t lds = recursion_lds_bytes(p.Kcap, p.Pcap, p.Ecap, any_bwd, g->f64);
+    const size_t lds = recursion_lds_bytes(p.Kcap, p.Pcap, p.Ecap, any_bwd, g->f64, p.shared != 0);
     if (lds > kLdsBytes) return fail(FB_EUNSUPPORTED, "state vectors and emission rows exceed the on-chip memory");
     return launch_recursion(g->nw, g->f64, p, lds, stream);
 }

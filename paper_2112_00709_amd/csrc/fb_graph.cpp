@@ -69,11 +69,23 @@ int upload_sell(fb_graph *g, const SellHost &h, SellDev &d)
     return FB_OK;
 }
 
+int upload_stream(fb_graph *g, const StreamHost &h, StreamDev &d)
+{
+    int rc;
+    if ((rc = upload(g, h.sub, &d.sub))) return rc;
+    if ((rc = upload(g, h.waves, &d.waves))) return rc;
+    if ((rc = upload(g, h.flagwords, &d.flagwords))) return rc;
+    return upload(g, h.arcs, &d.arcs);
+}
+
 }  // namespace
 
-size_t recursion_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t Ecap, bool any_backward, bool f64)
+size_t recursion_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t Ecap, bool any_backward, bool f64, bool shared)
 {
-    return ((size_t)Kcap * (any_backward ? 4 : 2) + (size_t)Pcap + 2 * (size_t)Ecap) * (f64 ? 8 : 4) + kLdsReserve;
+    // carrier-typed: state vectors, partial slots, reduction slots; then two emission rows (float) and,
+    // for packed graphs, the pdf id of every state
+    return ((size_t)Kcap * (any_backward ? 4 : 2) + (size_t)Pcap + 4 * kNWShared) * (f64 ? 8 : 4) +
+           (size_t)Ecap * (shared ? 8 : 12) + kLdsReserve;
 }
 
 size_t posterior_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t D, bool f64)
@@ -192,7 +204,8 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
         }
         g->nw = (max_sub_E >= 4096 || g->max_sub_K > 1024) ? kNWShared : kNWSmall;
         g->f64 = (flags & FB_GRAPH_WIDE_STATE) ? true : (flags & FB_GRAPH_NARROW_STATE) ? false : g->nw == kNWSmall;
-        g->h_fwd.nw = g->h_bwd.nw = g->nw;
+        SellHost sell_fwd, sell_bwd;   // row-split plans of the two recursions, flattened into streams below
+        sell_fwd.nw = sell_bwd.nw = g->nw - 1;   // the last wave of a workgroup moves data, the others walk arcs
         g->h_pdf.nw = kNWSmall;   // the posterior kernel always runs four waves
 
         std::vector<int64_t> ptr;
@@ -213,7 +226,7 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
                     col[(size_t)(e - e0)] = other[(size_t)e] - k0;
                     w[(size_t)(e - e0)] = to_log2(ww[(size_t)e]);
                 }
-                sell_append(dir ? g->h_bwd : g->h_fwd, k0, Ks, Ks, ptr.data(), col.data(), w.data(), rid.data(),
+                sell_append(dir ? sell_bwd : sell_fwd, k0, Ks, Ks, ptr.data(), col.data(), w.data(), rid.data(),
                             vid.data(), -INFINITY, 0.0f);
             }
             // states -> pdfs, ordinary sums: one row per pdf (every pdf for a shared graph, the
@@ -246,13 +259,17 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
         {   // nothing a kernel will index may leave its array
             std::string why;
             const int32_t nv = n_seq > 0 ? -1 : D;
-            if (!sell_in_bounds(g->h_fwd, -1, nv, why) || !sell_in_bounds(g->h_bwd, -1, nv, why) ||
+            if (!sell_in_bounds(sell_fwd, -1, nv, why) || !sell_in_bounds(sell_bwd, -1, nv, why) ||
                 !sell_in_bounds(g->h_pdf, D, 1, why))
                 rc = fail(FB_EHIP, "internal error: schedule out of bounds (" + why + ")");
+            else if (!stream_from_sell(sell_fwd, g->h_fwd, why) || !stream_from_sell(sell_bwd, g->h_bwd, why))
+                rc = fail(FB_EUNSUPPORTED, "graph too large: " + why);
+            else if (!stream_in_bounds(g->h_fwd, nv, why) || !stream_in_bounds(g->h_bwd, nv, why))
+                rc = fail(FB_EHIP, "internal error: stream out of bounds (" + why + ")");
         }
         const int32_t Pcap = std::max(g->h_fwd.max_part, g->h_bwd.max_part);
         const int32_t Ecap = n_seq > 0 ? g->max_sub_K : D;
-        if (rc == FB_OK && (recursion_lds_bytes(g->max_sub_K, Pcap, Ecap, true, g->f64) > kLdsBytes ||
+        if (rc == FB_OK && (recursion_lds_bytes(g->max_sub_K, Pcap, Ecap, true, g->f64, n_seq == 0) > kLdsBytes ||
             posterior_lds_bytes(g->max_sub_K, g->h_pdf.max_part, D, g->f64) > kLdsBytes)) {
             rc = fail(FB_EUNSUPPORTED, "graph too large: " + std::to_string(g->max_sub_K) + " states, " +
                                            std::to_string(Pcap) + " partial slots and " + std::to_string(Ecap) +
@@ -266,7 +283,7 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
             std::vector<int32_t> hp(pdf, pdf + K);
             const int32_t *dp = nullptr; const float *di = nullptr, *df = nullptr;
             if (!(rc = upload(g, hp, &dp)) && !(rc = upload(g, i2, &di)) && !(rc = upload(g, f2, &df)) &&
-                !(rc = upload_sell(g, g->h_fwd, g->fwd)) && !(rc = upload_sell(g, g->h_bwd, g->bwd)))
+                !(rc = upload_stream(g, g->h_fwd, g->fwd)) && !(rc = upload_stream(g, g->h_bwd, g->bwd)))
                 rc = upload_sell(g, g->h_pdf, g->pdfs);
             g->d_pdf = const_cast<int32_t *>(dp); g->d_init2 = const_cast<float *>(di); g->d_final2 = const_cast<float *>(df);
         }
@@ -314,10 +331,10 @@ static const void *layout_array(const fb_graph *g, int which, int64_t *n)
 int fb_graph_schedule_apply_host(const fb_graph *g, int which, int32_t sub, const double *x, double *y)
 {
     if (!g || !x || !y) return fail(FB_EINVAL, "fb_graph_schedule_apply_host: NULL argument");
-    const SellHost *S = which == 0 ? &g->h_fwd : which == 1 ? &g->h_bwd : which == 2 ? &g->h_pdf : nullptr;
-    if (!S || sub < 0 || (size_t)sub >= S->sub.size())
+    if (which < 0 || which > 2 || sub < 0 || (size_t)sub >= g->h_pdf.sub.size())
         return fail(FB_EINVAL, "fb_graph_schedule_apply_host: unknown schedule or sub-graph");
-    sell_apply_host(*S, sub, which != 2, x, y);
+    if (which == 2) sell_apply_host(g->h_pdf, sub, false, x, y);
+    else stream_apply_host(which == 0 ? g->h_fwd : g->h_bwd, sub, x, y);
     return FB_OK;
 }
 

@@ -69,6 +69,52 @@ void sell_append(SellHost &out, int32_t k0, int32_t K, int32_t n_rows, const int
 bool sell_in_bounds(const SellHost &S, int32_t n_out, int32_t n_vidx, std::string &why);
 void sell_apply_host(const SellHost &S, int32_t sub, bool log_semiring, const double *x, double *y);
 
+// ---------------------------------------------------------------------------
+// Stream form of a log-semiring schedule: what the recursion kernel interprets.
+// Every wave of the workgroup owns one contiguous, cyclic stream of "rows" of 64
+// entries (one per lane), grouped in batches of kBatchRows rows.  A row is either
+// 64 arcs (one per lane: gather, add the weight, fold into the lane's running
+// sum) or an info row that closes the slice: its entries say where each lane's
+// finished sum goes (a state, a partial slot, nowhere) and which staged emission
+// it takes.  A byte of flags per batch tells the rows' kinds, whether the batch
+// is padding to skip, and whether a level (workgroup barrier) ends after it.
+// The stream of one time step is the same every step, so the kernel prefetches
+// it kRing-1 batches ahead, across barriers and across steps.
+// ---------------------------------------------------------------------------
+constexpr int kBatchRows = 4;
+constexpr int kRing = 4;                        // batches per unrolled iteration = prefetch ring size
+constexpr uint32_t kFlagInfoMask = 0x0f;        // bit r: row r of the batch is an info row
+constexpr uint32_t kFlagSkip = 0x10;            // nothing to do in this batch (padding)
+constexpr uint32_t kFlagLevelEnd = 0x20;        // workgroup barrier after this batch
+constexpr uint32_t kOutIdle = 0xffffu;          // info entry: lane has no row in this slice
+constexpr uint32_t kOutPartial = 0x8000u;       // info entry: bit set -> partial slot (low 15 bits)
+
+struct WaveDesc {
+    int64_t arc_base;    // first entry of the wave's stream in `arcs`
+    int32_t n_iter;      // unrolled iterations per time step: batches / kRing
+    int32_t flag_base;   // first of its n_iter flag words (one byte per batch)
+};
+
+struct StreamHost {
+    int nw = 0;
+    std::vector<SubDesc> sub;          // wave_ptr0 = index of the sub-graph's first WaveDesc
+    std::vector<WaveDesc> waves;
+    std::vector<uint32_t> flagwords;
+    std::vector<Arc> arcs;             // info entries: src = 0, w = bits of (out16 | vidx16 << 16)
+    int32_t max_part = 0;
+};
+
+struct StreamDev {
+    const SubDesc *sub = nullptr;
+    const WaveDesc *waves = nullptr;
+    const uint32_t *flagwords = nullptr;
+    const Arc *arcs = nullptr;
+};
+
+bool stream_from_sell(const SellHost &S, StreamHost &out, std::string &why);
+bool stream_in_bounds(const StreamHost &S, int32_t n_vidx, std::string &why);
+void stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double *y);
+
 struct HostLayout {                   // the graph-layout step, kept for fb_graph_layout
     std::vector<int32_t> in_ptr, in_src, in_perm, out_ptr, out_dst, out_perm, pdf_ptr, pdf_states;
     std::vector<float> in_w, out_w;
@@ -85,9 +131,11 @@ struct fb_graph {
     bool f64 = false;                 // state vectors carried in double (exponentials stay single)
     fb::HostLayout lay;
     std::vector<int32_t> state_off;   // packed only
-    fb::SellHost h_fwd, h_bwd, h_pdf; // host schedules (kept for size queries)
+    fb::StreamHost h_fwd, h_bwd;      // host schedules of the two recursions
+    fb::SellHost h_pdf;               // host schedule of the posterior accumulation
     // device
-    fb::SellDev fwd, bwd, pdfs;
+    fb::StreamDev fwd, bwd;
+    fb::SellDev pdfs;
     int32_t *d_pdf = nullptr;         // [K]
     float *d_init2 = nullptr;         // [K] init * log2(e)
     float *d_final2 = nullptr;        // [K] final * log2(e)
@@ -100,7 +148,7 @@ void set_error(const std::string &msg);
 int fail(int code, const std::string &msg);
 
 struct RecDir {
-    SellDev sched;
+    StreamDev sched;
     const float *bound;    // start weights of this direction (init2 forward, final2 backward)
     const float *obound;   // end weights, for log Z
     void *out;             // normalised vectors, nullable: float, or the carrier type if out_carrier
@@ -145,7 +193,7 @@ int launch_recursion(int nw, bool f64, const RecParams &p, size_t lds_bytes, voi
 int launch_posteriors(const PostParams &p, size_t lds_bytes, void *stream);
 int launch_loss(const double *logz_num, const double *logz_den, const int32_t *lengths, int32_t B, double *loss,
                 void *stream);
-size_t recursion_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t Ecap, bool any_backward, bool f64);
+size_t recursion_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t Ecap, bool any_backward, bool f64, bool shared);
 size_t posterior_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t D, bool f64);
 
 }  // namespace fb

@@ -9,8 +9,9 @@
 // a time step needs workgroup barriers only, never a grid-wide one, and the
 // forward and backward recursions of a batch run side by side in one launch.
 // Within a step the sparse product is walked one matrix row per lane along a
-// static row-split sliced-ELL schedule (fb_sell.cpp); the arcs stream from L2,
-// the gathered vector comes from LDS.
+// static row-split sliced-ELL schedule (fb_sell.cpp) flattened into one stream of
+// arcs per wave (fb_stream.cpp) that is prefetched several batches ahead; the arcs
+// come from L2, the gathered vector from LDS.
 //
 // Arithmetic.  Internally logs are base 2 (weights and emissions are scaled by
 // log2 e once), so the semiring sum is v_exp_f32 / v_log_f32 with no
@@ -32,10 +33,12 @@ namespace {
 constexpr float kNegBig = -1.0e30f;   // stands for "no finite term yet"; values below it count as semiring zero
 constexpr double kLog2e = 1.4426950408889634074;
 constexpr double kLn2 = 0.69314718055994530942;
-constexpr int kEPT = 4;               // emission elements a thread prefetches per frame
 
 __device__ __forceinline__ float fexp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float flog2(float x) { return __builtin_amdgcn_logf(x); }
+
+__device__ __forceinline__ float tmax(float a, float b) { return fmaxf(a, b); }
+__device__ __forceinline__ double tmax(double a, double b) { return fmax(a, b); }
 
 // running (+)-sum in base 2: value = m + log2(s); m in the carrier type, s single
 template <class T>
@@ -44,13 +47,25 @@ __device__ __forceinline__ void lse_add(T &m, float &s, T x)
     const float d = (float)(x - m);
     const float e = fexp2(-fabsf(d));
     s = d > 0.0f ? fmaf(s, e, 1.0f) : s + e;
-    m = x > m ? x : m;
+    m = tmax(m, x);
+}
+
+// four terms at once: one rescale of the running sum, then plain exponentials
+template <class T>
+__device__ __forceinline__ void lse_add4(T &m, float &s, T x0, T x1, T x2, T x3)
+{
+    const T mn = tmax(tmax(tmax(m, x0), x1), tmax(x2, x3));
+    const float r = fexp2((float)(m - mn));
+    const float e0 = fexp2((float)(x0 - mn)), e1 = fexp2((float)(x1 - mn));
+    const float e2 = fexp2((float)(x2 - mn)), e3 = fexp2((float)(x3 - mn));
+    s = fmaf(s, r, (e0 + e1) + (e2 + e3));
+    m = mn;
 }
 
 template <class T>
 __device__ __forceinline__ void lse_merge(T &m, float &s, T m2, float s2)
 {
-    const T M = m2 > m ? m2 : m;
+    const T M = tmax(m, m2);
     s = s * fexp2((float)(m - M)) + s2 * fexp2((float)(m2 - M));
     m = M;
 }
@@ -59,10 +74,7 @@ template <class T>
 __device__ __forceinline__ T wave_max(T v)
 {
 #pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-        const T u = __shfl_xor(v, o, 64);
-        v = u > v ? u : v;
-    }
+    for (int o = 32; o >= 1; o >>= 1) v = tmax(v, (T)__shfl_xor(v, o, 64));
     return v;
 }
 
@@ -71,41 +83,6 @@ __device__ __forceinline__ float wave_sum(float v)
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
     return v;
-}
-
-// One level of a log-semiring schedule for this wave: every lane walks its row.
-template <class T, class Fin>
-__device__ __forceinline__ void sell_log_level(const SellDev &S, int wp, const T *vbase, T *part, int lane, Fin fin)
-{
-    const int s0 = S.wave_ptr[wp], s1 = S.wave_ptr[wp + 1];
-    for (int s = s0; s < s1; ++s) {
-        const int trip = S.slice_trip[s];
-        const Arc *ap = S.arcs + S.slice_arc[s] + lane;
-        T m = (T)kNegBig;
-        float sum = 0.0f;
-        int it = 0;
-        for (; it + 4 <= trip; it += 4) {
-            const Arc a0 = ap[0], a1 = ap[kWave], a2 = ap[2 * kWave], a3 = ap[3 * kWave];
-            ap += 4 * kWave;
-            const T x0 = vbase[a0.src] + (T)a0.w, x1 = vbase[a1.src] + (T)a1.w;
-            const T x2 = vbase[a2.src] + (T)a2.w, x3 = vbase[a3.src] + (T)a3.w;
-            lse_add(m, sum, x0);
-            lse_add(m, sum, x1);
-            lse_add(m, sum, x2);
-            lse_add(m, sum, x3);
-        }
-        for (; it < trip; ++it) {
-            const Arc a = ap[0];
-            ap += kWave;
-            lse_add(m, sum, vbase[a.src] + (T)a.w);
-        }
-        const T val = m + (T)flog2(sum);   // sum == 0 -> -inf
-        const int o = S.row_out[s * kWave + lane];
-        if (o >= 0)
-            fin(o, S.row_vidx[s * kWave + lane], val);
-        else if (o < -1)
-            part[-2 - o] = val;
-    }
 }
 
 // One level of a plain-sum schedule (posterior accumulation over tied states).
@@ -141,19 +118,27 @@ __device__ __forceinline__ void sell_sum_level(const SellDev &S, int wp, const f
 //   forward   x_n = alpha_n              = v_n o (+)_{in(j)}  (w (x) x_{n-1}[src])
 //   backward  x_n = beta_n (x) v_n       = v_n o (+)_{out(i)} (w (x) x_{n+1}[dst])
 // and beta_n itself is the row sum before v_n is applied.
+//
+// Waves 0..NW-2 compute: their only global-memory traffic inside the time loop
+// is their own arc stream, a fixed sequence of loads that stays kRing-1 batches
+// ahead of its use, across barriers and across time steps.  Wave NW-1 moves data:
+// it brings the next frame's emissions from HBM straight into LDS, copies the
+// finished vector of the previous step out, keeps the offsets and log Z.  HBM
+// latency therefore never sits in front of an arc load.
 // T: carrier type of the vectors (float or double).
 // ---------------------------------------------------------------------------
 template <int NW, class T>
 __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P)
 {
     extern __shared__ double lds_raw[];
-    constexpr int NT = NW * kWave;
+    constexpr int NT = NW * kWave, NC = NW - 1;
     const T kNegInf = (T)(-INFINITY);
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool io_wave = wave == NC;
     const int b = blockIdx.x % P.B;
     const RecDir &R = P.dir[blockIdx.x / P.B];
-    const SellDev &S = R.sched;
+    const StreamDev &S = R.sched;
     const bool bwd = R.backward != 0;
     const SubDesc sd = S.sub[P.shared ? 0 : b];
     const int K = sd.K, k0 = sd.k0, L = sd.n_levels;
@@ -163,8 +148,9 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
     T *xb = (T *)lds_raw;                        // x, two buffers of Kcap
     T *bh = xb + 2 * P.Kcap;                     // beta before v is applied, two buffers (backward only)
     T *part = bh + (P.any_backward ? 2 * P.Kcap : 0);
-    T *er = part + P.Pcap;                       // staged emissions (log2 units), two buffers of Ecap
-    T *red = er + 2 * P.Ecap;                    // [2][NW] step maxima, then scratch for the last reduction
+    T *red = part + P.Pcap;                      // [2][NW] step maxima, then 2*NW for the last reduction
+    float *er = (float *)(red + 4 * NW);         // staged emissions (natural log, as given), two buffers of Ecap
+    int32_t *pix = (int32_t *)(er + 2 * P.Ecap); // packed graphs: pdf id of every state of the sub-graph
 
     const float *em_seq = P.emis + (size_t)b * P.N * P.D;
     const size_t out_ld = P.shared ? (size_t)K : (size_t)P.Ktot;
@@ -173,109 +159,183 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
     T *out_t = (R.out && R.out_carrier) ? (T *)R.out + out_at : nullptr;
     float *off_seq = R.off ? R.off + (size_t)b * P.N : nullptr;
     auto frame = [&](int i) { return bwd ? Tn - 1 - i : i; };
-    auto write_row = [&](int f, const T *srcv) {   // coalesced copy of a finished vector to global memory
+
+    // ---- duties of the data-moving wave (called by that wave only, all 64 lanes)
+    // emissions of frame f -> dst, through the direct global->LDS path (no registers, any length)
+    auto stage = [&](int f, float *dst) {
+        const float *row = em_seq + (size_t)f * P.D;
+        if (P.shared) {
+            if ((P.D & 3) == 0 && ((uintptr_t)row & 15) == 0) {
+                for (int e0 = 0; e0 < nE; e0 += 4 * kWave)
+                    if (e0 + 4 * lane < nE)
+                        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(row + e0 + 4 * lane),
+                                                         (__attribute__((address_space(3))) void *)(dst + e0), 16, 0, 0);
+            } else {
+                for (int e0 = 0; e0 < nE; e0 += kWave)
+                    if (e0 + lane < nE)
+                        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(row + e0 + lane),
+                                                         (__attribute__((address_space(3))) void *)(dst + e0), 4, 0, 0);
+            }
+        } else {
+            for (int e0 = 0; e0 < nE; e0 += kWave)
+                if (e0 + lane < nE)
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(row + pix[e0 + lane]),
+                                                     (__attribute__((address_space(3))) void *)(dst + e0), 4, 0, 0);
+        }
+    };
+    auto staged_wait = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+    // a finished vector -> global memory, coalesced
+    auto write_row = [&](int f, const T *srcv) {
         if (out_f) {
             float *orow = out_f + (size_t)f * out_ld;
-            for (int k = tid; k < K; k += NT) orow[k] = (float)srcv[k] * R.out_scale;
+            for (int k = lane; k < K; k += kWave) orow[k] = (float)srcv[k] * R.out_scale;
         } else if (out_t) {
             T *orow = out_t + (size_t)f * out_ld;
-            for (int k = tid; k < K; k += NT) orow[k] = srcv[k];
+            if (sizeof(T) == 4 && (K & 3) == 0 && ((uintptr_t)orow & 15) == 0 && ((uintptr_t)srcv & 15) == 0) {
+                const float4 *s4 = (const float4 *)srcv;
+                float4 *o4 = (float4 *)orow;
+                for (int k = lane; k < K / 4; k += kWave) o4[k] = s4[k];
+            } else {
+                for (int k = lane; k < K; k += kWave) orow[k] = srcv[k];
+            }
         }
     };
 
     if (Tn > 0) {
-        // which element of an emission row each staged entry comes from
-        int eidx[kEPT];
-#pragma unroll
-        for (int j = 0; j < kEPT; ++j) {
-            const int e = tid + j * NT;
-            eidx[j] = e < nE ? (P.shared ? e : P.pdf[k0 + e]) : 0;
-        }
-        auto scaled = [](float v) { return (T)((T)v * (T)kLog2e); };
-        auto stage_tail = [&](const float *row, T *dst) {   // entries beyond the prefetch registers
-            for (int e = kEPT * NT + tid; e < nE; e += NT) dst[e] = scaled(row[P.shared ? e : P.pdf[k0 + e]]);
-        };
-        auto stage_direct = [&](int f, T *dst) {
-            const float *row = em_seq + (size_t)f * P.D;
-#pragma unroll
-            for (int j = 0; j < kEPT; ++j) {
-                const int e = tid + j * NT;
-                if (e < nE) dst[e] = scaled(row[eidx[j]]);
-            }
-            stage_tail(row, dst);
-        };
-        float ereg[kEPT];
-        auto prefetch = [&](int f) {
-            const float *row = em_seq + (size_t)f * P.D;
-#pragma unroll
-            for (int j = 0; j < kEPT; ++j) ereg[j] = (tid + j * NT < nE) ? row[eidx[j]] : 0.0f;
-        };
-        auto commit = [&](int f, T *dst) {
-#pragma unroll
-            for (int j = 0; j < kEPT; ++j) {
-                const int e = tid + j * NT;
-                if (e < nE) dst[e] = scaled(ereg[j]);
-            }
-            if (nE > kEPT * NT) stage_tail(em_seq + (size_t)f * P.D, dst);
-        };
-
         // ---- first frame of this direction: x = start weight (x) v
-        stage_direct(frame(0), er);
-        if (Tn > 1) stage_direct(frame(1), er + P.Ecap);
+        if (!P.shared)
+            for (int k = tid; k < K; k += NT) pix[k] = P.pdf[k0 + k];
+        __syncthreads();
+        if (io_wave) {
+            stage(frame(0), er);
+            if (Tn > 1) stage(frame(1), er + P.Ecap);
+            staged_wait();
+            if (off_seq && lane == 0) off_seq[frame(0)] = 0.0f;
+        }
         __syncthreads();
         T wmax = kNegInf;
         for (int k = tid; k < K; k += NT) {
             const T s = (T)R.bound[k0 + k];
-            const T x = s + er[P.shared ? P.pdf[k0 + k] : k];
+            const T x = s + (T)er[P.shared ? P.pdf[k0 + k] : k] * (T)kLog2e;
             xb[k] = x;
             if (bwd) bh[k] = s;
-            wmax = x > wmax ? x : wmax;
+            wmax = tmax(wmax, x);
         }
         wmax = wave_max(wmax);
         if (lane == 0) red[wave] = wmax;
-        if (Tn > 2) prefetch(frame(2));
-        if (off_seq && tid == 0) off_seq[frame(0)] = 0.0f;
         __syncthreads();
 
         double csum = 0.0;
-        for (int i = 1; i < Tn; ++i) {
-            const int cur = (i - 1) & 1, nxt = i & 1;
-            const T *xc = xb + cur * P.Kcap;
-            T *xn = xb + nxt * P.Kcap;
-            T *bn = bh + nxt * P.Kcap;
-            const T *ern = er + nxt * P.Ecap;
-            T M = red[cur * NW];
+        if (io_wave) {
+            for (int i = 1; i < Tn; ++i) {
+                const int cur = (i - 1) & 1, nxt = i & 1;
+                T M = red[cur * NW];
 #pragma unroll
-            for (int w = 1; w < NW; ++w) M = red[cur * NW + w] > M ? red[cur * NW + w] : M;
-            const T c = (M == kNegInf) ? (T)0 : M;
-            csum += (double)c;
-            if (off_seq && tid == 0) off_seq[frame(i)] = (float)c * R.out_scale;
-            write_row(frame(i - 1), bwd ? bh + cur * P.Kcap : xc);   // the previous step's vector is final now
-            wmax = kNegInf;
-            auto fin = [&](int o, int vi, T val) {
-                const T pre = val - c;
-                const T x = pre + ern[vi];
-                xn[o] = x;
-                if (bwd) bn[o] = pre;
-                wmax = x > wmax ? x : wmax;
-            };
-            for (int l = 0; l < L; ++l) {
-                sell_log_level<T>(S, sd.wave_ptr0 + l * NW + wave, l == 0 ? xc : part, part, lane, fin);
-                if (l + 1 < L) __syncthreads();
+                for (int w = 1; w < NW; ++w) M = tmax(M, red[cur * NW + w]);
+                const T c = (M == kNegInf) ? (T)0 : M;
+                csum += (double)c;
+                if (off_seq && lane == 0) off_seq[frame(i)] = (float)c * R.out_scale;
+                if (i + 1 < Tn) stage(frame(i + 1), er + cur * P.Ecap);   // buffer of frame(i-1): no longer read
+                write_row(frame(i - 1), bwd ? bh + cur * P.Kcap : xb + cur * P.Kcap);
+                if (lane == 0) red[nxt * NW + wave] = kNegInf;
+                staged_wait();
+                for (int l = 1; l < L; ++l) __syncthreads();
+                __syncthreads();
             }
-            // emissions two frames ahead: the row loaded during the last step goes to LDS,
-            // the next row starts its trip from HBM
-            if (i + 1 < Tn) commit(frame(i + 1), er + cur * P.Ecap);
-            if (i + 2 < Tn) prefetch(frame(i + 2));
-            wmax = wave_max(wmax);
-            if (lane == 0) red[nxt * NW + wave] = wmax;
-            __syncthreads();
+        } else {
+            // The wave's stream of batches is the same every step: keep kRing-1 batches in flight.
+            const WaveDesc wd = S.waves[sd.wave_ptr0 + wave];
+            const Arc *stream = S.arcs + wd.arc_base + lane;
+            const int n_iter = wd.n_iter, n_batch = n_iter * kRing;
+            // the flag words of the whole step live in two registers (word i in lane i), read with v_readlane
+            const uint32_t *fwp = S.flagwords + wd.flag_base;
+            const uint32_t fwv0 = lane < n_iter ? fwp[lane] : 0u;
+            const uint32_t fwv1 = lane + kWave < n_iter ? fwp[lane + kWave] : 0u;
+            Arc ring[kRing][kBatchRows];
+            auto load_batch = [&](Arc(&dst)[kBatchRows], int bidx) {
+                const Arc *p = stream + (size_t)bidx * (kBatchRows * kWave);
+#pragma unroll
+                for (int r = 0; r < kBatchRows; ++r) dst[r] = p[r * kWave];
+            };
+#pragma unroll
+            for (int j = 0; j + 1 < kRing; ++j) {
+                load_batch(ring[j], j);
+                __builtin_amdgcn_sched_barrier(0);   // keep the issue order: waits count loads in order
+            }
+
+            for (int i = 1; i < Tn; ++i) {
+                const int cur = (i - 1) & 1, nxt = i & 1;
+                const T *xc = xb + cur * P.Kcap;
+                T *xn = xb + nxt * P.Kcap;
+                T *bn = bh + nxt * P.Kcap;
+                const float *ern = er + nxt * P.Ecap;
+                T M = red[cur * NW];
+#pragma unroll
+                for (int w = 1; w < NW; ++w) M = tmax(M, red[cur * NW + w]);
+                const T c = (M == kNegInf) ? (T)0 : M;
+                wmax = kNegInf;
+                T m = (T)kNegBig;
+                float sum = 0.0f;
+                auto close_row = [&](float info) {   // an info row: the lane's running sum is complete
+                    const uint32_t u = __float_as_uint(info), o = u & 0xffffu;
+                    const T val = m + (T)flog2(sum);   // sum == 0 -> -inf
+                    m = (T)kNegBig;
+                    sum = 0.0f;
+                    if (o == kOutIdle) return;
+                    if (o & kOutPartial) {
+                        part[o & 0x7fffu] = val;
+                    } else {
+                        const T pre = val - c;
+                        const T x = pre + (T)ern[u >> 16] * (T)kLog2e;
+                        xn[o] = x;
+                        if (bwd) bn[o] = pre;
+                        wmax = tmax(wmax, x);
+                    }
+                };
+                const T *vbase = xc;
+                for (int it = 0; it < n_iter; ++it) {
+                    const uint32_t fw =
+                        it < kWave ? __builtin_amdgcn_readlane(fwv0, it) : __builtin_amdgcn_readlane(fwv1, it - kWave);
+#pragma unroll
+                    for (int j = 0; j < kRing; ++j) {
+                        int pf = it * kRing + j + (kRing - 1);
+                        if (pf >= n_batch) pf -= n_batch;
+                        load_batch(ring[(j + kRing - 1) % kRing], pf);
+                        __builtin_amdgcn_sched_barrier(0);
+                        const uint32_t f = (fw >> (8 * j)) & 0xffu;
+                        if (!(f & kFlagSkip)) {
+                            T g[kBatchRows];
+#pragma unroll
+                            for (int r = 0; r < kBatchRows; ++r) g[r] = vbase[ring[j][r].src];
+                            if ((f & kFlagInfoMask) == 0) {   // four arcs of the same rows
+                                lse_add4(m, sum, g[0] + (T)ring[j][0].w, g[1] + (T)ring[j][1].w, g[2] + (T)ring[j][2].w,
+                                         g[3] + (T)ring[j][3].w);
+                            } else {
+#pragma unroll
+                                for (int r = 0; r < kBatchRows; ++r) {
+                                    if (f & (1u << r))
+                                        close_row(ring[j][r].w);
+                                    else
+                                        lse_add(m, sum, g[r] + (T)ring[j][r].w);
+                                }
+                            }
+                        }
+                        if (f & kFlagLevelEnd) {
+                            __syncthreads();
+                            vbase = part;
+                        }
+                    }
+                }
+                wmax = wave_max(wmax);
+                if (lane == 0) red[nxt * NW + wave] = wmax;
+                __syncthreads();
+            }
         }
 
         // ---- last frame: write it out, close log Z with the end weights
         const int last = (Tn - 1) & 1;
         const T *xl = xb + last * P.Kcap;
-        write_row(frame(Tn - 1), bwd ? bh + last * P.Kcap : xl);
+        if (io_wave) write_row(frame(Tn - 1), bwd ? bh + last * P.Kcap : xl);
         if (R.logz) {
             T m = (T)kNegBig;
             float s = 0.0f;
@@ -285,7 +345,7 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
             T *rm = red + 2 * NW, *rs = rm + NW;
             if (lane == 0) { rm[wave] = m; rs[wave] = (T)s; }
             __syncthreads();
-            if (tid == 0) {
+            if (io_wave && lane == 0) {   // the lane that holds the sum of the offsets
                 m = rm[0]; s = (float)rs[0];
                 for (int w = 1; w < NW; ++w) lse_merge(m, s, rm[w], (float)rs[w]);
                 R.logz[b] = (csum + (double)m + (double)flog2(s)) * kLn2;
