@@ -46,6 +46,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=5, choices=[5], help="workload (configuration 5 is the benchmark)")
     ap.add_argument("--cpu-sample", type=int, default=0, help="sequences the CPU oracle is timed on (0 = 2 per thread)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (sequences are independent, so the batch would be "
@@ -128,10 +130,18 @@ def main() -> int:
                      "algorithmic_bytes": algo_bytes, "launch_ms": stage_ms["den_recursion"]},
     }
 
+    if args.calibrate_copy:
+        src = torch.empty((1 << 28,), dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)            # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+
     if not args.no_cpu_baseline:
         import oracle
         threads = oracle.num_threads()
-        ns = args.cpu_sample or min(w.B, 2 * threads)
+        ns = args.cpu_sample or min(w.B, 4 * threads)
         order = np.argsort(w.lengths, kind="stable")
         sel = np.sort(order[np.linspace(0, w.B - 1, ns).round().astype(int)])
         sample_updates = int(2 * np.sum(w.lengths[sel].astype(np.int64) * (w.den.E + w.num.arcs_per_seq(w.B)[sel])))

@@ -36,6 +36,7 @@ RecDir make_dir(const fb_graph *g, bool backward, void *out, bool out_carrier, f
     r.off = off;
     r.logz = logz;
     r.out_scale = out_scale;
+    r.Pcap = backward ? g->h_bwd.Pcap : g->h_fwd.Pcap;
     r.backward = backward ? 1 : 0;
     r.fill_pad = fill_pad ? 1 : 0;
     return r;
@@ -45,11 +46,6 @@ int run_recursion(const fb_graph *g, const float *emis, const int32_t *lengths, 
                   const RecDir *dirs, int n_dir, fb_stream stream)
 {
     RecParams p{};
-    bool any_bwd = false;
-    for (int i = 0; i < n_dir; ++i) {
-        p.dir[i] = dirs[i];
-        any_bwd = any_bwd || dirs[i].backward;
-    }
     p.n_dir = n_dir;
     p.pdf = g->d_pdf;
     p.emis = emis;
@@ -58,10 +54,12 @@ int run_recursion(const fb_graph *g, const float *emis, const int32_t *lengths, 
     p.shared = g->n_seq == 0;
     p.Ktot = g->K;
     p.Kcap = g->max_sub_K;
-    p.Pcap = std::max(g->h_fwd.max_part, g->h_bwd.max_part);
     p.Ecap = p.shared ? D : g->max_sub_K;
-    p.any_backward = any_bwd;
-    const size_t lds = recursion_lds_bytes(p.Kcap, p.Pcap, p.Ecap, any_bwd, g->f64, p.shared != 0);
+    size_t lds = 0;
+    for (int i = 0; i < n_dir; ++i) {
+        p.dir[i] = dirs[i];
+        lds = std::max(lds, recursion_lds_bytes(p.Kcap, dirs[i].Pcap, p.Ecap, dirs[i].backward != 0, g->f64, p.shared != 0));
+    }
     if (lds > kLdsBytes) return fail(FB_EUNSUPPORTED, "state vectors and emission rows exceed the on-chip memory");
     return launch_recursion(g->nw, g->f64, p, lds, stream);
 }

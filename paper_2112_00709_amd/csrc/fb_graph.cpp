@@ -80,12 +80,13 @@ int upload_stream(fb_graph *g, const StreamHost &h, StreamDev &d)
 
 }  // namespace
 
-size_t recursion_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t Ecap, bool any_backward, bool f64, bool shared)
+size_t recursion_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t Ecap, bool backward, bool f64, bool shared)
 {
-    // carrier-typed: state vectors, partial slots, reduction slots; then two emission rows (float) and,
-    // for packed graphs, the pdf id of every state
-    return ((size_t)Kcap * (any_backward ? 4 : 2) + (size_t)Pcap + 4 * kNWShared) * (f64 ? 8 : 4) +
-           (size_t)Ecap * (shared ? 8 : 12) + kLdsReserve;
+    // carrier-typed: state buffers (states, partial slots, a dump slot) and reduction slots;
+    // then three emission rows (float, plus a zero slot) and, for packed graphs, a pdf id per state
+    const size_t xs = (size_t)Kcap + (size_t)Pcap + 1;
+    return (xs * (backward ? 4 : 2) + 4 * kNWShared) * (f64 ? 8 : 4) + ((size_t)Ecap + 1) * 12 +
+           (shared ? 0 : (size_t)Ecap * 4) + kLdsReserve;
 }
 
 size_t posterior_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t D, bool f64)
@@ -262,14 +263,16 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
             if (!sell_in_bounds(sell_fwd, -1, nv, why) || !sell_in_bounds(sell_bwd, -1, nv, why) ||
                 !sell_in_bounds(g->h_pdf, D, 1, why))
                 rc = fail(FB_EHIP, "internal error: schedule out of bounds (" + why + ")");
-            else if (!stream_from_sell(sell_fwd, g->h_fwd, why) || !stream_from_sell(sell_bwd, g->h_bwd, why))
+            else if (!stream_from_sell(sell_fwd, g->max_sub_K, n_seq > 0 ? g->max_sub_K : D, g->h_fwd, why) ||
+                     !stream_from_sell(sell_bwd, g->max_sub_K, n_seq > 0 ? g->max_sub_K : D, g->h_bwd, why))
                 rc = fail(FB_EUNSUPPORTED, "graph too large: " + why);
             else if (!stream_in_bounds(g->h_fwd, nv, why) || !stream_in_bounds(g->h_bwd, nv, why))
                 rc = fail(FB_EHIP, "internal error: stream out of bounds (" + why + ")");
         }
-        const int32_t Pcap = std::max(g->h_fwd.max_part, g->h_bwd.max_part);
+        const int32_t Pcap = std::max(g->h_fwd.Pcap, g->h_bwd.Pcap);
         const int32_t Ecap = n_seq > 0 ? g->max_sub_K : D;
-        if (rc == FB_OK && (recursion_lds_bytes(g->max_sub_K, Pcap, Ecap, true, g->f64, n_seq == 0) > kLdsBytes ||
+        if (rc == FB_OK && (recursion_lds_bytes(g->max_sub_K, g->h_fwd.Pcap, Ecap, false, g->f64, n_seq == 0) > kLdsBytes ||
+            recursion_lds_bytes(g->max_sub_K, g->h_bwd.Pcap, Ecap, true, g->f64, n_seq == 0) > kLdsBytes ||
             posterior_lds_bytes(g->max_sub_K, g->h_pdf.max_part, D, g->f64) > kLdsBytes)) {
             rc = fail(FB_EUNSUPPORTED, "graph too large: " + std::to_string(g->max_sub_K) + " states, " +
                                            std::to_string(Pcap) + " partial slots and " + std::to_string(Ecap) +

@@ -71,28 +71,35 @@ void sell_apply_host(const SellHost &S, int32_t sub, bool log_semiring, const do
 
 // ---------------------------------------------------------------------------
 // Stream form of a log-semiring schedule: what the recursion kernel interprets.
-// Every wave of the workgroup owns one contiguous, cyclic stream of "rows" of 64
-// entries (one per lane), grouped in batches of kBatchRows rows.  A row is either
-// 64 arcs (one per lane: gather, add the weight, fold into the lane's running
-// sum) or an info row that closes the slice: its entries say where each lane's
-// finished sum goes (a state, a partial slot, nowhere) and which staged emission
-// it takes.  A byte of flags per batch tells the rows' kinds, whether the batch
-// is padding to skip, and whether a level (workgroup barrier) ends after it.
-// The stream of one time step is the same every step, so the kernel prefetches
-// it kRing-1 batches ahead, across barriers and across steps.
+// Every wave of the workgroup that walks arcs owns one contiguous, cyclic stream
+// of "rows" of 64 entries (one per lane), grouped in batches of kBatchRows rows.
+// A row is 64 arcs (one per lane: gather, add the weight, fold into the lane's
+// running sum), except that the last row of a batch may be an info row that
+// closes the slice: its entries say where each lane's finished sum goes and
+// which staged emission it takes.  Slices are padded with zero-weight (-inf)
+// arcs so that their info row falls on the last row of a batch.  A byte of flags
+// per batch tells whether it ends with an info row, whether it is padding to
+// skip, and whether a level (workgroup barrier) ends after it.  The stream of one
+// time step is the same every step, so the kernel keeps it kRing-1 batches ahead
+// of its use, across barriers and across steps.
+//
+// Info entry (in the weight field): low 16 bits = target index in the state
+// buffer of the step being written, [0, K) a state, Kcap + slot a partial slot,
+// Kcap + Pcap the dump slot of idle lanes; high 16 bits = index of the emission
+// in the staged emission vector, Ecap being a slot that always holds 0.
 // ---------------------------------------------------------------------------
 constexpr int kBatchRows = 4;
 constexpr int kRing = 4;                        // batches per unrolled iteration = prefetch ring size
-constexpr uint32_t kFlagInfoMask = 0x0f;        // bit r: row r of the batch is an info row
-constexpr uint32_t kFlagSkip = 0x10;            // nothing to do in this batch (padding)
-constexpr uint32_t kFlagLevelEnd = 0x20;        // workgroup barrier after this batch
-constexpr uint32_t kOutIdle = 0xffffu;          // info entry: lane has no row in this slice
-constexpr uint32_t kOutPartial = 0x8000u;       // info entry: bit set -> partial slot (low 15 bits)
+constexpr int kResident = 6;                    // batches per wave and step that stay in registers (<= 8)
+constexpr uint32_t kFlagInfo = 0x01;            // the batch's last row is an info row
+constexpr uint32_t kFlagLevelEnd = 0x02;        // workgroup barrier after this batch
+constexpr uint32_t kFlagSkip = 0x04;            // nothing to do in this batch (padding)
 
 struct WaveDesc {
     int64_t arc_base;    // first entry of the wave's stream in `arcs`
-    int32_t n_iter;      // unrolled iterations per time step: batches / kRing
-    int32_t flag_base;   // first of its n_iter flag words (one byte per batch)
+    int32_t n_iter;      // unrolled iterations per time step over the streamed batches (may be 0):
+                         // the wave's step is kResident + n_iter * kRing batches
+    int32_t flag_base;   // its flag words (one byte per batch): two for the resident batches, then n_iter
 };
 
 struct StreamHost {
@@ -100,8 +107,8 @@ struct StreamHost {
     std::vector<SubDesc> sub;          // wave_ptr0 = index of the sub-graph's first WaveDesc
     std::vector<WaveDesc> waves;
     std::vector<uint32_t> flagwords;
-    std::vector<Arc> arcs;             // info entries: src = 0, w = bits of (out16 | vidx16 << 16)
-    int32_t max_part = 0;
+    std::vector<Arc> arcs;             // info entries: src = 0, w = bits of (target16 | vidx16 << 16)
+    int32_t Kcap = 0, Pcap = 0, Ecap = 0;   // index space of the info entries (see above)
 };
 
 struct StreamDev {
@@ -111,7 +118,7 @@ struct StreamDev {
     const Arc *arcs = nullptr;
 };
 
-bool stream_from_sell(const SellHost &S, StreamHost &out, std::string &why);
+bool stream_from_sell(const SellHost &S, int32_t Kcap, int32_t Ecap, StreamHost &out, std::string &why);
 bool stream_in_bounds(const StreamHost &S, int32_t n_vidx, std::string &why);
 void stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double *y);
 
@@ -156,6 +163,7 @@ struct RecDir {
     float *off;            // [B][N] offsets, nullable
     double *logz;          // [B], nullable
     float out_scale;       // ln 2 for natural-log output, 1 to keep log2 units
+    int32_t Pcap;          // partial slots of this direction's schedule
     int backward;
     int fill_pad;          // write -inf / 0 into the rows of padded frames
 };
@@ -167,7 +175,7 @@ struct RecParams {
     const float *emis;
     const int32_t *lengths;
     int32_t B, N, D, shared, Ktot;
-    int32_t Kcap, Pcap, Ecap, any_backward;
+    int32_t Kcap, Ecap;
 };
 
 struct PostGraph {
@@ -193,7 +201,7 @@ int launch_recursion(int nw, bool f64, const RecParams &p, size_t lds_bytes, voi
 int launch_posteriors(const PostParams &p, size_t lds_bytes, void *stream);
 int launch_loss(const double *logz_num, const double *logz_den, const int32_t *lengths, int32_t B, double *loss,
                 void *stream);
-size_t recursion_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t Ecap, bool any_backward, bool f64, bool shared);
+size_t recursion_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t Ecap, bool backward, bool f64, bool shared);
 size_t posterior_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t D, bool f64);
 
 }  // namespace fb

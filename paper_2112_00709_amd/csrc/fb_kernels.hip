@@ -120,16 +120,26 @@ __device__ __forceinline__ void sell_sum_level(const SellDev &S, int wp, const f
 // and beta_n itself is the row sum before v_n is applied.
 //
 // Waves 0..NW-2 compute: their only global-memory traffic inside the time loop
-// is their own arc stream, a fixed sequence of loads that stays kRing-1 batches
-// ahead of its use, across barriers and across time steps.  Wave NW-1 moves data:
-// it brings the next frame's emissions from HBM straight into LDS, copies the
-// finished vector of the previous step out, keeps the offsets and log Z.  HBM
-// latency therefore never sits in front of an arc load.
-// T: carrier type of the vectors (float or double).
+// is their own arc stream, a fixed sequence of loads that stays ahead of its
+// use across barriers and across time steps; the LDS gathers of a batch are
+// issued one batch ahead of the arithmetic that consumes them.  Wave NW-1 moves
+// data: it brings the next frame's emissions from HBM straight into LDS, copies
+// the finished vector of the previous step out, keeps the offsets and log Z.
+// HBM latency therefore never sits in front of an arc load.
+//
+// LDS of a workgroup (carrier type T unless noted):
+//   xb   2 x Xs   x of the previous / current step; Xs = Kcap + Pcap + 1: the
+//                 states, then the partial slots of split rows, then a dump slot
+//   bh   2 x Xs   beta before v is applied (backward direction only)
+//   red  4 x NW   step maxima (two parities), scratch of the last reduction
+//   er   3 x (Ecap + 1) float   emissions as given (natural log) of the frame in use and
+//                               of the next two; slot Ecap = 0
+//   pix  Ecap int32             packed graphs: pdf id of every state
 // ---------------------------------------------------------------------------
 template <int NW, class T>
 __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P)
 {
+    constexpr int NRES = kResident;
     extern __shared__ double lds_raw[];
     constexpr int NT = NW * kWave, NC = NW - 1;
     const T kNegInf = (T)(-INFINITY);
@@ -144,13 +154,13 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
     const int K = sd.K, k0 = sd.k0, L = sd.n_levels;
     const int Tn = min(max(P.lengths[b], 0), P.N);
     const int nE = P.shared ? P.D : K;           // entries of a staged emission vector
+    const int Xs = P.Kcap + R.Pcap + 1, Es = P.Ecap + 1;
 
-    T *xb = (T *)lds_raw;                        // x, two buffers of Kcap
-    T *bh = xb + 2 * P.Kcap;                     // beta before v is applied, two buffers (backward only)
-    T *part = bh + (P.any_backward ? 2 * P.Kcap : 0);
-    T *red = part + P.Pcap;                      // [2][NW] step maxima, then 2*NW for the last reduction
-    float *er = (float *)(red + 4 * NW);         // staged emissions (natural log, as given), two buffers of Ecap
-    int32_t *pix = (int32_t *)(er + 2 * P.Ecap); // packed graphs: pdf id of every state of the sub-graph
+    T *xb = (T *)lds_raw;
+    T *bh = xb + 2 * Xs;
+    T *red = bh + (bwd ? 2 * Xs : 0);
+    float *er = (float *)(red + 4 * NW);
+    int32_t *pix = (int32_t *)(er + 3 * Es);
 
     const float *em_seq = P.emis + (size_t)b * P.N * P.D;
     const size_t out_ld = P.shared ? (size_t)K : (size_t)P.Ktot;
@@ -205,11 +215,13 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
         // ---- first frame of this direction: x = start weight (x) v
         if (!P.shared)
             for (int k = tid; k < K; k += NT) pix[k] = P.pdf[k0 + k];
+        if (tid < 3) er[tid * Es + P.Ecap] = 0.0f;   // the emission of rows that take none
         __syncthreads();
         if (io_wave) {
             stage(frame(0), er);
-            if (Tn > 1) stage(frame(1), er + P.Ecap);
+            if (Tn > 1) stage(frame(1), er + Es);
             staged_wait();
+            if (Tn > 2) stage(frame(2), er + 2 * Es);   // lands while step 1 runs
             if (off_seq && lane == 0) off_seq[frame(0)] = 0.0f;
         }
         __syncthreads();
@@ -235,64 +247,103 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                 const T c = (M == kNegInf) ? (T)0 : M;
                 csum += (double)c;
                 if (off_seq && lane == 0) off_seq[frame(i)] = (float)c * R.out_scale;
-                if (i + 1 < Tn) stage(frame(i + 1), er + cur * P.Ecap);   // buffer of frame(i-1): no longer read
-                write_row(frame(i - 1), bwd ? bh + cur * P.Kcap : xb + cur * P.Kcap);
+                staged_wait();   // frame i+1, requested a whole step ago, is in LDS
+                if (i + 2 < Tn) stage(frame(i + 2), er + ((i + 2) % 3) * Es);   // buffer of frame i-1: no longer read
+                write_row(frame(i - 1), bwd ? bh + cur * Xs : xb + cur * Xs);
                 if (lane == 0) red[nxt * NW + wave] = kNegInf;
-                staged_wait();
                 for (int l = 1; l < L; ++l) __syncthreads();
                 __syncthreads();
             }
         } else {
-            // The wave's stream of batches is the same every step: keep kRing-1 batches in flight.
             const WaveDesc wd = S.waves[sd.wave_ptr0 + wave];
-            const Arc *stream = S.arcs + wd.arc_base + lane;
-            const int n_iter = wd.n_iter, n_batch = n_iter * kRing;
-            // the flag words of the whole step live in two registers (word i in lane i), read with v_readlane
-            const uint32_t *fwp = S.flagwords + wd.flag_base;
-            const uint32_t fwv0 = lane < n_iter ? fwp[lane] : 0u;
-            const uint32_t fwv1 = lane + kWave < n_iter ? fwp[lane + kWave] : 0u;
-            Arc ring[kRing][kBatchRows];
+            // a lane's share of a batch is two 16-byte pieces: rows 0-1 and rows 2-3
+            const float4 *stream = (const float4 *)(S.arcs + wd.arc_base) + lane;
             auto load_batch = [&](Arc(&dst)[kBatchRows], int bidx) {
-                const Arc *p = stream + (size_t)bidx * (kBatchRows * kWave);
-#pragma unroll
-                for (int r = 0; r < kBatchRows; ++r) dst[r] = p[r * kWave];
+                const float4 *p = stream + (size_t)bidx * (2 * kWave);
+                const float4 lo = p[0], hi = p[kWave];
+                dst[0] = Arc{(int32_t)__float_as_uint(lo.x), lo.y};
+                dst[1] = Arc{(int32_t)__float_as_uint(lo.z), lo.w};
+                dst[2] = Arc{(int32_t)__float_as_uint(hi.x), hi.y};
+                dst[3] = Arc{(int32_t)__float_as_uint(hi.z), hi.w};
             };
+            // The first NRES batches of the wave's step stay in registers for the whole time loop;
+            // the rest of the stream is re-read every step through a ring that runs kRing-1 batches
+            // ahead of its use, across barriers and across steps (it holds graph data only).
+            Arc res[NRES][kBatchRows];
 #pragma unroll
-            for (int j = 0; j + 1 < kRing; ++j) {
-                load_batch(ring[j], j);
-                __builtin_amdgcn_sched_barrier(0);   // keep the issue order: waits count loads in order
+            for (int q = 0; q < NRES; ++q) load_batch(res[q], q);
+            stream += (size_t)NRES * (2 * kWave);
+            const int n_iter = wd.n_iter, n_batch = n_iter * kRing;   // streamed part
+            // flag bytes: words 0-1 of the wave hold those of the resident batches, then one word per
+            // iteration; kept in registers (word i in lane i) and read with v_readlane
+            const uint32_t *fwp = S.flagwords + wd.flag_base;
+            const uint32_t rflag0 = fwp[0], rflag1 = fwp[1];
+            const uint32_t fwv0 = lane < n_iter ? fwp[2 + lane] : 0u;
+            const uint32_t fwv1 = lane + kWave < n_iter ? fwp[2 + lane + kWave] : 0u;
+            Arc ring[kRing][kBatchRows];
+            if (n_iter > 0) {
+#pragma unroll
+                for (int j = 0; j + 1 < kRing; ++j) {
+                    load_batch(ring[j], j);
+                    __builtin_amdgcn_sched_barrier(0);   // keep the issue order: waits count loads in order
+                }
             }
+            T g[2][kBatchRows];   // gathered values: of the batch being folded, and of the next one
+            auto gather = [&](T(&dst)[kBatchRows], const Arc(&a)[kBatchRows], const T *vbase) {
+#pragma unroll
+                for (int r = 0; r < kBatchRows; ++r) dst[r] = vbase[a[r].src];
+            };
 
             for (int i = 1; i < Tn; ++i) {
                 const int cur = (i - 1) & 1, nxt = i & 1;
-                const T *xc = xb + cur * P.Kcap;
-                T *xn = xb + nxt * P.Kcap;
-                T *bn = bh + nxt * P.Kcap;
-                const float *ern = er + nxt * P.Ecap;
+                const T *xc = xb + cur * Xs;
+                T *xn = xb + nxt * Xs;
+                T *bn = bh + nxt * Xs;
+                const float *ern = er + (i % 3) * Es;
                 T M = red[cur * NW];
 #pragma unroll
                 for (int w = 1; w < NW; ++w) M = tmax(M, red[cur * NW + w]);
-                const T c = (M == kNegInf) ? (T)0 : M;
+                T c = (M == kNegInf) ? (T)0 : M;   // subtracted where a row leaves level 0
                 wmax = kNegInf;
                 T m = (T)kNegBig;
                 float sum = 0.0f;
-                auto close_row = [&](float info) {   // an info row: the lane's running sum is complete
-                    const uint32_t u = __float_as_uint(info), o = u & 0xffffu;
-                    const T val = m + (T)flog2(sum);   // sum == 0 -> -inf
-                    m = (T)kNegBig;
-                    sum = 0.0f;
-                    if (o == kOutIdle) return;
-                    if (o & kOutPartial) {
-                        part[o & 0x7fffu] = val;
-                    } else {
-                        const T pre = val - c;
-                        const T x = pre + (T)ern[u >> 16] * (T)kLog2e;
-                        xn[o] = x;
-                        if (bwd) bn[o] = pre;
-                        wmax = tmax(wmax, x);
+                const T *vbase = xc;
+                // fold one batch: a, gv = its entries and gathered values; next = the batch after it
+                // (its gathers are issued before this batch's arithmetic), has_next: there is one in this step
+                auto fold = [&](uint32_t f, const Arc(&a)[kBatchRows], const T(&gv)[kBatchRows], T(&gnext)[kBatchRows],
+                                const Arc(&next)[kBatchRows], bool has_next) {
+                    if (!(f & kFlagLevelEnd) && has_next) gather(gnext, next, vbase);
+                    if (!(f & kFlagSkip)) {
+                        if (!(f & kFlagInfo)) {
+                            lse_add4(m, sum, gv[0] + (T)a[0].w, gv[1] + (T)a[1].w, gv[2] + (T)a[2].w, gv[3] + (T)a[3].w);
+                        } else {   // three arcs, then the lane's sum is complete
+                            lse_add4(m, sum, gv[0] + (T)a[0].w, gv[1] + (T)a[1].w, gv[2] + (T)a[2].w, kNegInf);
+                            const uint32_t u = __float_as_uint(a[3].w);
+                            const T pre = m + (T)flog2(sum) - c;   // sum == 0 -> -inf
+                            const T x = pre + (T)ern[u >> 16] * (T)kLog2e;
+                            xn[u & 0xffffu] = x;
+                            if (bwd) bn[u & 0xffffu] = pre;
+                            wmax = tmax(wmax, x);
+                            m = (T)kNegBig;
+                            sum = 0.0f;
+                        }
+                    }
+                    if (f & kFlagLevelEnd) {   // partial sums of split rows are complete: combine them
+                        __syncthreads();
+                        vbase = xn + P.Kcap;
+                        c = (T)0;
+                        if (has_next) gather(gnext, next, vbase);
                     }
                 };
-                const T *vbase = xc;
+                gather(g[0], res[0], vbase);
+#pragma unroll
+                for (int q = 0; q < NRES; ++q) {
+                    const uint32_t f = ((q < 4 ? rflag0 : rflag1) >> (8 * (q & 3))) & 0xffu;
+                    if (q + 1 < NRES)
+                        fold(f, res[q], g[q & 1], g[(q + 1) & 1], res[q + 1], true);
+                    else
+                        fold(f, res[q], g[q & 1], g[(q + 1) & 1], ring[0], n_iter > 0);
+                }
                 for (int it = 0; it < n_iter; ++it) {
                     const uint32_t fw =
                         it < kWave ? __builtin_amdgcn_readlane(fwv0, it) : __builtin_amdgcn_readlane(fwv1, it - kWave);
@@ -302,28 +353,8 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                         if (pf >= n_batch) pf -= n_batch;
                         load_batch(ring[(j + kRing - 1) % kRing], pf);
                         __builtin_amdgcn_sched_barrier(0);
-                        const uint32_t f = (fw >> (8 * j)) & 0xffu;
-                        if (!(f & kFlagSkip)) {
-                            T g[kBatchRows];
-#pragma unroll
-                            for (int r = 0; r < kBatchRows; ++r) g[r] = vbase[ring[j][r].src];
-                            if ((f & kFlagInfoMask) == 0) {   // four arcs of the same rows
-                                lse_add4(m, sum, g[0] + (T)ring[j][0].w, g[1] + (T)ring[j][1].w, g[2] + (T)ring[j][2].w,
-                                         g[3] + (T)ring[j][3].w);
-                            } else {
-#pragma unroll
-                                for (int r = 0; r < kBatchRows; ++r) {
-                                    if (f & (1u << r))
-                                        close_row(ring[j][r].w);
-                                    else
-                                        lse_add(m, sum, g[r] + (T)ring[j][r].w);
-                                }
-                            }
-                        }
-                        if (f & kFlagLevelEnd) {
-                            __syncthreads();
-                            vbase = part;
-                        }
+                        fold((fw >> (8 * j)) & 0xffu, ring[j], g[(NRES + j) & 1], g[(NRES + j + 1) & 1], ring[(j + 1) % kRing],
+                             j + 1 < kRing || it + 1 < n_iter);
                     }
                 }
                 wmax = wave_max(wmax);
@@ -334,8 +365,8 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
 
         // ---- last frame: write it out, close log Z with the end weights
         const int last = (Tn - 1) & 1;
-        const T *xl = xb + last * P.Kcap;
-        if (io_wave) write_row(frame(Tn - 1), bwd ? bh + last * P.Kcap : xl);
+        const T *xl = xb + last * Xs;
+        if (io_wave) write_row(frame(Tn - 1), bwd ? bh + last * Xs : xl);
         if (R.logz) {
             T m = (T)kNegBig;
             float s = 0.0f;
