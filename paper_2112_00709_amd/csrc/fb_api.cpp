@@ -64,38 +64,39 @@ int run_recursion(const fb_graph *g, const float *emis, const int32_t *lengths, 
     return launch_recursion(g->nw, g->f64, p, lds, stream);
 }
 
-PostGraph make_post(const fb_graph *g, const void *a, const void *b, bool f64, float in_scale, float *state_post)
+PostGraph make_post(const fb_graph *g, const void *a, const void *b, bool f64, float in_scale, float sign, float *state_post)
 {
     PostGraph q{};
-    q.f64 = f64 ? 1 : 0;
     q.pdfs = g->pdfs;
-    q.sub = g->pdfs.sub;
     q.a = a;
     q.b = b;
+    q.f64 = f64 ? 1 : 0;
     q.in_scale = in_scale;
+    q.sign = sign;
     q.shared = g->n_seq == 0;
     q.Ktot = g->K;
+    q.Kcap = g->max_sub_K;
+    q.Rcap = g->h_pdf.max_rows;
     q.state_post = state_post;
     return q;
 }
 
-int run_posteriors(const PostGraph *gs, const fb_graph *const *graphs, int n_graph, const int32_t *lengths, int32_t B,
-                   int32_t N, int32_t D, float *pdf_out, fb_stream stream)
+int run_posteriors(const PostGraph *gs, int n_graph, const int32_t *lengths, int32_t B, int32_t N, int32_t D,
+                   float *pdf_out, fb_stream stream)
 {
     PostParams p{};
     p.n_graph = n_graph;
     for (int i = 0; i < n_graph; ++i) {
         p.g[i] = gs[i];
-        p.Kcap = std::max(p.Kcap, graphs[i]->max_sub_K);
-        if (gs[i].f64) p.Kcap64 = std::max(p.Kcap64, graphs[i]->max_sub_K);
-        p.Pcap = std::max(p.Pcap, graphs[i]->h_pdf.max_part);
+        p.Kcap = std::max(p.Kcap, gs[i].Kcap);
+        if (gs[i].f64) p.Kcap64 = std::max(p.Kcap64, gs[i].Kcap);
     }
     p.lengths = lengths;
     p.B = B; p.N = N; p.D = D;
     p.pdf_out = pdf_out;
-    p.frames_per_block = 4;
-    const size_t lds = 64 + (size_t)p.Kcap64 * 8 + ((size_t)p.Kcap + p.Pcap + D) * 4 + kLdsReserve;
-    if (lds > kLdsBytes) return fail(FB_EUNSUPPORTED, "state vector and pdf row exceed the on-chip memory");
+    p.frames_per_block = 8;
+    const size_t lds = posterior_lds_bytes(p);
+    if (lds > kLdsBytes) return fail(FB_EUNSUPPORTED, "state vector, pdf row and pdf tables exceed the on-chip memory");
     return launch_posteriors(p, lds, stream);
 }
 
@@ -173,8 +174,8 @@ int fb_posteriors(const fb_graph *g, const float *alpha, const float *beta, cons
     if (rc) return rc;
     if (!lengths) return fail(FB_EINVAL, "fb_posteriors: lengths is NULL");
     if (!state_post && !pdf_post) return fail(FB_EINVAL, "fb_posteriors: no output requested");
-    const PostGraph q = make_post(g, alpha, beta, false, kLog2ef, state_post);
-    return run_posteriors(&q, &g, 1, lengths, B, N, D, pdf_post, stream);
+    const PostGraph q = make_post(g, alpha, beta, false, kLog2ef, 1.0f, state_post);
+    return run_posteriors(&q, 1, lengths, B, N, D, pdf_post, stream);
 }
 
 size_t fb_lfmmi_workspace_bytes(const fb_graph *den, const fb_graph *num, int32_t B, int32_t N, int32_t D)
@@ -223,10 +224,9 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
     mark(2, stream);
 
     // Eq. 17: numerator pdf posteriors minus denominator pdf posteriors
-    const PostGraph q[2] = {make_post(num, num_a, num_b, num->f64, 1.0f, nullptr),
-                            make_post(den, den_a, den_b, den->f64, 1.0f, nullptr)};
-    const fb_graph *gs[2] = {num, den};
-    if ((rc = run_posteriors(q, gs, 2, lengths, B, N, D, grad, stream))) return rc;
+    const PostGraph q[2] = {make_post(den, den_a, den_b, den->f64, 1.0f, -1.0f, nullptr),
+                            make_post(num, num_a, num_b, num->f64, 1.0f, 1.0f, nullptr)};
+    if ((rc = run_posteriors(q, 2, lengths, B, N, D, grad, stream))) return rc;
     mark(3, stream);
     rc = launch_loss(zn, zd, lengths, B, loss, stream);
     mark(4, stream);

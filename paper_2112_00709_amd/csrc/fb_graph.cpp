@@ -69,6 +69,15 @@ int upload_sell(fb_graph *g, const SellHost &h, SellDev &d)
     return FB_OK;
 }
 
+int upload_pdf(fb_graph *g, const PdfHost &h, PdfDev &d)
+{
+    int rc;
+    if ((rc = upload(g, h.sub, &d.sub))) return rc;
+    if ((rc = upload(g, h.row_pdf, &d.row_pdf))) return rc;
+    if ((rc = upload(g, h.row_ptr, &d.row_ptr))) return rc;
+    return upload(g, h.states, &d.states);
+}
+
 int upload_stream(fb_graph *g, const StreamHost &h, StreamDev &d)
 {
     int rc;
@@ -85,13 +94,17 @@ size_t recursion_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t Ecap, bool backwa
     // carrier-typed: state buffers (states, partial slots, a dump slot) and reduction slots;
     // then three emission rows (float, plus a zero slot) and, for packed graphs, a pdf id per state
     const size_t xs = (size_t)Kcap + (size_t)Pcap + 1;
-    return (xs * (backward ? 4 : 2) + 4 * kNWShared) * (f64 ? 8 : 4) + ((size_t)Ecap + 1) * 12 +
+    return (xs * (backward ? 4 : 2) + 4 * kNWShared + 2) * (f64 ? 8 : 4) + ((size_t)Ecap + 1) * 12 +
            (shared ? 0 : (size_t)Ecap * 4) + kLdsReserve;
 }
 
-size_t posterior_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t D, bool f64)
+size_t posterior_lds_bytes(const PostParams &p)
 {
-    return 64 + (f64 ? (size_t)Kcap * 8 : 0) + ((size_t)Kcap + (size_t)Pcap + (size_t)D) * 4 + kLdsReserve;
+    // reduction slots, log posteriors of a double-carrier graph, per-state values, the pdf row,
+    // then every graph's states-by-pdf table in 16-bit entries
+    size_t n = 64 + (size_t)p.Kcap64 * 8 + ((size_t)p.Kcap + (size_t)p.D) * 4;
+    for (int i = 0; i < p.n_graph; ++i) n += ((size_t)p.g[i].Rcap * 2 + 1 + (size_t)p.g[i].Kcap + 3) / 2 * 4;
+    return n + kLdsReserve;
 }
 
 }  // namespace fb
@@ -143,6 +156,7 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
     *out = nullptr;
     if (K <= 0 || E < 0 || D <= 0) return fail(FB_EINVAL, "fb_graph_create: K <= 0, E < 0 or D <= 0");
     if (E > INT32_MAX / 2) return fail(FB_EUNSUPPORTED, "fb_graph_create: more than 2^30 arcs");
+    if (D > 0xffff) return fail(FB_EUNSUPPORTED, "fb_graph_create: more than 65535 pdfs");
     if ((E > 0 && (!src || !dst || !logw)) || !pdf || !init || !final_)
         return fail(FB_EINVAL, "fb_graph_create: NULL array");
     if ((flags & FB_GRAPH_WIDE_STATE) && (flags & FB_GRAPH_NARROW_STATE))
@@ -207,7 +221,6 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
         g->f64 = (flags & FB_GRAPH_WIDE_STATE) ? true : (flags & FB_GRAPH_NARROW_STATE) ? false : g->nw == kNWSmall;
         SellHost sell_fwd, sell_bwd;   // row-split plans of the two recursions, flattened into streams below
         sell_fwd.nw = sell_bwd.nw = g->nw - 1;   // the last wave of a workgroup moves data, the others walk arcs
-        g->h_pdf.nw = kNWSmall;   // the posterior kernel always runs four waves
 
         std::vector<int64_t> ptr;
         std::vector<int32_t> col, rid, vid;
@@ -230,38 +243,41 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
                 sell_append(dir ? sell_bwd : sell_fwd, k0, Ks, Ks, ptr.data(), col.data(), w.data(), rid.data(),
                             vid.data(), -INFINITY, 0.0f);
             }
-            // states -> pdfs, ordinary sums: one row per pdf (every pdf for a shared graph, the
-            // pdfs the sub-graph uses for packed graphs), listing the states tied to it
-            std::vector<int32_t> prow, pcol;
-            std::vector<int64_t> pptr{0};
+            // states grouped by pdf: one row per pdf (every pdf for a shared graph, the pdfs the
+            // sub-graph uses for packed graphs), states in ascending order inside a row
+            PdfHost &PH = g->h_pdf;
+            PdfSub ps{};
+            ps.k0 = k0; ps.K = Ks;
+            ps.row0 = (int32_t)PH.row_pdf.size(); ps.ptr0 = (int32_t)PH.row_ptr.size(); ps.st0 = (int32_t)PH.states.size();
             if (n_seq == 0) {
                 for (int32_t d = 0; d < D; ++d) {
-                    prow.push_back(d);
-                    for (int32_t i = L.pdf_ptr[d]; i < L.pdf_ptr[d + 1]; ++i) pcol.push_back(L.pdf_states[(size_t)i]);
-                    pptr.push_back((int64_t)pcol.size());
+                    PH.row_pdf.push_back((uint16_t)d);
+                    PH.row_ptr.push_back((uint16_t)L.pdf_ptr[d]);
                 }
+                PH.row_ptr.push_back((uint16_t)Ks);
+                for (int32_t i = 0; i < Ks; ++i) PH.states.push_back((uint16_t)L.pdf_states[(size_t)i]);
+                ps.n_rows = D;
             } else {
                 std::vector<int32_t> order((size_t)Ks);
                 std::iota(order.begin(), order.end(), 0);
                 std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return pdf[k0 + a] < pdf[k0 + b]; });
                 for (size_t i = 0; i < order.size(); ++i) {
                     if (i == 0 || pdf[k0 + order[i]] != pdf[k0 + order[i - 1]]) {
-                        if (i) pptr.push_back((int64_t)pcol.size());
-                        prow.push_back(pdf[k0 + order[i]]);
+                        PH.row_pdf.push_back((uint16_t)pdf[k0 + order[i]]);
+                        PH.row_ptr.push_back((uint16_t)i);
+                        ++ps.n_rows;
                     }
-                    pcol.push_back(order[i]);
+                    PH.states.push_back((uint16_t)order[i]);
                 }
-                pptr.push_back((int64_t)pcol.size());
+                PH.row_ptr.push_back((uint16_t)Ks);
             }
-            std::vector<float> ones(pcol.size(), 1.0f);
-            sell_append(g->h_pdf, k0, Ks, (int32_t)prow.size(), pptr.data(), pcol.data(), ones.data(), prow.data(),
-                        nullptr, 0.0f, 1.0f);
+            PH.max_rows = std::max(PH.max_rows, ps.n_rows);
+            PH.sub.push_back(ps);
         }
         {   // nothing a kernel will index may leave its array
             std::string why;
             const int32_t nv = n_seq > 0 ? -1 : D;
-            if (!sell_in_bounds(sell_fwd, -1, nv, why) || !sell_in_bounds(sell_bwd, -1, nv, why) ||
-                !sell_in_bounds(g->h_pdf, D, 1, why))
+            if (!sell_in_bounds(sell_fwd, -1, nv, why) || !sell_in_bounds(sell_bwd, -1, nv, why))
                 rc = fail(FB_EHIP, "internal error: schedule out of bounds (" + why + ")");
             else if (!stream_from_sell(sell_fwd, g->max_sub_K, n_seq > 0 ? g->max_sub_K : D, g->h_fwd, why) ||
                      !stream_from_sell(sell_bwd, g->max_sub_K, n_seq > 0 ? g->max_sub_K : D, g->h_bwd, why))
@@ -272,8 +288,7 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
         const int32_t Pcap = std::max(g->h_fwd.Pcap, g->h_bwd.Pcap);
         const int32_t Ecap = n_seq > 0 ? g->max_sub_K : D;
         if (rc == FB_OK && (recursion_lds_bytes(g->max_sub_K, g->h_fwd.Pcap, Ecap, false, g->f64, n_seq == 0) > kLdsBytes ||
-            recursion_lds_bytes(g->max_sub_K, g->h_bwd.Pcap, Ecap, true, g->f64, n_seq == 0) > kLdsBytes ||
-            posterior_lds_bytes(g->max_sub_K, g->h_pdf.max_part, D, g->f64) > kLdsBytes)) {
+            recursion_lds_bytes(g->max_sub_K, g->h_bwd.Pcap, Ecap, true, g->f64, n_seq == 0) > kLdsBytes)) {
             rc = fail(FB_EUNSUPPORTED, "graph too large: " + std::to_string(g->max_sub_K) + " states, " +
                                            std::to_string(Pcap) + " partial slots and " + std::to_string(Ecap) +
                                            " emission entries do not fit the on-chip memory of a compute unit");
@@ -287,7 +302,7 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
             const int32_t *dp = nullptr; const float *di = nullptr, *df = nullptr;
             if (!(rc = upload(g, hp, &dp)) && !(rc = upload(g, i2, &di)) && !(rc = upload(g, f2, &df)) &&
                 !(rc = upload_stream(g, g->h_fwd, g->fwd)) && !(rc = upload_stream(g, g->h_bwd, g->bwd)))
-                rc = upload_sell(g, g->h_pdf, g->pdfs);
+                rc = upload_pdf(g, g->h_pdf, g->pdfs);
             g->d_pdf = const_cast<int32_t *>(dp); g->d_init2 = const_cast<float *>(di); g->d_final2 = const_cast<float *>(df);
         }
     } catch (const std::bad_alloc &) {
@@ -336,8 +351,18 @@ int fb_graph_schedule_apply_host(const fb_graph *g, int which, int32_t sub, cons
     if (!g || !x || !y) return fail(FB_EINVAL, "fb_graph_schedule_apply_host: NULL argument");
     if (which < 0 || which > 2 || sub < 0 || (size_t)sub >= g->h_pdf.sub.size())
         return fail(FB_EINVAL, "fb_graph_schedule_apply_host: unknown schedule or sub-graph");
-    if (which == 2) sell_apply_host(g->h_pdf, sub, false, x, y);
-    else stream_apply_host(which == 0 ? g->h_fwd : g->h_bwd, sub, x, y);
+    if (which == 2) {
+        const PdfHost &PH = g->h_pdf;
+        const PdfSub &ps = PH.sub[(size_t)sub];
+        for (int32_t r = 0; r < ps.n_rows; ++r) {
+            double acc = 0.0;
+            for (int32_t i = PH.row_ptr[(size_t)ps.ptr0 + r]; i < PH.row_ptr[(size_t)ps.ptr0 + r + 1]; ++i)
+                acc += x[PH.states[(size_t)ps.st0 + i]];
+            y[PH.row_pdf[(size_t)ps.row0 + r]] = acc;
+        }
+    } else {
+        stream_apply_host(which == 0 ? g->h_fwd : g->h_bwd, sub, x, y);
+    }
     return FB_OK;
 }
 

@@ -122,6 +122,28 @@ bool stream_from_sell(const SellHost &S, int32_t Kcap, int32_t Ecap, StreamHost 
 bool stream_in_bounds(const StreamHost &S, int32_t n_vidx, std::string &why);
 void stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double *y);
 
+// States grouped by pdf for the posterior accumulation: per (sub-)graph, one row per pdf it uses
+// (every pdf for a shared graph), listing the local ids of the states tied to it.  16-bit entries:
+// a workgroup keeps its graph's table in LDS.
+struct PdfSub {
+    int32_t k0, K;        // the sub-graph's first state and state count
+    int32_t row0, n_rows; // its rows in row_pdf
+    int32_t ptr0;         // its n_rows + 1 offsets in row_ptr (relative to st0)
+    int32_t st0;          // its K entries in states
+    int32_t pad_[2];
+};
+
+struct PdfHost {
+    std::vector<PdfSub> sub;
+    std::vector<uint16_t> row_pdf, row_ptr, states;
+    int32_t max_rows = 0;
+};
+
+struct PdfDev {
+    const PdfSub *sub = nullptr;
+    const uint16_t *row_pdf = nullptr, *row_ptr = nullptr, *states = nullptr;
+};
+
 struct HostLayout {                   // the graph-layout step, kept for fb_graph_layout
     std::vector<int32_t> in_ptr, in_src, in_perm, out_ptr, out_dst, out_perm, pdf_ptr, pdf_states;
     std::vector<float> in_w, out_w;
@@ -139,10 +161,10 @@ struct fb_graph {
     fb::HostLayout lay;
     std::vector<int32_t> state_off;   // packed only
     fb::StreamHost h_fwd, h_bwd;      // host schedules of the two recursions
-    fb::SellHost h_pdf;               // host schedule of the posterior accumulation
+    fb::PdfHost h_pdf;                // states grouped by pdf, for the posterior accumulation
     // device
     fb::StreamDev fwd, bwd;
-    fb::SellDev pdfs;
+    fb::PdfDev pdfs;
     int32_t *d_pdf = nullptr;         // [K]
     float *d_init2 = nullptr;         // [K] init * log2(e)
     float *d_final2 = nullptr;        // [K] final * log2(e)
@@ -179,22 +201,23 @@ struct RecParams {
 };
 
 struct PostGraph {
-    SellDev pdfs;          // plain-sum schedule states -> pdfs
-    const SubDesc *sub;    // same as pdfs.sub
+    PdfDev pdfs;           // states grouped by pdf
     const void *a, *b;     // normalised forward / backward vectors, float or double
     int f64;               // a, b are double
     float in_scale;        // log2(e) if a, b are natural logs, 1 if log2 units
+    float sign;            // +1 / -1: how the graph's pdf posteriors enter pdf_out
     int32_t shared, Ktot;
+    int32_t Kcap, Rcap;    // largest (sub-)graph: states, pdf rows
     float *state_post;     // nullable
 };
 
 struct PostParams {
-    PostGraph g[2];        // g[0] contributes +, g[1] contributes - (absent if n_graph == 1)
+    PostGraph g[2];        // processed in order; a shared graph (one row per pdf) must come first
     int n_graph;
     const int32_t *lengths;
     int32_t B, N, D;
     float *pdf_out;        // [B][N][D], nullable
-    int32_t Kcap, Kcap64, Pcap, frames_per_block;   // Kcap64: largest double-carrier (sub-)graph
+    int32_t Kcap, Kcap64, frames_per_block;   // Kcap64: largest double-carrier (sub-)graph
 };
 
 int launch_recursion(int nw, bool f64, const RecParams &p, size_t lds_bytes, void *stream);
@@ -202,6 +225,6 @@ int launch_posteriors(const PostParams &p, size_t lds_bytes, void *stream);
 int launch_loss(const double *logz_num, const double *logz_den, const int32_t *lengths, int32_t B, double *loss,
                 void *stream);
 size_t recursion_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t Ecap, bool backward, bool f64, bool shared);
-size_t posterior_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t D, bool f64);
+size_t posterior_lds_bytes(const PostParams &p);
 
 }  // namespace fb

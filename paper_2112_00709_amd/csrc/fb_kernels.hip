@@ -85,28 +85,6 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// One level of a plain-sum schedule (posterior accumulation over tied states).
-template <class Fin>
-__device__ __forceinline__ void sell_sum_level(const SellDev &S, int wp, const float *vbase, float *part, int lane, Fin fin)
-{
-    const int s0 = S.wave_ptr[wp], s1 = S.wave_ptr[wp + 1];
-    for (int s = s0; s < s1; ++s) {
-        const int trip = S.slice_trip[s];
-        const Arc *ap = S.arcs + S.slice_arc[s] + lane;
-        float acc = 0.0f;
-        for (int it = 0; it < trip; ++it) {
-            const Arc a = ap[0];
-            ap += kWave;
-            acc = fmaf(a.w, vbase[a.src], acc);
-        }
-        const int o = S.row_out[s * kWave + lane];
-        if (o >= 0)
-            fin(o, acc);
-        else if (o < -1)
-            part[-2 - o] = acc;
-    }
-}
-
 }  // namespace
 
 // ---------------------------------------------------------------------------
@@ -159,7 +137,7 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
     T *xb = (T *)lds_raw;
     T *bh = xb + 2 * Xs;
     T *red = bh + (bwd ? 2 * Xs : 0);
-    float *er = (float *)(red + 4 * NW);
+    float *er = (float *)(red + 4 * NW + 2);
     int32_t *pix = (int32_t *)(er + 3 * Es);
 
     const float *em_seq = P.emis + (size_t)b * P.N * P.D;
@@ -400,30 +378,37 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
 
 // ---------------------------------------------------------------------------
 // Posteriors (Eq. 15) of one or two graphs and their accumulation into pdf
-// posteriors; with two graphs the second is subtracted (Eq. 17).  grid =
-// (ceil(N / frames_per_block), B), 256 threads.
+// posteriors; each graph enters with its sign (Eq. 17: numerator minus
+// denominator).  grid = (ceil(N / frames_per_block), B), kPostThreads threads.
+// A workgroup keeps the states-by-pdf tables of its sequence's graphs in LDS and
+// walks its frames one at a time: log posteriors of the frame -> LDS, maximum,
+// exponentials, sum, then one thread per pdf adds up the states tied to it in a
+// fixed order (no atomics: results do not depend on timing).
 // ---------------------------------------------------------------------------
+constexpr int kPostThreads = 512;
+
 namespace {
 
-// gamma of one frame of one graph into tb[0..K): softmax over the states of
-// (a + b) * in_scale, in base 2.  IT: element type of a and b.
+// exp2(log posterior - max) of one frame of one graph into tb[0..K) (unnormalised); returns 1 / their sum
+// (0 if the frame has no mass).  IT: element type of a and b; stage: tb itself, or a wider buffer.
 template <class IT>
-__device__ __forceinline__ void frame_posteriors(const IT *arow, const IT *brow, IT in_scale, int K, float *tb,
-                                                 IT *stage, float *red, float *srow, int tid, int lane, int wave)
+__device__ __forceinline__ float frame_posteriors(const IT *arow, const IT *brow, IT in_scale, int K, float *tb,
+                                                 IT *stage, float *red, int tid, int lane, int wave)
 {
-    constexpr int NT = kNWSmall * kWave;
+    constexpr int NT = kPostThreads, NWV = kPostThreads / kWave;
     IT mx = (IT)(-INFINITY);
     for (int k = tid; k < K; k += NT) {
         const IT t = (arow[k] + brow[k]) * in_scale;
         stage[k] = t;
-        mx = t > mx ? t : mx;
+        mx = tmax(mx, t);
     }
     mx = wave_max(mx);
     IT *redt = (IT *)red;
     if (lane == 0) redt[wave] = mx;
     __syncthreads();
     mx = redt[0];
-    for (int w = 1; w < kNWSmall; ++w) mx = redt[w] > mx ? redt[w] : mx;
+#pragma unroll
+    for (int w = 1; w < NWV; ++w) mx = tmax(mx, redt[w]);
     __syncthreads();
     float sum = 0.0f;
     if (mx != (IT)(-INFINITY))
@@ -437,34 +422,47 @@ __device__ __forceinline__ void frame_posteriors(const IT *arow, const IT *brow,
     sum = wave_sum(sum);
     if (lane == 0) red[wave] = sum;
     __syncthreads();
-    sum = (red[0] + red[1]) + (red[2] + red[3]);
-    const float inv = sum > 0.0f ? 1.0f / sum : 0.0f;
-    for (int k = tid; k < K; k += NT) {
-        const float gma = tb[k] * inv;
-        tb[k] = gma;
-        if (srow) srow[k] = gma;
-    }
-    __syncthreads();
+    sum = red[0];
+#pragma unroll
+    for (int w = 1; w < NWV; ++w) sum += red[w];
+    return sum > 0.0f ? 1.0f / sum : 0.0f;
 }
 
 }  // namespace
 
-__global__ __launch_bounds__(256) void fb_posterior_kernel(const PostParams P)
+__global__ __launch_bounds__(kPostThreads) void fb_posterior_kernel(const PostParams P)
 {
     extern __shared__ double lds_raw[];
-    constexpr int NW = kNWSmall, NT = NW * kWave;
+    constexpr int NT = kPostThreads;
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int b = blockIdx.y;
     const int T = min(max(P.lengths[b], 0), P.N);
-    float *red = (float *)lds_raw;                  // reduction slots: NW doubles or floats
+    const int n0 = blockIdx.x * P.frames_per_block;
+    float *red = (float *)lds_raw;                  // reduction slots: one double or float per wave
     double *stage64 = lds_raw + 8;                  // [Kcap64] log posteriors of a double-carrier graph
     float *tb = (float *)(stage64 + P.Kcap64);      // [Kcap] per-state values of the frame
-    float *part = tb + P.Kcap;
-    float *rho = part + P.Pcap;                     // [D]
+    float *rho = tb + P.Kcap;                       // [D]
+    uint16_t *tab = (uint16_t *)(rho + P.D);        // per graph: row_ptr [Rcap + 1], row_pdf [Rcap], states [Kcap]
+    const uint16_t *rp[2], *rd[2], *rs[2];
+    PdfSub ps[2];
+    if (n0 < T) {   // the tables are needed only if the chunk has a real frame
+        uint16_t *at = tab;
+        for (int gi = 0; gi < P.n_graph; ++gi) {
+            const PostGraph &G = P.g[gi];
+            ps[gi] = G.pdfs.sub[G.shared ? 0 : b];
+            uint16_t *p0 = at, *p1 = p0 + G.Rcap + 1, *p2 = p1 + G.Rcap;
+            for (int r = tid; r <= ps[gi].n_rows; r += NT) p0[r] = G.pdfs.row_ptr[ps[gi].ptr0 + r];
+            for (int r = tid; r < ps[gi].n_rows; r += NT) p1[r] = G.pdfs.row_pdf[ps[gi].row0 + r];
+            for (int k = tid; k < ps[gi].K; k += NT) p2[k] = G.pdfs.states[ps[gi].st0 + k];
+            rp[gi] = p0; rd[gi] = p1; rs[gi] = p2;
+            at = p0 + ((2 * G.Rcap + 1 + G.Kcap + 1) & ~1);   // next table starts 4-byte aligned
+        }
+        __syncthreads();
+    }
 
     for (int fi = 0; fi < P.frames_per_block; ++fi) {
-        const int n = blockIdx.x * P.frames_per_block + fi;
+        const int n = n0 + fi;
         if (n >= P.N) break;
         float *prow = P.pdf_out ? P.pdf_out + ((size_t)b * P.N + n) * P.D : nullptr;
         if (n >= T) {   // padded frame: zeros
@@ -473,33 +471,42 @@ __global__ __launch_bounds__(256) void fb_posterior_kernel(const PostParams P)
             for (int gi = 0; gi < P.n_graph; ++gi) {
                 const PostGraph &G = P.g[gi];
                 if (!G.state_post) continue;
-                const SubDesc sd = G.sub[G.shared ? 0 : b];
+                const PdfSub sd = G.pdfs.sub[G.shared ? 0 : b];
                 float *srow = G.shared ? G.state_post + ((size_t)b * P.N + n) * sd.K
                                        : G.state_post + (size_t)n * G.Ktot + sd.k0;
                 for (int k = tid; k < sd.K; k += NT) srow[k] = 0.0f;
             }
             continue;
         }
-        for (int d = tid; d < P.D; d += NT) rho[d] = 0.0f;
         for (int gi = 0; gi < P.n_graph; ++gi) {
             const PostGraph &G = P.g[gi];
-            const SubDesc sd = G.sub[G.shared ? 0 : b];
-            const int K = sd.K;
-            const size_t at = G.shared ? ((size_t)b * P.N + n) * K : (size_t)n * G.Ktot + sd.k0;
-            float *srow = G.state_post ? G.state_post + at : nullptr;
+            const int K = ps[gi].K;
+            const size_t at = G.shared ? ((size_t)b * P.N + n) * K : (size_t)n * G.Ktot + ps[gi].k0;
+            const bool covers_all = G.shared != 0;   // a shared graph has one row per pdf
+            if (gi == 0 && !covers_all && prow)
+                for (int d = tid; d < P.D; d += NT) rho[d] = 0.0f;
+            float inv;
             if (G.f64)
-                frame_posteriors<double>((const double *)G.a + at, (const double *)G.b + at, (double)G.in_scale, K, tb,
-                                         stage64, red, srow, tid, lane, wave);
+                inv = frame_posteriors<double>((const double *)G.a + at, (const double *)G.b + at, (double)G.in_scale, K, tb,
+                                               stage64, red, tid, lane, wave);
             else
-                frame_posteriors<float>((const float *)G.a + at, (const float *)G.b + at, G.in_scale, K, tb, tb, red,
-                                        srow, tid, lane, wave);
+                inv = frame_posteriors<float>((const float *)G.a + at, (const float *)G.b + at, G.in_scale, K, tb, tb, red,
+                                              tid, lane, wave);
+            if (G.state_post) {
+                float *srow = G.state_post + at;
+                for (int k = tid; k < K; k += NT) srow[k] = tb[k] * inv;
+            }
+            __syncthreads();   // tb complete (and red free again)
             if (prow) {
-                const float sign = gi == 0 ? 1.0f : -1.0f;
-                auto fin = [&](int o, float v) { rho[o] += sign * v; };
-                for (int l = 0; l < sd.n_levels; ++l) {
-                    sell_sum_level(G.pdfs, sd.wave_ptr0 + l * NW + wave, l == 0 ? tb : part, part, lane, fin);
-                    __syncthreads();
+                const float scale = G.sign * inv;
+                const uint16_t *ptr = rp[gi], *pdfid = rd[gi], *st = rs[gi];
+                for (int r = tid; r < ps[gi].n_rows; r += NT) {
+                    float acc = 0.0f;
+                    for (int i = ptr[r]; i < ptr[r + 1]; ++i) acc += tb[st[i]];
+                    if (gi == 0 && covers_all) rho[pdfid[r]] = acc * scale;
+                    else rho[pdfid[r]] += acc * scale;
                 }
+                __syncthreads();
             }
         }
         if (prow)
@@ -564,7 +571,7 @@ int launch_posteriors(const PostParams &p, size_t lds_bytes, void *stream)
             hipFuncSetAttribute((const void *)fb_posterior_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return fail(FB_EHIP, std::string("hipFuncSetAttribute(LDS size): ") + hipGetErrorString(e));
     }
-    hipLaunchKernelGGL(fb_posterior_kernel, grid, dim3(256), lds_bytes, (hipStream_t)stream, p);
+    hipLaunchKernelGGL(fb_posterior_kernel, grid, dim3(kPostThreads), lds_bytes, (hipStream_t)stream, p);
     return check_launch("posterior kernel launch");
 }
 
