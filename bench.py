@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
 # HBM bytes per denominator-recursion launch on configuration 5 from rocprofv3 --pmc
 # (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on a plain copy kernel);
 # see profiles/.  None until measured for the workload being run.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"config5": 522900 * 1024 * 2.00 + 2071000 * 1024 * 1.00}
 
 
 def log(*a):
