@@ -215,6 +215,10 @@ size_t fb_lfmmi_workspace_bytes(const fb_graph *den, const fb_graph *num, int32_
  *   loss  out, device double [1]; logz_num, logz_den out, device double [B], nullable
  *   ws    device scratch of at least fb_lfmmi_workspace_bytes(), 256-byte aligned;
  *         its contents are undefined before and after the call
+ * The numerator launch runs on a stream of the library's own that is forked from
+ * `stream` and joined back into it with events before the gradient is formed, so
+ * for the caller everything is ordered on `stream` as usual (FB_AMD_SERIAL=1 in the
+ * environment keeps all launches on `stream`).
  * FB_EINVAL: as fb_alpha, or ws too small / NULL, den packed, num shared.
  */
 int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths,
@@ -229,12 +233,12 @@ int32_t fb_limits_max_states(int32_t D, int shared);
 
 /*
  * Stage timing of lfmmi_loss_grad, for benchmarks.  fb_profile_enable(1) creates
- * five HIP events (the only allocation; not allowed while a stream is being
+ * seven HIP events (the only allocation; not allowed while a stream is being
  * captured); while enabled, lfmmi_loss_grad records one before and after each of
- * its four kernel launches on the caller's stream.  fb_profile_read waits for the
- * last recorded event and returns the milliseconds of the latest call's stages:
- * ms[0] numerator recursions, ms[1] denominator recursions, ms[2] posteriors and
- * gradient, ms[3] objective.  FB_EINVAL if profiling is off, ms is NULL (host
+ * its four kernel launches, on the stream the launch goes to.  fb_profile_read
+ * waits for the last recorded events and returns the milliseconds of the latest
+ * call's stages: ms[0] numerator recursions (they run beside the denominator's),
+ * ms[1] denominator recursions, ms[2] posteriors and gradient, ms[3] objective.  FB_EINVAL if profiling is off, ms is NULL (host
  * pointer) or no call was recorded.  fb_profile_enable(0) destroys the events.
  */
 int fb_profile_enable(int on);

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <cstdlib>
 
 #include "fb_internal.h"
 
@@ -105,22 +106,55 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 // stage timing of lfmmi_loss_grad (fb_profile_enable / fb_profile_read)
 struct Profile {
     bool on = false, recorded = false;
-    hipEvent_t ev[5] = {};
+    hipEvent_t ev[7] = {};   // 0-4 on the caller's stream, 5-6 around the numerator launch on the side stream
 } g_prof;
 
-void mark(int i, fb_stream stream)
+void mark(int i, hipStream_t stream)
 {
-    if (g_prof.on) (void)hipEventRecord(g_prof.ev[i], (hipStream_t)stream);
+    if (g_prof.on) (void)hipEventRecord(g_prof.ev[i], stream);
+}
+
+// A second stream (default priority) and two untimed events, created once per process by
+// side_stream_init, which fb_graph_create calls, so that compute calls themselves never allocate.
+// Setting FB_AMD_SERIAL=1 in the environment keeps everything on the caller's stream.
+struct SideStream {
+    bool ok = false, tried = false;
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+};
+
+SideStream &side_stream()
+{
+    static SideStream s;
+    return s;
 }
 
 }  // namespace
+
+namespace fb {
+
+void side_stream_init()
+{
+    SideStream &s = side_stream();
+    if (s.tried) return;
+    s.tried = true;
+    const char *serial = getenv("FB_AMD_SERIAL");
+    if (serial && serial[0] == '1') return;
+    if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) != hipSuccess) return;
+    if (hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&s.join, hipEventDisableTiming) != hipSuccess)
+        return;
+    s.ok = true;
+}
+
+}  // namespace fb
 
 extern "C" {
 
 int fb_profile_enable(int on)
 {
     if (on && !g_prof.on) {
-        for (int i = 0; i < 5; ++i)
+        for (int i = 0; i < 7; ++i)
             if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) {
                 for (int j = 0; j < i; ++j) (void)hipEventDestroy(g_prof.ev[j]);
                 return fail(FB_EHIP, "fb_profile_enable: hipEventCreate failed");
@@ -128,7 +162,7 @@ int fb_profile_enable(int on)
         g_prof.on = true;
         g_prof.recorded = false;
     } else if (!on && g_prof.on) {
-        for (int i = 0; i < 5; ++i) (void)hipEventDestroy(g_prof.ev[i]);
+        for (int i = 0; i < 7; ++i) (void)hipEventDestroy(g_prof.ev[i]);
         g_prof.on = false;
         g_prof.recorded = false;
     }
@@ -139,8 +173,10 @@ int fb_profile_read(float *ms)
 {
     if (!g_prof.on || !g_prof.recorded || !ms) return fail(FB_EINVAL, "fb_profile_read: nothing recorded");
     if (hipEventSynchronize(g_prof.ev[4]) != hipSuccess) return fail(FB_EHIP, "fb_profile_read: hipEventSynchronize failed");
+    if (hipEventSynchronize(g_prof.ev[6]) != hipSuccess) return fail(FB_EHIP, "fb_profile_read: hipEventSynchronize failed");
+    const int first[4] = {5, 1, 2, 3}, last[4] = {6, 2, 3, 4};
     for (int i = 0; i < 4; ++i)
-        if (hipEventElapsedTime(&ms[i], g_prof.ev[i], g_prof.ev[i + 1]) != hipSuccess)
+        if (hipEventElapsedTime(&ms[i], g_prof.ev[first[i]], g_prof.ev[last[i]]) != hipSuccess)
             return fail(FB_EHIP, "fb_profile_read: hipEventElapsedTime failed");
     return FB_OK;
 }
@@ -212,24 +248,36 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
     double *zn = logz_num ? logz_num : (double *)w; w += align256((size_t)B * sizeof(double));
     double *zd = logz_den ? logz_den : (double *)w;
 
-    // both recursions of a graph run side by side in one launch
+    // Both recursions of a graph run side by side in one launch.  The denominator launch goes first on
+    // the caller's stream; the (much smaller) numerator launch runs beside it on the library's side stream
+    // and fills compute units as short sequences of the denominator finish.
     RecDir dn[2] = {make_dir(num, false, num_a, true, nullptr, zn, 1.0f, false),
                     make_dir(num, true, num_b, true, nullptr, nullptr, 1.0f, false)};
-    mark(0, stream);
-    if ((rc = run_recursion(num, emis, lengths, B, N, D, dn, 2, stream))) return rc;
-    mark(1, stream);
     RecDir dd[2] = {make_dir(den, false, den_a, true, nullptr, zd, 1.0f, false),
                     make_dir(den, true, den_b, true, nullptr, nullptr, 1.0f, false)};
-    if ((rc = run_recursion(den, emis, lengths, B, N, D, dd, 2, stream))) return rc;
-    mark(2, stream);
+    hipStream_t main_s = (hipStream_t)stream;
+    SideStream &side = side_stream();
+    const bool fork = side.ok && hipEventRecord(side.fork, main_s) == hipSuccess &&
+                      hipStreamWaitEvent(side.stream, side.fork, 0) == hipSuccess;
+    hipStream_t num_s = fork ? side.stream : main_s;
+    mark(0, main_s);
+    mark(1, main_s);
+    if ((rc = run_recursion(den, emis, lengths, B, N, D, dd, 2, main_s))) return rc;
+    mark(2, main_s);
+    mark(5, num_s);
+    if ((rc = run_recursion(num, emis, lengths, B, N, D, dn, 2, num_s))) return rc;
+    mark(6, num_s);
+    if (fork && (hipEventRecord(side.join, side.stream) != hipSuccess || hipStreamWaitEvent(main_s, side.join, 0) != hipSuccess))
+        return fail(FB_EHIP, "lfmmi_loss_grad: joining the side stream failed");
 
     // Eq. 17: numerator pdf posteriors minus denominator pdf posteriors
     const PostGraph q[2] = {make_post(den, den_a, den_b, den->f64, 1.0f, -1.0f, nullptr),
                             make_post(num, num_a, num_b, num->f64, 1.0f, 1.0f, nullptr)};
+    if (fork) mark(2, main_s);   // the gradient stage starts when both recursion launches are done
     if ((rc = run_posteriors(q, 2, lengths, B, N, D, grad, stream))) return rc;
-    mark(3, stream);
+    mark(3, main_s);
     rc = launch_loss(zn, zd, lengths, B, loss, stream);
-    mark(4, stream);
+    mark(4, main_s);
     if (g_prof.on && rc == FB_OK) g_prof.recorded = true;
     return rc;
 }

@@ -174,6 +174,7 @@ struct fb_graph {
 namespace fb {
 
 void set_error(const std::string &msg);
+void side_stream_init();   // once per process: the stream lfmmi_loss_grad runs the numerator launch on
 int fail(int code, const std::string &msg);
 
 struct RecDir {
