@@ -90,7 +90,7 @@ int run_posteriors(const PostGraph *gs, int n_graph, const int32_t *lengths, int
     for (int i = 0; i < n_graph; ++i) {
         p.g[i] = gs[i];
         p.Kcap = std::max(p.Kcap, gs[i].Kcap);
-        if (gs[i].f64) p.Kcap64 = std::max(p.Kcap64, gs[i].Kcap);
+        if (gs[i].f64) p.Kcap64 = std::max(p.Kcap64, (gs[i].Kcap + 1) & ~1);   // even: what follows stays 16-byte aligned
     }
     p.lengths = lengths;
     p.B = B; p.N = N; p.D = D;

@@ -389,19 +389,26 @@ constexpr int kPostThreads = 512;
 
 namespace {
 
-// exp2(log posterior - max) of one frame of one graph into tb[0..K) (unnormalised); returns 1 / their sum
-// (0 if the frame has no mass).  IT: element type of a and b; stage: tb itself, or a wider buffer.
+// First pass over one frame of one graph: log posteriors (a + b) * in_scale into stage[0..K); returns
+// the thread's maximum.  IT: element type of a and b.
 template <class IT>
-__device__ __forceinline__ float frame_posteriors(const IT *arow, const IT *brow, IT in_scale, int K, float *tb,
-                                                 IT *stage, float *red, int tid, int lane, int wave)
+__device__ __forceinline__ IT frame_logpost(const IT *arow, const IT *brow, IT in_scale, int K, IT *stage, int tid)
 {
-    constexpr int NT = kPostThreads, NWV = kPostThreads / kWave;
     IT mx = (IT)(-INFINITY);
-    for (int k = tid; k < K; k += NT) {
+    for (int k = tid; k < K; k += kPostThreads) {
         const IT t = (arow[k] + brow[k]) * in_scale;
         stage[k] = t;
         mx = tmax(mx, t);
     }
+    return mx;
+}
+
+// Rest of the frame: block maximum, exp2(log posterior - max) into tb[0..K) (unnormalised); returns
+// 1 / their sum (0 if the frame has no mass).  stage: tb itself, or a wider buffer.
+template <class IT>
+__device__ __forceinline__ float frame_finish(IT mx, int K, float *tb, const IT *stage, float *red, int tid, int lane, int wave)
+{
+    constexpr int NT = kPostThreads, NWV = kPostThreads / kWave;
     mx = wave_max(mx);
     IT *redt = (IT *)red;
     if (lane == 0) redt[wave] = mx;
@@ -428,17 +435,20 @@ __device__ __forceinline__ float frame_posteriors(const IT *arow, const IT *brow
     return sum > 0.0f ? 1.0f / sum : 0.0f;
 }
 
+constexpr int kPostPrefetch = 3;   // 16-byte pieces per thread and array held in registers: 6144 states
+
 }  // namespace
 
 __global__ __launch_bounds__(kPostThreads) void fb_posterior_kernel(const PostParams P)
 {
     extern __shared__ double lds_raw[];
-    constexpr int NT = kPostThreads;
+    constexpr int NT = kPostThreads, U = kPostPrefetch;
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int b = blockIdx.y;
     const int T = min(max(P.lengths[b], 0), P.N);
     const int n0 = blockIdx.x * P.frames_per_block;
+    const int n_end = min(min(n0 + P.frames_per_block, P.N), T);   // real frames of this chunk: [n0, n_end)
     float *red = (float *)lds_raw;                  // reduction slots: one double or float per wave
     double *stage64 = lds_raw + 8;                  // [Kcap64] log posteriors of a double-carrier graph
     float *tb = (float *)(stage64 + P.Kcap64);      // [Kcap] per-state values of the frame
@@ -446,7 +456,24 @@ __global__ __launch_bounds__(kPostThreads) void fb_posterior_kernel(const PostPa
     uint16_t *tab = (uint16_t *)(rho + P.D);        // per graph: row_ptr [Rcap + 1], row_pdf [Rcap], states [Kcap]
     const uint16_t *rp[2], *rd[2], *rs[2];
     PdfSub ps[2];
-    if (n0 < T) {   // the tables are needed only if the chunk has a real frame
+    // The first graph's rows of the next frame travel from HBM into registers while the current frame is
+    // worked on (when it is a shared graph of float vectors whose rows are 16-byte aligned).
+    const PostGraph &G0 = P.g[0];
+    const int K0 = G0.pdfs.sub[0].K;
+    const bool pre = G0.shared && !G0.f64 && (K0 & 3) == 0 && (((uintptr_t)G0.a | (uintptr_t)G0.b) & 15) == 0 && n0 < n_end;
+    const int Kpre = pre ? min(K0, NT * 4 * U) : 0;   // states covered by the prefetch registers
+    float4 pa[U], pb[U];
+    auto issue = [&](int n) {
+        const float4 *ar = (const float4 *)((const float *)G0.a + ((size_t)b * P.N + n) * K0);
+        const float4 *br = (const float4 *)((const float *)G0.b + ((size_t)b * P.N + n) * K0);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int q = u * NT + tid;
+            if (q * 4 < Kpre) { pa[u] = ar[q]; pb[u] = br[q]; }
+        }
+    };
+    if (pre) issue(n0);
+    if (n0 < n_end) {   // the tables are needed only if the chunk has a real frame
         uint16_t *at = tab;
         for (int gi = 0; gi < P.n_graph; ++gi) {
             const PostGraph &G = P.g[gi];
@@ -486,12 +513,32 @@ __global__ __launch_bounds__(kPostThreads) void fb_posterior_kernel(const PostPa
             if (gi == 0 && !covers_all && prow)
                 for (int d = tid; d < P.D; d += NT) rho[d] = 0.0f;
             float inv;
-            if (G.f64)
-                inv = frame_posteriors<double>((const double *)G.a + at, (const double *)G.b + at, (double)G.in_scale, K, tb,
-                                               stage64, red, tid, lane, wave);
-            else
-                inv = frame_posteriors<float>((const float *)G.a + at, (const float *)G.b + at, G.in_scale, K, tb, tb, red,
-                                              tid, lane, wave);
+            if (G.f64) {
+                const double mx = frame_logpost<double>((const double *)G.a + at, (const double *)G.b + at, (double)G.in_scale, K,
+                                                        stage64, tid);
+                inv = frame_finish<double>(mx, K, tb, stage64, red, tid, lane, wave);
+            } else if (gi == 0 && pre) {
+                float mx = -INFINITY;   // this frame's rows are in the registers
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int q = u * NT + tid;
+                    if (q * 4 < Kpre) {
+                        float4 t;
+                        t.x = (pa[u].x + pb[u].x) * G.in_scale; t.y = (pa[u].y + pb[u].y) * G.in_scale;
+                        t.z = (pa[u].z + pb[u].z) * G.in_scale; t.w = (pa[u].w + pb[u].w) * G.in_scale;
+                        ((float4 *)tb)[q] = t;
+                        mx = tmax(tmax(mx, tmax(t.x, t.y)), tmax(t.z, t.w));
+                    }
+                }
+                if (n + 1 < n_end) issue(n + 1);   // the next frame starts its trip now
+                if (K > Kpre)
+                    mx = tmax(mx, frame_logpost<float>((const float *)G.a + at + Kpre, (const float *)G.b + at + Kpre,
+                                                       G.in_scale, K - Kpre, tb + Kpre, tid));
+                inv = frame_finish<float>(mx, K, tb, tb, red, tid, lane, wave);
+            } else {
+                const float mx = frame_logpost<float>((const float *)G.a + at, (const float *)G.b + at, G.in_scale, K, tb, tid);
+                inv = frame_finish<float>(mx, K, tb, tb, red, tid, lane, wave);
+            }
             if (G.state_post) {
                 float *srow = G.state_post + at;
                 for (int k = tid; k < K; k += NT) srow[k] = tb[k] * inv;
@@ -500,11 +547,35 @@ __global__ __launch_bounds__(kPostThreads) void fb_posterior_kernel(const PostPa
             if (prow) {
                 const float scale = G.sign * inv;
                 const uint16_t *ptr = rp[gi], *pdfid = rd[gi], *st = rs[gi];
-                for (int r = tid; r < ps[gi].n_rows; r += NT) {
-                    float acc = 0.0f;
-                    for (int i = ptr[r]; i < ptr[r + 1]; ++i) acc += tb[st[i]];
-                    if (gi == 0 && covers_all) rho[pdfid[r]] = acc * scale;
-                    else rho[pdfid[r]] += acc * scale;
+                const int n_rows = ps[gi].n_rows;
+                // tpr threads share a pdf when there are fewer pdfs than threads (tpr a power of two <= 16);
+                // each thread walks two pdfs at once so that two chains of dependent LDS reads overlap
+                int tpr = 1;
+                while (tpr < 16 && n_rows * tpr * 2 <= NT) tpr *= 2;
+                const int rpp = NT / tpr, part = tid & (tpr - 1);
+                for (int r0 = tid / tpr; r0 < n_rows; r0 += 2 * rpp) {
+                    const int r1 = r0 + rpp;
+                    const bool two = r1 < n_rows;
+                    int i0 = ptr[r0] + part, i1 = two ? ptr[r1] + part : 0;
+                    const int e0 = ptr[r0 + 1], e1 = two ? ptr[r1 + 1] : 0;
+                    float acc0 = 0.0f, acc1 = 0.0f;
+                    while (i0 < e0 || i1 < e1) {
+                        const float v0 = i0 < e0 ? tb[st[i0]] : 0.0f, v1 = i1 < e1 ? tb[st[i1]] : 0.0f;
+                        acc0 += v0; acc1 += v1;
+                        i0 += tpr; i1 += tpr;
+                    }
+                    for (int o = tpr >> 1; o >= 1; o >>= 1) {   // fixed order: results do not depend on timing
+                        acc0 += __shfl_xor(acc0, o, 64);
+                        acc1 += __shfl_xor(acc1, o, 64);
+                    }
+                    if (part == 0) {
+                        if (gi == 0 && covers_all) rho[pdfid[r0]] = acc0 * scale;
+                        else rho[pdfid[r0]] += acc0 * scale;
+                        if (two) {
+                            if (gi == 0 && covers_all) rho[pdfid[r1]] = acc1 * scale;
+                            else rho[pdfid[r1]] += acc1 * scale;
+                        }
+                    }
                 }
                 __syncthreads();
             }
