@@ -37,8 +37,22 @@ constexpr double kLn2 = 0.69314718055994530942;
 __device__ __forceinline__ float fexp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float flog2(float x) { return __builtin_amdgcn_logf(x); }
 
-__device__ __forceinline__ float tmax(float a, float b) { return fmaxf(a, b); }
+// Maxima of values that are never NaN here: single instructions, without the quieting of
+// signalling NaNs that fmaxf() implies.
+__device__ __forceinline__ float tmax(float a, float b)
+{
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ float tmax3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
 __device__ __forceinline__ double tmax(double a, double b) { return fmax(a, b); }
+__device__ __forceinline__ double tmax3(double a, double b, double c) { return fmax(fmax(a, b), c); }
 
 // running (+)-sum in base 2: value = m + log2(s); m in the carrier type, s single
 template <class T>
@@ -54,11 +68,21 @@ __device__ __forceinline__ void lse_add(T &m, float &s, T x)
 template <class T>
 __device__ __forceinline__ void lse_add4(T &m, float &s, T x0, T x1, T x2, T x3)
 {
-    const T mn = tmax(tmax(tmax(m, x0), x1), tmax(x2, x3));
+    const T mn = tmax3(tmax3(m, x0, x1), x2, x3);
     const float r = fexp2((float)(m - mn));
     const float e0 = fexp2((float)(x0 - mn)), e1 = fexp2((float)(x1 - mn));
     const float e2 = fexp2((float)(x2 - mn)), e3 = fexp2((float)(x3 - mn));
     s = fmaf(s, r, (e0 + e1) + (e2 + e3));
+    m = mn;
+}
+
+template <class T>
+__device__ __forceinline__ void lse_add3(T &m, float &s, T x0, T x1, T x2)
+{
+    const T mn = tmax(tmax3(m, x0, x1), x2);
+    const float r = fexp2((float)(m - mn));
+    const float e0 = fexp2((float)(x0 - mn)), e1 = fexp2((float)(x1 - mn)), e2 = fexp2((float)(x2 - mn));
+    s = fmaf(s, r, (e0 + e1) + e2);
     m = mn;
 }
 
@@ -295,7 +319,7 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                         if (!(f & kFlagInfo)) {
                             lse_add4(m, sum, gv[0] + (T)a[0].w, gv[1] + (T)a[1].w, gv[2] + (T)a[2].w, gv[3] + (T)a[3].w);
                         } else {   // three arcs, then the lane's sum is complete
-                            lse_add4(m, sum, gv[0] + (T)a[0].w, gv[1] + (T)a[1].w, gv[2] + (T)a[2].w, kNegInf);
+                            lse_add3(m, sum, gv[0] + (T)a[0].w, gv[1] + (T)a[1].w, gv[2] + (T)a[2].w);
                             const uint32_t u = __float_as_uint(a[3].w);
                             const T pre = m + (T)flog2(sum) - c;   // sum == 0 -> -inf
                             const T x = pre + (T)ern[u >> 16] * (T)kLog2e;
