@@ -37,7 +37,7 @@ RecDir make_dir(const fb_graph *g, bool backward, void *out, bool out_carrier, f
     r.off = off;
     r.logz = logz;
     r.out_scale = out_scale;
-    r.Pcap = backward ? g->h_bwd.Pcap : g->h_fwd.Pcap;
+    r.Ccap = backward ? g->h_bwd.Ccap : g->h_fwd.Ccap;
     r.backward = backward ? 1 : 0;
     r.fill_pad = fill_pad ? 1 : 0;
     return r;
@@ -59,7 +59,7 @@ int run_recursion(const fb_graph *g, const float *emis, const int32_t *lengths, 
     size_t lds = 0;
     for (int i = 0; i < n_dir; ++i) {
         p.dir[i] = dirs[i];
-        lds = std::max(lds, recursion_lds_bytes(p.Kcap, dirs[i].Pcap, p.Ecap, dirs[i].backward != 0, g->f64, p.shared != 0));
+        lds = std::max(lds, recursion_lds_bytes(p.Kcap, dirs[i].Ccap, p.Ecap, dirs[i].backward != 0, g->f64, p.shared != 0));
     }
     if (lds > kLdsBytes) return fail(FB_EUNSUPPORTED, "state vectors and emission rows exceed the on-chip memory");
     return launch_recursion(g->nw, g->f64, p, lds, stream);

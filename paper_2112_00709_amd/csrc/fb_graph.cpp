@@ -56,19 +56,6 @@ int upload(fb_graph *g, const std::vector<T> &h, const T **dev)
     return FB_OK;
 }
 
-int upload_sell(fb_graph *g, const SellHost &h, SellDev &d)
-{
-    int rc;
-    if ((rc = upload(g, h.sub, &d.sub))) return rc;
-    if ((rc = upload(g, h.wave_ptr, &d.wave_ptr))) return rc;
-    if ((rc = upload(g, h.slice_trip, &d.slice_trip))) return rc;
-    if ((rc = upload(g, h.slice_arc, &d.slice_arc))) return rc;
-    if ((rc = upload(g, h.row_out, &d.row_out))) return rc;
-    if ((rc = upload(g, h.row_vidx, &d.row_vidx))) return rc;
-    if ((rc = upload(g, h.arcs, &d.arcs))) return rc;
-    return FB_OK;
-}
-
 int upload_pdf(fb_graph *g, const PdfHost &h, PdfDev &d)
 {
     int rc;
@@ -84,16 +71,18 @@ int upload_stream(fb_graph *g, const StreamHost &h, StreamDev &d)
     if ((rc = upload(g, h.sub, &d.sub))) return rc;
     if ((rc = upload(g, h.waves, &d.waves))) return rc;
     if ((rc = upload(g, h.flagwords, &d.flagwords))) return rc;
+    if ((rc = upload(g, h.clones, &d.clones))) return rc;
+    if ((rc = upload(g, h.zero_rows, &d.zero_rows))) return rc;
     return upload(g, h.arcs, &d.arcs);
 }
 
 }  // namespace
 
-size_t recursion_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t Ecap, bool backward, bool f64, bool shared)
+size_t recursion_lds_bytes(int32_t Kcap, int32_t Ccap, int32_t Ecap, bool backward, bool f64, bool shared)
 {
-    // carrier-typed: state buffers (states, partial slots, a dump slot) and reduction slots;
+    // carrier-typed: state buffers (states, clone slots, a dump slot) and reduction slots;
     // then three emission rows (float, plus a zero slot) and, for packed graphs, a pdf id per state
-    const size_t xs = (size_t)Kcap + (size_t)Pcap + 1;
+    const size_t xs = (size_t)Kcap + (size_t)Ccap + 1;
     return (xs * (backward ? 4 : 2) + 4 * kNWShared + 2) * (f64 ? 8 : 4) + ((size_t)Ecap + 1) * 12 +
            (shared ? 0 : (size_t)Ecap * 4) + kLdsReserve;
 }
@@ -130,10 +119,10 @@ const char *fb_strerror(int code)
 int32_t fb_limits_max_states(int32_t D, int shared)
 {
     if (D <= 0) return 0;
-    // backward recursion: four state vectors, partial slots (allow K/8), two emission rows
+    // backward recursion: four state vectors, clone slots (allow K/8), three emission rows
     // (D entries for a shared graph, one per state for packed graphs)
-    const double avail = (double)kLdsBytes - (double)kLdsReserve - (shared ? 8.0 * D : 0.0);
-    const double per_state = 4.0 * (4.0 + 0.125 + (shared ? 0.0 : 2.0));
+    const double avail = (double)kLdsBytes - (double)kLdsReserve - (shared ? 12.0 * D : 0.0);
+    const double per_state = 4.0 * (4.0 + 0.125 + (shared ? 0.0 : 4.0));
     const double k = avail / per_state;
     return k < 1 ? 0 : (int32_t)k;
 }
@@ -219,16 +208,16 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
         }
         g->nw = (max_sub_E >= 4096 || g->max_sub_K > 1024) ? kNWShared : kNWSmall;
         g->f64 = (flags & FB_GRAPH_WIDE_STATE) ? true : (flags & FB_GRAPH_NARROW_STATE) ? false : g->nw == kNWSmall;
-        SellHost sell_fwd, sell_bwd;   // row-split plans of the two recursions, flattened into streams below
+        SellHost sell_fwd, sell_bwd;   // sliced plans of the two recursions, flattened into streams below
         sell_fwd.nw = sell_bwd.nw = g->nw - 1;   // the last wave of a workgroup moves data, the others walk arcs
 
         std::vector<int64_t> ptr;
-        std::vector<int32_t> col, rid, vid;
+        std::vector<int32_t> col, vid;
         std::vector<float> w;
         for (int32_t s = 0; s < n_sub; ++s) {
             const int32_t k0 = n_seq > 0 ? state_off[s] : 0, k1 = n_seq > 0 ? state_off[s + 1] : K, Ks = k1 - k0;
-            rid.resize((size_t)Ks); vid.resize((size_t)Ks);
-            for (int32_t k = 0; k < Ks; ++k) { rid[k] = k; vid[k] = n_seq > 0 ? k : pdf[k0 + k]; }
+            vid.resize((size_t)Ks);
+            for (int32_t k = 0; k < Ks; ++k) vid[k] = n_seq > 0 ? k : pdf[k0 + k];
             for (int dir = 0; dir < 2; ++dir) {
                 const std::vector<int32_t> &p = dir ? L.out_ptr : L.in_ptr, &other = dir ? L.out_dst : L.in_src;
                 const std::vector<float> &ww = dir ? L.out_w : L.in_w;
@@ -240,8 +229,7 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
                     col[(size_t)(e - e0)] = other[(size_t)e] - k0;
                     w[(size_t)(e - e0)] = to_log2(ww[(size_t)e]);
                 }
-                sell_append(dir ? sell_bwd : sell_fwd, k0, Ks, Ks, ptr.data(), col.data(), w.data(), rid.data(),
-                            vid.data(), -INFINITY, 0.0f);
+                sell_append(dir ? sell_bwd : sell_fwd, k0, Ks, ptr.data(), col.data(), w.data(), vid.data());
             }
             // states grouped by pdf: one row per pdf (every pdf for a shared graph, the pdfs the
             // sub-graph uses for packed graphs), states in ascending order inside a row
@@ -277,7 +265,7 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
         {   // nothing a kernel will index may leave its array
             std::string why;
             const int32_t nv = n_seq > 0 ? -1 : D;
-            if (!sell_in_bounds(sell_fwd, -1, nv, why) || !sell_in_bounds(sell_bwd, -1, nv, why))
+            if (!sell_in_bounds(sell_fwd, nv, why) || !sell_in_bounds(sell_bwd, nv, why))
                 rc = fail(FB_EHIP, "internal error: schedule out of bounds (" + why + ")");
             else if (!stream_from_sell(sell_fwd, g->max_sub_K, n_seq > 0 ? g->max_sub_K : D, g->h_fwd, why) ||
                      !stream_from_sell(sell_bwd, g->max_sub_K, n_seq > 0 ? g->max_sub_K : D, g->h_bwd, why))
@@ -285,12 +273,12 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
             else if (!stream_in_bounds(g->h_fwd, nv, why) || !stream_in_bounds(g->h_bwd, nv, why))
                 rc = fail(FB_EHIP, "internal error: stream out of bounds (" + why + ")");
         }
-        const int32_t Pcap = std::max(g->h_fwd.Pcap, g->h_bwd.Pcap);
+        const int32_t Ccap = std::max(g->h_fwd.Ccap, g->h_bwd.Ccap);
         const int32_t Ecap = n_seq > 0 ? g->max_sub_K : D;
-        if (rc == FB_OK && (recursion_lds_bytes(g->max_sub_K, g->h_fwd.Pcap, Ecap, false, g->f64, n_seq == 0) > kLdsBytes ||
-            recursion_lds_bytes(g->max_sub_K, g->h_bwd.Pcap, Ecap, true, g->f64, n_seq == 0) > kLdsBytes)) {
+        if (rc == FB_OK && (recursion_lds_bytes(g->max_sub_K, g->h_fwd.Ccap, Ecap, false, g->f64, n_seq == 0) > kLdsBytes ||
+            recursion_lds_bytes(g->max_sub_K, g->h_bwd.Ccap, Ecap, true, g->f64, n_seq == 0) > kLdsBytes)) {
             rc = fail(FB_EUNSUPPORTED, "graph too large: " + std::to_string(g->max_sub_K) + " states, " +
-                                           std::to_string(Pcap) + " partial slots and " + std::to_string(Ecap) +
+                                           std::to_string(Ccap) + " clone slots and " + std::to_string(Ecap) +
                                            " emission entries do not fit the on-chip memory of a compute unit");
         }
 

@@ -13,87 +13,94 @@ namespace fb {
 constexpr int kWave = 64;            // gfx950 wavefront
 constexpr int kNWShared = 16;        // waves per workgroup, large (sub-)graphs
 constexpr int kNWSmall = 4;          // waves per workgroup, small (sub-)graphs
-constexpr int kChunk = 32;           // longest arc list one lane walks; longer rows are split
+constexpr int kChunk = 32;           // arcs one lane walks for one row; longer rows get more lanes
 constexpr size_t kLdsBytes = 160 * 1024;
 constexpr size_t kLdsReserve = 1024; // reduction slots etc.
 
 // One (src, weight) pair of a row of a sparse semiring matrix, as the kernels read it.
 struct Arc {
     int32_t src;   // index into the vector the row gathers from
-    float w;       // weight (log2 units in the log semiring; 1 / 0 in the plain-sum use)
+    float w;       // weight (log2 units)
+};
+
+// A row with more than 64 * kChunk arcs is computed as several "clone" rows, each a state of its
+// own in the recursion (slots after the sub-graph's K states): every clone sums a share of the
+// row's arcs and takes the row's emission, every arc that leaves the row's state is repeated for
+// each clone, and the state's value is the (+)-sum of its clones wherever a vector leaves the kernel.
+struct CloneDesc {
+    int32_t state;   // the row (local state id); it keeps the first share itself
+    int32_t first;   // its further clones are slots first .. first + count - 1 (local index K + slot)
+    int32_t count;
+    int32_t pad_;
 };
 
 // Part of a schedule that belongs to one (sub-)graph.
 struct SubDesc {
     int32_t k0;         // first state of the sub-graph in the global numbering
     int32_t K;          // its number of states
-    int32_t n_levels;   // passes over the rows: 1 + the depth of row splitting
-    int32_t n_part;     // partial-result slots used by split rows
-    int32_t wave_ptr0;  // where its [(n_levels * nw) + 1] slice ranges start in wave_ptr
-    int32_t pad_[3];
+    int32_t n_slot;     // clone slots it uses
+    int32_t clone0;     // its CloneDesc entries: clone0 .. clone0 + n_cdesc - 1
+    int32_t n_cdesc;
+    int32_t zero0;      // its rows without arcs: zero0 .. zero0 + n_zero - 1 in the zero-row list
+    int32_t n_zero;
+    int32_t wave_ptr0;  // host plan: where its nw + 1 slice ranges start; stream: its first WaveDesc
 };
 
-// Row-split sliced-ELL schedule of a sparse matrix-vector product, host side.
-// Rows are grouped 64 to a slice (one row per lane), a slice is padded to its
-// longest row, rows longer than kChunk are split into partial rows that a later
-// level combines, and slices are dealt to the nw waves of a workgroup so that
-// every wave has about the same number of arc visits.
+// Sliced plan of a sparse matrix-vector product in the log semifield, host side.
+// A slice is 64 lanes walking arcs in lockstep.  A row with n arcs takes g lanes of
+// one slice, g the smallest power of two with ceil(n / g) <= kChunk (at most 64; beyond
+// that the row is cloned, see CloneDesc); all rows of a slice take the same g, the g
+// partial sums of a row are combined across lanes when the slice ends.  Rows are
+// sorted by length so a slice is padded little; rows without arcs are not scheduled
+// at all (zero_rows).  Slices are dealt to the nw waves of a workgroup longest-first.
 struct SellHost {
     int nw = 0;
     std::vector<SubDesc> sub;
-    std::vector<int32_t> wave_ptr;    // slice ranges per (sub, level, wave)
+    std::vector<int32_t> wave_ptr;    // slice ranges per (sub, wave)
     std::vector<int32_t> slice_trip;  // arcs each lane of the slice walks
+    std::vector<int32_t> slice_lg;    // log2 of the lanes per row
     std::vector<int64_t> slice_arc;   // first arc of the slice in `arcs`
-    std::vector<int32_t> row_out;     // [n_slices*64]: >=0 final row id, -1 idle lane, <=-2 partial slot -2-o
+    std::vector<int32_t> row_out;     // [n_slices*64]: >= 0 target (state, or K + clone slot) written by this
+                                      // lane, -1 a lane that writes nothing
     std::vector<int32_t> row_vidx;    // [n_slices*64]: index of the row's emission in the staged emission vector
     std::vector<Arc> arcs;            // slice-major, then step, then lane
-    int32_t max_part = 0;
+    std::vector<CloneDesc> clones;
+    std::vector<int32_t> zero_rows;   // local ids of rows without arcs
+    int32_t max_slot = 0;             // most clone slots of any sub-graph
 };
 
-// Device copy of a SellHost.
-struct SellDev {
-    const SubDesc *sub = nullptr;
-    const int32_t *wave_ptr = nullptr;
-    const int32_t *slice_trip = nullptr;
-    const int64_t *slice_arc = nullptr;
-    const int32_t *row_out = nullptr;
-    const int32_t *row_vidx = nullptr;
-    const Arc *arcs = nullptr;
-};
+// rows [0, K) of a CSR-like matrix over K columns: entries ptr[r]..ptr[r+1] with column col[] and
+// weight w[] (log2 units); row_vidx[r] = emission index of row r.  Appends one sub-plan to `out`.
+void sell_append(SellHost &out, int32_t k0, int32_t K, const int64_t *ptr, const int32_t *col, const float *w,
+                 const int32_t *row_vidx);
 
-// rows [0, n_rows) of a CSR-like matrix: entries ptr[r]..ptr[r+1] with column col[] and weight w[].
-// Appends one sub-schedule to `out`.
-void sell_append(SellHost &out, int32_t k0, int32_t K, int32_t n_rows, const int64_t *ptr, const int32_t *col,
-                 const float *w, const int32_t *row_out_id, const int32_t *row_vidx_id, float pad_w, float one_w);
-
-bool sell_in_bounds(const SellHost &S, int32_t n_out, int32_t n_vidx, std::string &why);
-void sell_apply_host(const SellHost &S, int32_t sub, bool log_semiring, const double *x, double *y);
+bool sell_in_bounds(const SellHost &S, int32_t n_vidx, std::string &why);
 
 // ---------------------------------------------------------------------------
-// Stream form of a log-semiring schedule: what the recursion kernel interprets.
-// Every wave of the workgroup that walks arcs owns one contiguous, cyclic stream
-// of "rows" of 64 entries (one per lane), grouped in batches of kBatchRows rows.
-// A row is 64 arcs (one per lane: gather, add the weight, fold into the lane's
-// running sum), except that the last row of a batch may be an info row that
-// closes the slice: its entries say where each lane's finished sum goes and
-// which staged emission it takes.  Slices are padded with zero-weight (-inf)
-// arcs so that their info row falls on the last row of a batch.  A byte of flags
-// per batch tells whether it ends with an info row, whether it is padding to
-// skip, and whether a level (workgroup barrier) ends after it.  The stream of one
-// time step is the same every step, so the kernel keeps it kRing-1 batches ahead
-// of its use, across barriers and across steps.
+// Stream form of a plan: what the recursion kernel interprets.  Every wave of the
+// workgroup that walks arcs owns one contiguous, cyclic stream of "rows" of 64
+// entries (one per lane), grouped in batches of kBatchRows rows.  A row is 64 arcs
+// (one per lane: gather, add the weight, fold into the lane's running sum), except
+// that the last row of a batch may be an info row that closes the slice: its
+// entries say where each lane's finished sum goes and which staged emission it
+// takes.  Slices are padded with zero-weight (-inf) arcs so that their info row
+// falls on the last row of a batch.  A byte of flags per batch tells whether it
+// ends with an info row, whether it is padding to skip, and over how many lanes
+// the sums of a row are spread.  The stream of one time step is the same every
+// step, so the kernel keeps it kRing-1 batches ahead of its use, across barriers
+// and across steps.
 //
 // Info entry (in the weight field): low 16 bits = target index in the state
-// buffer of the step being written, [0, K) a state, Kcap + slot a partial slot,
-// Kcap + Pcap the dump slot of idle lanes; high 16 bits = index of the emission
-// in the staged emission vector, Ecap being a slot that always holds 0.
+// buffer of the step being written, [0, K) a state, Kcap + slot a clone slot,
+// Kcap + Ccap the dump slot of lanes that write nothing; high 16 bits = index of
+// the emission in the staged emission vector, Ecap being a slot that always holds 0.
 // ---------------------------------------------------------------------------
 constexpr int kBatchRows = 4;
 constexpr int kRing = 4;                        // batches per unrolled iteration = prefetch ring size
 constexpr int kResident = 6;                    // batches per wave and step that stay in registers (<= 8)
 constexpr uint32_t kFlagInfo = 0x01;            // the batch's last row is an info row
-constexpr uint32_t kFlagLevelEnd = 0x02;        // workgroup barrier after this batch
 constexpr uint32_t kFlagSkip = 0x04;            // nothing to do in this batch (padding)
+constexpr int kFlagLgShift = 3;                 // bits 3-5 of an info batch: log2 of the lanes per row
 
 struct WaveDesc {
     int64_t arc_base;    // first entry of the wave's stream in `arcs`
@@ -108,7 +115,9 @@ struct StreamHost {
     std::vector<WaveDesc> waves;
     std::vector<uint32_t> flagwords;
     std::vector<Arc> arcs;             // info entries: src = 0, w = bits of (target16 | vidx16 << 16)
-    int32_t Kcap = 0, Pcap = 0, Ecap = 0;   // index space of the info entries (see above)
+    std::vector<CloneDesc> clones;
+    std::vector<int32_t> zero_rows;
+    int32_t Kcap = 0, Ccap = 0, Ecap = 0;   // index space of the info entries (see above)
 };
 
 struct StreamDev {
@@ -116,6 +125,8 @@ struct StreamDev {
     const WaveDesc *waves = nullptr;
     const uint32_t *flagwords = nullptr;
     const Arc *arcs = nullptr;
+    const CloneDesc *clones = nullptr;
+    const int32_t *zero_rows = nullptr;
 };
 
 bool stream_from_sell(const SellHost &S, int32_t Kcap, int32_t Ecap, StreamHost &out, std::string &why);
@@ -186,7 +197,7 @@ struct RecDir {
     float *off;            // [B][N] offsets, nullable
     double *logz;          // [B], nullable
     float out_scale;       // ln 2 for natural-log output, 1 to keep log2 units
-    int32_t Pcap;          // partial slots of this direction's schedule
+    int32_t Ccap;          // clone slots of this direction's schedule
     int backward;
     int fill_pad;          // write -inf / 0 into the rows of padded frames
 };
@@ -225,7 +236,7 @@ int launch_recursion(int nw, bool f64, const RecParams &p, size_t lds_bytes, voi
 int launch_posteriors(const PostParams &p, size_t lds_bytes, void *stream);
 int launch_loss(const double *logz_num, const double *logz_den, const int32_t *lengths, int32_t B, double *loss,
                 void *stream);
-size_t recursion_lds_bytes(int32_t Kcap, int32_t Pcap, int32_t Ecap, bool backward, bool f64, bool shared);
+size_t recursion_lds_bytes(int32_t Kcap, int32_t Ccap, int32_t Ecap, bool backward, bool f64, bool shared);
 size_t posterior_lds_bytes(const PostParams &p);
 
 }  // namespace fb

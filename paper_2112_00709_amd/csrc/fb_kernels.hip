@@ -102,6 +102,61 @@ __device__ __forceinline__ T wave_max(T v)
     return v;
 }
 
+// Data-parallel-primitive moves inside rows of 16 lanes, and reads of single lanes, for 32- and 64-bit values.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) { return __uint_as_float(dpp_u<CTRL>(__float_as_uint(v))); }
+template <int CTRL>
+__device__ __forceinline__ double dpp_mov(double v)
+{
+    const uint64_t u = (uint64_t)__double_as_longlong(v);
+    const uint64_t r = (uint64_t)dpp_u<CTRL>((uint32_t)u) | ((uint64_t)dpp_u<CTRL>((uint32_t)(u >> 32)) << 32);
+    return __longlong_as_double((long long)r);
+}
+__device__ __forceinline__ float lane_value(float v, int l)
+{
+    return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(v), l));
+}
+__device__ __forceinline__ double lane_value(double v, int l)
+{
+    const uint64_t u = (uint64_t)__double_as_longlong(v);
+    const uint64_t r = (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)u, l) |
+                       ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(u >> 32), l) << 32);
+    return __longlong_as_double((long long)r);
+}
+
+// v of every lane replaced by op over its aligned group of 2^lg lanes (lg = 1..6, the same in all
+// lanes).  Inside a row of 16 lanes: exchanges with the lane whose number differs in one bit
+// (the mirror moves equal that exchange once groups of 4 resp. 8 lanes hold one value); across
+// rows: the four row results are read into scalars.
+template <class V, class Op>
+__device__ __forceinline__ V group_all(V v, int lg, int lane, Op op)
+{
+    v = op(v, dpp_mov<0xB1>(v));                  // quad_perm [1,0,3,2]
+    if (lg >= 2) v = op(v, dpp_mov<0x4E>(v));     // quad_perm [2,3,0,1]
+    if (lg >= 3) v = op(v, dpp_mov<0x141>(v));    // row_half_mirror
+    if (lg >= 4) v = op(v, dpp_mov<0x140>(v));    // row_mirror
+    if (lg >= 5) {
+        const V lo = op(lane_value(v, 0), lane_value(v, 16)), hi = op(lane_value(v, 32), lane_value(v, 48));
+        v = lg == 6 ? op(lo, hi) : (lane < 32 ? lo : hi);
+    }
+    return v;
+}
+
+// (m, s) of every lane replaced by the (+)-sum over its aligned group of 2^lg lanes (all lanes of
+// the group end with the same pair): first the maximum, then the sums rescaled to it
+template <class T>
+__device__ __forceinline__ void group_total(T &m, float &s, int lg, int lane)
+{
+    const T mg = group_all(m, lg, lane, [](T a, T b) { return tmax(a, b); });
+    s = group_all(s * fexp2((float)(m - mg)), lg, lane, [](float a, float b) { return a + b; });
+    m = mg;
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll
@@ -130,8 +185,8 @@ __device__ __forceinline__ float wave_sum(float v)
 // HBM latency therefore never sits in front of an arc load.
 //
 // LDS of a workgroup (carrier type T unless noted):
-//   xb   2 x Xs   x of the previous / current step; Xs = Kcap + Pcap + 1: the
-//                 states, then the partial slots of split rows, then a dump slot
+//   xb   2 x Xs   x of the previous / current step; Xs = Kcap + Ccap + 1: the
+//                 states, then the clones of rows too long for one slice, then a dump slot
 //   bh   2 x Xs   beta before v is applied (backward direction only)
 //   red  4 x NW   step maxima (two parities), scratch of the last reduction
 //   er   3 x (Ecap + 1) float   emissions as given (natural log) of the frame in use and
@@ -153,10 +208,10 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
     const StreamDev &S = R.sched;
     const bool bwd = R.backward != 0;
     const SubDesc sd = S.sub[P.shared ? 0 : b];
-    const int K = sd.K, k0 = sd.k0, L = sd.n_levels;
+    const int K = sd.K, k0 = sd.k0, nC = sd.n_slot;
     const int Tn = min(max(P.lengths[b], 0), P.N);
     const int nE = P.shared ? P.D : K;           // entries of a staged emission vector
-    const int Xs = P.Kcap + R.Pcap + 1, Es = P.Ecap + 1;
+    const int Xs = P.Kcap + R.Ccap + 1, Es = P.Ecap + 1;
 
     T *xb = (T *)lds_raw;
     T *bh = xb + 2 * Xs;
@@ -196,7 +251,8 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
         }
     };
     auto staged_wait = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
-    // a finished vector -> global memory, coalesced
+    // a finished vector -> global memory, coalesced; a cloned state leaves as the (+)-sum of its clones
+    const CloneDesc *cdesc = S.clones + sd.clone0;
     auto write_row = [&](int f, const T *srcv) {
         if (out_f) {
             float *orow = out_f + (size_t)f * out_ld;
@@ -211,6 +267,17 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                 for (int k = lane; k < K; k += kWave) orow[k] = srcv[k];
             }
         }
+        if (out_f || out_t)
+            for (int j = lane; j < sd.n_cdesc; j += kWave) {   // stores of one wave to one address keep their order
+                const CloneDesc cd = cdesc[j];
+                T m = (T)kNegBig;
+                float s = 0.0f;
+                lse_add(m, s, srcv[cd.state]);
+                for (int i = 0; i < cd.count; ++i) lse_add(m, s, srcv[P.Kcap + cd.first + i]);
+                const T v = m + (T)flog2(s);
+                if (out_f) out_f[(size_t)f * out_ld + cd.state] = (float)v * R.out_scale;
+                else out_t[(size_t)f * out_ld + cd.state] = v;
+            }
     };
 
     if (Tn > 0) {
@@ -235,6 +302,10 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
             if (bwd) bh[k] = s;
             wmax = tmax(wmax, x);
         }
+        for (int k = tid; k < nC; k += NT) {   // clones start empty: the state itself holds the start weight
+            xb[P.Kcap + k] = kNegInf;
+            if (bwd) bh[P.Kcap + k] = kNegInf;
+        }
         wmax = wave_max(wmax);
         if (lane == 0) red[wave] = wmax;
         __syncthreads();
@@ -253,7 +324,6 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                 if (i + 2 < Tn) stage(frame(i + 2), er + ((i + 2) % 3) * Es);   // buffer of frame i-1: no longer read
                 write_row(frame(i - 1), bwd ? bh + cur * Xs : xb + cur * Xs);
                 if (lane == 0) red[nxt * NW + wave] = kNegInf;
-                for (int l = 1; l < L; ++l) __syncthreads();
                 __syncthreads();
             }
         } else {
@@ -305,21 +375,29 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                 T M = red[cur * NW];
 #pragma unroll
                 for (int w = 1; w < NW; ++w) M = tmax(M, red[cur * NW + w]);
-                T c = (M == kNegInf) ? (T)0 : M;   // subtracted where a row leaves level 0
+                const T c = (M == kNegInf) ? (T)0 : M;
                 wmax = kNegInf;
                 T m = (T)kNegBig;
                 float sum = 0.0f;
                 const T *vbase = xc;
+                if (i <= 2)   // rows without arcs: the semiring zero from the second frame on, in both buffers
+                    for (int z = tid; z < sd.n_zero; z += NC * kWave) {
+                        const int k = S.zero_rows[sd.zero0 + z];
+                        xn[k] = kNegInf;
+                        if (bwd) bn[k] = kNegInf;
+                    }
                 // fold one batch: a, gv = its entries and gathered values; next = the batch after it
                 // (its gathers are issued before this batch's arithmetic), has_next: there is one in this step
                 auto fold = [&](uint32_t f, const Arc(&a)[kBatchRows], const T(&gv)[kBatchRows], T(&gnext)[kBatchRows],
                                 const Arc(&next)[kBatchRows], bool has_next) {
-                    if (!(f & kFlagLevelEnd) && has_next) gather(gnext, next, vbase);
+                    if (has_next) gather(gnext, next, vbase);
                     if (!(f & kFlagSkip)) {
                         if (!(f & kFlagInfo)) {
                             lse_add4(m, sum, gv[0] + (T)a[0].w, gv[1] + (T)a[1].w, gv[2] + (T)a[2].w, gv[3] + (T)a[3].w);
-                        } else {   // three arcs, then the lane's sum is complete
+                        } else {   // three arcs, then the row's sum is complete
                             lse_add3(m, sum, gv[0] + (T)a[0].w, gv[1] + (T)a[1].w, gv[2] + (T)a[2].w);
+                            const int lg = (int)((f >> kFlagLgShift) & 7u);
+                            if (lg) group_total(m, sum, lg, lane);   // the row's arcs were spread over 2^lg lanes
                             const uint32_t u = __float_as_uint(a[3].w);
                             const T pre = m + (T)flog2(sum) - c;   // sum == 0 -> -inf
                             const T x = pre + (T)ern[u >> 16] * (T)kLog2e;
@@ -329,12 +407,6 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                             m = (T)kNegBig;
                             sum = 0.0f;
                         }
-                    }
-                    if (f & kFlagLevelEnd) {   // partial sums of split rows are complete: combine them
-                        __syncthreads();
-                        vbase = xn + P.Kcap;
-                        c = (T)0;
-                        if (has_next) gather(gnext, next, vbase);
                     }
                 };
                 gather(g[0], res[0], vbase);
@@ -373,6 +445,10 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
             T m = (T)kNegBig;
             float s = 0.0f;
             for (int k = tid; k < K; k += NT) lse_add(m, s, xl[k] + (T)R.obound[k0 + k]);
+            for (int j = tid; j < sd.n_cdesc; j += NT) {   // clones end with their state's weight
+                const CloneDesc cd = cdesc[j];
+                for (int i = 0; i < cd.count; ++i) lse_add(m, s, xl[P.Kcap + cd.first + i] + (T)R.obound[k0 + cd.state]);
+            }
 #pragma unroll
             for (int o = 32; o >= 1; o >>= 1) lse_merge(m, s, (T)__shfl_xor(m, o, 64), __shfl_xor(s, o, 64));
             T *rm = red + 2 * NW, *rs = rm + NW;

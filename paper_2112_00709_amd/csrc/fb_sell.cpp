@@ -1,19 +1,21 @@
-// Host-side construction of the row-split sliced-ELL schedules the kernels walk.
+// Host-side construction of the sliced plans the recursion kernel walks.
 //
 // The forward recursion (Eq. 13) multiplies by T transposed: row j of the
 // product gathers the arcs that enter state j.  The backward recursion (Eq. 14)
 // multiplies by T: row i gathers the arcs that leave state i.  Both are sparse
-// matrix x vector products in the log semifield, and so is (in ordinary
-// arithmetic) the accumulation of state posteriors into pdf posteriors.  This
-// file turns any such matrix into a static work plan for one workgroup:
-//   * one row per lane, 64 rows per slice, slice padded to its longest row;
-//   * rows sorted by length so that padding is small;
-//   * a row longer than kChunk entries is cut into partial rows; the partial
-//     results land in numbered slots and the next level combines them with the
-//     same row-per-lane loop (in-degree skew never leaves a lane alone with
-//     thousands of arcs);
+// matrix x vector products in the log semifield.  This file turns such a matrix
+// into a static work plan for one workgroup:
+//   * 64 lanes per slice; a row takes 1, 2, 4, ... 64 lanes of one slice so that
+//     no lane walks more than kChunk arcs, and all rows of a slice take the same
+//     number of lanes (the kernel adds the lanes of a row up when the slice ends);
+//   * a row too long even for 64 lanes is cloned: the clones are rows of their own
+//     whose values the next step gathers like any other state (the arcs that leave
+//     the row's state are repeated for every clone), so in-degree skew costs
+//     neither a second pass nor a workgroup barrier;
+//   * rows sorted by length so that a slice is padded little; rows without arcs
+//     are left out (their value is the semiring zero at every step but the first);
 //   * slices are dealt to the waves of the workgroup longest-first, so every
-//     wave walks about the same number of arcs between two barriers.
+//     wave walks about the same number of batches per time step.
 #include <algorithm>
 #include <cmath>
 #include <numeric>
@@ -26,187 +28,184 @@ namespace fb {
 namespace {
 
 struct Item {
-    int32_t out;       // row_out encoding
+    int32_t out;       // target: state, or K + clone slot
     int32_t vidx;
-    int64_t begin;     // range in the level's entry pool
+    int64_t begin;     // range in the expanded arc pool
     int32_t n;
 };
 
+int lanes_log2(int32_t n)
+{
+    int lg = 0;
+    while (lg < 6 && (n + (1 << lg) - 1) / (1 << lg) > kChunk) ++lg;
+    return lg;
+}
+
+// batches of the stream a slice of this width takes (its info row closes the last one)
+int32_t slice_batches(int32_t trip) { return trip / kBatchRows + 1; }
+
 }  // namespace
 
-void sell_append(SellHost &S, int32_t k0, int32_t K, int32_t n_rows, const int64_t *ptr, const int32_t *col,
-                 const float *w, const int32_t *row_out_id, const int32_t *row_vidx_id, float pad_w, float one_w)
+void sell_append(SellHost &S, int32_t k0, int32_t K, const int64_t *ptr, const int32_t *col, const float *w,
+                 const int32_t *row_vidx)
 {
     const int nw = S.nw;
     SubDesc sd{};
     sd.k0 = k0;
     sd.K = K;
     sd.wave_ptr0 = (int32_t)S.wave_ptr.size();
+    sd.clone0 = (int32_t)S.clones.size();
+    sd.zero0 = (int32_t)S.zero_rows.size();
 
-    // entry pool of the current level
-    std::vector<int32_t> pcol(col, col + ptr[n_rows]);
-    std::vector<float> pw(w, w + ptr[n_rows]);
-    struct Row { int32_t out, vidx; int64_t begin; int32_t n; };
-    std::vector<Row> rows(n_rows);
-    for (int32_t r = 0; r < n_rows; ++r)
-        rows[r] = Row{row_out_id[r], row_vidx_id ? row_vidx_id[r] : 0, ptr[r], (int32_t)(ptr[r + 1] - ptr[r])};
-
-    int32_t n_part = 0, n_levels = 0;
-    while (!rows.empty()) {
-        std::vector<Item> items;
-        std::vector<Row> next_rows;
-        std::vector<int32_t> ncol;
-        std::vector<float> nwgt;
-        for (const Row &r : rows) {
-            if (r.n <= kChunk) {
-                items.push_back(Item{r.out, r.vidx, r.begin, r.n});
-                continue;
-            }
-            int32_t nch = (r.n + kChunk - 1) / kChunk, base = r.n / nch, rem = r.n % nch;
-            int64_t at = r.begin;
-            Row nr{r.out, r.vidx, (int64_t)ncol.size(), nch};
-            for (int32_t c = 0; c < nch; ++c) {
-                int32_t len = base + (c < rem ? 1 : 0);
-                items.push_back(Item{-2 - n_part, 0, at, len});
-                ncol.push_back(n_part);
-                nwgt.push_back(one_w);
-                ++n_part;
-                at += len;
-            }
-            next_rows.push_back(nr);
-        }
-        // longest rows first (stable: equal lengths keep row order)
-        std::stable_sort(items.begin(), items.end(), [](const Item &a, const Item &b) { return a.n > b.n; });
-        const int32_t n_sl = (int32_t)((items.size() + kWave - 1) / kWave);
-        // deal slices to waves: longest first, to the least loaded wave
-        std::vector<std::vector<int32_t>> mine(nw);
-        std::vector<int64_t> load(nw, 0);
-        for (int32_t s = 0; s < n_sl; ++s) {
-            int best = 0;
-            for (int wv = 1; wv < nw; ++wv)
-                if (load[wv] < load[best]) best = wv;
-            mine[best].push_back(s);
-            load[best] += items[(size_t)s * kWave].n + 3;   // +3: fixed cost of a slice in arc visits
-        }
-        for (int wv = 0; wv < nw; ++wv) {
-            S.wave_ptr.push_back((int32_t)S.slice_trip.size());
-            for (int32_t s : mine[wv]) {
-                const int32_t trip = items[(size_t)s * kWave].n;
-                S.slice_trip.push_back(trip);
-                S.slice_arc.push_back((int64_t)S.arcs.size());
-                const size_t first = (size_t)s * kWave;
-                for (int lane = 0; lane < kWave; ++lane) {
-                    const bool live = first + lane < items.size();
-                    S.row_out.push_back(live ? items[first + lane].out : -1);
-                    S.row_vidx.push_back(live ? items[first + lane].vidx : 0);
-                }
-                for (int32_t it = 0; it < trip; ++it)
-                    for (int lane = 0; lane < kWave; ++lane) {
-                        Arc a{0, pad_w};
-                        if (first + lane < items.size() && it < items[first + lane].n) {
-                            const int64_t e = items[first + lane].begin + it;
-                            a.src = pcol[e];
-                            a.w = pw[e];
-                        }
-                        S.arcs.push_back(a);
-                    }
-            }
-        }
-        ++n_levels;
-        rows.swap(next_rows);
-        pcol.swap(ncol);
-        pw.swap(nwgt);
+    // rows that need clones, and their slots
+    const int64_t row_cap = (int64_t)kWave * kChunk;
+    std::vector<int32_t> n_share((size_t)K, 1), first_slot((size_t)K, 0);
+    int32_t n_slot = 0;
+    for (int32_t r = 0; r < K; ++r) {
+        const int64_t n = ptr[r + 1] - ptr[r];
+        if (n <= row_cap) continue;
+        n_share[r] = (int32_t)((n + row_cap - 1) / row_cap);
+        first_slot[r] = n_slot;
+        S.clones.push_back(CloneDesc{r, n_slot, n_share[r] - 1, 0});
+        n_slot += n_share[r] - 1;
     }
-    S.wave_ptr.push_back((int32_t)S.slice_trip.size());   // end of the last (level, wave) range
-    sd.n_levels = n_levels;
-    sd.n_part = n_part;
-    S.max_part = std::max(S.max_part, n_part);
+    sd.n_slot = n_slot;
+    sd.n_cdesc = (int32_t)S.clones.size() - sd.clone0;
+
+    // arc pool with the arcs out of cloned states repeated, then one item per row or clone
+    std::vector<int32_t> pcol;
+    std::vector<float> pw;
+    std::vector<Item> items;
+    for (int32_t r = 0; r < K; ++r) {
+        const int64_t begin = (int64_t)pcol.size();
+        for (int64_t e = ptr[r]; e < ptr[r + 1]; ++e) {
+            pcol.push_back(col[e]);
+            pw.push_back(w[e]);
+            for (int32_t c = 1; c < n_share[col[e]]; ++c) {
+                pcol.push_back(K + first_slot[col[e]] + c - 1);
+                pw.push_back(w[e]);
+            }
+        }
+        const int64_t n = (int64_t)pcol.size() - begin;
+        if (n == 0) {
+            S.zero_rows.push_back(r);
+            continue;
+        }
+        const int32_t shares = n_share[r];
+        int64_t at = begin;
+        for (int32_t c = 0; c < shares; ++c) {
+            const int32_t len = (int32_t)(n / shares + (c < n % shares ? 1 : 0));
+            items.push_back(Item{c == 0 ? r : K + first_slot[r] + c - 1, row_vidx[r], at, len});
+            at += len;
+        }
+    }
+    sd.n_zero = (int32_t)S.zero_rows.size() - sd.zero0;
+
+    // longest rows first (stable: equal lengths keep row order); a slice takes its lanes-per-row from
+    // its first (longest) row, the rows after it are not longer and fit the same share of lanes
+    std::stable_sort(items.begin(), items.end(), [](const Item &a, const Item &b) { return a.n > b.n; });
+    struct Slice { size_t first; int32_t count, lg, trip; };
+    std::vector<Slice> slices;
+    for (size_t i = 0; i < items.size();) {
+        Slice sl{};
+        sl.first = i;
+        sl.lg = lanes_log2(items[i].n);
+        sl.count = (int32_t)std::min<size_t>((size_t)(kWave >> sl.lg), items.size() - i);
+        sl.trip = (items[i].n + (1 << sl.lg) - 1) >> sl.lg;
+        slices.push_back(sl);
+        i += (size_t)sl.count;
+    }
+    // deal slices to waves: most batches first, to the least loaded wave
+    std::vector<size_t> order(slices.size());
+    std::iota(order.begin(), order.end(), (size_t)0);
+    std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) { return slices[a].trip > slices[b].trip; });
+    std::vector<std::vector<size_t>> mine((size_t)nw);
+    std::vector<int64_t> load((size_t)nw, 0);
+    for (size_t s : order) {
+        int best = 0;
+        for (int wv = 1; wv < nw; ++wv)
+            if (load[wv] < load[best]) best = wv;
+        mine[best].push_back(s);
+        load[best] += slice_batches(slices[s].trip);
+    }
+    for (int wv = 0; wv < nw; ++wv) {
+        S.wave_ptr.push_back((int32_t)S.slice_trip.size());
+        for (size_t s : mine[wv]) {
+            const Slice &sl = slices[s];
+            const int g = 1 << sl.lg;
+            S.slice_trip.push_back(sl.trip);
+            S.slice_lg.push_back(sl.lg);
+            S.slice_arc.push_back((int64_t)S.arcs.size());
+            for (int lane = 0; lane < kWave; ++lane) {
+                const int it = lane >> sl.lg;
+                const bool live = it < sl.count;
+                S.row_out.push_back(live && (lane & (g - 1)) == 0 ? items[sl.first + it].out : -1);
+                S.row_vidx.push_back(live ? items[sl.first + it].vidx : -1);
+            }
+            // lane t of a row's g lanes walks arcs [t * trip, (t + 1) * trip) of the row
+            for (int32_t step = 0; step < sl.trip; ++step)
+                for (int lane = 0; lane < kWave; ++lane) {
+                    Arc a{0, -INFINITY};
+                    const int it = lane >> sl.lg;
+                    if (it < sl.count) {
+                        const Item &im = items[sl.first + it];
+                        const int64_t j = (int64_t)(lane & (g - 1)) * sl.trip + step;
+                        if (j < im.n) {
+                            a.src = pcol[(size_t)(im.begin + j)];
+                            a.w = pw[(size_t)(im.begin + j)];
+                        }
+                    }
+                    S.arcs.push_back(a);
+                }
+        }
+    }
+    S.wave_ptr.push_back((int32_t)S.slice_trip.size());   // end of the last wave's range
+    S.max_slot = std::max(S.max_slot, n_slot);
     S.sub.push_back(sd);
 }
 
-}  // namespace fb
-
-namespace fb {
-
-// Every index a kernel will dereference while walking the schedule stays inside
-// the arrays it indexes.  n_out: number of targets of final rows, n_vidx: entries of
-// the staged emission vector; a negative value means "the sub-graph's own state count".
-bool sell_in_bounds(const SellHost &S, int32_t n_out, int32_t n_vidx, std::string &why)
+// Every index a kernel will dereference while walking the plan stays inside the arrays it
+// indexes.  n_vidx: entries of the staged emission vector; a negative value means "the
+// sub-graph's own state count".
+bool sell_in_bounds(const SellHost &S, int32_t n_vidx, std::string &why)
 {
     const size_t n_slices = S.slice_trip.size();
-    if (S.slice_arc.size() != n_slices || S.row_out.size() != n_slices * kWave || S.row_vidx.size() != n_slices * kWave) {
+    if (S.slice_arc.size() != n_slices || S.slice_lg.size() != n_slices || S.row_out.size() != n_slices * kWave ||
+        S.row_vidx.size() != n_slices * kWave) {
         why = "slice arrays disagree in size";
         return false;
     }
     for (const SubDesc &sd : S.sub) {
-        const size_t need = (size_t)sd.wave_ptr0 + (size_t)sd.n_levels * S.nw + 1;
-        if (sd.wave_ptr0 < 0 || need > S.wave_ptr.size()) { why = "wave_ptr range"; return false; }
-        for (int32_t l = 0; l < sd.n_levels; ++l)
-            for (int wv = 0; wv < S.nw; ++wv) {
-                const int32_t s0 = S.wave_ptr[(size_t)sd.wave_ptr0 + l * S.nw + wv];
-                const int32_t s1 = S.wave_ptr[(size_t)sd.wave_ptr0 + l * S.nw + wv + 1];
-                if (s0 < 0 || s1 < s0 || (size_t)s1 > n_slices) { why = "slice range"; return false; }
-                for (int32_t s = s0; s < s1; ++s) {
-                    const int32_t trip = S.slice_trip[s];
-                    if (trip < 0 || trip > kChunk) { why = "trip count"; return false; }
-                    if (S.slice_arc[s] < 0 || (size_t)S.slice_arc[s] + (size_t)trip * kWave > S.arcs.size()) {
-                        why = "arc range";
-                        return false;
-                    }
-                    const int32_t src_lim = l == 0 ? sd.K : sd.n_part;
-                    for (size_t a = (size_t)S.slice_arc[s]; a < (size_t)S.slice_arc[s] + (size_t)trip * kWave; ++a)
-                        if (S.arcs[a].src < 0 || S.arcs[a].src >= std::max(src_lim, 1)) { why = "arc source"; return false; }
-                    for (int lane = 0; lane < kWave; ++lane) {
-                        const int32_t o = S.row_out[(size_t)s * kWave + lane], v = S.row_vidx[(size_t)s * kWave + lane];
-                        if (o >= (n_out < 0 ? sd.K : n_out) || (o < -1 && -2 - o >= sd.n_part)) { why = "row target"; return false; }
-                        if (v < 0 || v >= std::max(n_vidx < 0 ? sd.K : n_vidx, 1)) { why = "emission index"; return false; }
-                    }
+        if (sd.wave_ptr0 < 0 || (size_t)sd.wave_ptr0 + (size_t)S.nw + 1 > S.wave_ptr.size()) { why = "wave_ptr range"; return false; }
+        if (sd.clone0 < 0 || sd.n_cdesc < 0 || (size_t)sd.clone0 + (size_t)sd.n_cdesc > S.clones.size()) { why = "clone range"; return false; }
+        if (sd.zero0 < 0 || sd.n_zero < 0 || (size_t)sd.zero0 + (size_t)sd.n_zero > S.zero_rows.size()) { why = "zero-row range"; return false; }
+        for (int32_t c = 0; c < sd.n_cdesc; ++c) {
+            const CloneDesc &cd = S.clones[(size_t)sd.clone0 + c];
+            if (cd.state < 0 || cd.state >= sd.K || cd.first < 0 || cd.count < 1 || cd.first + cd.count > sd.n_slot) { why = "clone entry"; return false; }
+        }
+        for (int32_t z = 0; z < sd.n_zero; ++z)
+            if (S.zero_rows[(size_t)sd.zero0 + z] < 0 || S.zero_rows[(size_t)sd.zero0 + z] >= sd.K) { why = "zero row"; return false; }
+        const int32_t n_idx = sd.K + sd.n_slot;
+        for (int wv = 0; wv < S.nw; ++wv) {
+            const int32_t s0 = S.wave_ptr[(size_t)sd.wave_ptr0 + wv], s1 = S.wave_ptr[(size_t)sd.wave_ptr0 + wv + 1];
+            if (s0 < 0 || s1 < s0 || (size_t)s1 > n_slices) { why = "slice range"; return false; }
+            for (int32_t s = s0; s < s1; ++s) {
+                const int32_t trip = S.slice_trip[s];
+                if (trip < 1) { why = "trip count"; return false; }
+                if (S.slice_lg[s] < 0 || S.slice_lg[s] > 6) { why = "lanes per row"; return false; }
+                if (S.slice_arc[s] < 0 || (size_t)S.slice_arc[s] + (size_t)trip * kWave > S.arcs.size()) { why = "arc range"; return false; }
+                for (size_t a = (size_t)S.slice_arc[s]; a < (size_t)S.slice_arc[s] + (size_t)trip * kWave; ++a)
+                    if (S.arcs[a].src < 0 || S.arcs[a].src >= n_idx) { why = "arc source"; return false; }
+                for (int lane = 0; lane < kWave; ++lane) {
+                    const int32_t o = S.row_out[(size_t)s * kWave + lane], v = S.row_vidx[(size_t)s * kWave + lane];
+                    if (o < -1 || o >= n_idx) { why = "row target"; return false; }
+                    if (v < -1 || v >= std::max(n_vidx < 0 ? sd.K : n_vidx, 1)) { why = "emission index"; return false; }
+                    if (o >= 0 && v < 0) { why = "row without emission index"; return false; }
                 }
             }
+        }
     }
     return true;
-}
-
-// The schedule of sub-graph `sub` applied on the host in double precision, in the
-// log semifield (log_semiring) or in ordinary arithmetic: y[out] for every final
-// row, exactly as the kernels walk it (levels, slices, lanes), without the
-// emission / offset step.  y must hold n_out doubles and is pre-filled by the caller.
-void sell_apply_host(const SellHost &S, int32_t sub, bool log_semiring, const double *x, double *y)
-{
-    const SubDesc &sd = S.sub[(size_t)sub];
-    std::vector<double> part((size_t)std::max(sd.n_part, 1), 0.0);
-    for (int32_t l = 0; l < sd.n_levels; ++l) {
-        const double *v = l == 0 ? x : part.data();
-        std::vector<std::pair<int32_t, double>> writes;   // a level reads partials of the previous one only
-        for (int wv = 0; wv < S.nw; ++wv) {
-            const int32_t s0 = S.wave_ptr[(size_t)sd.wave_ptr0 + l * S.nw + wv];
-            const int32_t s1 = S.wave_ptr[(size_t)sd.wave_ptr0 + l * S.nw + wv + 1];
-            for (int32_t s = s0; s < s1; ++s)
-                for (int lane = 0; lane < kWave; ++lane) {
-                    const int32_t o = S.row_out[(size_t)s * kWave + lane];
-                    if (o == -1) continue;
-                    double m = -INFINITY, acc = 0.0;
-                    for (int32_t it = 0; it < S.slice_trip[s]; ++it) {
-                        const Arc &a = S.arcs[(size_t)S.slice_arc[s] + (size_t)it * kWave + lane];
-                        if (log_semiring) m = std::max(m, (double)a.w + v[a.src]);
-                        else acc += (double)a.w * v[a.src];
-                    }
-                    if (log_semiring) {
-                        if (m == -INFINITY) acc = -INFINITY;
-                        else {
-                            for (int32_t it = 0; it < S.slice_trip[s]; ++it) {
-                                const Arc &a = S.arcs[(size_t)S.slice_arc[s] + (size_t)it * kWave + lane];
-                                acc += std::exp2((double)a.w + v[a.src] - m);
-                            }
-                            acc = m + std::log2(acc);
-                        }
-                    }
-                    if (o >= 0) y[o] = acc;
-                    else writes.emplace_back(-2 - o, acc);
-                }
-        }
-        for (auto &wr : writes) part[(size_t)wr.first] = wr.second;
-    }
 }
 
 }  // namespace fb

@@ -51,13 +51,16 @@ bool stream_from_sell(const SellHost &S, int32_t Kcap, int32_t Ecap, StreamHost 
 {
     out.nw = S.nw;
     out.Kcap = Kcap;
-    out.Pcap = S.max_part;
+    out.Ccap = S.max_slot;
     out.Ecap = Ecap;
-    if ((int64_t)Kcap + S.max_part + 1 > 0xffff || Ecap + 1 > 0xffff) {
-        why = "states plus partial slots, or emission entries, beyond 16 bits";
+    out.clones = S.clones;
+    out.zero_rows = S.zero_rows;
+    if ((int64_t)Kcap + S.max_slot + 1 > 0xffff || Ecap + 1 > 0xffff) {
+        why = "states plus clone slots, or emission entries, beyond 16 bits";
         return false;
     }
-    const uint32_t idle_info = (uint32_t)(Kcap + S.max_part) | ((uint32_t)Ecap << 16);
+    const uint32_t dump = (uint32_t)(Kcap + S.max_slot);
+    const uint32_t idle_info = dump | ((uint32_t)Ecap << 16);
     const Arc pad_arc{0, -INFINITY};
     for (const SubDesc &ssd : S.sub) {
         SubDesc sd = ssd;
@@ -67,38 +70,33 @@ bool stream_from_sell(const SellHost &S, int32_t Kcap, int32_t Ecap, StreamHost 
             wd.arc_base = (int64_t)out.arcs.size();
             std::vector<uint8_t> flags;   // one per batch
             std::vector<Arc> lin;         // the wave's rows in order, 64 entries each
-            auto pad_batch = [&](uint8_t f) {   // three zero-weight arcs and an info row that goes to the dump slot
+            auto pad_batch = [&]() {   // three zero-weight arcs and an info row that goes to the dump slot
                 for (int e = 0; e < (kBatchRows - 1) * kWave; ++e) lin.push_back(pad_arc);
                 for (int lane = 0; lane < kWave; ++lane) lin.push_back(Arc{0, bits_to_float(idle_info)});
-                flags.push_back((uint8_t)(f | kFlagInfo | kFlagSkip));
+                flags.push_back((uint8_t)(kFlagInfo | kFlagSkip));
             };
-            for (int32_t l = 0; l < ssd.n_levels; ++l) {
-                const int32_t s0 = S.wave_ptr[(size_t)ssd.wave_ptr0 + l * S.nw + wv];
-                const int32_t s1 = S.wave_ptr[(size_t)ssd.wave_ptr0 + l * S.nw + wv + 1];
-                const size_t first_flag = flags.size();
-                for (int32_t s = s0; s < s1; ++s) {
-                    const int32_t trip = S.slice_trip[s];
-                    int32_t rows = 0;
-                    for (int32_t it = 0; it < trip; ++it, ++rows)
-                        for (int lane = 0; lane < kWave; ++lane)
-                            lin.push_back(S.arcs[(size_t)S.slice_arc[s] + (size_t)it * kWave + lane]);
-                    for (; rows % kBatchRows != kBatchRows - 1; ++rows)   // the info row closes a batch
-                        for (int lane = 0; lane < kWave; ++lane) lin.push_back(pad_arc);
-                    for (int lane = 0; lane < kWave; ++lane) {
-                        const int32_t o = S.row_out[(size_t)s * kWave + lane], v = S.row_vidx[(size_t)s * kWave + lane];
-                        uint32_t info = idle_info;
-                        if (o >= 0) info = (uint32_t)o | ((uint32_t)v << 16);
-                        else if (o < -1) info = (uint32_t)(Kcap + (-2 - o)) | ((uint32_t)Ecap << 16);   // partial: no emission
-                        lin.push_back(Arc{0, bits_to_float(info)});
-                    }
-                    ++rows;
-                    for (int32_t bt = 0; bt < rows / kBatchRows; ++bt)
-                        flags.push_back(bt + 1 == rows / kBatchRows ? (uint8_t)kFlagInfo : (uint8_t)0);
+            const int32_t s0 = S.wave_ptr[(size_t)ssd.wave_ptr0 + wv], s1 = S.wave_ptr[(size_t)ssd.wave_ptr0 + wv + 1];
+            for (int32_t s = s0; s < s1; ++s) {
+                const int32_t trip = S.slice_trip[s];
+                int32_t rows = 0;
+                for (int32_t it = 0; it < trip; ++it, ++rows)
+                    for (int lane = 0; lane < kWave; ++lane)
+                        lin.push_back(S.arcs[(size_t)S.slice_arc[s] + (size_t)it * kWave + lane]);
+                for (; rows % kBatchRows != kBatchRows - 1; ++rows)   // the info row closes a batch
+                    for (int lane = 0; lane < kWave; ++lane) lin.push_back(pad_arc);
+                for (int lane = 0; lane < kWave; ++lane) {
+                    const int32_t o = S.row_out[(size_t)s * kWave + lane], v = S.row_vidx[(size_t)s * kWave + lane];
+                    // a lane that shares a row without writing it still takes the row's emission: all lanes
+                    // of a row then hold the same value, which keeps the step maximum exact
+                    const uint32_t tgt = o < 0 ? dump : (o < ssd.K ? (uint32_t)o : (uint32_t)(Kcap + (o - ssd.K)));
+                    lin.push_back(Arc{0, bits_to_float(tgt | ((uint32_t)(v < 0 ? Ecap : v) << 16))});
                 }
-                if (flags.size() == first_flag) pad_batch(0);   // a wave without work here still carries the barrier
-                if (l + 1 < ssd.n_levels) flags.back() |= (uint8_t)kFlagLevelEnd;
+                ++rows;
+                for (int32_t bt = 0; bt < rows / kBatchRows; ++bt)
+                    flags.push_back(bt + 1 == rows / kBatchRows
+                                        ? (uint8_t)(kFlagInfo | ((uint32_t)S.slice_lg[s] << kFlagLgShift)) : (uint8_t)0);
             }
-            while (flags.size() < (size_t)kResident || (flags.size() - kResident) % kRing) pad_batch(0);   // whole iterations
+            while (flags.size() < (size_t)kResident || (flags.size() - kResident) % kRing) pad_batch();   // whole iterations
             if ((flags.size() - kResident) / kRing > 2 * kWave) {
                 why = "more than " + std::to_string(2 * kWave * kRing * kBatchRows * kWave) + " arcs per wave and time step";
                 return false;
@@ -134,7 +132,15 @@ bool stream_in_bounds(const StreamHost &S, int32_t n_vidx, std::string &why)
 {
     for (const SubDesc &sd : S.sub) {
         if (sd.wave_ptr0 < 0 || (size_t)sd.wave_ptr0 + S.nw > S.waves.size()) { why = "wave table range"; return false; }
-        if (sd.K > S.Kcap || sd.n_part > S.Pcap) { why = "index space"; return false; }
+        if (sd.K > S.Kcap || sd.n_slot > S.Ccap) { why = "index space"; return false; }
+        if (sd.clone0 < 0 || sd.n_cdesc < 0 || (size_t)sd.clone0 + (size_t)sd.n_cdesc > S.clones.size()) { why = "clone range"; return false; }
+        if (sd.zero0 < 0 || sd.n_zero < 0 || (size_t)sd.zero0 + (size_t)sd.n_zero > S.zero_rows.size()) { why = "zero-row range"; return false; }
+        for (int32_t c = 0; c < sd.n_cdesc; ++c) {
+            const CloneDesc &cd = S.clones[(size_t)sd.clone0 + c];
+            if (cd.state < 0 || cd.state >= sd.K || cd.first < 0 || cd.count < 1 || cd.first + cd.count > sd.n_slot) { why = "clone entry"; return false; }
+        }
+        for (int32_t z = 0; z < sd.n_zero; ++z)
+            if (S.zero_rows[(size_t)sd.zero0 + z] < 0 || S.zero_rows[(size_t)sd.zero0 + z] >= sd.K) { why = "zero row"; return false; }
         for (int wv = 0; wv < S.nw; ++wv) {
             const WaveDesc &wd = S.waves[(size_t)sd.wave_ptr0 + wv];
             if (wd.n_iter < 0 || wd.n_iter > 2 * kWave || wd.flag_base < 0 ||
@@ -147,80 +153,87 @@ bool stream_in_bounds(const StreamHost &S, int32_t n_vidx, std::string &why)
                 why = "stream range";
                 return false;
             }
-            int32_t level = 0;
             for (size_t bt = 0; bt < n_batches; ++bt) {
                 const uint32_t f = batch_flags(S, wd, bt);
+                if (((f >> kFlagLgShift) & 7u) > 6u) { why = "lanes per row"; return false; }
                 for (int r = 0; r < kBatchRows; ++r)
                     for (int lane = 0; lane < kWave; ++lane) {
                         const Arc &a = S.arcs[(size_t)wd.arc_base + entry_at(bt, r, lane)];
                         // every row is gathered, info rows included: src must always be safe
-                        const int32_t lim = level == 0 ? sd.K : std::max(sd.n_part, 1);
-                        if (a.src < 0 || a.src >= lim) { why = "arc source"; return false; }
+                        if (a.src < 0 || a.src >= sd.K + sd.n_slot) { why = "arc source"; return false; }
                         if (r == kBatchRows - 1 && (f & kFlagInfo)) {
                             const uint32_t u = float_to_bits(a.w);
                             const int32_t t = (int32_t)(u & 0xffff), v = (int32_t)(u >> 16);
-                            const bool state = t < sd.K, slot = t >= S.Kcap && t < S.Kcap + sd.n_part;
-                            const bool dump = t == S.Kcap + S.Pcap;
+                            const bool state = t < sd.K, slot = t >= S.Kcap && t < S.Kcap + sd.n_slot;
+                            const bool dump = t == S.Kcap + S.Ccap;
                             if (!state && !slot && !dump) { why = "row target"; return false; }
                             if (v != S.Ecap && v >= (n_vidx < 0 ? sd.K : n_vidx)) { why = "emission index"; return false; }
-                            if (!state && v != S.Ecap) { why = "emission on a partial row"; return false; }
                         } else if (!(a.w <= 0.0f) && !(a.w > 0.0f)) {
                             why = "NaN weight";
                             return false;
                         }
                     }
-                if (f & kFlagLevelEnd) ++level;
             }
-            if (level != std::max(sd.n_levels, 1) - 1) { why = "barrier count"; return false; }
-            if (batch_flags(S, wd, n_batches - 1) & kFlagLevelEnd) { why = "barrier on the last batch"; return false; }
         }
     }
     return true;
 }
 
-// The streams of sub-graph `sub` interpreted on the host in double precision,
-// level by level as the kernel does between barriers: y[state] for every row that
-// targets a state (before emission and offset are applied).
+// The streams of sub-graph `sub` interpreted on the host in double precision as the kernel
+// does (lanes, groups of lanes, clones): y[state] for every state, before emission and offset
+// are applied; x holds one value per state.
 void stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double *y)
 {
     const SubDesc &sd = S.sub[(size_t)sub];
-    std::vector<double> part((size_t)std::max(sd.n_part, 1), 0.0);
-    std::vector<size_t> at((size_t)S.nw, 0);   // next batch of every wave
-    for (int32_t l = 0; l < std::max(sd.n_levels, 1); ++l) {
-        const double *v = l == 0 ? x : part.data();
-        std::vector<std::pair<int32_t, double>> writes;
-        for (int wv = 0; wv < S.nw; ++wv) {
-            const WaveDesc &wd = S.waves[(size_t)sd.wave_ptr0 + wv];
-            const size_t n_batches = wave_batches(wd);
-            std::vector<std::vector<double>> terms(kWave);   // running (+)-sum of every lane, kept as its terms
-            while (at[wv] < n_batches) {
-                const size_t bt = at[wv]++;
-                const uint32_t f = batch_flags(S, wd, bt);
-                if (!(f & kFlagSkip))
-                    for (int r = 0; r < kBatchRows; ++r)
-                        for (int lane = 0; lane < kWave; ++lane) {
-                            const Arc &a = S.arcs[(size_t)wd.arc_base + entry_at(bt, r, lane)];
-                            if (!(r == kBatchRows - 1 && (f & kFlagInfo))) {
-                                terms[lane].push_back((double)a.w + v[a.src]);
-                                continue;
-                            }
-                            double m = -INFINITY, acc = 0.0;
-                            for (double t : terms[lane]) m = std::max(m, t);
-                            if (m == -INFINITY) acc = -INFINITY;
-                            else {
-                                for (double t : terms[lane]) acc += std::exp2(t - m);
-                                acc = m + std::log2(acc);
-                            }
-                            terms[lane].clear();
-                            const int32_t t = (int32_t)(float_to_bits(a.w) & 0xffff);
-                            if (t < sd.K) y[t] = acc;
-                            else if (t < S.Kcap + S.Pcap) writes.emplace_back(t - S.Kcap, acc);
-                        }
-                if (f & kFlagLevelEnd) break;
-            }
+    // the vector the rows gather from: a cloned state's value sits in the state itself, its clones hold zero
+    std::vector<double> xe(x, x + sd.K);
+    xe.resize((size_t)sd.K + (size_t)sd.n_slot, -INFINITY);
+    std::vector<double> ye((size_t)sd.K + (size_t)sd.n_slot, -INFINITY);
+    auto lse = [](const std::vector<double> &t) {
+        double m = -INFINITY, acc = 0.0;
+        for (double v : t) m = std::max(m, v);
+        if (m == -INFINITY) return m;
+        for (double v : t) acc += std::exp2(v - m);
+        return m + std::log2(acc);
+    };
+    for (int wv = 0; wv < S.nw; ++wv) {
+        const WaveDesc &wd = S.waves[(size_t)sd.wave_ptr0 + wv];
+        const size_t n_batches = wave_batches(wd);
+        std::vector<std::vector<double>> terms(kWave);   // running (+)-sum of every lane, kept as its terms
+        for (size_t bt = 0; bt < n_batches; ++bt) {
+            const uint32_t f = batch_flags(S, wd, bt);
+            if (f & kFlagSkip) continue;
+            const int g = 1 << ((f >> kFlagLgShift) & 7u);
+            for (int r = 0; r < kBatchRows; ++r)
+                for (int lane = 0; lane < kWave; ++lane) {
+                    const Arc &a = S.arcs[(size_t)wd.arc_base + entry_at(bt, r, lane)];
+                    if (!(r == kBatchRows - 1 && (f & kFlagInfo))) {
+                        terms[lane].push_back((double)a.w + xe[(size_t)a.src]);
+                        continue;
+                    }
+                    if (lane % g == 0) {   // the row's lanes are complete: the info row is the batch's last
+                        std::vector<double> all;
+                        for (int t = 0; t < g; ++t) all.insert(all.end(), terms[lane + t].begin(), terms[lane + t].end());
+                        for (int t = 0; t < g; ++t) terms[lane + t].assign(1, lse(all));   // every lane of the row holds the total
+                    }
+                }
+            if (f & kFlagInfo)
+                for (int lane = 0; lane < kWave; ++lane) {
+                    const Arc &a = S.arcs[(size_t)wd.arc_base + entry_at(bt, kBatchRows - 1, lane)];
+                    const int32_t t = (int32_t)(float_to_bits(a.w) & 0xffff);
+                    if (t < sd.K) ye[(size_t)t] = terms[lane][0];
+                    else if (t < S.Kcap + sd.n_slot) ye[(size_t)sd.K + (size_t)(t - S.Kcap)] = terms[lane][0];
+                    terms[lane].clear();
+                }
         }
-        for (auto &wr : writes) part[(size_t)wr.first] = wr.second;
     }
+    for (int32_t c = 0; c < sd.n_cdesc; ++c) {   // a cloned state is the (+)-sum of its clones
+        const CloneDesc &cd = S.clones[(size_t)sd.clone0 + c];
+        std::vector<double> all{ye[(size_t)cd.state]};
+        for (int32_t i = 0; i < cd.count; ++i) all.push_back(ye[(size_t)sd.K + (size_t)cd.first + i]);
+        ye[(size_t)cd.state] = lse(all);
+    }
+    for (int32_t k = 0; k < sd.K; ++k) y[k] = ye[(size_t)k];
 }
 
 }  // namespace fb

@@ -68,11 +68,13 @@ def _direct_product(K, rows, cols, w2, x):
     return y
 
 
-@pytest.mark.parametrize("case", ["zipf_hubs", "uniform", "chains"])
+@pytest.mark.parametrize("case", ["zipf_hubs", "zipf_clones", "uniform", "chains"])
 def test_kernel_schedule_computes_the_sparse_products(case):
     rng = np.random.default_rng(5)
-    if case == "zipf_hubs":          # hub rows are split over several levels
+    if case == "zipf_hubs":          # hub rows are spread over 2 ... 64 lanes
         w = wl.config4(K=900, B=2, Nmin=3, Nmax=4, D=64); g = w.den
+    elif case == "zipf_clones":      # the largest hubs are too long for one slice and get clones
+        w = wl.config4(K=3500, B=2, Nmin=3, Nmax=4, D=64); g = w.den
     elif case == "uniform":
         w = wl.config3(K=300, B=2, N=3, D=20); g = w.den
     else:
@@ -100,9 +102,11 @@ def test_kernel_schedule_computes_the_sparse_products(case):
     h.destroy()
 
 
-def test_hub_graph_really_has_split_rows():
+def test_hub_graphs_really_have_long_rows():
     w = wl.config4(K=900, B=2, Nmin=3, Nmax=4, D=64)
-    assert np.bincount(w.den.dst, minlength=900).max() > 32 * 32     # at least three levels
+    assert np.bincount(w.den.dst, minlength=900).max() > 32 * 32     # a row spread over all 64 lanes
+    w = wl.config4(K=3500, B=2, Nmin=3, Nmax=4, D=64)
+    assert np.bincount(w.den.dst, minlength=3500).max() > 2 * 64 * 32   # a row with at least two clones
 
 
 def _raises(code, fn, *a, **k):
