@@ -96,6 +96,10 @@ int run_posteriors(const PostGraph *gs, int n_graph, const int32_t *lengths, int
     p.B = B; p.N = N; p.D = D;
     p.pdf_out = pdf_out;
     p.frames_per_block = 8;
+    if (gradient_kernel_applies(p)) {   // shared float denominator + small packed numerators: the specialised kernel
+        const size_t glds = gradient_lds_bytes(p);
+        if (glds <= kLdsBytes) return launch_gradient(p, glds, stream);
+    }
     const size_t lds = posterior_lds_bytes(p);
     if (lds > kLdsBytes) return fail(FB_EUNSUPPORTED, "state vector, pdf row and pdf tables exceed the on-chip memory");
     return launch_posteriors(p, lds, stream);

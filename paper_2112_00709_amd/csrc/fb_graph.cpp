@@ -62,6 +62,7 @@ int upload_pdf(fb_graph *g, const PdfHost &h, PdfDev &d)
     if ((rc = upload(g, h.sub, &d.sub))) return rc;
     if ((rc = upload(g, h.row_pdf, &d.row_pdf))) return rc;
     if ((rc = upload(g, h.row_ptr, &d.row_ptr))) return rc;
+    if ((rc = upload(g, h.pos, &d.pos))) return rc;
     return upload(g, h.states, &d.states);
 }
 
@@ -244,6 +245,8 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
                 }
                 PH.row_ptr.push_back((uint16_t)Ks);
                 for (int32_t i = 0; i < Ks; ++i) PH.states.push_back((uint16_t)L.pdf_states[(size_t)i]);
+                PH.pos.resize((size_t)Ks);
+                for (int32_t i = 0; i < Ks; ++i) PH.pos[(size_t)L.pdf_states[(size_t)i]] = (uint16_t)i;
                 ps.n_rows = D;
             } else {
                 std::vector<int32_t> order((size_t)Ks);

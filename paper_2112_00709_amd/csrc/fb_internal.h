@@ -147,12 +147,13 @@ struct PdfSub {
 struct PdfHost {
     std::vector<PdfSub> sub;
     std::vector<uint16_t> row_pdf, row_ptr, states;
+    std::vector<uint16_t> pos;   // shared graph only: pos[k] = place of state k in `states` (its inverse)
     int32_t max_rows = 0;
 };
 
 struct PdfDev {
     const PdfSub *sub = nullptr;
-    const uint16_t *row_pdf = nullptr, *row_ptr = nullptr, *states = nullptr;
+    const uint16_t *row_pdf = nullptr, *row_ptr = nullptr, *states = nullptr, *pos = nullptr;
 };
 
 struct HostLayout {                   // the graph-layout step, kept for fb_graph_layout
@@ -234,6 +235,9 @@ struct PostParams {
 
 int launch_recursion(int nw, bool f64, const RecParams &p, size_t lds_bytes, void *stream);
 int launch_posteriors(const PostParams &p, size_t lds_bytes, void *stream);
+bool gradient_kernel_applies(const PostParams &p);
+size_t gradient_lds_bytes(const PostParams &p);
+int launch_gradient(const PostParams &p, size_t lds_bytes, void *stream);
 int launch_loss(const double *logz_num, const double *logz_den, const int32_t *lengths, int32_t B, double *loss,
                 void *stream);
 size_t recursion_lds_bytes(int32_t Kcap, int32_t Ccap, int32_t Ecap, bool backward, bool f64, bool shared);
