@@ -27,11 +27,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
+# transcendental issue rate: 256 CUs x 64 lanes x 2.4 GHz at a quarter of the plain fp32 rate
+EXP_PEAK_PER_S = 256 * 64 * 2.4e9 / 4
 
 # HBM bytes per denominator-recursion launch on configuration 5 from rocprofv3 --pmc
 # (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on a plain copy kernel);
 # see profiles/.  None until measured for the workload being run.
-MEASURED_TRAFFIC_BYTES = {"config5": 522900 * 1024 * 2.00 + 2071000 * 1024 * 1.00}
+MEASURED_TRAFFIC_BYTES = {"config5": 522200 * 1024 * 2.00 + 2072000 * 1024 * 1.00}
 
 
 def log(*a):
@@ -128,6 +130,10 @@ def main() -> int:
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes": algo_bytes, "launch_ms": stage_ms["den_recursion"]},
+        # the bound that applies to that launch: one exponential per arc-update on the quarter-rate unit
+        "roofline_alu": {"bound": "alu", "achieved": upd_den / (stage_ms["den_recursion"] * 1e-3) / 1e12,
+                         "peak": EXP_PEAK_PER_S / 1e12, "unit": "T exp/s (one per arc-update)",
+                         "frac": upd_den / (stage_ms["den_recursion"] * 1e-3) / EXP_PEAK_PER_S},
     }
 
     if args.calibrate_copy:
