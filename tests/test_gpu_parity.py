@@ -185,7 +185,7 @@ def test_config3_full(fb):
 
 
 def test_config4_scaled(fb):
-    """Full 6000-state hub graph (rows split over three levels), small ragged batch."""
+    """Full 6000-state hub graph (rows spread over up to 64 lanes, the largest hubs cloned), small ragged batch."""
     w = wl.config4(B=6, Nmin=20, Nmax=60)
     compare_fb(fb, w.den, w.D, w.emis, w.lengths, name="config4-scaled")
 
@@ -227,6 +227,42 @@ def test_carrier_precision_can_be_forced(fb):
     # state (that is why small graphs default to double): sane, but only to 1e-4
     compare_fb(fb, c.num, c.D, c.emis, c.lengths, name="config2 narrow state", state="narrow", post_tol=1e-4)
     compare_fb(fb, c.num, c.D, c.emis, c.lengths, name="config2 wide state", state="wide")
+
+
+def test_cloned_hub_rows_small(fb):
+    """A 3500-state hub graph whose largest in-degree needs clones, every sequence checked in full."""
+    w = wl.config4(K=3500, B=3, Nmin=10, Nmax=25, D=300)
+    assert np.bincount(w.den.dst, minlength=3500).max() > 2 * 64 * 32
+    compare_fb(fb, w.den, w.D, w.emis, w.lengths, name="config4 K=3500 (cloned hubs)")
+
+
+def test_gradient_kernel_paths(fb):
+    """lfmmi_loss_grad through the specialised gradient kernel (denominator states a multiple of 4) and through
+    the general posterior kernel (any other state count), both against the oracle."""
+    compare_lfmmi(fb, wl.config5(K=800, B=5, Lmin=3, Lmax=9, D=120), name="lfmmi, K=800 (specialised kernel)")
+    compare_lfmmi(fb, wl.config5(K=798, B=5, Lmin=3, Lmax=9, D=120), name="lfmmi, K=798 (general kernel)")
+    compare_lfmmi(fb, wl.config5(K=1000, B=4, Lmin=3, Lmax=9, D=50), name="lfmmi, D=50 (fewer pdfs than threads)")
+
+
+def test_lfmmi_with_an_infeasible_numerator(fb):
+    """A numerator chain longer than its utterance: log Z_num = -inf, its pdf posteriors are 0, the gradient of that
+    utterance is minus the denominator's pdf posteriors, nothing is NaN."""
+    import torch
+    w = wl.config5(K=400, B=4, Lmin=3, Lmax=6, D=60)
+    lengths = w.lengths.copy()
+    lengths[1] = 4                                   # 3 states per phone, at least 3 phones: cannot finish
+    ref = oracle.lfmmi(w.den, w.num, w.emis, lengths)
+    Gd, Gn = fb.graph_from(w.den, w.D), fb.graph_from(w.num, w.D)
+    loss, zn, zd, grad = fb.lfmmi_loss_grad(Gd, Gn, dev(w.emis), dev(lengths.astype(np.int32)))
+    torch.cuda.synchronize()
+    zn, zd, grad = host(zn), host(zd), host(grad)
+    assert np.isneginf(zn[1]) and np.isneginf(ref.logz_num[1]) and np.isfinite(zd).all()
+    assert not np.isnan(grad).any()
+    for b in range(w.B):
+        assert np.abs(grad[b] - ref.grad[b]).max() <= TOL_POST_ABS
+    np.testing.assert_allclose(grad[1, :4].sum(axis=1), -1.0, atol=2e-5)
+    assert np.isneginf(float(host(loss)[0]))
+    Gd.destroy(); Gn.destroy()
 
 
 # ------------------------------------------------------------------ edge cases
