@@ -40,6 +40,60 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def context_workloads(fb, wl, torch):
+    """fb_alpha + fb_beta + fb_posteriors (three calls, vectors through HBM) on the other workloads."""
+    out = {}
+    side = torch.cuda.Stream()   # one for all workloads: the box has few hardware queues to map streams onto
+    for name, make in (("config1", wl.config1), ("config2", wl.config2), ("config3", wl.config3),
+                       ("config4", wl.config4), ("paper_shape_den", wl.paper_shape_den)):
+        w = make()
+        g = w.num if w.den is None else w.den
+        t0 = time.time()
+        G = fb.graph_from(g, w.D)
+        create_s = time.time() - t0
+        emis = torch.from_numpy(w.emis).cuda()
+        lengths = torch.from_numpy(w.lengths).cuda()
+
+        def run():   # the two recursions are independent: one on a second stream, as a caller would run them
+            main = torch.cuda.current_stream()
+            side.wait_stream(main)
+            a, _, _ = fb.fb_alpha(G, emis, lengths)
+            with torch.cuda.stream(side):
+                b_, _, _ = fb.fb_beta(G, emis, lengths)
+            main.wait_stream(side)
+            b_.record_stream(main)
+            fb.fb_posteriors(G, a, b_, lengths, w.B, w.N, want_state=False)
+
+        for _ in range(2):
+            run()
+        torch.cuda.synchronize()
+        n = 5
+        t0 = time.perf_counter()
+        for _ in range(n):
+            run()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / n
+        upd = w.arc_updates(g)
+        frames = int(w.lengths.sum())
+        if g.packed:
+            k_frames = int(np.sum(w.lengths.astype(np.int64) * np.diff(g.state_off)))   # sum_b N_b K_b
+            d_frames = k_frames                                                            # at most one pdf per state
+        else:
+            k_frames, d_frames = frames * g.K, frames * int(np.unique(g.pdf).size)
+        # compulsory bytes: alpha and beta each read the used emissions and write the vector; the posteriors
+        # read both vectors and write one pdf row per frame
+        algo = 2 * (4 * d_frames + 4 * k_frames) + 8 * k_frames + 4 * frames * w.D
+        out[name] = {"B": w.B, "N_max": w.N, "K": g.K, "E": g.E, "D": w.D, "ms": ms, "arc_updates": upd,
+                     "arc_updates_per_s": upd / (ms * 1e-3), "algorithmic_bytes": algo,
+                     "hbm_frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "graph_create_s": create_s}
+        if name == "paper_shape_den":   # Table 1: 1.04 s for the denominator forward-backward on an RTX 2080 Ti
+            out[name]["paper_table1_s"] = 1.04
+        log(f"[bench] {name}: {ms:.3f} ms, {upd / (ms * 1e-3):.3e} arc-updates/s, HBM fraction {out[name]['hbm_frac']:.3f}")
+        G.destroy()
+        del emis
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -48,6 +102,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=5, choices=[5], help="workload (configuration 5 is the benchmark)")
     ap.add_argument("--cpu-sample", type=int, default=0, help="sequences the CPU oracle is timed on (0 = 2 per thread)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--context", action="store_true",
+                    help="also time fb_alpha + fb_beta + fb_posteriors on configurations 1-4 and on the paper-shaped "
+                         "denominator (context figures, added to the JSON line as other_workloads)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -71,7 +128,8 @@ def main() -> int:
         f"den K={w.den.K} E={w.den.E}; num K={w.num.K} E={w.num.E}; frames={int(w.lengths.sum())}")
     t0 = time.time()
     den, num = fb.graph_from(w.den, w.D), fb.graph_from(w.num, w.D)
-    log(f"[bench] graph layout + schedules + upload: {time.time() - t0:.3f}s (not part of a step)")
+    graph_create_s = time.time() - t0
+    log(f"[bench] graph layout + schedules + upload: {graph_create_s:.3f}s (not part of a step)")
     emis = torch.from_numpy(w.emis).cuda()
     lengths = torch.from_numpy(w.lengths).cuda()
     ws = torch.empty((fb.fb_lfmmi_workspace_bytes(den, num, w.B, w.N, w.D),), dtype=torch.uint8, device="cuda")
@@ -90,6 +148,12 @@ def main() -> int:
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     loss = float(out[0].item())
+    # the same step timed one at a time (events on the launching stream): median and minimum
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for e0, e1 in evs:
+        e0.record(); step(); e1.record()
+    torch.cuda.synchronize()
+    single = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
 
     # stage times with HIP events recorded by the library on the launching stream
     fb.fb_profile_enable(True)
@@ -122,6 +186,8 @@ def main() -> int:
                    "B": w.B, "N_max": w.N, "frames": frames, "D": w.D,
                    "den_states": w.den.K, "den_arcs": w.den.E, "num_states": w.num.K, "num_arcs": w.num.E},
         "lfmmi_ms_per_batch": ms_per_step,
+        "ms_per_step_median": single[len(single) // 2], "ms_per_step_min": single[0],
+        "graph_create_s": graph_create_s,
         "arc_updates_per_step": arc_updates,
         "arc_updates_padded": 2 * w.B * w.N * w.den.E,
         "stage_ms": stage_ms,
@@ -135,6 +201,9 @@ def main() -> int:
                          "peak": EXP_PEAK_PER_S / 1e12, "unit": "T exp/s (one per arc-update)",
                          "frac": upd_den / (stage_ms["den_recursion"] * 1e-3) / EXP_PEAK_PER_S},
     }
+
+    if args.context:
+        result["other_workloads"] = context_workloads(fb, wl, torch)
 
     if args.calibrate_copy:
         src = torch.empty((1 << 28,), dtype=torch.float32, device="cuda").fill_(1.0)
@@ -154,10 +223,20 @@ def main() -> int:
         t0 = time.perf_counter()
         oracle.lfmmi(w.den, w.num, w.emis, w.lengths, sel=sel)
         dt = time.perf_counter() - t0
+        # one utterance of median length on one thread (the single-thread reference figure)
+        mid = np.array([int(order[w.B // 2])])
+        mid_updates = int(2 * w.lengths[mid[0]] * (w.den.E + w.num.arcs_per_seq(w.B)[mid[0]]))
+        oracle.set_num_threads(1)
+        t1 = time.perf_counter()
+        oracle.lfmmi(w.den, w.num, w.emis, w.lengths, sel=mid)
+        dt1 = time.perf_counter() - t1
+        oracle.set_num_threads(threads)
         result["cpu_baseline"] = {
             "value": sample_updates / dt, "unit": "arc-updates/s", "cores": int(min(threads, ns)), "kind": "oracle",
             "sample": f"{ns} of {w.B} utterances of config5 spread over the length range "
-                      f"({sample_updates} arc-updates, {dt:.1f} s, fp64, OpenMP over utterances)"}
+                      f"({sample_updates} arc-updates, {dt:.1f} s, fp64, OpenMP over utterances)",
+            "single_thread_value": mid_updates / dt1,
+            "single_thread_sample": f"the utterance of median length ({mid_updates} arc-updates, {dt1:.1f} s)"}
     print(json.dumps(result), flush=True)
     den.destroy(); num.destroy()
     return 0
