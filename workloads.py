@@ -62,6 +62,23 @@ class Graph:
         return np.bincount(seq_of_state[self.src], minlength=B).astype(np.int64)
 
 
+def packed_subset(g: "Graph", sel) -> "Graph":
+    """The packed graphs of the sequences in ``sel`` (in that order) as a packed graph of their own."""
+    assert g.packed
+    so = g.state_off
+    src, dst, lw, pdf, init, fin, off = [], [], [], [], [], [], [0]
+    for b in sel:
+        k0, k1 = int(so[b]), int(so[b + 1])
+        m = (g.src >= k0) & (g.src < k1)
+        src.append(g.src[m] - k0 + off[-1]); dst.append(g.dst[m] - k0 + off[-1]); lw.append(g.logw[m])
+        pdf.append(g.pdf[k0:k1]); init.append(g.init[k0:k1]); fin.append(g.final[k0:k1])
+        off.append(off[-1] + k1 - k0)
+    return Graph(K=off[-1], src=np.concatenate(src).astype(np.int32), dst=np.concatenate(dst).astype(np.int32),
+                 logw=np.concatenate(lw).astype(np.float32), pdf=np.concatenate(pdf).astype(np.int32),
+                 init=np.concatenate(init).astype(np.float32), final=np.concatenate(fin).astype(np.float32),
+                 state_off=np.array(off, dtype=np.int32))
+
+
 @dataclass
 class Workload:
     name: str
