@@ -265,6 +265,14 @@ def test_lfmmi_with_an_infeasible_numerator(fb):
     Gd.destroy(); Gn.destroy()
 
 
+def test_ctc_topology(fb):
+    """A third graph family: CTC topologies (blank states tied to one pdf, two start and two end states per graph,
+    unit weights), log-softmax emissions."""
+    w = wl.ctc_workload()
+    compare_fb(fb, w.num, w.D, w.emis, w.lengths, name="ctc topologies")
+    compare_fb(fb, w.num, w.D, w.emis, w.lengths, name="ctc topologies, float vectors", state="narrow", post_tol=1e-4)
+
+
 # ------------------------------------------------------------------ edge cases
 
 def test_single_frame_and_single_state(fb):

@@ -175,6 +175,51 @@ def chain_graphs(rng: np.random.Generator, phones: np.ndarray, D: int) -> Graph:
     return Graph(K, src, dst, logw, pdf, init, final, state_off=off.astype(np.int32))
 
 
+def ctc_graphs(labels: list, blank: int = 0) -> Graph:
+    """Connectionist-temporal-classification topologies (the paper's introduction names CTC as one of
+    the sequence criteria its forward-backward serves), one per label sequence, packed block-diagonally.
+    A sequence of L labels has 2L + 1 states: blank, label 1, blank, label 2, ..., label L, blank.  Every state
+    has a self-loop and an arc to the next state; a label state also has an arc to the next label state when the
+    two labels differ.  All weights are 1-bar (log 1 = 0): the model has no transition probabilities.  A path
+    starts in the first blank or the first label and ends in the last label or the last blank.  pdf of a blank
+    state = ``blank``, of a label state = its label."""
+    src, dst, pdf, init, final, off = [], [], [], [], [], [0]
+    for lab in labels:
+        lab = [int(x) for x in lab]
+        L = len(lab)
+        assert L >= 1 and all(x != blank for x in lab)
+        k0, Kb = off[-1], 2 * L + 1
+        for s in range(Kb):
+            src.append(k0 + s); dst.append(k0 + s)                       # self-loop
+            if s + 1 < Kb:
+                src.append(k0 + s); dst.append(k0 + s + 1)               # to the next state
+            if s % 2 == 1 and s + 2 < Kb and lab[s // 2] != lab[s // 2 + 1]:
+                src.append(k0 + s); dst.append(k0 + s + 2)               # label to a different next label
+            pdf.append(blank if s % 2 == 0 else lab[s // 2])
+            init.append(0.0 if s <= 1 else NEG_INF)
+            final.append(0.0 if s >= Kb - 2 else NEG_INF)
+        off.append(k0 + Kb)
+    E = len(src)
+    return Graph(K=off[-1], src=np.asarray(src, np.int32), dst=np.asarray(dst, np.int32), logw=np.zeros(E, np.float32),
+                 pdf=np.asarray(pdf, np.int32), init=np.asarray(init, np.float32), final=np.asarray(final, np.float32),
+                 state_off=np.asarray(off, np.int32))
+
+
+def ctc_workload(B: int = 12, D: int = 40, Lmin: int = 3, Lmax: int = 25, seed: int = SEED0 + 6) -> Workload:
+    """Random label sequences (repeats allowed, so some skip arcs are absent), N_b uniform on [2 L_b + 1, 3 L_b + 4],
+    emissions = log-softmax of N(0, 2) scores, as a network with a softmax output layer gives them."""
+    rng = np.random.default_rng(seed)
+    L = rng.integers(Lmin, Lmax + 1, size=B)
+    labels = [rng.integers(1, D, size=int(l)).tolist() for l in L]
+    lengths = np.array([int(rng.integers(2 * l + 1, 3 * l + 5)) for l in L], dtype=np.int32)
+    N = int(lengths.max())
+    x = rng.standard_normal((B, N, D)) * 2.0
+    emis = (x - np.log(np.sum(np.exp(x), axis=2, keepdims=True))).astype(np.float32)
+    w = Workload(name="ctc", D=D, emis=emis, lengths=lengths, num=ctc_graphs(labels))
+    w.labels = labels
+    return w
+
+
 def _emissions(rng: np.random.Generator, B: int, N: int, D: int, sigma: float) -> np.ndarray:
     out = np.empty((B, N, D), dtype=np.float32)
     for b in range(B):                      # per sequence: bounded temporaries
