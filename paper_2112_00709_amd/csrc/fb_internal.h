@@ -96,7 +96,7 @@ bool sell_in_bounds(const SellHost &S, int32_t n_vidx, std::string &why);
 // the emission in the staged emission vector, Ecap being a slot that always holds 0.
 // ---------------------------------------------------------------------------
 constexpr int kBatchRows = 4;
-constexpr int kRing = 4;                        // batches per unrolled iteration = prefetch ring size
+constexpr int kRing = 3;                        // batches per unrolled iteration = prefetch ring size
 constexpr int kResident = 6;                    // batches per wave and step that stay in registers (<= 8)
 constexpr uint32_t kFlagInfo = 0x01;            // the batch's last row is an info row
 constexpr uint32_t kFlagSkip = 0x04;            // nothing to do in this batch (padding)

@@ -360,7 +360,11 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                     __builtin_amdgcn_sched_barrier(0);   // keep the issue order: waits count loads in order
                 }
             }
-            T g[2][kBatchRows];   // gathered values: of the batch being folded, and of the next one
+            // gathered values of the batch being folded and of the next one; the buffers rotate with the batch
+            // number, and an unrolled iteration must bring the rotation back to where it started
+            constexpr int GB = kRing % 2 == 0 ? 2 : 3;
+            static_assert(kRing % GB == 0, "ring size must be a multiple of the gather buffer count");
+            T g[GB][kBatchRows];
             auto gather = [&](T(&dst)[kBatchRows], const Arc(&a)[kBatchRows], const T *vbase) {
 #pragma unroll
                 for (int r = 0; r < kBatchRows; ++r) dst[r] = vbase[a[r].src];
@@ -414,9 +418,9 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                 for (int q = 0; q < NRES; ++q) {
                     const uint32_t f = ((q < 4 ? rflag0 : rflag1) >> (8 * (q & 3))) & 0xffu;
                     if (q + 1 < NRES)
-                        fold(f, res[q], g[q & 1], g[(q + 1) & 1], res[q + 1], true);
+                        fold(f, res[q], g[q % GB], g[(q + 1) % GB], res[q + 1], true);
                     else
-                        fold(f, res[q], g[q & 1], g[(q + 1) & 1], ring[0], n_iter > 0);
+                        fold(f, res[q], g[q % GB], g[(q + 1) % GB], ring[0], n_iter > 0);
                 }
                 for (int it = 0; it < n_iter; ++it) {
                     const uint32_t fw =
@@ -427,7 +431,7 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                         if (pf >= n_batch) pf -= n_batch;
                         load_batch(ring[(j + kRing - 1) % kRing], pf);
                         __builtin_amdgcn_sched_barrier(0);
-                        fold((fw >> (8 * j)) & 0xffu, ring[j], g[(NRES + j) & 1], g[(NRES + j + 1) & 1], ring[(j + 1) % kRing],
+                        fold((fw >> (8 * j)) & 0xffu, ring[j], g[(NRES + j) % GB], g[(NRES + j + 1) % GB], ring[(j + 1) % kRing],
                              j + 1 < kRing || it + 1 < n_iter);
                     }
                 }
