@@ -46,6 +46,9 @@ def lib() -> ctypes.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        # PyTorch first: it ships its own HIP runtime, and the library must bind to that copy (loading the
+        # system's runtime before it leaves PyTorch without a GPU)
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, i32, i64, u32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32, ctypes.c_size_t
         L.fb_graph_create.argtypes = [ctypes.POINTER(vp), i32, i64, vp, vp, vp, vp, vp, vp, i32, i32, vp, u32]

@@ -80,8 +80,11 @@ bool stream_from_sell(const SellHost &S, int32_t Kcap, int32_t Ecap, StreamHost 
                 const int32_t trip = S.slice_trip[s];
                 int32_t rows = 0;
                 for (int32_t it = 0; it < trip; ++it, ++rows)
-                    for (int lane = 0; lane < kWave; ++lane)
-                        lin.push_back(S.arcs[(size_t)S.slice_arc[s] + (size_t)it * kWave + lane]);
+                    for (int lane = 0; lane < kWave; ++lane) {
+                        Arc a = S.arcs[(size_t)S.slice_arc[s] + (size_t)it * kWave + lane];
+                        if (a.src >= ssd.K) a.src = Kcap + (a.src - ssd.K);   // a clone: its slot in the state buffer
+                        lin.push_back(a);
+                    }
                 for (; rows % kBatchRows != kBatchRows - 1; ++rows)   // the info row closes a batch
                     for (int lane = 0; lane < kWave; ++lane) lin.push_back(pad_arc);
                 for (int lane = 0; lane < kWave; ++lane) {
@@ -160,7 +163,10 @@ bool stream_in_bounds(const StreamHost &S, int32_t n_vidx, std::string &why)
                     for (int lane = 0; lane < kWave; ++lane) {
                         const Arc &a = S.arcs[(size_t)wd.arc_base + entry_at(bt, r, lane)];
                         // every row is gathered, info rows included: src must always be safe
-                        if (a.src < 0 || a.src >= sd.K + sd.n_slot) { why = "arc source"; return false; }
+                        if (a.src < 0 || (a.src >= sd.K && (a.src < S.Kcap || a.src >= S.Kcap + sd.n_slot))) {
+                            why = "arc source";
+                            return false;
+                        }
                         if (r == kBatchRows - 1 && (f & kFlagInfo)) {
                             const uint32_t u = float_to_bits(a.w);
                             const int32_t t = (int32_t)(u & 0xffff), v = (int32_t)(u >> 16);
@@ -208,7 +214,7 @@ void stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double
                 for (int lane = 0; lane < kWave; ++lane) {
                     const Arc &a = S.arcs[(size_t)wd.arc_base + entry_at(bt, r, lane)];
                     if (!(r == kBatchRows - 1 && (f & kFlagInfo))) {
-                        terms[lane].push_back((double)a.w + xe[(size_t)a.src]);
+                        terms[lane].push_back((double)a.w + xe[(size_t)(a.src < sd.K ? a.src : sd.K + (a.src - S.Kcap))]);
                         continue;
                     }
                     if (lane % g == 0) {   // the row's lanes are complete: the info row is the batch's last

@@ -236,6 +236,35 @@ def test_cloned_hub_rows_small(fb):
     compare_fb(fb, w.den, w.D, w.emis, w.lengths, name="config4 K=3500 (cloned hubs)")
 
 
+def _pack(graphs):
+    src, dst, lw, pdf, init, fin, off = [], [], [], [], [], [], [0]
+    for g in graphs:
+        src.append(g.src + off[-1]); dst.append(g.dst + off[-1]); lw.append(g.logw)
+        pdf.append(g.pdf); init.append(g.init); fin.append(g.final); off.append(off[-1] + g.K)
+    return wl.Graph(K=off[-1], src=np.concatenate(src).astype(np.int32), dst=np.concatenate(dst).astype(np.int32),
+                    logw=np.concatenate(lw).astype(np.float32), pdf=np.concatenate(pdf).astype(np.int32),
+                    init=np.concatenate(init).astype(np.float32), final=np.concatenate(fin).astype(np.float32),
+                    state_off=np.array(off, dtype=np.int32))
+
+
+def test_packed_graphs_with_hubs_and_clones(fb):
+    """Packed graphs of different sizes on the 16-wave kernel, each with rows spread over many lanes and with cloned
+    rows (the clone slots of a smaller graph sit behind the largest graph's states); and a shared graph with one
+    giant hub that every state points to."""
+    rng = np.random.default_rng(11)
+    g = _pack([wl.random_graph(rng, K, 64, zipf_s=1.1) for K in (1500, 1150)])
+    assert max(np.bincount(g.dst[g.dst >= 1500], minlength=g.K).max(), np.bincount(g.dst[g.dst < 1500]).max()) > 64 * 32
+    emis = (rng.standard_normal((2, 14, 64)) * 2).astype(np.float32)
+    compare_fb(fb, g, 64, emis, np.array([14, 9], np.int32), name="packed hub graphs")
+    compare_fb(fb, g, 64, emis, np.array([14, 9], np.int32), name="packed hub graphs, double vectors", state="wide")
+    g0 = wl.random_graph(rng, 2600, 17, mean_extra_deg=2.0)
+    every = np.arange(g0.K, dtype=np.int32)
+    hub = wl.Graph(g0.K, np.concatenate([g0.src, every]), np.concatenate([g0.dst, np.zeros(g0.K, np.int32)]),
+                   np.concatenate([g0.logw, np.full(g0.K, -1.5, np.float32)]), g0.pdf, g0.init, g0.final)
+    emis = (rng.standard_normal((2, 11, 17)) * 2).astype(np.float32)
+    compare_fb(fb, hub, 17, emis, np.array([11, 6], np.int32), name="one giant hub")
+
+
 def test_gradient_kernel_paths(fb):
     """lfmmi_loss_grad through the specialised gradient kernel (denominator states a multiple of 4) and through
     the general posterior kernel (any other state count), both against the oracle."""

@@ -68,13 +68,27 @@ def _direct_product(K, rows, cols, w2, x):
     return y
 
 
-@pytest.mark.parametrize("case", ["zipf_hubs", "zipf_clones", "uniform", "chains"])
+def _pack(graphs):
+    src, dst, lw, pdf, init, fin, off = [], [], [], [], [], [], [0]
+    for g in graphs:
+        src.append(g.src + off[-1]); dst.append(g.dst + off[-1]); lw.append(g.logw)
+        pdf.append(g.pdf); init.append(g.init); fin.append(g.final); off.append(off[-1] + g.K)
+    return wl.Graph(K=off[-1], src=np.concatenate(src).astype(np.int32), dst=np.concatenate(dst).astype(np.int32),
+                    logw=np.concatenate(lw).astype(np.float32), pdf=np.concatenate(pdf).astype(np.int32),
+                    init=np.concatenate(init).astype(np.float32), final=np.concatenate(fin).astype(np.float32),
+                    state_off=np.array(off, dtype=np.int32))
+
+
+@pytest.mark.parametrize("case", ["zipf_hubs", "zipf_clones", "packed_clones", "uniform", "chains"])
 def test_kernel_schedule_computes_the_sparse_products(case):
     rng = np.random.default_rng(5)
     if case == "zipf_hubs":          # hub rows are spread over 2 ... 64 lanes
         w = wl.config4(K=900, B=2, Nmin=3, Nmax=4, D=64); g = w.den
     elif case == "zipf_clones":      # the largest hubs are too long for one slice and get clones
         w = wl.config4(K=3500, B=2, Nmin=3, Nmax=4, D=64); g = w.den
+    elif case == "packed_clones":    # packed graphs of different sizes, the smaller one with cloned hubs
+        w = wl.config4(K=3500, B=2, Nmin=3, Nmax=4, D=64)
+        g = _pack([wl.config4(K=3800, B=1, Nmin=3, Nmax=4, D=64).den, w.den])
     elif case == "uniform":
         w = wl.config3(K=300, B=2, N=3, D=20); g = w.den
     else:
