@@ -20,7 +20,10 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "fb_oracle.c")
 _LIB = os.path.join(_HERE, "libfb_oracle.so")
+_VSRC = os.path.join(_HERE, "viterbi_oracle.c")
+_VLIB = os.path.join(_HERE, "libviterbi_oracle.so")
 _lib = None
+_vlib = None
 
 
 def build(force: bool = False) -> str:
@@ -28,6 +31,8 @@ def build(force: bool = False) -> str:
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC",
                                "-o", _LIB, _SRC, "-lm"])
+    if force or not os.path.exists(_VLIB) or os.path.getmtime(_VLIB) < os.path.getmtime(_VSRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-shared", "-fPIC", "-o", _VLIB, _VSRC, "-lm"])
     return _LIB
 
 
@@ -164,3 +169,46 @@ def lfmmi(den, num, emis: np.ndarray, lengths: np.ndarray, sel: Optional[Sequenc
     if rc != 0:
         raise ValueError("oracle: malformed argument")
     return LFMMIResult(zn, zd, grad)
+
+
+@dataclass
+class ViterbiResult:
+    score: np.ndarray           # [nsel] best-path score (tropical-semiring "log Z")
+    path: np.ndarray            # [nsel, N] int32: state per frame (global numbering), -1 on padded frames
+
+
+def viterbi(g, emis: np.ndarray, lengths: np.ndarray, sel: Optional[Sequence[int]] = None) -> ViterbiResult:
+    """Best path (tropical semiring) of the selected sequences; see viterbi_oracle.c."""
+    global _vlib
+    if _vlib is None:
+        build()
+        _vlib = ctypes.CDLL(_VLIB)
+        _vlib.vto_viterbi.restype = ctypes.c_int
+    emis = _c(emis, np.float32)
+    lengths = _c(lengths, np.int32)
+    B, N, D = emis.shape
+    sel = np.arange(B, dtype=np.int32) if sel is None else _c(sel, np.int32)
+    src, dst, logw, pdf, init, fin, state_off, arc_off = _graph_args(g)
+    score = np.empty(sel.shape[0], dtype=np.float64)
+    path = np.empty((sel.shape[0], N), dtype=np.int32)
+    rc = _vlib.vto_viterbi(
+        ctypes.c_int32(g.K), ctypes.c_int64(src.shape[0]), _p(src), _p(dst), _p(logw), _p(pdf), _p(init), _p(fin),
+        _p(state_off), _p(arc_off), _p(emis), _p(lengths), ctypes.c_int32(B), ctypes.c_int32(N), ctypes.c_int32(D),
+        _p(sel), ctypes.c_int32(sel.shape[0]), _p(score), _p(path))
+    if rc != 0:
+        raise ValueError("oracle: malformed argument")
+    return ViterbiResult(score, path)
+
+
+def path_score(g, emis_b: np.ndarray, path: np.ndarray) -> float:
+    """Score of a given state sequence in double precision: init + emissions + the best arc between consecutive
+    states (parallel arcs: the largest weight) + final; -inf if an arc is missing.  Used to check that a path
+    returned by anybody is valid and attains a score."""
+    T = int(path.shape[0])
+    s = float(g.init[path[0]]) + float(emis_b[0, g.pdf[path[0]]])
+    for n in range(1, T):
+        m = (g.src == path[n - 1]) & (g.dst == path[n])
+        if not m.any():
+            return float("-inf")
+        s += float(np.max(g.logw[m])) + float(emis_b[n, g.pdf[path[n]]])
+    return s + float(g.final[path[T - 1]])
