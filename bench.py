@@ -90,6 +90,21 @@ def context_workloads(fb, wl, torch):
             out[name]["paper_table1_s"] = 1.04
         log(f"[bench] {name}: {ms:.3f} ms, {upd / (ms * 1e-3):.3e} arc-updates/s, HBM fraction {out[name]['hbm_frac']:.3f}")
         G.destroy()
+        if name in ("config4", "paper_shape_den"):   # best path (tropical semiring) on the same inputs
+            Gv = fb.graph_from(g, w.D, viterbi=True)
+            for _ in range(2):
+                fb.fb_viterbi(Gv, emis, lengths)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(n):
+                fb.fb_viterbi(Gv, emis, lengths)
+            torch.cuda.synchronize()
+            vms = (time.perf_counter() - t0) * 1e3 / n
+            valgo = 4 * d_frames + 2 * k_frames + 4 * frames     # used emissions read, back-pointers written, path written
+            out[name + "_viterbi"] = {"ms": vms, "arc_updates": upd // 2, "arc_updates_per_s": upd / 2 / (vms * 1e-3),
+                                      "algorithmic_bytes": valgo, "hbm_frac": valgo / (vms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+            log(f"[bench] {name} best path: {vms:.3f} ms, {upd / 2 / (vms * 1e-3):.3e} arc-updates/s")
+            Gv.destroy()
         del emis
     return out
 

@@ -20,7 +20,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfb_amd.so")
 
 FB_OK, FB_EINVAL, FB_ENOMEM, FB_EHIP, FB_EUNSUPPORTED = 0, -1, -2, -3, -4
-FB_GRAPH_HOST_ONLY, FB_GRAPH_WIDE_STATE, FB_GRAPH_NARROW_STATE = 1, 2, 4
+FB_GRAPH_HOST_ONLY, FB_GRAPH_WIDE_STATE, FB_GRAPH_NARROW_STATE, FB_GRAPH_VITERBI = 1, 2, 4, 8
 LAYOUT = {"in_ptr": 0, "in_src": 1, "in_w": 2, "in_perm": 3, "out_ptr": 4, "out_dst": 5, "out_w": 6,
           "out_perm": 7, "pdf_ptr": 8, "pdf_states": 9}
 
@@ -28,7 +28,7 @@ LAYOUT = {"in_ptr": 0, "in_src": 1, "in_w": 2, "in_perm": 3, "out_ptr": 4, "out_
 SYMBOLS = ["fb_graph_create", "fb_graph_destroy", "fb_graph_layout_size", "fb_graph_layout", "fb_check_lengths",
            "fb_alpha", "fb_beta", "fb_posteriors", "fb_lfmmi_workspace_bytes", "lfmmi_loss_grad",
            "fb_limits_max_states", "fb_strerror", "fb_last_error", "fb_graph_schedule_apply_host",
-           "fb_profile_enable", "fb_profile_read"]
+           "fb_profile_enable", "fb_profile_read", "fb_viterbi_workspace_bytes", "fb_viterbi"]
 
 
 class FBError(RuntimeError):
@@ -75,6 +75,10 @@ def lib() -> ctypes.CDLL:
         L.lfmmi_loss_grad.restype = ctypes.c_int
         L.fb_limits_max_states.argtypes = [i32, ctypes.c_int]
         L.fb_limits_max_states.restype = i32
+        L.fb_viterbi_workspace_bytes.argtypes = [vp, i32, i32]
+        L.fb_viterbi_workspace_bytes.restype = sz
+        L.fb_viterbi.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+        L.fb_viterbi.restype = ctypes.c_int
         L.fb_profile_enable.argtypes = [ctypes.c_int]
         L.fb_profile_enable.restype = ctypes.c_int
         L.fb_profile_read.argtypes = [vp]
@@ -127,9 +131,11 @@ class Graph:
             pass
 
 
-def fb_graph_create(K, src, dst, logw, pdf, init, final, D, state_off=None, host_only=False, state="auto") -> Graph:
-    """state: 'auto', 'wide' (double carriers) or 'narrow' (single carriers)."""
+def fb_graph_create(K, src, dst, logw, pdf, init, final, D, state_off=None, host_only=False, state="auto",
+                    viterbi=False) -> Graph:
+    """state: 'auto', 'wide' (double carriers) or 'narrow' (single carriers); viterbi: also prepare fb_viterbi."""
     flags = (FB_GRAPH_HOST_ONLY if host_only else 0) | {"auto": 0, "wide": FB_GRAPH_WIDE_STATE, "narrow": FB_GRAPH_NARROW_STATE}[state]
+    flags |= FB_GRAPH_VITERBI if viterbi else 0
     src, dst, logw = _np(src, np.int32), _np(dst, np.int32), _np(logw, np.float32)
     pdf, init, final = _np(pdf, np.int32), _np(init, np.float32), _np(final, np.float32)
     state_off = _np(state_off, np.int32)
@@ -141,9 +147,9 @@ def fb_graph_create(K, src, dst, logw, pdf, init, final, D, state_off=None, host
     return Graph(h, int(K), E, int(D), n_seq, host_only)
 
 
-def graph_from(g, D: int, host_only: bool = False, state: str = "auto") -> Graph:
+def graph_from(g, D: int, host_only: bool = False, state: str = "auto", viterbi: bool = False) -> Graph:
     """Build from an object with fields K, src, dst, logw, pdf, init, final, state_off."""
-    return fb_graph_create(g.K, g.src, g.dst, g.logw, g.pdf, g.init, g.final, D, g.state_off, host_only, state)
+    return fb_graph_create(g.K, g.src, g.dst, g.logw, g.pdf, g.init, g.final, D, g.state_off, host_only, state, viterbi)
 
 
 def fb_graph_layout(g: Graph, name: str) -> np.ndarray:
@@ -243,6 +249,20 @@ def fb_posteriors(g: Graph, alpha, beta, lengths, B: int, N: int, want_state: bo
 
 def fb_lfmmi_workspace_bytes(den: Graph, num: Graph, B: int, N: int, D: int) -> int:
     return int(lib().fb_lfmmi_workspace_bytes(den.handle, num.handle, B, N, D))
+
+
+def fb_viterbi(g: Graph, emis, lengths, ws=None):
+    """-> (score [B] float64, path [B,N] int32), on the device.  The graph must have been built with viterbi=True."""
+    torch = _torch()
+    B, N, D = _dev_inputs(emis, lengths)
+    need = int(lib().fb_viterbi_workspace_bytes(g.handle, B, N))
+    if ws is None:
+        ws = torch.empty((need,), dtype=torch.uint8, device=emis.device)
+    score = torch.empty((B,), dtype=torch.float64, device=emis.device)
+    path = torch.empty((B, N), dtype=torch.int32, device=emis.device)
+    _check(lib().fb_viterbi(g.handle, _dp(emis), _dp(lengths), B, N, D, _dp(score), _dp(path), _dp(ws), int(ws.numel()),
+                            _stream()))
+    return score, path
 
 
 def lfmmi_loss_grad(den: Graph, num: Graph, emis, lengths, ws=None, grad=None):

@@ -44,7 +44,7 @@ RecDir make_dir(const fb_graph *g, bool backward, void *out, bool out_carrier, f
 }
 
 int run_recursion(const fb_graph *g, const float *emis, const int32_t *lengths, int32_t B, int32_t N, int32_t D,
-                  const RecDir *dirs, int n_dir, fb_stream stream)
+                  const RecDir *dirs, int n_dir, fb_stream stream, bool tropical = false)
 {
     RecParams p{};
     p.n_dir = n_dir;
@@ -59,10 +59,11 @@ int run_recursion(const fb_graph *g, const float *emis, const int32_t *lengths, 
     size_t lds = 0;
     for (int i = 0; i < n_dir; ++i) {
         p.dir[i] = dirs[i];
-        lds = std::max(lds, recursion_lds_bytes(p.Kcap, dirs[i].Ccap, p.Ecap, dirs[i].backward != 0, g->f64, p.shared != 0));
+        lds = std::max(lds, recursion_lds_bytes(p.Kcap, dirs[i].Ccap, p.Ecap, dirs[i].backward != 0, g->f64, p.shared != 0,
+                                                tropical));
     }
     if (lds > kLdsBytes) return fail(FB_EUNSUPPORTED, "state vectors and emission rows exceed the on-chip memory");
-    return launch_recursion(g->nw, g->f64, p, lds, stream);
+    return launch_recursion(g->nw, g->f64, tropical, p, lds, stream);
 }
 
 PostGraph make_post(const fb_graph *g, const void *a, const void *b, bool f64, float in_scale, float sign, float *state_post)
@@ -216,6 +217,35 @@ int fb_posteriors(const fb_graph *g, const float *alpha, const float *beta, cons
     if (!state_post && !pdf_post) return fail(FB_EINVAL, "fb_posteriors: no output requested");
     const PostGraph q = make_post(g, alpha, beta, false, kLog2ef, 1.0f, state_post);
     return run_posteriors(&q, 1, lengths, B, N, D, pdf_post, stream);
+}
+
+size_t fb_viterbi_workspace_bytes(const fb_graph *g, int32_t B, int32_t N)
+{
+    if (!g || B <= 0 || N <= 0) return 0;
+    const size_t rows = g->n_seq == 0 ? (size_t)B * N * g->K : (size_t)N * g->K;
+    return align256(rows * sizeof(uint16_t)) + align256((size_t)B * sizeof(int32_t));
+}
+
+int fb_viterbi(const fb_graph *g, const float *emis, const int32_t *lengths, int32_t B, int32_t N, int32_t D, double *score,
+               int32_t *path, void *ws, size_t ws_bytes, fb_stream stream)
+{
+    int rc = check_common("fb_viterbi", g, emis, lengths, B, N, D);
+    if (rc) return rc;
+    if (!g->viterbi) return fail(FB_EINVAL, "fb_viterbi: the graph was built without FB_GRAPH_VITERBI");
+    if (!score || !path) return fail(FB_EINVAL, "fb_viterbi: score or path is NULL");
+    if (!ws || ws_bytes < fb_viterbi_workspace_bytes(g, B, N)) return fail(FB_EINVAL, "fb_viterbi: workspace missing or too small");
+    if (((uintptr_t)ws & 255) != 0) return fail(FB_EINVAL, "fb_viterbi: workspace must be 256-byte aligned");
+    const size_t rows = g->n_seq == 0 ? (size_t)B * N * g->K : (size_t)N * g->K;
+    uint16_t *bp = (uint16_t *)ws;
+    int32_t *last = (int32_t *)((char *)ws + align256(rows * sizeof(uint16_t)));
+    RecDir d = make_dir(g, false, nullptr, false, nullptr, score, 1.0f, false);
+    const bool own_plan = g->h_fwd.Ccap > 0;   // the forward plan has clones: walk the plan built without them
+    d.sched = g->vit;
+    d.Ccap = own_plan ? g->h_vit.Ccap : g->h_fwd.Ccap;
+    d.bp = bp;
+    d.last = last;
+    if ((rc = run_recursion(g, emis, lengths, B, N, D, &d, 1, stream, true))) return rc;
+    return launch_backtrace(bp, last, lengths, g->vit.sub, B, N, g->n_seq == 0, g->K, path, stream);
 }
 
 size_t fb_lfmmi_workspace_bytes(const fb_graph *den, const fb_graph *num, int32_t B, int32_t N, int32_t D)

@@ -72,7 +72,7 @@ struct SellHost {
 // rows [0, K) of a CSR-like matrix over K columns: entries ptr[r]..ptr[r+1] with column col[] and
 // weight w[] (log2 units); row_vidx[r] = emission index of row r.  Appends one sub-plan to `out`.
 void sell_append(SellHost &out, int32_t k0, int32_t K, const int64_t *ptr, const int32_t *col, const float *w,
-                 const int32_t *row_vidx);
+                 const int32_t *row_vidx, bool allow_clones);
 
 bool sell_in_bounds(const SellHost &S, int32_t n_vidx, std::string &why);
 
@@ -173,9 +173,11 @@ struct fb_graph {
     fb::HostLayout lay;
     std::vector<int32_t> state_off;   // packed only
     fb::StreamHost h_fwd, h_bwd;      // host schedules of the two recursions
+    fb::StreamHost h_vit;             // forward schedule without clones (FB_GRAPH_VITERBI and h_fwd has clones)
+    bool viterbi = false;             // FB_GRAPH_VITERBI was given
     fb::PdfHost h_pdf;                // states grouped by pdf, for the posterior accumulation
     // device
-    fb::StreamDev fwd, bwd;
+    fb::StreamDev fwd, bwd, vit;      // vit: what fb_viterbi walks (= fwd when that has no clones)
     fb::PdfDev pdfs;
     int32_t *d_pdf = nullptr;         // [K]
     float *d_init2 = nullptr;         // [K] init * log2(e)
@@ -201,6 +203,8 @@ struct RecDir {
     int32_t Ccap;          // clone slots of this direction's schedule
     int backward;
     int fill_pad;          // write -inf / 0 into the rows of padded frames
+    uint16_t *bp;          // tropical semiring: back-pointers, laid out like a vector output, nullable otherwise
+    int32_t *last;         // tropical semiring: [B] local id of the best end state (-1: none)
 };
 
 struct RecParams {
@@ -233,14 +237,17 @@ struct PostParams {
     int32_t Kcap, Kcap64, frames_per_block;   // Kcap64: largest double-carrier (sub-)graph
 };
 
-int launch_recursion(int nw, bool f64, const RecParams &p, size_t lds_bytes, void *stream);
+int launch_recursion(int nw, bool f64, bool tropical, const RecParams &p, size_t lds_bytes, void *stream);
+int launch_backtrace(const uint16_t *bp, const int32_t *last, const int32_t *lengths, const SubDesc *sub, int32_t B,
+                     int32_t N, int32_t shared, int32_t Ktot, int32_t *path, void *stream);
 int launch_posteriors(const PostParams &p, size_t lds_bytes, void *stream);
 bool gradient_kernel_applies(const PostParams &p);
 size_t gradient_lds_bytes(const PostParams &p);
 int launch_gradient(const PostParams &p, size_t lds_bytes, void *stream);
 int launch_loss(const double *logz_num, const double *logz_den, const int32_t *lengths, int32_t B, double *loss,
                 void *stream);
-size_t recursion_lds_bytes(int32_t Kcap, int32_t Ccap, int32_t Ecap, bool backward, bool f64, bool shared);
+size_t recursion_lds_bytes(int32_t Kcap, int32_t Ccap, int32_t Ecap, bool backward, bool f64, bool shared,
+                           bool tropical = false);
 size_t posterior_lds_bytes(const PostParams &p);
 
 }  // namespace fb

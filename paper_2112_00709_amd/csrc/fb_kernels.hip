@@ -117,6 +117,9 @@ __device__ __forceinline__ double dpp_mov(double v)
     const uint64_t r = (uint64_t)dpp_u<CTRL>((uint32_t)u) | ((uint64_t)dpp_u<CTRL>((uint32_t)(u >> 32)) << 32);
     return __longlong_as_double((long long)r);
 }
+template <int CTRL>
+__device__ __forceinline__ int dpp_mov(int v) { return (int)dpp_u<CTRL>((uint32_t)v); }
+__device__ __forceinline__ int lane_value(int v, int l) { return __builtin_amdgcn_readlane(v, l); }
 __device__ __forceinline__ float lane_value(float v, int l)
 {
     return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(v), l));
@@ -157,6 +160,16 @@ __device__ __forceinline__ void group_total(T &m, float &s, int lg, int lane)
     m = mg;
 }
 
+// Tropical semiring: the maximum over the group and the back-pointer of a lane that holds it
+// (of the smallest back-pointer among those lanes, so the choice does not depend on timing).
+template <class T>
+__device__ __forceinline__ void group_best(T &m, int &arg, int lg, int lane)
+{
+    const T mg = group_all(m, lg, lane, [](T a, T b) { return tmax(a, b); });
+    arg = group_all(m == mg ? arg : 0x7fffffff, lg, lane, [](int a, int b) { return min(a, b); });
+    m = mg;
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll
@@ -192,8 +205,9 @@ __device__ __forceinline__ float wave_sum(float v)
 //   er   3 x (Ecap + 1) float   emissions as given (natural log) of the frame in use and
 //                               of the next two; slot Ecap = 0
 //   pix  Ecap int32             packed graphs: pdf id of every state
+//   bpb  2 x Xs uint16          tropical semiring only: back-pointers of the previous / current step
 // ---------------------------------------------------------------------------
-template <int NW, class T>
+template <int NW, class T, bool TROP>
 __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P)
 {
     constexpr int NRES = kResident;
@@ -218,6 +232,7 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
     T *red = bh + (bwd ? 2 * Xs : 0);
     float *er = (float *)(red + 4 * NW + 2);
     int32_t *pix = (int32_t *)(er + 3 * Es);
+    uint16_t *bpb = (uint16_t *)(pix + (P.shared ? 0 : P.Ecap));   // tropical semiring: 2 x Xs back-pointers
 
     const float *em_seq = P.emis + (size_t)b * P.N * P.D;
     const size_t out_ld = P.shared ? (size_t)K : (size_t)P.Ktot;
@@ -280,6 +295,15 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
             }
     };
 
+    // tropical semiring: the back-pointers of frame f (f >= 1) -> global memory
+    uint16_t *bp_seq = (TROP && R.bp) ? R.bp + out_at : nullptr;
+    auto write_bp = [&](int f, const uint16_t *srcb) {
+        if (bp_seq) {
+            uint16_t *orow = bp_seq + (size_t)f * out_ld;
+            for (int k = lane; k < K; k += kWave) orow[k] = srcb[k];
+        }
+    };
+
     if (Tn > 0) {
         // ---- first frame of this direction: x = start weight (x) v
         if (!P.shared)
@@ -323,6 +347,7 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                 staged_wait();   // frame i+1, requested a whole step ago, is in LDS
                 if (i + 2 < Tn) stage(frame(i + 2), er + ((i + 2) % 3) * Es);   // buffer of frame i-1: no longer read
                 write_row(frame(i - 1), bwd ? bh + cur * Xs : xb + cur * Xs);
+                if (TROP && i >= 2) write_bp(i - 1, bpb + cur * Xs);
                 if (lane == 0) red[nxt * NW + wave] = kNegInf;
                 __syncthreads();
             }
@@ -381,8 +406,10 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                 for (int w = 1; w < NW; ++w) M = tmax(M, red[cur * NW + w]);
                 const T c = (M == kNegInf) ? (T)0 : M;
                 wmax = kNegInf;
-                T m = (T)kNegBig;
+                T m = TROP ? kNegInf : (T)kNegBig;
                 float sum = 0.0f;
+                int arg = 0;                         // tropical semiring: the state the best term so far came from
+                uint16_t *bpn = bpb + nxt * Xs;
                 const T *vbase = xc;
                 if (i <= 2)   // rows without arcs: the semiring zero from the second frame on, in both buffers
                     for (int z = tid; z < sd.n_zero; z += NC * kWave) {
@@ -396,7 +423,28 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                                 const Arc(&next)[kBatchRows], bool has_next) {
                     if (has_next) gather(gnext, next, vbase);
                     if (!(f & kFlagSkip)) {
-                        if (!(f & kFlagInfo)) {
+                        if constexpr (TROP) {
+                            // (+) = max: keep the largest term and the state it came from (the first of equal terms)
+                            auto take = [&](T x, int s) {
+                                if (x > m) { m = x; arg = s; }
+                            };
+                            take(gv[0] + (T)a[0].w, a[0].src);
+                            take(gv[1] + (T)a[1].w, a[1].src);
+                            take(gv[2] + (T)a[2].w, a[2].src);
+                            if (!(f & kFlagInfo)) {
+                                take(gv[3] + (T)a[3].w, a[3].src);
+                            } else {
+                                const int lg = (int)((f >> kFlagLgShift) & 7u);
+                                if (lg) group_best(m, arg, lg, lane);
+                                const uint32_t u = __float_as_uint(a[3].w);
+                                const T x = (m - c) + (T)ern[u >> 16] * (T)kLog2e;
+                                xn[u & 0xffffu] = x;
+                                bpn[u & 0xffffu] = (uint16_t)arg;
+                                wmax = tmax(wmax, x);
+                                m = kNegInf;
+                                arg = 0;
+                            }
+                        } else if (!(f & kFlagInfo)) {
                             lse_add4(m, sum, gv[0] + (T)a[0].w, gv[1] + (T)a[1].w, gv[2] + (T)a[2].w, gv[3] + (T)a[3].w);
                         } else {   // three arcs, then the row's sum is complete
                             lse_add3(m, sum, gv[0] + (T)a[0].w, gv[1] + (T)a[1].w, gv[2] + (T)a[2].w);
@@ -445,7 +493,32 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
         const int last = (Tn - 1) & 1;
         const T *xl = xb + last * Xs;
         if (io_wave) write_row(frame(Tn - 1), bwd ? bh + last * Xs : xl);
-        if (R.logz) {
+        if (TROP) {
+            if (io_wave && Tn >= 2) write_bp(Tn - 1, bpb + last * Xs);
+            // score = max_k (x[k] + end weight) and a state that attains it (the smallest such k)
+            T m = kNegInf;
+            int at = 0x7fffffff;
+            for (int k = tid; k < K; k += NT) {
+                const T t = xl[k] + (T)R.obound[k0 + k];
+                if (t > m) { m = t; at = k; }
+            }
+#pragma unroll
+            for (int o = 32; o >= 1; o >>= 1) {
+                const T m2 = (T)__shfl_xor(m, o, 64);
+                const int a2 = __shfl_xor(at, o, 64);
+                if (m2 > m || (m2 == m && a2 < at)) { m = m2; at = a2; }
+            }
+            T *rm = red + 2 * NW, *rs = rm + NW;
+            if (lane == 0) { rm[wave] = m; rs[wave] = (T)at; }
+            __syncthreads();
+            if (io_wave && lane == 0) {   // the lane that holds the sum of the offsets
+                m = rm[0]; T a = rs[0];
+                for (int w = 1; w < NW; ++w)
+                    if (rm[w] > m || (rm[w] == m && rs[w] < a)) { m = rm[w]; a = rs[w]; }
+                if (R.logz) R.logz[b] = (csum + (double)m) * kLn2;
+                if (R.last) R.last[b] = m == kNegInf ? -1 : (int)a;
+            }
+        } else if (R.logz) {
             T m = (T)kNegBig;
             float s = 0.0f;
             for (int k = tid; k < K; k += NT) lse_add(m, s, xl[k] + (T)R.obound[k0 + k]);
@@ -464,8 +537,9 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                 R.logz[b] = (csum + (double)m + (double)flog2(s)) * kLn2;
             }
         }
-    } else if (R.logz && tid == 0) {
-        R.logz[b] = -INFINITY;
+    } else if (tid == 0) {
+        if (R.logz) R.logz[b] = -INFINITY;
+        if (TROP && R.last) R.last[b] = -1;
     }
 
     // ---- padded frames
@@ -916,6 +990,26 @@ __global__ __launch_bounds__(256) void fb_loss_kernel(const double *zn, const do
     if (threadIdx.x == 0) *loss = acc[0];
 }
 
+// Best path from the back-pointers: one thread per sequence walks from the best end state to frame 0.
+// bp: [B][N][K] (shared graph) or [N][Ktot] (packed graphs), row n holding the predecessors of frame n.
+__global__ __launch_bounds__(64) void fb_backtrace_kernel(const uint16_t *bp, const int32_t *last, const int32_t *lengths,
+                                                          const SubDesc *sub, int32_t B, int32_t N, int32_t shared,
+                                                          int32_t Ktot, int32_t *path)
+{
+    const int b = blockIdx.x * 64 + threadIdx.x;
+    if (b >= B) return;
+    const SubDesc sd = sub[shared ? 0 : b];
+    const int T = min(max(lengths[b], 0), N);
+    int32_t *prow = path + (size_t)b * N;
+    int s = T > 0 ? last[b] : -1;
+    for (int n = T; n < N; ++n) prow[n] = -1;
+    for (int n = T - 1; n >= 0; --n) {
+        prow[n] = s < 0 ? -1 : sd.k0 + s;
+        if (n > 0 && s >= 0)
+            s = shared ? bp[((size_t)b * N + n) * sd.K + s] : bp[(size_t)n * Ktot + sd.k0 + s];
+    }
+}
+
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
@@ -937,13 +1031,28 @@ static int launch_rec(Kern kern, int nw, const RecParams &p, size_t lds_bytes, v
     return check_launch("recursion kernel launch");
 }
 
-int launch_recursion(int nw, bool f64, const RecParams &p, size_t lds_bytes, void *stream)
+int launch_recursion(int nw, bool f64, bool tropical, const RecParams &p, size_t lds_bytes, void *stream)
 {
+    if (tropical) {
+        if (nw == kNWShared)
+            return f64 ? launch_rec(fb_recursion_kernel<kNWShared, double, true>, nw, p, lds_bytes, stream)
+                       : launch_rec(fb_recursion_kernel<kNWShared, float, true>, nw, p, lds_bytes, stream);
+        return f64 ? launch_rec(fb_recursion_kernel<kNWSmall, double, true>, nw, p, lds_bytes, stream)
+                   : launch_rec(fb_recursion_kernel<kNWSmall, float, true>, nw, p, lds_bytes, stream);
+    }
     if (nw == kNWShared)
-        return f64 ? launch_rec(fb_recursion_kernel<kNWShared, double>, nw, p, lds_bytes, stream)
-                   : launch_rec(fb_recursion_kernel<kNWShared, float>, nw, p, lds_bytes, stream);
-    return f64 ? launch_rec(fb_recursion_kernel<kNWSmall, double>, nw, p, lds_bytes, stream)
-               : launch_rec(fb_recursion_kernel<kNWSmall, float>, nw, p, lds_bytes, stream);
+        return f64 ? launch_rec(fb_recursion_kernel<kNWShared, double, false>, nw, p, lds_bytes, stream)
+                   : launch_rec(fb_recursion_kernel<kNWShared, float, false>, nw, p, lds_bytes, stream);
+    return f64 ? launch_rec(fb_recursion_kernel<kNWSmall, double, false>, nw, p, lds_bytes, stream)
+               : launch_rec(fb_recursion_kernel<kNWSmall, float, false>, nw, p, lds_bytes, stream);
+}
+
+int launch_backtrace(const uint16_t *bp, const int32_t *last, const int32_t *lengths, const SubDesc *sub, int32_t B,
+                     int32_t N, int32_t shared, int32_t Ktot, int32_t *path, void *stream)
+{
+    hipLaunchKernelGGL(fb_backtrace_kernel, dim3((unsigned)((B + 63) / 64)), dim3(64), 0, (hipStream_t)stream, bp, last,
+                       lengths, sub, B, N, shared, Ktot, path);
+    return check_launch("backtrace kernel launch");
 }
 
 int launch_posteriors(const PostParams &p, size_t lds_bytes, void *stream)

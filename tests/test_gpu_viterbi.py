@@ -1,0 +1,94 @@
+"""fb_viterbi (the recursion in the tropical semiring) against the fp64 oracle: the score is unique and must agree;
+the path need not be the oracle's, but it must be a path of the graph that attains the score.  GPU only."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+TOL_REL = 1e-4          # as for log Z
+
+
+@pytest.fixture(scope="module")
+def fb():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2112_00709_amd as lib
+    lib.lib()
+    return lib
+
+
+def check(fb, g, D, emis, lengths, name, sel=None, state="auto"):
+    import torch
+    B, N, _ = emis.shape
+    sel = list(range(B)) if sel is None else list(sel)
+    print(f"[gpu-case] viterbi {name}: B={B} N={N} D={D} K={g.K} E={g.E} state={state}", flush=True)
+    ref = oracle.viterbi(g, emis, lengths, sel=sel)
+    G = fb.graph_from(g, D, state=state, viterbi=True)
+    score, path = fb.fb_viterbi(G, torch.from_numpy(emis).cuda(), torch.from_numpy(lengths.astype(np.int32)).cuda())
+    torch.cuda.synchronize()
+    score, path = score.cpu().numpy(), path.cpu().numpy()
+    for i, b in enumerate(sel):
+        T = int(lengths[b])
+        assert np.all(path[b, T:] == -1)
+        if np.isneginf(ref.score[i]):
+            assert np.isneginf(score[b]) and np.all(path[b] == -1)
+            continue
+        assert abs(score[b] - ref.score[i]) <= TOL_REL * max(1.0, abs(ref.score[i])), (name, b, score[b], ref.score[i])
+        p = path[b, :T]
+        lo, hi = (g.state_off[b], g.state_off[b + 1]) if g.packed else (0, g.K)
+        assert np.all((p >= lo) & (p < hi))
+        got = oracle.path_score(g, emis[b], p)          # -inf if two consecutive states are not joined by an arc
+        assert abs(got - ref.score[i]) <= TOL_REL * max(1.0, abs(ref.score[i])), (name, b, got, ref.score[i])
+    G.destroy()
+    return score, path
+
+
+def test_viterbi_small_configurations(fb):
+    w = wl.config1(); check(fb, w.den, w.D, w.emis, w.lengths, "config1")
+    w = wl.config2(); check(fb, w.num, w.D, w.emis, w.lengths, "config2")
+    w = wl.config3(B=6, N=40); check(fb, w.den, w.D, w.emis, w.lengths, "config3 B=6 N=40")
+    w = wl.ctc_workload(); check(fb, w.num, w.D, w.emis, w.lengths, "ctc")
+
+
+def test_viterbi_hub_graph_without_clones(fb):
+    """Rows longer than 2048 arcs stay whole in the plan fb_viterbi walks (a back-pointer must name a state)."""
+    w = wl.config4(K=3500, B=3, Nmin=10, Nmax=25, D=300)
+    check(fb, w.den, w.D, w.emis, w.lengths, "config4 K=3500")
+    check(fb, w.den, w.D, w.emis, w.lengths, "config4 K=3500, double vectors", state="wide")
+
+
+def test_viterbi_config4_full_size_sampled(fb):
+    w = wl.config4()
+    order = np.argsort(w.lengths)
+    check(fb, w.den, w.D, w.emis, w.lengths, "config4 full", sel=[int(order[0]), int(order[-1])])
+
+
+def test_viterbi_edge_cases(fb):
+    rng = np.random.default_rng(3)
+    g = wl.chain_graphs(rng, np.array([2, 3, 2]), 11)
+    lengths = np.array([6, 8, 9], np.int32)                           # the second chain cannot finish
+    emis = rng.normal(size=(3, 9, 11)).astype(np.float32)
+    emis[2, 4, :] = -np.inf
+    s, p = check(fb, g, 11, emis, lengths, "infeasible chains")
+    assert np.isneginf(s[1]) and np.isneginf(s[2]) and np.isfinite(s[0])
+    g1 = wl.Graph(1, np.array([0], np.int32), np.array([0], np.int32), np.array([-0.25], np.float32),
+                  np.array([2], np.int32), np.array([-0.5], np.float32), np.array([-1.0], np.float32))
+    e1 = rng.normal(size=(3, 4, 5)).astype(np.float32)
+    check(fb, g1, 5, e1, np.array([1, 4, 2], np.int32), "one state")
+    g2 = wl.tiny_graph(9, 6, 4)
+    e2 = rng.normal(size=(2, 7, 4)).astype(np.float32)
+    check(fb, g2, 4, e2, np.array([7, 5], np.int32), "tiny graph with -inf entries")
+
+
+def test_viterbi_needs_the_flag(fb):
+    import torch
+    w = wl.config1()
+    G = fb.graph_from(w.den, w.D)
+    with pytest.raises(fb.FBError) as e:
+        fb.fb_viterbi(G, torch.from_numpy(w.emis).cuda(), torch.from_numpy(w.lengths).cuda())
+    assert e.value.code == fb.FB_EINVAL
+    G.destroy()
