@@ -13,7 +13,8 @@ namespace fb {
 constexpr int kWave = 64;            // gfx950 wavefront
 constexpr int kNWShared = 16;        // waves per workgroup, large (sub-)graphs
 constexpr int kNWSmall = 4;          // waves per workgroup, small (sub-)graphs
-constexpr int kChunk = 32;           // arcs one lane walks for one row; longer rows get more lanes
+constexpr int kChunk = 32;           // arcs one lane walks for a row that has a lane to itself; longer rows get more lanes
+constexpr int kChunkWide = 64;       // arcs one lane walks for a row spread over several lanes
 constexpr size_t kLdsBytes = 160 * 1024;
 constexpr size_t kLdsReserve = 1024; // reduction slots etc.
 
@@ -23,7 +24,7 @@ struct Arc {
     float w;       // weight (log2 units)
 };
 
-// A row with more than 64 * kChunk arcs is computed as several "clone" rows, each a state of its
+// A row with more than 64 * kChunkWide arcs is computed as several "clone" rows, each a state of its
 // own in the recursion (slots after the sub-graph's K states): every clone sums a share of the
 // row's arcs and takes the row's emission, every arc that leaves the row's state is repeated for
 // each clone, and the state's value is the (+)-sum of its clones wherever a vector leaves the kernel.
@@ -47,9 +48,9 @@ struct SubDesc {
 };
 
 // Sliced plan of a sparse matrix-vector product in the log semifield, host side.
-// A slice is 64 lanes walking arcs in lockstep.  A row with n arcs takes g lanes of
-// one slice, g the smallest power of two with ceil(n / g) <= kChunk (at most 64; beyond
-// that the row is cloned, see CloneDesc); all rows of a slice take the same g, the g
+// A slice is 64 lanes walking arcs in lockstep.  A row with n <= kChunk arcs takes one lane; a longer
+// one g lanes of one slice, g the smallest power of two with ceil(n / g) <= kChunkWide (at most 64;
+// beyond that the row is cloned, see CloneDesc); all rows of a slice take the same g, the g
 // partial sums of a row are combined across lanes when the slice ends.  Rows are
 // sorted by length so a slice is padded little; rows without arcs are not scheduled
 // at all (zero_rows).  Slices are dealt to the nw waves of a workgroup longest-first.

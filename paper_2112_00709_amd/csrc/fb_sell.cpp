@@ -5,9 +5,9 @@
 // multiplies by T: row i gathers the arcs that leave state i.  Both are sparse
 // matrix x vector products in the log semifield.  This file turns such a matrix
 // into a static work plan for one workgroup:
-//   * 64 lanes per slice; a row takes 1, 2, 4, ... 64 lanes of one slice so that
-//     no lane walks more than kChunk arcs, and all rows of a slice take the same
-//     number of lanes (the kernel adds the lanes of a row up when the slice ends);
+//   * 64 lanes per slice; a row of up to kChunk arcs takes one lane, a longer one 2, 4, ... 64
+//     lanes of one slice so that no lane walks more than kChunkWide arcs, and all rows of a
+//     slice take the same number of lanes (the kernel adds the lanes of a row up when the slice ends);
 //   * a row too long even for 64 lanes is cloned: the clones are rows of their own
 //     whose values the next step gathers like any other state (the arcs that leave
 //     the row's state are repeated for every clone), so in-degree skew costs
@@ -37,7 +37,7 @@ struct Item {
 int lanes_log2(int32_t n)
 {
     int lg = 0;
-    while (lg < 6 && (n + (1 << lg) - 1) / (1 << lg) > kChunk) ++lg;
+    while (lg < 6 && (n + (1 << lg) - 1) / (1 << lg) > (lg == 0 ? kChunk : kChunkWide)) ++lg;
     return lg;
 }
 
@@ -58,7 +58,7 @@ void sell_append(SellHost &S, int32_t k0, int32_t K, const int64_t *ptr, const i
     sd.zero0 = (int32_t)S.zero_rows.size();
 
     // rows that need clones, and their slots
-    const int64_t row_cap = (int64_t)kWave * kChunk;
+    const int64_t row_cap = (int64_t)kWave * kChunkWide;
     std::vector<int32_t> n_share((size_t)K, 1), first_slot((size_t)K, 0);
     int32_t n_slot = 0;
     for (int32_t r = 0; r < K; ++r) {

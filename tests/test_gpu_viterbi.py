@@ -55,7 +55,7 @@ def test_viterbi_small_configurations(fb):
 
 
 def test_viterbi_hub_graph_without_clones(fb):
-    """Rows longer than 2048 arcs stay whole in the plan fb_viterbi walks (a back-pointer must name a state)."""
+    """Rows longer than 4096 arcs stay whole in the plan fb_viterbi walks (a back-pointer must name a state)."""
     w = wl.config4(K=3500, B=3, Nmin=10, Nmax=25, D=300)
     check(fb, w.den, w.D, w.emis, w.lengths, "config4 K=3500")
     check(fb, w.den, w.D, w.emis, w.lengths, "config4 K=3500, double vectors", state="wide")
