@@ -225,7 +225,8 @@ size_t fb_lfmmi_workspace_bytes(const fb_graph *den, const fb_graph *num, int32_
  * The numerator launch runs on a stream of the library's own that is forked from
  * `stream` and joined back into it with events before the gradient is formed, so
  * for the caller everything is ordered on `stream` as usual (FB_AMD_SERIAL=1 in the
- * environment keeps all launches on `stream`).
+ * environment keeps all launches on `stream`).  That stream and its two events belong to
+ * the process: calls of lfmmi_loss_grad from several host threads must not overlap.
  * FB_EINVAL: as fb_alpha, or ws too small / NULL, den packed, num shared.
  */
 int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths,
