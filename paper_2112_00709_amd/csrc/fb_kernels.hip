@@ -94,14 +94,6 @@ __device__ __forceinline__ void lse_merge(T &m, float &s, T m2, float s2)
     m = M;
 }
 
-template <class T>
-__device__ __forceinline__ T wave_max(T v)
-{
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v = tmax(v, (T)__shfl_xor(v, o, 64));
-    return v;
-}
-
 // Data-parallel-primitive moves inside rows of 16 lanes, and reads of single lanes, for 32- and 64-bit values.
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_u(uint32_t v)
@@ -170,11 +162,16 @@ __device__ __forceinline__ void group_best(T &m, int &arg, int lg, int lane)
     m = mg;
 }
 
+// reductions over the whole wave; every lane gets the result
+template <class T>
+__device__ __forceinline__ T wave_max(T v)
+{
+    return group_all(v, 6, (int)(threadIdx.x & (kWave - 1)), [](T a, T b) { return tmax(a, b); });
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+    return group_all(v, 6, (int)(threadIdx.x & (kWave - 1)), [](float a, float b) { return a + b; });
 }
 
 }  // namespace
