@@ -304,6 +304,19 @@ def test_ctc_topology(fb):
 
 # ------------------------------------------------------------------ edge cases
 
+def test_largest_graphs_the_kernels_take(fb):
+    """State counts right at the documented limit (the state vectors fill the on-chip memory of a compute unit)."""
+    rng = np.random.default_rng(21)
+    K = fb.fb_limits_max_states(84, True)
+    g = wl.random_graph(rng, K, 84, mean_extra_deg=2.0)
+    emis = (rng.standard_normal((2, 6, 84)) * 2).astype(np.float32)
+    compare_fb(fb, g, 84, emis, np.array([6, 4], np.int32), name=f"shared graph at the limit K={K}")
+    Kp = fb.fb_limits_max_states(40, False)
+    gp = _pack([wl.random_graph(rng, Kp, 40, mean_extra_deg=2.0), wl.random_graph(rng, 700, 40)])
+    emis = (rng.standard_normal((2, 5, 40)) * 2).astype(np.float32)
+    compare_fb(fb, gp, 40, emis, np.array([5, 5], np.int32), name=f"packed graphs, the larger at the limit K={Kp}")
+
+
 def test_single_frame_and_single_state(fb):
     g = wl.Graph(1, np.array([0], np.int32), np.array([0], np.int32), np.array([-0.25], np.float32),
                  np.array([2], np.int32), np.array([-0.5], np.float32), np.array([-1.0], np.float32))
