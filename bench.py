@@ -91,7 +91,7 @@ def context_workloads(fb, wl, torch):
         log(f"[bench] {name}: {ms:.3f} ms, {upd / (ms * 1e-3):.3e} arc-updates/s, HBM fraction {out[name]['hbm_frac']:.3f}")
         G.destroy()
         if name in ("config4", "paper_shape_den"):   # best path (tropical semiring) on the same inputs
-            Gv = fb.graph_from(g, w.D, viterbi=True)
+            Gv = fb.graph_from(g, w.D)
             for _ in range(2):
                 fb.fb_viterbi(Gv, emis, lengths)
             torch.cuda.synchronize()

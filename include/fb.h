@@ -102,11 +102,9 @@ enum {
     FB_GRAPH_HOST_ONLY = 1, /* build and keep the layouts on the host only: no GPU is touched;
                                the handle serves fb_graph_layout* but no compute call */
     FB_GRAPH_WIDE_STATE = 2, /* carry the state vectors in double (see "Precision" below) */
-    FB_GRAPH_NARROW_STATE = 4, /* carry them in single; with neither flag the library chooses:
+    FB_GRAPH_NARROW_STATE = 4 /* carry them in single; with neither flag the library chooses:
                                double for small (sub-)graphs (< 4096 arcs and <= 1024 states each),
                                single otherwise */
-    FB_GRAPH_VITERBI = 8    /* also prepare what fb_viterbi needs (a forward plan whose rows are never
-                               split into clone states, so that a back-pointer always names a state) */
 };
 
 /* Arrays that fb_graph_layout can copy out (graph-layout step; integer work, one
@@ -163,7 +161,6 @@ int fb_graph_layout(const fb_graph *g, int which, void *host_out, size_t bytes);
  *   which = 0  forward plan:  y[j] = (+)-sum over arcs entering j of (w (x) x[src]), log2 units
  *   which = 1  backward plan: y[i] = (+)-sum over arcs leaving i of (w (x) x[dst]), log2 units
  *   which = 2  pdf plan:      y[d] = sum of x over the states tied to pdf d (ordinary sum)
- *   which = 3  the forward plan fb_viterbi walks (graph built with FB_GRAPH_VITERBI), applied like which = 0
  * sub: 0 for a shared graph, the sequence index for packed graphs; x and y use
  * the sub-graph's local state numbering (y: pdf ids for which = 2; entries
  * without a row keep their value).  Weights are the graph's log-weights times
@@ -245,10 +242,9 @@ size_t fb_viterbi_workspace_bytes(const fb_graph *g, int32_t B, int32_t N);
  *                for n < lengths[b]; -1 on padded frames and when the score is -inf.
  * Several paths may attain the score; which one is returned is fixed for a given graph and
  * input (results do not depend on timing) but otherwise unspecified.
- *   g      built with FB_GRAPH_VITERBI (FB_EINVAL otherwise)
  *   score  out, device double [B];  path  out, device int32 [B][N]
  *   ws     device scratch of at least fb_viterbi_workspace_bytes(), 256-byte aligned
- *          (the back-pointers: 2 bytes per state and frame)
+ *          (the back-pointers: 2 bytes per state and frame, a little more for graphs with very long rows)
  * Errors as fb_alpha.
  */
 int fb_viterbi(const fb_graph *g, const float *emis, const int32_t *lengths, int32_t B, int32_t N, int32_t D,

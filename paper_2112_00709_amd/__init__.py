@@ -20,7 +20,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfb_amd.so")
 
 FB_OK, FB_EINVAL, FB_ENOMEM, FB_EHIP, FB_EUNSUPPORTED = 0, -1, -2, -3, -4
-FB_GRAPH_HOST_ONLY, FB_GRAPH_WIDE_STATE, FB_GRAPH_NARROW_STATE, FB_GRAPH_VITERBI = 1, 2, 4, 8
+FB_GRAPH_HOST_ONLY, FB_GRAPH_WIDE_STATE, FB_GRAPH_NARROW_STATE = 1, 2, 4
 LAYOUT = {"in_ptr": 0, "in_src": 1, "in_w": 2, "in_perm": 3, "out_ptr": 4, "out_dst": 5, "out_w": 6,
           "out_perm": 7, "pdf_ptr": 8, "pdf_states": 9}
 
@@ -131,11 +131,9 @@ class Graph:
             pass
 
 
-def fb_graph_create(K, src, dst, logw, pdf, init, final, D, state_off=None, host_only=False, state="auto",
-                    viterbi=False) -> Graph:
-    """state: 'auto', 'wide' (double carriers) or 'narrow' (single carriers); viterbi: also prepare fb_viterbi."""
+def fb_graph_create(K, src, dst, logw, pdf, init, final, D, state_off=None, host_only=False, state="auto") -> Graph:
+    """state: 'auto', 'wide' (double carriers) or 'narrow' (single carriers)."""
     flags = (FB_GRAPH_HOST_ONLY if host_only else 0) | {"auto": 0, "wide": FB_GRAPH_WIDE_STATE, "narrow": FB_GRAPH_NARROW_STATE}[state]
-    flags |= FB_GRAPH_VITERBI if viterbi else 0
     src, dst, logw = _np(src, np.int32), _np(dst, np.int32), _np(logw, np.float32)
     pdf, init, final = _np(pdf, np.int32), _np(init, np.float32), _np(final, np.float32)
     state_off = _np(state_off, np.int32)
@@ -147,9 +145,9 @@ def fb_graph_create(K, src, dst, logw, pdf, init, final, D, state_off=None, host
     return Graph(h, int(K), E, int(D), n_seq, host_only)
 
 
-def graph_from(g, D: int, host_only: bool = False, state: str = "auto", viterbi: bool = False) -> Graph:
+def graph_from(g, D: int, host_only: bool = False, state: str = "auto") -> Graph:
     """Build from an object with fields K, src, dst, logw, pdf, init, final, state_off."""
-    return fb_graph_create(g.K, g.src, g.dst, g.logw, g.pdf, g.init, g.final, D, g.state_off, host_only, state, viterbi)
+    return fb_graph_create(g.K, g.src, g.dst, g.logw, g.pdf, g.init, g.final, D, g.state_off, host_only, state)
 
 
 def fb_graph_layout(g: Graph, name: str) -> np.ndarray:
@@ -252,7 +250,7 @@ def fb_lfmmi_workspace_bytes(den: Graph, num: Graph, B: int, N: int, D: int) -> 
 
 
 def fb_viterbi(g: Graph, emis, lengths, ws=None):
-    """-> (score [B] float64, path [B,N] int32), on the device.  The graph must have been built with viterbi=True."""
+    """-> (score [B] float64, path [B,N] int32), on the device."""
     torch = _torch()
     B, N, D = _dev_inputs(emis, lengths)
     need = int(lib().fb_viterbi_workspace_bytes(g.handle, B, N))

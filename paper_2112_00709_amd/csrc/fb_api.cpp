@@ -219,10 +219,18 @@ int fb_posteriors(const fb_graph *g, const float *alpha, const float *beta, cons
     return run_posteriors(&q, 1, lengths, B, N, D, pdf_post, stream);
 }
 
+// Back-pointer rows: per frame the states and, behind them, the clone slots of the forward plan.
+// shared graph: [B][N][K + Ccap]; packed graphs: [N][K + n_seq * Ccap] (sequence b: its state columns, then
+// its Ccap clone columns at K + b * Ccap).
+static size_t viterbi_bp_ld(const fb_graph *g)
+{
+    return (size_t)g->K + (size_t)(g->n_seq == 0 ? 1 : g->n_seq) * (size_t)g->h_fwd.Ccap;
+}
+
 size_t fb_viterbi_workspace_bytes(const fb_graph *g, int32_t B, int32_t N)
 {
     if (!g || B <= 0 || N <= 0) return 0;
-    const size_t rows = g->n_seq == 0 ? (size_t)B * N * g->K : (size_t)N * g->K;
+    const size_t rows = (g->n_seq == 0 ? (size_t)B * N : (size_t)N) * viterbi_bp_ld(g);
     return align256(rows * sizeof(uint16_t)) + align256((size_t)B * sizeof(int32_t));
 }
 
@@ -231,21 +239,22 @@ int fb_viterbi(const fb_graph *g, const float *emis, const int32_t *lengths, int
 {
     int rc = check_common("fb_viterbi", g, emis, lengths, B, N, D);
     if (rc) return rc;
-    if (!g->viterbi) return fail(FB_EINVAL, "fb_viterbi: the graph was built without FB_GRAPH_VITERBI");
     if (!score || !path) return fail(FB_EINVAL, "fb_viterbi: score or path is NULL");
     if (!ws || ws_bytes < fb_viterbi_workspace_bytes(g, B, N)) return fail(FB_EINVAL, "fb_viterbi: workspace missing or too small");
     if (((uintptr_t)ws & 255) != 0) return fail(FB_EINVAL, "fb_viterbi: workspace must be 256-byte aligned");
-    const size_t rows = g->n_seq == 0 ? (size_t)B * N * g->K : (size_t)N * g->K;
+    const size_t rows = (g->n_seq == 0 ? (size_t)B * N : (size_t)N) * viterbi_bp_ld(g);
     uint16_t *bp = (uint16_t *)ws;
     int32_t *last = (int32_t *)((char *)ws + align256(rows * sizeof(uint16_t)));
     RecDir d = make_dir(g, false, nullptr, false, nullptr, score, 1.0f, false);
-    const bool own_plan = g->h_fwd.Ccap > 0;   // the forward plan has clones: walk the plan built without them
-    d.sched = g->vit;
-    d.Ccap = own_plan ? g->h_vit.Ccap : g->h_fwd.Ccap;
     d.bp = bp;
+    d.bp_ld = (int64_t)viterbi_bp_ld(g);
     d.last = last;
     if ((rc = run_recursion(g, emis, lengths, B, N, D, &d, 1, stream, true))) return rc;
-    return launch_backtrace(bp, last, lengths, g->vit.sub, B, N, g->n_seq == 0, g->K, path, stream);
+    BacktraceParams bt{};
+    bt.bp = bp; bt.bp_ld = d.bp_ld; bt.last = last; bt.lengths = lengths; bt.sched = g->fwd;
+    bt.B = B; bt.N = N; bt.shared = g->n_seq == 0; bt.Ktot = g->K; bt.Kcap = g->max_sub_K; bt.Ccap = g->h_fwd.Ccap;
+    bt.path = path;
+    return launch_backtrace(bt, stream);
 }
 
 size_t fb_lfmmi_workspace_bytes(const fb_graph *den, const fb_graph *num, int32_t B, int32_t N, int32_t D)

@@ -184,7 +184,6 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
     try {
         g->K = K; g->E = E; g->D = D; g->n_seq = n_seq;
         g->host_only = (flags & FB_GRAPH_HOST_ONLY) != 0;
-        g->viterbi = (flags & FB_GRAPH_VITERBI) != 0;
         if (n_seq > 0) g->state_off.assign(state_off, state_off + n_seq + 1);
 
         // ---- graph-layout step: integer work, weights only permuted
@@ -210,8 +209,8 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
         }
         g->nw = (max_sub_E >= 4096 || g->max_sub_K > 1024) ? kNWShared : kNWSmall;
         g->f64 = (flags & FB_GRAPH_WIDE_STATE) ? true : (flags & FB_GRAPH_NARROW_STATE) ? false : g->nw == kNWSmall;
-        SellHost sell_fwd, sell_bwd, sell_vit;   // sliced plans of the recursions, flattened into streams below
-        sell_fwd.nw = sell_bwd.nw = sell_vit.nw = g->nw - 1;   // the last wave of a workgroup moves data, the others walk arcs
+        SellHost sell_fwd, sell_bwd;   // sliced plans of the two recursions, flattened into streams below
+        sell_fwd.nw = sell_bwd.nw = g->nw - 1;   // the last wave of a workgroup moves data, the others walk arcs
 
         std::vector<int64_t> ptr;
         std::vector<int32_t> col, vid;
@@ -231,9 +230,7 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
                     col[(size_t)(e - e0)] = other[(size_t)e] - k0;
                     w[(size_t)(e - e0)] = to_log2(ww[(size_t)e]);
                 }
-                sell_append(dir ? sell_bwd : sell_fwd, k0, Ks, ptr.data(), col.data(), w.data(), vid.data(), true);
-                if (dir == 0 && g->viterbi)
-                    sell_append(sell_vit, k0, Ks, ptr.data(), col.data(), w.data(), vid.data(), false);
+                sell_append(dir ? sell_bwd : sell_fwd, k0, Ks, ptr.data(), col.data(), w.data(), vid.data());
             }
             // states grouped by pdf: one row per pdf (every pdf for a shared graph, the pdfs the
             // sub-graph uses for packed graphs), states in ascending order inside a row
@@ -278,14 +275,6 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
                 rc = fail(FB_EUNSUPPORTED, "graph too large: " + why);
             else if (!stream_in_bounds(g->h_fwd, nv, why) || !stream_in_bounds(g->h_bwd, nv, why))
                 rc = fail(FB_EHIP, "internal error: stream out of bounds (" + why + ")");
-            if (rc == FB_OK && g->viterbi && g->h_fwd.Ccap > 0) {   // else fb_viterbi walks the forward plan itself
-                if (!sell_in_bounds(sell_vit, nv, why))
-                    rc = fail(FB_EHIP, "internal error: schedule out of bounds (" + why + ")");
-                else if (!stream_from_sell(sell_vit, g->max_sub_K, n_seq > 0 ? g->max_sub_K : D, g->h_vit, why))
-                    rc = fail(FB_EUNSUPPORTED, "graph too large: " + why);
-                else if (!stream_in_bounds(g->h_vit, nv, why))
-                    rc = fail(FB_EHIP, "internal error: stream out of bounds (" + why + ")");
-            }
         }
         const int32_t Ccap = std::max(g->h_fwd.Ccap, g->h_bwd.Ccap);
         const int32_t Ecap = n_seq > 0 ? g->max_sub_K : D;
@@ -306,10 +295,6 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
             if (!(rc = upload(g, hp, &dp)) && !(rc = upload(g, i2, &di)) && !(rc = upload(g, f2, &df)) &&
                 !(rc = upload_stream(g, g->h_fwd, g->fwd)) && !(rc = upload_stream(g, g->h_bwd, g->bwd)))
                 rc = upload_pdf(g, g->h_pdf, g->pdfs);
-            if (rc == FB_OK && g->viterbi) {
-                if (g->h_fwd.Ccap > 0) rc = upload_stream(g, g->h_vit, g->vit);
-                else g->vit = g->fwd;
-            }
             g->d_pdf = const_cast<int32_t *>(dp); g->d_init2 = const_cast<float *>(di); g->d_final2 = const_cast<float *>(df);
         }
     } catch (const std::bad_alloc &) {
@@ -356,9 +341,8 @@ static const void *layout_array(const fb_graph *g, int which, int64_t *n)
 int fb_graph_schedule_apply_host(const fb_graph *g, int which, int32_t sub, const double *x, double *y)
 {
     if (!g || !x || !y) return fail(FB_EINVAL, "fb_graph_schedule_apply_host: NULL argument");
-    if (which < 0 || which > 3 || sub < 0 || (size_t)sub >= g->h_pdf.sub.size())
+    if (which < 0 || which > 2 || sub < 0 || (size_t)sub >= g->h_pdf.sub.size())
         return fail(FB_EINVAL, "fb_graph_schedule_apply_host: unknown schedule or sub-graph");
-    if (which == 3 && !g->viterbi) return fail(FB_EINVAL, "fb_graph_schedule_apply_host: graph built without FB_GRAPH_VITERBI");
     if (which == 2) {
         const PdfHost &PH = g->h_pdf;
         const PdfSub &ps = PH.sub[(size_t)sub];
@@ -369,7 +353,7 @@ int fb_graph_schedule_apply_host(const fb_graph *g, int which, int32_t sub, cons
             y[PH.row_pdf[(size_t)ps.row0 + r]] = acc;
         }
     } else {
-        stream_apply_host(which == 0 ? g->h_fwd : which == 1 ? g->h_bwd : (g->h_fwd.Ccap > 0 ? g->h_vit : g->h_fwd), sub, x, y);
+        stream_apply_host(which == 0 ? g->h_fwd : g->h_bwd, sub, x, y);
     }
     return FB_OK;
 }

@@ -73,7 +73,7 @@ struct SellHost {
 // rows [0, K) of a CSR-like matrix over K columns: entries ptr[r]..ptr[r+1] with column col[] and
 // weight w[] (log2 units); row_vidx[r] = emission index of row r.  Appends one sub-plan to `out`.
 void sell_append(SellHost &out, int32_t k0, int32_t K, const int64_t *ptr, const int32_t *col, const float *w,
-                 const int32_t *row_vidx, bool allow_clones);
+                 const int32_t *row_vidx);
 
 bool sell_in_bounds(const SellHost &S, int32_t n_vidx, std::string &why);
 
@@ -174,11 +174,9 @@ struct fb_graph {
     fb::HostLayout lay;
     std::vector<int32_t> state_off;   // packed only
     fb::StreamHost h_fwd, h_bwd;      // host schedules of the two recursions
-    fb::StreamHost h_vit;             // forward schedule without clones (FB_GRAPH_VITERBI and h_fwd has clones)
-    bool viterbi = false;             // FB_GRAPH_VITERBI was given
     fb::PdfHost h_pdf;                // states grouped by pdf, for the posterior accumulation
     // device
-    fb::StreamDev fwd, bwd, vit;      // vit: what fb_viterbi walks (= fwd when that has no clones)
+    fb::StreamDev fwd, bwd;
     fb::PdfDev pdfs;
     int32_t *d_pdf = nullptr;         // [K]
     float *d_init2 = nullptr;         // [K] init * log2(e)
@@ -204,7 +202,8 @@ struct RecDir {
     int32_t Ccap;          // clone slots of this direction's schedule
     int backward;
     int fill_pad;          // write -inf / 0 into the rows of padded frames
-    uint16_t *bp;          // tropical semiring: back-pointers, laid out like a vector output, nullable otherwise
+    uint16_t *bp;          // tropical semiring: back-pointers (see fb_viterbi in fb_api.cpp for the layout), else NULL
+    int64_t bp_ld;         // elements per frame row of bp
     int32_t *last;         // tropical semiring: [B] local id of the best end state (-1: none)
 };
 
@@ -239,8 +238,16 @@ struct PostParams {
 };
 
 int launch_recursion(int nw, bool f64, bool tropical, const RecParams &p, size_t lds_bytes, void *stream);
-int launch_backtrace(const uint16_t *bp, const int32_t *last, const int32_t *lengths, const SubDesc *sub, int32_t B,
-                     int32_t N, int32_t shared, int32_t Ktot, int32_t *path, void *stream);
+struct BacktraceParams {
+    const uint16_t *bp;      // back-pointers written by the recursion kernel
+    int64_t bp_ld;           // elements per frame row
+    const int32_t *last;     // [B] best end state in the kernel's index space, -1: none
+    const int32_t *lengths;
+    StreamDev sched;         // the forward plan (sub-graphs, clones)
+    int32_t B, N, shared, Ktot, Kcap, Ccap;
+    int32_t *path;           // [B][N]
+};
+int launch_backtrace(const BacktraceParams &p, void *stream);
 int launch_posteriors(const PostParams &p, size_t lds_bytes, void *stream);
 bool gradient_kernel_applies(const PostParams &p);
 size_t gradient_lds_bytes(const PostParams &p);

@@ -292,12 +292,15 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
             }
     };
 
-    // tropical semiring: the back-pointers of frame f (f >= 1) -> global memory
-    uint16_t *bp_seq = (TROP && R.bp) ? R.bp + out_at : nullptr;
+    // tropical semiring: the back-pointers of frame f (f >= 1) -> global memory; a row holds the states
+    // and, behind them, the clone slots (a back-pointer is an index into the state buffer: a state, or
+    // Kcap + slot for a clone)
     auto write_bp = [&](int f, const uint16_t *srcb) {
-        if (bp_seq) {
-            uint16_t *orow = bp_seq + (size_t)f * out_ld;
-            for (int k = lane; k < K; k += kWave) orow[k] = srcb[k];
+        if (TROP && R.bp) {
+            uint16_t *orow = R.bp + (P.shared ? ((size_t)b * P.N + f) * R.bp_ld : (size_t)f * R.bp_ld);
+            uint16_t *ost = orow + (P.shared ? 0 : k0), *ocl = orow + (P.shared ? K : P.Ktot + b * R.Ccap);
+            for (int k = lane; k < K; k += kWave) ost[k] = srcb[k];
+            for (int j = lane; j < nC; j += kWave) ocl[j] = srcb[P.Kcap + j];
         }
     };
 
@@ -498,6 +501,13 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
             for (int k = tid; k < K; k += NT) {
                 const T t = xl[k] + (T)R.obound[k0 + k];
                 if (t > m) { m = t; at = k; }
+            }
+            for (int j = tid; j < sd.n_cdesc; j += NT) {   // clones end with their state's weight
+                const CloneDesc cd = cdesc[j];
+                for (int i = 0; i < cd.count; ++i) {
+                    const T t = xl[P.Kcap + cd.first + i] + (T)R.obound[k0 + cd.state];
+                    if (t > m || (t == m && P.Kcap + cd.first + i < at)) { m = t; at = P.Kcap + cd.first + i; }
+                }
             }
 #pragma unroll
             for (int o = 32; o >= 1; o >>= 1) {
@@ -988,22 +998,31 @@ __global__ __launch_bounds__(256) void fb_loss_kernel(const double *zn, const do
 }
 
 // Best path from the back-pointers: one thread per sequence walks from the best end state to frame 0.
-// bp: [B][N][K] (shared graph) or [N][Ktot] (packed graphs), row n holding the predecessors of frame n.
-__global__ __launch_bounds__(64) void fb_backtrace_kernel(const uint16_t *bp, const int32_t *last, const int32_t *lengths,
-                                                          const SubDesc *sub, int32_t B, int32_t N, int32_t shared,
-                                                          int32_t Ktot, int32_t *path)
+// Indices are those of the state buffer (a state, or Kcap + slot for a clone of a very long row); a clone
+// is reported as the state it belongs to.
+__global__ __launch_bounds__(64) void fb_backtrace_kernel(const BacktraceParams P)
 {
     const int b = blockIdx.x * 64 + threadIdx.x;
-    if (b >= B) return;
-    const SubDesc sd = sub[shared ? 0 : b];
-    const int T = min(max(lengths[b], 0), N);
-    int32_t *prow = path + (size_t)b * N;
-    int s = T > 0 ? last[b] : -1;
-    for (int n = T; n < N; ++n) prow[n] = -1;
+    if (b >= P.B) return;
+    const SubDesc sd = P.sched.sub[P.shared ? 0 : b];
+    const CloneDesc *cdesc = P.sched.clones + sd.clone0;
+    const int T = min(max(P.lengths[b], 0), P.N);
+    int32_t *prow = P.path + (size_t)b * P.N;
+    int s = T > 0 ? P.last[b] : -1;
+    for (int n = T; n < P.N; ++n) prow[n] = -1;
     for (int n = T - 1; n >= 0; --n) {
-        prow[n] = s < 0 ? -1 : sd.k0 + s;
-        if (n > 0 && s >= 0)
-            s = shared ? bp[((size_t)b * N + n) * sd.K + s] : bp[(size_t)n * Ktot + sd.k0 + s];
+        if (s < 0) { prow[n] = -1; continue; }
+        int state = s;
+        int64_t col = (P.shared ? 0 : sd.k0) + s;
+        if (s >= P.Kcap) {   // a clone slot
+            const int slot = s - P.Kcap;
+            state = 0;
+            for (int j = 0; j < sd.n_cdesc; ++j)
+                if (slot >= cdesc[j].first && slot < cdesc[j].first + cdesc[j].count) state = cdesc[j].state;
+            col = (P.shared ? sd.K : (int64_t)P.Ktot + (int64_t)b * P.Ccap) + slot;
+        }
+        prow[n] = sd.k0 + state;
+        if (n > 0) s = P.bp[(P.shared ? ((size_t)b * P.N + n) : (size_t)n) * P.bp_ld + col];
     }
 }
 
@@ -1044,11 +1063,9 @@ int launch_recursion(int nw, bool f64, bool tropical, const RecParams &p, size_t
                : launch_rec(fb_recursion_kernel<kNWSmall, float, false>, nw, p, lds_bytes, stream);
 }
 
-int launch_backtrace(const uint16_t *bp, const int32_t *last, const int32_t *lengths, const SubDesc *sub, int32_t B,
-                     int32_t N, int32_t shared, int32_t Ktot, int32_t *path, void *stream)
+int launch_backtrace(const BacktraceParams &p, void *stream)
 {
-    hipLaunchKernelGGL(fb_backtrace_kernel, dim3((unsigned)((B + 63) / 64)), dim3(64), 0, (hipStream_t)stream, bp, last,
-                       lengths, sub, B, N, shared, Ktot, path);
+    hipLaunchKernelGGL(fb_backtrace_kernel, dim3((unsigned)((p.B + 63) / 64)), dim3(64), 0, (hipStream_t)stream, p);
     return check_launch("backtrace kernel launch");
 }
 

@@ -47,7 +47,7 @@ int32_t slice_batches(int32_t trip) { return trip / kBatchRows + 1; }
 }  // namespace
 
 void sell_append(SellHost &S, int32_t k0, int32_t K, const int64_t *ptr, const int32_t *col, const float *w,
-                 const int32_t *row_vidx, bool allow_clones)
+                 const int32_t *row_vidx)
 {
     const int nw = S.nw;
     SubDesc sd{};
@@ -63,7 +63,7 @@ void sell_append(SellHost &S, int32_t k0, int32_t K, const int64_t *ptr, const i
     int32_t n_slot = 0;
     for (int32_t r = 0; r < K; ++r) {
         const int64_t n = ptr[r + 1] - ptr[r];
-        if (n <= row_cap || !allow_clones) continue;   // without clones a long row keeps 64 lanes and walks longer
+        if (n <= row_cap) continue;
         n_share[r] = (int32_t)((n + row_cap - 1) / row_cap);
         first_slot[r] = n_slot;
         S.clones.push_back(CloneDesc{r, n_slot, n_share[r] - 1, 0});

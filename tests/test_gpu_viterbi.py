@@ -27,7 +27,7 @@ def check(fb, g, D, emis, lengths, name, sel=None, state="auto"):
     sel = list(range(B)) if sel is None else list(sel)
     print(f"[gpu-case] viterbi {name}: B={B} N={N} D={D} K={g.K} E={g.E} state={state}", flush=True)
     ref = oracle.viterbi(g, emis, lengths, sel=sel)
-    G = fb.graph_from(g, D, state=state, viterbi=True)
+    G = fb.graph_from(g, D, state=state)
     score, path = fb.fb_viterbi(G, torch.from_numpy(emis).cuda(), torch.from_numpy(lengths.astype(np.int32)).cuda())
     torch.cuda.synchronize()
     score, path = score.cpu().numpy(), path.cpu().numpy()
@@ -54,11 +54,20 @@ def test_viterbi_small_configurations(fb):
     w = wl.ctc_workload(); check(fb, w.num, w.D, w.emis, w.lengths, "ctc")
 
 
-def test_viterbi_hub_graph_without_clones(fb):
-    """Rows longer than 4096 arcs stay whole in the plan fb_viterbi walks (a back-pointer must name a state)."""
+def test_viterbi_hub_graphs_with_clones(fb):
+    """The longest rows are computed as clone states; a back-pointer may name a clone, the path names its state."""
     w = wl.config4(K=3500, B=3, Nmin=10, Nmax=25, D=300)
     check(fb, w.den, w.D, w.emis, w.lengths, "config4 K=3500")
     check(fb, w.den, w.D, w.emis, w.lengths, "config4 K=3500, double vectors", state="wide")
+    rng = np.random.default_rng(11)
+    gs = [wl.random_graph(rng, K, 64, zipf_s=1.3) for K in (2200, 1700)]
+    off = np.array([0, 2200, 3900], np.int32)
+    g = wl.Graph(K=3900, src=np.concatenate([gs[0].src, gs[1].src + 2200]).astype(np.int32),
+                 dst=np.concatenate([gs[0].dst, gs[1].dst + 2200]).astype(np.int32),
+                 logw=np.concatenate([gs[0].logw, gs[1].logw]), pdf=np.concatenate([gs[0].pdf, gs[1].pdf]),
+                 init=np.concatenate([gs[0].init, gs[1].init]), final=np.concatenate([gs[0].final, gs[1].final]), state_off=off)
+    emis = (rng.standard_normal((2, 14, 64)) * 2).astype(np.float32)
+    check(fb, g, 64, emis, np.array([14, 9], np.int32), "packed hub graphs with clones")
 
 
 def test_viterbi_config4_full_size_sampled(fb):
@@ -82,13 +91,3 @@ def test_viterbi_edge_cases(fb):
     g2 = wl.tiny_graph(9, 6, 4)
     e2 = rng.normal(size=(2, 7, 4)).astype(np.float32)
     check(fb, g2, 4, e2, np.array([7, 5], np.int32), "tiny graph with -inf entries")
-
-
-def test_viterbi_needs_the_flag(fb):
-    import torch
-    w = wl.config1()
-    G = fb.graph_from(w.den, w.D)
-    with pytest.raises(fb.FBError) as e:
-        fb.fb_viterbi(G, torch.from_numpy(w.emis).cuda(), torch.from_numpy(w.lengths).cuda())
-    assert e.value.code == fb.FB_EINVAL
-    G.destroy()

@@ -109,14 +109,6 @@ def test_kernel_schedule_computes_the_sparse_products(case):
             fin = np.isfinite(want)
             assert np.array_equal(np.isneginf(y), np.isneginf(want))
             np.testing.assert_allclose(y[fin], want[fin], rtol=0, atol=1e-9)
-        if case == "zipf_clones":      # the plan of fb_viterbi keeps the longest rows whole (no clones)
-            hv = fb.graph_from(g, w.D, host_only=True, viterbi=True)
-            y = fb.fb_graph_schedule_apply_host(hv, 3, sub, x, np.full(Ks, 123.0))
-            want = _direct_product(Ks, dst, src, ww, x)
-            fin = np.isfinite(want)
-            assert np.array_equal(np.isneginf(y), np.isneginf(want))
-            np.testing.assert_allclose(y[fin], want[fin], rtol=0, atol=1e-9)
-            hv.destroy()
         gam = rng.random(Ks)
         y = fb.fb_graph_schedule_apply_host(h, 2, sub, gam, np.zeros(w.D))
         want = np.bincount(g.pdf[k0:k1], weights=gam, minlength=w.D)
