@@ -199,7 +199,9 @@ def main() -> int:
         "config": {"workload": "config5: LF-MMI loss+grad, Zipf denominator K=6000 E~60k shared by B=128, "
                                "128 packed numerator chains, D=3000, N_b=round(3.6 L_b)",
                    "B": w.B, "N_max": w.N, "frames": frames, "D": w.D,
-                   "den_states": w.den.K, "den_arcs": w.den.E, "num_states": w.num.K, "num_arcs": w.num.E},
+                   "den_states": w.den.K, "den_arcs": w.den.E, "num_states": w.num.K, "num_arcs": w.num.E,
+                   # arcs the compute plans walk per step: parallel arcs (same source and destination) are merged
+                   "den_plan_arcs": int(np.unique(w.den.src.astype(np.int64) * w.den.K + w.den.dst).size)},
         "lfmmi_ms_per_batch": ms_per_step,
         "ms_per_step_median": single[len(single) // 2], "ms_per_step_min": single[0],
         "graph_create_s": graph_create_s,

@@ -224,7 +224,7 @@ int fb_posteriors(const fb_graph *g, const float *alpha, const float *beta, cons
 // its Ccap clone columns at K + b * Ccap).
 static size_t viterbi_bp_ld(const fb_graph *g)
 {
-    return (size_t)g->K + (size_t)(g->n_seq == 0 ? 1 : g->n_seq) * (size_t)g->h_fwd.Ccap;
+    return (size_t)g->K + (size_t)(g->n_seq == 0 ? 1 : g->n_seq) * (size_t)(g->own_trop ? g->h_trop : g->h_fwd).Ccap;
 }
 
 size_t fb_viterbi_workspace_bytes(const fb_graph *g, int32_t B, int32_t N)
@@ -246,13 +246,15 @@ int fb_viterbi(const fb_graph *g, const float *emis, const int32_t *lengths, int
     uint16_t *bp = (uint16_t *)ws;
     int32_t *last = (int32_t *)((char *)ws + align256(rows * sizeof(uint16_t)));
     RecDir d = make_dir(g, false, nullptr, false, nullptr, score, 1.0f, false);
+    d.sched = g->trop;
+    d.Ccap = (g->own_trop ? g->h_trop : g->h_fwd).Ccap;
     d.bp = bp;
     d.bp_ld = (int64_t)viterbi_bp_ld(g);
     d.last = last;
     if ((rc = run_recursion(g, emis, lengths, B, N, D, &d, 1, stream, true))) return rc;
     BacktraceParams bt{};
-    bt.bp = bp; bt.bp_ld = d.bp_ld; bt.last = last; bt.lengths = lengths; bt.sched = g->fwd;
-    bt.B = B; bt.N = N; bt.shared = g->n_seq == 0; bt.Ktot = g->K; bt.Kcap = g->max_sub_K; bt.Ccap = g->h_fwd.Ccap;
+    bt.bp = bp; bt.bp_ld = d.bp_ld; bt.last = last; bt.lengths = lengths; bt.sched = g->trop;
+    bt.B = B; bt.N = N; bt.shared = g->n_seq == 0; bt.Ktot = g->K; bt.Kcap = g->max_sub_K; bt.Ccap = d.Ccap;
     bt.path = path;
     return launch_backtrace(bt, stream);
 }

@@ -40,6 +40,45 @@ void stable_group(const int32_t *keys, int64_t n, int32_t n_keys, std::vector<in
 
 float to_log2(float x) { return (float)((double)x * kLog2e); }   // -inf stays -inf
 
+// rows [0, K) of a CSR-like matrix with parallel entries (same row and column) combined: (+) of the log
+// semiring (log2 of the sum of the powers of two, in double) or, tropical, their maximum.  Columns come out
+// in ascending order inside a row.  Returns whether anything was combined.
+bool merge_parallel(int32_t K, const std::vector<int64_t> &ptr, const std::vector<int32_t> &col, const std::vector<float> &w,
+                    bool tropical, std::vector<int64_t> &mptr, std::vector<int32_t> &mcol, std::vector<float> &mw)
+{
+    mptr.assign((size_t)K + 1, 0);
+    mcol.clear();
+    mw.clear();
+    bool any = false;
+    std::vector<std::pair<int32_t, float>> row;
+    for (int32_t r = 0; r < K; ++r) {
+        row.clear();
+        for (int64_t e = ptr[r]; e < ptr[r + 1]; ++e) row.emplace_back(col[(size_t)e], w[(size_t)e]);
+        std::stable_sort(row.begin(), row.end(), [](const std::pair<int32_t, float> &a, const std::pair<int32_t, float> &b) {
+            return a.first < b.first;
+        });
+        for (size_t i = 0; i < row.size();) {
+            size_t j = i + 1;
+            double m = row[i].second;
+            while (j < row.size() && row[j].first == row[i].first) m = std::max(m, (double)row[j++].second);
+            double v = m;
+            if (j > i + 1) {
+                any = true;
+                if (!tropical && m != -INFINITY) {
+                    double s = 0.0;
+                    for (size_t t = i; t < j; ++t) s += std::exp2((double)row[t].second - m);
+                    v = m + std::log2(s);
+                }
+            }
+            mcol.push_back(row[i].first);
+            mw.push_back((float)v);
+            i = j;
+        }
+        mptr[(size_t)r + 1] = (int64_t)mcol.size();
+    }
+    return any;
+}
+
 template <class T>
 int upload(fb_graph *g, const std::vector<T> &h, const T **dev)
 {
@@ -209,8 +248,9 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
         }
         g->nw = (max_sub_E >= 4096 || g->max_sub_K > 1024) ? kNWShared : kNWSmall;
         g->f64 = (flags & FB_GRAPH_WIDE_STATE) ? true : (flags & FB_GRAPH_NARROW_STATE) ? false : g->nw == kNWSmall;
-        SellHost sell_fwd, sell_bwd;   // sliced plans of the two recursions, flattened into streams below
-        sell_fwd.nw = sell_bwd.nw = g->nw - 1;   // the last wave of a workgroup moves data, the others walk arcs
+        SellHost sell_fwd, sell_bwd, sell_trop;   // sliced plans of the recursions, flattened into streams below
+        sell_fwd.nw = sell_bwd.nw = sell_trop.nw = g->nw - 1;   // the last wave of a workgroup moves data, the others walk arcs
+        bool any_parallel = false;
 
         std::vector<int64_t> ptr;
         std::vector<int32_t> col, vid;
@@ -230,7 +270,19 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
                     col[(size_t)(e - e0)] = other[(size_t)e] - k0;
                     w[(size_t)(e - e0)] = to_log2(ww[(size_t)e]);
                 }
-                sell_append(dir ? sell_bwd : sell_fwd, k0, Ks, ptr.data(), col.data(), w.data(), vid.data());
+                // The plans carry one arc per (row, column): parallel arcs are (+)-added here, once, in double
+                // (the exported layout keeps them apart).  The two semirings add differently, so the best-path
+                // plan is a plan of its own as soon as the graph has parallel arcs.
+                std::vector<int64_t> mptr;
+                std::vector<int32_t> mcol;
+                std::vector<float> mw;
+                const bool dup = merge_parallel(Ks, ptr, col, w, false, mptr, mcol, mw);
+                sell_append(dir ? sell_bwd : sell_fwd, k0, Ks, mptr.data(), mcol.data(), mw.data(), vid.data());
+                if (dir == 0) {
+                    any_parallel = any_parallel || dup;
+                    merge_parallel(Ks, ptr, col, w, true, mptr, mcol, mw);
+                    sell_append(sell_trop, k0, Ks, mptr.data(), mcol.data(), mw.data(), vid.data());
+                }
             }
             // states grouped by pdf: one row per pdf (every pdf for a shared graph, the pdfs the
             // sub-graph uses for packed graphs), states in ascending order inside a row
@@ -275,6 +327,15 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
                 rc = fail(FB_EUNSUPPORTED, "graph too large: " + why);
             else if (!stream_in_bounds(g->h_fwd, nv, why) || !stream_in_bounds(g->h_bwd, nv, why))
                 rc = fail(FB_EHIP, "internal error: stream out of bounds (" + why + ")");
+            g->own_trop = any_parallel;
+            if (rc == FB_OK && g->own_trop) {
+                if (!sell_in_bounds(sell_trop, nv, why))
+                    rc = fail(FB_EHIP, "internal error: schedule out of bounds (" + why + ")");
+                else if (!stream_from_sell(sell_trop, g->max_sub_K, n_seq > 0 ? g->max_sub_K : D, g->h_trop, why))
+                    rc = fail(FB_EUNSUPPORTED, "graph too large: " + why);
+                else if (!stream_in_bounds(g->h_trop, nv, why))
+                    rc = fail(FB_EHIP, "internal error: stream out of bounds (" + why + ")");
+            }
         }
         const int32_t Ccap = std::max(g->h_fwd.Ccap, g->h_bwd.Ccap);
         const int32_t Ecap = n_seq > 0 ? g->max_sub_K : D;
@@ -295,6 +356,10 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
             if (!(rc = upload(g, hp, &dp)) && !(rc = upload(g, i2, &di)) && !(rc = upload(g, f2, &df)) &&
                 !(rc = upload_stream(g, g->h_fwd, g->fwd)) && !(rc = upload_stream(g, g->h_bwd, g->bwd)))
                 rc = upload_pdf(g, g->h_pdf, g->pdfs);
+            if (rc == FB_OK) {
+                if (g->own_trop) rc = upload_stream(g, g->h_trop, g->trop);
+                else g->trop = g->fwd;
+            }
             g->d_pdf = const_cast<int32_t *>(dp); g->d_init2 = const_cast<float *>(di); g->d_final2 = const_cast<float *>(df);
         }
     } catch (const std::bad_alloc &) {

@@ -14,7 +14,7 @@ constexpr int kWave = 64;            // gfx950 wavefront
 constexpr int kNWShared = 16;        // waves per workgroup, large (sub-)graphs
 constexpr int kNWSmall = 4;          // waves per workgroup, small (sub-)graphs
 constexpr int kChunk = 32;           // arcs one lane walks for a row that has a lane to itself; longer rows get more lanes
-constexpr int kChunkWide = 64;       // arcs one lane walks for a row spread over several lanes
+constexpr int kChunkWide = 32;       // arcs one lane walks for a row spread over several lanes
 constexpr size_t kLdsBytes = 160 * 1024;
 constexpr size_t kLdsReserve = 1024; // reduction slots etc.
 
@@ -98,7 +98,7 @@ bool sell_in_bounds(const SellHost &S, int32_t n_vidx, std::string &why);
 // ---------------------------------------------------------------------------
 constexpr int kBatchRows = 4;
 constexpr int kRing = 3;                        // batches per unrolled iteration = prefetch ring size
-constexpr int kResident = 6;                    // batches per wave and step that stay in registers (<= 8)
+constexpr int kResident = 7;                    // batches per wave and step that stay in registers (<= 8)
 constexpr uint32_t kFlagInfo = 0x01;            // the batch's last row is an info row
 constexpr uint32_t kFlagSkip = 0x04;            // nothing to do in this batch (padding)
 constexpr int kFlagLgShift = 3;                 // bits 3-5 of an info batch: log2 of the lanes per row
@@ -174,9 +174,11 @@ struct fb_graph {
     fb::HostLayout lay;
     std::vector<int32_t> state_off;   // packed only
     fb::StreamHost h_fwd, h_bwd;      // host schedules of the two recursions
+    fb::StreamHost h_trop;            // forward schedule of the tropical semiring, when it differs (own_trop)
+    bool own_trop = false;            // the graph has parallel arcs: they combine by max there, not by (+)
     fb::PdfHost h_pdf;                // states grouped by pdf, for the posterior accumulation
     // device
-    fb::StreamDev fwd, bwd;
+    fb::StreamDev fwd, bwd, trop;     // trop = fwd unless own_trop
     fb::PdfDev pdfs;
     int32_t *d_pdf = nullptr;         // [K]
     float *d_init2 = nullptr;         // [K] init * log2(e)

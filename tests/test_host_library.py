@@ -103,12 +103,14 @@ def test_kernel_schedule_computes_the_sparse_products(case):
         x[rng.integers(0, Ks)] = -np.inf
         inside = (g.src >= k0) & (g.src < k1)
         src, dst, ww = g.src[inside] - k0, g.dst[inside] - k0, w2[inside]
+        parallel = np.unique(src.astype(np.int64) * Ks + dst).size < src.size
         for which, rows, cols in ((0, dst, src), (1, src, dst)):
             y = fb.fb_graph_schedule_apply_host(h, which, sub, x, np.full(Ks, 123.0))
             want = _direct_product(Ks, rows, cols, ww, x)
             fin = np.isfinite(want)
             assert np.array_equal(np.isneginf(y), np.isneginf(want))
-            np.testing.assert_allclose(y[fin], want[fin], rtol=0, atol=1e-9)
+            # the plans hold the (+)-sum of parallel arcs rounded to float once more: 1e-6 where a graph has any
+            np.testing.assert_allclose(y[fin], want[fin], rtol=0, atol=1e-6 if parallel else 1e-9)
         gam = rng.random(Ks)
         y = fb.fb_graph_schedule_apply_host(h, 2, sub, gam, np.zeros(w.D))
         want = np.bincount(g.pdf[k0:k1], weights=gam, minlength=w.D)
