@@ -111,6 +111,7 @@ int upload_stream(fb_graph *g, const StreamHost &h, StreamDev &d)
     if ((rc = upload(g, h.sub, &d.sub))) return rc;
     if ((rc = upload(g, h.waves, &d.waves))) return rc;
     if ((rc = upload(g, h.flagwords, &d.flagwords))) return rc;
+    if ((rc = upload(g, h.vix, &d.vix))) return rc;
     if ((rc = upload(g, h.clones, &d.clones))) return rc;
     if ((rc = upload(g, h.zero_rows, &d.zero_rows))) return rc;
     return upload(g, h.arcs, &d.arcs);
@@ -121,10 +122,11 @@ int upload_stream(fb_graph *g, const StreamHost &h, StreamDev &d)
 size_t recursion_lds_bytes(int32_t Kcap, int32_t Ccap, int32_t Ecap, bool backward, bool f64, bool shared, bool tropical)
 {
     // carrier-typed: state buffers (states, clone slots, a dump slot) and reduction slots;
-    // then three emission rows (float, plus a zero slot) and, for packed graphs, a pdf id per state
+    // then three emission rows (float, plus a zero slot), for packed graphs a pdf id per state, the emission index table
     const size_t xs = (size_t)Kcap + (size_t)Ccap + 1;
     return (xs * (backward ? 4 : 2) + 4 * kNWShared + 2) * (f64 ? 8 : 4) + ((size_t)Ecap + 1) * 12 +
-           (shared ? 0 : (size_t)Ecap * 4) + (tropical ? xs * 4 : 0) + kLdsReserve;   // tropical: two rows of 16-bit back-pointers
+           (shared ? 0 : (size_t)Ecap * 4) + (tropical ? xs * 4 : 0) + ((xs + 1) & ~(size_t)1) * 2 +
+           kLdsReserve;   // tropical: two rows of 16-bit back-pointers; always: the 16-bit emission index of every target
 }
 
 size_t posterior_lds_bytes(const PostParams &p)
@@ -162,7 +164,7 @@ int32_t fb_limits_max_states(int32_t D, int shared)
     // backward recursion: four state vectors, clone slots (allow K/8), three emission rows
     // (D entries for a shared graph, one per state for packed graphs)
     const double avail = (double)kLdsBytes - (double)kLdsReserve - (shared ? 12.0 * D : 0.0);
-    const double per_state = 4.0 * (4.0 + 0.125 + (shared ? 0.0 : 4.0));
+    const double per_state = 4.0 * (4.0 + 0.125 + (shared ? 0.0 : 4.0)) + 2.0 * 1.125;   // + the 16-bit emission index table
     const double k = avail / per_state;
     return k < 1 ? 0 : (int32_t)k;
 }

@@ -82,26 +82,27 @@ bool sell_in_bounds(const SellHost &S, int32_t n_vidx, std::string &why);
 // workgroup that walks arcs owns one contiguous, cyclic stream of "rows" of 64
 // entries (one per lane), grouped in batches of kBatchRows rows.  A row is 64 arcs
 // (one per lane: gather, add the weight, fold into the lane's running sum), except
-// that the last row of a batch may be an info row that closes the slice: its
-// entries say where each lane's finished sum goes and which staged emission it
-// takes.  Slices are padded with zero-weight (-inf) arcs so that their info row
-// falls on the last row of a batch.  A byte of flags per batch tells whether it
-// ends with an info row, whether it is padding to skip, and over how many lanes
+// that the last entry of a lane in a slice also says where the lane's finished sum
+// goes: the slice's arcs are padded with zero-weight (-inf) arcs to whole batches,
+// and the source field of every lane's entry in the last row of the slice's last
+// batch carries the target in its upper half.  A byte of flags per batch tells
+// whether it closes a slice, whether it is padding to skip, and over how many lanes
 // the sums of a row are spread.  The stream of one time step is the same every
 // step, so the kernel keeps it kRing-1 batches ahead of its use, across barriers
 // and across steps.
 //
-// Info entry (in the weight field): low 16 bits = target index in the state
-// buffer of the step being written, [0, K) a state, Kcap + slot a clone slot,
-// Kcap + Ccap the dump slot of lanes that write nothing; high 16 bits = index of
-// the emission in the staged emission vector, Ecap being a slot that always holds 0.
+// Closing entry: src = source index (low 16 bits) | target << 16; the target is an
+// index into the state buffer of the step being written, [0, K) a state, Kcap + slot
+// a clone slot, Kcap + Ccap the dump slot of lanes that write nothing.  The emission
+// a target takes is looked up in a table over the same index space (vix: index into
+// the staged emission vector, Ecap being a slot that always holds 0).
 // ---------------------------------------------------------------------------
 constexpr int kBatchRows = 4;
 constexpr int kRing = 3;                        // batches per unrolled iteration = prefetch ring size
 constexpr int kResident = 7;                    // batches per wave and step that stay in registers (<= 8)
-constexpr uint32_t kFlagInfo = 0x01;            // the batch's last row is an info row
+constexpr uint32_t kFlagInfo = 0x01;            // the batch closes a slice: its last row carries the targets
 constexpr uint32_t kFlagSkip = 0x04;            // nothing to do in this batch (padding)
-constexpr int kFlagLgShift = 3;                 // bits 3-5 of an info batch: log2 of the lanes per row
+constexpr int kFlagLgShift = 3;                 // bits 3-5 of a closing batch: log2 of the lanes per row
 
 struct WaveDesc {
     int64_t arc_base;    // first entry of the wave's stream in `arcs`
@@ -115,10 +116,11 @@ struct StreamHost {
     std::vector<SubDesc> sub;          // wave_ptr0 = index of the sub-graph's first WaveDesc
     std::vector<WaveDesc> waves;
     std::vector<uint32_t> flagwords;
-    std::vector<Arc> arcs;             // info entries: src = 0, w = bits of (target16 | vidx16 << 16)
+    std::vector<Arc> arcs;
+    std::vector<uint16_t> vix;         // per sub-graph, Kcap + Ccap + 1 entries: emission index of every target
     std::vector<CloneDesc> clones;
     std::vector<int32_t> zero_rows;
-    int32_t Kcap = 0, Ccap = 0, Ecap = 0;   // index space of the info entries (see above)
+    int32_t Kcap = 0, Ccap = 0, Ecap = 0;   // index space of targets and emission indices (see above)
 };
 
 struct StreamDev {
@@ -126,6 +128,7 @@ struct StreamDev {
     const WaveDesc *waves = nullptr;
     const uint32_t *flagwords = nullptr;
     const Arc *arcs = nullptr;
+    const uint16_t *vix = nullptr;
     const CloneDesc *clones = nullptr;
     const int32_t *zero_rows = nullptr;
 };

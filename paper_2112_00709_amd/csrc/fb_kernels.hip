@@ -77,16 +77,6 @@ __device__ __forceinline__ void lse_add4(T &m, float &s, T x0, T x1, T x2, T x3)
 }
 
 template <class T>
-__device__ __forceinline__ void lse_add3(T &m, float &s, T x0, T x1, T x2)
-{
-    const T mn = tmax(tmax3(m, x0, x1), x2);
-    const float r = fexp2((float)(m - mn));
-    const float e0 = fexp2((float)(x0 - mn)), e1 = fexp2((float)(x1 - mn)), e2 = fexp2((float)(x2 - mn));
-    s = fmaf(s, r, (e0 + e1) + e2);
-    m = mn;
-}
-
-template <class T>
 __device__ __forceinline__ void lse_merge(T &m, float &s, T m2, float s2)
 {
     const T M = tmax(m, m2);
@@ -202,6 +192,7 @@ __device__ __forceinline__ float wave_sum(float v)
 //   er   3 x (Ecap + 1) float   emissions as given (natural log) of the frame in use and
 //                               of the next two; slot Ecap = 0
 //   pix  Ecap int32             packed graphs: pdf id of every state
+//   vix  Xs uint16              which staged emission every target (state, clone, dump slot) takes
 //   bpb  2 x Xs uint16          tropical semiring only: back-pointers of the previous / current step
 // ---------------------------------------------------------------------------
 template <int NW, class T, bool TROP>
@@ -229,7 +220,8 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
     T *red = bh + (bwd ? 2 * Xs : 0);
     float *er = (float *)(red + 4 * NW + 2);
     int32_t *pix = (int32_t *)(er + 3 * Es);
-    uint16_t *bpb = (uint16_t *)(pix + (P.shared ? 0 : P.Ecap));   // tropical semiring: 2 x Xs back-pointers
+    uint16_t *vix = (uint16_t *)(pix + (P.shared ? 0 : P.Ecap));   // emission index of every target
+    uint16_t *bpb = vix + ((Xs + 1) & ~1);                         // tropical semiring: 2 x Xs back-pointers
 
     const float *em_seq = P.emis + (size_t)b * P.N * P.D;
     const size_t out_ld = P.shared ? (size_t)K : (size_t)P.Ktot;
@@ -308,6 +300,7 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
         // ---- first frame of this direction: x = start weight (x) v
         if (!P.shared)
             for (int k = tid; k < K; k += NT) pix[k] = P.pdf[k0 + k];
+        for (int k = tid; k < Xs; k += NT) vix[k] = S.vix[(size_t)(P.shared ? 0 : b) * Xs + k];
         if (tid < 3) er[tid * Es + P.Ecap] = 0.0f;   // the emission of rows that take none
         __syncthreads();
         if (io_wave) {
@@ -390,9 +383,11 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
             constexpr int GB = kRing % 2 == 0 ? 2 : 3;
             static_assert(kRing % GB == 0, "ring size must be a multiple of the gather buffer count");
             T g[GB][kBatchRows];
-            auto gather = [&](T(&dst)[kBatchRows], const Arc(&a)[kBatchRows], const T *vbase) {
+            // closing: the batch closes a slice, the source field of its last row carries the target too
+            auto gather = [&](T(&dst)[kBatchRows], const Arc(&a)[kBatchRows], const T *vbase, bool closing) {
 #pragma unroll
-                for (int r = 0; r < kBatchRows; ++r) dst[r] = vbase[a[r].src];
+                for (int r = 0; r + 1 < kBatchRows; ++r) dst[r] = vbase[a[r].src];
+                dst[kBatchRows - 1] = vbase[closing ? (int32_t)((uint32_t)a[kBatchRows - 1].src & 0xffffu) : a[kBatchRows - 1].src];
             };
 
             for (int i = 1; i < Tn; ++i) {
@@ -417,62 +412,68 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                         xn[k] = kNegInf;
                         if (bwd) bn[k] = kNegInf;
                     }
-                // fold one batch: a, gv = its entries and gathered values; next = the batch after it
-                // (its gathers are issued before this batch's arithmetic), has_next: there is one in this step
+                // fold one batch: a, gv = its entries and gathered values; next = the batch after it (its
+                // gathers are issued before this batch's arithmetic), fnext = its flags, has_next: there is one
                 auto fold = [&](uint32_t f, const Arc(&a)[kBatchRows], const T(&gv)[kBatchRows], T(&gnext)[kBatchRows],
-                                const Arc(&next)[kBatchRows], bool has_next) {
-                    if (has_next) gather(gnext, next, vbase);
+                                const Arc(&next)[kBatchRows], uint32_t fnext, bool has_next) {
+                    if (has_next) gather(gnext, next, vbase, (fnext & kFlagInfo) != 0);
                     if (!(f & kFlagSkip)) {
+                        const bool closing = (f & kFlagInfo) != 0;
+                        const uint32_t last = (uint32_t)a[3].src;   // closing: source | target << 16
+                        const T x0 = gv[0] + (T)a[0].w, x1 = gv[1] + (T)a[1].w, x2 = gv[2] + (T)a[2].w, x3 = gv[3] + (T)a[3].w;
                         if constexpr (TROP) {
                             // (+) = max: keep the largest term and the state it came from (the first of equal terms)
                             auto take = [&](T x, int s) {
                                 if (x > m) { m = x; arg = s; }
                             };
-                            take(gv[0] + (T)a[0].w, a[0].src);
-                            take(gv[1] + (T)a[1].w, a[1].src);
-                            take(gv[2] + (T)a[2].w, a[2].src);
-                            if (!(f & kFlagInfo)) {
-                                take(gv[3] + (T)a[3].w, a[3].src);
-                            } else {
+                            take(x0, a[0].src);
+                            take(x1, a[1].src);
+                            take(x2, a[2].src);
+                            take(x3, closing ? (int)(last & 0xffffu) : a[3].src);
+                            if (closing) {
                                 const int lg = (int)((f >> kFlagLgShift) & 7u);
                                 if (lg) group_best(m, arg, lg, lane);
-                                const uint32_t u = __float_as_uint(a[3].w);
-                                const T x = (m - c) + (T)ern[u >> 16] * (T)kLog2e;
-                                xn[u & 0xffffu] = x;
-                                bpn[u & 0xffffu] = (uint16_t)arg;
+                                const uint32_t tgt = last >> 16;
+                                const T x = (m - c) + (T)ern[vix[tgt]] * (T)kLog2e;
+                                xn[tgt] = x;
+                                bpn[tgt] = (uint16_t)arg;
                                 wmax = tmax(wmax, x);
                                 m = kNegInf;
                                 arg = 0;
                             }
-                        } else if (!(f & kFlagInfo)) {
-                            lse_add4(m, sum, gv[0] + (T)a[0].w, gv[1] + (T)a[1].w, gv[2] + (T)a[2].w, gv[3] + (T)a[3].w);
-                        } else {   // three arcs, then the row's sum is complete
-                            lse_add3(m, sum, gv[0] + (T)a[0].w, gv[1] + (T)a[1].w, gv[2] + (T)a[2].w);
-                            const int lg = (int)((f >> kFlagLgShift) & 7u);
-                            if (lg) group_total(m, sum, lg, lane);   // the row's arcs were spread over 2^lg lanes
-                            const uint32_t u = __float_as_uint(a[3].w);
-                            const T pre = m + (T)flog2(sum) - c;   // sum == 0 -> -inf
-                            const T x = pre + (T)ern[u >> 16] * (T)kLog2e;
-                            xn[u & 0xffffu] = x;
-                            if (bwd) bn[u & 0xffffu] = pre;
-                            wmax = tmax(wmax, x);
-                            m = (T)kNegBig;
-                            sum = 0.0f;
+                        } else {
+                            lse_add4(m, sum, x0, x1, x2, x3);
+                            if (closing) {   // the rows' sums are complete
+                                const int lg = (int)((f >> kFlagLgShift) & 7u);
+                                if (lg) group_total(m, sum, lg, lane);   // the row's arcs were spread over 2^lg lanes
+                                const uint32_t tgt = last >> 16;
+                                const T pre = m + (T)flog2(sum) - c;   // sum == 0 -> -inf
+                                const T x = pre + (T)ern[vix[tgt]] * (T)kLog2e;
+                                xn[tgt] = x;
+                                if (bwd) bn[tgt] = pre;
+                                wmax = tmax(wmax, x);
+                                m = (T)kNegBig;
+                                sum = 0.0f;
+                            }
                         }
                     }
                 };
-                gather(g[0], res[0], vbase);
+                auto rflag = [&](int q) { return ((q < 4 ? rflag0 : rflag1) >> (8 * (q & 3))) & 0xffu; };
+                const uint32_t fw_first = n_iter > 0 ? (uint32_t)__builtin_amdgcn_readlane(fwv0, 0) : 0u;
+                gather(g[0], res[0], vbase, (rflag(0) & kFlagInfo) != 0);
 #pragma unroll
                 for (int q = 0; q < NRES; ++q) {
-                    const uint32_t f = ((q < 4 ? rflag0 : rflag1) >> (8 * (q & 3))) & 0xffu;
                     if (q + 1 < NRES)
-                        fold(f, res[q], g[q % GB], g[(q + 1) % GB], res[q + 1], true);
+                        fold(rflag(q), res[q], g[q % GB], g[(q + 1) % GB], res[q + 1], rflag(q + 1), true);
                     else
-                        fold(f, res[q], g[q % GB], g[(q + 1) % GB], ring[0], n_iter > 0);
+                        fold(rflag(q), res[q], g[q % GB], g[(q + 1) % GB], ring[0], fw_first & 0xffu, n_iter > 0);
                 }
+                uint32_t fw = fw_first;
                 for (int it = 0; it < n_iter; ++it) {
-                    const uint32_t fw =
-                        it < kWave ? __builtin_amdgcn_readlane(fwv0, it) : __builtin_amdgcn_readlane(fwv1, it - kWave);
+                    // flags of the next iteration (its first byte belongs to the batch after this iteration's last)
+                    const int itn = it + 1 < n_iter ? it + 1 : it;
+                    const uint32_t fwn =
+                        itn < kWave ? __builtin_amdgcn_readlane(fwv0, itn) : __builtin_amdgcn_readlane(fwv1, itn - kWave);
 #pragma unroll
                     for (int j = 0; j < kRing; ++j) {
                         int pf = it * kRing + j + (kRing - 1);
@@ -480,8 +481,9 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                         load_batch(ring[(j + kRing - 1) % kRing], pf);
                         __builtin_amdgcn_sched_barrier(0);
                         fold((fw >> (8 * j)) & 0xffu, ring[j], g[(NRES + j) % GB], g[(NRES + j + 1) % GB], ring[(j + 1) % kRing],
-                             j + 1 < kRing || it + 1 < n_iter);
+                             j + 1 < kRing ? (fw >> (8 * (j + 1))) & 0xffu : fwn & 0xffu, j + 1 < kRing || it + 1 < n_iter);
                     }
+                    fw = fwn;
                 }
                 wmax = wave_max(wmax);
                 if (lane == 0) red[nxt * NW + wave] = wmax;

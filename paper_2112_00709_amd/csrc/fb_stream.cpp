@@ -60,44 +60,41 @@ bool stream_from_sell(const SellHost &S, int32_t Kcap, int32_t Ecap, StreamHost 
         return false;
     }
     const uint32_t dump = (uint32_t)(Kcap + S.max_slot);
-    const uint32_t idle_info = dump | ((uint32_t)Ecap << 16);
+    const size_t xs = (size_t)dump + 1;
     const Arc pad_arc{0, -INFINITY};
     for (const SubDesc &ssd : S.sub) {
         SubDesc sd = ssd;
         sd.wave_ptr0 = (int32_t)out.waves.size();
+        const size_t vix0 = out.vix.size();
+        out.vix.resize(vix0 + xs, (uint16_t)Ecap);   // targets that are never written take the zero emission
         for (int wv = 0; wv < S.nw; ++wv) {
             WaveDesc wd{};
             wd.arc_base = (int64_t)out.arcs.size();
             std::vector<uint8_t> flags;   // one per batch
             std::vector<Arc> lin;         // the wave's rows in order, 64 entries each
-            auto pad_batch = [&]() {   // three zero-weight arcs and an info row that goes to the dump slot
+            auto pad_batch = [&]() {   // zero-weight arcs whose sums go to the dump slot
                 for (int e = 0; e < (kBatchRows - 1) * kWave; ++e) lin.push_back(pad_arc);
-                for (int lane = 0; lane < kWave; ++lane) lin.push_back(Arc{0, bits_to_float(idle_info)});
+                for (int lane = 0; lane < kWave; ++lane) lin.push_back(Arc{(int32_t)(dump << 16), -INFINITY});
                 flags.push_back((uint8_t)(kFlagInfo | kFlagSkip));
             };
             const int32_t s0 = S.wave_ptr[(size_t)ssd.wave_ptr0 + wv], s1 = S.wave_ptr[(size_t)ssd.wave_ptr0 + wv + 1];
             for (int32_t s = s0; s < s1; ++s) {
                 const int32_t trip = S.slice_trip[s];
-                int32_t rows = 0;
-                for (int32_t it = 0; it < trip; ++it, ++rows)
+                const int32_t nb = (trip + kBatchRows - 1) / kBatchRows, rows = nb * kBatchRows;
+                for (int32_t it = 0; it < rows; ++it)
                     for (int lane = 0; lane < kWave; ++lane) {
-                        Arc a = S.arcs[(size_t)S.slice_arc[s] + (size_t)it * kWave + lane];
+                        Arc a = it < trip ? S.arcs[(size_t)S.slice_arc[s] + (size_t)it * kWave + lane] : pad_arc;
                         if (a.src >= ssd.K) a.src = Kcap + (a.src - ssd.K);   // a clone: its slot in the state buffer
+                        if (it == rows - 1) {   // the lane's last entry of the slice also names its target
+                            const int32_t o = S.row_out[(size_t)s * kWave + lane], v = S.row_vidx[(size_t)s * kWave + lane];
+                            const uint32_t tgt = o < 0 ? dump : (o < ssd.K ? (uint32_t)o : (uint32_t)(Kcap + (o - ssd.K)));
+                            a.src = (int32_t)((uint32_t)a.src | (tgt << 16));
+                            if (o >= 0) out.vix[vix0 + tgt] = (uint16_t)v;
+                        }
                         lin.push_back(a);
                     }
-                for (; rows % kBatchRows != kBatchRows - 1; ++rows)   // the info row closes a batch
-                    for (int lane = 0; lane < kWave; ++lane) lin.push_back(pad_arc);
-                for (int lane = 0; lane < kWave; ++lane) {
-                    const int32_t o = S.row_out[(size_t)s * kWave + lane], v = S.row_vidx[(size_t)s * kWave + lane];
-                    // a lane that shares a row without writing it still takes the row's emission: all lanes
-                    // of a row then hold the same value, which keeps the step maximum exact
-                    const uint32_t tgt = o < 0 ? dump : (o < ssd.K ? (uint32_t)o : (uint32_t)(Kcap + (o - ssd.K)));
-                    lin.push_back(Arc{0, bits_to_float(tgt | ((uint32_t)(v < 0 ? Ecap : v) << 16))});
-                }
-                ++rows;
-                for (int32_t bt = 0; bt < rows / kBatchRows; ++bt)
-                    flags.push_back(bt + 1 == rows / kBatchRows
-                                        ? (uint8_t)(kFlagInfo | ((uint32_t)S.slice_lg[s] << kFlagLgShift)) : (uint8_t)0);
+                for (int32_t bt = 0; bt < nb; ++bt)
+                    flags.push_back(bt + 1 == nb ? (uint8_t)(kFlagInfo | ((uint32_t)S.slice_lg[s] << kFlagLgShift)) : (uint8_t)0);
             }
             while (flags.size() < (size_t)kResident || (flags.size() - kResident) % kRing) pad_batch();   // whole iterations
             if ((flags.size() - kResident) / kRing > 2 * kWave) {
@@ -133,6 +130,7 @@ bool stream_from_sell(const SellHost &S, int32_t Kcap, int32_t Ecap, StreamHost 
 // n_vidx: entries of the staged emission vector (negative: the sub-graph's state count).
 bool stream_in_bounds(const StreamHost &S, int32_t n_vidx, std::string &why)
 {
+    if (S.vix.size() != S.sub.size() * ((size_t)S.Kcap + S.Ccap + 1)) { why = "emission index table size"; return false; }
     for (const SubDesc &sd : S.sub) {
         if (sd.wave_ptr0 < 0 || (size_t)sd.wave_ptr0 + S.nw > S.waves.size()) { why = "wave table range"; return false; }
         if (sd.K > S.Kcap || sd.n_slot > S.Ccap) { why = "index space"; return false; }
@@ -162,21 +160,21 @@ bool stream_in_bounds(const StreamHost &S, int32_t n_vidx, std::string &why)
                 for (int r = 0; r < kBatchRows; ++r)
                     for (int lane = 0; lane < kWave; ++lane) {
                         const Arc &a = S.arcs[(size_t)wd.arc_base + entry_at(bt, r, lane)];
-                        // every row is gathered, info rows included: src must always be safe
-                        if (a.src < 0 || (a.src >= sd.K && (a.src < S.Kcap || a.src >= S.Kcap + sd.n_slot))) {
+                        const bool closing = r == kBatchRows - 1 && (f & kFlagInfo);
+                        const int32_t src = closing ? (int32_t)((uint32_t)a.src & 0xffffu) : a.src;
+                        if (src < 0 || (src >= sd.K && (src < S.Kcap || src >= S.Kcap + sd.n_slot))) {
                             why = "arc source";
                             return false;
                         }
-                        if (r == kBatchRows - 1 && (f & kFlagInfo)) {
-                            const uint32_t u = float_to_bits(a.w);
-                            const int32_t t = (int32_t)(u & 0xffff), v = (int32_t)(u >> 16);
+                        if (!(a.w <= 0.0f) && !(a.w > 0.0f)) { why = "NaN weight"; return false; }
+                        if (closing) {
+                            const int32_t t = (int32_t)((uint32_t)a.src >> 16);
                             const bool state = t < sd.K, slot = t >= S.Kcap && t < S.Kcap + sd.n_slot;
                             const bool dump = t == S.Kcap + S.Ccap;
                             if (!state && !slot && !dump) { why = "row target"; return false; }
+                            const int32_t v = S.vix[(size_t)(&sd - S.sub.data()) * ((size_t)S.Kcap + S.Ccap + 1) + (size_t)t];
                             if (v != S.Ecap && v >= (n_vidx < 0 ? sd.K : n_vidx)) { why = "emission index"; return false; }
-                        } else if (!(a.w <= 0.0f) && !(a.w > 0.0f)) {
-                            why = "NaN weight";
-                            return false;
+                            if (dump && v != S.Ecap) { why = "emission on the dump slot"; return false; }
                         }
                     }
             }
@@ -213,24 +211,24 @@ void stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double
             for (int r = 0; r < kBatchRows; ++r)
                 for (int lane = 0; lane < kWave; ++lane) {
                     const Arc &a = S.arcs[(size_t)wd.arc_base + entry_at(bt, r, lane)];
-                    if (!(r == kBatchRows - 1 && (f & kFlagInfo))) {
-                        terms[lane].push_back((double)a.w + xe[(size_t)(a.src < sd.K ? a.src : sd.K + (a.src - S.Kcap))]);
-                        continue;
-                    }
-                    if (lane % g == 0) {   // the row's lanes are complete: the info row is the batch's last
-                        std::vector<double> all;
-                        for (int t = 0; t < g; ++t) all.insert(all.end(), terms[lane + t].begin(), terms[lane + t].end());
-                        for (int t = 0; t < g; ++t) terms[lane + t].assign(1, lse(all));   // every lane of the row holds the total
-                    }
+                    const bool closing = r == kBatchRows - 1 && (f & kFlagInfo);
+                    const int32_t src = closing ? (int32_t)((uint32_t)a.src & 0xffffu) : a.src;
+                    terms[lane].push_back((double)a.w + xe[(size_t)(src < sd.K ? src : sd.K + (src - S.Kcap))]);
                 }
-            if (f & kFlagInfo)
+            if (f & kFlagInfo) {
+                for (int lane = 0; lane < kWave; lane += g) {   // the row's lanes are complete
+                    std::vector<double> all;
+                    for (int t = 0; t < g; ++t) all.insert(all.end(), terms[lane + t].begin(), terms[lane + t].end());
+                    for (int t = 0; t < g; ++t) terms[lane + t].assign(1, lse(all));   // every lane of the row holds the total
+                }
                 for (int lane = 0; lane < kWave; ++lane) {
                     const Arc &a = S.arcs[(size_t)wd.arc_base + entry_at(bt, kBatchRows - 1, lane)];
-                    const int32_t t = (int32_t)(float_to_bits(a.w) & 0xffff);
+                    const int32_t t = (int32_t)((uint32_t)a.src >> 16);
                     if (t < sd.K) ye[(size_t)t] = terms[lane][0];
                     else if (t < S.Kcap + sd.n_slot) ye[(size_t)sd.K + (size_t)(t - S.Kcap)] = terms[lane][0];
                     terms[lane].clear();
                 }
+            }
         }
     }
     for (int32_t c = 0; c < sd.n_cdesc; ++c) {   // a cloned state is the (+)-sum of its clones
