@@ -41,8 +41,8 @@ int lanes_log2(int32_t n)
     return lg;
 }
 
-// batches of the stream a slice of this width takes (its info row closes the last one)
-int32_t slice_batches(int32_t trip) { return trip / kBatchRows + 1; }
+// batches of the stream a slice of this width takes
+int32_t slice_batches(int32_t trip) { return (trip + kBatchRows - 1) / kBatchRows; }
 
 }  // namespace
 
