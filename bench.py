@@ -27,8 +27,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
-# transcendental issue rate: 256 CUs x 64 lanes x 2.4 GHz at a quarter of the plain fp32 rate
-EXP_PEAK_PER_S = 256 * 64 * 2.4e9 / 4
+# plain (unpacked, non-fused) fp32 VALU issue rate: 256 CUs x 64 lanes x 2.4 GHz = 157.3 TFLOP/s / 4
+VALU_PEAK_PER_S = 256 * 64 * 2.4e9
 
 # HBM bytes per denominator-recursion launch on configuration 5 from rocprofv3 --pmc
 # (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on a plain copy kernel);
@@ -213,10 +213,14 @@ def main() -> int:
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes": algo_bytes, "launch_ms": stage_ms["den_recursion"]},
-        # the bound that applies to that launch: one exponential per arc-update on the quarter-rate unit
-        "roofline_alu": {"bound": "alu", "achieved": upd_den / (stage_ms["den_recursion"] * 1e-3) / 1e12,
-                         "peak": EXP_PEAK_PER_S / 1e12, "unit": "T exp/s (one per arc-update)",
-                         "frac": upd_den / (stage_ms["den_recursion"] * 1e-3) / EXP_PEAK_PER_S},
+        # the bound that applies to that launch: VALU issue.  The (+)-update of one arc needs at least an add
+        # (weight), a max, a subtract, an exponential and an add; the exponential runs at a quarter of the
+        # plain fp32 rate, so an arc-update is at least 4 + 4 = 8 lane-issue slots of the 256 x 64 x 2.4e9 per second
+        # (packed fp32 is not used in this build)
+        "roofline_alu": {"bound": "alu", "achieved": 8 * upd_den / (stage_ms["den_recursion"] * 1e-3) / 1e12,
+                         "peak": VALU_PEAK_PER_S / 1e12, "unit": "T fp32 lane-ops/s (8 per arc-update, the exp as 4)",
+                         "frac": 8 * upd_den / (stage_ms["den_recursion"] * 1e-3) / VALU_PEAK_PER_S,
+                         "exp_frac": upd_den / (stage_ms["den_recursion"] * 1e-3) / (VALU_PEAK_PER_S / 4)},
     }
 
     if args.context:
