@@ -106,6 +106,26 @@ def context_workloads(fb, wl, torch):
             log(f"[bench] {name} best path: {vms:.3f} ms, {upd / 2 / (vms * 1e-3):.3e} arc-updates/s")
             Gv.destroy()
         del emis
+    # LF-MMI loss + gradient with both graphs the size of the paper's (Table 3 gives 0.220 s for this stage on an RTX 2080 Ti)
+    w = wl.paper_shape_lfmmi()
+    den, num = fb.graph_from(w.den, w.D), fb.graph_from(w.num, w.D)
+    emis, lengths = torch.from_numpy(w.emis).cuda(), torch.from_numpy(w.lengths).cuda()
+    ws = torch.empty((fb.fb_lfmmi_workspace_bytes(den, num, w.B, w.N, w.D),), dtype=torch.uint8, device="cuda")
+    grad = torch.empty((w.B, w.N, w.D), dtype=torch.float32, device="cuda")
+    for _ in range(2):
+        fb.lfmmi_loss_grad(den, num, emis, lengths, ws=ws, grad=grad)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(5):
+        fb.lfmmi_loss_grad(den, num, emis, lengths, ws=ws, grad=grad)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / 5
+    upd = w.arc_updates(w.den) + w.arc_updates(w.num)
+    out["paper_shape_lfmmi"] = {"B": w.B, "N_max": w.N, "D": w.D, "den_states": w.den.K, "den_arcs": w.den.E,
+                                "num_states": w.num.K, "num_arcs": w.num.E, "ms": ms, "arc_updates": upd,
+                                "arc_updates_per_s": upd / (ms * 1e-3), "paper_table3_s": 0.220}
+    log(f"[bench] paper_shape_lfmmi: {ms:.3f} ms, {upd / (ms * 1e-3):.3e} arc-updates/s")
+    den.destroy(); num.destroy()
     return out
 
 

@@ -79,6 +79,7 @@ PostGraph make_post(const fb_graph *g, const void *a, const void *b, bool f64, f
     q.Ktot = g->K;
     q.Kcap = g->max_sub_K;
     q.Rcap = g->h_pdf.max_rows;
+    q.ld = g->K;
     q.state_post = state_post;
     return q;
 }
@@ -259,10 +260,13 @@ int fb_viterbi(const fb_graph *g, const float *emis, const int32_t *lengths, int
     return launch_backtrace(bt, stream);
 }
 
+// rows of the denominator's workspace vectors start on 16-byte boundaries
+static size_t lfmmi_den_ld(const fb_graph *den) { return ((size_t)den->K + 3) & ~(size_t)3; }
+
 size_t fb_lfmmi_workspace_bytes(const fb_graph *den, const fb_graph *num, int32_t B, int32_t N, int32_t D)
 {
     if (!den || !num || B <= 0 || N <= 0 || D <= 0) return 0;
-    const size_t den_vec = align256((size_t)B * N * den->K * (den->f64 ? 8 : 4));
+    const size_t den_vec = align256((size_t)B * N * lfmmi_den_ld(den) * (den->f64 ? 8 : 4));
     const size_t num_vec = align256((size_t)N * num->K * (num->f64 ? 8 : 4));
     const size_t z = align256((size_t)B * sizeof(double));
     return 2 * den_vec + 2 * num_vec + 2 * z;
@@ -284,7 +288,7 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
 
     // workspace: forward and backward vectors of both graphs in log2 units, log Z when the caller keeps none
     char *w = (char *)ws;
-    const size_t den_vec = align256((size_t)B * N * den->K * (den->f64 ? 8 : 4));
+    const size_t den_vec = align256((size_t)B * N * lfmmi_den_ld(den) * (den->f64 ? 8 : 4));
     const size_t num_vec = align256((size_t)N * num->K * (num->f64 ? 8 : 4));
     void *den_a = w; w += den_vec;
     void *den_b = w; w += den_vec;
@@ -300,6 +304,7 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
                     make_dir(num, true, num_b, true, nullptr, nullptr, 1.0f, false)};
     RecDir dd[2] = {make_dir(den, false, den_a, true, nullptr, zd, 1.0f, false),
                     make_dir(den, true, den_b, true, nullptr, nullptr, 1.0f, false)};
+    dd[0].out_ld = dd[1].out_ld = (int32_t)lfmmi_den_ld(den);
     hipStream_t main_s = (hipStream_t)stream;
     SideStream &side = side_stream();
     const bool fork = side.ok && hipEventRecord(side.fork, main_s) == hipSuccess &&
@@ -316,8 +321,9 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
         return fail(FB_EHIP, "lfmmi_loss_grad: joining the side stream failed");
 
     // Eq. 17: numerator pdf posteriors minus denominator pdf posteriors
-    const PostGraph q[2] = {make_post(den, den_a, den_b, den->f64, 1.0f, -1.0f, nullptr),
-                            make_post(num, num_a, num_b, num->f64, 1.0f, 1.0f, nullptr)};
+    PostGraph q[2] = {make_post(den, den_a, den_b, den->f64, 1.0f, -1.0f, nullptr),
+                      make_post(num, num_a, num_b, num->f64, 1.0f, 1.0f, nullptr)};
+    q[0].ld = (int32_t)lfmmi_den_ld(den);
     if (fork) mark(2, main_s);   // the gradient stage starts when both recursion launches are done
     if ((rc = run_posteriors(q, 2, lengths, B, N, D, grad, stream))) return rc;
     mark(3, main_s);

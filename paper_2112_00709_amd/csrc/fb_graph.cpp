@@ -299,8 +299,10 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
                 }
                 PH.row_ptr.push_back((uint16_t)Ks);
                 for (int32_t i = 0; i < Ks; ++i) PH.states.push_back((uint16_t)L.pdf_states[(size_t)i]);
-                PH.pos.resize((size_t)Ks);
+                // padded to a multiple of 4 entries that point behind the states (read 4 at a time)
+                PH.pos.assign((size_t)((Ks + 3) & ~3), (uint16_t)0);
                 for (int32_t i = 0; i < Ks; ++i) PH.pos[(size_t)L.pdf_states[(size_t)i]] = (uint16_t)i;
+                for (int32_t i = Ks; i < ((Ks + 3) & ~3); ++i) PH.pos[(size_t)i] = (uint16_t)i;
                 ps.n_rows = D;
             } else {
                 std::vector<int32_t> order((size_t)Ks);

@@ -207,6 +207,7 @@ struct RecDir {
     int32_t Ccap;          // clone slots of this direction's schedule
     int backward;
     int fill_pad;          // write -inf / 0 into the rows of padded frames
+    int32_t out_ld;        // shared graph: elements between the rows of consecutive frames of out (0: the state count)
     uint16_t *bp;          // tropical semiring: back-pointers (see fb_viterbi in fb_api.cpp for the layout), else NULL
     int64_t bp_ld;         // elements per frame row of bp
     int32_t *last;         // tropical semiring: [B] local id of the best end state (-1: none)
@@ -230,6 +231,7 @@ struct PostGraph {
     float sign;            // +1 / -1: how the graph's pdf posteriors enter pdf_out
     int32_t shared, Ktot;
     int32_t Kcap, Rcap;    // largest (sub-)graph: states, pdf rows
+    int32_t ld;            // shared graph: elements between the rows of consecutive frames of a, b (>= K)
     float *state_post;     // nullable
 };
 

@@ -224,8 +224,8 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
     uint16_t *bpb = vix + ((Xs + 1) & ~1);                         // tropical semiring: 2 x Xs back-pointers
 
     const float *em_seq = P.emis + (size_t)b * P.N * P.D;
-    const size_t out_ld = P.shared ? (size_t)K : (size_t)P.Ktot;
-    const size_t out_at = P.shared ? (size_t)b * P.N * K : (size_t)k0;
+    const size_t out_ld = P.shared ? (size_t)(R.out_ld ? R.out_ld : K) : (size_t)P.Ktot;
+    const size_t out_at = P.shared ? (size_t)b * P.N * out_ld : (size_t)k0;
     float *out_f = (R.out && !R.out_carrier) ? (float *)R.out + out_at : nullptr;
     T *out_t = (R.out && R.out_carrier) ? (T *)R.out + out_at : nullptr;
     float *off_seq = R.off ? R.off + (size_t)b * P.N : nullptr;
@@ -263,10 +263,13 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
             for (int k = lane; k < K; k += kWave) orow[k] = (float)srcv[k] * R.out_scale;
         } else if (out_t) {
             T *orow = out_t + (size_t)f * out_ld;
-            if (sizeof(T) == 4 && (K & 3) == 0 && ((uintptr_t)orow & 15) == 0 && ((uintptr_t)srcv & 15) == 0) {
+            if (sizeof(T) == 4 && (out_ld & 3) == 0 && (size_t)((K + 3) & ~3) <= out_ld && ((uintptr_t)orow & 15) == 0 &&
+                ((uintptr_t)srcv & 15) == 0) {
+                // whole 16-byte pieces; when K is not a multiple of 4 the last one takes up to 3 values that lie
+                // behind the states in LDS into the row's padding, which nobody reads
                 const float4 *s4 = (const float4 *)srcv;
                 float4 *o4 = (float4 *)orow;
-                for (int k = lane; k < K / 4; k += kWave) o4[k] = s4[k];
+                for (int k = lane; k < (K + 3) / 4; k += kWave) o4[k] = s4[k];
             } else {
                 for (int k = lane; k < K; k += kWave) orow[k] = srcv[k];
             }
@@ -647,12 +650,13 @@ __global__ __launch_bounds__(kPostThreads) void fb_posterior_kernel(const PostPa
     // worked on (when it is a shared graph of float vectors whose rows are 16-byte aligned).
     const PostGraph &G0 = P.g[0];
     const int K0 = G0.pdfs.sub[0].K;
-    const bool pre = G0.shared && !G0.f64 && (K0 & 3) == 0 && (((uintptr_t)G0.a | (uintptr_t)G0.b) & 15) == 0 && n0 < n_end;
+    const bool pre = G0.shared && !G0.f64 && (K0 & 3) == 0 && (G0.ld & 3) == 0 && (((uintptr_t)G0.a | (uintptr_t)G0.b) & 15) == 0 &&
+                     n0 < n_end;
     const int Kpre = pre ? min(K0, NT * 4 * U) : 0;   // states covered by the prefetch registers
     float4 pa[U], pb[U];
     auto issue = [&](int n) {
-        const float4 *ar = (const float4 *)((const float *)G0.a + ((size_t)b * P.N + n) * K0);
-        const float4 *br = (const float4 *)((const float *)G0.b + ((size_t)b * P.N + n) * K0);
+        const float4 *ar = (const float4 *)((const float *)G0.a + ((size_t)b * P.N + n) * G0.ld);
+        const float4 *br = (const float4 *)((const float *)G0.b + ((size_t)b * P.N + n) * G0.ld);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int q = u * NT + tid;
@@ -695,7 +699,7 @@ __global__ __launch_bounds__(kPostThreads) void fb_posterior_kernel(const PostPa
         for (int gi = 0; gi < P.n_graph; ++gi) {
             const PostGraph &G = P.g[gi];
             const int K = ps[gi].K;
-            const size_t at = G.shared ? ((size_t)b * P.N + n) * K : (size_t)n * G.Ktot + ps[gi].k0;
+            const size_t at = G.shared ? ((size_t)b * P.N + n) * G.ld : (size_t)n * G.Ktot + ps[gi].k0;
             const bool covers_all = G.shared != 0;   // a shared graph has one row per pdf
             if (gi == 0 && !covers_all && prow)
                 for (int d = tid; d < P.D; d += NT) rho[d] = 0.0f;
@@ -727,7 +731,7 @@ __global__ __launch_bounds__(kPostThreads) void fb_posterior_kernel(const PostPa
                 inv = frame_finish<float>(mx, K, tb, tb, red, tid, lane, wave);
             }
             if (G.state_post) {
-                float *srow = G.state_post + at;
+                float *srow = G.state_post + (G.shared ? ((size_t)b * P.N + n) * K : at);
                 for (int k = tid; k < K; k += NT) srow[k] = tb[k] * inv;
             }
             __syncthreads();   // tb complete (and red free again)
@@ -811,8 +815,9 @@ __global__ __launch_bounds__(kGradThreads, 5) void fb_grad_kernel(const PostPara
     const int K1 = ps1.K, R1 = ps1.n_rows;
 
     float *red = (float *)lds_raw;                       // [32] maxima, then sums, of waves 0-7
-    float *tb = red + 32;                                // [K0 rounded to 4] exp(log posterior - max), pdf order
-    float *rho = tb + ((K0 + 3) & ~3);                   // [D rounded to 4]
+    float *tb = red + 32;                                // [K0 rounded to 4, + 4] exp(log posterior - max), pdf order;
+                                                         // the places behind K0 take the padding of a row's last piece
+    float *rho = tb + ((K0 + 3) & ~3) + 4;               // [D rounded to 4]
     float *en = rho + ((D + 3) & ~3);                    // [G1.Kcap] the numerator's exp(log posterior - max)
     uint16_t *nptr = (uint16_t *)(en + G1.Kcap);         // numerator tables: row_ptr [Rcap + 1], row_pdf [Rcap], states [Kcap]
     uint16_t *npdf = nptr + G1.Rcap + 1, *nst = npdf + G1.Rcap;
@@ -830,8 +835,8 @@ __global__ __launch_bounds__(kGradThreads, 5) void fb_grad_kernel(const PostPara
         uint2 posr[U];                // places (4 x 16 bit) of the thread's states in pdf order
         uint32_t prange[kGradPdf];    // state ranges (begin | end << 16) of the thread's pdfs tid, tid + MT, ...
         auto issue = [&](int n) {
-            const float4 *ar = (const float4 *)((const float *)G0.a + ((size_t)b * P.N + n) * K0);
-            const float4 *br = (const float4 *)((const float *)G0.b + ((size_t)b * P.N + n) * K0);
+            const float4 *ar = (const float4 *)((const float *)G0.a + ((size_t)b * P.N + n) * G0.ld);
+            const float4 *br = (const float4 *)((const float *)G0.b + ((size_t)b * P.N + n) * G0.ld);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int q = u * MT + tid;
@@ -863,6 +868,11 @@ __global__ __launch_bounds__(kGradThreads, 5) void fb_grad_kernel(const PostPara
                 if (q * 4 < K0) {
                     t[u][0] = (pa[u].x + pb[u].x) * G0.in_scale; t[u][1] = (pa[u].y + pb[u].y) * G0.in_scale;
                     t[u][2] = (pa[u].z + pb[u].z) * G0.in_scale; t[u][3] = (pa[u].w + pb[u].w) * G0.in_scale;
+                    if (q * 4 + 3 >= K0) {   // the row's last piece when K0 is not a multiple of 4: padding counts as zero-bar
+                        if (q * 4 + 1 >= K0) t[u][1] = -INFINITY;
+                        if (q * 4 + 2 >= K0) t[u][2] = -INFINITY;
+                        t[u][3] = -INFINITY;
+                    }
                     mx = tmax(tmax(mx, tmax(t[u][0], t[u][1])), tmax(t[u][2], t[u][3]));
                 }
             }
@@ -1087,7 +1097,8 @@ bool gradient_kernel_applies(const PostParams &p)
 {
     if (p.n_graph != 2 || !p.pdf_out) return false;
     const PostGraph &d = p.g[0], &n = p.g[1];
-    return d.shared && !d.f64 && !d.state_post && d.pdfs.pos && (d.Kcap & 3) == 0 && d.Kcap <= kGradMain * 4 * kGradU &&
+    return d.shared && !d.f64 && !d.state_post && d.pdfs.pos && (d.ld & 3) == 0 && d.ld >= ((d.Kcap + 3) & ~3) &&
+           d.Kcap <= kGradMain * 4 * kGradU &&
            (((uintptr_t)d.a | (uintptr_t)d.b) & 15) == 0 && p.D <= kGradMain * kGradPdf && !n.shared && !n.state_post &&
            n.Kcap <= kGradNumK && n.Rcap <= kGradNumK;
 }
@@ -1095,7 +1106,7 @@ bool gradient_kernel_applies(const PostParams &p)
 size_t gradient_lds_bytes(const PostParams &p)
 {
     const PostGraph &d = p.g[0], &n = p.g[1];
-    return 128 + ((size_t)((d.Kcap + 3) & ~3) + (size_t)((p.D + 3) & ~3) + (size_t)n.Kcap) * 4 +
+    return 128 + ((size_t)((d.Kcap + 3) & ~3) + 4 + (size_t)((p.D + 3) & ~3) + (size_t)n.Kcap) * 4 +
            ((size_t)n.Rcap * 2 + 1 + (size_t)n.Kcap + 3) / 2 * 4;
 }
 

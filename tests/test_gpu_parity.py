@@ -266,11 +266,15 @@ def test_packed_graphs_with_hubs_and_clones(fb):
 
 
 def test_gradient_kernel_paths(fb):
-    """lfmmi_loss_grad through the specialised gradient kernel (denominator states a multiple of 4) and through
-    the general posterior kernel (any other state count), both against the oracle."""
+    """lfmmi_loss_grad through the specialised gradient kernel (any state count up to its limit: rows of the
+    workspace are padded to 16 bytes) and through the general posterior kernel (numerators over 512 states, more
+    than 3072 pdfs), both against the oracle."""
     compare_lfmmi(fb, wl.config5(K=800, B=5, Lmin=3, Lmax=9, D=120), name="lfmmi, K=800 (specialised kernel)")
-    compare_lfmmi(fb, wl.config5(K=798, B=5, Lmin=3, Lmax=9, D=120), name="lfmmi, K=798 (general kernel)")
+    for K in (798, 797, 799):
+        compare_lfmmi(fb, wl.config5(K=K, B=5, Lmin=3, Lmax=9, D=120), name=f"lfmmi, K={K} (specialised kernel, padded rows)")
     compare_lfmmi(fb, wl.config5(K=1000, B=4, Lmin=3, Lmax=9, D=50), name="lfmmi, D=50 (fewer pdfs than threads)")
+    compare_lfmmi(fb, wl.config5(K=300, B=3, Lmin=171, Lmax=180, D=40), name="lfmmi, numerators over 512 states (general kernel)")
+    compare_lfmmi(fb, wl.config5(K=250, B=3, Lmin=3, Lmax=6, D=3100), name="lfmmi, D=3100 (general kernel)")
 
 
 def test_lfmmi_with_an_infeasible_numerator(fb):

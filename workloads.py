@@ -310,6 +310,16 @@ def paper_shape_den(K: int = 3022, E_target: int = 50984, B: int = 128, N: int =
     return Workload("paper_shape_den", D, emis, np.full(B, N, dtype=np.int32), den=g)
 
 
+def paper_shape_lfmmi(B: int = 128, N: int = 700, D: int = 84) -> Workload:
+    """Context workload with the sizes of the paper's benchmark for both graphs (Table 1 / Analysis section):
+    the denominator of ``paper_shape_den`` and, for every utterance, a numerator chain the size of the largest
+    alignment graph of the paper's corpus (454 states; here 151 phones = 453 states, 905 arcs); 700 frames each."""
+    w = paper_shape_den(B=B, N=N, D=D)
+    rng = np.random.default_rng(SEED0 + 7)
+    num = chain_graphs(rng, np.full(B, 151, dtype=np.int64), D)
+    return Workload("paper_shape_lfmmi", D, w.emis, w.lengths, den=w.den, num=num)
+
+
 CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
 
 
