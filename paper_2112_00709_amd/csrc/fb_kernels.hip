@@ -199,6 +199,9 @@ template <int NW, class T, bool TROP>
 __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P)
 {
     constexpr int NRES = kResident;
+    // The large-graph kernel is the critical path of a call; small-graph launches that run beside it on the same
+    // compute units (the numerators of an LF-MMI call) take the issue slots it leaves.
+    if (NW == kNWShared) __builtin_amdgcn_s_setprio(3);
     extern __shared__ double lds_raw[];
     constexpr int NT = NW * kWave, NC = NW - 1;
     const T kNegInf = (T)(-INFINITY);
