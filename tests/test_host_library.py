@@ -118,6 +118,43 @@ def test_kernel_schedule_computes_the_sparse_products(case):
     h.destroy()
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_kernel_schedule_on_random_graph_shapes(seed):
+    """The plans of randomly shaped graphs (hubs, parallel arcs, -inf weights, packed graphs of unequal size, sourceless
+    and sinkless states), interpreted on the host, against the direct sparse products."""
+    rng = np.random.default_rng(100 + seed)
+    kind = seed % 4
+    if kind == 0:
+        g = wl.random_graph(rng, int(rng.integers(5, 3000)), 9, zipf_s=float(rng.uniform(1.0, 1.6)),
+                            mean_extra_deg=float(rng.uniform(0.5, 14)))
+    elif kind == 1:
+        g = _pack([wl.random_graph(rng, int(rng.integers(2, 1800)), 9, zipf_s=1.3) for _ in range(int(rng.integers(2, 5)))])
+    elif kind == 2:
+        g = _pack([wl.tiny_graph(int(rng.integers(0, 99)), int(rng.integers(1, 9)), 9) for _ in range(3)])
+    else:
+        g0 = wl.random_graph(rng, 5200, 9, mean_extra_deg=1.0)          # one giant hub and parallel arcs into it
+        every = np.concatenate([np.arange(g0.K), np.arange(0, g0.K, 3)]).astype(np.int32)
+        g = wl.Graph(g0.K, np.concatenate([g0.src, every]), np.concatenate([g0.dst, np.full(every.size, 7, np.int32)]),
+                     np.concatenate([g0.logw, rng.normal(size=every.size).astype(np.float32)]), g0.pdf, g0.init, g0.final)
+    h = _host_graph(g, 9)
+    off = g.state_off if g.packed else np.array([0, g.K])
+    w2 = (g.logw.astype(np.float64) * np.log2(np.e)).astype(np.float32).astype(np.float64)
+    for sub in range(len(off) - 1):
+        k0, k1 = int(off[sub]), int(off[sub + 1])
+        Ks = k1 - k0
+        x = rng.normal(size=Ks) * 5
+        x[rng.integers(0, Ks, size=max(1, Ks // 10))] = -np.inf
+        inside = (g.src >= k0) & (g.src < k1)
+        src, dst, ww = g.src[inside] - k0, g.dst[inside] - k0, w2[inside]
+        for which, rows, cols in ((0, dst, src), (1, src, dst)):
+            y = fb.fb_graph_schedule_apply_host(h, which, sub, x, np.full(Ks, 123.0))
+            want = _direct_product(Ks, rows, cols, ww, x)
+            fin = np.isfinite(want)
+            assert np.array_equal(np.isneginf(y), np.isneginf(want))
+            np.testing.assert_allclose(y[fin], want[fin], rtol=0, atol=1e-6)
+    h.destroy()
+
+
 def test_hub_graphs_really_have_long_rows():
     w = wl.config4(K=900, B=2, Nmin=3, Nmax=4, D=64)
     assert np.bincount(w.den.dst, minlength=900).max() > 32 * 32     # a row spread over all 64 lanes
