@@ -243,6 +243,26 @@ def main() -> int:
                          "exp_frac": upd_den / (stage_ms["den_recursion"] * 1e-3) / (VALU_PEAK_PER_S / 4)},
     }
 
+    # the rate a plain device copy reaches on this machine (1 GiB read + 1 GiB written per copy), beside the published peak
+    src = torch.empty((1 << 28,), dtype=torch.float32, device="cuda").fill_(1.0)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * src.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del src, dst
+    result["roofline"]["copy_gbs"] = copy_gbs
+    result["roofline"]["frac_of_copy"] = achieved / copy_gbs
+    # the whole step against the bytes a fully fused loss+gradient would move per real frame (emission entries read
+    # by both directions, alpha written and read once, gradient written): 8K + 8D' + 4D
+    fused_bytes = frames * (8 * w.den.K + 8 * d_used + 4 * w.D)
+    result["whole_step_hbm"] = {"model_bytes": fused_bytes, "achieved": fused_bytes / (ms_per_step * 1e-3) / 1e9,
+                                "unit": "GB/s", "frac": fused_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
     if args.context:
         result["other_workloads"] = context_workloads(fb, wl, torch)
 

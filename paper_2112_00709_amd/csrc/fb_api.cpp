@@ -63,6 +63,21 @@ int run_recursion(const fb_graph *g, const float *emis, const int32_t *lengths, 
                                                 tropical));
     }
     if (lds > kLdsBytes) return fail(FB_EUNSUPPORTED, "state vectors and emission rows exceed the on-chip memory");
+    // large graphs with float vectors: the instantiation with fixed-length state buffers, when everything fits them
+    // (the tropical instantiation keeps sized buffers: with fixed ones it runs out of registers)
+    if (g->nw == kNWShared && !g->f64 && !tropical && recursion_fixed_available()) {
+        size_t lds_fixed = 0;
+        bool fits = true;
+        for (int i = 0; i < n_dir; ++i) {
+            fits = fits && p.Kcap + dirs[i].Ccap + 1 <= kXsFixed;
+            lds_fixed = std::max(lds_fixed, recursion_lds_bytes(p.Kcap, dirs[i].Ccap, p.Ecap, dirs[i].backward != 0, false,
+                                                                p.shared != 0, tropical, kXsFixed));
+        }
+        if (fits && lds_fixed <= kLdsBytes) {
+            p.xs_fixed = kXsFixed;
+            lds = lds_fixed;
+        }
+    }
     return launch_recursion(g->nw, g->f64, tropical, p, lds, stream);
 }
 

@@ -119,11 +119,12 @@ int upload_stream(fb_graph *g, const StreamHost &h, StreamDev &d)
 
 }  // namespace
 
-size_t recursion_lds_bytes(int32_t Kcap, int32_t Ccap, int32_t Ecap, bool backward, bool f64, bool shared, bool tropical)
+size_t recursion_lds_bytes(int32_t Kcap, int32_t Ccap, int32_t Ecap, bool backward, bool f64, bool shared, bool tropical,
+                           int32_t xs_fixed)
 {
     // carrier-typed: state buffers (states, clone slots, a dump slot) and reduction slots;
     // then three emission rows (float, plus a zero slot), for packed graphs a pdf id per state, the emission index table
-    const size_t xs = (size_t)Kcap + (size_t)Ccap + 1;
+    const size_t xs = xs_fixed ? (size_t)xs_fixed : (size_t)Kcap + (size_t)Ccap + 1;
     return (xs * (backward ? 4 : 2) + 4 * kNWShared + 2) * (f64 ? 8 : 4) + ((size_t)Ecap + 1) * 12 +
            (shared ? 0 : (size_t)Ecap * 4) + (tropical ? xs * 4 : 0) + ((xs + 1) & ~(size_t)1) * 2 +
            kLdsReserve;   // tropical: two rows of 16-bit back-pointers; always: the 16-bit emission index of every target
@@ -326,8 +327,8 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
             const int32_t nv = n_seq > 0 ? -1 : D;
             if (!sell_in_bounds(sell_fwd, nv, why) || !sell_in_bounds(sell_bwd, nv, why))
                 rc = fail(FB_EHIP, "internal error: schedule out of bounds (" + why + ")");
-            else if (!stream_from_sell(sell_fwd, g->max_sub_K, n_seq > 0 ? g->max_sub_K : D, g->h_fwd, why) ||
-                     !stream_from_sell(sell_bwd, g->max_sub_K, n_seq > 0 ? g->max_sub_K : D, g->h_bwd, why))
+            else if (!stream_from_sell(sell_fwd, g->max_sub_K, n_seq > 0 ? g->max_sub_K : D, g->f64 ? 8 : 4, g->h_fwd, why) ||
+                     !stream_from_sell(sell_bwd, g->max_sub_K, n_seq > 0 ? g->max_sub_K : D, g->f64 ? 8 : 4, g->h_bwd, why))
                 rc = fail(FB_EUNSUPPORTED, "graph too large: " + why);
             else if (!stream_in_bounds(g->h_fwd, nv, why) || !stream_in_bounds(g->h_bwd, nv, why))
                 rc = fail(FB_EHIP, "internal error: stream out of bounds (" + why + ")");
@@ -335,7 +336,7 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
             if (rc == FB_OK && g->own_trop) {
                 if (!sell_in_bounds(sell_trop, nv, why))
                     rc = fail(FB_EHIP, "internal error: schedule out of bounds (" + why + ")");
-                else if (!stream_from_sell(sell_trop, g->max_sub_K, n_seq > 0 ? g->max_sub_K : D, g->h_trop, why))
+                else if (!stream_from_sell(sell_trop, g->max_sub_K, n_seq > 0 ? g->max_sub_K : D, g->f64 ? 8 : 4, g->h_trop, why))
                     rc = fail(FB_EUNSUPPORTED, "graph too large: " + why);
                 else if (!stream_in_bounds(g->h_trop, nv, why))
                     rc = fail(FB_EHIP, "internal error: stream out of bounds (" + why + ")");

@@ -17,10 +17,15 @@ constexpr int kChunk = 32;           // arcs one lane walks for a row that has a
 constexpr int kChunkWide = 32;       // arcs one lane walks for a row spread over several lanes
 constexpr size_t kLdsBytes = 160 * 1024;
 constexpr size_t kLdsReserve = 1024; // reduction slots etc.
+// Large graphs with float vectors whose states, clone slots and dump slot fit this many entries run a kernel
+// instantiation whose LDS state buffers have this fixed length: buffer addresses are then compile-time
+// constants and a gather needs no address arithmetic.
+constexpr int kXsFixed = 6656;
 
 // One (src, weight) pair of a row of a sparse semiring matrix, as the kernels read it.
 struct Arc {
-    int32_t src;   // index into the vector the row gathers from
+    int32_t src;   // where the row gathers from: byte offset into the vector (index x element size) in a stream
+                   // (StreamHost), a plain index in a sliced plan (SellHost)
     float w;       // weight (log2 units)
 };
 
@@ -121,6 +126,7 @@ struct StreamHost {
     std::vector<CloneDesc> clones;
     std::vector<int32_t> zero_rows;
     int32_t Kcap = 0, Ccap = 0, Ecap = 0;   // index space of targets and emission indices (see above)
+    int32_t esize = 4;                      // arc sources are index x esize
 };
 
 struct StreamDev {
@@ -133,7 +139,8 @@ struct StreamDev {
     const int32_t *zero_rows = nullptr;
 };
 
-bool stream_from_sell(const SellHost &S, int32_t Kcap, int32_t Ecap, StreamHost &out, std::string &why);
+// esize: bytes per element of the vector the kernel gathers from (4 or 8); arc sources become byte offsets
+bool stream_from_sell(const SellHost &S, int32_t Kcap, int32_t Ecap, int32_t esize, StreamHost &out, std::string &why);
 bool stream_in_bounds(const StreamHost &S, int32_t n_vidx, std::string &why);
 void stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double *y);
 
@@ -221,6 +228,7 @@ struct RecParams {
     const int32_t *lengths;
     int32_t B, N, D, shared, Ktot;
     int32_t Kcap, Ecap;
+    int32_t xs_fixed;      // kXsFixed: launch the fixed-buffer instantiation; 0: buffers sized by the graph
 };
 
 struct PostGraph {
@@ -245,6 +253,7 @@ struct PostParams {
 };
 
 int launch_recursion(int nw, bool f64, bool tropical, const RecParams &p, size_t lds_bytes, void *stream);
+bool recursion_fixed_available();   // the fixed-buffer instantiation (RecParams::xs_fixed) may be launched
 struct BacktraceParams {
     const uint16_t *bp;      // back-pointers written by the recursion kernel
     int64_t bp_ld;           // elements per frame row
@@ -261,8 +270,9 @@ size_t gradient_lds_bytes(const PostParams &p);
 int launch_gradient(const PostParams &p, size_t lds_bytes, void *stream);
 int launch_loss(const double *logz_num, const double *logz_den, const int32_t *lengths, int32_t B, double *loss,
                 void *stream);
+// xs_fixed: 0, or kXsFixed for the fixed-buffer instantiation
 size_t recursion_lds_bytes(int32_t Kcap, int32_t Ccap, int32_t Ecap, bool backward, bool f64, bool shared,
-                           bool tropical = false);
+                           bool tropical = false, int32_t xs_fixed = 0);
 size_t posterior_lds_bytes(const PostParams &p);
 
 }  // namespace fb

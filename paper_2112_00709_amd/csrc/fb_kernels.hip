@@ -24,6 +24,8 @@
 // (they act on differences to the running maximum, which are small).
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "fb_internal.h"
 
 namespace fb {
@@ -194,8 +196,13 @@ __device__ __forceinline__ float wave_sum(float v)
 //   pix  Ecap int32             packed graphs: pdf id of every state
 //   vix  Xs uint16              which staged emission every target (state, clone, dump slot) takes
 //   bpb  2 x Xs uint16          tropical semiring only: back-pointers of the previous / current step
+//
+// XF != 0: the state buffers have the fixed length XF (>= Kcap + Ccap + 1) whatever the graph.  The
+// time loop is then unrolled over the two buffer parities, every buffer address is a compile-time
+// constant, and a gather is one ds_read whose address register is the arc's source field as stored
+// (a byte offset) with the buffer in the instruction's offset field.
 // ---------------------------------------------------------------------------
-template <int NW, class T, bool TROP>
+template <int NW, class T, bool TROP, int XF>
 __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P)
 {
     constexpr int NRES = kResident;
@@ -216,7 +223,8 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
     const int K = sd.K, k0 = sd.k0, nC = sd.n_slot;
     const int Tn = min(max(P.lengths[b], 0), P.N);
     const int nE = P.shared ? P.D : K;           // entries of a staged emission vector
-    const int Xs = P.Kcap + R.Ccap + 1, Es = P.Ecap + 1;
+    const int nX = P.Kcap + R.Ccap + 1;          // states, clone slots, dump slot
+    const int Xs = XF ? XF : nX, Es = P.Ecap + 1;
 
     T *xb = (T *)lds_raw;
     T *bh = xb + 2 * Xs;
@@ -225,6 +233,7 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
     int32_t *pix = (int32_t *)(er + 3 * Es);
     uint16_t *vix = (uint16_t *)(pix + (P.shared ? 0 : P.Ecap));   // emission index of every target
     uint16_t *bpb = vix + ((Xs + 1) & ~1);                         // tropical semiring: 2 x Xs back-pointers
+    constexpr int kSrcShift = sizeof(T) == 4 ? 2 : 3;              // an arc's source field is index << kSrcShift
 
     const float *em_seq = P.emis + (size_t)b * P.N * P.D;
     const size_t out_ld = P.shared ? (size_t)(R.out_ld ? R.out_ld : K) : (size_t)P.Ktot;
@@ -306,7 +315,7 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
         // ---- first frame of this direction: x = start weight (x) v
         if (!P.shared)
             for (int k = tid; k < K; k += NT) pix[k] = P.pdf[k0 + k];
-        for (int k = tid; k < Xs; k += NT) vix[k] = S.vix[(size_t)(P.shared ? 0 : b) * Xs + k];
+        for (int k = tid; k < nX; k += NT) vix[k] = S.vix[(size_t)(P.shared ? 0 : b) * nX + k];
         if (tid < 3) er[tid * Es + P.Ecap] = 0.0f;   // the emission of rows that take none
         __syncthreads();
         if (io_wave) {
@@ -353,9 +362,11 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
         } else {
             const WaveDesc wd = S.waves[sd.wave_ptr0 + wave];
             // a lane's share of a batch is two 16-byte pieces: rows 0-1 and rows 2-3
-            const float4 *stream = (const float4 *)(S.arcs + wd.arc_base) + lane;
-            auto load_batch = [&](Arc(&dst)[kBatchRows], int bidx) {
-                const float4 *p = stream + (size_t)bidx * (2 * kWave);
+            // (the address is a wave-uniform base plus the lane's 16 bytes: no per-lane 64-bit arithmetic)
+            const uint64_t arc_base = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)wd.arc_base) |
+                                      ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(wd.arc_base >> 32)) << 32);
+            const float4 *stream = (const float4 *)(S.arcs + arc_base);
+            auto load_from = [&](Arc(&dst)[kBatchRows], const float4 *p) {   // p: the lane's first piece
                 const float4 lo = p[0], hi = p[kWave];
                 dst[0] = Arc{(int32_t)__float_as_uint(lo.x), lo.y};
                 dst[1] = Arc{(int32_t)__float_as_uint(lo.z), lo.w};
@@ -367,9 +378,13 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
             // ahead of its use, across barriers and across steps (it holds graph data only).
             Arc res[NRES][kBatchRows];
 #pragma unroll
-            for (int q = 0; q < NRES; ++q) load_batch(res[q], q);
-            stream += (size_t)NRES * (2 * kWave);
-            const int n_iter = wd.n_iter, n_batch = n_iter * kRing;   // streamed part
+            for (int q = 0; q < NRES; ++q) load_from(res[q], stream + (size_t)q * (2 * kWave) + lane);
+            // streamed part: rp0 = the lane's piece of its first batch, rp = of the batch to request next (the
+            // requests walk the part cyclically, so the pointer moves by one batch per request and goes back
+            // to rp0 once per time step, at a place every step knows: no index arithmetic per batch)
+            const float4 *const rp0 = stream + (size_t)NRES * (2 * kWave) + lane;
+            const float4 *rp = rp0;
+            const int n_iter = wd.n_iter;
             // flag bytes: words 0-1 of the wave hold those of the resident batches, then one word per
             // iteration; kept in registers (word i in lane i) and read with v_readlane
             const uint32_t *fwp = S.flagwords + wd.flag_base;
@@ -380,7 +395,8 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
             if (n_iter > 0) {
 #pragma unroll
                 for (int j = 0; j + 1 < kRing; ++j) {
-                    load_batch(ring[j], j);
+                    load_from(ring[j], rp);
+                    rp += 2 * kWave;
                     __builtin_amdgcn_sched_barrier(0);   // keep the issue order: waits count loads in order
                 }
             }
@@ -389,15 +405,30 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
             constexpr int GB = kRing % 2 == 0 ? 2 : 3;
             static_assert(kRing % GB == 0, "ring size must be a multiple of the gather buffer count");
             T g[GB][kBatchRows];
-            // closing: the batch closes a slice, the source field of its last row carries the target too
-            auto gather = [&](T(&dst)[kBatchRows], const Arc(&a)[kBatchRows], const T *vbase, bool closing) {
+            // Source fields are byte offsets into the buffer vbase.  With fixed buffers the workgroup's LDS
+            // starts at address 0 (the host launches this instantiation only if the kernel has no static LDS)
+            // and the buffer sits at a constant address, so the load takes the field itself as its address.
+            // The source field of a batch's last row carries the row's target in its upper half when the batch
+            // closes a slice (zero otherwise: offsets stay below 64 KB), so its lower half is the source either way.
+            auto gather = [&](T(&dst)[kBatchRows], const Arc(&a)[kBatchRows], const T *vbase) {
+                auto at = [&](int32_t off) {
+                    if constexpr (XF != 0) {
+                        typedef const __attribute__((address_space(3))) T lds_ct;
+                        const uint32_t addr = (uint32_t)off + (vbase == xb ? 0u : (uint32_t)(XF * sizeof(T)));
+                        return *(lds_ct *)(uintptr_t)addr;
+                    } else {
+                        return *(const T *)((const char *)vbase + off);
+                    }
+                };
 #pragma unroll
-                for (int r = 0; r + 1 < kBatchRows; ++r) dst[r] = vbase[a[r].src];
-                dst[kBatchRows - 1] = vbase[closing ? (int32_t)((uint32_t)a[kBatchRows - 1].src & 0xffffu) : a[kBatchRows - 1].src];
+                for (int r = 0; r + 1 < kBatchRows; ++r) dst[r] = at(a[r].src);
+                dst[kBatchRows - 1] = at((int32_t)((uint32_t)a[kBatchRows - 1].src & 0xffffu));
             };
 
-            for (int i = 1; i < Tn; ++i) {
-                const int cur = (i - 1) & 1, nxt = i & 1;
+            // one time step; curc: parity of the buffer that holds the previous step (an int, or a
+            // compile-time constant when the buffers have fixed addresses)
+            auto step = [&](int i, auto curc) {
+                const int cur = curc, nxt = cur ^ 1;
                 const T *xc = xb + cur * Xs;
                 T *xn = xb + nxt * Xs;
                 T *bn = bh + nxt * Xs;
@@ -419,13 +450,20 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                         if (bwd) bn[k] = kNegInf;
                     }
                 // fold one batch: a, gv = its entries and gathered values; next = the batch after it (its
-                // gathers are issued before this batch's arithmetic), fnext = its flags, has_next: there is one
+                // gathers are issued before this batch's arithmetic), has_next: there is one
                 auto fold = [&](uint32_t f, const Arc(&a)[kBatchRows], const T(&gv)[kBatchRows], T(&gnext)[kBatchRows],
-                                const Arc(&next)[kBatchRows], uint32_t fnext, bool has_next) {
-                    if (has_next) gather(gnext, next, vbase, (fnext & kFlagInfo) != 0);
+                                const Arc(&next)[kBatchRows], bool has_next) {
+                    if (has_next) gather(gnext, next, vbase);
                     if (!(f & kFlagSkip)) {
                         const bool closing = (f & kFlagInfo) != 0;
                         const uint32_t last = (uint32_t)a[3].src;   // closing: source | target << 16
+                        // the target, opaque to the optimiser: for the batches that stay in registers it would
+                        // otherwise keep every target's addresses in registers of their own across the time loop
+                        auto target = [&]() {
+                            uint32_t v = last;
+                            asm volatile("" : "+v"(v));
+                            return v >> 16;
+                        };
                         const T x0 = gv[0] + (T)a[0].w, x1 = gv[1] + (T)a[1].w, x2 = gv[2] + (T)a[2].w, x3 = gv[3] + (T)a[3].w;
                         if constexpr (TROP) {
                             // (+) = max: keep the largest term and the state it came from (the first of equal terms)
@@ -435,14 +473,14 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                             take(x0, a[0].src);
                             take(x1, a[1].src);
                             take(x2, a[2].src);
-                            take(x3, closing ? (int)(last & 0xffffu) : a[3].src);
+                            take(x3, (int)(last & 0xffffu));
                             if (closing) {
                                 const int lg = (int)((f >> kFlagLgShift) & 7u);
                                 if (lg) group_best(m, arg, lg, lane);
-                                const uint32_t tgt = last >> 16;
+                                const uint32_t tgt = target();
                                 const T x = (m - c) + (T)ern[vix[tgt]] * (T)kLog2e;
                                 xn[tgt] = x;
-                                bpn[tgt] = (uint16_t)arg;
+                                bpn[tgt] = (uint16_t)(arg >> kSrcShift);
                                 wmax = tmax(wmax, x);
                                 m = kNegInf;
                                 arg = 0;
@@ -452,7 +490,7 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                             if (closing) {   // the rows' sums are complete
                                 const int lg = (int)((f >> kFlagLgShift) & 7u);
                                 if (lg) group_total(m, sum, lg, lane);   // the row's arcs were spread over 2^lg lanes
-                                const uint32_t tgt = last >> 16;
+                                const uint32_t tgt = target();
                                 const T pre = m + (T)flog2(sum) - c;   // sum == 0 -> -inf
                                 const T x = pre + (T)ern[vix[tgt]] * (T)kLog2e;
                                 xn[tgt] = x;
@@ -466,13 +504,13 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                 };
                 auto rflag = [&](int q) { return ((q < 4 ? rflag0 : rflag1) >> (8 * (q & 3))) & 0xffu; };
                 const uint32_t fw_first = n_iter > 0 ? (uint32_t)__builtin_amdgcn_readlane(fwv0, 0) : 0u;
-                gather(g[0], res[0], vbase, (rflag(0) & kFlagInfo) != 0);
+                gather(g[0], res[0], vbase);
 #pragma unroll
                 for (int q = 0; q < NRES; ++q) {
                     if (q + 1 < NRES)
-                        fold(rflag(q), res[q], g[q % GB], g[(q + 1) % GB], res[q + 1], rflag(q + 1), true);
+                        fold(rflag(q), res[q], g[q % GB], g[(q + 1) % GB], res[q + 1], true);
                     else
-                        fold(rflag(q), res[q], g[q % GB], g[(q + 1) % GB], ring[0], fw_first & 0xffu, n_iter > 0);
+                        fold(rflag(q), res[q], g[q % GB], g[(q + 1) % GB], ring[0], n_iter > 0);
                 }
                 uint32_t fw = fw_first;
                 for (int it = 0; it < n_iter; ++it) {
@@ -482,18 +520,26 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                         itn < kWave ? __builtin_amdgcn_readlane(fwv0, itn) : __builtin_amdgcn_readlane(fwv1, itn - kWave);
 #pragma unroll
                     for (int j = 0; j < kRing; ++j) {
-                        int pf = it * kRing + j + (kRing - 1);
-                        if (pf >= n_batch) pf -= n_batch;
-                        load_batch(ring[(j + kRing - 1) % kRing], pf);
+                        load_from(ring[(j + kRing - 1) % kRing], rp);
+                        if (j == 0 && it + 1 == n_iter) rp = rp0;   // that was the part's last batch
+                        else rp += 2 * kWave;
                         __builtin_amdgcn_sched_barrier(0);
                         fold((fw >> (8 * j)) & 0xffu, ring[j], g[(NRES + j) % GB], g[(NRES + j + 1) % GB], ring[(j + 1) % kRing],
-                             j + 1 < kRing ? (fw >> (8 * (j + 1))) & 0xffu : fwn & 0xffu, j + 1 < kRing || it + 1 < n_iter);
+                             j + 1 < kRing || it + 1 < n_iter);
                     }
                     fw = fwn;
                 }
                 wmax = wave_max(wmax);
                 if (lane == 0) red[nxt * NW + wave] = wmax;
                 __syncthreads();
+            };
+            if constexpr (XF != 0) {
+                for (int i = 1; i < Tn; i += 2) {
+                    step(i, std::integral_constant<int, 0>{});
+                    if (i + 1 < Tn) step(i + 1, std::integral_constant<int, 1>{});
+                }
+            } else {
+                for (int i = 1; i < Tn; ++i) step(i, (i - 1) & 1);
             }
         }
 
@@ -1062,20 +1108,36 @@ static int launch_rec(Kern kern, int nw, const RecParams &p, size_t lds_bytes, v
     return check_launch("recursion kernel launch");
 }
 
+bool recursion_fixed_available()
+{
+    // the fixed-buffer instantiation addresses LDS from 0: usable only while the kernel has no static LDS in front
+    // of its dynamic array (a property of the build, looked up once)
+    static const bool ok = [] {
+        hipFuncAttributes attr{};
+        const hipError_t e = hipFuncGetAttributes(&attr, (const void *)fb_recursion_kernel<kNWShared, float, false, kXsFixed>);
+        return e == hipSuccess && attr.sharedSizeBytes == 0;
+    }();
+    return ok;
+}
+
 int launch_recursion(int nw, bool f64, bool tropical, const RecParams &p, size_t lds_bytes, void *stream)
 {
+    if (p.xs_fixed) {   // fixed-length state buffers: large graphs with float vectors only
+        if (p.xs_fixed != kXsFixed || nw != kNWShared || f64 || tropical) return fail(FB_EHIP, "internal error: fixed-buffer launch");
+        return launch_rec(fb_recursion_kernel<kNWShared, float, false, kXsFixed>, nw, p, lds_bytes, stream);
+    }
     if (tropical) {
         if (nw == kNWShared)
-            return f64 ? launch_rec(fb_recursion_kernel<kNWShared, double, true>, nw, p, lds_bytes, stream)
-                       : launch_rec(fb_recursion_kernel<kNWShared, float, true>, nw, p, lds_bytes, stream);
-        return f64 ? launch_rec(fb_recursion_kernel<kNWSmall, double, true>, nw, p, lds_bytes, stream)
-                   : launch_rec(fb_recursion_kernel<kNWSmall, float, true>, nw, p, lds_bytes, stream);
+            return f64 ? launch_rec(fb_recursion_kernel<kNWShared, double, true, 0>, nw, p, lds_bytes, stream)
+                       : launch_rec(fb_recursion_kernel<kNWShared, float, true, 0>, nw, p, lds_bytes, stream);
+        return f64 ? launch_rec(fb_recursion_kernel<kNWSmall, double, true, 0>, nw, p, lds_bytes, stream)
+                   : launch_rec(fb_recursion_kernel<kNWSmall, float, true, 0>, nw, p, lds_bytes, stream);
     }
     if (nw == kNWShared)
-        return f64 ? launch_rec(fb_recursion_kernel<kNWShared, double, false>, nw, p, lds_bytes, stream)
-                   : launch_rec(fb_recursion_kernel<kNWShared, float, false>, nw, p, lds_bytes, stream);
-    return f64 ? launch_rec(fb_recursion_kernel<kNWSmall, double, false>, nw, p, lds_bytes, stream)
-               : launch_rec(fb_recursion_kernel<kNWSmall, float, false>, nw, p, lds_bytes, stream);
+        return f64 ? launch_rec(fb_recursion_kernel<kNWShared, double, false, 0>, nw, p, lds_bytes, stream)
+                   : launch_rec(fb_recursion_kernel<kNWShared, float, false, 0>, nw, p, lds_bytes, stream);
+    return f64 ? launch_rec(fb_recursion_kernel<kNWSmall, double, false, 0>, nw, p, lds_bytes, stream)
+               : launch_rec(fb_recursion_kernel<kNWSmall, float, false, 0>, nw, p, lds_bytes, stream);
 }
 
 int launch_backtrace(const BacktraceParams &p, void *stream)

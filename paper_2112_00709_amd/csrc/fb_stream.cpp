@@ -47,16 +47,17 @@ size_t wave_batches(const WaveDesc &wd) { return (size_t)kResident + (size_t)wd.
 
 }  // namespace
 
-bool stream_from_sell(const SellHost &S, int32_t Kcap, int32_t Ecap, StreamHost &out, std::string &why)
+bool stream_from_sell(const SellHost &S, int32_t Kcap, int32_t Ecap, int32_t esize, StreamHost &out, std::string &why)
 {
     out.nw = S.nw;
+    out.esize = esize;
     out.Kcap = Kcap;
     out.Ccap = S.max_slot;
     out.Ecap = Ecap;
     out.clones = S.clones;
     out.zero_rows = S.zero_rows;
-    if ((int64_t)Kcap + S.max_slot + 1 > 0xffff || Ecap + 1 > 0xffff) {
-        why = "states plus clone slots, or emission entries, beyond 16 bits";
+    if (((int64_t)Kcap + S.max_slot + 1) * esize > 0xffff || Ecap + 1 > 0xffff) {
+        why = "state vector (with clone slots) beyond 64 KB, or emission entries beyond 16 bits";
         return false;
     }
     const uint32_t dump = (uint32_t)(Kcap + S.max_slot);
@@ -85,6 +86,7 @@ bool stream_from_sell(const SellHost &S, int32_t Kcap, int32_t Ecap, StreamHost 
                     for (int lane = 0; lane < kWave; ++lane) {
                         Arc a = it < trip ? S.arcs[(size_t)S.slice_arc[s] + (size_t)it * kWave + lane] : pad_arc;
                         if (a.src >= ssd.K) a.src = Kcap + (a.src - ssd.K);   // a clone: its slot in the state buffer
+                        a.src *= esize;                                       // byte offset into the buffer
                         if (it == rows - 1) {   // the lane's last entry of the slice also names its target
                             const int32_t o = S.row_out[(size_t)s * kWave + lane], v = S.row_vidx[(size_t)s * kWave + lane];
                             const uint32_t tgt = o < 0 ? dump : (o < ssd.K ? (uint32_t)o : (uint32_t)(Kcap + (o - ssd.K)));
@@ -130,6 +132,7 @@ bool stream_from_sell(const SellHost &S, int32_t Kcap, int32_t Ecap, StreamHost 
 // n_vidx: entries of the staged emission vector (negative: the sub-graph's state count).
 bool stream_in_bounds(const StreamHost &S, int32_t n_vidx, std::string &why)
 {
+    if (S.esize != 4 && S.esize != 8) { why = "element size"; return false; }
     if (S.vix.size() != S.sub.size() * ((size_t)S.Kcap + S.Ccap + 1)) { why = "emission index table size"; return false; }
     for (const SubDesc &sd : S.sub) {
         if (sd.wave_ptr0 < 0 || (size_t)sd.wave_ptr0 + S.nw > S.waves.size()) { why = "wave table range"; return false; }
@@ -161,8 +164,9 @@ bool stream_in_bounds(const StreamHost &S, int32_t n_vidx, std::string &why)
                     for (int lane = 0; lane < kWave; ++lane) {
                         const Arc &a = S.arcs[(size_t)wd.arc_base + entry_at(bt, r, lane)];
                         const bool closing = r == kBatchRows - 1 && (f & kFlagInfo);
-                        const int32_t src = closing ? (int32_t)((uint32_t)a.src & 0xffffu) : a.src;
-                        if (src < 0 || (src >= sd.K && (src < S.Kcap || src >= S.Kcap + sd.n_slot))) {
+                        const int32_t off = closing ? (int32_t)((uint32_t)a.src & 0xffffu) : a.src;
+                        const int32_t src = off / S.esize;
+                        if (off < 0 || off % S.esize || (src >= sd.K && (src < S.Kcap || src >= S.Kcap + sd.n_slot))) {
                             why = "arc source";
                             return false;
                         }
@@ -212,7 +216,7 @@ void stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double
                 for (int lane = 0; lane < kWave; ++lane) {
                     const Arc &a = S.arcs[(size_t)wd.arc_base + entry_at(bt, r, lane)];
                     const bool closing = r == kBatchRows - 1 && (f & kFlagInfo);
-                    const int32_t src = closing ? (int32_t)((uint32_t)a.src & 0xffffu) : a.src;
+                    const int32_t src = (closing ? (int32_t)((uint32_t)a.src & 0xffffu) : a.src) / S.esize;
                     terms[lane].push_back((double)a.w + xe[(size_t)(src < sd.K ? src : sd.K + (src - S.Kcap))]);
                 }
             if (f & kFlagInfo) {
