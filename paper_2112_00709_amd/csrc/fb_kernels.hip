@@ -207,7 +207,8 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
 {
     constexpr int NRES = kResident;
     // The large-graph kernel is the critical path of a call; small-graph launches that run beside it on the same
-    // compute units (the numerators of an LF-MMI call) take the issue slots it leaves.
+    // compute units (the numerators of an LF-MMI call) take the issue slots it leaves.  (The data-moving wave
+    // keeps this priority; the others vary theirs within a time step, see below.)
     if (NW == kNWShared) __builtin_amdgcn_s_setprio(3);
     extern __shared__ double lds_raw[];
     constexpr int NT = NW * kWave, NC = NW - 1;
@@ -269,10 +270,27 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
     auto staged_wait = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
     // a finished vector -> global memory, coalesced; a cloned state leaves as the (+)-sum of its clones
     const CloneDesc *cdesc = S.clones + sd.clone0;
+    // (copies go in groups of several pieces per lane, all read before any is stored: a store's data registers
+    // can only be reused once the store has completed, so a read-one-store-one loop would pay a full HBM
+    // round trip per piece)
+    auto copy_out = [&](auto *orow, const auto *srcv, int n, auto cvt) {
+        constexpr int U = 16;
+        for (int k0 = 0; k0 < n; k0 += U * kWave) {
+            std::remove_cv_t<std::remove_reference_t<decltype(srcv[0])>> v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = srcv[min(k0 + u * kWave + lane, n - 1)];
+#pragma unroll
+            for (int u = 0; u < U; ++u) asm volatile("" : "+v"(v[u]));   // every read stays in front of the stores
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (k0 + u * kWave + lane < n) orow[k0 + u * kWave + lane] = cvt(v[u]);
+        }
+    };
     auto write_row = [&](int f, const T *srcv) {
         if (out_f) {
             float *orow = out_f + (size_t)f * out_ld;
-            for (int k = lane; k < K; k += kWave) orow[k] = (float)srcv[k] * R.out_scale;
+            const float scale = R.out_scale;
+            copy_out(orow, srcv, K, [scale](T x) { return (float)x * scale; });
         } else if (out_t) {
             T *orow = out_t + (size_t)f * out_ld;
             if (sizeof(T) == 4 && (out_ld & 3) == 0 && (size_t)((K + 3) & ~3) <= out_ld && ((uintptr_t)orow & 15) == 0 &&
@@ -281,9 +299,21 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                 // behind the states in LDS into the row's padding, which nobody reads
                 const float4 *s4 = (const float4 *)srcv;
                 float4 *o4 = (float4 *)orow;
-                for (int k = lane; k < (K + 3) / 4; k += kWave) o4[k] = s4[k];
+                constexpr int U = 8;
+                const int n4 = (K + 3) / 4;
+                for (int k0 = 0; k0 < n4; k0 += U * kWave) {
+                    float4 v[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) v[u] = s4[min(k0 + u * kWave + lane, n4 - 1)];
+#pragma unroll
+                    for (int u = 0; u < U; ++u)   // every read stays in front of the stores
+                        asm volatile("" : "+v"(v[u].x), "+v"(v[u].y), "+v"(v[u].z), "+v"(v[u].w));
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+                        if (k0 + u * kWave + lane < n4) o4[k0 + u * kWave + lane] = v[u];
+                }
             } else {
-                for (int k = lane; k < K; k += kWave) orow[k] = srcv[k];
+                copy_out(orow, srcv, K, [](T x) { return x; });
             }
         }
         if (out_f || out_t)
@@ -306,8 +336,8 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
         if (TROP && R.bp) {
             uint16_t *orow = R.bp + (P.shared ? ((size_t)b * P.N + f) * R.bp_ld : (size_t)f * R.bp_ld);
             uint16_t *ost = orow + (P.shared ? 0 : k0), *ocl = orow + (P.shared ? K : P.Ktot + b * R.Ccap);
-            for (int k = lane; k < K; k += kWave) ost[k] = srcb[k];
-            for (int j = lane; j < nC; j += kWave) ocl[j] = srcb[P.Kcap + j];
+            copy_out(ost, srcb, K, [](uint16_t x) { return x; });
+            copy_out(ocl, srcb + P.Kcap, nC, [](uint16_t x) { return x; });
         }
     };
 
@@ -433,6 +463,11 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                 T *xn = xb + nxt * Xs;
                 T *bn = bh + nxt * Xs;
                 const float *ern = er + (i % 3) * Es;
+                // Waves of equal priority are served oldest first, so with one fixed priority the younger waves of
+                // a SIMD would do most of their step alone after the older ones have finished theirs.  A wave's
+                // priority therefore falls as its step advances: whoever has more left goes first, and the waves
+                // of a SIMD reach the barrier together.
+                if (NW == kNWShared) __builtin_amdgcn_s_setprio(3);
                 T M = red[cur * NW];
 #pragma unroll
                 for (int w = 1; w < NW; ++w) M = tmax(M, red[cur * NW + w]);
@@ -513,7 +548,9 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                         fold(rflag(q), res[q], g[q % GB], g[(q + 1) % GB], ring[0], n_iter > 0);
                 }
                 uint32_t fw = fw_first;
+                if (NW == kNWShared) __builtin_amdgcn_s_setprio(2);
                 for (int it = 0; it < n_iter; ++it) {
+                    if (NW == kNWShared && it == (n_iter + 1) / 2) __builtin_amdgcn_s_setprio(1);
                     // flags of the next iteration (its first byte belongs to the batch after this iteration's last)
                     const int itn = it + 1 < n_iter ? it + 1 : it;
                     const uint32_t fwn =
