@@ -112,7 +112,7 @@ int run_posteriors(const PostGraph *gs, int n_graph, const int32_t *lengths, int
     p.lengths = lengths;
     p.B = B; p.N = N; p.D = D;
     p.pdf_out = pdf_out;
-    p.frames_per_block = 8;
+    p.frames_per_block = 6;
     if (gradient_kernel_applies(p)) {   // shared float denominator + small packed numerators: the specialised kernel
         const size_t glds = gradient_lds_bytes(p);
         if (glds <= kLdsBytes) return launch_gradient(p, glds, stream);

@@ -190,7 +190,9 @@ __device__ __forceinline__ float wave_sum(float v)
 //   xb   2 x Xs   x of the previous / current step; Xs = Kcap + Ccap + 1: the
 //                 states, then the clones of rows too long for one slice, then a dump slot
 //   bh   2 x Xs   beta before v is applied (backward direction only)
-//   red  4 x NW   step maxima (two parities), scratch of the last reduction
+//   red  4 x NW   step maxima, scratch of the last reduction.  Float vectors: the maximum of step i is
+//                 word i % 3, reached by one LDS atomic maximum per wave; the data-moving wave clears
+//                 the word of the step after next.  Double vectors: one slot per wave and parity.
 //   er   3 x (Ecap + 1) float   emissions as given (natural log) of the frame in use and
 //                               of the next two; slot Ecap = 0
 //   pix  Ecap int32             packed graphs: pdf id of every state
@@ -243,6 +245,27 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
     T *out_t = (R.out && R.out_carrier) ? (T *)R.out + out_at : nullptr;
     float *off_seq = R.off ? R.off + (size_t)b * P.N : nullptr;
     auto frame = [&](int i) { return bwd ? Tn - 1 - i : i; };
+    // the maximum over the workgroup of the vector of step i (the next step normalises by it)
+    constexpr bool kAtomMax = sizeof(T) == 4;
+    auto put_max = [&](int i, T wmax) {
+        wmax = wave_max(wmax);
+        if (lane == 0) {   // (one lane per wave: atomics of many lanes on one word are served one at a time)
+            if constexpr (kAtomMax)
+                __builtin_amdgcn_ds_fmaxf((__attribute__((address_space(3))) float *)(red + i % 3), (float)wmax, 0, 0, false);
+            else
+                red[(i & 1) * NW + wave] = wmax;
+        }
+    };
+    auto get_max = [&](int i) {
+        if constexpr (kAtomMax) {
+            return red[i % 3];
+        } else {
+            T M = red[(i & 1) * NW];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) M = tmax(M, red[(i & 1) * NW + w]);
+            return M;
+        }
+    };
 
     // ---- duties of the data-moving wave (called by that wave only, all 64 lanes)
     // emissions of frame f -> dst, through the direct global->LDS path (no registers, any length)
@@ -347,6 +370,7 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
             for (int k = tid; k < K; k += NT) pix[k] = P.pdf[k0 + k];
         for (int k = tid; k < nX; k += NT) vix[k] = S.vix[(size_t)(P.shared ? 0 : b) * nX + k];
         if (tid < 3) er[tid * Es + P.Ecap] = 0.0f;   // the emission of rows that take none
+        if (kAtomMax && tid < 3) red[tid] = kNegInf;
         __syncthreads();
         if (io_wave) {
             stage(frame(0), er);
@@ -368,17 +392,14 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
             xb[P.Kcap + k] = kNegInf;
             if (bwd) bh[P.Kcap + k] = kNegInf;
         }
-        wmax = wave_max(wmax);
-        if (lane == 0) red[wave] = wmax;
+        put_max(0, wmax);
         __syncthreads();
 
         double csum = 0.0;
         if (io_wave) {
             for (int i = 1; i < Tn; ++i) {
-                const int cur = (i - 1) & 1, nxt = i & 1;
-                T M = red[cur * NW];
-#pragma unroll
-                for (int w = 1; w < NW; ++w) M = tmax(M, red[cur * NW + w]);
+                const int cur = (i - 1) & 1;
+                const T M = get_max(i - 1);
                 const T c = (M == kNegInf) ? (T)0 : M;
                 csum += (double)c;
                 if (off_seq && lane == 0) off_seq[frame(i)] = (float)c * R.out_scale;
@@ -386,7 +407,10 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                 if (i + 2 < Tn) stage(frame(i + 2), er + ((i + 2) % 3) * Es);   // buffer of frame i-1: no longer read
                 write_row(frame(i - 1), bwd ? bh + cur * Xs : xb + cur * Xs);
                 if (TROP && i >= 2) write_bp(i - 1, bpb + cur * Xs);
-                if (lane == 0) red[nxt * NW + wave] = kNegInf;
+                if (lane == 0) {   // its own slot counts for nothing / the word of step i + 1 starts empty
+                    if (kAtomMax) red[(i + 1) % 3] = kNegInf;
+                    else red[(i & 1) * NW + wave] = kNegInf;
+                }
                 __syncthreads();
             }
         } else {
@@ -468,9 +492,7 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                 // priority therefore falls as its step advances: whoever has more left goes first, and the waves
                 // of a SIMD reach the barrier together.
                 if (NW == kNWShared) __builtin_amdgcn_s_setprio(3);
-                T M = red[cur * NW];
-#pragma unroll
-                for (int w = 1; w < NW; ++w) M = tmax(M, red[cur * NW + w]);
+                const T M = get_max(i - 1);
                 const T c = (M == kNegInf) ? (T)0 : M;
                 wmax = kNegInf;
                 T m = TROP ? kNegInf : (T)kNegBig;
@@ -566,8 +588,7 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                     }
                     fw = fwn;
                 }
-                wmax = wave_max(wmax);
-                if (lane == 0) red[nxt * NW + wave] = wmax;
+                put_max(i, wmax);
                 __syncthreads();
             };
             if constexpr (XF != 0) {
