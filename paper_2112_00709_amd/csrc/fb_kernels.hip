@@ -490,8 +490,16 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                 // Waves of equal priority are served oldest first, so with one fixed priority the younger waves of
                 // a SIMD would do most of their step alone after the older ones have finished theirs.  A wave's
                 // priority therefore falls as its step advances: whoever has more left goes first, and the waves
-                // of a SIMD reach the barrier together.
-                if (NW == kNWShared) __builtin_amdgcn_s_setprio(3);
+                // of a SIMD reach the barrier together.  The younger half of the waves stays one level above the
+                // older half, which would otherwise still win every tie.
+                const bool young = wave >= NW / 2;
+                auto prio = [&](auto level) {   // level: a compile-time constant 1..3
+                    if (NW == kNWShared) {
+                        if (young) __builtin_amdgcn_s_setprio(decltype(level)::value);
+                        else __builtin_amdgcn_s_setprio(decltype(level)::value - 1);
+                    }
+                };
+                prio(std::integral_constant<int, 3>{});
                 const T M = get_max(i - 1);
                 const T c = (M == kNegInf) ? (T)0 : M;
                 wmax = kNegInf;
@@ -570,9 +578,9 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                         fold(rflag(q), res[q], g[q % GB], g[(q + 1) % GB], ring[0], n_iter > 0);
                 }
                 uint32_t fw = fw_first;
-                if (NW == kNWShared) __builtin_amdgcn_s_setprio(2);
+                prio(std::integral_constant<int, 2>{});
                 for (int it = 0; it < n_iter; ++it) {
-                    if (NW == kNWShared && it == (n_iter + 1) / 2) __builtin_amdgcn_s_setprio(1);
+                    if (it == (n_iter + 1) / 2) prio(std::integral_constant<int, 1>{});
                     // flags of the next iteration (its first byte belongs to the batch after this iteration's last)
                     const int itn = it + 1 < n_iter ? it + 1 : it;
                     const uint32_t fwn =
