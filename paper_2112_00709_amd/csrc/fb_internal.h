@@ -65,10 +65,14 @@ struct SellHost {
     std::vector<int32_t> wave_ptr;    // slice ranges per (sub, wave)
     std::vector<int32_t> slice_trip;  // arcs each lane of the slice walks
     std::vector<int32_t> slice_lg;    // log2 of the lanes per row
+    std::vector<int32_t> slice_stack; // 0: a plain slice.  2 / 4: that many slices of rows with at most 2 / exactly 1
+                                      // arcs stacked into one batch of kBatchRows rows (trip = kBatchRows, lg = 0):
+                                      // part t of a lane is rows [t * kBatchRows / stack, (t + 1) * kBatchRows / stack)
     std::vector<int64_t> slice_arc;   // first arc of the slice in `arcs`
-    std::vector<int32_t> row_out;     // [n_slices*64]: >= 0 target (state, or K + clone slot) written by this
-                                      // lane, -1 a lane that writes nothing
-    std::vector<int32_t> row_vidx;    // [n_slices*64]: index of the row's emission in the staged emission vector
+    std::vector<int32_t> row_out;     // [n_slices*64*kBatchRows], entry (slice, lane, part): >= 0 target (state, or
+                                      // K + clone slot) written by this lane for this part, -1 nothing (a plain
+                                      // slice has part 0 only)
+    std::vector<int32_t> row_vidx;    // same shape: index of the row's emission in the staged emission vector
     std::vector<Arc> arcs;            // slice-major, then step, then lane
     std::vector<CloneDesc> clones;
     std::vector<int32_t> zero_rows;   // local ids of rows without arcs
@@ -96,6 +100,10 @@ bool sell_in_bounds(const SellHost &S, int32_t n_vidx, std::string &why);
 // step, so the kernel keeps it kRing-1 batches ahead of its use, across barriers
 // and across steps.
 //
+// Stacked batches (kFlagDual, kFlagQuad; the first kMaxStacked batches of a wave's step only): the rows
+// of several slices whose rows have one or two arcs share one batch, and every part carries its
+// own target in the upper half of the source field of its last row (rows 1 and 3, or all four).
+//
 // Closing entry: src = source index (low 16 bits) | target << 16; the target is an
 // index into the state buffer of the step being written, [0, K) a state, Kcap + slot
 // a clone slot, Kcap + Ccap the dump slot of lanes that write nothing.  The emission
@@ -107,6 +115,9 @@ constexpr int kRing = 3;                        // batches per unrolled iteratio
 constexpr int kResident = 7;                    // batches per wave and step that stay in registers (<= 8)
 constexpr uint32_t kFlagInfo = 0x01;            // the batch closes a slice: its last row carries the targets
 constexpr uint32_t kFlagSkip = 0x04;            // nothing to do in this batch (padding)
+constexpr int kMaxStacked = 2;                  // stacked batches a wave may have: its first batches of a step
+constexpr uint32_t kFlagDual = 0x40;            // with kFlagInfo: two stacked slices, rows 0-1 and rows 2-3, each closed
+constexpr uint32_t kFlagQuad = 0x80;            // with kFlagInfo: four stacked slices of one row each, each closed
 constexpr int kFlagLgShift = 3;                 // bits 3-5 of a closing batch: log2 of the lanes per row
 
 struct WaveDesc {

@@ -25,6 +25,7 @@
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
+#include <utility>
 
 #include "fb_internal.h"
 
@@ -204,6 +205,13 @@ __device__ __forceinline__ float wave_sum(float v)
 // constant, and a gather is one ds_read whose address register is the arc's source field as stored
 // (a byte offset) with the buffer in the instruction's offset field.
 // ---------------------------------------------------------------------------
+// f(integral_constant<int, 0>), f(integral_constant<int, 1>), ...: a loop whose counter is a compile-time constant
+template <class F, int... I>
+__device__ __forceinline__ void unrolled(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+
 template <int NW, class T, bool TROP, int XF>
 __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P)
 {
@@ -218,8 +226,31 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool io_wave = wave == NC;
-    const int b = blockIdx.x % P.B;
-    const RecDir &R = P.dir[blockIdx.x / P.B];
+    // Workgroup -> (sequence, direction).  Workgroups start in the order of their index.  In the large-graph
+    // instantiation (one workgroup fills a compute unit) the longest sequences therefore come first, both
+    // directions of a sequence side by side: whatever delays the start of a workgroup - a second wave of
+    // workgroups when there are more than compute units, workgroups of another launch in the way - then
+    // falls on the sequences that have time to spare.
+    int b = blockIdx.x % P.B;
+    int which = blockIdx.x / P.B;
+    if (NW == kNWShared) {
+        which = blockIdx.x % P.n_dir;
+        const int r = blockIdx.x / P.n_dir;   // this workgroup takes the sequence of rank r by length
+        int *sel = (int *)lds_raw;
+        for (int cand = tid; cand < P.B; cand += NT) {
+            const int lc = min(max(P.lengths[cand], 0), P.N);
+            int rank = 0;   // sequences that go before cand: the longer ones, and of the equally long the earlier ones
+            for (int j = 0; j < P.B; ++j) {
+                const int lj = min(max(P.lengths[j], 0), P.N);
+                rank += (lj > lc || (lj == lc && j < cand)) ? 1 : 0;
+            }
+            if (rank == r) *sel = cand;
+        }
+        __syncthreads();
+        b = __builtin_amdgcn_readfirstlane(*sel);
+        __syncthreads();   // the word is part of a state buffer from here on
+    }
+    const RecDir &R = P.dir[which];
     const StreamDev &S = R.sched;
     const bool bwd = R.backward != 0;
     const SubDesc sd = S.sub[P.shared ? 0 : b];
@@ -464,7 +495,9 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
             // and the buffer sits at a constant address, so the load takes the field itself as its address.
             // The source field of a batch's last row carries the row's target in its upper half when the batch
             // closes a slice (zero otherwise: offsets stay below 64 KB), so its lower half is the source either way.
-            auto gather = [&](T(&dst)[kBatchRows], const Arc(&a)[kBatchRows], const T *vbase) {
+            // stacked: the batch holds the rows of several stacked slices, whose parts all end with a target in
+            // the upper half (only the first kMaxStacked batches of a step can be: the flag is a constant false elsewhere)
+            auto gather = [&](T(&dst)[kBatchRows], const Arc(&a)[kBatchRows], const T *vbase, bool stacked) {
                 auto at = [&](int32_t off) {
                     if constexpr (XF != 0) {
                         typedef const __attribute__((address_space(3))) T lds_ct;
@@ -474,9 +507,18 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                         return *(const T *)((const char *)vbase + off);
                     }
                 };
+                if (stacked) {
 #pragma unroll
-                for (int r = 0; r + 1 < kBatchRows; ++r) dst[r] = at(a[r].src);
-                dst[kBatchRows - 1] = at((int32_t)((uint32_t)a[kBatchRows - 1].src & 0xffffu));
+                    for (int r = 0; r < kBatchRows; ++r) {
+                        uint32_t s = (uint32_t)a[r].src;
+                        asm volatile("" : "+v"(s));   // (not hoisted out of the time loop: see target() below)
+                        dst[r] = at((int32_t)(s & 0xffffu));
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r + 1 < kBatchRows; ++r) dst[r] = at(a[r].src);
+                    dst[kBatchRows - 1] = at((int32_t)((uint32_t)a[kBatchRows - 1].src & 0xffffu));
+                }
             };
 
             // one time step; curc: parity of the buffer that holds the previous step (an int, or a
@@ -516,10 +558,53 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                     }
                 // fold one batch: a, gv = its entries and gathered values; next = the batch after it (its
                 // gathers are issued before this batch's arithmetic), has_next: there is one
-                auto fold = [&](uint32_t f, const Arc(&a)[kBatchRows], const T(&gv)[kBatchRows], T(&gnext)[kBatchRows],
-                                const Arc(&next)[kBatchRows], bool has_next) {
-                    if (has_next) gather(gnext, next, vbase);
-                    if (!(f & kFlagSkip)) {
+                // res: the batch is one of the first kMaxStacked of the step (the only ones that may be stacked);
+                // next_stacked: the batch after it is a stacked one
+                auto fold = [&](auto res, uint32_t f, const Arc(&a)[kBatchRows], const T(&gv)[kBatchRows], T(&gnext)[kBatchRows],
+                                const Arc(&next)[kBatchRows], bool next_stacked, bool has_next) {
+                    if (has_next) gather(gnext, next, vbase, next_stacked);
+                    if (decltype(res)::value && (f & (kFlagDual | kFlagQuad))) {
+                        // Stacked slices: every part of the lane is a row of its own with one or two terms, closed
+                        // here; the running sums of the lane are not touched (stacked batches come first).
+                        // val: the part's (+)-sum; parg: tropical semiring, where its best term came from
+                        auto close_part = [&](T val, int parg, uint32_t field) {
+                            asm volatile("" : "+v"(field));
+                            const uint32_t tgt = field >> 16;
+                            const T pre = val - c;
+                            const T x = pre + (T)ern[vix[tgt]] * (T)kLog2e;
+                            xn[tgt] = x;
+                            if constexpr (TROP) bpn[tgt] = (uint16_t)(parg >> kSrcShift);
+                            else if (bwd) bn[tgt] = pre;
+                            wmax = tmax(wmax, x);
+                        };
+                        T xs[kBatchRows];
+#pragma unroll
+                        for (int r = 0; r < kBatchRows; ++r) xs[r] = gv[r] + (T)a[r].w;
+                        if (f & kFlagQuad) {
+#pragma unroll
+                            for (int r = 0; r < kBatchRows; ++r) {   // one term: the sum is the term
+                                const uint32_t field = (uint32_t)a[r].src;
+                                if constexpr (TROP) close_part(xs[r], xs[r] > kNegInf ? (int)(field & 0xffffu) : 0, field);
+                                else close_part(xs[r] > (T)kNegBig ? xs[r] : kNegInf, 0, field);   // (as the running sums treat it)
+                            }
+                        } else {
+#pragma unroll
+                            for (int p = 0; p < 2; ++p) {
+                                const T u0 = xs[2 * p], u1 = xs[2 * p + 1];
+                                const uint32_t field = (uint32_t)a[2 * p + 1].src;
+                                if constexpr (TROP) {
+                                    T pm = kNegInf;
+                                    int parg = 0;
+                                    if (u0 > pm) { pm = u0; parg = a[2 * p].src; }
+                                    if (u1 > pm) { pm = u1; parg = (int)(field & 0xffffu); }
+                                    close_part(pm, parg, field);
+                                } else {
+                                    const T pm = tmax3((T)kNegBig, u0, u1);
+                                    close_part(pm + (T)flog2(fexp2((float)(u0 - pm)) + fexp2((float)(u1 - pm))), 0, field);   // 0 -> -inf
+                                }
+                            }
+                        }
+                    } else if (!(f & kFlagSkip)) {
                         const bool closing = (f & kFlagInfo) != 0;
                         const uint32_t last = (uint32_t)a[3].src;   // closing: source | target << 16
                         // the target, opaque to the optimiser: for the batches that stay in registers it would
@@ -569,14 +654,16 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                 };
                 auto rflag = [&](int q) { return ((q < 4 ? rflag0 : rflag1) >> (8 * (q & 3))) & 0xffu; };
                 const uint32_t fw_first = n_iter > 0 ? (uint32_t)__builtin_amdgcn_readlane(fwv0, 0) : 0u;
-                gather(g[0], res[0], vbase);
-#pragma unroll
-                for (int q = 0; q < NRES; ++q) {
-                    if (q + 1 < NRES)
-                        fold(rflag(q), res[q], g[q % GB], g[(q + 1) % GB], res[q + 1], true);
+                auto is_stacked = [&](uint32_t f) { return (f & (kFlagDual | kFlagQuad)) != 0; };
+                gather(g[0], res[0], vbase, is_stacked(rflag(0)));
+                unrolled([&](auto qc) {
+                    constexpr int q = decltype(qc)::value;
+                    if constexpr (q + 1 < NRES)
+                        fold(std::bool_constant<(q < kMaxStacked)>{}, rflag(q), res[q], g[q % GB], g[(q + 1) % GB], res[q + 1],
+                             q + 1 < kMaxStacked && is_stacked(rflag(q + 1)), true);
                     else
-                        fold(rflag(q), res[q], g[q % GB], g[(q + 1) % GB], ring[0], n_iter > 0);
-                }
+                        fold(std::bool_constant<(q < kMaxStacked)>{}, rflag(q), res[q], g[q % GB], g[(q + 1) % GB], ring[0], false, n_iter > 0);
+                }, std::make_integer_sequence<int, NRES>{});
                 uint32_t fw = fw_first;
                 prio(std::integral_constant<int, 2>{});
                 for (int it = 0; it < n_iter; ++it) {
@@ -591,7 +678,7 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                         if (j == 0 && it + 1 == n_iter) rp = rp0;   // that was the part's last batch
                         else rp += 2 * kWave;
                         __builtin_amdgcn_sched_barrier(0);
-                        fold((fw >> (8 * j)) & 0xffu, ring[j], g[(NRES + j) % GB], g[(NRES + j + 1) % GB], ring[(j + 1) % kRing],
+                        fold(std::false_type{}, (fw >> (8 * j)) & 0xffu, ring[j], g[(NRES + j) % GB], g[(NRES + j + 1) % GB], ring[(j + 1) % kRing], false,
                              j + 1 < kRing || it + 1 < n_iter);
                     }
                     fw = fwn;

@@ -14,6 +14,7 @@
 //     neither a second pass nor a workgroup barrier;
 //   * rows sorted by length so that a slice is padded little; rows without arcs
 //     are left out (their value is the semiring zero at every step but the first);
+//   * slices of rows with one or two arcs are stacked four (two) to a batch;
 //   * slices are dealt to the waves of the workgroup longest-first, so every
 //     wave walks about the same number of batches per time step.
 #include <algorithm>
@@ -115,37 +116,104 @@ void sell_append(SellHost &S, int32_t k0, int32_t K, const int64_t *ptr, const i
         slices.push_back(sl);
         i += (size_t)sl.count;
     }
-    // deal slices to waves: most batches first, to the least loaded wave
-    std::vector<size_t> order(slices.size());
-    std::iota(order.begin(), order.end(), (size_t)0);
-    std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) { return slices[a].trip > slices[b].trip; });
-    std::vector<std::vector<size_t>> mine((size_t)nw);
+    // Slices whose rows have one arc (or at most two) are stacked, four (two) of them to a batch: a lane then
+    // works on four (two) rows of different slices at once and no batch is three quarters (half) padding.
+    // Stacked batches have a kernel path of their own that exists only for the first batches of a wave's step,
+    // so a wave takes at most kMaxStacked of them and they come first in its list.
+    struct Unit { int stack; size_t sub[kBatchRows]; int n_sub; int64_t batches; };
+    std::vector<Unit> stacked, plain;
+    {
+        std::vector<size_t> one, two;
+        for (size_t s = 0; s < slices.size(); ++s) {
+            if (slices[s].lg == 0 && slices[s].trip == 1) one.push_back(s);
+            else if (slices[s].lg == 0 && slices[s].trip == 2) two.push_back(s);
+            else plain.push_back(Unit{0, {s, 0, 0, 0}, 1, slice_batches(slices[s].trip)});
+        }
+        auto group = [&](const std::vector<size_t> &v, int stack) {
+            for (size_t i = 0; i < v.size(); i += (size_t)stack) {
+                Unit u{stack, {0, 0, 0, 0}, 0, 1};
+                for (size_t j = i; j < v.size() && j < i + (size_t)stack; ++j) u.sub[u.n_sub++] = v[j];
+                if (u.n_sub == 1) plain.push_back(Unit{0, {u.sub[0], 0, 0, 0}, 1, 1});   // nothing to stack it with
+                else stacked.push_back(u);
+            }
+        };
+        group(two, 2);
+        group(one, kBatchRows);
+    }
+    // deal to waves: most batches first, to the wave that would finish first
+    // Waves go round the four SIMDs of a compute unit.  In a 16-wave workgroup the last SIMD hosts the
+    // data-moving wave in place of a fourth arc-walking one, so its three arc-walking waves run a little
+    // faster than the others and take a little more (measured: a tenth more is best).
+    std::vector<std::vector<Unit>> mine((size_t)nw);
     std::vector<int64_t> load((size_t)nw, 0);
-    for (size_t s : order) {
-        // Waves go round the four SIMDs of a compute unit.  In a 16-wave workgroup the last SIMD hosts the
-        // data-moving wave in place of a fourth arc-walking one, so its three arc-walking waves run a little
-        // faster than the others and take a little more (measured: a tenth more is best).
-        const int64_t nbat = slice_batches(slices[s].trip);
-        auto finish = [&](int wv) { return (double)(load[wv] + nbat) / ((nw == kNWShared - 1 && wv % 4 == 3) ? 1.1 : 1.0); };
+    std::vector<int> n_stacked((size_t)nw, 0);
+    auto finish = [&](int wv, int64_t nbat) {
+        return (double)(load[wv] + nbat) / ((nw == kNWShared - 1 && wv % 4 == 3) ? 1.1 : 1.0);
+    };
+    for (const Unit &u : stacked) {
+        int best = -1;
+        for (int wv = 0; wv < nw; ++wv)
+            if (n_stacked[wv] < kMaxStacked && (best < 0 || finish(wv, 1) < finish(best, 1))) best = wv;
+        if (best < 0) {   // every wave has its fill of stacked batches: these slices stay plain
+            for (int j = 0; j < u.n_sub; ++j) plain.push_back(Unit{0, {u.sub[j], 0, 0, 0}, 1, 1});
+            continue;
+        }
+        mine[best].push_back(u);
+        load[best] += 1;
+        ++n_stacked[best];
+    }
+    std::stable_sort(plain.begin(), plain.end(), [&](const Unit &a, const Unit &b) { return a.batches > b.batches; });
+    for (const Unit &u : plain) {
         int best = 0;
         for (int wv = 1; wv < nw; ++wv)
-            if (finish(wv) < finish(best)) best = wv;
-        mine[best].push_back(s);
-        load[best] += nbat;
+            if (finish(wv, u.batches) < finish(best, u.batches)) best = wv;
+        mine[best].push_back(u);
+        load[best] += u.batches;
     }
     for (int wv = 0; wv < nw; ++wv) {
         S.wave_ptr.push_back((int32_t)S.slice_trip.size());
-        for (size_t s : mine[wv]) {
-            const Slice &sl = slices[s];
+        for (const Unit &u : mine[wv]) {
+            if (u.stack) {
+                // one batch: part t of a lane = the lane's row of slice u.sub[t], kBatchRows / stack rows each
+                const int rows_per = kBatchRows / u.stack;
+                S.slice_trip.push_back(kBatchRows);
+                S.slice_lg.push_back(0);
+                S.slice_stack.push_back(u.stack);
+                S.slice_arc.push_back((int64_t)S.arcs.size());
+                for (int lane = 0; lane < kWave; ++lane)
+                    for (int part = 0; part < kBatchRows; ++part) {
+                        const bool live = part < u.n_sub && lane < slices[u.sub[part]].count;
+                        S.row_out.push_back(live ? items[slices[u.sub[part]].first + (size_t)lane].out : -1);
+                        S.row_vidx.push_back(live ? items[slices[u.sub[part]].first + (size_t)lane].vidx : -1);
+                    }
+                for (int row = 0; row < kBatchRows; ++row)
+                    for (int lane = 0; lane < kWave; ++lane) {
+                        Arc a{0, -INFINITY};
+                        const int part = row / rows_per, j = row % rows_per;
+                        if (part < u.n_sub && lane < slices[u.sub[part]].count) {
+                            const Item &im = items[slices[u.sub[part]].first + (size_t)lane];
+                            if (j < im.n) {
+                                a.src = pcol[(size_t)(im.begin + j)];
+                                a.w = pw[(size_t)(im.begin + j)];
+                            }
+                        }
+                        S.arcs.push_back(a);
+                    }
+                continue;
+            }
+            const Slice &sl = slices[u.sub[0]];
             const int g = 1 << sl.lg;
             S.slice_trip.push_back(sl.trip);
             S.slice_lg.push_back(sl.lg);
+            S.slice_stack.push_back(0);
             S.slice_arc.push_back((int64_t)S.arcs.size());
             for (int lane = 0; lane < kWave; ++lane) {
                 const int it = lane >> sl.lg;
                 const bool live = it < sl.count;
-                S.row_out.push_back(live && (lane & (g - 1)) == 0 ? items[sl.first + it].out : -1);
-                S.row_vidx.push_back(live ? items[sl.first + it].vidx : -1);
+                for (int part = 0; part < kBatchRows; ++part) {
+                    S.row_out.push_back(part == 0 && live && (lane & (g - 1)) == 0 ? items[sl.first + it].out : -1);
+                    S.row_vidx.push_back(part == 0 && live ? items[sl.first + it].vidx : -1);
+                }
             }
             // lane t of a row's g lanes walks arcs [t * trip, (t + 1) * trip) of the row
             for (int32_t step = 0; step < sl.trip; ++step)
@@ -175,8 +243,8 @@ void sell_append(SellHost &S, int32_t k0, int32_t K, const int64_t *ptr, const i
 bool sell_in_bounds(const SellHost &S, int32_t n_vidx, std::string &why)
 {
     const size_t n_slices = S.slice_trip.size();
-    if (S.slice_arc.size() != n_slices || S.slice_lg.size() != n_slices || S.row_out.size() != n_slices * kWave ||
-        S.row_vidx.size() != n_slices * kWave) {
+    if (S.slice_arc.size() != n_slices || S.slice_lg.size() != n_slices || S.slice_stack.size() != n_slices ||
+        S.row_out.size() != n_slices * kWave * kBatchRows || S.row_vidx.size() != n_slices * kWave * kBatchRows) {
         why = "slice arrays disagree in size";
         return false;
     }
@@ -194,18 +262,25 @@ bool sell_in_bounds(const SellHost &S, int32_t n_vidx, std::string &why)
         for (int wv = 0; wv < S.nw; ++wv) {
             const int32_t s0 = S.wave_ptr[(size_t)sd.wave_ptr0 + wv], s1 = S.wave_ptr[(size_t)sd.wave_ptr0 + wv + 1];
             if (s0 < 0 || s1 < s0 || (size_t)s1 > n_slices) { why = "slice range"; return false; }
+            int n_stacked = 0;
             for (int32_t s = s0; s < s1; ++s) {
-                const int32_t trip = S.slice_trip[s];
+                const int32_t trip = S.slice_trip[s], stack = S.slice_stack[s];
                 if (trip < 1) { why = "trip count"; return false; }
                 if (S.slice_lg[s] < 0 || S.slice_lg[s] > 6) { why = "lanes per row"; return false; }
+                if (stack != 0 && stack != 2 && stack != kBatchRows) { why = "stack size"; return false; }
+                if (stack && (trip != kBatchRows || S.slice_lg[s] != 0 || s - s0 != n_stacked || ++n_stacked > kMaxStacked)) {
+                    why = "stacked slice";   // one batch, one lane per row, first in the wave's list, at most kMaxStacked
+                    return false;
+                }
                 if (S.slice_arc[s] < 0 || (size_t)S.slice_arc[s] + (size_t)trip * kWave > S.arcs.size()) { why = "arc range"; return false; }
                 for (size_t a = (size_t)S.slice_arc[s]; a < (size_t)S.slice_arc[s] + (size_t)trip * kWave; ++a)
                     if (S.arcs[a].src < 0 || S.arcs[a].src >= n_idx) { why = "arc source"; return false; }
-                for (int lane = 0; lane < kWave; ++lane) {
-                    const int32_t o = S.row_out[(size_t)s * kWave + lane], v = S.row_vidx[(size_t)s * kWave + lane];
+                for (int e = 0; e < kWave * kBatchRows; ++e) {
+                    const int32_t o = S.row_out[(size_t)s * kWave * kBatchRows + e], v = S.row_vidx[(size_t)s * kWave * kBatchRows + e];
                     if (o < -1 || o >= n_idx) { why = "row target"; return false; }
                     if (v < -1 || v >= std::max(n_vidx < 0 ? sd.K : n_vidx, 1)) { why = "emission index"; return false; }
                     if (o >= 0 && v < 0) { why = "row without emission index"; return false; }
+                    if (o >= 0 && e % kBatchRows >= std::max(stack, 1)) { why = "target of a part the slice does not have"; return false; }
                 }
             }
         }

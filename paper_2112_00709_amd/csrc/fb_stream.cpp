@@ -80,23 +80,33 @@ bool stream_from_sell(const SellHost &S, int32_t Kcap, int32_t Ecap, int32_t esi
             };
             const int32_t s0 = S.wave_ptr[(size_t)ssd.wave_ptr0 + wv], s1 = S.wave_ptr[(size_t)ssd.wave_ptr0 + wv + 1];
             for (int32_t s = s0; s < s1; ++s) {
-                const int32_t trip = S.slice_trip[s];
+                const int32_t trip = S.slice_trip[s], stack = S.slice_stack[s];
                 const int32_t nb = (trip + kBatchRows - 1) / kBatchRows, rows = nb * kBatchRows;
+                const int32_t rows_per = stack ? kBatchRows / stack : rows;   // rows of one part of a lane
+                if (stack && flags.size() >= (size_t)kMaxStacked) {
+                    why = "stacked batch behind the first batches of a wave";
+                    return false;
+                }
                 for (int32_t it = 0; it < rows; ++it)
                     for (int lane = 0; lane < kWave; ++lane) {
                         Arc a = it < trip ? S.arcs[(size_t)S.slice_arc[s] + (size_t)it * kWave + lane] : pad_arc;
                         if (a.src >= ssd.K) a.src = Kcap + (a.src - ssd.K);   // a clone: its slot in the state buffer
                         a.src *= esize;                                       // byte offset into the buffer
-                        if (it == rows - 1) {   // the lane's last entry of the slice also names its target
-                            const int32_t o = S.row_out[(size_t)s * kWave + lane], v = S.row_vidx[(size_t)s * kWave + lane];
+                        if (it % rows_per == rows_per - 1) {   // the last entry of a part also names the part's target
+                            const size_t at = ((size_t)s * kWave + lane) * kBatchRows + (size_t)(it / rows_per);
+                            const int32_t o = S.row_out[at], v = S.row_vidx[at];
                             const uint32_t tgt = o < 0 ? dump : (o < ssd.K ? (uint32_t)o : (uint32_t)(Kcap + (o - ssd.K)));
                             a.src = (int32_t)((uint32_t)a.src | (tgt << 16));
                             if (o >= 0) out.vix[vix0 + tgt] = (uint16_t)v;
                         }
                         lin.push_back(a);
                     }
-                for (int32_t bt = 0; bt < nb; ++bt)
-                    flags.push_back(bt + 1 == nb ? (uint8_t)(kFlagInfo | ((uint32_t)S.slice_lg[s] << kFlagLgShift)) : (uint8_t)0);
+                for (int32_t bt = 0; bt < nb; ++bt) {
+                    uint32_t f = bt + 1 == nb ? (kFlagInfo | ((uint32_t)S.slice_lg[s] << kFlagLgShift)) : 0u;
+                    if (stack == 2) f |= kFlagDual;
+                    if (stack == kBatchRows) f |= kFlagQuad;
+                    flags.push_back((uint8_t)f);
+                }
             }
             while (flags.size() < (size_t)kResident || (flags.size() - kResident) % kRing) pad_batch();   // whole iterations
             if ((flags.size() - kResident) / kRing > 2 * kWave) {
@@ -160,10 +170,17 @@ bool stream_in_bounds(const StreamHost &S, int32_t n_vidx, std::string &why)
             for (size_t bt = 0; bt < n_batches; ++bt) {
                 const uint32_t f = batch_flags(S, wd, bt);
                 if (((f >> kFlagLgShift) & 7u) > 6u) { why = "lanes per row"; return false; }
+                const bool dual = (f & kFlagDual) != 0, quad = (f & kFlagQuad) != 0;
+                if ((dual || quad) && (bt >= (size_t)kMaxStacked || !(f & kFlagInfo) || (dual && quad) || ((f >> kFlagLgShift) & 7u) ||
+                                       (f & kFlagSkip))) {
+                    why = "stacked batch";
+                    return false;
+                }
                 for (int r = 0; r < kBatchRows; ++r)
                     for (int lane = 0; lane < kWave; ++lane) {
                         const Arc &a = S.arcs[(size_t)wd.arc_base + entry_at(bt, r, lane)];
-                        const bool closing = r == kBatchRows - 1 && (f & kFlagInfo);
+                        // rows that end a part carry a target
+                        const bool closing = (f & kFlagInfo) && (r == kBatchRows - 1 || quad || (dual && r % 2 == 1));
                         const int32_t off = closing ? (int32_t)((uint32_t)a.src & 0xffffu) : a.src;
                         const int32_t src = off / S.esize;
                         if (off < 0 || off % S.esize || (src >= sd.K && (src < S.Kcap || src >= S.Kcap + sd.n_slot))) {
@@ -211,6 +228,24 @@ void stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double
         for (size_t bt = 0; bt < n_batches; ++bt) {
             const uint32_t f = batch_flags(S, wd, bt);
             if (f & kFlagSkip) continue;
+            if (f & (kFlagDual | kFlagQuad)) {   // stacked slices: every part of a lane is a row of its own, closed here
+                const int rows_per = (f & kFlagQuad) ? 1 : 2;
+                for (int lane = 0; lane < kWave; ++lane)
+                    for (int part = 0; part < kBatchRows / rows_per; ++part) {
+                        std::vector<double> tm;
+                        int32_t t = 0;
+                        for (int j = 0; j < rows_per; ++j) {
+                            const Arc &a = S.arcs[(size_t)wd.arc_base + entry_at(bt, part * rows_per + j, lane)];
+                            const bool last = j == rows_per - 1;
+                            const int32_t src = (last ? (int32_t)((uint32_t)a.src & 0xffffu) : a.src) / S.esize;
+                            tm.push_back((double)a.w + xe[(size_t)(src < sd.K ? src : sd.K + (src - S.Kcap))]);
+                            if (last) t = (int32_t)((uint32_t)a.src >> 16);
+                        }
+                        if (t < sd.K) ye[(size_t)t] = lse(tm);
+                        else if (t < S.Kcap + sd.n_slot) ye[(size_t)sd.K + (size_t)(t - S.Kcap)] = lse(tm);
+                    }
+                continue;
+            }
             const int g = 1 << ((f >> kFlagLgShift) & 7u);
             for (int r = 0; r < kBatchRows; ++r)
                 for (int lane = 0; lane < kWave; ++lane) {
