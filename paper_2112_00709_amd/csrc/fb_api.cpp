@@ -43,10 +43,19 @@ RecDir make_dir(const fb_graph *g, bool backward, void *out, bool out_carrier, f
     return r;
 }
 
+// A range of the sequences in order of length (RecParams::order); order == nullptr: all of them.
+struct RankRange {
+    const int32_t *order = nullptr;
+    int32_t rank0 = 0, count = 0;
+};
+
 int run_recursion(const fb_graph *g, const float *emis, const int32_t *lengths, int32_t B, int32_t N, int32_t D,
-                  const RecDir *dirs, int n_dir, fb_stream stream, bool tropical = false)
+                  const RecDir *dirs, int n_dir, fb_stream stream, bool tropical = false, RankRange range = RankRange())
 {
     RecParams p{};
+    p.order = range.order;
+    p.rank0 = range.rank0;
+    p.n_launch = range.count;
     p.n_dir = n_dir;
     p.pdf = g->d_pdf;
     p.emis = emis;
@@ -100,9 +109,12 @@ PostGraph make_post(const fb_graph *g, const void *a, const void *b, bool f64, f
 }
 
 int run_posteriors(const PostGraph *gs, int n_graph, const int32_t *lengths, int32_t B, int32_t N, int32_t D,
-                   float *pdf_out, fb_stream stream)
+                   float *pdf_out, fb_stream stream, RankRange range = RankRange())
 {
     PostParams p{};
+    p.order = range.order;
+    p.rank0 = range.rank0;
+    p.n_launch = range.count;
     p.n_graph = n_graph;
     for (int i = 0; i < n_graph; ++i) {
         p.g[i] = gs[i];
@@ -124,6 +136,23 @@ int run_posteriors(const PostGraph *gs, int n_graph, const int32_t *lengths, int
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+double env_frac(const char *name, double dflt)   // (tuning aid: a fraction in (0, 1) from the environment)
+{
+    const char *s = getenv(name);
+    const double v = s ? atof(s) : 0.0;
+    return v > 0.0 && v < 1.0 ? v : dflt;
+}
+
+// First rank of length group i + 1 of B sequences in order of length (see lfmmi_loss_grad).
+int32_t group_cut(int32_t B, int i)
+{
+    static const double frac[3] = {env_frac("FB_AMD_CUT0", 0.25), env_frac("FB_AMD_CUT1", 0.60), env_frac("FB_AMD_CUT2", 0.97)};
+    // Workgroups of a launch go round the 8 XCDs of the chip by index, starting at the first: ranges of a
+    // multiple of 4 sequences (8 workgroups) keep every XCD at the same number of workgroups over all launches.
+    const int32_t c = ((int32_t)(frac[i] * B + 0.5) + 2) / 4 * 4;
+    return std::min(std::max(c, 4 * (i + 1)), (B - 4 * (3 - i)) / 4 * 4);
+}
+
 // stage timing of lfmmi_loss_grad (fb_profile_enable / fb_profile_read)
 struct Profile {
     bool on = false, recorded = false;
@@ -135,13 +164,20 @@ void mark(int i, hipStream_t stream)
     if (g_prof.on) (void)hipEventRecord(g_prof.ev[i], stream);
 }
 
-// A second stream (default priority) and two untimed events, created once per process by
+// Three further streams (default priority) and untimed events, created once per process by
 // side_stream_init, which fb_graph_create calls, so that compute calls themselves never allocate.
-// Setting FB_AMD_SERIAL=1 in the environment keeps everything on the caller's stream.
+// With the caller's stream that makes four, the number of hardware queues a process has: one per length
+// group of lfmmi_loss_grad (group 0, the longest sequences, on the caller's stream).  `stream` (= group[0])
+// also takes the numerator launch of a call too small for groups.  Setting FB_AMD_SERIAL=1 in the
+// environment keeps everything on the caller's stream.
+constexpr int kGroups = 4;
 struct SideStream {
     bool ok = false, tried = false;
     hipStream_t stream = nullptr;
     hipEvent_t fork = nullptr, join = nullptr;
+    hipStream_t group[kGroups - 1] = {};
+    hipEvent_t num_done = nullptr;              // the numerator launch has finished
+    hipEvent_t group_done[kGroups - 1] = {};    // a side group's gradient launch has finished
 };
 
 SideStream &side_stream()
@@ -161,10 +197,15 @@ void side_stream_init()
     s.tried = true;
     const char *serial = getenv("FB_AMD_SERIAL");
     if (serial && serial[0] == '1') return;
-    if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) != hipSuccess) return;
     if (hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&s.join, hipEventDisableTiming) != hipSuccess)
+        hipEventCreateWithFlags(&s.join, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&s.num_done, hipEventDisableTiming) != hipSuccess)
         return;
+    for (int i = 0; i < kGroups - 1; ++i)
+        if (hipStreamCreateWithFlags(&s.group[i], hipStreamNonBlocking) != hipSuccess ||
+            hipEventCreateWithFlags(&s.group_done[i], hipEventDisableTiming) != hipSuccess)
+            return;
+    s.stream = s.group[0];
     s.ok = true;
 }
 
@@ -284,7 +325,7 @@ size_t fb_lfmmi_workspace_bytes(const fb_graph *den, const fb_graph *num, int32_
     const size_t den_vec = align256((size_t)B * N * lfmmi_den_ld(den) * (den->f64 ? 8 : 4));
     const size_t num_vec = align256((size_t)N * num->K * (num->f64 ? 8 : 4));
     const size_t z = align256((size_t)B * sizeof(double));
-    return 2 * den_vec + 2 * num_vec + 2 * z;
+    return 2 * den_vec + 2 * num_vec + 2 * z + align256((size_t)B * sizeof(int32_t));   // + the sequences in order of length
 }
 
 int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths, int32_t B,
@@ -310,7 +351,8 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
     void *num_a = w; w += num_vec;
     void *num_b = w; w += num_vec;
     double *zn = logz_num ? logz_num : (double *)w; w += align256((size_t)B * sizeof(double));
-    double *zd = logz_den ? logz_den : (double *)w;
+    double *zd = logz_den ? logz_den : (double *)w; w += align256((size_t)B * sizeof(double));
+    int32_t *order = (int32_t *)w;
 
     // Both recursions of a graph run side by side in one launch.  The denominator launch goes first on
     // the caller's stream; the (much smaller) numerator launch runs beside it on the library's side stream
@@ -322,26 +364,71 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
     dd[0].out_ld = dd[1].out_ld = (int32_t)lfmmi_den_ld(den);
     hipStream_t main_s = (hipStream_t)stream;
     SideStream &side = side_stream();
-    const bool fork = side.ok && hipEventRecord(side.fork, main_s) == hipSuccess &&
-                      hipStreamWaitEvent(side.stream, side.fork, 0) == hipSuccess;
-    hipStream_t num_s = fork ? side.stream : main_s;
-    mark(0, main_s);
-    mark(1, main_s);
-    if ((rc = run_recursion(den, emis, lengths, B, N, D, dd, 2, main_s))) return rc;
-    mark(2, main_s);
-    mark(5, num_s);
-    if ((rc = run_recursion(num, emis, lengths, B, N, D, dn, 2, num_s))) return rc;
-    mark(6, num_s);
-    if (fork && (hipEventRecord(side.join, side.stream) != hipSuccess || hipStreamWaitEvent(main_s, side.join, 0) != hipSuccess))
-        return fail(FB_EHIP, "lfmmi_loss_grad: joining the side stream failed");
-
     // Eq. 17: numerator pdf posteriors minus denominator pdf posteriors
     PostGraph q[2] = {make_post(den, den_a, den_b, den->f64, 1.0f, -1.0f, nullptr),
                       make_post(num, num_a, num_b, num->f64, 1.0f, 1.0f, nullptr)};
     q[0].ld = (int32_t)lfmmi_den_ld(den);
-    if (fork) mark(2, main_s);   // the gradient stage starts when both recursion launches are done
-    if ((rc = run_posteriors(q, 2, lengths, B, N, D, grad, stream))) return rc;
-    mark(3, main_s);
+
+    if (side.ok && B >= 8 * kGroups) {
+        // Length groups.  A sequence's gradient needs only that sequence's vectors, and the sequences of a
+        // batch differ in length, so the compute units of the short ones would idle until the longest
+        // denominator recursion ends.  The batch is therefore cut into kGroups ranges of the sequences in
+        // order of length; every range has a denominator launch and a gradient launch of its own on a stream
+        // of its own, and the gradient of a range starts as soon as that range's recursions are done, on the
+        // compute units its sequences have left.  A denominator workgroup fills a compute unit (no other
+        // workgroup fits beside it), so none of this work shares a compute unit with the longest sequences,
+        // which set the time of the call.  The numerators of all sequences are one launch behind the
+        // denominator launch of the last range (a few very short sequences): launched at once it would take
+        // compute units before every denominator workgroup has one.  Range 0 (the longest sequences) runs on
+        // the caller's stream and is small: its gradient launch is all that is left when its recursion ends.
+        const int32_t cut[kGroups + 1] = {0, group_cut(B, 0), group_cut(B, 1), group_cut(B, 2), B};
+        hipStream_t gs[kGroups] = {main_s, side.group[0], side.group[1], side.group[2]};
+        auto ok = [](hipError_t e) { return e == hipSuccess; };
+        mark(0, main_s);
+        if ((rc = launch_order(lengths, B, N, order, main_s))) return rc;
+        if (!ok(hipEventRecord(side.fork, main_s))) return fail(FB_EHIP, "lfmmi_loss_grad: event record failed");
+        for (int g = 1; g < kGroups; ++g)
+            if (!ok(hipStreamWaitEvent(gs[g], side.fork, 0))) return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
+        mark(1, main_s);
+        for (int g = 0; g < kGroups; ++g) {
+            const RankRange range{order, cut[g], cut[g + 1] - cut[g]};
+            if ((rc = run_recursion(den, emis, lengths, B, N, D, dd, 2, gs[g], false, range))) return rc;
+        }
+        mark(5, gs[kGroups - 1]);
+        if ((rc = run_recursion(num, emis, lengths, B, N, D, dn, 2, gs[kGroups - 1], false, RankRange{order, 0, B}))) return rc;
+        mark(6, gs[kGroups - 1]);
+        if (!ok(hipEventRecord(side.num_done, gs[kGroups - 1]))) return fail(FB_EHIP, "lfmmi_loss_grad: event record failed");
+        for (int g = kGroups - 1; g >= 0; --g) {
+            const RankRange range{order, cut[g], cut[g + 1] - cut[g]};
+            if (g < kGroups - 1 && !ok(hipStreamWaitEvent(gs[g], side.num_done, 0)))
+                return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
+            if (g == 0) mark(2, main_s);   // the longest sequences' recursions are done: the last gradient launch starts
+            if ((rc = run_posteriors(q, 2, lengths, B, N, D, grad, gs[g], range))) return rc;
+            if (g > 0 && !ok(hipEventRecord(side.group_done[g - 1], gs[g])))
+                return fail(FB_EHIP, "lfmmi_loss_grad: event record failed");
+        }
+        for (int g = 1; g < kGroups; ++g)
+            if (!ok(hipStreamWaitEvent(main_s, side.group_done[g - 1], 0))) return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
+        mark(3, main_s);
+    } else {
+        // One launch per stage: the denominator launch on the caller's stream, the (much smaller) numerator
+        // launch beside it on the library's side stream, then the gradient.
+        const bool fork = side.ok && hipEventRecord(side.fork, main_s) == hipSuccess &&
+                          hipStreamWaitEvent(side.stream, side.fork, 0) == hipSuccess;
+        hipStream_t num_s = fork ? side.stream : main_s;
+        mark(0, main_s);
+        mark(1, main_s);
+        if ((rc = run_recursion(den, emis, lengths, B, N, D, dd, 2, main_s))) return rc;
+        mark(2, main_s);
+        mark(5, num_s);
+        if ((rc = run_recursion(num, emis, lengths, B, N, D, dn, 2, num_s))) return rc;
+        mark(6, num_s);
+        if (fork && (hipEventRecord(side.join, side.stream) != hipSuccess || hipStreamWaitEvent(main_s, side.join, 0) != hipSuccess))
+            return fail(FB_EHIP, "lfmmi_loss_grad: joining the side stream failed");
+        if (fork) mark(2, main_s);   // the gradient stage starts when both recursion launches are done
+        if ((rc = run_posteriors(q, 2, lengths, B, N, D, grad, stream))) return rc;
+        mark(3, main_s);
+    }
     rc = launch_loss(zn, zd, lengths, B, loss, stream);
     mark(4, main_s);
     if (g_prof.on && rc == FB_OK) g_prof.recorded = true;

@@ -240,6 +240,10 @@ struct RecParams {
     int32_t B, N, D, shared, Ktot;
     int32_t Kcap, Ecap;
     int32_t xs_fixed;      // kXsFixed: launch the fixed-buffer instantiation; 0: buffers sized by the graph
+    // A launch may cover a range of the sequences in order of length: order[r] = the sequence of rank r
+    // (longest first, written by launch_order), ranks [rank0, rank0 + n_launch).  order == nullptr: all B.
+    const int32_t *order;
+    int32_t rank0, n_launch;
 };
 
 struct PostGraph {
@@ -261,6 +265,8 @@ struct PostParams {
     int32_t B, N, D;
     float *pdf_out;        // [B][N][D], nullable
     int32_t Kcap, Kcap64, frames_per_block;   // Kcap64: largest double-carrier (sub-)graph
+    const int32_t *order;  // as in RecParams: the launch covers ranks [rank0, rank0 + n_launch); nullptr: all B
+    int32_t rank0, n_launch;
 };
 
 int launch_recursion(int nw, bool f64, bool tropical, const RecParams &p, size_t lds_bytes, void *stream);
@@ -279,6 +285,9 @@ int launch_posteriors(const PostParams &p, size_t lds_bytes, void *stream);
 bool gradient_kernel_applies(const PostParams &p);
 size_t gradient_lds_bytes(const PostParams &p);
 int launch_gradient(const PostParams &p, size_t lds_bytes, void *stream);
+// order[r] = index of the sequence of rank r when sorted by length (clamped to [0, N]), longest first, equal
+// lengths by index
+int launch_order(const int32_t *lengths, int32_t B, int32_t N, int32_t *order, void *stream);
 int launch_loss(const double *logz_num, const double *logz_den, const int32_t *lengths, int32_t B, double *loss,
                 void *stream);
 // xs_fixed: 0, or kXsFixed for the fixed-buffer instantiation

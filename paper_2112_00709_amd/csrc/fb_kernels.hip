@@ -231,11 +231,18 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
     // directions of a sequence side by side: whatever delays the start of a workgroup - a second wave of
     // workgroups when there are more than compute units, workgroups of another launch in the way - then
     // falls on the sequences that have time to spare.
-    int b = blockIdx.x % P.B;
-    int which = blockIdx.x / P.B;
+    // (A launch may cover only a range of ranks, P.order then holds the sequences in order of length.)
+    const int n_launch = P.order ? P.n_launch : P.B;
+    int b = blockIdx.x % n_launch;
+    int which = blockIdx.x / n_launch;
     if (NW == kNWShared) {
         which = blockIdx.x % P.n_dir;
-        const int r = blockIdx.x / P.n_dir;   // this workgroup takes the sequence of rank r by length
+        b = blockIdx.x / P.n_dir;
+    }
+    if (P.order) {
+        b = P.order[P.rank0 + b];
+    } else if (NW == kNWShared) {
+        const int r = b;   // this workgroup takes the sequence of rank r by length
         int *sel = (int *)lds_raw;
         for (int cand = tid; cand < P.B; cand += NT) {
             const int lc = min(max(P.lengths[cand], 0), P.N);
@@ -837,7 +844,7 @@ __global__ __launch_bounds__(kPostThreads) void fb_posterior_kernel(const PostPa
     constexpr int NT = kPostThreads, U = kPostPrefetch;
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int b = blockIdx.y;
+    const int b = P.order ? P.order[P.rank0 + blockIdx.y] : blockIdx.y;
     const int T = min(max(P.lengths[b], 0), P.N);
     const int n0 = blockIdx.x * P.frames_per_block;
     const int n_end = min(min(n0 + P.frames_per_block, P.N), T);   // real frames of this chunk: [n0, n_end)
@@ -1007,7 +1014,7 @@ __global__ __launch_bounds__(kGradThreads, 5) void fb_grad_kernel(const PostPara
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool den_side = wave < MT / kWave;
-    const int b = blockIdx.y;
+    const int b = P.order ? P.order[P.rank0 + blockIdx.y] : blockIdx.y;
     const int T = min(max(P.lengths[b], 0), P.N);
     const int n0 = blockIdx.x * P.frames_per_block;
     const int n_end = min(min(n0 + P.frames_per_block, P.N), T);   // real frames of this chunk: [n0, n_end)
@@ -1193,6 +1200,21 @@ __global__ __launch_bounds__(kGradThreads, 5) void fb_grad_kernel(const PostPara
     }
 }
 
+// order[rank] = b: the sequences by length, longest first (equal lengths by index).  One thread per sequence
+// counts the sequences that go before its own.
+__global__ __launch_bounds__(256) void fb_order_kernel(const int32_t *lengths, int32_t B, int32_t N, int32_t *order)
+{
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    if (b >= B) return;
+    const int lb = min(max(lengths[b], 0), N);
+    int rank = 0;
+    for (int j = 0; j < B; ++j) {
+        const int lj = min(max(lengths[j], 0), N);
+        rank += (lj > lb || (lj == lb && j < b)) ? 1 : 0;
+    }
+    order[rank] = b;
+}
+
 // loss = sum_b (log Z_num[b] - log Z_den[b]) over the sequences that have frames (Eq. 16),
 // summed in double in a fixed order.
 __global__ __launch_bounds__(256) void fb_loss_kernel(const double *zn, const double *zd, const int32_t *lengths, int32_t B,
@@ -1257,7 +1279,8 @@ static int launch_rec(Kern kern, int nw, const RecParams &p, size_t lds_bytes, v
         const hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return fail(FB_EHIP, std::string("hipFuncSetAttribute(LDS size): ") + hipGetErrorString(e));
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(p.B * p.n_dir)), dim3(nw * kWave), lds_bytes, (hipStream_t)stream, p);
+    const int32_t n_seq = p.order ? p.n_launch : p.B;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(n_seq * p.n_dir)), dim3(nw * kWave), lds_bytes, (hipStream_t)stream, p);
     return check_launch("recursion kernel launch");
 }
 
@@ -1301,7 +1324,7 @@ int launch_backtrace(const BacktraceParams &p, void *stream)
 
 int launch_posteriors(const PostParams &p, size_t lds_bytes, void *stream)
 {
-    const dim3 grid((unsigned)((p.N + p.frames_per_block - 1) / p.frames_per_block), (unsigned)p.B);
+    const dim3 grid((unsigned)((p.N + p.frames_per_block - 1) / p.frames_per_block), (unsigned)(p.order ? p.n_launch : p.B));
     if (lds_bytes > 64 * 1024) {
         const hipError_t e =
             hipFuncSetAttribute((const void *)fb_posterior_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
@@ -1330,7 +1353,7 @@ size_t gradient_lds_bytes(const PostParams &p)
 
 int launch_gradient(const PostParams &p, size_t lds_bytes, void *stream)
 {
-    const dim3 grid((unsigned)((p.N + p.frames_per_block - 1) / p.frames_per_block), (unsigned)p.B);
+    const dim3 grid((unsigned)((p.N + p.frames_per_block - 1) / p.frames_per_block), (unsigned)(p.order ? p.n_launch : p.B));
     auto kern = p.g[1].f64 ? fb_grad_kernel<double> : fb_grad_kernel<float>;
     if (lds_bytes > 64 * 1024) {
         const hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
@@ -1338,6 +1361,12 @@ int launch_gradient(const PostParams &p, size_t lds_bytes, void *stream)
     }
     hipLaunchKernelGGL(kern, grid, dim3(kGradThreads), lds_bytes, (hipStream_t)stream, p);
     return check_launch("gradient kernel launch");
+}
+
+int launch_order(const int32_t *lengths, int32_t B, int32_t N, int32_t *order, void *stream)
+{
+    hipLaunchKernelGGL(fb_order_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, (hipStream_t)stream, lengths, B, N, order);
+    return check_launch("order kernel launch");
 }
 
 int launch_loss(const double *zn, const double *zd, const int32_t *lengths, int32_t B, double *loss, void *stream)
