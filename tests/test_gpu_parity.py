@@ -277,6 +277,26 @@ def test_gradient_kernel_paths(fb):
     compare_lfmmi(fb, wl.config5(K=250, B=3, Lmin=3, Lmax=6, D=3100), name="lfmmi, D=3100 (general kernel)")
 
 
+@pytest.mark.parametrize("B", [32, 37, 66])
+def test_lfmmi_in_length_groups(fb, B):
+    """Batches large enough for lfmmi_loss_grad to cut them into ranges of sequences by length (one denominator and
+    one gradient launch per range on streams of their own): batch sizes that are and are not multiples of the
+    range granularity, many equal lengths, every sequence checked against the oracle; a second call on the same
+    graphs must give the same bits."""
+    import torch
+    w2 = wl.config5(K=300, B=B, Lmin=2, Lmax=9, D=40)   # 8 distinct lengths: most ranks are decided by index
+    assert np.unique(w2.lengths).size < B // 3
+    compare_lfmmi(fb, w2, name=f"lfmmi in length groups, B={B}")
+    Gd, Gn = fb.graph_from(w2.den, w2.D), fb.graph_from(w2.num, w2.D)
+    e, l = dev(w2.emis), dev(w2.lengths.astype(np.int32))
+    first = [host(x).copy() for x in fb.lfmmi_loss_grad(Gd, Gn, e, l)]
+    again = [host(x).copy() for x in fb.lfmmi_loss_grad(Gd, Gn, e, l)]
+    torch.cuda.synchronize()
+    for a, b in zip(first, again):
+        assert np.array_equal(a, b)
+    Gd.destroy(); Gn.destroy()
+
+
 def test_lfmmi_with_an_infeasible_numerator(fb):
     """A numerator chain longer than its utterance: log Z_num = -inf, its pdf posteriors are 0, the gradient of that
     utterance is minus the denominator's pdf posteriors, nothing is NaN."""
