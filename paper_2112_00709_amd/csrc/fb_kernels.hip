@@ -235,7 +235,7 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
     const int n_launch = P.order ? P.n_launch : P.B;
     int b = blockIdx.x % n_launch;
     int which = blockIdx.x / n_launch;
-    if (NW == kNWShared) {
+    if (NW == kNWShared || P.order) {   // in order of length: both directions of a sequence side by side
         which = blockIdx.x % P.n_dir;
         b = blockIdx.x / P.n_dir;
     }
