@@ -113,11 +113,11 @@ def context_workloads(fb, wl, torch):
     ws = torch.empty((fb.fb_lfmmi_workspace_bytes(den, num, w.B, w.N, w.D),), dtype=torch.uint8, device="cuda")
     grad = torch.empty((w.B, w.N, w.D), dtype=torch.float32, device="cuda")
     for _ in range(2):
-        fb.lfmmi_loss_grad(den, num, emis, lengths, ws=ws, grad=grad)
+        fb.lfmmi_loss_grad(den, num, emis, lengths, ws=ws, grad=grad, lengths_host=w.lengths)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(5):
-        fb.lfmmi_loss_grad(den, num, emis, lengths, ws=ws, grad=grad)
+        fb.lfmmi_loss_grad(den, num, emis, lengths, ws=ws, grad=grad, lengths_host=w.lengths)
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / 5
     upd = w.arc_updates(w.den) + w.arc_updates(w.num)
@@ -140,6 +140,7 @@ def main() -> int:
     ap.add_argument("--context", action="store_true",
                     help="also time fb_alpha + fb_beta + fb_posteriors on configurations 1-4 and on the paper-shaped "
                          "denominator (context figures, added to the JSON line as other_workloads)")
+    ap.add_argument("--context-only", action="store_true", help=argparse.SUPPRESS)   # the child process of --context
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -156,6 +157,9 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     fb.lib()
     torch.cuda.set_device(0)
+    if args.context_only:
+        print(json.dumps(context_workloads(fb, wl, torch)), flush=True)
+        return 0
 
     t_gen = time.time()
     w = wl.config5()
@@ -171,8 +175,8 @@ def main() -> int:
     grad = torch.empty((w.B, w.N, w.D), dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
 
-    def step():
-        return fb.lfmmi_loss_grad(den, num, emis, lengths, ws=ws, grad=grad)
+    def step():   # the host knows the lengths (it made the batch): the entry point for ragged batches
+        return fb.lfmmi_loss_grad(den, num, emis, lengths, ws=ws, grad=grad, lengths_host=w.lengths)
 
     for _ in range(args.warmup):
         step()
@@ -264,7 +268,12 @@ def main() -> int:
                                 "unit": "GB/s", "frac": fused_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
     if args.context:
-        result["other_workloads"] = context_workloads(fb, wl, torch)
+        # In a process of its own, without the library's three group streams: these workloads run fb_alpha and
+        # fb_beta on two streams of the caller's, and a process has only four hardware queues for all its streams.
+        import subprocess
+        child = subprocess.run([sys.executable, os.path.abspath(__file__), "--context-only"], stdout=subprocess.PIPE,
+                               env=dict(os.environ, FB_AMD_GROUPS="0"), check=True, text=True)
+        result["other_workloads"] = json.loads(child.stdout.strip().splitlines()[-1])
 
     if args.calibrate_copy:
         src = torch.empty((1 << 28,), dtype=torch.float32, device="cuda").fill_(1.0)

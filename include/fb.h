@@ -9,6 +9,7 @@
  *   fb_beta          beta_n  = T (beta_{n+1} o v_{n+1})                Eq. 14
  *   fb_posteriors    p(z_n | x) = alpha_n beta_n / sum_z alpha_N(z)    Eq. 15
  *   lfmmi_loss_grad  L = log p(X|G_num) - log p(X|G_den), dL/dphi      Eq. 16-17
+ *   lfmmi_loss_grad_ragged  the same, scheduled for sequences of unequal length
  *
  * and, with the tropical semiring ((+) = max) in place of the log semiring,
  *
@@ -229,6 +230,30 @@ size_t fb_lfmmi_workspace_bytes(const fb_graph *den, const fb_graph *num, int32_
 int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths,
                     int32_t B, int32_t N, int32_t D, double *loss, double *logz_num, double *logz_den,
                     float *grad, void *ws, size_t ws_bytes, fb_stream stream);
+
+/*
+ * The same objective and derivative (Eq. 16-17) for a batch whose sequences differ in length,
+ * given a host copy of the lengths:
+ *   lengths_host  host int32 [B], the values of `lengths`; used to decide how the work is
+ *                 scheduled, never for the results (if it disagrees with `lengths` the call is
+ *                 still correct, only possibly slower); NULL: exactly lfmmi_loss_grad
+ * When the shorter sequences would leave more than 15 % of the denominator recursion's
+ * compute-unit time idle, the batch is cut into four ranges of the sequences in order of length
+ * (the order is computed on the device from `lengths`); every range has its own denominator
+ * and gradient launch on a stream of its own (the caller's and three of the library's), and
+ * the gradient of the shorter ranges runs on the compute units their sequences have left
+ * while the recursion of the longest range is still going.  Everything is forked from and
+ * joined back into `stream` with events, so for the caller the call is ordered on `stream` as
+ * usual.  Otherwise, for B < 32, and when FB_AMD_GROUPS=0 or FB_AMD_SERIAL=1 is in the
+ * environment (the three streams are then not created: with the caller's they take the
+ * four hardware queues a process has), the call is lfmmi_loss_grad.  Same arguments,
+ * workspace, results (bit for bit) and errors as lfmmi_loss_grad; calls from several host
+ * threads must not overlap.
+ */
+int lfmmi_loss_grad_ragged(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths,
+                           const int32_t *lengths_host, int32_t B, int32_t N, int32_t D, double *loss,
+                           double *logz_num, double *logz_den, float *grad, void *ws, size_t ws_bytes,
+                           fb_stream stream);
 
 /* Bytes of device workspace fb_viterbi needs for these sizes (0 on bad arguments). */
 size_t fb_viterbi_workspace_bytes(const fb_graph *g, int32_t B, int32_t N);

@@ -26,7 +26,7 @@ LAYOUT = {"in_ptr": 0, "in_src": 1, "in_w": 2, "in_perm": 3, "out_ptr": 4, "out_
 
 # every symbol include/fb.h declares
 SYMBOLS = ["fb_graph_create", "fb_graph_destroy", "fb_graph_layout_size", "fb_graph_layout", "fb_check_lengths",
-           "fb_alpha", "fb_beta", "fb_posteriors", "fb_lfmmi_workspace_bytes", "lfmmi_loss_grad",
+           "fb_alpha", "fb_beta", "fb_posteriors", "fb_lfmmi_workspace_bytes", "lfmmi_loss_grad", "lfmmi_loss_grad_ragged",
            "fb_limits_max_states", "fb_strerror", "fb_last_error", "fb_graph_schedule_apply_host",
            "fb_profile_enable", "fb_profile_read", "fb_viterbi_workspace_bytes", "fb_viterbi"]
 
@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.fb_lfmmi_workspace_bytes.restype = sz
         L.lfmmi_loss_grad.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.lfmmi_loss_grad.restype = ctypes.c_int
+        L.lfmmi_loss_grad_ragged.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.lfmmi_loss_grad_ragged.restype = ctypes.c_int
         L.fb_limits_max_states.argtypes = [i32, ctypes.c_int]
         L.fb_limits_max_states.restype = i32
         L.fb_viterbi_workspace_bytes.argtypes = [vp, i32, i32]
@@ -263,9 +265,11 @@ def fb_viterbi(g: Graph, emis, lengths, ws=None):
     return score, path
 
 
-def lfmmi_loss_grad(den: Graph, num: Graph, emis, lengths, ws=None, grad=None):
+def lfmmi_loss_grad(den: Graph, num: Graph, emis, lengths, ws=None, grad=None, lengths_host=None):
     """-> (loss [1] float64, logz_num [B], logz_den [B], grad [B,N,D]), all on the device.
-    ``ws`` (uint8 CUDA tensor of fb_lfmmi_workspace_bytes) and ``grad`` may be passed in for reuse."""
+    ``ws`` (uint8 CUDA tensor of fb_lfmmi_workspace_bytes) and ``grad`` may be passed in for reuse.
+    ``lengths_host``: a host copy of ``lengths`` (numpy int32 or a sequence); with it the call goes to
+    lfmmi_loss_grad_ragged, which schedules batches of unequal lengths better (same results)."""
     torch = _torch()
     B, N, D = _dev_inputs(emis, lengths)
     need = fb_lfmmi_workspace_bytes(den, num, B, N, D)
@@ -276,6 +280,14 @@ def lfmmi_loss_grad(den: Graph, num: Graph, emis, lengths, ws=None, grad=None):
     loss = torch.empty((1,), dtype=torch.float64, device=emis.device)
     zn = torch.empty((B,), dtype=torch.float64, device=emis.device)
     zd = torch.empty((B,), dtype=torch.float64, device=emis.device)
-    _check(lib().lfmmi_loss_grad(den.handle, num.handle, _dp(emis), _dp(lengths), B, N, D, _dp(loss), _dp(zn), _dp(zd),
-                                 _dp(grad), _dp(ws), int(ws.numel()), _stream()))
+    if lengths_host is not None:
+        lh = np.ascontiguousarray(np.asarray(lengths_host), dtype=np.int32)
+        if lh.shape != (B,):
+            raise ValueError("lengths_host must hold one length per sequence")
+        _check(lib().lfmmi_loss_grad_ragged(den.handle, num.handle, _dp(emis), _dp(lengths), lh.ctypes.data_as(ctypes.c_void_p),
+                                            B, N, D, _dp(loss), _dp(zn), _dp(zd), _dp(grad), _dp(ws), int(ws.numel()),
+                                            _stream()))
+    else:
+        _check(lib().lfmmi_loss_grad(den.handle, num.handle, _dp(emis), _dp(lengths), B, N, D, _dp(loss), _dp(zn), _dp(zd),
+                                     _dp(grad), _dp(ws), int(ws.numel()), _stream()))
     return loss, zn, zd, grad

@@ -26,10 +26,10 @@ def _make_function():
 
     class _LFMMI(torch.autograd.Function):
         @staticmethod
-        def forward(ctx, emis, lengths, den, num, ws):
+        def forward(ctx, emis, lengths, den, num, ws, lengths_host):
             if emis.dtype != torch.float32 or not emis.is_cuda:
                 raise TypeError("emis must be a float32 tensor on the GPU")
-            loss, zn, zd, grad = lfmmi_loss_grad(den, num, emis.contiguous(), lengths, ws=ws)
+            loss, zn, zd, grad = lfmmi_loss_grad(den, num, emis.contiguous(), lengths, ws=ws, lengths_host=lengths_host)
             ctx.save_for_backward(grad)
             ctx.mark_non_differentiable(zn, zd)
             return loss, zn, zd
@@ -37,7 +37,7 @@ def _make_function():
         @staticmethod
         def backward(ctx, g_loss, _g_zn, _g_zd):
             (grad,) = ctx.saved_tensors
-            return grad * g_loss.to(grad.dtype), None, None, None, None
+            return grad * g_loss.to(grad.dtype), None, None, None, None, None
 
     return _LFMMI
 
@@ -45,17 +45,18 @@ def _make_function():
 _fn = None
 
 
-def lfmmi_loss(emis, lengths, den: Graph, num: Graph, ws: Optional[object] = None):
+def lfmmi_loss(emis, lengths, den: Graph, num: Graph, ws: Optional[object] = None, lengths_host=None):
     """-> (loss [1] float64 (sum over utterances of log Z_num - log Z_den), logz_num [B], logz_den [B]).
 
     ``emis``: float32 CUDA tensor [B, N, D] that may require grad; ``lengths``: int32 CUDA tensor [B];
     ``den``: shared denominator graph; ``num``: packed numerator graphs of the same B utterances;
-    ``ws``: optional reusable workspace (uint8 CUDA tensor of ``fb_lfmmi_workspace_bytes`` bytes).
+    ``ws``: optional reusable workspace (uint8 CUDA tensor of ``fb_lfmmi_workspace_bytes`` bytes);
+    ``lengths_host``: optional host copy of ``lengths`` (batches of unequal lengths are then scheduled better).
     """
     global _fn
     if _fn is None:
         _fn = _make_function()
-    return _fn.apply(emis, lengths, den, num, ws)
+    return _fn.apply(emis, lengths, den, num, ws, lengths_host)
 
 
 def workspace(den: Graph, num: Graph, B: int, N: int, D: int, device="cuda"):

@@ -173,6 +173,7 @@ void mark(int i, hipStream_t stream)
 constexpr int kGroups = 4;
 struct SideStream {
     bool ok = false, tried = false;
+    bool groups_ok = false;                     // the group streams exist (FB_AMD_GROUPS=0 in the environment: they do not)
     hipStream_t stream = nullptr;
     hipEvent_t fork = nullptr, join = nullptr;
     hipStream_t group[kGroups - 1] = {};
@@ -201,12 +202,19 @@ void side_stream_init()
         hipEventCreateWithFlags(&s.join, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&s.num_done, hipEventDisableTiming) != hipSuccess)
         return;
-    for (int i = 0; i < kGroups - 1; ++i)
+    if (hipStreamCreateWithFlags(&s.group[0], hipStreamNonBlocking) != hipSuccess) return;
+    s.stream = s.group[0];
+    s.ok = true;
+    // A process has four hardware queues: a caller who runs work of its own on further streams beside this
+    // library's may prefer to keep them (then lfmmi_loss_grad_ragged works like lfmmi_loss_grad).
+    const char *groups = getenv("FB_AMD_GROUPS");
+    if (groups && groups[0] == '0') return;
+    if (hipEventCreateWithFlags(&s.group_done[0], hipEventDisableTiming) != hipSuccess) return;
+    for (int i = 1; i < kGroups - 1; ++i)
         if (hipStreamCreateWithFlags(&s.group[i], hipStreamNonBlocking) != hipSuccess ||
             hipEventCreateWithFlags(&s.group_done[i], hipEventDisableTiming) != hipSuccess)
             return;
-    s.stream = s.group[0];
-    s.ok = true;
+    s.groups_ok = true;
 }
 
 }  // namespace fb
@@ -328,9 +336,10 @@ size_t fb_lfmmi_workspace_bytes(const fb_graph *den, const fb_graph *num, int32_
     return 2 * den_vec + 2 * num_vec + 2 * z + align256((size_t)B * sizeof(int32_t));   // + the sequences in order of length
 }
 
-int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths, int32_t B,
-                    int32_t N, int32_t D, double *loss, double *logz_num, double *logz_den, float *grad, void *ws,
-                    size_t ws_bytes, fb_stream stream)
+// in_groups: run the batch as ranges of sequences by length (see below)
+static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths, int32_t B,
+                     int32_t N, int32_t D, double *loss, double *logz_num, double *logz_den, float *grad, void *ws,
+                     size_t ws_bytes, fb_stream stream, bool in_groups)
 {
     int rc = check_common("lfmmi_loss_grad", den, emis, lengths, B, N, D);
     if (rc) return rc;
@@ -369,7 +378,7 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
                       make_post(num, num_a, num_b, num->f64, 1.0f, 1.0f, nullptr)};
     q[0].ld = (int32_t)lfmmi_den_ld(den);
 
-    if (side.ok && B >= 8 * kGroups) {
+    if (in_groups && side.groups_ok && B >= 8 * kGroups) {
         // Length groups.  A sequence's gradient needs only that sequence's vectors, and the sequences of a
         // batch differ in length, so the compute units of the short ones would idle until the longest
         // denominator recursion ends.  The batch is therefore cut into kGroups ranges of the sequences in
@@ -433,6 +442,33 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
     mark(4, main_s);
     if (g_prof.on && rc == FB_OK) g_prof.recorded = true;
     return rc;
+}
+
+int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths, int32_t B,
+                    int32_t N, int32_t D, double *loss, double *logz_num, double *logz_den, float *grad, void *ws,
+                    size_t ws_bytes, fb_stream stream)
+{
+    return lfmmi_run(den, num, emis, lengths, B, N, D, loss, logz_num, logz_den, grad, ws, ws_bytes, stream, false);
+}
+
+int lfmmi_loss_grad_ragged(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths,
+                           const int32_t *lengths_host, int32_t B, int32_t N, int32_t D, double *loss, double *logz_num,
+                           double *logz_den, float *grad, void *ws, size_t ws_bytes, fb_stream stream)
+{
+    // Length groups pay when compute units would otherwise idle: the shorter sequences leave
+    // (1 - mean length / longest length) of the denominator launch's compute-unit time unused.
+    bool in_groups = false;
+    if (lengths_host && B > 0 && N > 0) {
+        int64_t sum = 0;
+        int32_t longest = 0;
+        for (int32_t b = 0; b < B; ++b) {
+            const int32_t l = std::min(std::max(lengths_host[b], 0), N);
+            sum += l;
+            longest = std::max(longest, l);
+        }
+        in_groups = longest > 0 && (double)sum < 0.85 * (double)longest * B;
+    }
+    return lfmmi_run(den, num, emis, lengths, B, N, D, loss, logz_num, logz_den, grad, ws, ws_bytes, stream, in_groups);
 }
 
 }  // extern "C"

@@ -122,7 +122,7 @@ def compare_fb(fb, g, D, emis, lengths, sel=None, name="", state="auto", post_to
     return out
 
 
-def compare_lfmmi(fb, w, sel=None, name=""):
+def compare_lfmmi(fb, w, sel=None, name="", ragged=False):
     import torch
     B = w.B
     sel = list(range(B)) if sel is None else list(sel)
@@ -130,7 +130,8 @@ def compare_lfmmi(fb, w, sel=None, name=""):
     ref = oracle.lfmmi(w.den, w.num, w.emis, w.lengths, sel=sel)
     say(f"{name}: lfmmi_loss_grad B={B} N={w.N} D={w.D} Kden={w.den.K} Knum={w.num.K}")
     Gd, Gn = fb.graph_from(w.den, w.D), fb.graph_from(w.num, w.D)
-    loss, zn, zd, grad = fb.lfmmi_loss_grad(Gd, Gn, dev(w.emis), dev(w.lengths.astype(np.int32)))
+    loss, zn, zd, grad = fb.lfmmi_loss_grad(Gd, Gn, dev(w.emis), dev(w.lengths.astype(np.int32)),
+                                            lengths_host=w.lengths if ragged else None)
     torch.cuda.synchronize()
     loss, zn, zd = float(host(loss)[0]), host(zn), host(zd)
     for i, b in enumerate(sel):
@@ -214,6 +215,7 @@ def test_config5_full_size_sampled(fb):
     order = np.argsort(w.lengths)
     sel = [int(order[0]), int(order[len(order) // 3]), int(order[-1])]
     compare_lfmmi(fb, w, sel=sel, name="config5-full")
+    compare_lfmmi(fb, w, sel=sel, name="config5-full, as bench.py launches it", ragged=True)
 
 
 def test_carrier_precision_can_be_forced(fb):
@@ -282,18 +284,21 @@ def test_lfmmi_in_length_groups(fb, B):
     """Batches large enough for lfmmi_loss_grad to cut them into ranges of sequences by length (one denominator and
     one gradient launch per range on streams of their own): batch sizes that are and are not multiples of the
     range granularity, many equal lengths, every sequence checked against the oracle; a second call on the same
-    graphs must give the same bits."""
+    graphs and the plain entry point must give the same bits."""
     import torch
     w2 = wl.config5(K=300, B=B, Lmin=2, Lmax=9, D=40)   # 8 distinct lengths: most ranks are decided by index
     assert np.unique(w2.lengths).size < B // 3
-    compare_lfmmi(fb, w2, name=f"lfmmi in length groups, B={B}")
+    assert w2.lengths.mean() < 0.85 * w2.lengths.max()   # unequal enough for the ragged entry point to cut
+    compare_lfmmi(fb, w2, name=f"lfmmi in length groups, B={B}", ragged=True)
     Gd, Gn = fb.graph_from(w2.den, w2.D), fb.graph_from(w2.num, w2.D)
     e, l = dev(w2.emis), dev(w2.lengths.astype(np.int32))
-    first = [host(x).copy() for x in fb.lfmmi_loss_grad(Gd, Gn, e, l)]
-    again = [host(x).copy() for x in fb.lfmmi_loss_grad(Gd, Gn, e, l)]
+    first = [host(x).copy() for x in fb.lfmmi_loss_grad(Gd, Gn, e, l, lengths_host=w2.lengths)]
+    again = [host(x).copy() for x in fb.lfmmi_loss_grad(Gd, Gn, e, l, lengths_host=w2.lengths)]
+    plain = [host(x).copy() for x in fb.lfmmi_loss_grad(Gd, Gn, e, l)]
     torch.cuda.synchronize()
-    for a, b in zip(first, again):
+    for a, b, c in zip(first, again, plain):
         assert np.array_equal(a, b)
+        assert np.array_equal(a, c)                      # the two entry points agree bit for bit
     Gd.destroy(); Gn.destroy()
 
 
