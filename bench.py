@@ -33,7 +33,7 @@ VALU_PEAK_PER_S = 256 * 64 * 2.4e9
 # HBM bytes per denominator-recursion launch on configuration 5 from rocprofv3 --pmc
 # (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on a plain copy kernel);
 # see profiles/.  None until measured for the workload being run.
-MEASURED_TRAFFIC_BYTES = {"config5": 521000 * 1024 * 2.00 + 2071000 * 1024 * 1.00}
+MEASURED_TRAFFIC_BYTES = {"config5": 532601 * 1024 * 2.00 + 2077313 * 1024 * 1.00}
 
 
 def log(*a):
@@ -233,7 +233,10 @@ def main() -> int:
         "arc_updates_padded": 2 * w.B * w.N * w.den.E,
         "stage_ms": stage_ms,
         "loss": loss,
-        "roofline": {"kernel": "fb_recursion_kernel<16> (denominator alpha+beta, one launch)",
+        # the denominator recursion of a step is four launches of this kernel (one per length group, on four
+        # streams) that start together; achieved = the bytes of all four / the time from their start to the end
+        # of the last one (the longest sequences'), which is what den_recursion brackets
+        "roofline": {"kernel": "fb_recursion_kernel<16> (denominator alpha+beta; 4 concurrent launches, one per length group)",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes": algo_bytes, "launch_ms": stage_ms["den_recursion"]},
