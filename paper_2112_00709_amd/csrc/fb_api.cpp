@@ -401,6 +401,11 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
         mark(1, main_s);
         for (int g = 0; g < kGroups; ++g) {
             const RankRange range{order, cut[g], cut[g + 1] - cut[g]};
+            // The workgroups of the longest range should be the first to be placed.  When calls follow one
+            // another without a pause all four launches are already queued when the fork event fires and would
+            // be dispatched at the same moment; an empty kernel in front of the others holds them back by a
+            // launch latency (measured: 0.1 ms per call).
+            if (g > 0 && (rc = launch_delay(gs[g]))) return rc;
             if ((rc = run_recursion(den, emis, lengths, B, N, D, dd, 2, gs[g], false, range))) return rc;
         }
         mark(5, gs[kGroups - 1]);

@@ -287,6 +287,7 @@ size_t gradient_lds_bytes(const PostParams &p);
 int launch_gradient(const PostParams &p, size_t lds_bytes, void *stream);
 // order[r] = index of the sequence of rank r when sorted by length (clamped to [0, N]), longest first, equal
 // lengths by index
+int launch_delay(void *stream);   // an empty kernel: what follows on the stream starts a launch latency later
 int launch_order(const int32_t *lengths, int32_t B, int32_t N, int32_t *order, void *stream);
 int launch_loss(const double *logz_num, const double *logz_den, const int32_t *lengths, int32_t B, double *loss,
                 void *stream);
