@@ -399,30 +399,38 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
         for (int g = 1; g < kGroups; ++g)
             if (!ok(hipStreamWaitEvent(gs[g], side.fork, 0))) return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
         mark(1, main_s);
-        for (int g = 0; g < kGroups; ++g) {
-            const RankRange range{order, cut[g], cut[g + 1] - cut[g]};
-            // The workgroups of the longest range should be the first to be placed.  When calls follow one
-            // another without a pause all four launches are already queued when the fork event fires and would
-            // be dispatched at the same moment; an empty kernel in front of the others holds them back by a
-            // launch latency (measured: 0.1 ms per call).
-            if (g > 0 && (rc = launch_delay(gs[g]))) return rc;
-            if ((rc = run_recursion(den, emis, lengths, B, N, D, dd, 2, gs[g], false, range))) return rc;
-        }
-        mark(5, gs[kGroups - 1]);
-        if ((rc = run_recursion(num, emis, lengths, B, N, D, dn, 2, gs[kGroups - 1], false, RankRange{order, 0, B}))) return rc;
-        mark(6, gs[kGroups - 1]);
-        if (!ok(hipEventRecord(side.num_done, gs[kGroups - 1]))) return fail(FB_EHIP, "lfmmi_loss_grad: event record failed");
-        for (int g = kGroups - 1; g >= 0; --g) {
-            const RankRange range{order, cut[g], cut[g + 1] - cut[g]};
-            if (g < kGroups - 1 && !ok(hipStreamWaitEvent(gs[g], side.num_done, 0)))
-                return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
-            if (g == 0) mark(2, main_s);   // the longest sequences' recursions are done: the last gradient launch starts
-            if ((rc = run_posteriors(q, 2, lengths, B, N, D, grad, gs[g], range))) return rc;
-            if (g > 0 && !ok(hipEventRecord(side.group_done[g - 1], gs[g])))
-                return fail(FB_EHIP, "lfmmi_loss_grad: event record failed");
-        }
+        // From here on the side streams hold work of this call: whatever happens, the caller's stream waits
+        // for them before the call returns.
+        auto stages = [&]() -> int {
+            int r;
+            for (int g = 0; g < kGroups; ++g) {
+                const RankRange range{order, cut[g], cut[g + 1] - cut[g]};
+                // The workgroups of the longest range should be the first to be placed.  When calls follow one
+                // another without a pause all four launches are already queued when the fork event fires and
+                // would be dispatched at the same moment; an empty kernel in front of the others holds them
+                // back by a launch latency (measured: 0.1 ms per call).
+                if (g > 0 && (r = launch_delay(gs[g]))) return r;
+                if ((r = run_recursion(den, emis, lengths, B, N, D, dd, 2, gs[g], false, range))) return r;
+            }
+            mark(5, gs[kGroups - 1]);
+            if ((r = run_recursion(num, emis, lengths, B, N, D, dn, 2, gs[kGroups - 1], false, RankRange{order, 0, B}))) return r;
+            mark(6, gs[kGroups - 1]);
+            if (!ok(hipEventRecord(side.num_done, gs[kGroups - 1]))) return fail(FB_EHIP, "lfmmi_loss_grad: event record failed");
+            for (int g = kGroups - 1; g >= 0; --g) {
+                const RankRange range{order, cut[g], cut[g + 1] - cut[g]};
+                if (g < kGroups - 1 && !ok(hipStreamWaitEvent(gs[g], side.num_done, 0)))
+                    return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
+                if (g == 0) mark(2, main_s);   // the longest sequences' recursions are done: the last gradient launch starts
+                if ((r = run_posteriors(q, 2, lengths, B, N, D, grad, gs[g], range))) return r;
+            }
+            return FB_OK;
+        };
+        rc = stages();
         for (int g = 1; g < kGroups; ++g)
-            if (!ok(hipStreamWaitEvent(main_s, side.group_done[g - 1], 0))) return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
+            if ((!ok(hipEventRecord(side.group_done[g - 1], gs[g])) || !ok(hipStreamWaitEvent(main_s, side.group_done[g - 1], 0))) &&
+                rc == FB_OK)
+                rc = fail(FB_EHIP, "lfmmi_loss_grad: joining the group streams failed");
+        if (rc) return rc;
         mark(3, main_s);
     } else {
         // One launch per stage: the denominator launch on the caller's stream, the (much smaller) numerator
@@ -432,13 +440,16 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
         hipStream_t num_s = fork ? side.stream : main_s;
         mark(0, main_s);
         mark(1, main_s);
-        if ((rc = run_recursion(den, emis, lengths, B, N, D, dd, 2, main_s))) return rc;
+        rc = run_recursion(den, emis, lengths, B, N, D, dd, 2, main_s);
         mark(2, main_s);
         mark(5, num_s);
-        if ((rc = run_recursion(num, emis, lengths, B, N, D, dn, 2, num_s))) return rc;
+        if (rc == FB_OK) rc = run_recursion(num, emis, lengths, B, N, D, dn, 2, num_s);
         mark(6, num_s);
-        if (fork && (hipEventRecord(side.join, side.stream) != hipSuccess || hipStreamWaitEvent(main_s, side.join, 0) != hipSuccess))
-            return fail(FB_EHIP, "lfmmi_loss_grad: joining the side stream failed");
+        // the caller's stream waits for the side stream also when a launch has failed
+        if (fork && (hipEventRecord(side.join, side.stream) != hipSuccess || hipStreamWaitEvent(main_s, side.join, 0) != hipSuccess) &&
+            rc == FB_OK)
+            rc = fail(FB_EHIP, "lfmmi_loss_grad: joining the side stream failed");
+        if (rc) return rc;
         if (fork) mark(2, main_s);   // the gradient stage starts when both recursion launches are done
         if ((rc = run_posteriors(q, 2, lengths, B, N, D, grad, stream))) return rc;
         mark(3, main_s);
