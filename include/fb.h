@@ -232,23 +232,31 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
                     float *grad, void *ws, size_t ws_bytes, fb_stream stream);
 
 /*
- * The same objective and derivative (Eq. 16-17) for a batch whose sequences differ in length,
- * given a host copy of the lengths:
+ * The same objective and derivative (Eq. 16-17), given a host copy of the lengths, from which
+ * the library picks how the work of the call is scheduled:
  *   lengths_host  host int32 [B], the values of `lengths`; used to decide how the work is
  *                 scheduled, never for the results (if it disagrees with `lengths` the call is
  *                 still correct, only possibly slower); NULL: exactly lfmmi_loss_grad
- * When the shorter sequences would leave more than 15 % of the denominator recursion's
- * compute-unit time idle, the batch is cut into four ranges of the sequences in order of length
- * (the order is computed on the device from `lengths`); every range has its own denominator
- * and gradient launch on a stream of its own (the caller's and three of the library's), and
- * the gradient of the shorter ranges runs on the compute units their sequences have left
- * while the recursion of the longest range is still going.  Everything is forked from and
- * joined back into `stream` with events, so for the caller the call is ordered on `stream` as
- * usual.  Otherwise, for B < 32, and when FB_AMD_GROUPS=0 or FB_AMD_SERIAL=1 is in the
- * environment (the three streams are then not created: with the caller's they take the
- * four hardware queues a process has), the call is lfmmi_loss_grad.  Same arguments,
- * workspace, results (bit for bit) and errors as lfmmi_loss_grad; calls from several host
- * threads must not overlap.
+ * (a) Sequences that differ in length: when the shorter ones would leave more than 15 % of the
+ * denominator recursion's compute-unit time idle (and B >= 32), the batch is cut into four ranges
+ * of the sequences in order of length (the order is computed on the device from `lengths`);
+ * every range has its own denominator and gradient launch on a stream of its own (the caller's
+ * and three of the library's), and the gradient of the shorter ranges runs on the compute
+ * units their sequences have left while the recursion of the longest range is still going.
+ * Results equal lfmmi_loss_grad's bit for bit.  Not used when FB_AMD_GROUPS=0 or
+ * FB_AMD_SERIAL=1 is in the environment (the three streams are then not created: with the
+ * caller's they take the four hardware queues a process has).
+ * (b) Sequences of (nearly) equal length, a denominator graph large enough for the 16-wave
+ * kernel and 2 B >= the number of compute units: no compute unit falls free before the
+ * denominator recursion ends, so the numerator recursion cannot hide beside it.  The
+ * denominator's share of the gradient is then formed while the numerator recursion runs (on
+ * the library's side stream) and the numerators' share is added by a last small launch;
+ * the gradient may differ from lfmmi_loss_grad's by the rounding of that one addition.
+ * Not used when FB_AMD_SERIAL=1 is in the environment.
+ * (c) Otherwise the call is lfmmi_loss_grad.
+ * In every case the library's streams are forked from and joined back into `stream` with
+ * events, so for the caller the call is ordered on `stream` as usual.  Same arguments,
+ * workspace and errors as lfmmi_loss_grad; calls from several host threads must not overlap.
  */
 int lfmmi_loss_grad_ragged(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths,
                            const int32_t *lengths_host, int32_t B, int32_t N, int32_t D, double *loss,

@@ -51,7 +51,7 @@ def lfmmi_loss(emis, lengths, den: Graph, num: Graph, ws: Optional[object] = Non
     ``emis``: float32 CUDA tensor [B, N, D] that may require grad; ``lengths``: int32 CUDA tensor [B];
     ``den``: shared denominator graph; ``num``: packed numerator graphs of the same B utterances;
     ``ws``: optional reusable workspace (uint8 CUDA tensor of ``fb_lfmmi_workspace_bytes`` bytes);
-    ``lengths_host``: optional host copy of ``lengths`` (batches of unequal lengths are then scheduled better).
+    ``lengths_host``: optional host copy of ``lengths`` (the launches of the call are then scheduled by them).
     """
     global _fn
     if _fn is None:

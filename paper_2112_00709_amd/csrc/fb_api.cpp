@@ -109,9 +109,10 @@ PostGraph make_post(const fb_graph *g, const void *a, const void *b, bool f64, f
 }
 
 int run_posteriors(const PostGraph *gs, int n_graph, const int32_t *lengths, int32_t B, int32_t N, int32_t D,
-                   float *pdf_out, fb_stream stream, RankRange range = RankRange())
+                   float *pdf_out, fb_stream stream, RankRange range = RankRange(), bool accumulate = false)
 {
     PostParams p{};
+    p.accumulate = accumulate ? 1 : 0;
     p.order = range.order;
     p.rank0 = range.rank0;
     p.n_launch = range.count;
@@ -128,6 +129,10 @@ int run_posteriors(const PostGraph *gs, int n_graph, const int32_t *lengths, int
     if (gradient_kernel_applies(p)) {   // shared float denominator + small packed numerators: the specialised kernel
         const size_t glds = gradient_lds_bytes(p);
         if (glds <= kLdsBytes) return launch_gradient(p, glds, stream);
+    }
+    if (num_add_kernel_applies(p)) {
+        p.frames_per_block = 8;
+        return launch_num_add(p, stream);
     }
     const size_t lds = posterior_lds_bytes(p);
     if (lds > kLdsBytes) return fail(FB_EUNSUPPORTED, "state vector, pdf row and pdf tables exceed the on-chip memory");
@@ -176,6 +181,7 @@ struct SideStream {
     bool groups_ok = false;                     // the group streams exist (FB_AMD_GROUPS=0 in the environment: they do not)
     hipStream_t stream = nullptr;
     hipEvent_t fork = nullptr, join = nullptr;
+    int n_cu = 0;                               // compute units of the device
     hipStream_t group[kGroups - 1] = {};
     hipEvent_t num_done = nullptr;              // the numerator launch has finished
     hipEvent_t group_done[kGroups - 1] = {};    // a side group's gradient launch has finished
@@ -196,6 +202,9 @@ void side_stream_init()
     SideStream &s = side_stream();
     if (s.tried) return;
     s.tried = true;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&s.n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        s.n_cu = 0;
     const char *serial = getenv("FB_AMD_SERIAL");
     if (serial && serial[0] == '1') return;
     if (hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) != hipSuccess ||
@@ -336,10 +345,11 @@ size_t fb_lfmmi_workspace_bytes(const fb_graph *den, const fb_graph *num, int32_
     return 2 * den_vec + 2 * num_vec + 2 * z + align256((size_t)B * sizeof(int32_t));   // + the sequences in order of length
 }
 
-// in_groups: run the batch as ranges of sequences by length (see below)
+// in_groups: run the batch as ranges of sequences by length; num_apart: the numerators' share of the gradient in a
+// launch of its own (see below)
 static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths, int32_t B,
                      int32_t N, int32_t D, double *loss, double *logz_num, double *logz_den, float *grad, void *ws,
-                     size_t ws_bytes, fb_stream stream, bool in_groups)
+                     size_t ws_bytes, fb_stream stream, bool in_groups, bool num_apart)
 {
     int rc = check_common("lfmmi_loss_grad", den, emis, lengths, B, N, D);
     if (rc) return rc;
@@ -432,6 +442,30 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
                 rc = fail(FB_EHIP, "lfmmi_loss_grad: joining the group streams failed");
         if (rc) return rc;
         mark(3, main_s);
+    } else if (num_apart && side.ok) {
+        // Sequences of (nearly) equal length whose denominator workgroups fill the chip: no compute unit falls
+        // free before the denominator recursion ends, so the numerator recursion cannot run beside it and would
+        // stand between it and the gradient.  Here the denominator's share of the gradient (minus its pdf
+        // posteriors, every row of the output) starts as soon as the denominator recursion is done, the numerator
+        // recursion runs beside that launch, and a last small launch adds the numerators' pdf posteriors to the
+        // rows (each touches only the pdfs its sequence's graph uses).
+        if (hipEventRecord(side.fork, main_s) != hipSuccess || hipStreamWaitEvent(side.stream, side.fork, 0) != hipSuccess)
+            return fail(FB_EHIP, "lfmmi_loss_grad: forking the side stream failed");
+        mark(0, main_s);
+        mark(1, main_s);
+        rc = run_recursion(den, emis, lengths, B, N, D, dd, 2, main_s);
+        mark(2, main_s);
+        mark(5, side.stream);
+        if (rc == FB_OK) rc = run_recursion(num, emis, lengths, B, N, D, dn, 2, side.stream);
+        mark(6, side.stream);
+        if (rc == FB_OK) rc = run_posteriors(&q[0], 1, lengths, B, N, D, grad, main_s);
+        // the caller's stream waits for the side stream also when a launch has failed
+        if ((hipEventRecord(side.join, side.stream) != hipSuccess || hipStreamWaitEvent(main_s, side.join, 0) != hipSuccess) &&
+            rc == FB_OK)
+            rc = fail(FB_EHIP, "lfmmi_loss_grad: joining the side stream failed");
+        if (rc) return rc;
+        if ((rc = run_posteriors(&q[1], 1, lengths, B, N, D, grad, main_s, RankRange(), true))) return rc;
+        mark(3, main_s);
     } else {
         // One launch per stage: the denominator launch on the caller's stream, the (much smaller) numerator
         // launch beside it on the library's side stream, then the gradient.
@@ -464,7 +498,7 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
                     int32_t N, int32_t D, double *loss, double *logz_num, double *logz_den, float *grad, void *ws,
                     size_t ws_bytes, fb_stream stream)
 {
-    return lfmmi_run(den, num, emis, lengths, B, N, D, loss, logz_num, logz_den, grad, ws, ws_bytes, stream, false);
+    return lfmmi_run(den, num, emis, lengths, B, N, D, loss, logz_num, logz_den, grad, ws, ws_bytes, stream, false, false);
 }
 
 int lfmmi_loss_grad_ragged(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths,
@@ -473,7 +507,7 @@ int lfmmi_loss_grad_ragged(const fb_graph *den, const fb_graph *num, const float
 {
     // Length groups pay when compute units would otherwise idle: the shorter sequences leave
     // (1 - mean length / longest length) of the denominator launch's compute-unit time unused.
-    bool in_groups = false;
+    bool in_groups = false, num_apart = false;
     if (lengths_host && B > 0 && N > 0) {
         int64_t sum = 0;
         int32_t longest = 0;
@@ -483,8 +517,12 @@ int lfmmi_loss_grad_ragged(const fb_graph *den, const fb_graph *num, const float
             longest = std::max(longest, l);
         }
         in_groups = longest > 0 && (double)sum < 0.85 * (double)longest * B;
+        // Otherwise, when the denominator workgroups (two per sequence, each filling a compute unit) take the
+        // whole chip, the numerators' share of the gradient goes apart (see lfmmi_run).
+        const int n_cu = side_stream().n_cu;
+        num_apart = !in_groups && longest > 0 && den && den->nw == kNWShared && n_cu > 0 && 2 * (int64_t)B >= n_cu;
     }
-    return lfmmi_run(den, num, emis, lengths, B, N, D, loss, logz_num, logz_den, grad, ws, ws_bytes, stream, in_groups);
+    return lfmmi_run(den, num, emis, lengths, B, N, D, loss, logz_num, logz_den, grad, ws, ws_bytes, stream, in_groups, num_apart);
 }
 
 }  // extern "C"

@@ -267,6 +267,8 @@ struct PostParams {
     int32_t Kcap, Kcap64, frames_per_block;   // Kcap64: largest double-carrier (sub-)graph
     const int32_t *order;  // as in RecParams: the launch covers ranks [rank0, rank0 + n_launch); nullptr: all B
     int32_t rank0, n_launch;
+    int32_t accumulate;    // one packed graph: its pdf posteriors are added to the rows pdf_out already holds (only the
+                           // entries of pdfs the sequence's graph uses are touched; padded frames are left alone)
 };
 
 int launch_recursion(int nw, bool f64, bool tropical, const RecParams &p, size_t lds_bytes, void *stream);
@@ -285,6 +287,8 @@ int launch_posteriors(const PostParams &p, size_t lds_bytes, void *stream);
 bool gradient_kernel_applies(const PostParams &p);
 size_t gradient_lds_bytes(const PostParams &p);
 int launch_gradient(const PostParams &p, size_t lds_bytes, void *stream);
+bool num_add_kernel_applies(const PostParams &p);   // accumulate mode, one packed graph of small sub-graphs
+int launch_num_add(const PostParams &p, void *stream);
 // order[r] = index of the sequence of rank r when sorted by length (clamped to [0, N]), longest first, equal
 // lengths by index
 int launch_delay(void *stream);   // an empty kernel: what follows on the stream starts a launch latency later

@@ -893,6 +893,7 @@ __global__ __launch_bounds__(kPostThreads) void fb_posterior_kernel(const PostPa
         if (n >= P.N) break;
         float *prow = P.pdf_out ? P.pdf_out + ((size_t)b * P.N + n) * P.D : nullptr;
         if (n >= T) {   // padded frame: zeros
+            if (P.accumulate) continue;
             if (prow)
                 for (int d = tid; d < P.D; d += NT) prow[d] = 0.0f;
             for (int gi = 0; gi < P.n_graph; ++gi) {
@@ -910,7 +911,7 @@ __global__ __launch_bounds__(kPostThreads) void fb_posterior_kernel(const PostPa
             const int K = ps[gi].K;
             const size_t at = G.shared ? ((size_t)b * P.N + n) * G.ld : (size_t)n * G.Ktot + ps[gi].k0;
             const bool covers_all = G.shared != 0;   // a shared graph has one row per pdf
-            if (gi == 0 && !covers_all && prow)
+            if (gi == 0 && !covers_all && prow && !P.accumulate)
                 for (int d = tid; d < P.D; d += NT) rho[d] = 0.0f;
             float inv;
             if (G.f64) {
@@ -969,18 +970,23 @@ __global__ __launch_bounds__(kPostThreads) void fb_posterior_kernel(const PostPa
                         acc1 += __shfl_xor(acc1, o, 64);
                     }
                     if (part == 0) {
-                        if (gi == 0 && covers_all) rho[pdfid[r0]] = acc0 * scale;
-                        else rho[pdfid[r0]] += acc0 * scale;
-                        if (two) {
-                            if (gi == 0 && covers_all) rho[pdfid[r1]] = acc1 * scale;
-                            else rho[pdfid[r1]] += acc1 * scale;
+                        if (P.accumulate) {   // straight into the caller's row: a sequence's rows name distinct pdfs
+                            prow[pdfid[r0]] += acc0 * scale;
+                            if (two) prow[pdfid[r1]] += acc1 * scale;
+                        } else {
+                            if (gi == 0 && covers_all) rho[pdfid[r0]] = acc0 * scale;
+                            else rho[pdfid[r0]] += acc0 * scale;
+                            if (two) {
+                                if (gi == 0 && covers_all) rho[pdfid[r1]] = acc1 * scale;
+                                else rho[pdfid[r1]] += acc1 * scale;
+                            }
                         }
                     }
                 }
                 __syncthreads();
             }
         }
-        if (prow)
+        if (prow && !P.accumulate)
             for (int d = tid; d < P.D; d += NT) prow[d] = rho[d];
         __syncthreads();
     }
@@ -1200,6 +1206,82 @@ __global__ __launch_bounds__(kGradThreads, 5) void fb_grad_kernel(const PostPara
     }
 }
 
+// The pdf posteriors of small packed graphs (at most kGradNumK states and pdf rows each; the numerators of an
+// LF-MMI call) added, with the graph's sign, to rows that already hold another graph's share (PostParams::accumulate).
+// grid = (ceil(N / frames_per_block), B), one wave per workgroup: the wave walks its frames as the last wave of
+// fb_grad_kernel does (same arithmetic, same order), with the rows of the next frame on their way while it works,
+// and adds straight into the caller's rows: a sequence's pdf rows name distinct pdfs, padded frames are left alone.
+template <class NT>
+__global__ __launch_bounds__(kWave) void fb_num_add_kernel(const PostParams P)
+{
+    extern __shared__ double lds_raw[];
+    constexpr int NU = kGradNumU;
+    const int lane = threadIdx.x;
+    const int b = P.order ? P.order[P.rank0 + blockIdx.y] : blockIdx.y;
+    const int T = min(max(P.lengths[b], 0), P.N);
+    const int n0 = blockIdx.x * P.frames_per_block;
+    const int n_end = min(n0 + P.frames_per_block, T);   // real frames of this chunk: [n0, n_end)
+    if (n0 >= n_end) return;
+    const PostGraph &G1 = P.g[0];
+    const PdfSub ps1 = G1.pdfs.sub[b];
+    const int K1 = ps1.K, R1 = ps1.n_rows;
+    float *en = (float *)lds_raw;                        // [Kcap] exp(log posterior - max)
+    uint16_t *nptr = (uint16_t *)(en + G1.Kcap);         // row_ptr [Rcap + 1], row_pdf [Rcap], states [Kcap]
+    uint16_t *npdf = nptr + G1.Rcap + 1, *nst = npdf + G1.Rcap;
+    NT qa[NU], qb[NU];
+    auto issue = [&](int n) {
+        const NT *ar = (const NT *)G1.a + (size_t)n * G1.Ktot + ps1.k0, *br = (const NT *)G1.b + (size_t)n * G1.Ktot + ps1.k0;
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const int k = u * kWave + lane;
+            if (k < K1) { qa[u] = ar[k]; qb[u] = br[k]; }
+        }
+    };
+    issue(n0);
+    for (int r = lane; r <= R1; r += kWave) nptr[r] = G1.pdfs.row_ptr[ps1.ptr0 + r];
+    for (int r = lane; r < R1; r += kWave) npdf[r] = G1.pdfs.row_pdf[ps1.row0 + r];
+    for (int k = lane; k < K1; k += kWave) nst[k] = G1.pdfs.states[ps1.st0 + k];
+    for (int n = n0; n < n_end; ++n) {
+        NT t[NU];
+        NT mx = (NT)(-INFINITY);
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const int k = u * kWave + lane;
+            if (k < K1) {
+                t[u] = (qa[u] + qb[u]) * (NT)G1.in_scale;
+                mx = tmax(mx, t[u]);
+            }
+        }
+        if (n + 1 < n_end) issue(n + 1);
+        mx = wave_max(mx);
+        float sum = 0.0f;
+        const bool mass = mx != (NT)(-INFINITY);
+        __syncthreads();   // (one wave: orders the previous frame's reads of en before these writes)
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const int k = u * kWave + lane;
+            if (k < K1) {
+                const float e = mass ? fexp2((float)(t[u] - mx)) : 0.0f;
+                en[k] = e;
+                sum += e;
+            }
+        }
+        sum = wave_sum(sum);
+        const float scale = sum > 0.0f ? G1.sign / sum : 0.0f;
+        __syncthreads();   // the writes of en (and, in the first frame, of the tables) before the reads below
+        float *prow = P.pdf_out + ((size_t)b * P.N + n) * P.D;
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const int r = u * kWave + lane;
+            if (r < R1) {
+                float acc = 0.0f;
+                for (int i = nptr[r]; i < nptr[r + 1]; ++i) acc += en[nst[i]];
+                prow[npdf[r]] += acc * scale;
+            }
+        }
+    }
+}
+
 // order[rank] = b: the sequences by length, longest first (equal lengths by index).  One thread per sequence
 // counts the sequences that go before its own.
 __global__ __launch_bounds__(256) void fb_order_kernel(const int32_t *lengths, int32_t B, int32_t N, int32_t *order)
@@ -1361,6 +1443,23 @@ int launch_gradient(const PostParams &p, size_t lds_bytes, void *stream)
     }
     hipLaunchKernelGGL(kern, grid, dim3(kGradThreads), lds_bytes, (hipStream_t)stream, p);
     return check_launch("gradient kernel launch");
+}
+
+bool num_add_kernel_applies(const PostParams &p)
+{
+    if (p.n_graph != 1 || !p.accumulate || !p.pdf_out) return false;
+    const PostGraph &n = p.g[0];
+    return !n.shared && !n.state_post && n.Kcap <= kGradNumK && n.Rcap <= kGradNumK;
+}
+
+int launch_num_add(const PostParams &p, void *stream)
+{
+    const PostGraph &n = p.g[0];
+    const size_t lds_bytes = (size_t)n.Kcap * 4 + ((size_t)n.Rcap * 2 + 1 + (size_t)n.Kcap + 3) / 2 * 4;
+    const dim3 grid((unsigned)((p.N + p.frames_per_block - 1) / p.frames_per_block), (unsigned)(p.order ? p.n_launch : p.B));
+    auto kern = n.f64 ? fb_num_add_kernel<double> : fb_num_add_kernel<float>;
+    hipLaunchKernelGGL(kern, grid, dim3(kWave), lds_bytes, (hipStream_t)stream, p);
+    return check_launch("numerator kernel launch");
 }
 
 // Does nothing: a launch whose only effect is that what follows it on its stream starts one launch latency later.

@@ -305,6 +305,35 @@ def test_lfmmi_in_length_groups(fb, B):
     Gd.destroy(); Gn.destroy()
 
 
+@pytest.mark.parametrize("phones,N,short", [(5, 24, (21, 23, 16)), (180, 560, (555, 559, 545))])
+def test_lfmmi_equal_lengths_numerators_apart(fb, phones, N, short):
+    """A batch of (nearly) equal lengths whose denominator workgroups take every compute unit (B = 128, a graph
+    large enough for the 16-wave kernel): the ragged entry point then forms the denominator's share of the
+    gradient while the numerator recursion runs and adds the numerators' share in a launch of its own: the
+    one-wave kernel for numerators of up to 512 states, the general posterior kernel for larger ones (540 here).
+    Every sequence against the oracle; a few shorter sequences so that padded frames occur; same results as the
+    plain entry point up to the rounding of one addition."""
+    import torch
+    base = wl.paper_shape_den(K=1100, E_target=5000, B=128, N=N, D=30)
+    rng = np.random.default_rng(5)
+    num = wl.chain_graphs(rng, np.full(128, phones, dtype=np.int64), 30)
+    lengths = base.lengths.copy()
+    lengths[[3, 77, 127]] = short
+    w = wl.Workload("equal lengths", 30, base.emis, lengths, den=base.den, num=num)
+    assert w.lengths.mean() >= 0.85 * w.lengths.max()
+    compare_lfmmi(fb, w, name=f"lfmmi, equal lengths, numerators of {3 * phones} states apart", ragged=True)
+    Gd, Gn = fb.graph_from(w.den, w.D), fb.graph_from(w.num, w.D)
+    e, l = dev(w.emis), dev(w.lengths.astype(np.int32))
+    apart = [host(x).copy() for x in fb.lfmmi_loss_grad(Gd, Gn, e, l, lengths_host=w.lengths)]
+    again = [host(x).copy() for x in fb.lfmmi_loss_grad(Gd, Gn, e, l, lengths_host=w.lengths)]
+    plain = [host(x).copy() for x in fb.lfmmi_loss_grad(Gd, Gn, e, l)]
+    torch.cuda.synchronize()
+    for a, b, c in zip(apart, again, plain):
+        assert np.array_equal(a, b)
+        assert np.allclose(a, c, rtol=0, atol=1e-6)
+    Gd.destroy(); Gn.destroy()
+
+
 def test_lfmmi_with_an_infeasible_numerator(fb):
     """A numerator chain longer than its utterance: log Z_num = -inf, its pdf posteriors are 0, the gradient of that
     utterance is minus the denominator's pdf posteriors, nothing is NaN."""
