@@ -242,21 +242,24 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
  * of the sequences in order of length (the order is computed on the device from `lengths`);
  * every range has its own denominator and gradient launch on a stream of its own (the caller's
  * and three of the library's), and the gradient of the shorter ranges runs on the compute
- * units their sequences have left while the recursion of the longest range is still going.
- * Results equal lfmmi_loss_grad's bit for bit.  Not used when FB_AMD_GROUPS=0 or
+ * units their sequences have left while the recursion of the longest range is still going
+ * (for one range the numerators' share of the gradient is added by a launch of its own, as
+ * in (b)).  Not used when FB_AMD_GROUPS=0 or
  * FB_AMD_SERIAL=1 is in the environment (the three streams are then not created: with the
  * caller's they take the four hardware queues a process has).
  * (b) Sequences of (nearly) equal length, a denominator graph large enough for the 16-wave
  * kernel and 2 B >= the number of compute units: no compute unit falls free before the
  * denominator recursion ends, so the numerator recursion cannot hide beside it.  The
  * denominator's share of the gradient is then formed while the numerator recursion runs (on
- * the library's side stream) and the numerators' share is added by a last small launch;
- * the gradient may differ from lfmmi_loss_grad's by the rounding of that one addition.
+ * the library's side stream) and the numerators' share is added by a last small launch.
  * Not used when FB_AMD_SERIAL=1 is in the environment.
  * (c) Otherwise the call is lfmmi_loss_grad.
  * In every case the library's streams are forked from and joined back into `stream` with
  * events, so for the caller the call is ordered on `stream` as usual.  Same arguments,
- * workspace and errors as lfmmi_loss_grad; calls from several host threads must not overlap.
+ * workspace and errors as lfmmi_loss_grad, same loss and log Z bit for bit; where the
+ * numerators' share is added by a launch of its own a gradient entry may differ from
+ * lfmmi_loss_grad's by the rounding of that one addition.  Calls from several host threads
+ * must not overlap.
  */
 int lfmmi_loss_grad_ragged(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths,
                            const int32_t *lengths_host, int32_t B, int32_t N, int32_t D, double *loss,

@@ -151,7 +151,7 @@ double env_frac(const char *name, double dflt)   // (tuning aid: a fraction in (
 // First rank of length group i + 1 of B sequences in order of length (see lfmmi_loss_grad).
 int32_t group_cut(int32_t B, int i)
 {
-    static const double frac[3] = {env_frac("FB_AMD_CUT0", 0.25), env_frac("FB_AMD_CUT1", 0.60), env_frac("FB_AMD_CUT2", 0.97)};
+    static const double frac[3] = {env_frac("FB_AMD_CUT0", 0.25), env_frac("FB_AMD_CUT1", 0.50), env_frac("FB_AMD_CUT2", 0.97)};
     // Workgroups of a launch go round the 8 XCDs of the chip by index, starting at the first: ranges of a
     // multiple of 4 sequences (8 workgroups) keep every XCD at the same number of workgroups over all launches.
     const int32_t c = ((int32_t)(frac[i] * B + 0.5) + 2) / 4 * 4;
@@ -428,6 +428,16 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
             if (!ok(hipEventRecord(side.num_done, gs[kGroups - 1]))) return fail(FB_EHIP, "lfmmi_loss_grad: event record failed");
             for (int g = kGroups - 1; g >= 0; --g) {
                 const RankRange range{order, cut[g], cut[g + 1] - cut[g]};
+                if (g == kGroups - 2) {
+                    // This range's recursions end before the numerator launch does (it only gets the compute units
+                    // that short sequences have left): the denominator's share of its gradient does not wait for
+                    // the numerators, whose share a small launch adds afterwards (as in the schedule for equal
+                    // lengths below).
+                    if ((r = run_posteriors(&q[0], 1, lengths, B, N, D, grad, gs[g], range))) return r;
+                    if (!ok(hipStreamWaitEvent(gs[g], side.num_done, 0))) return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
+                    if ((r = run_posteriors(&q[1], 1, lengths, B, N, D, grad, gs[g], range, true))) return r;
+                    continue;
+                }
                 if (g < kGroups - 1 && !ok(hipStreamWaitEvent(gs[g], side.num_done, 0)))
                     return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
                 if (g == 0) mark(2, main_s);   // the longest sequences' recursions are done: the last gradient launch starts

@@ -287,7 +287,8 @@ def test_lfmmi_in_length_groups(fb, B):
     """Batches large enough for lfmmi_loss_grad to cut them into ranges of sequences by length (one denominator and
     one gradient launch per range on streams of their own): batch sizes that are and are not multiples of the
     range granularity, many equal lengths, every sequence checked against the oracle; a second call on the same
-    graphs and the plain entry point must give the same bits."""
+    graphs must give the same bits, the plain entry point the same objective and log Z bit for bit and the
+    same gradient up to the rounding of one addition."""
     import torch
     w2 = wl.config5(K=300, B=B, Lmin=2, Lmax=9, D=40)   # 8 distinct lengths: most ranks are decided by index
     assert np.unique(w2.lengths).size < B // 3
@@ -299,9 +300,12 @@ def test_lfmmi_in_length_groups(fb, B):
     again = [host(x).copy() for x in fb.lfmmi_loss_grad(Gd, Gn, e, l, lengths_host=w2.lengths)]
     plain = [host(x).copy() for x in fb.lfmmi_loss_grad(Gd, Gn, e, l)]
     torch.cuda.synchronize()
-    for a, b, c in zip(first, again, plain):
+    for i, (a, b, c) in enumerate(zip(first, again, plain)):
         assert np.array_equal(a, b)
-        assert np.array_equal(a, c)                      # the two entry points agree bit for bit
+        if i < 3:
+            assert np.array_equal(a, c)                  # objective and log Z: the two entry points agree bit for bit
+        else:
+            assert np.allclose(a, c, rtol=0, atol=1e-6)  # gradient: up to the rounding of one addition
     Gd.destroy(); Gn.destroy()
 
 
