@@ -292,6 +292,14 @@ int fb_viterbi(const fb_graph *g, const float *emis, const int32_t *lengths, int
  * shared != 0: shared-graph kernels; 0: packed-graph kernels. */
 int32_t fb_limits_max_states(int32_t D, int shared);
 
+/* Diagnostic: which form of the arc weights the graph's device plans carry.  1: 2^w, for the
+ * kernel instantiation that multiplies (large graphs with float vectors whose finite weights
+ * all lie within 64 binary orders of magnitude of 1: there the product form is exact to
+ * rounding); 0: w, added in the exponent (every other graph, and every graph when
+ * FB_AMD_LINEAR=0 is in the environment); -1: g is NULL.  The results of the compute calls are
+ * the same to rounding either way. */
+int fb_graph_linear_weights(const fb_graph *g);
+
 /*
  * Stage timing of lfmmi_loss_grad, for benchmarks.  fb_profile_enable(1) creates
  * seven HIP events (the only allocation; not allowed while a stream is being

@@ -28,7 +28,7 @@ LAYOUT = {"in_ptr": 0, "in_src": 1, "in_w": 2, "in_perm": 3, "out_ptr": 4, "out_
 SYMBOLS = ["fb_graph_create", "fb_graph_destroy", "fb_graph_layout_size", "fb_graph_layout", "fb_check_lengths",
            "fb_alpha", "fb_beta", "fb_posteriors", "fb_lfmmi_workspace_bytes", "lfmmi_loss_grad", "lfmmi_loss_grad_ragged",
            "fb_limits_max_states", "fb_strerror", "fb_last_error", "fb_graph_schedule_apply_host",
-           "fb_profile_enable", "fb_profile_read", "fb_viterbi_workspace_bytes", "fb_viterbi"]
+           "fb_profile_enable", "fb_profile_read", "fb_viterbi_workspace_bytes", "fb_viterbi", "fb_graph_linear_weights"]
 
 
 class FBError(RuntimeError):
@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.lfmmi_loss_grad.restype = ctypes.c_int
         L.lfmmi_loss_grad_ragged.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.lfmmi_loss_grad_ragged.restype = ctypes.c_int
+        L.fb_graph_linear_weights.argtypes = [vp]
+        L.fb_graph_linear_weights.restype = ctypes.c_int
         L.fb_limits_max_states.argtypes = [i32, ctypes.c_int]
         L.fb_limits_max_states.restype = i32
         L.fb_viterbi_workspace_bytes.argtypes = [vp, i32, i32]
@@ -183,6 +185,11 @@ def fb_profile_read() -> dict:
     ms = (ctypes.c_float * 4)()
     _check(lib().fb_profile_read(ctypes.cast(ms, ctypes.c_void_p)))
     return {"num_recursion": ms[0], "den_recursion": ms[1], "posteriors_grad": ms[2], "loss": ms[3]}
+
+
+def fb_graph_linear_weights(g: Graph) -> bool:
+    """Diagnostic: the graph's device plans carry weights as 2^w (the multiplying kernel instantiation)."""
+    return int(lib().fb_graph_linear_weights(g.handle)) == 1
 
 
 def fb_limits_max_states(D: int, shared: bool) -> int:

@@ -87,6 +87,11 @@ int run_recursion(const fb_graph *g, const float *emis, const int32_t *lengths, 
             lds = lds_fixed;
         }
     }
+    // graphs whose streams carry weights as 2^w were found to fit the fixed buffers when they were created
+    if (g->linear_w && !tropical) {
+        if (!p.xs_fixed) return fail(FB_EHIP, "internal error: linear weights without fixed buffers");
+        p.linear_w = 1;
+    }
     return launch_recursion(g->nw, g->f64, tropical, p, lds, stream);
 }
 

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <cstdlib>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -105,7 +106,8 @@ int upload_pdf(fb_graph *g, const PdfHost &h, PdfDev &d)
     return upload(g, h.states, &d.states);
 }
 
-int upload_stream(fb_graph *g, const StreamHost &h, StreamDev &d)
+// arcs: the list to upload in place of h.arcs (same length), or nullptr
+int upload_stream(fb_graph *g, const StreamHost &h, StreamDev &d, const std::vector<Arc> *arcs = nullptr)
 {
     int rc;
     if ((rc = upload(g, h.sub, &d.sub))) return rc;
@@ -114,7 +116,7 @@ int upload_stream(fb_graph *g, const StreamHost &h, StreamDev &d)
     if ((rc = upload(g, h.vix, &d.vix))) return rc;
     if ((rc = upload(g, h.clones, &d.clones))) return rc;
     if ((rc = upload(g, h.zero_rows, &d.zero_rows))) return rc;
-    return upload(g, h.arcs, &d.arcs);
+    return upload(g, arcs ? *arcs : h.arcs, &d.arcs);
 }
 
 }  // namespace
@@ -158,6 +160,8 @@ const char *fb_strerror(int code)
     default: return "unknown error code";
     }
 }
+
+int fb_graph_linear_weights(const fb_graph *g) { return g ? (g->linear_w ? 1 : 0) : -1; }
 
 int32_t fb_limits_max_states(int32_t D, int shared)
 {
@@ -322,6 +326,7 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
             PH.max_rows = std::max(PH.max_rows, ps.n_rows);
             PH.sub.push_back(ps);
         }
+        std::vector<Arc> lin_fwd, lin_bwd;   // the arc lists with weights as 2^w, when the graph runs that instantiation
         {   // nothing a kernel will index may leave its array
             std::string why;
             const int32_t nv = n_seq > 0 ? -1 : D;
@@ -332,7 +337,20 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
                 rc = fail(FB_EUNSUPPORTED, "graph too large: " + why);
             else if (!stream_in_bounds(g->h_fwd, nv, why) || !stream_in_bounds(g->h_bwd, nv, why))
                 rc = fail(FB_EHIP, "internal error: stream out of bounds (" + why + ")");
-            g->own_trop = any_parallel;
+            // Large graphs with float vectors that fit the fixed-length buffers run the kernel instantiation that
+            // takes weights as 2^w (one multiply-add per arc instead of an add before the exponential), unless a
+            // weight is outside the range in which that is exact to rounding.  The best-path plan cannot share
+            // such a stream.
+            static const bool no_linear = getenv("FB_AMD_LINEAR") && getenv("FB_AMD_LINEAR")[0] == '0';   // (diagnostic switch)
+            if (rc == FB_OK && !no_linear && !g->host_only && g->nw == kNWShared && !g->f64 &&
+                g->max_sub_K + std::max(g->h_fwd.Ccap, g->h_bwd.Ccap) + 1 <= kXsFixed) {
+                const int32_t Ecap1 = n_seq > 0 ? g->max_sub_K : D;
+                g->linear_w = recursion_lds_bytes(g->max_sub_K, g->h_bwd.Ccap, Ecap1, true, false, n_seq == 0, false, kXsFixed) <= kLdsBytes &&
+                              recursion_lds_bytes(g->max_sub_K, g->h_fwd.Ccap, Ecap1, false, false, n_seq == 0, false, kXsFixed) <= kLdsBytes &&
+                              recursion_fixed_available() && stream_linear_weights(g->h_fwd, lin_fwd) &&
+                              stream_linear_weights(g->h_bwd, lin_bwd);
+            }
+            g->own_trop = any_parallel || g->linear_w;
             if (rc == FB_OK && g->own_trop) {
                 if (!sell_in_bounds(sell_trop, nv, why))
                     rc = fail(FB_EHIP, "internal error: schedule out of bounds (" + why + ")");
@@ -359,7 +377,8 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
             std::vector<int32_t> hp(pdf, pdf + K);
             const int32_t *dp = nullptr; const float *di = nullptr, *df = nullptr;
             if (!(rc = upload(g, hp, &dp)) && !(rc = upload(g, i2, &di)) && !(rc = upload(g, f2, &df)) &&
-                !(rc = upload_stream(g, g->h_fwd, g->fwd)) && !(rc = upload_stream(g, g->h_bwd, g->bwd)))
+                !(rc = upload_stream(g, g->h_fwd, g->fwd, g->linear_w ? &lin_fwd : nullptr)) &&
+                !(rc = upload_stream(g, g->h_bwd, g->bwd, g->linear_w ? &lin_bwd : nullptr)))
                 rc = upload_pdf(g, g->h_pdf, g->pdfs);
             if (rc == FB_OK) {
                 if (g->own_trop) rc = upload_stream(g, g->h_trop, g->trop);

@@ -154,6 +154,12 @@ struct StreamDev {
 bool stream_from_sell(const SellHost &S, int32_t Kcap, int32_t Ecap, int32_t esize, StreamHost &out, std::string &why);
 bool stream_in_bounds(const StreamHost &S, int32_t n_vidx, std::string &why);
 void stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double *y);
+// The arc list of S with the weights of all batches but the stacked ones replaced by 2^w, for the kernel
+// instantiation that multiplies instead of adding in the exponent; arcs of weight zero-bar (padding included) get
+// weight 0 and the dump slot, which always holds zero-bar, as their source, so that they never raise a running
+// maximum.  False (out unspecified) if a finite weight lies outside [-kLinearSpan, kLinearSpan] (log2 units).
+constexpr float kLinearSpan = 64.0f;
+bool stream_linear_weights(const StreamHost &S, std::vector<Arc> &out);
 
 // States grouped by pdf for the posterior accumulation: per (sub-)graph, one row per pdf it uses
 // (every pdf for a shared graph), listing the local ids of the states tied to it.  16-bit entries:
@@ -197,6 +203,7 @@ struct fb_graph {
     fb::StreamHost h_fwd, h_bwd;      // host schedules of the two recursions
     fb::StreamHost h_trop;            // forward schedule of the tropical semiring, when it differs (own_trop)
     bool own_trop = false;            // the graph has parallel arcs: they combine by max there, not by (+)
+    bool linear_w = false;            // the device copies of fwd / bwd carry weights as 2^w (see stream_linear_weights)
     fb::PdfHost h_pdf;                // states grouped by pdf, for the posterior accumulation
     // device
     fb::StreamDev fwd, bwd, trop;     // trop = fwd unless own_trop
@@ -240,6 +247,7 @@ struct RecParams {
     int32_t B, N, D, shared, Ktot;
     int32_t Kcap, Ecap;
     int32_t xs_fixed;      // kXsFixed: launch the fixed-buffer instantiation; 0: buffers sized by the graph
+    int32_t linear_w;      // the streams carry weights as 2^w (fixed-buffer instantiation only)
     // A launch may cover a range of the sequences in order of length: order[r] = the sequence of rank r
     // (longest first, written by launch_order), ranks [rank0, rank0 + n_launch).  order == nullptr: all B.
     const int32_t *order;

@@ -21,7 +21,9 @@
 // subtracted amounts are the offsets handed back to the caller and their sum is
 // accumulated in double for log Z.  The vector's element type ("carrier") is
 // float or double; exponentials and logarithms are single precision either way
-// (they act on differences to the running maximum, which are small).
+// (they act on differences to the running maximum, which are small).  One
+// instantiation (LINW) takes the arc weights as 2^w and multiplies: see
+// stream_linear_weights for when a graph gets it.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -76,6 +78,20 @@ __device__ __forceinline__ void lse_add4(T &m, float &s, T x0, T x1, T x2, T x3)
     const float e0 = fexp2((float)(x0 - mn)), e1 = fexp2((float)(x1 - mn));
     const float e2 = fexp2((float)(x2 - mn)), e3 = fexp2((float)(x3 - mn));
     s = fmaf(s, r, (e0 + e1) + (e2 + e3));
+    m = mn;
+}
+
+// four terms whose weights are given as W = 2^w: the running maximum is over the gathered values alone
+template <class T>
+__device__ __forceinline__ void lse_add4w(T &m, float &s, T g0, T g1, T g2, T g3, float W0, float W1, float W2, float W3)
+{
+    const T mn = tmax3(tmax3(m, g0, g1), g2, g3);
+    const float r = fexp2((float)(m - mn));
+    float p = fexp2((float)(g0 - mn)) * W0;
+    p = fmaf(fexp2((float)(g1 - mn)), W1, p);
+    p = fmaf(fexp2((float)(g2 - mn)), W2, p);
+    p = fmaf(fexp2((float)(g3 - mn)), W3, p);
+    s = fmaf(s, r, p);
     m = mn;
 }
 
@@ -212,9 +228,10 @@ __device__ __forceinline__ void unrolled(F &&f, std::integer_sequence<int, I...>
     (f(std::integral_constant<int, I>{}), ...);
 }
 
-template <int NW, class T, bool TROP, int XF>
+template <int NW, class T, bool TROP, int XF, bool LINW = false>
 __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P)
 {
+    static_assert(!LINW || (!TROP && XF != 0), "weights as 2^w: log semifield, fixed buffers");
     constexpr int NRES = kResident;
     // The large-graph kernel is the critical path of a call; small-graph launches that run beside it on the same
     // compute units (the numerators of an LF-MMI call) take the issue slots it leaves.  (The data-moving wave
@@ -430,6 +447,7 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
             xb[P.Kcap + k] = kNegInf;
             if (bwd) bh[P.Kcap + k] = kNegInf;
         }
+        if (tid == 0) xb[nX - 1] = xb[Xs + nX - 1] = kNegInf;   // the dump slot holds zero-bar in both buffers, always
         put_max(0, wmax);
         __syncthreads();
 
@@ -621,6 +639,24 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                             asm volatile("" : "+v"(v));
                             return v >> 16;
                         };
+                        if constexpr (LINW) {
+                            // weights as 2^w: a multiply-add per term in place of the add before the exponential;
+                            // arcs of weight zero-bar gather the dump slot (zero-bar) and never raise the maximum
+                            lse_add4w(m, sum, gv[0], gv[1], gv[2], gv[3], a[0].w, a[1].w, a[2].w, a[3].w);
+                            if (closing) {
+                                const int lg = (int)((f >> kFlagLgShift) & 7u);
+                                if (lg) group_total(m, sum, lg, lane);
+                                const uint32_t tgt = target();
+                                const T pre = m + (T)flog2(sum) - c;   // sum == 0 -> -inf
+                                const T x = pre + (T)ern[vix[tgt]] * (T)kLog2e;
+                                xn[tgt] = x;
+                                if (bwd) bn[tgt] = pre;
+                                wmax = tmax(wmax, x);
+                                m = (T)kNegBig;
+                                sum = 0.0f;
+                            }
+                            return;
+                        }
                         const T x0 = gv[0] + (T)a[0].w, x1 = gv[1] + (T)a[1].w, x2 = gv[2] + (T)a[2].w, x3 = gv[3] + (T)a[3].w;
                         if constexpr (TROP) {
                             // (+) = max: keep the largest term and the state it came from (the first of equal terms)
@@ -1372,8 +1408,11 @@ bool recursion_fixed_available()
     // of its dynamic array (a property of the build, looked up once)
     static const bool ok = [] {
         hipFuncAttributes attr{};
+        hipFuncAttributes attr_lin{};
         const hipError_t e = hipFuncGetAttributes(&attr, (const void *)fb_recursion_kernel<kNWShared, float, false, kXsFixed>);
-        return e == hipSuccess && attr.sharedSizeBytes == 0;
+        const hipError_t e_lin =
+            hipFuncGetAttributes(&attr_lin, (const void *)fb_recursion_kernel<kNWShared, float, false, kXsFixed, true>);
+        return e == hipSuccess && attr.sharedSizeBytes == 0 && e_lin == hipSuccess && attr_lin.sharedSizeBytes == 0;
     }();
     return ok;
 }
@@ -1382,8 +1421,10 @@ int launch_recursion(int nw, bool f64, bool tropical, const RecParams &p, size_t
 {
     if (p.xs_fixed) {   // fixed-length state buffers: large graphs with float vectors only
         if (p.xs_fixed != kXsFixed || nw != kNWShared || f64 || tropical) return fail(FB_EHIP, "internal error: fixed-buffer launch");
+        if (p.linear_w) return launch_rec(fb_recursion_kernel<kNWShared, float, false, kXsFixed, true>, nw, p, lds_bytes, stream);
         return launch_rec(fb_recursion_kernel<kNWShared, float, false, kXsFixed>, nw, p, lds_bytes, stream);
     }
+    if (p.linear_w) return fail(FB_EHIP, "internal error: linear weights without fixed buffers");
     if (tropical) {
         if (nw == kNWShared)
             return f64 ? launch_rec(fb_recursion_kernel<kNWShared, double, true, 0>, nw, p, lds_bytes, stream)

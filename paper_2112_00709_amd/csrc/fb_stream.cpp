@@ -279,4 +279,50 @@ void stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double
     for (int32_t k = 0; k < sd.K; ++k) y[k] = ye[(size_t)k];
 }
 
+bool stream_linear_weights(const StreamHost &S, std::vector<Arc> &out)
+{
+    out = S.arcs;
+    const uint32_t dump_off = (uint32_t)(S.Kcap + S.Ccap) * (uint32_t)S.esize;
+    const size_t per_batch = (size_t)kBatchEntries;
+    for (const WaveDesc &wd : S.waves) {
+        bool live[kWave] = {};   // the lane has had an arc of finite weight since its last row ended
+        for (size_t q = 0; q < wave_batches(wd); ++q) {
+            if (batch_flags(S, wd, q) & (kFlagDual | kFlagQuad)) continue;   // stacked batches add in the exponent as before
+            Arc *a = out.data() + (size_t)wd.arc_base + q * per_batch;
+            // A row spread over 2^lg lanes ends with its total in every lane of the group; the plan lets only the
+            // group's first lane write it and sends the others to the dump slot.  Here the dump slot must keep
+            // zero-bar, so the other lanes write the same value to the same state instead.
+            const uint32_t fl = batch_flags(S, wd, q);
+            const int lg = (int)((fl >> kFlagLgShift) & 7u);
+            if ((fl & kFlagInfo) && lg > 0) {
+                const uint32_t dump = (uint32_t)(S.Kcap + S.Ccap);
+                for (int lane = 0; lane < kWave; ++lane) {
+                    Arc &e = a[entry_at(0, kBatchRows - 1, lane)];
+                    const Arc &first = a[entry_at(0, kBatchRows - 1, lane & ~((1 << lg) - 1))];
+                    if (((uint32_t)e.src >> 16) == dump)
+                        e.src = (int32_t)(((uint32_t)e.src & 0xffffu) | ((uint32_t)first.src & 0xffff0000u));
+                }
+            }
+            for (int lane = 0; lane < kWave; ++lane)
+                for (int r = 0; r < kBatchRows; ++r) {
+                    Arc &e = a[entry_at(0, r, lane)];
+                    if (e.w == -INFINITY) {
+                        e.src = (int32_t)(((uint32_t)e.src & 0xffff0000u) | dump_off);
+                        e.w = 0.0f;
+                    } else {
+                        if (!(e.w >= -kLinearSpan && e.w <= kLinearSpan)) return false;
+                        e.w = exp2f(e.w);
+                        live[lane] = true;
+                    }
+                }
+            if (fl & kFlagInfo)   // rows end here: nothing but zero-bar may go to the dump slot
+                for (int lane = 0; lane < kWave; ++lane) {
+                    if (live[lane] && ((uint32_t)a[entry_at(0, kBatchRows - 1, lane)].src >> 16) == (uint32_t)(S.Kcap + S.Ccap)) return false;
+                    live[lane] = false;
+                }
+        }
+    }
+    return true;
+}
+
 }  // namespace fb

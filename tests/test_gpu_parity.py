@@ -447,6 +447,44 @@ def test_shared_graph_equals_its_packed_replication(fb):
         np.testing.assert_allclose(a["gamma"][b, :lengths[b]], p["gamma"][:lengths[b], b * g.K:(b + 1) * g.K], atol=2e-6)
 
 
+def test_both_forms_of_the_arc_weights(fb):
+    """Large graphs with float vectors run the kernel instantiation that takes weights as 2^w when every finite weight
+    is within 64 binary orders of magnitude of 1, the adding one otherwise.  The same hub-heavy graph (rows spread
+    over several lanes) with: ordinary weights; some arcs of weight zero-bar and some tiny but in-range weights,
+    from sources that dominate the frame (they must not swamp the other terms of their rows); one weight out of
+    range (falls back to the adding form).  All against the oracle."""
+    rng = np.random.default_rng(77)
+    D, B, N = 60, 6, 20
+    g = wl.random_graph(rng, 1500, D, zipf_s=1.1, mean_extra_deg=6.0)
+    emis = (rng.standard_normal((B, N, D)) * 2.5).astype(np.float32)
+    emis[:, :, 7] += 30.0                                     # the states tied to pdf 7 dominate every frame
+    lengths = np.array([20, 17, 20, 3, 11, 20], dtype=np.int32)
+    strong = np.flatnonzero(g.pdf[g.src] == 7)                # arcs that leave the dominating states
+    assert strong.size > 50
+
+    G = fb.graph_from(g, D)
+    assert fb.fb_graph_linear_weights(G)
+    G.destroy()
+    compare_fb(fb, g, D, emis, lengths, name="weights as 2^w, ordinary weights")
+
+    w2 = g.logw.copy()
+    w2[strong[0::3]] = -np.inf                                # zero-bar arcs out of the strongest sources
+    w2[strong[1::3]] = -40.0                                  # 2^-57.7: tiny, in range
+    g2 = wl.Graph(g.K, g.src, g.dst, w2, g.pdf, g.init, g.final)
+    G = fb.graph_from(g2, D)
+    assert fb.fb_graph_linear_weights(G)
+    G.destroy()
+    compare_fb(fb, g2, D, emis, lengths, name="weights as 2^w, zero-bar and tiny weights on dominating sources")
+
+    w3 = g.logw.copy()
+    w3[strong[0]] = -60.0                                     # 2^-86.6: out of range
+    g3 = wl.Graph(g.K, g.src, g.dst, w3, g.pdf, g.init, g.final)
+    G = fb.graph_from(g3, D)
+    assert not fb.fb_graph_linear_weights(G)
+    G.destroy()
+    compare_fb(fb, g3, D, emis, lengths, name="a weight out of range: the adding form")
+
+
 def test_results_are_deterministic(fb):
     import torch
     w = wl.config5(K=800, B=5, Lmin=3, Lmax=8, D=120)
