@@ -113,11 +113,19 @@ PostGraph make_post(const fb_graph *g, const void *a, const void *b, bool f64, f
     return q;
 }
 
+// what the one-barrier gradient kernel needs beside the vectors (PostParams::cum_a, cum_b, logz); all null: not given
+struct Offsets {
+    const float *cum_a = nullptr, *cum_b = nullptr;
+    const double *logz = nullptr;
+};
+
 int run_posteriors(const PostGraph *gs, int n_graph, const int32_t *lengths, int32_t B, int32_t N, int32_t D,
-                   float *pdf_out, fb_stream stream, RankRange range = RankRange(), bool accumulate = false)
+                   float *pdf_out, fb_stream stream, RankRange range = RankRange(), bool accumulate = false,
+                   Offsets offs = Offsets())
 {
     PostParams p{};
     p.accumulate = accumulate ? 1 : 0;
+    if (offs.cum_a && offs.cum_b && offs.logz) { p.cum_a = offs.cum_a; p.cum_b = offs.cum_b; p.logz = offs.logz; }
     p.order = range.order;
     p.rank0 = range.rank0;
     p.n_launch = range.count;
@@ -347,7 +355,8 @@ size_t fb_lfmmi_workspace_bytes(const fb_graph *den, const fb_graph *num, int32_
     const size_t den_vec = align256((size_t)B * N * lfmmi_den_ld(den) * (den->f64 ? 8 : 4));
     const size_t num_vec = align256((size_t)N * num->K * (num->f64 ? 8 : 4));
     const size_t z = align256((size_t)B * sizeof(double));
-    return 2 * den_vec + 2 * num_vec + 2 * z + align256((size_t)B * sizeof(int32_t));   // + the sequences in order of length
+    const size_t cum = align256((size_t)B * N * sizeof(float));   // running offsets of the denominator rows, per direction
+    return 2 * den_vec + 2 * num_vec + 2 * z + align256((size_t)B * sizeof(int32_t)) + 2 * cum;   // + the sequences in order of length
 }
 
 // in_groups: run the batch as ranges of sequences by length; num_apart: the numerators' share of the gradient in a
@@ -376,7 +385,9 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
     void *num_b = w; w += num_vec;
     double *zn = logz_num ? logz_num : (double *)w; w += align256((size_t)B * sizeof(double));
     double *zd = logz_den ? logz_den : (double *)w; w += align256((size_t)B * sizeof(double));
-    int32_t *order = (int32_t *)w;
+    int32_t *order = (int32_t *)w; w += align256((size_t)B * sizeof(int32_t));
+    float *cum_a = (float *)w; w += align256((size_t)B * N * sizeof(float));
+    float *cum_b = (float *)w;
 
     // Both recursions of a graph run side by side in one launch.  The denominator launch goes first on
     // the caller's stream; the (much smaller) numerator launch runs beside it on the library's side stream
@@ -386,6 +397,11 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
     RecDir dd[2] = {make_dir(den, false, den_a, true, nullptr, zd, 1.0f, false),
                     make_dir(den, true, den_b, true, nullptr, nullptr, 1.0f, false)};
     dd[0].out_ld = dd[1].out_ld = (int32_t)lfmmi_den_ld(den);
+    dd[0].cum = cum_a;
+    dd[1].cum = cum_b;
+    Offsets offs;
+    static const bool four_barriers = getenv("FB_AMD_GRAD1") && getenv("FB_AMD_GRAD1")[0] == '0';   // (diagnostic switch)
+    if (!four_barriers) { offs.cum_a = cum_a; offs.cum_b = cum_b; offs.logz = zd; }
     hipStream_t main_s = (hipStream_t)stream;
     SideStream &side = side_stream();
     // Eq. 17: numerator pdf posteriors minus denominator pdf posteriors
@@ -438,7 +454,7 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
                     // that short sequences have left): the denominator's share of its gradient does not wait for
                     // the numerators, whose share a small launch adds afterwards (as in the schedule for equal
                     // lengths below).
-                    if ((r = run_posteriors(&q[0], 1, lengths, B, N, D, grad, gs[g], range))) return r;
+                    if ((r = run_posteriors(&q[0], 1, lengths, B, N, D, grad, gs[g], range, false, offs))) return r;
                     if (!ok(hipStreamWaitEvent(gs[g], side.num_done, 0))) return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
                     if ((r = run_posteriors(&q[1], 1, lengths, B, N, D, grad, gs[g], range, true))) return r;
                     continue;
@@ -446,7 +462,7 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
                 if (g < kGroups - 1 && !ok(hipStreamWaitEvent(gs[g], side.num_done, 0)))
                     return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
                 if (g == 0) mark(2, main_s);   // the longest sequences' recursions are done: the last gradient launch starts
-                if ((r = run_posteriors(q, 2, lengths, B, N, D, grad, gs[g], range))) return r;
+                if ((r = run_posteriors(q, 2, lengths, B, N, D, grad, gs[g], range, false, offs))) return r;
             }
             return FB_OK;
         };
@@ -473,7 +489,7 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
         mark(5, side.stream);
         if (rc == FB_OK) rc = run_recursion(num, emis, lengths, B, N, D, dn, 2, side.stream);
         mark(6, side.stream);
-        if (rc == FB_OK) rc = run_posteriors(&q[0], 1, lengths, B, N, D, grad, main_s);
+        if (rc == FB_OK) rc = run_posteriors(&q[0], 1, lengths, B, N, D, grad, main_s, RankRange(), false, offs);
         // the caller's stream waits for the side stream also when a launch has failed
         if ((hipEventRecord(side.join, side.stream) != hipSuccess || hipStreamWaitEvent(main_s, side.join, 0) != hipSuccess) &&
             rc == FB_OK)
@@ -500,7 +516,7 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
             rc = fail(FB_EHIP, "lfmmi_loss_grad: joining the side stream failed");
         if (rc) return rc;
         if (fork) mark(2, main_s);   // the gradient stage starts when both recursion launches are done
-        if ((rc = run_posteriors(q, 2, lengths, B, N, D, grad, stream))) return rc;
+        if ((rc = run_posteriors(q, 2, lengths, B, N, D, grad, stream, RankRange(), false, offs))) return rc;
         mark(3, main_s);
     }
     rc = launch_loss(zn, zd, lengths, B, loss, stream);

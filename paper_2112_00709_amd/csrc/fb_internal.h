@@ -227,6 +227,7 @@ struct RecDir {
     void *out;             // normalised vectors, nullable: float, or the carrier type if out_carrier
     int out_carrier;       // out holds carrier-type values (workspace), not float
     float *off;            // [B][N] offsets, nullable
+    float *cum;            // [B][N] running sums of the offsets (log2 units: stored row + cum = the true row), nullable
     double *logz;          // [B], nullable
     float out_scale;       // ln 2 for natural-log output, 1 to keep log2 units
     int32_t Ccap;          // clone slots of this direction's schedule
@@ -275,6 +276,10 @@ struct PostParams {
     int32_t Kcap, Kcap64, frames_per_block;   // Kcap64: largest double-carrier (sub-)graph
     const int32_t *order;  // as in RecParams: the launch covers ranks [rank0, rank0 + n_launch); nullptr: all B
     int32_t rank0, n_launch;
+    // Two graphs through the gradient kernel: the running sums of the offsets of g[0]'s forward and backward rows,
+    // [B][N] each, log2 units, and its log Z [B] (natural log); all three or none.
+    const float *cum_a, *cum_b;
+    const double *logz;
     int32_t accumulate;    // one packed graph: its pdf posteriors are added to the rows pdf_out already holds (only the
                            // entries of pdfs the sequence's graph uses are touched; padded frames are left alone)
 };

@@ -433,6 +433,7 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
             staged_wait();
             if (Tn > 2) stage(frame(2), er + 2 * Es);   // lands while step 1 runs
             if (off_seq && lane == 0) off_seq[frame(0)] = 0.0f;
+            if (R.cum && lane == 0) R.cum[(size_t)b * P.N + frame(0)] = 0.0f;
         }
         __syncthreads();
         T wmax = kNegInf;
@@ -459,6 +460,7 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
                 const T c = (M == kNegInf) ? (T)0 : M;
                 csum += (double)c;
                 if (off_seq && lane == 0) off_seq[frame(i)] = (float)c * R.out_scale;
+                if (R.cum && lane == 0) R.cum[(size_t)b * P.N + frame(i)] = (float)csum;
                 staged_wait();   // frame i+1, requested a whole step ago, is in LDS
                 if (i + 2 < Tn) stage(frame(i + 2), er + ((i + 2) % 3) * Es);   // buffer of frame i-1: no longer read
                 write_row(frame(i - 1), bwd ? bh + cur * Xs : xb + cur * Xs);
@@ -1242,6 +1244,201 @@ __global__ __launch_bounds__(kGradThreads, 5) void fb_grad_kernel(const PostPara
     }
 }
 
+// ---------------------------------------------------------------------------
+// The same gradient with one workgroup barrier per frame, for calls whose
+// recursions also left the running sums of their offsets (PostParams::cum_a, cum_b:
+// A_n, B_n with alpha_n = stored row + A_n, beta_n = stored row + B_n, log2 units)
+// and log Z.  The exponentials of a frame are then taken of
+//   t_k - (log2 Z - A_n - B_n) = log2 of the posterior itself (<= 0, largest >= -log2 K),
+// so the frame's maximum, its reduction over the workgroup and the barrier behind
+// it fall away (the values are still normalised by their own sum: a drift of the
+// float recursions cancels as before).  The denominator waves store their pdf
+// posteriors straight from the sums (no staging of the row in LDS), adding the
+// numerator's value for the pdf, which the numerator wave has left in a small list
+// (two buffers, by frame parity) before the frame's barrier; the exponentials in
+// pdf order have two buffers as well, so nothing of frame n + 1 overwrites what
+// frame n still reads.  Everything else as in fb_grad_kernel (same sums, same order).
+// LDS: red [2][8] sums of waves 0-7; tb [2][K0r + 4]; nval [2][Rcap] the numerator's pdf
+// posteriors by pdf row; en [Kcap] numerator exponentials; nidx [D] 16-bit: pdf -> its row in
+// this sequence's numerator + 1, 0 = none; the numerator tables.
+// ---------------------------------------------------------------------------
+template <class NT>
+__global__ __launch_bounds__(kGradThreads, 5) void fb_grad1_kernel(const PostParams P)
+{
+    extern __shared__ double lds_raw[];
+    constexpr int MT = kGradMain, U = kGradU, NU = kGradNumU;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool den_side = wave < MT / kWave;
+    const int b = P.order ? P.order[P.rank0 + blockIdx.y] : blockIdx.y;
+    const int T = min(max(P.lengths[b], 0), P.N);
+    const int n0 = blockIdx.x * P.frames_per_block;
+    const int n_end = min(min(n0 + P.frames_per_block, P.N), T);   // real frames of this chunk: [n0, n_end)
+    const bool has_num = P.n_graph == 2;   // one graph: the shared graph's share alone (no numerators: wave 8 only keeps the barriers)
+    const PostGraph &G0 = P.g[0], &G1 = P.g[1];
+    const int K0 = G0.pdfs.sub[0].K, D = P.D;
+    const int K0r = ((K0 + 3) & ~3) + 4;
+    const PdfSub ps1 = has_num ? G1.pdfs.sub[b] : PdfSub{};
+    const int K1 = ps1.K, R1 = ps1.n_rows;
+
+    float *red = (float *)lds_raw;                       // [2][16]
+    float *tb = red + 32;                                // [2][K0r]
+    float *nval = tb + 2 * K0r;                          // [2][Rcap]
+    float *en = nval + 2 * G1.Rcap;                      // [Kcap]
+    uint16_t *nidx = (uint16_t *)(en + G1.Kcap);         // [D rounded to 2]
+    uint16_t *nptr = nidx + ((D + 1) & ~1);              // numerator tables: row_ptr [Rcap + 1], row_pdf [Rcap], states [Kcap]
+    uint16_t *npdf = nptr + G1.Rcap + 1, *nst = npdf + G1.Rcap;
+
+    for (int n = n0 + (n_end > n0 ? n_end - n0 : 0); n < min(n0 + P.frames_per_block, P.N); ++n) {   // padded frames: zeros
+        float *prow = P.pdf_out + ((size_t)b * P.N + n) * D;
+        for (int d = tid; d < D; d += kGradThreads) prow[d] = 0.0f;
+    }
+    if (n0 >= n_end) return;
+
+    // which numerator row a pdf has (the same for every frame of the block)
+    for (int d = tid; d < D; d += kGradThreads) nidx[d] = 0;
+    __syncthreads();
+    for (int r = tid; r < R1; r += kGradThreads) nidx[G1.pdfs.row_pdf[ps1.row0 + r]] = (uint16_t)(r + 1);   // (R1 = 0 without numerators)
+    // (visible to the denominator waves after the first frame's barrier)
+
+    if (den_side) {
+        float4 pa[U], pb[U];          // rows of the frame being prefetched / worked on
+        float ca, cb;                 // A_n, B_n of that frame
+        uint2 posr[U];                // places (4 x 16 bit) of the thread's states in pdf order
+        uint32_t prange[kGradPdf];    // state ranges (begin | end << 16) of the thread's pdfs tid, tid + MT, ...
+        const double z2 = P.logz ? P.logz[b] * kLog2e : 0.0;   // log2 Z of the shared graph
+        auto issue = [&](int n) {
+            const float4 *ar = (const float4 *)((const float *)G0.a + ((size_t)b * P.N + n) * G0.ld);
+            const float4 *br = (const float4 *)((const float *)G0.b + ((size_t)b * P.N + n) * G0.ld);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int q = u * MT + tid;
+                if (q * 4 < K0) { pa[u] = ar[q]; pb[u] = br[q]; }
+            }
+            ca = P.cum_a[(size_t)b * P.N + n];
+            cb = P.cum_b[(size_t)b * P.N + n];
+        };
+        issue(n0);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int q = u * MT + tid;
+            posr[u] = q * 4 < K0 ? ((const uint2 *)G0.pdfs.pos)[q] : make_uint2(0u, 0u);
+        }
+#pragma unroll
+        for (int j = 0; j < kGradPdf; ++j) {
+            const int d = j * MT + tid;
+            prange[j] = d < D ? (uint32_t)G0.pdfs.row_ptr[d] | ((uint32_t)G0.pdfs.row_ptr[d + 1] << 16) : 0u;
+        }
+        for (int n = n0; n < n_end; ++n) {
+            const int par = (n - n0) & 1;
+            float *tbn = tb + par * K0r;
+            // log2 Z - A_n - B_n; a sequence without any path (log Z = -inf) has no posteriors
+            const double shift_d = z2 - (double)ca - (double)cb;
+            const bool mass = shift_d > -1.0e300 && shift_d < 1.0e300;
+            const float shift = mass ? (float)shift_d : 0.0f;
+            float sum = 0.0f;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int q = u * MT + tid;
+                if (q * 4 < K0) {
+                    float e[4];
+                    e[0] = fexp2((pa[u].x + pb[u].x) * G0.in_scale - shift); e[1] = fexp2((pa[u].y + pb[u].y) * G0.in_scale - shift);
+                    e[2] = fexp2((pa[u].z + pb[u].z) * G0.in_scale - shift); e[3] = fexp2((pa[u].w + pb[u].w) * G0.in_scale - shift);
+                    if (q * 4 + 3 >= K0) {   // the row's last piece when K0 is not a multiple of 4: padding counts as zero-bar
+                        if (q * 4 + 1 >= K0) e[1] = 0.0f;
+                        if (q * 4 + 2 >= K0) e[2] = 0.0f;
+                        e[3] = 0.0f;
+                    }
+                    if (!mass) e[0] = e[1] = e[2] = e[3] = 0.0f;
+                    sum += (e[0] + e[1]) + (e[2] + e[3]);
+                    tbn[posr[u].x & 0xffffu] = e[0]; tbn[posr[u].x >> 16] = e[1];
+                    tbn[posr[u].y & 0xffffu] = e[2]; tbn[posr[u].y >> 16] = e[3];
+                }
+            }
+            if (n + 1 < n_end) issue(n + 1);   // the next frame starts its trip now
+            sum = wave_sum(sum);
+            if (lane == 0) red[par * 16 + wave] = sum;
+            __syncthreads();                       // the frame's only barrier
+            sum = red[par * 16];
+#pragma unroll
+            for (int w = 1; w < MT / kWave; ++w) sum += red[par * 16 + w];
+            const float scale = sum > 0.0f ? G0.sign / sum : 0.0f;
+            float *prow = P.pdf_out + ((size_t)b * P.N + n) * D;
+            const float *nv = nval + par * G1.Rcap;
+#pragma unroll
+            for (int j = 0; j < kGradPdf; ++j) {
+                const int d = j * MT + tid;
+                if (d < D) {
+                    float acc = 0.0f;
+                    for (int i = (int)(prange[j] & 0xffffu); i < (int)(prange[j] >> 16); ++i) acc += tbn[i];   // ascending states
+                    const int r = nidx[d];
+                    float v = acc * scale;
+                    if (r) v += nv[r - 1];
+                    prow[d] = v;
+                }
+            }
+        }
+    } else {
+        NT qa[NU], qb[NU];            // rows of the frame being prefetched / worked on
+        auto issue = [&](int n) {
+            const NT *ar = (const NT *)G1.a + (size_t)n * G1.Ktot + ps1.k0, *br = (const NT *)G1.b + (size_t)n * G1.Ktot + ps1.k0;
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+                const int k = u * kWave + lane;
+                if (k < K1) { qa[u] = ar[k]; qb[u] = br[k]; }
+            }
+        };
+        if (!has_num) {
+            for (int n = n0; n < n_end; ++n) __syncthreads();
+            return;
+        }
+        issue(n0);
+        for (int r = lane; r <= R1; r += kWave) nptr[r] = G1.pdfs.row_ptr[ps1.ptr0 + r];
+        for (int k = lane; k < K1; k += kWave) nst[k] = G1.pdfs.states[ps1.st0 + k];
+        for (int n = n0; n < n_end; ++n) {
+            const int par = (n - n0) & 1;
+            NT t[NU];
+            NT mx = (NT)(-INFINITY);
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+                const int k = u * kWave + lane;
+                if (k < K1) {
+                    t[u] = (qa[u] + qb[u]) * (NT)G1.in_scale;
+                    mx = tmax(mx, t[u]);
+                }
+            }
+            if (n + 1 < n_end) issue(n + 1);
+            mx = wave_max(mx);
+            float sum = 0.0f;
+            const bool mass = mx != (NT)(-INFINITY);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the previous frame's reads of en come first
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+                const int k = u * kWave + lane;
+                if (k < K1) {
+                    const float e = mass ? fexp2((float)(t[u] - mx)) : 0.0f;
+                    en[k] = e;
+                    sum += e;
+                }
+            }
+            sum = wave_sum(sum);
+            const float scale = sum > 0.0f ? G1.sign / sum : 0.0f;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the wave's writes of en (and of its tables) before its reads
+            float *nv = nval + par * G1.Rcap;
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+                const int r = u * kWave + lane;
+                if (r < R1) {
+                    float acc = 0.0f;
+                    for (int i = nptr[r]; i < nptr[r + 1]; ++i) acc += en[nst[i]];
+                    nv[r] = acc * scale;
+                }
+            }
+            __syncthreads();                       // the frame's only barrier: the denominator waves may read nv
+        }
+    }
+}
+
 // The pdf posteriors of small packed graphs (at most kGradNumK states and pdf rows each; the numerators of an
 // LF-MMI call) added, with the graph's sign, to rows that already hold another graph's share (PostParams::accumulate).
 // grid = (ceil(N / frames_per_block), B), one wave per workgroup: the wave walks its frames as the last wave of
@@ -1459,6 +1656,11 @@ int launch_posteriors(const PostParams &p, size_t lds_bytes, void *stream)
 
 bool gradient_kernel_applies(const PostParams &p)
 {
+    if (p.n_graph == 1 && p.cum_a && p.pdf_out && !p.accumulate) {   // the shared graph's share alone: fb_grad1_kernel without numerators
+        const PostGraph &d = p.g[0];
+        return d.shared && !d.f64 && !d.state_post && d.pdfs.pos && (d.ld & 3) == 0 && d.ld >= ((d.Kcap + 3) & ~3) &&
+               d.Kcap <= kGradMain * 4 * kGradU && (((uintptr_t)d.a | (uintptr_t)d.b) & 15) == 0 && p.D <= kGradMain * kGradPdf;
+    }
     if (p.n_graph != 2 || !p.pdf_out) return false;
     const PostGraph &d = p.g[0], &n = p.g[1];
     return d.shared && !d.f64 && !d.state_post && d.pdfs.pos && (d.ld & 3) == 0 && d.ld >= ((d.Kcap + 3) & ~3) &&
@@ -1470,6 +1672,10 @@ bool gradient_kernel_applies(const PostParams &p)
 size_t gradient_lds_bytes(const PostParams &p)
 {
     const PostGraph &d = p.g[0], &n = p.g[1];
+    if (p.cum_a) {   // fb_grad1_kernel (one graph: no numerator tables)
+        const size_t nR = p.n_graph == 2 ? (size_t)n.Rcap : 0, nK = p.n_graph == 2 ? (size_t)n.Kcap : 0;
+        return 128 + (2 * ((size_t)((d.Kcap + 3) & ~3) + 4) + 2 * nR + nK) * 4 + ((size_t)((p.D + 1) & ~1) + nR * 2 + 1 + nK + 3) / 2 * 4;
+    }
     return 128 + ((size_t)((d.Kcap + 3) & ~3) + 4 + (size_t)((p.D + 3) & ~3) + (size_t)n.Kcap) * 4 +
            ((size_t)n.Rcap * 2 + 1 + (size_t)n.Kcap + 3) / 2 * 4;
 }
@@ -1477,7 +1683,8 @@ size_t gradient_lds_bytes(const PostParams &p)
 int launch_gradient(const PostParams &p, size_t lds_bytes, void *stream)
 {
     const dim3 grid((unsigned)((p.N + p.frames_per_block - 1) / p.frames_per_block), (unsigned)(p.order ? p.n_launch : p.B));
-    auto kern = p.g[1].f64 ? fb_grad_kernel<double> : fb_grad_kernel<float>;
+    auto kern = p.cum_a ? (p.n_graph == 2 && p.g[1].f64 ? fb_grad1_kernel<double> : fb_grad1_kernel<float>)
+                        : (p.g[1].f64 ? fb_grad_kernel<double> : fb_grad_kernel<float>);
     if (lds_bytes > 64 * 1024) {
         const hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return fail(FB_EHIP, std::string("hipFuncSetAttribute(LDS size): ") + hipGetErrorString(e));
