@@ -256,10 +256,9 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
  * (c) Otherwise the call is lfmmi_loss_grad.
  * In every case the library's streams are forked from and joined back into `stream` with
  * events, so for the caller the call is ordered on `stream` as usual.  Same arguments,
- * workspace and errors as lfmmi_loss_grad, same loss and log Z bit for bit; where the
- * numerators' share is added by a launch of its own a gradient entry may differ from
- * lfmmi_loss_grad's by the rounding of that one addition.  Calls from several host threads
- * must not overlap.
+ * workspace and errors as lfmmi_loss_grad, same loss and log Z bit for bit, the same
+ * gradient to rounding (the launches of the schedules form the same sums in different
+ * orders).  Calls from several host threads must not overlap.
  */
 int lfmmi_loss_grad_ragged(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths,
                            const int32_t *lengths_host, int32_t B, int32_t N, int32_t D, double *loss,

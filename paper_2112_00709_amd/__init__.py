@@ -276,8 +276,7 @@ def lfmmi_loss_grad(den: Graph, num: Graph, emis, lengths, ws=None, grad=None, l
     """-> (loss [1] float64, logz_num [B], logz_den [B], grad [B,N,D]), all on the device.
     ``ws`` (uint8 CUDA tensor of fb_lfmmi_workspace_bytes) and ``grad`` may be passed in for reuse.
     ``lengths_host``: a host copy of ``lengths`` (numpy int32 or a sequence); with it the call goes to
-    lfmmi_loss_grad_ragged, which picks the schedule of the call's launches from them (same results up to the
-    rounding of one addition per gradient entry)."""
+    lfmmi_loss_grad_ragged, which picks the schedule of the call's launches from them (same results to rounding)."""
     torch = _torch()
     B, N, D = _dev_inputs(emis, lengths)
     need = fb_lfmmi_workspace_bytes(den, num, B, N, D)

@@ -113,7 +113,7 @@ PostGraph make_post(const fb_graph *g, const void *a, const void *b, bool f64, f
     return q;
 }
 
-// what the one-barrier gradient kernel needs beside the vectors (PostParams::cum_a, cum_b, logz); all null: not given
+// what the gradient kernel needs beside the vectors (PostParams::cum_a, cum_b, logz); all null: not given
 struct Offsets {
     const float *cum_a = nullptr, *cum_b = nullptr;
     const double *logz = nullptr;
@@ -400,8 +400,7 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
     dd[0].cum = cum_a;
     dd[1].cum = cum_b;
     Offsets offs;
-    static const bool four_barriers = getenv("FB_AMD_GRAD1") && getenv("FB_AMD_GRAD1")[0] == '0';   // (diagnostic switch)
-    if (!four_barriers) { offs.cum_a = cum_a; offs.cum_b = cum_b; offs.logz = zd; }
+    offs.cum_a = cum_a; offs.cum_b = cum_b; offs.logz = zd;
     hipStream_t main_s = (hipStream_t)stream;
     SideStream &side = side_stream();
     // Eq. 17: numerator pdf posteriors minus denominator pdf posteriors

@@ -1033,16 +1033,28 @@ __global__ __launch_bounds__(kPostThreads) void fb_posterior_kernel(const PostPa
 // ---------------------------------------------------------------------------
 // Gradient of the LF-MMI objective (Eq. 17) for the usual pair of graphs: a shared
 // denominator whose vectors are float, packed numerators with at most kGradNumK
-// states and pdf rows each.  Same results as fb_posterior_kernel with these two
-// graphs (same per-frame normalisation, fixed summation order), organised for speed:
-// grid = (ceil(N / frames_per_block), B), 9 waves.  Waves 0-7 work on the
-// denominator: a thread keeps, for the whole block, the places of "its" states in
-// pdf order and the state ranges of "its" pdfs in registers, the rows of the next
-// frame travel from HBM into registers while the current frame is worked on, and
-// exp(log posterior - max) goes to LDS in pdf order, so that a pdf's states are
-// neighbours.  Wave 8 works on the numerator of the same frame at the same time,
-// with wave-level reductions only, and adds its pdf posteriors in last.  Four
-// workgroup barriers per frame.
+// states and pdf rows each (or the denominator's share alone), for calls whose
+// recursions also left the running sums of their offsets (PostParams::cum_a, cum_b:
+// A_n, B_n with alpha_n = stored row + A_n, beta_n = stored row + B_n, log2 units)
+// and log Z.  Same sums in the same order as fb_posterior_kernel, organised for speed:
+// grid = (ceil(N / frames_per_block), B), 9 waves, one workgroup barrier per frame.
+// Waves 0-7 work on the denominator: a thread keeps, for the whole block, the
+// places of "its" states in pdf order and the state ranges of "its" pdfs in
+// registers, the rows of the next frame travel from HBM into registers while the
+// current frame is worked on, and the exponentials go to LDS in pdf order, so that a
+// pdf's states are neighbours.  The exponentials of a frame are taken of
+//   t_k - (log2 Z - A_n - B_n) = log2 of the posterior itself (<= 0, largest >= -log2 K),
+// so no maximum over the frame, no reduction of it over the workgroup and no barrier
+// behind it are needed (the values are still normalised by their own sum, so a drift
+// of the float recursions cancels).  The denominator waves store their pdf posteriors
+// straight from the sums (no staging of the row in LDS), adding the numerator's value
+// for the pdf, which wave 8 - it works on the numerator of the same frame at the same
+// time, with wave-level reductions only - has left in a small list (two buffers, by
+// frame parity) before the frame's barrier; the exponentials in pdf order have two
+// buffers as well, so nothing of frame n + 1 overwrites what frame n still reads.
+// LDS: red [2][16] sums of waves 0-7; tb [2][K0 rounded to 4, + 4]; nval [2][Rcap] the numerator's pdf
+// posteriors by pdf row; en [Kcap] numerator exponentials; nidx [D] 16-bit: pdf -> its row in
+// this sequence's numerator + 1, 0 = none; the numerator tables.
 // ---------------------------------------------------------------------------
 constexpr int kGradMain = 512, kGradThreads = kGradMain + kWave;
 constexpr int kGradU = 3;        // 16-byte pieces of a denominator row per thread: 6144 states
@@ -1052,218 +1064,6 @@ constexpr int kGradNumK = kGradNumU * kWave;
 
 template <class NT>
 __global__ __launch_bounds__(kGradThreads, 5) void fb_grad_kernel(const PostParams P)
-{
-    extern __shared__ double lds_raw[];
-    constexpr int MT = kGradMain, U = kGradU, NU = kGradNumU;
-    const int tid = threadIdx.x, lane = tid & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const bool den_side = wave < MT / kWave;
-    const int b = P.order ? P.order[P.rank0 + blockIdx.y] : blockIdx.y;
-    const int T = min(max(P.lengths[b], 0), P.N);
-    const int n0 = blockIdx.x * P.frames_per_block;
-    const int n_end = min(min(n0 + P.frames_per_block, P.N), T);   // real frames of this chunk: [n0, n_end)
-    const PostGraph &G0 = P.g[0], &G1 = P.g[1];
-    const int K0 = G0.pdfs.sub[0].K, D = P.D;
-    const PdfSub ps1 = G1.pdfs.sub[b];
-    const int K1 = ps1.K, R1 = ps1.n_rows;
-
-    float *red = (float *)lds_raw;                       // [32] maxima, then sums, of waves 0-7
-    float *tb = red + 32;                                // [K0 rounded to 4, + 4] exp(log posterior - max), pdf order;
-                                                         // the places behind K0 take the padding of a row's last piece
-    float *rho = tb + ((K0 + 3) & ~3) + 4;               // [D rounded to 4]
-    float *en = rho + ((D + 3) & ~3);                    // [G1.Kcap] the numerator's exp(log posterior - max)
-    uint16_t *nptr = (uint16_t *)(en + G1.Kcap);         // numerator tables: row_ptr [Rcap + 1], row_pdf [Rcap], states [Kcap]
-    uint16_t *npdf = nptr + G1.Rcap + 1, *nst = npdf + G1.Rcap;
-
-    // padded frame: zeros, written by all threads of the block
-    auto zero_row = [&](int n) {
-        float *prow = P.pdf_out + ((size_t)b * P.N + n) * D;
-        for (int d = tid; d < D; d += kGradThreads) prow[d] = 0.0f;
-    };
-
-    // The two sides run separate loops over the frames (their registers never live together); both
-    // pass the same four barriers per real frame.
-    if (den_side) {
-        float4 pa[U], pb[U];          // rows of the frame being prefetched / worked on
-        uint2 posr[U];                // places (4 x 16 bit) of the thread's states in pdf order
-        uint32_t prange[kGradPdf];    // state ranges (begin | end << 16) of the thread's pdfs tid, tid + MT, ...
-        auto issue = [&](int n) {
-            const float4 *ar = (const float4 *)((const float *)G0.a + ((size_t)b * P.N + n) * G0.ld);
-            const float4 *br = (const float4 *)((const float *)G0.b + ((size_t)b * P.N + n) * G0.ld);
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int q = u * MT + tid;
-                if (q * 4 < K0) { pa[u] = ar[q]; pb[u] = br[q]; }
-            }
-        };
-        if (n0 < n_end) {
-            issue(n0);
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int q = u * MT + tid;
-                posr[u] = q * 4 < K0 ? ((const uint2 *)G0.pdfs.pos)[q] : make_uint2(0u, 0u);
-            }
-#pragma unroll
-            for (int j = 0; j < kGradPdf; ++j) {
-                const int d = j * MT + tid;
-                prange[j] = d < D ? (uint32_t)G0.pdfs.row_ptr[d] | ((uint32_t)G0.pdfs.row_ptr[d + 1] << 16) : 0u;
-            }
-        }
-        for (int fi = 0; fi < P.frames_per_block; ++fi) {
-            const int n = n0 + fi;
-            if (n >= P.N) break;
-            if (n >= T) { zero_row(n); continue; }
-            float t[U][4];
-            float mx = -INFINITY;
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int q = u * MT + tid;
-                if (q * 4 < K0) {
-                    t[u][0] = (pa[u].x + pb[u].x) * G0.in_scale; t[u][1] = (pa[u].y + pb[u].y) * G0.in_scale;
-                    t[u][2] = (pa[u].z + pb[u].z) * G0.in_scale; t[u][3] = (pa[u].w + pb[u].w) * G0.in_scale;
-                    if (q * 4 + 3 >= K0) {   // the row's last piece when K0 is not a multiple of 4: padding counts as zero-bar
-                        if (q * 4 + 1 >= K0) t[u][1] = -INFINITY;
-                        if (q * 4 + 2 >= K0) t[u][2] = -INFINITY;
-                        t[u][3] = -INFINITY;
-                    }
-                    mx = tmax(tmax(mx, tmax(t[u][0], t[u][1])), tmax(t[u][2], t[u][3]));
-                }
-            }
-            if (n + 1 < n_end) issue(n + 1);   // the next frame starts its trip now
-            mx = wave_max(mx);
-            if (lane == 0) red[wave] = mx;
-            __syncthreads();                       // (1)
-            mx = red[0];
-#pragma unroll
-            for (int w = 1; w < MT / kWave; ++w) mx = tmax(mx, red[w]);
-            float sum = 0.0f;
-            const bool mass = mx != -INFINITY;
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int q = u * MT + tid;
-                if (q * 4 < K0) {
-                    float e[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) e[j] = mass ? fexp2(t[u][j] - mx) : 0.0f;
-                    sum += (e[0] + e[1]) + (e[2] + e[3]);
-                    tb[posr[u].x & 0xffffu] = e[0]; tb[posr[u].x >> 16] = e[1];
-                    tb[posr[u].y & 0xffffu] = e[2]; tb[posr[u].y >> 16] = e[3];
-                }
-            }
-            sum = wave_sum(sum);
-            if (lane == 0) red[16 + wave] = sum;
-            __syncthreads();                       // (2)
-            sum = red[16];
-#pragma unroll
-            for (int w = 1; w < MT / kWave; ++w) sum += red[16 + w];
-            const float scale = sum > 0.0f ? G0.sign / sum : 0.0f;
-#pragma unroll
-            for (int j = 0; j < kGradPdf; ++j) {
-                const int d = j * MT + tid;
-                if (d < D) {
-                    float acc = 0.0f;
-                    for (int i = (int)(prange[j] & 0xffffu); i < (int)(prange[j] >> 16); ++i) acc += tb[i];   // ascending states
-                    rho[d] = acc * scale;
-                }
-            }
-            __syncthreads();                       // (3)
-            __syncthreads();                       // (4) the numerator's pdf posteriors are in
-            float *prow = P.pdf_out + ((size_t)b * P.N + n) * D;
-            if ((D & 3) == 0 && ((uintptr_t)prow & 15) == 0) {
-                for (int d4 = tid; d4 < D / 4; d4 += MT) ((float4 *)prow)[d4] = ((const float4 *)rho)[d4];
-            } else {
-                for (int d = tid; d < D; d += MT) prow[d] = rho[d];
-            }
-        }
-    } else {
-        NT qa[NU], qb[NU];            // rows of the frame being prefetched / worked on
-        auto issue = [&](int n) {
-            const NT *ar = (const NT *)G1.a + (size_t)n * G1.Ktot + ps1.k0, *br = (const NT *)G1.b + (size_t)n * G1.Ktot + ps1.k0;
-#pragma unroll
-            for (int u = 0; u < NU; ++u) {
-                const int k = u * kWave + lane;
-                if (k < K1) { qa[u] = ar[k]; qb[u] = br[k]; }
-            }
-        };
-        if (n0 < n_end) {
-            issue(n0);
-            for (int r = lane; r <= R1; r += kWave) nptr[r] = G1.pdfs.row_ptr[ps1.ptr0 + r];
-            for (int r = lane; r < R1; r += kWave) npdf[r] = G1.pdfs.row_pdf[ps1.row0 + r];
-            for (int k = lane; k < K1; k += kWave) nst[k] = G1.pdfs.states[ps1.st0 + k];
-        }
-        for (int fi = 0; fi < P.frames_per_block; ++fi) {
-            const int n = n0 + fi;
-            if (n >= P.N) break;
-            if (n >= T) { zero_row(n); continue; }
-            NT t[NU];
-            NT mx = (NT)(-INFINITY);
-#pragma unroll
-            for (int u = 0; u < NU; ++u) {
-                const int k = u * kWave + lane;
-                if (k < K1) {
-                    t[u] = (qa[u] + qb[u]) * (NT)G1.in_scale;
-                    mx = tmax(mx, t[u]);
-                }
-            }
-            if (n + 1 < n_end) issue(n + 1);
-            mx = wave_max(mx);
-            __syncthreads();                       // (1)
-            float sum = 0.0f;
-            const bool mass = mx != (NT)(-INFINITY);
-#pragma unroll
-            for (int u = 0; u < NU; ++u) {
-                const int k = u * kWave + lane;
-                if (k < K1) {
-                    const float e = mass ? fexp2((float)(t[u] - mx)) : 0.0f;
-                    en[k] = e;
-                    sum += e;
-                }
-            }
-            sum = wave_sum(sum);
-            const float scale = sum > 0.0f ? G1.sign / sum : 0.0f;
-            __syncthreads();                       // (2) also puts the wave's writes of en before its reads below
-            float nv[NU];
-#pragma unroll
-            for (int u = 0; u < NU; ++u) {
-                const int r = u * kWave + lane;
-                nv[u] = 0.0f;
-                if (r < R1) {
-                    float acc = 0.0f;
-                    for (int i = nptr[r]; i < nptr[r + 1]; ++i) acc += en[nst[i]];
-                    nv[u] = acc * scale;
-                }
-            }
-            __syncthreads();                       // (3) the denominator's pdf posteriors are in
-#pragma unroll
-            for (int u = 0; u < NU; ++u) {
-                const int r = u * kWave + lane;
-                if (r < R1) rho[npdf[r]] += nv[u];   // one row per pdf: no two lanes meet
-            }
-            __syncthreads();                       // (4)
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------
-// The same gradient with one workgroup barrier per frame, for calls whose
-// recursions also left the running sums of their offsets (PostParams::cum_a, cum_b:
-// A_n, B_n with alpha_n = stored row + A_n, beta_n = stored row + B_n, log2 units)
-// and log Z.  The exponentials of a frame are then taken of
-//   t_k - (log2 Z - A_n - B_n) = log2 of the posterior itself (<= 0, largest >= -log2 K),
-// so the frame's maximum, its reduction over the workgroup and the barrier behind
-// it fall away (the values are still normalised by their own sum: a drift of the
-// float recursions cancels as before).  The denominator waves store their pdf
-// posteriors straight from the sums (no staging of the row in LDS), adding the
-// numerator's value for the pdf, which the numerator wave has left in a small list
-// (two buffers, by frame parity) before the frame's barrier; the exponentials in
-// pdf order have two buffers as well, so nothing of frame n + 1 overwrites what
-// frame n still reads.  Everything else as in fb_grad_kernel (same sums, same order).
-// LDS: red [2][8] sums of waves 0-7; tb [2][K0r + 4]; nval [2][Rcap] the numerator's pdf
-// posteriors by pdf row; en [Kcap] numerator exponentials; nidx [D] 16-bit: pdf -> its row in
-// this sequence's numerator + 1, 0 = none; the numerator tables.
-// ---------------------------------------------------------------------------
-template <class NT>
-__global__ __launch_bounds__(kGradThreads, 5) void fb_grad1_kernel(const PostParams P)
 {
     extern __shared__ double lds_raw[];
     constexpr int MT = kGradMain, U = kGradU, NU = kGradNumU;
@@ -1656,12 +1456,13 @@ int launch_posteriors(const PostParams &p, size_t lds_bytes, void *stream)
 
 bool gradient_kernel_applies(const PostParams &p)
 {
-    if (p.n_graph == 1 && p.cum_a && p.pdf_out && !p.accumulate) {   // the shared graph's share alone: fb_grad1_kernel without numerators
+    if (!p.cum_a || !p.cum_b || !p.logz || !p.pdf_out || p.accumulate) return false;
+    if (p.n_graph == 1) {   // the shared graph's share alone: no numerators
         const PostGraph &d = p.g[0];
         return d.shared && !d.f64 && !d.state_post && d.pdfs.pos && (d.ld & 3) == 0 && d.ld >= ((d.Kcap + 3) & ~3) &&
                d.Kcap <= kGradMain * 4 * kGradU && (((uintptr_t)d.a | (uintptr_t)d.b) & 15) == 0 && p.D <= kGradMain * kGradPdf;
     }
-    if (p.n_graph != 2 || !p.pdf_out) return false;
+    if (p.n_graph != 2) return false;
     const PostGraph &d = p.g[0], &n = p.g[1];
     return d.shared && !d.f64 && !d.state_post && d.pdfs.pos && (d.ld & 3) == 0 && d.ld >= ((d.Kcap + 3) & ~3) &&
            d.Kcap <= kGradMain * 4 * kGradU &&
@@ -1672,19 +1473,14 @@ bool gradient_kernel_applies(const PostParams &p)
 size_t gradient_lds_bytes(const PostParams &p)
 {
     const PostGraph &d = p.g[0], &n = p.g[1];
-    if (p.cum_a) {   // fb_grad1_kernel (one graph: no numerator tables)
-        const size_t nR = p.n_graph == 2 ? (size_t)n.Rcap : 0, nK = p.n_graph == 2 ? (size_t)n.Kcap : 0;
-        return 128 + (2 * ((size_t)((d.Kcap + 3) & ~3) + 4) + 2 * nR + nK) * 4 + ((size_t)((p.D + 1) & ~1) + nR * 2 + 1 + nK + 3) / 2 * 4;
-    }
-    return 128 + ((size_t)((d.Kcap + 3) & ~3) + 4 + (size_t)((p.D + 3) & ~3) + (size_t)n.Kcap) * 4 +
-           ((size_t)n.Rcap * 2 + 1 + (size_t)n.Kcap + 3) / 2 * 4;
+    const size_t nR = p.n_graph == 2 ? (size_t)n.Rcap : 0, nK = p.n_graph == 2 ? (size_t)n.Kcap : 0;   // one graph: no numerator tables
+    return 128 + (2 * ((size_t)((d.Kcap + 3) & ~3) + 4) + 2 * nR + nK) * 4 + ((size_t)((p.D + 1) & ~1) + nR * 2 + 1 + nK + 3) / 2 * 4;
 }
 
 int launch_gradient(const PostParams &p, size_t lds_bytes, void *stream)
 {
     const dim3 grid((unsigned)((p.N + p.frames_per_block - 1) / p.frames_per_block), (unsigned)(p.order ? p.n_launch : p.B));
-    auto kern = p.cum_a ? (p.n_graph == 2 && p.g[1].f64 ? fb_grad1_kernel<double> : fb_grad1_kernel<float>)
-                        : (p.g[1].f64 ? fb_grad_kernel<double> : fb_grad_kernel<float>);
+    auto kern = p.n_graph == 2 && p.g[1].f64 ? fb_grad_kernel<double> : fb_grad_kernel<float>;
     if (lds_bytes > 64 * 1024) {
         const hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return fail(FB_EHIP, std::string("hipFuncSetAttribute(LDS size): ") + hipGetErrorString(e));

@@ -288,7 +288,7 @@ def test_lfmmi_in_length_groups(fb, B):
     one gradient launch per range on streams of their own): batch sizes that are and are not multiples of the
     range granularity, many equal lengths, every sequence checked against the oracle; a second call on the same
     graphs must give the same bits, the plain entry point the same objective and log Z bit for bit and the
-    same gradient up to the rounding of one addition."""
+    same gradient to rounding (the launches form the same sums in another order)."""
     import torch
     w2 = wl.config5(K=300, B=B, Lmin=2, Lmax=9, D=40)   # 8 distinct lengths: most ranks are decided by index
     assert np.unique(w2.lengths).size < B // 3
@@ -305,7 +305,7 @@ def test_lfmmi_in_length_groups(fb, B):
         if i < 3:
             assert np.array_equal(a, c)                  # objective and log Z: the two entry points agree bit for bit
         else:
-            assert np.allclose(a, c, rtol=0, atol=1e-6)  # gradient: up to the rounding of one addition
+            assert np.allclose(a, c, rtol=0, atol=3e-6)  # gradient: the same sums formed in another order
     Gd.destroy(); Gn.destroy()
 
 
@@ -316,7 +316,7 @@ def test_lfmmi_equal_lengths_numerators_apart(fb, phones, N, short):
     gradient while the numerator recursion runs and adds the numerators' share in a launch of its own: the
     one-wave kernel for numerators of up to 512 states, the general posterior kernel for larger ones (540 here).
     Every sequence against the oracle; a few shorter sequences so that padded frames occur; same results as the
-    plain entry point up to the rounding of one addition."""
+    plain entry point to rounding."""
     import torch
     base = wl.paper_shape_den(K=1100, E_target=5000, B=128, N=N, D=30)
     rng = np.random.default_rng(5)
@@ -334,7 +334,7 @@ def test_lfmmi_equal_lengths_numerators_apart(fb, phones, N, short):
     torch.cuda.synchronize()
     for a, b, c in zip(apart, again, plain):
         assert np.array_equal(a, b)
-        assert np.allclose(a, c, rtol=0, atol=1e-6)
+        assert np.allclose(a, c, rtol=0, atol=3e-6)      # the same sums formed in another order
     Gd.destroy(); Gn.destroy()
 
 
