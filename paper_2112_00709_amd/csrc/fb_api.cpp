@@ -375,7 +375,8 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
     if (!ws || ws_bytes < need) return fail(FB_EINVAL, "lfmmi_loss_grad: workspace missing or too small");
     if (((uintptr_t)ws & 255) != 0) return fail(FB_EINVAL, "lfmmi_loss_grad: workspace must be 256-byte aligned");
 
-    // workspace: forward and backward vectors of both graphs in log2 units, log Z when the caller keeps none
+    // workspace: forward and backward vectors of both graphs in log2 units, log Z when the caller keeps none, the
+    // sequences in order of length, the running offsets of the denominator's forward and backward rows
     char *w = (char *)ws;
     const size_t den_vec = align256((size_t)B * N * lfmmi_den_ld(den) * (den->f64 ? 8 : 4));
     const size_t num_vec = align256((size_t)N * num->K * (num->f64 ? 8 : 4));
