@@ -162,6 +162,11 @@ int fb_graph_layout(const fb_graph *g, int which, void *host_out, size_t bytes);
  *   which = 0  forward plan:  y[j] = (+)-sum over arcs entering j of (w (x) x[src]), log2 units
  *   which = 1  backward plan: y[i] = (+)-sum over arcs leaving i of (w (x) x[dst]), log2 units
  *   which = 2  pdf plan:      y[d] = sum of x over the states tied to pdf d (ordinary sum)
+ *   which = 3, 4  the forward / backward plan in the form with weights as 2^w (see
+ *              fb_graph_linear_weights), whatever form the device copy has: same results to
+ *              rounding; FB_EUNSUPPORTED if a weight of the graph is out of that form's range;
+ *              the walk also checks what the multiplying kernel relies on (an internal
+ *              error, FB_EHIP, if it does not hold)
  * sub: 0 for a shared graph, the sequence index for packed graphs; x and y use
  * the sub-graph's local state numbering (y: pdf ids for which = 2; entries
  * without a row keep their value).  Weights are the graph's log-weights times

@@ -430,8 +430,16 @@ static const void *layout_array(const fb_graph *g, int which, int64_t *n)
 int fb_graph_schedule_apply_host(const fb_graph *g, int which, int32_t sub, const double *x, double *y)
 {
     if (!g || !x || !y) return fail(FB_EINVAL, "fb_graph_schedule_apply_host: NULL argument");
-    if (which < 0 || which > 2 || sub < 0 || (size_t)sub >= g->h_pdf.sub.size())
+    if (which < 0 || which > 4 || sub < 0 || (size_t)sub >= g->h_pdf.sub.size())
         return fail(FB_EINVAL, "fb_graph_schedule_apply_host: unknown schedule or sub-graph");
+    if (which >= 3) {   // the forward / backward stream with weights as 2^w
+        const StreamHost &S = which == 3 ? g->h_fwd : g->h_bwd;
+        std::vector<Arc> lin;
+        std::string why;
+        if (!stream_linear_weights(S, lin)) return fail(FB_EUNSUPPORTED, "fb_graph_schedule_apply_host: the weights of this graph do not take the form 2^w");
+        if (!stream_apply_host(S, sub, x, y, &lin, why)) return fail(FB_EHIP, "internal error: stream with weights as 2^w (" + why + ")");
+        return FB_OK;
+    }
     if (which == 2) {
         const PdfHost &PH = g->h_pdf;
         const PdfSub &ps = PH.sub[(size_t)sub];
@@ -442,7 +450,8 @@ int fb_graph_schedule_apply_host(const fb_graph *g, int which, int32_t sub, cons
             y[PH.row_pdf[(size_t)ps.row0 + r]] = acc;
         }
     } else {
-        stream_apply_host(which == 0 ? g->h_fwd : g->h_bwd, sub, x, y);
+        std::string why;
+        stream_apply_host(which == 0 ? g->h_fwd : g->h_bwd, sub, x, y, nullptr, why);
     }
     return FB_OK;
 }

@@ -153,7 +153,10 @@ struct StreamDev {
 // esize: bytes per element of the vector the kernel gathers from (4 or 8); arc sources become byte offsets
 bool stream_from_sell(const SellHost &S, int32_t Kcap, int32_t Ecap, int32_t esize, StreamHost &out, std::string &why);
 bool stream_in_bounds(const StreamHost &S, int32_t n_vidx, std::string &why);
-void stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double *y);
+// y = the (+)-product of sub-graph `sub` with x, computed on the host by walking the stream as the kernel does.
+// lin: nullptr, or the arc list stream_linear_weights made of S: then the walk also checks what the multiplying
+// kernel instantiation relies on (false, with the reason in why, if it does not hold).
+bool stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double *y, const std::vector<Arc> *lin, std::string &why);
 // The arc list of S with the weights of all batches but the stacked ones replaced by 2^w, for the kernel
 // instantiation that multiplies instead of adding in the exponent; arcs of weight zero-bar (padding included) get
 // weight 0 and the dump slot, which always holds zero-bar, as their source, so that they never raise a running

@@ -207,7 +207,7 @@ bool stream_in_bounds(const StreamHost &S, int32_t n_vidx, std::string &why)
 // The streams of sub-graph `sub` interpreted on the host in double precision as the kernel
 // does (lanes, groups of lanes, clones): y[state] for every state, before emission and offset
 // are applied; x holds one value per state.
-void stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double *y)
+bool stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double *y, const std::vector<Arc> *lin, std::string &why)
 {
     const SubDesc &sd = S.sub[(size_t)sub];
     // the vector the rows gather from: a cloned state's value sits in the state itself, its clones hold zero
@@ -247,11 +247,22 @@ void stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double
                 continue;
             }
             const int g = 1 << ((f >> kFlagLgShift) & 7u);
+            const std::vector<Arc> &arcs = lin ? *lin : S.arcs;
+            const int32_t dump = S.Kcap + S.Ccap;
             for (int r = 0; r < kBatchRows; ++r)
                 for (int lane = 0; lane < kWave; ++lane) {
-                    const Arc &a = S.arcs[(size_t)wd.arc_base + entry_at(bt, r, lane)];
+                    const Arc &a = arcs[(size_t)wd.arc_base + entry_at(bt, r, lane)];
                     const bool closing = r == kBatchRows - 1 && (f & kFlagInfo);
                     const int32_t src = (closing ? (int32_t)((uint32_t)a.src & 0xffffu) : a.src) / S.esize;
+                    if (lin) {
+                        // weights as 2^w: an entry of weight 0 must gather the dump slot (zero-bar), or the
+                        // kernel's running maximum, which is over the gathered values alone, could exceed every term
+                        if (a.w == 0.0f && src != dump) { why = "an entry of weight 0 gathers a state"; return false; }
+                        if (a.w != 0.0f && src == dump) { why = "a weighted entry gathers the dump slot"; return false; }
+                        const double xv = src == dump ? -INFINITY : xe[(size_t)(src < sd.K ? src : sd.K + (src - S.Kcap))];
+                        terms[lane].push_back((a.w == 0.0f ? -INFINITY : std::log2((double)a.w)) + xv);
+                        continue;
+                    }
                     terms[lane].push_back((double)a.w + xe[(size_t)(src < sd.K ? src : sd.K + (src - S.Kcap))]);
                 }
             if (f & kFlagInfo) {
@@ -261,8 +272,9 @@ void stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double
                     for (int t = 0; t < g; ++t) terms[lane + t].assign(1, lse(all));   // every lane of the row holds the total
                 }
                 for (int lane = 0; lane < kWave; ++lane) {
-                    const Arc &a = S.arcs[(size_t)wd.arc_base + entry_at(bt, kBatchRows - 1, lane)];
+                    const Arc &a = arcs[(size_t)wd.arc_base + entry_at(bt, kBatchRows - 1, lane)];
                     const int32_t t = (int32_t)((uint32_t)a.src >> 16);
+                    if (lin && t == dump && terms[lane][0] != -INFINITY) { why = "a row's total goes to the dump slot"; return false; }
                     if (t < sd.K) ye[(size_t)t] = terms[lane][0];
                     else if (t < S.Kcap + sd.n_slot) ye[(size_t)sd.K + (size_t)(t - S.Kcap)] = terms[lane][0];
                     terms[lane].clear();
@@ -277,6 +289,7 @@ void stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double
         ye[(size_t)cd.state] = lse(all);
     }
     for (int32_t k = 0; k < sd.K; ++k) y[k] = ye[(size_t)k];
+    return true;
 }
 
 bool stream_linear_weights(const StreamHost &S, std::vector<Arc> &out)

@@ -155,6 +155,51 @@ def test_kernel_schedule_on_random_graph_shapes(seed):
     h.destroy()
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_plans_with_weights_as_powers_of_two(seed):
+    """The form of the plans the multiplying kernel instantiation walks (weights as 2^w; zero-bar arcs and padding
+    gather the dump slot; the lanes of a row spread over several lanes all write the row's total to its state):
+    interpreted on the host it gives the same products as the adding form, and the walk finds nothing the
+    multiplying kernel could not rely on.  Graphs with hubs, clones, parallel arcs, zero-bar weights; packed graphs;
+    a weight out of range is refused."""
+    rng = np.random.default_rng(300 + seed)
+    kind = seed % 3
+    if kind == 0:
+        g = wl.random_graph(rng, int(rng.integers(1100, 3600)), 9, zipf_s=float(rng.uniform(1.0, 1.5)),
+                            mean_extra_deg=float(rng.uniform(2, 12)))
+    elif kind == 1:
+        g = _pack([wl.random_graph(rng, int(rng.integers(200, 1500)), 9, zipf_s=1.3) for _ in range(3)])
+    else:
+        g0 = wl.random_graph(rng, 5200, 9, mean_extra_deg=1.0)          # one giant hub and parallel arcs into it
+        every = np.concatenate([np.arange(g0.K), np.arange(0, g0.K, 3)]).astype(np.int32)
+        g = wl.Graph(g0.K, np.concatenate([g0.src, every]), np.concatenate([g0.dst, np.full(every.size, 7, np.int32)]),
+                     np.concatenate([g0.logw, rng.normal(size=every.size).astype(np.float32)]), g0.pdf, g0.init, g0.final)
+    logw = g.logw.copy()
+    logw[rng.integers(0, logw.size, size=logw.size // 20)] = -np.inf     # zero-bar arcs
+    logw[rng.integers(0, logw.size, size=5)] = -40.0                      # tiny, in range
+    g = wl.Graph(g.K, g.src, g.dst, logw, g.pdf, g.init, g.final, state_off=g.state_off if g.packed else None)
+    h = _host_graph(g, 9)
+    off = g.state_off if g.packed else np.array([0, g.K])
+    for sub in range(len(off) - 1):
+        Ks = int(off[sub + 1] - off[sub])
+        x = rng.normal(size=Ks) * 30                                      # a wide range: the maximum matters
+        x[rng.integers(0, Ks, size=max(1, Ks // 10))] = -np.inf
+        for which in (0, 1):
+            want = fb.fb_graph_schedule_apply_host(h, which, sub, x, np.full(Ks, 123.0))
+            y = fb.fb_graph_schedule_apply_host(h, which + 3, sub, x, np.full(Ks, 123.0))
+            assert np.array_equal(np.isneginf(y), np.isneginf(want))
+            fin = np.isfinite(want)
+            np.testing.assert_allclose(y[fin], want[fin], rtol=0, atol=1e-5)
+    h.destroy()
+    far = g.logw.copy()
+    far[g.src == g.src[np.flatnonzero(np.isfinite(far))[0]]] = -60.0      # every arc out of one state 2^-86.6: out of range
+    h = _host_graph(wl.Graph(g.K, g.src, g.dst, far, g.pdf, g.init, g.final, state_off=g.state_off if g.packed else None), 9)
+    with pytest.raises(fb.FBError) as err:
+        fb.fb_graph_schedule_apply_host(h, 3, 0, np.zeros(int(off[1] - off[0])), np.zeros(int(off[1] - off[0])))
+    assert err.value.code == fb.FB_EUNSUPPORTED
+    h.destroy()
+
+
 def test_hub_graphs_really_have_long_rows():
     w = wl.config4(K=900, B=2, Nmin=3, Nmax=4, D=64)
     assert np.bincount(w.den.dst, minlength=900).max() > 32 * 32     # a row spread over all 64 lanes
