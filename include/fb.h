@@ -249,7 +249,9 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
  * and three of the library's), and the gradient of the shorter ranges runs on the compute
  * units their sequences have left while the recursion of the longest range is still going
  * (for one range the numerators' share of the gradient is added by a launch of its own, as
- * in (b)).  Not used when FB_AMD_GROUPS=0 or
+ * in (b); the gradient of the shorter half of the longest range waits, with
+ * hipStreamWaitValue32 where the device has it, for a counter that half's recursion
+ * workgroups increment, not for the end of the launch).  Not used when FB_AMD_GROUPS=0 or
  * FB_AMD_SERIAL=1 is in the environment (the three streams are then not created: with the
  * caller's they take the four hardware queues a process has).
  * (b) Sequences of (nearly) equal length, a denominator graph large enough for the 16-wave

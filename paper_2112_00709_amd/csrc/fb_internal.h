@@ -256,6 +256,11 @@ struct RecParams {
     // (longest first, written by launch_order), ranks [rank0, rank0 + n_launch).  order == nullptr: all B.
     const int32_t *order;
     int32_t rank0, n_launch;
+    // Progress counters (nullptr: none): a workgroup that has written everything it writes adds one to done[i],
+    // i = how many of done_from[0..2] its rank (in order of length) has reached; i = 0 counts for nothing.
+    // A stream can wait for such a word (hipStreamWaitValue32) and so for part of a launch.
+    uint32_t *done;
+    int32_t done_from[3];
 };
 
 struct PostGraph {
@@ -308,7 +313,7 @@ int launch_num_add(const PostParams &p, void *stream);
 // order[r] = index of the sequence of rank r when sorted by length (clamped to [0, N]), longest first, equal
 // lengths by index
 int launch_delay(void *stream);   // an empty kernel: what follows on the stream starts a launch latency later
-int launch_order(const int32_t *lengths, int32_t B, int32_t N, int32_t *order, void *stream);
+int launch_order(const int32_t *lengths, int32_t B, int32_t N, int32_t *order, uint32_t *done, void *stream);   // done: four words to clear, or nullptr
 int launch_loss(const double *logz_num, const double *logz_den, const int32_t *lengths, int32_t B, double *loss,
                 void *stream);
 // xs_fixed: 0, or kXsFixed for the fixed-buffer instantiation

@@ -811,6 +811,17 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
         if (off_seq)
             for (int f = Tn + tid; f < P.N; f += NT) off_seq[f] = 0.0f;
     }
+
+    // ---- progress counter: everything this workgroup writes is on its way; make it visible device-wide, then count
+    if (P.done) {
+        const int rank = P.rank0 + (int)blockIdx.x / P.n_dir;   // (launches with counters cover ranks in order)
+        const int slot = (rank >= P.done_from[0] ? 1 : 0) + (rank >= P.done_from[1] ? 1 : 0) + (rank >= P.done_from[2] ? 1 : 0);
+        __syncthreads();
+        if (tid == 0 && slot > 0) {
+            __threadfence();
+            atomicAdd(P.done + slot, 1u);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -1317,9 +1328,10 @@ __global__ __launch_bounds__(kWave) void fb_num_add_kernel(const PostParams P)
 
 // order[rank] = b: the sequences by length, longest first (equal lengths by index).  One thread per sequence
 // counts the sequences that go before its own.
-__global__ __launch_bounds__(256) void fb_order_kernel(const int32_t *lengths, int32_t B, int32_t N, int32_t *order)
+__global__ __launch_bounds__(256) void fb_order_kernel(const int32_t *lengths, int32_t B, int32_t N, int32_t *order, uint32_t *done)
 {
     const int b = blockIdx.x * 256 + threadIdx.x;
+    if (done && b < 4) done[b] = 0u;   // the progress counters of the call start at zero
     if (b >= B) return;
     const int lb = min(max(lengths[b], 0), N);
     int rank = 0;
@@ -1515,9 +1527,9 @@ int launch_delay(void *stream)
     return check_launch("delay kernel launch");
 }
 
-int launch_order(const int32_t *lengths, int32_t B, int32_t N, int32_t *order, void *stream)
+int launch_order(const int32_t *lengths, int32_t B, int32_t N, int32_t *order, uint32_t *done, void *stream)
 {
-    hipLaunchKernelGGL(fb_order_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, (hipStream_t)stream, lengths, B, N, order);
+    hipLaunchKernelGGL(fb_order_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, (hipStream_t)stream, lengths, B, N, order, done);
     return check_launch("order kernel launch");
 }
 
