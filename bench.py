@@ -33,7 +33,7 @@ VALU_PEAK_PER_S = 256 * 64 * 2.4e9
 # HBM bytes per denominator-recursion launch on configuration 5 from rocprofv3 --pmc
 # (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on a plain copy kernel);
 # see profiles/.  None until measured for the workload being run.
-MEASURED_TRAFFIC_BYTES = {"config5": 532534 * 1024 * 2.00 + 2077677 * 1024 * 1.00}
+MEASURED_TRAFFIC_BYTES = {"config5": 532536 * 1024 * 2.00 + 2077684 * 1024 * 1.00}
 
 
 def log(*a):
