@@ -37,7 +37,11 @@
  * call is a DEVICE pointer owned by the caller; the library neither allocates
  * nor frees nor synchronises in a compute call, it only enqueues kernels on
  * `stream` (a hipStream_t, NULL = the default stream).  Inputs are read-only.
- * Outputs are overwritten in full unless stated.
+ * Outputs are overwritten in full unless stated.  A compute call may be recorded
+ * into a HIP graph by stream capture on `stream` (streams of the library's own
+ * that a call uses are forked from and joined into `stream` with events; nothing
+ * is cleared with a memset; the one step that cannot be recorded, a stream wait
+ * on a value in lfmmi_loss_grad_ragged, is left out while `stream` is capturing).
  *
  * Layouts (row-major, last index fastest):
  *   emis, pdf_post, grad   float [B][N][D]

@@ -455,7 +455,10 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
         // gradient of part 0 waits for the launch itself.  (Measured: 2.94 instead of 3.03 ms per call with two
         // parts; three or four parts give the same.)
         // ranks [part_from[p], part_from[p + 1]); entries beyond n_part stay at B + 1 (never reached)
-        const int n_part = (side.can_wait_value && cut[1] >= 4 * kRange0Parts) ? kRange0Parts : 1;
+        // (a stream wait on a value cannot be recorded into a graph: not while the caller's stream is being captured)
+        hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+        const bool plain_stream = hipStreamIsCapturing(main_s, &capturing) == hipSuccess && capturing == hipStreamCaptureStatusNone;
+        const int n_part = (side.can_wait_value && plain_stream && cut[1] >= 4 * kRange0Parts) ? kRange0Parts : 1;
         int32_t part_from[5] = {0, B + 1, B + 1, B + 1, B + 1};
         for (int pt = 1; pt < n_part; ++pt) part_from[pt] = (int32_t)((int64_t)cut[1] * pt / n_part);
         part_from[n_part] = cut[1];

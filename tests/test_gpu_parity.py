@@ -485,6 +485,45 @@ def test_both_forms_of_the_arc_weights(fb):
     compare_fb(fb, g3, D, emis, lengths, name="a weight out of range: the adding form")
 
 
+def test_lfmmi_call_replayed_from_a_graph(fb):
+    """The LF-MMI call captured into a HIP graph (through torch) on a side stream and replayed: the library's own
+    streams are forked from and joined into the capturing stream with events, it allocates nothing and clears its
+    counters with a kernel, so every replay - with new emissions written into the same input buffer between
+    replays, and eager work in between - must give what the eager call gives on those emissions."""
+    import torch
+    w = wl.config5(K=300, B=40, Lmin=2, Lmax=9, D=40)
+    assert w.lengths.mean() < 0.85 * w.lengths.max()
+    Gd, Gn = fb.graph_from(w.den, w.D), fb.graph_from(w.num, w.D)
+    e = dev(w.emis).clone()
+    l = dev(w.lengths.astype(np.int32))
+    ws = torch.empty((fb.fb_lfmmi_workspace_bytes(Gd, Gn, w.B, w.N, w.D),), dtype=torch.uint8, device="cuda")
+    grad = torch.empty((w.B, w.N, w.D), dtype=torch.float32, device="cuda")
+    fb.lfmmi_loss_grad(Gd, Gn, e, l, ws=ws, grad=grad, lengths_host=w.lengths)      # warm-up outside the capture
+    torch.cuda.synchronize()
+    say("graph: capture of lfmmi_loss_grad_ragged")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        out = fb.lfmmi_loss_grad(Gd, Gn, e, l, ws=ws, grad=grad, lengths_host=w.lengths)
+    rng = np.random.default_rng(3)
+    for rep in range(3):
+        new = (w.emis + rng.standard_normal(w.emis.shape).astype(np.float32) * (0.5 * rep)).astype(np.float32)
+        e.copy_(dev(new))
+        torch.cuda.synchronize()
+        say(f"graph: replay {rep}")
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [host(x).copy() for x in out]
+        ws2 = torch.empty_like(ws)
+        want = [host(x).copy() for x in fb.lfmmi_loss_grad(Gd, Gn, dev(new), l, ws=ws2, lengths_host=w.lengths)]   # eager, other buffers
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(zip(got, want)):
+            if i < 3:
+                assert np.array_equal(a, b), i
+            else:
+                assert np.allclose(a, b, rtol=0, atol=3e-6)
+    Gd.destroy(); Gn.destroy()
+
+
 def test_results_are_deterministic(fb):
     import torch
     w = wl.config5(K=800, B=5, Lmin=3, Lmax=8, D=120)
