@@ -207,6 +207,20 @@ def _dp(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
+# Tests set this to have every buffer the binding allocates for an output or a workspace start out as NaN
+# (all bits set) instead of whatever the allocator hands back: a kernel that leaves part of an output unwritten,
+# or reads workspace it has not written in the same call, then cannot pass by luck.
+POISON_NEW_BUFFERS = False
+
+
+def _new(shape, dtype, device):
+    torch = _torch()
+    t = torch.empty(shape, dtype=dtype, device=device)
+    if POISON_NEW_BUFFERS:
+        t.view(torch.uint8).fill_(255)
+    return t
+
+
 def _stream():
     return ctypes.c_void_p(_torch().cuda.current_stream().cuda_stream)
 
@@ -228,9 +242,9 @@ def _vec_shape(g: Graph, B: int, N: int):
 def _recursion(fn, g: Graph, emis, lengths, want_vectors: bool):
     torch = _torch()
     B, N, D = _dev_inputs(emis, lengths)
-    vec = torch.empty(_vec_shape(g, B, N), dtype=torch.float32, device=emis.device) if want_vectors else None
-    off = torch.empty((B, N), dtype=torch.float32, device=emis.device)
-    logz = torch.empty((B,), dtype=torch.float64, device=emis.device)
+    vec = _new(_vec_shape(g, B, N), torch.float32, emis.device) if want_vectors else None
+    off = _new((B, N), torch.float32, emis.device)
+    logz = _new((B,), torch.float64, emis.device)
     _check(fn(g.handle, _dp(emis), _dp(lengths), B, N, D, _dp(vec), _dp(off), _dp(logz), _stream()))
     return vec, off, logz
 
@@ -248,8 +262,8 @@ def fb_beta(g: Graph, emis, lengths, want_vectors: bool = True):
 def fb_posteriors(g: Graph, alpha, beta, lengths, B: int, N: int, want_state: bool = True, want_pdf: bool = True):
     """-> (state_post like alpha, pdf_post [B,N,D])."""
     torch = _torch()
-    state = torch.empty_like(alpha) if want_state else None
-    pdfp = torch.empty((B, N, g.D), dtype=torch.float32, device=alpha.device) if want_pdf else None
+    state = _new(tuple(alpha.shape), torch.float32, alpha.device) if want_state else None
+    pdfp = _new((B, N, g.D), torch.float32, alpha.device) if want_pdf else None
     _check(lib().fb_posteriors(g.handle, _dp(alpha), _dp(beta), _dp(lengths), B, N, g.D, _dp(state), _dp(pdfp), _stream()))
     return state, pdfp
 
@@ -264,9 +278,9 @@ def fb_viterbi(g: Graph, emis, lengths, ws=None):
     B, N, D = _dev_inputs(emis, lengths)
     need = int(lib().fb_viterbi_workspace_bytes(g.handle, B, N))
     if ws is None:
-        ws = torch.empty((need,), dtype=torch.uint8, device=emis.device)
-    score = torch.empty((B,), dtype=torch.float64, device=emis.device)
-    path = torch.empty((B, N), dtype=torch.int32, device=emis.device)
+        ws = _new((need,), torch.uint8, emis.device)
+    score = _new((B,), torch.float64, emis.device)
+    path = _new((B, N), torch.int32, emis.device)
     _check(lib().fb_viterbi(g.handle, _dp(emis), _dp(lengths), B, N, D, _dp(score), _dp(path), _dp(ws), int(ws.numel()),
                             _stream()))
     return score, path
@@ -281,12 +295,12 @@ def lfmmi_loss_grad(den: Graph, num: Graph, emis, lengths, ws=None, grad=None, l
     B, N, D = _dev_inputs(emis, lengths)
     need = fb_lfmmi_workspace_bytes(den, num, B, N, D)
     if ws is None:
-        ws = torch.empty((need,), dtype=torch.uint8, device=emis.device)
+        ws = _new((need,), torch.uint8, emis.device)
     if grad is None:
-        grad = torch.empty((B, N, D), dtype=torch.float32, device=emis.device)
-    loss = torch.empty((1,), dtype=torch.float64, device=emis.device)
-    zn = torch.empty((B,), dtype=torch.float64, device=emis.device)
-    zd = torch.empty((B,), dtype=torch.float64, device=emis.device)
+        grad = _new((B, N, D), torch.float32, emis.device)
+    loss = _new((1,), torch.float64, emis.device)
+    zn = _new((B,), torch.float64, emis.device)
+    zd = _new((B,), torch.float64, emis.device)
     if lengths_host is not None:
         lh = np.ascontiguousarray(np.asarray(lengths_host), dtype=np.int32)
         if lh.shape != (B,):

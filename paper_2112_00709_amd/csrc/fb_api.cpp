@@ -157,17 +157,10 @@ int run_posteriors(const PostGraph *gs, int n_graph, const int32_t *lengths, int
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-double env_frac(const char *name, double dflt)   // (tuning aid: a fraction in (0, 1) from the environment)
-{
-    const char *s = getenv(name);
-    const double v = s ? atof(s) : 0.0;
-    return v > 0.0 && v < 1.0 ? v : dflt;
-}
-
 // First rank of length group i + 1 of B sequences in order of length (see lfmmi_loss_grad).
 int32_t group_cut(int32_t B, int i, bool fills_chip)
 {
-    static const double frac[3] = {env_frac("FB_AMD_CUT0", 0.25), env_frac("FB_AMD_CUT1", 0.50), env_frac("FB_AMD_CUT2", 0.97)};
+    static const double frac[3] = {0.25, 0.50, 0.97};
     // Workgroups of a launch go round the 8 XCDs of the chip by index, starting at the first, and inside an XCD
     // round its 4 shader engines; a workgroup waits for a compute unit of the engine it is sent to even while
     // others are free elsewhere.  The first two ranges therefore take multiples of 16 sequences (32 workgroups)

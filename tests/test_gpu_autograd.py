@@ -20,6 +20,7 @@ def fb():
     assert torch.cuda.is_available(), "these tests need the GPU"
     import paper_2112_00709_amd as lib
     lib.lib()
+    lib.POISON_NEW_BUFFERS = True   # outputs and workspaces start out as NaN
     return lib
 
 

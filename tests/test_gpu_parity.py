@@ -31,6 +31,7 @@ def fb():
     assert torch.cuda.is_available(), "these tests need the GPU"
     import paper_2112_00709_amd as lib
     lib.lib()                       # fails loudly if the HIP library is not built
+    lib.POISON_NEW_BUFFERS = True   # outputs and workspaces start out as NaN: nothing passes on stale memory
     return lib
 
 
@@ -125,15 +126,21 @@ def compare_fb(fb, g, D, emis, lengths, sel=None, name="", state="auto", post_to
     return out
 
 
-def compare_lfmmi(fb, w, sel=None, name="", ragged=False):
+def compare_lfmmi(fb, w, sel=None, name="", ragged=False, emis=None):
+    """emis: emissions to use in place of w.emis (calls that follow one another in a test take different ones, so
+    that what an earlier call left in recycled device memory is never the right answer of a later one)."""
     import torch
     B = w.B
+    emis = w.emis if emis is None else emis
     sel = list(range(B)) if sel is None else list(sel)
     say(f"{name}: oracle LF-MMI on {len(sel)} of {B} sequences")
-    ref = oracle.lfmmi(w.den, w.num, w.emis, w.lengths, sel=sel)
+    ref = oracle.lfmmi(w.den, w.num, emis, w.lengths, sel=sel)
     say(f"{name}: lfmmi_loss_grad B={B} N={w.N} D={w.D} Kden={w.den.K} Knum={w.num.K}")
     Gd, Gn = fb.graph_from(w.den, w.D), fb.graph_from(w.num, w.D)
-    loss, zn, zd, grad = fb.lfmmi_loss_grad(Gd, Gn, dev(w.emis), dev(w.lengths.astype(np.int32)),
+    # workspace and gradient handed in, every byte set: NaN wherever the call does not write
+    ws = torch.full((fb.fb_lfmmi_workspace_bytes(Gd, Gn, B, w.N, w.D),), 255, dtype=torch.uint8, device="cuda")
+    grad = torch.full((B, w.N, w.D), float("nan"), dtype=torch.float32, device="cuda")
+    loss, zn, zd, grad = fb.lfmmi_loss_grad(Gd, Gn, dev(emis), dev(w.lengths.astype(np.int32)), ws=ws, grad=grad,
                                             lengths_host=w.lengths if ragged else None)
     torch.cuda.synchronize()
     loss, zn, zd = float(host(loss)[0]), host(zn), host(zd)
@@ -200,10 +207,15 @@ def test_config5_scaled(fb):
     compare_fb(fb, w.num, w.D, w.emis, w.lengths, name="config5-scaled numerator")
 
 
+def spread_by_length(lengths, n):
+    """n sequences spread evenly over the batch in order of length (the shortest and the longest included)."""
+    order = np.argsort(lengths, kind="stable")
+    return sorted(int(order[i]) for i in np.unique(np.linspace(0, len(order) - 1, n).round().astype(int)))
+
+
 def test_config4_full_size_sampled(fb):
     w = wl.config4()
-    order = np.argsort(w.lengths)
-    sel = [int(order[0]), int(order[len(order) // 2]), int(order[-1])]
+    sel = spread_by_length(w.lengths, 32)
     out = compare_fb(fb, w.den, w.D, w.emis, w.lengths, sel=sel, name="config4-full")
     for b in range(w.B):
         T = int(w.lengths[b])
@@ -213,12 +225,39 @@ def test_config4_full_size_sampled(fb):
     assert ok.all()                                                  # forward and backward agree on log Z
 
 
-def test_config5_full_size_sampled(fb):
+def test_config5_full_size_every_sequence(fb):
+    """Configuration 5 at full size, every one of the 128 sequences against the oracle, through both entry points;
+    the second call takes other emissions than the first, and both get a workspace and a gradient buffer full of NaN."""
     w = wl.config5()
-    order = np.argsort(w.lengths)
-    sel = [int(order[0]), int(order[len(order) // 3]), int(order[-1])]
-    compare_lfmmi(fb, w, sel=sel, name="config5-full")
-    compare_lfmmi(fb, w, sel=sel, name="config5-full, as bench.py launches it", ragged=True)
+    compare_lfmmi(fb, w, name="config5-full")
+    other = np.ascontiguousarray(w.emis[::-1])          # the same draws dealt to other sequences
+    compare_lfmmi(fb, w, name="config5-full, as bench.py launches it", ragged=True, emis=other)
+
+
+def test_lfmmi_large_denominator_ragged_every_rank(fb):
+    """A denominator large enough for the 16-wave recursion kernel and the specialised gradient kernel (K = 1500,
+    about 15k arcs) under a ragged batch of 64 (length groups, the counter-gated part of the longest range
+    included): every sequence against the oracle, through both entry points, on different emissions."""
+    w = wl.config5(K=1500, B=64, Lmin=3, Lmax=40, D=200)
+    assert w.den.E >= 4096 and w.lengths.mean() < 0.85 * w.lengths.max()
+    compare_lfmmi(fb, w, name="lfmmi, K=1500, B=64 ragged", ragged=True)
+    compare_lfmmi(fb, w, name="lfmmi, K=1500, B=64, plain entry point", emis=np.ascontiguousarray(w.emis[::-1]))
+    w = wl.config5(K=1500, B=80, Lmin=3, Lmax=40, D=200)
+    compare_lfmmi(fb, w, name="lfmmi, K=1500, B=80 ragged", ragged=True, emis=np.ascontiguousarray(-w.emis))
+
+
+def test_paper_shape_full_size_sampled(fb):
+    """The shape of the paper's benchmark (Analysis section; Table 1): a 3022-state denominator of about 51k arcs,
+    128 sequences of 700 frames, 84 outputs, numerator chains of 453 states.  16 sequences spread over the batch
+    against the oracle: fb_alpha / fb_beta / fb_posteriors, and the LF-MMI call in its schedule for equal lengths."""
+    w = wl.paper_shape_lfmmi()
+    sel = list(range(3, w.B, 8))
+    out = compare_fb(fb, w.den, w.D, w.emis, w.lengths, sel=sel, name="paper-shaped denominator")
+    np.testing.assert_allclose(out["rho"].sum(axis=2), 1.0, atol=5e-5)
+    del out
+    compare_lfmmi(fb, w, sel=sel, name="paper-shaped LF-MMI (equal lengths)", ragged=True,
+                  emis=np.ascontiguousarray(w.emis[::-1]))
+    compare_lfmmi(fb, w, sel=sel, name="paper-shaped LF-MMI, plain entry point", emis=np.ascontiguousarray(-w.emis))
 
 
 def test_carrier_precision_can_be_forced(fb):

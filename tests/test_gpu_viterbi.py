@@ -18,6 +18,7 @@ def fb():
     assert torch.cuda.is_available(), "these tests need the GPU"
     import paper_2112_00709_amd as lib
     lib.lib()
+    lib.POISON_NEW_BUFFERS = True   # outputs and workspaces start out as NaN
     return lib
 
 
@@ -72,8 +73,9 @@ def test_viterbi_hub_graphs_with_clones(fb):
 
 def test_viterbi_config4_full_size_sampled(fb):
     w = wl.config4()
-    order = np.argsort(w.lengths)
-    check(fb, w.den, w.D, w.emis, w.lengths, "config4 full", sel=[int(order[0]), int(order[-1])])
+    order = np.argsort(w.lengths, kind="stable")
+    sel = sorted(int(order[i]) for i in np.unique(np.linspace(0, w.B - 1, 32).round().astype(int)))
+    check(fb, w.den, w.D, w.emis, w.lengths, "config4 full", sel=sel)
 
 
 def test_viterbi_edge_cases(fb):
