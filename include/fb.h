@@ -166,6 +166,10 @@ int fb_graph_layout(const fb_graph *g, int which, void *host_out, size_t bytes);
  *   which = 0  forward plan:  y[j] = (+)-sum over arcs entering j of (w (x) x[src]), log2 units
  *   which = 1  backward plan: y[i] = (+)-sum over arcs leaving i of (w (x) x[dst]), log2 units
  *   which = 2  pdf plan:      y[d] = sum of x over the states tied to pdf d (ordinary sum)
+ *   which = 5, 6  the forward / backward plan of the probability-domain kernel (fb_graph_linear_weights = 2, also
+ *              kept by host-only handles of graphs that qualify), in ordinary arithmetic:
+ *              y[j] = sum over arcs entering (leaving) j of e^logw x[src] - x and y are plain numbers here;
+ *              FB_EUNSUPPORTED if the graph has no such plan
  *   which = 3, 4  the forward / backward plan in the form with weights as 2^w (see
  *              fb_graph_linear_weights), whatever form the device copy has: same results to
  *              rounding; FB_EUNSUPPORTED if a weight of the graph is out of that form's range;
@@ -309,6 +313,18 @@ int32_t fb_limits_max_states(int32_t D, int shared);
  * FB_AMD_LINEAR=0 is in the environment); -1: g is NULL.  The results of the compute calls are
  * the same to rounding either way. */
 int fb_graph_linear_weights(const fb_graph *g);
+
+/* Diagnostic: how many (sequence, direction) runs the probability-domain recursion kernel has given up and
+ * redone in the log form since the library was loaded (see fb_graph_linear_weights: form 2).  Synchronises
+ * the device. */
+int64_t fb_debug_linear_restarts(void);
+
+/* Diagnostic, host only: the cycles the gathers of one time step of the probability-domain kernel take in the
+ * on-chip memory under the bank model its arc order is chosen by (32 banks of 4 bytes; a 64-lane gather is served
+ * as two halves, each in as many cycles as its busiest bank has distinct addresses), and the least any order could
+ * take (two cycles per gather).  backward: 0 the forward plan, 1 the backward plan.  FB_EUNSUPPORTED if the graph
+ * has no such plan. */
+int fb_graph_plan_cycles(const fb_graph *g, int backward, int64_t *cycles, int64_t *cycles_floor);
 
 /*
  * Stage timing of lfmmi_loss_grad, for benchmarks.  fb_profile_enable(1) creates

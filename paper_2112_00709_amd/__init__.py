@@ -28,7 +28,8 @@ LAYOUT = {"in_ptr": 0, "in_src": 1, "in_w": 2, "in_perm": 3, "out_ptr": 4, "out_
 SYMBOLS = ["fb_graph_create", "fb_graph_destroy", "fb_graph_layout_size", "fb_graph_layout", "fb_check_lengths",
            "fb_alpha", "fb_beta", "fb_posteriors", "fb_lfmmi_workspace_bytes", "lfmmi_loss_grad", "lfmmi_loss_grad_ragged",
            "fb_limits_max_states", "fb_strerror", "fb_last_error", "fb_graph_schedule_apply_host",
-           "fb_profile_enable", "fb_profile_read", "fb_viterbi_workspace_bytes", "fb_viterbi", "fb_graph_linear_weights"]
+           "fb_profile_enable", "fb_profile_read", "fb_viterbi_workspace_bytes", "fb_viterbi", "fb_graph_linear_weights",
+           "fb_debug_linear_restarts", "fb_graph_plan_cycles"]
 
 
 class FBError(RuntimeError):
@@ -77,6 +78,10 @@ def lib() -> ctypes.CDLL:
         L.lfmmi_loss_grad_ragged.restype = ctypes.c_int
         L.fb_graph_linear_weights.argtypes = [vp]
         L.fb_graph_linear_weights.restype = ctypes.c_int
+        L.fb_graph_plan_cycles.argtypes = [vp, ctypes.c_int, vp, vp]
+        L.fb_graph_plan_cycles.restype = ctypes.c_int
+        L.fb_debug_linear_restarts.argtypes = []
+        L.fb_debug_linear_restarts.restype = i64
         L.fb_limits_max_states.argtypes = [i32, ctypes.c_int]
         L.fb_limits_max_states.restype = i32
         L.fb_viterbi_workspace_bytes.argtypes = [vp, i32, i32]
@@ -187,9 +192,22 @@ def fb_profile_read() -> dict:
     return {"num_recursion": ms[0], "den_recursion": ms[1], "posteriors_grad": ms[2], "loss": ms[3]}
 
 
-def fb_graph_linear_weights(g: Graph) -> bool:
-    """Diagnostic: the graph's device plans carry weights as 2^w (the multiplying kernel instantiation)."""
-    return int(lib().fb_graph_linear_weights(g.handle)) == 1
+def fb_graph_linear_weights(g: Graph) -> int:
+    """Diagnostic: 0 the graph's recursions add weights in the exponent, 1 they multiply by 2^w, 2 they run in the
+    probability domain (and fall back to form 0 where a sequence leaves its range)."""
+    return int(lib().fb_graph_linear_weights(g.handle))
+
+
+def fb_graph_plan_cycles(g: Graph, backward: bool):
+    """Diagnostic: (modelled on-chip memory cycles of one time step's gathers, the floor of two per gather)."""
+    c, f = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().fb_graph_plan_cycles(g.handle, 1 if backward else 0, ctypes.byref(c), ctypes.byref(f)))
+    return int(c.value), int(f.value)
+
+
+def fb_debug_linear_restarts() -> int:
+    """Diagnostic: runs the probability-domain kernel has redone in the log form so far (synchronises)."""
+    return int(lib().fb_debug_linear_restarts())
 
 
 def fb_limits_max_states(D: int, shared: bool) -> int:

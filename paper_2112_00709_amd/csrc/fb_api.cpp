@@ -40,6 +40,7 @@ RecDir make_dir(const fb_graph *g, bool backward, void *out, bool out_carrier, f
     r.Ccap = backward ? g->h_bwd.Ccap : g->h_fwd.Ccap;
     r.backward = backward ? 1 : 0;
     r.fill_pad = fill_pad ? 1 : 0;
+    r.prob = backward ? g->pbwd : g->pfwd;
     return r;
 }
 
@@ -89,6 +90,13 @@ int run_recursion(const fb_graph *g, const float *emis, const int32_t *lengths, 
             p.xs_fixed = kXsFixed;
             lds = lds_fixed;
         }
+    }
+    // graphs that run in the probability domain were found to fit the fixed buffers when they were created
+    if (g->linear_p && !tropical) {
+        if (!p.xs_fixed) return fail(FB_EHIP, "internal error: probability-domain kernel without fixed buffers");
+        p.linear_p = 1;
+        p.used_pdf = g->used_pdf;
+        p.all_pdfs_used = g->all_pdfs_used ? 1 : 0;
     }
     // graphs whose streams carry weights as 2^w were found to fit the fixed buffers when they were created
     if (g->linear_w && !tropical) {
@@ -156,6 +164,30 @@ int run_posteriors(const PostGraph *gs, int n_graph, const int32_t *lengths, int
 }
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Whether every launch that reads the denominator's vectors in an LF-MMI call of this shape is one of the gradient
+// kernel (run_posteriors decides the same way): both graphs together, or the denominator alone.
+bool gradient_reads_denominator(const PostGraph *q, const int32_t *lengths, int32_t B, int32_t N, int32_t D, float *grad)
+{
+    const float dummy_f = 0.0f;
+    const double dummy_d = 0.0;
+    for (int n_graph = 1; n_graph <= 2; ++n_graph) {
+        PostParams p{};
+        p.cum_a = p.cum_b = &dummy_f;   // (only tested for presence)
+        p.logz = &dummy_d;
+        p.n_graph = n_graph;
+        for (int i = 0; i < n_graph; ++i) {
+            p.g[i] = q[i];
+            p.Kcap = std::max(p.Kcap, q[i].Kcap);
+        }
+        p.lengths = lengths;
+        p.B = B; p.N = N; p.D = D;
+        p.pdf_out = grad;
+        p.frames_per_block = 6;
+        if (!gradient_kernel_applies(p) || gradient_lds_bytes(p) > kLdsBytes) return false;
+    }
+    return true;
+}
 
 // First rank of length group i + 1 of B sequences in order of length (see lfmmi_loss_grad).
 int32_t group_cut(int32_t B, int i, bool fills_chip)
@@ -362,7 +394,8 @@ size_t fb_lfmmi_workspace_bytes(const fb_graph *den, const fb_graph *num, int32_
     const size_t num_vec = align256((size_t)N * num->K * (num->f64 ? 8 : 4));
     const size_t z = align256((size_t)B * sizeof(double));
     const size_t cum = align256((size_t)B * N * sizeof(float));   // running offsets of the denominator rows, per direction
-    return 2 * den_vec + 2 * num_vec + 2 * z + align256((size_t)B * sizeof(int32_t)) + 2 * cum + 256;   // + the sequences in order of length, a progress counter
+    // + the sequences in order of length, a progress counter, the form of every sequence's forward and backward rows
+    return 2 * den_vec + 2 * num_vec + 2 * z + align256((size_t)B * sizeof(int32_t)) + 2 * cum + 256 + 2 * align256((size_t)B * sizeof(int32_t));
 }
 
 // in_groups: run the batch as ranges of sequences by length; num_apart: the numerators' share of the gradient in a
@@ -395,7 +428,9 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
     int32_t *order = (int32_t *)w; w += align256((size_t)B * sizeof(int32_t));
     float *cum_a = (float *)w; w += align256((size_t)B * N * sizeof(float));
     float *cum_b = (float *)w; w += align256((size_t)B * N * sizeof(float));
-    uint32_t *done = (uint32_t *)w;
+    uint32_t *done = (uint32_t *)w; w += 256;
+    int32_t *fmt_a = (int32_t *)w; w += align256((size_t)B * sizeof(int32_t));
+    int32_t *fmt_b = (int32_t *)w;
 
     // Both recursions of a graph run side by side in one launch.  The denominator launch goes first on
     // the caller's stream; the (much smaller) numerator launch runs beside it on the library's side stream
@@ -415,6 +450,16 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
     PostGraph q[2] = {make_post(den, den_a, den_b, den->f64, 1.0f, -1.0f, nullptr),
                       make_post(num, num_a, num_b, num->f64, 1.0f, 1.0f, nullptr)};
     q[0].ld = (int32_t)lfmmi_den_ld(den);
+    // A denominator that runs in the probability domain leaves its vectors as they are kept (no logarithms on the
+    // way out) when it is the gradient kernel that reads them; which sequences' rows have that form (all but those
+    // that fell back to the log form) it says per sequence and direction.
+    if (den->linear_p && gradient_reads_denominator(q, lengths, B, N, D, grad)) {
+        dd[0].out_linear = dd[1].out_linear = 1;
+        dd[0].fmt = fmt_a;
+        dd[1].fmt = fmt_b;
+        q[0].fmt_a = fmt_a;
+        q[0].fmt_b = fmt_b;
+    }
 
     if (in_groups && side.groups_ok && B >= 8 * kGroups) {
         // Length groups.  A sequence's gradient needs only that sequence's vectors, and the sequences of a

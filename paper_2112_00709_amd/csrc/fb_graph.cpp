@@ -161,7 +161,21 @@ const char *fb_strerror(int code)
     }
 }
 
-int fb_graph_linear_weights(const fb_graph *g) { return g ? (g->linear_w ? 1 : 0) : -1; }
+int fb_graph_linear_weights(const fb_graph *g) { return g ? (g->linear_p ? 2 : g->linear_w ? 1 : 0) : -1; }
+
+int64_t fb_debug_linear_restarts(void) { return (int64_t)linear_restarts(); }
+
+int fb_graph_plan_cycles(const fb_graph *g, int backward, int64_t *cycles, int64_t *cycles_floor)
+{
+    if (!g || !cycles || !cycles_floor) return fail(FB_EINVAL, "fb_graph_plan_cycles: NULL argument");
+    if (!g->linear_p) return fail(FB_EUNSUPPORTED, "fb_graph_plan_cycles: this graph has no probability-domain plan");
+    const PStreamHost &S = backward ? g->hp_bwd : g->hp_fwd;
+    std::vector<double> x((size_t)S.K, 1.0), y((size_t)S.K, 0.0);
+    std::string why;
+    if (!pstream_apply_host(S, x.data(), y.data(), cycles, cycles_floor, why))
+        return fail(FB_EHIP, "internal error: probability-domain plan (" + why + ")");
+    return FB_OK;
+}
 
 int32_t fb_limits_max_states(int32_t D, int shared)
 {
@@ -258,6 +272,7 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
         SellHost sell_fwd, sell_bwd, sell_trop;   // sliced plans of the recursions, flattened into streams below
         sell_fwd.nw = sell_bwd.nw = sell_trop.nw = g->nw - 1;   // the last wave of a workgroup moves data, the others walk arcs
         bool any_parallel = false;
+        bool prob_ok = n_seq == 0;   // the plans of the probability-domain kernel could be built
 
         std::vector<int64_t> ptr;
         std::vector<int32_t> col, vid;
@@ -285,6 +300,15 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
                 std::vector<float> mw;
                 const bool dup = merge_parallel(Ks, ptr, col, w, false, mptr, mcol, mw);
                 sell_append(dir ? sell_bwd : sell_fwd, k0, Ks, mptr.data(), mcol.data(), mw.data(), vid.data());
+                // large shared graphs with float vectors: also the plan of the probability-domain kernel
+                if (prob_ok && g->nw == kNWShared && !g->f64 && D <= 64 * kWave - 4) {   // (one mask bit per pdf in 64 x 64 bits, the row and its end marker in 1024 pieces)
+                    std::string why;
+                    PStreamHost &ps = dir ? g->hp_bwd : g->hp_fwd;
+                    prob_ok = pstream_build(Ks, mptr.data(), mcol.data(), mw.data(), vid.data(), D, ps, why) &&
+                              pstream_in_bounds(ps, D, why);
+                } else {
+                    prob_ok = false;
+                }
                 if (dir == 0) {
                     any_parallel = any_parallel || dup;
                     merge_parallel(Ks, ptr, col, w, true, mptr, mcol, mw);
@@ -350,6 +374,19 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
                               recursion_fixed_available() && stream_linear_weights(g->h_fwd, lin_fwd) &&
                               stream_linear_weights(g->h_bwd, lin_bwd);
             }
+            // Large shared graphs with float vectors, at most 4096 pdfs and weights in range run their recursions in
+            // the probability domain (one multiply-add per arc, one exponential per row; see linear_run); the
+            // log form above stays on the device as what a sequence falls back to.
+            static const bool no_prob = getenv("FB_AMD_PROBABILITY") && getenv("FB_AMD_PROBABILITY")[0] == '0';   // (diagnostic switch)
+            if (rc == FB_OK && prob_ok && !no_prob && !g->host_only &&
+                g->max_sub_K + std::max(g->h_fwd.Ccap, g->h_bwd.Ccap) + 1 <= kXsFixed &&
+                std::max(recursion_lds_bytes(g->max_sub_K, g->h_bwd.Ccap, D, true, false, true, false, kXsFixed),
+                         probability_lds_bytes(D, true)) <= kLdsBytes &&
+                recursion_fixed_available()) {
+                g->linear_p = true;
+                g->linear_w = false;   // the log form it falls back to adds in the exponent
+            }
+            if (g->host_only && prob_ok) g->linear_p = true;   // (host-only handles keep the plans for fb_graph_schedule_apply_host)
             g->own_trop = any_parallel || g->linear_w;
             if (rc == FB_OK && g->own_trop) {
                 if (!sell_in_bounds(sell_trop, nv, why))
@@ -383,6 +420,30 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
             if (rc == FB_OK) {
                 if (g->own_trop) rc = upload_stream(g, g->h_trop, g->trop);
                 else g->trop = g->fwd;
+            }
+            if (rc == FB_OK && g->linear_p) {
+                std::vector<uint64_t> used((size_t)kWave, 0);   // bit 4 j + c of entry l: pdf 4 (64 j + l) + c is tied to a state
+                std::vector<char> seen((size_t)D, 0);
+                for (int32_t k = 0; k < K; ++k) {
+                    const int32_t q = pdf[k] / 4, c = pdf[k] % 4;
+                    used[(size_t)(q % kWave)] |= (uint64_t)1 << (4 * (q / kWave) + c);
+                    seen[(size_t)pdf[k]] = 1;
+                }
+                g->all_pdfs_used = std::count(seen.begin(), seen.end(), (char)1) == (ptrdiff_t)D;
+                auto up = [&](const PStreamHost &h, PStreamDev &d) {
+                    int r;
+                    if ((r = upload(g, h.waves, &d.waves)) || (r = upload(g, h.units, &d.units)) ||
+                        (r = upload(g, h.close_words, &d.close_words)) || (r = upload(g, h.clones, &d.clones)) ||
+                        (r = upload(g, h.zero_rows, &d.zero_rows)))
+                        return r;
+                    d.n_clones = (int32_t)h.clones.size();
+                    d.n_zero = (int32_t)h.zero_rows.size();
+                    d.Ccap = h.Ccap;
+                    d.bias = h.bias;
+                    d.dim = h.dim;
+                    return (int)FB_OK;
+                };
+                if (!(rc = up(g->hp_fwd, g->pfwd)) && !(rc = up(g->hp_bwd, g->pbwd))) rc = upload(g, used, &g->used_pdf);
             }
             g->d_pdf = const_cast<int32_t *>(dp); g->d_init2 = const_cast<float *>(di); g->d_final2 = const_cast<float *>(df);
         }
@@ -430,8 +491,15 @@ static const void *layout_array(const fb_graph *g, int which, int64_t *n)
 int fb_graph_schedule_apply_host(const fb_graph *g, int which, int32_t sub, const double *x, double *y)
 {
     if (!g || !x || !y) return fail(FB_EINVAL, "fb_graph_schedule_apply_host: NULL argument");
-    if (which < 0 || which > 4 || sub < 0 || (size_t)sub >= g->h_pdf.sub.size())
+    if (which < 0 || which > 6 || sub < 0 || (size_t)sub >= g->h_pdf.sub.size())
         return fail(FB_EINVAL, "fb_graph_schedule_apply_host: unknown schedule or sub-graph");
+    if (which >= 5) {   // the plans of the probability-domain kernel: ordinary arithmetic
+        if (!g->linear_p) return fail(FB_EUNSUPPORTED, "fb_graph_schedule_apply_host: this graph has no probability-domain plan");
+        std::string why;
+        if (!pstream_apply_host(which == 5 ? g->hp_fwd : g->hp_bwd, x, y, nullptr, nullptr, why))
+            return fail(FB_EHIP, "internal error: probability-domain plan (" + why + ")");
+        return FB_OK;
+    }
     if (which >= 3) {   // the forward / backward stream with weights as 2^w
         const StreamHost &S = which == 3 ? g->h_fwd : g->h_bwd;
         std::vector<Arc> lin;

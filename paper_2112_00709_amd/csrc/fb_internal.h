@@ -21,6 +21,7 @@ constexpr size_t kLdsReserve = 1024; // reduction slots etc.
 // instantiation whose LDS state buffers have this fixed length: buffer addresses are then compile-time
 // constants and a gather needs no address arithmetic.
 constexpr int kXsFixed = 6656;
+constexpr int kXbStride = 32768;     // probability-domain kernel: bytes between its two state buffers
 
 // One (src, weight) pair of a row of a sparse semiring matrix, as the kernels read it.
 struct Arc {
@@ -163,6 +164,63 @@ bool stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double
 // maximum.  False (out unspecified) if a finite weight lies outside [-kLinearSpan, kLinearSpan] (log2 units).
 constexpr float kLinearSpan = 64.0f;
 bool stream_linear_weights(const StreamHost &S, std::vector<Arc> &out);
+constexpr float kLinWeightSpan = 64.0f, kLinRowSumTop = 40.0f;   // log2 bounds on an arc weight for the probability-domain kernel
+
+// ---------------------------------------------------------------------------
+// Plan of the probability-domain recursion kernel (fb_pstream.cpp): per arc-walking wave a sequence of units (two
+// arcs per lane: three 32-bit words {source 0 | source 1 << 16, 2^w of arc 0, 2^w of arc 1}, sources = byte offsets
+// into the state buffer), some of which end a slice; per slice one close word per lane {target byte offset |
+// emission byte offset << 16}.
+// ---------------------------------------------------------------------------
+constexpr int kPChunk = 32;       // arcs one lane walks at most for a row (longer rows take more lanes)
+constexpr int kPResident = 22;    // units per wave and step that stay in registers
+constexpr int kPRing = 4;         // units of the streamed part in flight
+// A wave's units in the order it walks them: the first kPHead stay in registers, then come groups of three, two that
+// stay in registers and one that is re-read from L2 at every step (so the re-reading is spread over the step),
+// kPPatterned positions in all; what follows is all re-read.
+constexpr int kPHead = 2;
+constexpr int kPPatterned = kPHead + (kPResident - kPHead) / 2 * 3;
+constexpr int kPMaxClose = 8;     // slices per wave and step
+constexpr int kPMaxUnits = 128;   // units per wave and step
+
+struct PWaveDesc {
+    int64_t unit_base;            // first unit of the wave in `units` (units of 3 x 64 words)
+    int32_t n_units;              // its units per time step
+    int32_t n_close;              // its slices
+    int32_t cw_base;              // its close words: (cw_base + c) * 64 + lane
+    int32_t pad_;
+    uint64_t close_mask[kPMaxUnits / 64];   // bit u: unit u ends a slice
+    uint64_t lgs;                 // 3 bits per slice: log2 of the lanes its rows are spread over
+};
+
+struct PStreamHost {
+    int32_t K = 0, Ccap = 0;      // states, clone slots (the dump slot is K + Ccap)
+    int32_t bias = 0;             // log2 of the scale the kernel keeps its vector at (see linear_run)
+    float dim = 0.0f;             // the value below which an entry that is not zero makes a run give up
+    std::vector<PWaveDesc> waves; // kNWShared - 1
+    std::vector<uint32_t> units;
+    std::vector<uint32_t> close_words;
+    std::vector<CloneDesc> clones;
+    std::vector<int32_t> zero_rows;   // states without an arc of non-zero weight
+};
+
+struct PStreamDev {
+    const PWaveDesc *waves = nullptr;
+    const uint32_t *units = nullptr;
+    const uint32_t *close_words = nullptr;
+    const CloneDesc *clones = nullptr;
+    const int32_t *zero_rows = nullptr;
+    int32_t n_clones = 0, n_zero = 0, Ccap = 0, bias = 0;
+    float dim = 0.0f;
+};
+
+// rows [0, K) of a CSR-like matrix: entries ptr[r]..ptr[r+1], column col[], weight w[] (log2 units; -inf entries are
+// dropped); row_vidx[r] = emission index of row r, n_vidx = number of emission entries.  False, with the reason in
+// why, if the matrix does not fit the kernel (weights out of range, too many slices, ...).
+bool pstream_build(int32_t K, const int64_t *ptr, const int32_t *col, const float *w, const int32_t *row_vidx, int32_t n_vidx,
+                   PStreamHost &out, std::string &why);
+bool pstream_in_bounds(const PStreamHost &S, int32_t n_vidx, std::string &why);
+bool pstream_apply_host(const PStreamHost &S, const double *x, double *y, int64_t *cycles, int64_t *cycles_floor, std::string &why);
 
 // States grouped by pdf for the posterior accumulation: per (sub-)graph, one row per pdf it uses
 // (every pdf for a shared graph), listing the local ids of the states tied to it.  16-bit entries:
@@ -207,6 +265,11 @@ struct fb_graph {
     fb::StreamHost h_trop;            // forward schedule of the tropical semiring, when it differs (own_trop)
     bool own_trop = false;            // the graph has parallel arcs: they combine by max there, not by (+)
     bool linear_w = false;            // the device copies of fwd / bwd carry weights as 2^w (see stream_linear_weights)
+    bool linear_p = false;            // the recursions run in the probability domain (linear_run): the plans below exist
+    fb::PStreamHost hp_fwd, hp_bwd;   // its plans, host
+    fb::PStreamDev pfwd, pbwd;        // and device
+    const uint64_t *used_pdf = nullptr;   // device [64]: bit 4 j + c of entry l: pdf 4 (64 j + l) + c is tied to a state
+    bool all_pdfs_used = false;
     fb::PdfHost h_pdf;                // states grouped by pdf, for the posterior accumulation
     // device
     fb::StreamDev fwd, bwd, trop;     // trop = fwd unless own_trop
@@ -240,6 +303,10 @@ struct RecDir {
     uint16_t *bp;          // tropical semiring: back-pointers (see fb_viterbi in fb_api.cpp for the layout), else NULL
     int64_t bp_ld;         // elements per frame row of bp
     int32_t *last;         // tropical semiring: [B] local id of the best end state (-1: none)
+    PStreamDev prob;       // probability-domain kernel: its plan for this direction
+    int out_linear;        // ... out takes the vectors as they are kept (entry = 2^(log2 of the true value - cum)), not their logs
+    int32_t *fmt;          // ... [B], nullable: 1 if the sequence's rows in out are in that form, 0 if they are logs (the run
+                           //     fell back to the log form)
 };
 
 struct RecParams {
@@ -252,6 +319,9 @@ struct RecParams {
     int32_t Kcap, Ecap;
     int32_t xs_fixed;      // kXsFixed: launch the fixed-buffer instantiation; 0: buffers sized by the graph
     int32_t linear_w;      // the streams carry weights as 2^w (fixed-buffer instantiation only)
+    int32_t linear_p;      // launch the probability-domain kernel (dir[].prob, used_pdf)
+    const uint64_t *used_pdf;   // [64] bit 4 j + c of entry l: pdf 4 (64 j + l) + c is tied to a state of the (shared) graph
+    int32_t all_pdfs_used;      // every pdf is
     // A launch may cover a range of the sequences in order of length: order[r] = the sequence of rank r
     // (longest first, written by launch_order), ranks [rank0, rank0 + n_launch).  order == nullptr: all B.
     const int32_t *order;
@@ -273,6 +343,8 @@ struct PostGraph {
     int32_t Kcap, Rcap;    // largest (sub-)graph: states, pdf rows
     int32_t ld;            // shared graph: elements between the rows of consecutive frames of a, b (>= K)
     float *state_post;     // nullable
+    const int32_t *fmt_a, *fmt_b;   // gradient kernel, shared float graph: [B] each, nullable: 1 = the sequence's rows of a
+                           // (b) hold the values themselves, 2^(log2 of the true value - cum_a (cum_b)), 0 / NULL = their logs
 };
 
 struct PostParams {
@@ -294,6 +366,7 @@ struct PostParams {
 
 int launch_recursion(int nw, bool f64, bool tropical, const RecParams &p, size_t lds_bytes, void *stream);
 bool recursion_fixed_available();   // the fixed-buffer instantiation (RecParams::xs_fixed) may be launched
+unsigned int linear_restarts();     // diagnostic: runs the probability-domain kernel gave up and redid in the log form (synchronises)
 struct BacktraceParams {
     const uint16_t *bp;      // back-pointers written by the recursion kernel
     int64_t bp_ld;           // elements per frame row
@@ -320,5 +393,6 @@ int launch_loss(const double *logz_num, const double *logz_den, const int32_t *l
 size_t recursion_lds_bytes(int32_t Kcap, int32_t Ccap, int32_t Ecap, bool backward, bool f64, bool shared,
                            bool tropical = false, int32_t xs_fixed = 0);
 size_t posterior_lds_bytes(const PostParams &p);
+size_t probability_lds_bytes(int32_t D, bool backward);   // the probability-domain kernel's own use (its launch takes the larger of this and the log form's)
 
 }  // namespace fb

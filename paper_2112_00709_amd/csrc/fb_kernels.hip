@@ -26,6 +26,7 @@
 // stream_linear_weights for when a graph gets it.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <type_traits>
 #include <utility>
 
@@ -48,6 +49,12 @@ __device__ __forceinline__ float tmax(float a, float b)
 {
     float r;
     asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ float tmin(float a, float b)
+{
+    float r;
+    asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
     return r;
 }
 __device__ __forceinline__ float tmax3(float a, float b, float c)
@@ -228,30 +235,20 @@ __device__ __forceinline__ void unrolled(F &&f, std::integer_sequence<int, I...>
     (f(std::integral_constant<int, I>{}), ...);
 }
 
-template <int NW, class T, bool TROP, int XF, bool LINW = false>
-__global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P)
+// Workgroup -> (sequence, direction).  Workgroups start in the order of their index.  In the large-graph
+// kernels (one workgroup fills a compute unit) the longest sequences therefore come first, both
+// directions of a sequence side by side: whatever delays the start of a workgroup - a second wave of
+// workgroups when there are more than compute units, workgroups of another launch in the way - then
+// falls on the sequences that have time to spare.
+// (A launch may cover only a range of ranks, P.order then holds the sequences in order of length.)
+template <int NW>
+__device__ __forceinline__ void resolve_sequence(const RecParams &P, double *lds_raw, int &b, int &which)
 {
-    static_assert(!LINW || (!TROP && XF != 0), "weights as 2^w: log semifield, fixed buffers");
-    constexpr int NRES = kResident;
-    // The large-graph kernel is the critical path of a call; small-graph launches that run beside it on the same
-    // compute units (the numerators of an LF-MMI call) take the issue slots it leaves.  (The data-moving wave
-    // keeps this priority; the others vary theirs within a time step, see below.)
-    if (NW == kNWShared) __builtin_amdgcn_s_setprio(3);
-    extern __shared__ double lds_raw[];
-    constexpr int NT = NW * kWave, NC = NW - 1;
-    const T kNegInf = (T)(-INFINITY);
-    const int tid = threadIdx.x, lane = tid & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const bool io_wave = wave == NC;
-    // Workgroup -> (sequence, direction).  Workgroups start in the order of their index.  In the large-graph
-    // instantiation (one workgroup fills a compute unit) the longest sequences therefore come first, both
-    // directions of a sequence side by side: whatever delays the start of a workgroup - a second wave of
-    // workgroups when there are more than compute units, workgroups of another launch in the way - then
-    // falls on the sequences that have time to spare.
-    // (A launch may cover only a range of ranks, P.order then holds the sequences in order of length.)
+    constexpr int NT = NW * kWave;
+    const int tid = threadIdx.x;
     const int n_launch = P.order ? P.n_launch : P.B;
-    int b = blockIdx.x % n_launch;
-    int which = blockIdx.x / n_launch;
+    b = blockIdx.x % n_launch;
+    which = blockIdx.x / n_launch;
     if (NW == kNWShared || P.order) {   // in order of length: both directions of a sequence side by side
         which = blockIdx.x % P.n_dir;
         b = blockIdx.x / P.n_dir;
@@ -274,6 +271,33 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
         b = __builtin_amdgcn_readfirstlane(*sel);
         __syncthreads();   // the word is part of a state buffer from here on
     }
+}
+
+// Progress counter of a launch: everything this workgroup writes is on its way; make it visible device-wide, then count.
+__device__ __forceinline__ void count_done(const RecParams &P)
+{
+    if (P.done) {
+        const int rank = P.rank0 + (int)blockIdx.x / P.n_dir;   // (launches with counters cover ranks in order)
+        const int slot = (rank >= P.done_from[0] ? 1 : 0) + (rank >= P.done_from[1] ? 1 : 0) + (rank >= P.done_from[2] ? 1 : 0);
+        __syncthreads();
+        if (threadIdx.x == 0 && slot > 0) {
+            __threadfence();
+            atomicAdd(P.done + slot, 1u);
+        }
+    }
+}
+
+// One (sequence, direction) pair from its first frame to its last, by the whole workgroup.
+template <int NW, class T, bool TROP, int XF, bool LINW = false>
+__device__ __forceinline__ void recursion_run(const RecParams &P, const int b, const int which, double *lds_raw)
+{
+    static_assert(!LINW || (!TROP && XF != 0), "weights as 2^w: log semifield, fixed buffers");
+    constexpr int NRES = kResident;
+    constexpr int NT = NW * kWave, NC = NW - 1;
+    const T kNegInf = (T)(-INFINITY);
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool io_wave = wave == NC;
     const RecDir &R = P.dir[which];
     const StreamDev &S = R.sched;
     const bool bwd = R.backward != 0;
@@ -812,16 +836,578 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
             for (int f = Tn + tid; f < P.N; f += NT) off_seq[f] = 0.0f;
     }
 
-    // ---- progress counter: everything this workgroup writes is on its way; make it visible device-wide, then count
-    if (P.done) {
-        const int rank = P.rank0 + (int)blockIdx.x / P.n_dir;   // (launches with counters cover ranks in order)
-        const int slot = (rank >= P.done_from[0] ? 1 : 0) + (rank >= P.done_from[1] ? 1 : 0) + (rank >= P.done_from[2] ? 1 : 0);
+}
+
+// ---------------------------------------------------------------------------
+// The same recursions carried in the probability domain (the matrix products of Eq. 4-5, rescaled at every step;
+// the results handed out are those of Eq. 13-14).  For large shared graphs with float vectors.
+//
+// The vector in LDS holds P[k] = 2^(log2 of the true value - offset), the offset accumulated per sequence, so an
+// arc costs one LDS gather and one multiply-add (the plan carries 2^w) and a row one exponential (its emission)
+// instead of one exponential per arc.  At every step the vector is rescaled by the power of two that brings the
+// previous step's largest entry to [2^bias, 2^(bias + 1)) (exact), and the emissions of a frame enter relative to
+// the largest emission the graph uses in that frame.  bias is chosen per graph and direction so that no row sum
+// can overflow (from the largest sum of weights of a row).
+//
+// The plan (fb_pstream.cpp).  Each arc-walking wave has a list of units - two arcs per lane in three registers - most
+// of which stay in registers for the whole time loop (the rest cycles through a small ring fed from L2), a bit per
+// unit that says whether a slice of rows ends there, and a register per slice that says, per lane, where the
+// lane's sum goes and which emission it takes.  The order of the arcs in a lane and of the rows in a slice has been
+// chosen on the host so that the 32 lanes of half a wave gather from different banks.
+//
+// Range guard.  A float holds what lies within 2^-126 of the scale; the log form holds everything.  Whenever a
+// state that is not the semiring zero would come to lie below `dim` - the value under which its product with the
+// graph's smallest weight could be flushed to zero - or the step's largest entry falls too far for the next
+// rescaling to be a float, the workgroup gives the sequence up (returns false) and its caller runs it again from
+// the first frame in the log form.  Every sum a completed run has formed is therefore exact to rounding.  The
+// give-up travels through the step maximum the waves exchange anyway: a lane that sees such a state reports +inf
+// as its maximum.
+//
+// What leaves the kernel: the vectors as they are kept (RecDir::out_linear, for the gradient kernel) or, in the
+// form of the other kernel, normalised rows in log2 units (the data-moving wave takes the logarithms as it copies
+// a vector out); offsets and log Z as there.
+// LDS: xb, the previous / current vector, kXsFixed floats each at addresses 0 and kXbStride; bh 2 x kXsFixed behind
+// them (backward only: beta before the emission is applied); red 64 floats (0-2 step maxima, 4-6 the frames' emission maxima in log2 units, 7
+// scratch, 32-63 the last reduction); er 3 x Es floats, Es = D + 1 rounded up to 4: the emissions as given of the
+// frame in use and of the next two, entry D = -inf (what the dump slot "emits").
+// ---------------------------------------------------------------------------
+__device__ unsigned int g_linear_restarts;   // diagnostic: sequences (x directions) given up by linear_run since the library was loaded
+
+typedef uint32_t close_words_t __attribute__((ext_vector_type(kPMaxClose)));
+
+__device__ __forceinline__ bool linear_run(const RecParams &P, const int b, const int which, double *lds_raw)
+{
+    constexpr int NW = kNWShared, XF = kXsFixed, R = kPResident;
+    constexpr int NT = NW * kWave, NC = NW - 1;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool io_wave = wave == NC;
+    const RecDir &R_ = P.dir[which];
+    const PStreamDev &S = R_.prob;
+    const bool bwd = R_.backward != 0;
+    const int K = P.Kcap, nC = S.Ccap;
+    const int Tn = min(max(P.lengths[b], 0), P.N);
+    const int nE = P.D;
+    const int nX = K + nC + 1;                   // states, clone slots, dump slot
+    // the two buffers of the vector in use lie kXbStride bytes apart, further than a buffer is long and a power of two:
+    // an arc's source (an offset into a buffer) and the buffer's address then combine by OR
+    constexpr int Xs = kXbStride / 4;
+    static_assert(kXbStride >= XF * 4 && (kXbStride & (kXbStride - 1)) == 0 && 2 * kXbStride <= 0x10000, "buffer stride");
+    const int Es = (P.D + 1 + 3) & ~3;
+    if (Tn <= 0) return false;                   // (nothing to run: the log form writes the empty results)
+
+    float *xb = (float *)lds_raw;
+    float *bh = xb + Xs + XF;                    // (backward only; its two buffers follow each other)
+    float *red = bwd ? bh + 2 * XF : bh;
+    float *er = red + 64;
+    float *emaxw = red + 4;
+
+    const float *em_seq = P.emis + (size_t)b * P.N * P.D;
+    const size_t out_ld = (size_t)(R_.out_ld ? R_.out_ld : K);
+    float *out_row0 = R_.out ? (float *)R_.out + (size_t)b * P.N * out_ld : nullptr;
+    float *off_seq = R_.off ? R_.off + (size_t)b * P.N : nullptr;
+    auto frame = [&](int i) { return bwd ? Tn - 1 - i : i; };
+    auto put_max = [&](int i, float wmax) {
+        wmax = wave_max(wmax);
+        if (lane == 0) __builtin_amdgcn_ds_fmaxf((__attribute__((address_space(3))) float *)(red + i % 3), wmax, 0, 0, false);
+    };
+    const int kLinBias = S.bias;
+    const float kLinDimP = S.dim;
+    const float unbias = __uint_as_float((uint32_t)(127 - kLinBias) << 23);   // 2^-bias
+    // a step maximum the run cannot go on from: a lane gave up (+inf), or the vector fell more than 126 binary orders
+    // in one step (its rescaling would not be a float)
+    const float mx_floor = __uint_as_float((uint32_t)max(kLinBias - 126 + 127, 1) << 23);
+    auto gives_up = [&](float mx) { return !(mx < INFINITY) || (mx > 0.0f && mx < mx_floor); };
+    // the power of two that brings mx (finite, 0 or >= mx_floor) to [2^bias, 2^(bias + 1)), and minus its log2
+    auto rescale = [&](float mx, float &sc, float &neg_log2_sc) {
+        const int ex = (int)((__float_as_uint(mx) >> 23) & 0xffu);
+        const bool live = mx > 0.0f;
+        sc = live ? __uint_as_float((uint32_t)(254 + kLinBias - ex) << 23) : 1.0f;
+        neg_log2_sc = live ? (float)(ex - 127 - kLinBias) : 0.0f;
+    };
+
+    // ---- duties of the data-moving wave
+    auto stage = [&](int f, float *dst) {
+        const float *row = em_seq + (size_t)f * P.D;
+        if ((P.D & 3) == 0 && ((uintptr_t)row & 15) == 0) {
+            for (int e0 = 0; e0 < nE; e0 += 4 * kWave)
+                if (e0 + 4 * lane < nE)
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(row + e0 + 4 * lane),
+                                                     (__attribute__((address_space(3))) void *)(dst + e0), 16, 0, 0);
+        } else {
+            for (int e0 = 0; e0 < nE; e0 += kWave)
+                if (e0 + lane < nE)
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(row + e0 + lane),
+                                                     (__attribute__((address_space(3))) void *)(dst + e0), 4, 0, 0);
+        }
+    };
+    auto staged_wait = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+    // the largest emission (log2 units) among the pdfs the graph uses, of a staged frame; 0 if it has none above
+    // zero-bar.  16 bytes per lane and read (the compute waves keep the LDS queue full: few, wide reads); bit 4 j + c of
+    // a lane's mask: pdf 4 (64 j + lane) + c is used (what lies behind the row is never marked)
+    const uint64_t used = io_wave ? P.used_pdf[lane] : 0;
+    const uint32_t used_lo = (uint32_t)used, used_hi = (uint32_t)(used >> 32);
+    auto frame_emax = [&](const float *row) {
+        float m = -INFINITY;
+        const float4 *r4 = (const float4 *)row;
+        const int n4 = Es / 4;
+        constexpr int U = 8;
+        for (int j0 = 0; j0 * kWave < n4; j0 += U) {
+            float4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = r4[min((j0 + u) * kWave + lane, n4 - 1)];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                // an entry the graph does not use counts as -inf: all bits of `keep` are the entry's bit of the mask
+                const uint32_t word = 4 * (j0 + u) < 32 ? used_lo : used_hi;
+                const int at = (4 * (j0 + u)) & 31;
+                auto pick = [&](float x, int c) {
+                    const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe((int)word, (uint32_t)(at + c), 1u);
+                    return __uint_as_float((__float_as_uint(x) & keep) | (0xff800000u & ~keep));
+                };
+                m = tmax3(m, pick(v[u].x, 0), pick(v[u].y, 1));
+                m = tmax3(m, pick(v[u].z, 2), pick(v[u].w, 3));
+            }
+        }
+        m = wave_max(m) * (float)kLog2e;
+        return m > -INFINITY ? m : 0.0f;
+    };
+    // the same when the graph uses every pdf (what lies behind the row in the last 16 bytes is -inf or belongs to no pdf:
+    // the caller has set it to -inf)
+    auto frame_emax_all = [&](const float *row) {
+        float m = -INFINITY;
+        const float4 *r4 = (const float4 *)row;
+        const int n4 = Es / 4;
+        constexpr int U = 8;
+        for (int j0 = 0; j0 * kWave < n4; j0 += U) {
+            float4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = r4[min((j0 + u) * kWave + lane, n4 - 1)];
+#pragma unroll
+            for (int u = 0; u < U; ++u) m = tmax3(tmax3(m, v[u].x, v[u].y), v[u].z, v[u].w);
+        }
+        m = wave_max(m) * (float)kLog2e;
+        return m > -INFINITY ? m : 0.0f;
+    };
+    const bool all_used = P.all_pdfs_used != 0;
+    auto emax_of = [&](const float *row) { return all_used ? frame_emax_all(row) : frame_emax(row); };
+    const CloneDesc *cdesc = S.clones;
+    // a finished vector -> global memory, coalesced; a cloned state leaves as the sum of its clones.  Either as it is
+    // (RecDir::out_linear: the reader has the offsets and the scale) or as log2 of (entry x 2^-bias) x out_scale, the
+    // exponent and the mantissa taken apart first so that neither an entry far below the scale is lost nor the
+    // entries near it are rounded at the magnitude of the bias.
+    const bool out_lin = R_.out_linear != 0;
+    auto to_log = [&](float v) {
+        const float e = (float)(__builtin_amdgcn_frexp_expf(v) - kLinBias);   // (v = 0: -inf comes from the mantissa)
+        return (e + flog2(__builtin_amdgcn_frexp_mantf(v))) * R_.out_scale;
+    };
+    auto write_row = [&](int f, const float *srcv) {
+        if (!out_row0) return;
+        float *orow = out_row0 + (size_t)f * out_ld;
+        const float4 *s4 = (const float4 *)srcv;
+        const int n4 = (K + 3) / 4;
+        const bool vec = (out_ld & 3) == 0 && (size_t)(n4 * 4) <= out_ld && ((uintptr_t)orow & 15) == 0;
+        constexpr int U = 8;
+        for (int q0 = 0; q0 < n4; q0 += U * kWave) {
+            float4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = s4[min(q0 + u * kWave + lane, n4 - 1)];
+            if (!out_lin) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    v[u].x = to_log(v[u].x); v[u].y = to_log(v[u].y);
+                    v[u].z = to_log(v[u].z); v[u].w = to_log(v[u].w);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)   // every read and conversion stays in front of the stores
+                asm volatile("" : "+v"(v[u].x), "+v"(v[u].y), "+v"(v[u].z), "+v"(v[u].w));
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int q = q0 + u * kWave + lane;
+                if (q < n4) {
+                    if (vec) {   // (the row's padding may take up to 3 values that lie behind the states)
+                        ((float4 *)orow)[q] = v[u];
+                    } else {
+                        if (4 * q + 0 < K) orow[4 * q + 0] = v[u].x;
+                        if (4 * q + 1 < K) orow[4 * q + 1] = v[u].y;
+                        if (4 * q + 2 < K) orow[4 * q + 2] = v[u].z;
+                        if (4 * q + 3 < K) orow[4 * q + 3] = v[u].w;
+                    }
+                }
+            }
+        }
+        for (int j = lane; j < S.n_clones; j += kWave) {   // stores of one wave to one address keep their order
+            const CloneDesc cd = cdesc[j];
+            float t = srcv[cd.state];
+            for (int i = 0; i < cd.count; ++i) t += srcv[K + cd.first + i];
+            orow[cd.state] = out_lin ? t : to_log(t);
+        }
+    };
+    // what the readers of a row get beside it: log2 of the true row = log2 of the stored row + cum (in the linear
+    // form the stored row still carries the scale 2^bias)
+    const double cum_shift = out_lin ? (double)kLinBias : 0.0;
+
+    // ---- first frame of this direction: the start weights and the frame's emissions, relative to their maximum
+    if (tid < 12) er[(tid >> 2) * Es + Es - 4 + (tid & 3)] = -INFINITY;   // behind the rows (staging never writes there; the row's own last entries are rewritten)
+    __syncthreads();
+    if (tid < 3) er[tid * Es + P.D] = -INFINITY;   // what the dump slot "emits": its entry stays zero whatever the frame's scale
+    if (tid < 8) red[tid] = tid == 7 ? -INFINITY : 0.0f;
+    __syncthreads();
+    if (io_wave) {
+        stage(frame(0), er);
+        if (Tn > 1) stage(frame(1), er + Es);
+        staged_wait();
+        const float e0 = emax_of(er);
+        const float e1 = Tn > 1 ? emax_of(er + Es) : 0.0f;
+        if (lane == 0) { emaxw[0] = e0; emaxw[1] = e1; }
+        if (Tn > 2) stage(frame(2), er + 2 * Es);   // lands while step 1 runs
+    }
+    __syncthreads();
+    const float emx0 = emaxw[0];
+    {
+        float ymax = -INFINITY;
+        for (int k = tid; k < K; k += NT) ymax = tmax(ymax, R_.bound[k] + fmaf(er[P.pdf[k]], (float)kLog2e, -emx0));
+        ymax = wave_max(ymax);
+        if (lane == 0) __builtin_amdgcn_ds_fmaxf((__attribute__((address_space(3))) float *)(red + 7), ymax, 0, 0, false);
+    }
+    __syncthreads();
+    const float M0 = red[7];
+    const float base0 = M0 > -INFINITY ? M0 - (float)kLinBias : 0.0f;   // log2 of the first vector = log2 of its entries + base0 (+ the emission maximum)
+    float wmax = 0.0f;
+    for (int k = tid; k < K; k += NT) {
+        const float s = R_.bound[k];
+        const float y = s + fmaf(er[P.pdf[k]], (float)kLog2e, -emx0) - base0;
+        const float px = fexp2(y);
+        xb[k] = px;
+        if (bwd) bh[k] = fexp2(s - base0);
+        const bool dim = y > -INFINITY && px < kLinDimP;
+        wmax = dim ? INFINITY : tmax(wmax, px);
+    }
+    for (int k = tid; k < nC; k += NT) {   // clones start empty: the state itself holds the start weight
+        xb[K + k] = 0.0f;
+        if (bwd) bh[K + k] = 0.0f;
+    }
+    if (tid == 0) xb[nX - 1] = xb[Xs + nX - 1] = 0.0f;   // the dump slot holds zero in both buffers, always
+    put_max(0, wmax);
+    __syncthreads();
+
+    // offsets: log2 of the true row of step i = log2 of (the row in LDS x 2^-bias: what is written out) + sum_{j <= i} c_j,
+    // with c_0 = base0 + bias (+ the emission maximum of the frame, forward) and c_i = -log2(scale of step i) + the
+    // emission maximum of frame(i) (forward) or of frame(i - 1) (backward: the row sum of Eq. 14 is taken before the
+    // frame's own emission)
+    double csum = 0.0;
+    bool ok = true;
+    if (io_wave) {
+        float c = base0 + (float)kLinBias + (bwd ? 0.0f : emx0);
+        csum = (double)c;
+        if (lane == 0) {
+            if (off_seq) off_seq[frame(0)] = c * R_.out_scale;
+            if (R_.cum) R_.cum[(size_t)b * P.N + frame(0)] = (float)(csum - cum_shift);
+        }
+        for (int i = 1; i < Tn; ++i) {
+            const int cur = (i - 1) & 1;
+            const float mx = red[(i - 1) % 3];
+            if (gives_up(mx)) { ok = false; break; }
+            float sc, nls;
+            rescale(mx, sc, nls);
+            c = nls + emaxw[(bwd ? i - 1 : i) % 3];
+            csum += (double)c;
+            if (lane == 0) {
+                if (off_seq) off_seq[frame(i)] = c * R_.out_scale;
+                if (R_.cum) R_.cum[(size_t)b * P.N + frame(i)] = (float)(csum - cum_shift);
+            }
+            staged_wait();   // frame i+1, requested a whole step ago, is in LDS
+            if (i + 1 < Tn) {
+                const float en = emax_of(er + ((i + 1) % 3) * Es);
+                if (lane == 0) emaxw[(i + 1) % 3] = en;   // (the word of frame i - 2: read for the last time in step i - 1)
+            }
+            if (i + 2 < Tn) stage(frame(i + 2), er + ((i + 2) % 3) * Es);   // buffer of frame i-1: no longer read
+            write_row(frame(i - 1), bwd ? bh + cur * XF : xb + cur * Xs);
+            if (lane == 0) red[(i + 1) % 3] = 0.0f;   // the word of step i + 1 starts empty
+            __syncthreads();
+        }
+    } else {
+        const PWaveDesc wd = S.waves[wave];
+        const int n_units_w = __builtin_amdgcn_readfirstlane(wd.n_units);
+        auto uniform64 = [](uint64_t v) {
+            return (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v) |
+                   ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32)) << 32);
+        };
+        const uint64_t mask0_w = uniform64(wd.close_mask[0]), mask1_w = uniform64(wd.close_mask[1]), lgs_w = uniform64(wd.lgs);
+        struct Unit { uint32_t s; float w0, w1; };
+        // unit u of the wave: a wave-uniform base (three words per lane) plus the lane's 12 bytes
+        const uint32_t *const ubase = S.units + (size_t)uniform64((uint64_t)wd.unit_base) * (3 * kWave);
+        const uint32_t lane3 = (uint32_t)lane * 3u;
+        auto load_unit = [&](Unit &dst, const uint32_t *base) __attribute__((always_inline)) {
+            dst.s = base[lane3];
+            dst.w0 = __uint_as_float(base[lane3 + 1]);
+            dst.w1 = __uint_as_float(base[lane3 + 2]);
+        };
+        // The wave's units in walking order (see kPPatterned): which positions stay in registers, which are re-read.
+        // Re-read ("streamed") unit m of a step sits in ring[m % kPRing] and is asked for kPRing - 1 streamed units ahead
+        // of its use; the first kPRing - 1 of a step when the step before ends.  Every place that asks does so whatever
+        // the wave's unit count (for a unit that is not there, the last one again): the number of loads on their way
+        // at any point of the code is then a constant, which is what the waits on them are counted by.
+        constexpr int NP = kPPatterned, H = kPHead, NG = (R - H) / 2;   // patterned positions, head, groups
+        static_assert((R - H) % 2 == 0 && NP <= 64 && NP % 4 == 0, "groups of two resident units and a streamed one; close bits of the patterned part in one 64-bit word; blocks of 4");
+        const int n_s = n_units_w <= H ? 0 : n_units_w <= NP ? (n_units_w - H) / 3 : NG + (n_units_w - NP);   // streamed units per step
+        Unit res[R];   // (units behind the wave's last one are zero words or another wave's: never folded)
+        unrolled([&](auto qc) __attribute__((always_inline)) {
+            constexpr int q = decltype(qc)::value;
+            load_unit(res[q], ubase + (size_t)(q < H ? q : H + 3 * ((q - H) / 2) + (q - H) % 2) * (3 * kWave));
+        }, std::make_integer_sequence<int, R>{});
+        close_words_t cwv;
+        unrolled([&](auto cc) __attribute__((always_inline)) {
+            constexpr int c = decltype(cc)::value;
+            cwv[c] = S.close_words[((size_t)wd.cw_base + c) * kWave + lane];
+        }, std::make_integer_sequence<int, kPMaxClose>{});
+        Unit ring[kPRing];
+        // streamed unit m -> its ring place (in the patterned part streamed unit m is position H + 3 m + 2; behind it, unit
+        // NP + t is streamed unit NG + t)
+        // (the base the requests add to is made opaque at every step: an address formed at the place of the request is a
+        // scalar base plus the lane's offset, while addresses kept over the whole loop, as the compiler would have them,
+        // take a register pair each)
+        uint32_t ub_lo = (uint32_t)(uintptr_t)ubase, ub_hi = (uint32_t)((uintptr_t)ubase >> 32);
+        auto request = [&](Unit &dst, int m) __attribute__((always_inline)) {
+            m = max(min(m, n_s - 1), 0);
+            const int u = m < NG ? H + 3 * m + 2 : NP + (m - NG);
+            typedef const __attribute__((address_space(1))) uint32_t global_u32;   // (an address built from integers: say that it is global memory)
+            global_u32 *ub = (global_u32 *)((uintptr_t)ub_lo | ((uintptr_t)ub_hi << 32)) + (size_t)u * (3 * kWave);
+            dst.s = ub[lane3];
+            dst.w0 = __uint_as_float(ub[lane3 + 1]);
+            dst.w1 = __uint_as_float(ub[lane3 + 2]);
+            __builtin_amdgcn_sched_barrier(0);   // keep the issue order: waits count loads in order
+        };
+        unrolled([&](auto mc) __attribute__((always_inline)) {
+            constexpr int m = decltype(mc)::value;
+            request(ring[m], m);
+        }, std::make_integer_sequence<int, kPRing - 1>{});
+
+        auto step = [&](int i) __attribute__((always_inline)) -> bool {
+            const int cur = (i - 1) & 1, nxt = cur ^ 1;   // which buffer holds the previous step's vector
+            float *xn = xb + nxt * Xs;
+            float *bn = bh + nxt * XF;
+            const uint32_t gbase = (uint32_t)cur * (uint32_t)kXbStride;   // (uniform) address of the buffer the gathers read
+            const char *ern = (const char *)(er + (i % 3) * Es);
+            const float mx = red[(i - 1) % 3];
+            if (gives_up(mx)) return false;   // (the same word in every wave: all of them leave here)
+            float sc, nls;
+            rescale(mx, sc, nls);
+            const float emx = emaxw[i % 3];
+            wmax = 0.0f;
+            float wlow = INFINITY;   // the smallest entry this lane has written for a state that is not zero
+            float acc = 0.0f;
+            // the wave's constants, opaque at every step: what is derived from them is computed where it is used (a
+            // scalar instruction or two) instead of being kept in scalar registers that do not exist
+            uint32_t m_lo = (uint32_t)mask0_w, m_hi = (uint32_t)(mask0_w >> 32), m1_lo = (uint32_t)mask1_w, m1_hi = (uint32_t)(mask1_w >> 32);
+            uint32_t lg_lo = (uint32_t)lgs_w;
+            int n_units = n_units_w;
+            asm volatile("" : "+s"(m_lo), "+s"(m_hi), "+s"(m1_lo), "+s"(m1_hi), "+s"(lg_lo), "+s"(n_units), "+s"(ub_lo), "+s"(ub_hi));
+            int nclose = 0;   // slices closed so far in this step (uniform)
+            if (i <= 2)   // rows without arcs: zero from the second frame on, in both buffers
+                for (int z = tid; z < S.n_zero; z += NC * kWave) {
+                    const int k = S.zero_rows[z];
+                    xn[k] = 0.0f;
+                    if (bwd) bn[k] = 0.0f;
+                }
+            // the two values a unit gathers; sources are byte offsets, the workgroup's LDS starts at address 0
+            auto gather = [&](float2 &g, uint32_t s) __attribute__((always_inline)) {
+                typedef const __attribute__((address_space(3))) float lds_ct;
+                // one instruction per address: a half of the word, zero-extended, OR the buffer's address.  (In assembly
+                // also so that the addresses are formed at every step: left to itself the compiler keeps every resident
+                // unit's two addresses in registers of their own.)
+                uint32_t lo, hi;
+                asm volatile("v_or_b32_sdwa %0, %3, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n\t"
+                             "v_or_b32_sdwa %1, %3, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1"
+                             : "=&v"(lo), "=v"(hi) : "v"(s), "s"(gbase));
+                g.x = *(lds_ct *)(uintptr_t)lo;
+                g.y = *(lds_ct *)(uintptr_t)hi;
+            };
+            // a slice ends: the lanes of a row are added up, the row is rescaled, takes its emission, is stored.  The
+            // emission of the slice that ends next is asked for as soon as the one before it has ended, so that it has
+            // arrived when it is needed (LDS answers in order: asked for at the end, it would wait behind the gathers).
+            float e_next;
+            uint32_t cw_next;
+            auto ask_emission = [&]() __attribute__((always_inline)) {
+                cw_next = cwv[nclose];
+                e_next = *(const float *)(ern + (cw_next >> 16));
+            };
+            ask_emission();
+            auto close_slice = [&]() __attribute__((always_inline)) {
+                const int lg = (int)((lg_lo >> (3 * nclose)) & 7u);
+                const uint32_t cw = cw_next;
+                const float ep = fmaf(e_next, (float)kLog2e, -emx);   // log2 of the emission relative to the frame's best
+                ++nclose;
+                if (nclose < kPMaxClose) ask_emission();
+                for (int sft = 0; sft < lg; ++sft)   // the lanes of a row are neighbours: a butterfly over 2^lg lanes (few rows are that long)
+                    acc += __uint_as_float((uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ (1 << sft)) << 2, (int)__float_as_uint(acc)));
+                const float pb = acc * sc;
+                const float px = pb * fexp2(ep);
+                *(float *)((char *)xn + (cw & 0xffffu)) = px;
+                if (bwd) *(float *)((char *)bn + (cw & 0xffffu)) = pb;
+                wmax = tmax(wmax, px);
+                // (an emission too small for a float gives px = 0: that counts as an entry that is too small)
+                wlow = tmin(wlow, (acc > 0.0f && ep > -INFINITY) ? px : INFINITY);
+                acc = 0.0f;
+            };
+            // position u of the patterned part: which registers hold it
+            auto unit_at = [&](auto uc) __attribute__((always_inline)) -> Unit {
+                constexpr int u = decltype(uc)::value;
+                if constexpr (u < H) return res[u];
+                else if constexpr ((u - H) % 3 == 2) return ring[((u - H) / 3) % kPRing];
+                else return res[H + 2 * ((u - H) / 3) + (u - H) % 3];
+            };
+            // gathered values of the unit being folded and of the next GD: under load a gather takes a few hundred cycles
+            constexpr int GD = 3, NGB = GD + 1;
+            static_assert(kPRing % NGB == 0 && GD <= H + 1 && GD <= kPRing - 1, "buffer names repeat with the ring; the first gathers are of resident units");
+            float2 G[NGB];
+            unrolled([&](auto uc) __attribute__((always_inline)) {
+                constexpr int u = decltype(uc)::value;
+                gather(G[u], unit_at(std::integral_constant<int, u>{}).s);
+            }, std::make_integer_sequence<int, GD>{});
+            // Waves of equal priority are served oldest first, so with one fixed priority the younger waves of a SIMD
+            // would do most of their step alone after the older ones have finished theirs.  A wave's priority therefore
+            // falls as its step advances, and the younger half of the waves stays one level above the older half.
+            const bool young = wave >= NW / 2;
+            auto prio = [&](auto level) __attribute__((always_inline)) {   // level: a compile-time constant 1..2
+                if (young) __builtin_amdgcn_s_setprio(decltype(level)::value);
+                else __builtin_amdgcn_s_setprio(decltype(level)::value - 1);
+            };
+            prio(std::integral_constant<int, 2>{});
+            // (the units are in order, so nothing follows a unit that is not there; looked at every fourth position)
+            auto block = [&](auto self, auto kc) __attribute__((always_inline)) -> void {
+                constexpr int u0 = decltype(kc)::value * 4;
+                if constexpr (u0 < NP) {
+                    if (n_units > u0) {
+                        if constexpr (u0 == NP / 2) prio(std::integral_constant<int, 1>{});
+                        unrolled([&](auto jc) __attribute__((always_inline)) {
+                            constexpr int u = u0 + decltype(jc)::value;
+                            // a streamed unit: the place of the one before it in the ring is free, the unit kPRing - 1 further on goes there
+                            if constexpr (u >= H && (u - H) % 3 == 2) {
+                                constexpr int m = (u - H) / 3;
+                                request(ring[(m + kPRing - 1) % kPRing], m + kPRing - 1);
+                            }
+                            // (gathered whether the wave has that unit or not - its registers hold valid sources either way -
+                            // so that the number of gathers on their way is a constant too)
+                            if constexpr (u + GD < NP) gather(G[(u + GD) % NGB], unit_at(std::integral_constant<int, u + GD>{}).s);
+                            else gather(G[(u + GD) % NGB], ring[(NG + (u + GD - NP)) % kPRing].s);   // the first units behind the patterned part
+                            const Unit me = unit_at(std::integral_constant<int, u>{});
+                            acc = fmaf(G[u % NGB].x, me.w0, acc);
+                            acc = fmaf(G[u % NGB].y, me.w1, acc);
+                            if (((u < 32 ? m_lo : m_hi) >> (u & 31)) & 1u) close_slice();
+                        }, std::make_integer_sequence<int, 4>{});
+                        self(self, std::integral_constant<int, decltype(kc)::value + 1>{});
+                    }
+                }
+            };
+            block(block, std::integral_constant<int, 0>{});
+            // behind the patterned part: streamed units; unit NP + t is streamed unit NG + t; kPRing positions to a round,
+            // so that the names of the ring places and of the gather buffers repeat
+            static_assert(NP % NGB == 0 && NG % kPRing != -1, "rounds");
+            for (int t0 = 0; NP + t0 < n_units; t0 += kPRing) {
+#pragma unroll
+                for (int tt = 0; tt < kPRing; ++tt) {   // (a plain loop: closures inside a loop that stays a loop are not taken apart by the compiler)
+                    const int t = t0 + tt;
+                    if (NP + t < n_units) {
+                        const int mr = NG + tt;   // (t0 is a multiple of kPRing: only tt names the buffers)
+                        request(ring[(mr + kPRing - 1) % kPRing], NG + t + kPRing - 1);
+                        gather(G[(NP + tt + GD) % NGB], ring[(mr + GD) % kPRing].s);
+                        acc = fmaf(G[(NP + tt) % NGB].x, ring[mr % kPRing].w0, acc);
+                        acc = fmaf(G[(NP + tt) % NGB].y, ring[mr % kPRing].w1, acc);
+                        const int at = NP + t;
+                        const uint32_t word = at < 32 ? m_lo : at < 64 ? m_hi : at < 96 ? m1_lo : m1_hi;
+                        if ((word >> (at & 31)) & 1u) close_slice();
+                    }
+                }
+            }
+            // the first streamed units of the next step (every place of the ring is free now)
+            unrolled([&](auto mc) __attribute__((always_inline)) {
+                constexpr int m = decltype(mc)::value;
+                request(ring[m], m);
+            }, std::make_integer_sequence<int, kPRing - 1>{});
+            // an entry below the range: the run gives up (see above)
+            put_max(i, wlow < kLinDimP ? INFINITY : wmax);
+            __syncthreads();
+            return true;
+        };
+        for (int i = 1; i < Tn && ok; ++i) ok = step(i);
+    }
+    // a state below the range in the last step: give up as well (every wave reads the same word)
+    if (ok && !(red[(Tn - 1) % 3] < INFINITY)) ok = false;   // (the last vector is not rescaled: only a lane's give-up counts)
+    __builtin_amdgcn_s_setprio(3);
+    if (!ok) {
+        // every wave has left the time loop at the same step; nothing of this run may still be on its way to LDS or
+        // to the output rows when the log form starts over
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
         __syncthreads();
-        if (tid == 0 && slot > 0) {
-            __threadfence();
-            atomicAdd(P.done + slot, 1u);
+        if (tid == 0) atomicAdd(&g_linear_restarts, 1u);
+        return false;
+    }
+
+    // ---- last frame: write it out, close log Z with the end weights
+    const int last = (Tn - 1) & 1;
+    const float *xl = xb + last * Xs;
+    if (io_wave) write_row(frame(Tn - 1), bwd ? bh + last * XF : xl);
+    if (R_.logz) {
+        float m = kNegBig, s = 0.0f;
+        for (int k = tid; k < K; k += NT) lse_add(m, s, flog2(xl[k] * unbias) + R_.obound[k]);
+        for (int j = tid; j < S.n_clones; j += NT) {   // clones end with their state's weight
+            const CloneDesc cd = cdesc[j];
+            for (int i = 0; i < cd.count; ++i) lse_add(m, s, flog2(xl[K + cd.first + i] * unbias) + R_.obound[cd.state]);
+        }
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) lse_merge(m, s, __shfl_xor(m, o, 64), __shfl_xor(s, o, 64));
+        float *rm = red + 32, *rs = rm + NW;
+        const float em_last = emaxw[(Tn - 1) % 3];
+        if (lane == 0) { rm[wave] = m; rs[wave] = s; }
+        __syncthreads();
+        if (io_wave && lane == 0) {   // the lane that holds the sum of the offsets
+            m = rm[0]; s = rs[0];
+            for (int w = 1; w < NW; ++w) lse_merge(m, s, rm[w], rs[w]);
+            // backward: the vector of the last step still lacks the scale of its frame's emissions
+            R_.logz[b] = (csum + (bwd ? (double)em_last : 0.0) + (double)m + (double)flog2(s)) * kLn2;
         }
     }
+    // ---- padded frames
+    if (R_.fill_pad) {
+        if (out_row0)
+            for (int f = Tn; f < P.N; ++f) {
+                float *orow = out_row0 + (size_t)f * out_ld;
+                for (int k = tid; k < K; k += NT) orow[k] = -INFINITY;
+            }
+        if (off_seq)
+            for (int f = Tn + tid; f < P.N; f += NT) off_seq[f] = 0.0f;
+    }
+    if (R_.fmt && tid == 0) R_.fmt[b] = out_lin ? 1 : 0;   // which form this sequence's rows have
+    return true;
+}
+
+__global__ __launch_bounds__(kNWShared * 64) void fb_linear_kernel(const RecParams P)
+{
+    __builtin_amdgcn_s_setprio(3);
+    extern __shared__ double lds_raw[];
+    int b, which;
+    resolve_sequence<kNWShared>(P, lds_raw, b, which);
+    if (!linear_run(P, b, which, lds_raw)) {
+        recursion_run<kNWShared, float, false, kXsFixed, false>(P, b, which, lds_raw);
+        if (P.dir[which].fmt && threadIdx.x == 0) P.dir[which].fmt[b] = 0;   // this sequence's rows are in the log form
+    }
+    count_done(P);
+}
+
+template <int NW, class T, bool TROP, int XF, bool LINW = false>
+__global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P)
+{
+    // The large-graph kernel is the critical path of a call; small-graph launches that run beside it on the same
+    // compute units (the numerators of an LF-MMI call) take the issue slots it leaves.  (The data-moving wave
+    // keeps this priority; the others vary theirs within a time step.)
+    if (NW == kNWShared) __builtin_amdgcn_s_setprio(3);
+    extern __shared__ double lds_raw[];
+    int b, which;
+    resolve_sequence<NW>(P, lds_raw, b, which);
+    recursion_run<NW, T, TROP, XF, LINW>(P, b, which, lds_raw);
+    count_done(P);
 }
 
 // ---------------------------------------------------------------------------
@@ -1118,6 +1704,17 @@ __global__ __launch_bounds__(kGradThreads, 5) void fb_grad_kernel(const PostPara
         uint2 posr[U];                // places (4 x 16 bit) of the thread's states in pdf order
         uint32_t prange[kGradPdf];    // state ranges (begin | end << 16) of the thread's pdfs tid, tid + MT, ...
         const double z2 = P.logz ? P.logz[b] * kLog2e : 0.0;   // log2 Z of the shared graph
+        // the form of this sequence's rows: the values themselves (what the probability-domain recursion leaves), or logs
+        const bool lin_a = G0.fmt_a && G0.fmt_a[b] != 0, lin_b = G0.fmt_b && G0.fmt_b[b] != 0;
+        const bool any_lin = lin_a || lin_b;
+        const float in_scale0 = G0.in_scale;
+        auto as_value = [in_scale0](float v, bool lin) -> double {   // a row entry as a double: itself, or 2^(its log2)
+            if (lin) return (double)v;
+            const float x = v * in_scale0;
+            if (!(x > -1.0e30f)) return 0.0;
+            const float fl = floorf(x);
+            return ldexp((double)fexp2(x - fl), (int)fl);
+        };
         auto issue = [&](int n) {
             const float4 *ar = (const float4 *)((const float *)G0.a + ((size_t)b * P.N + n) * G0.ld);
             const float4 *br = (const float4 *)((const float *)G0.b + ((size_t)b * P.N + n) * G0.ld);
@@ -1147,14 +1744,27 @@ __global__ __launch_bounds__(kGradThreads, 5) void fb_grad_kernel(const PostPara
             const double shift_d = z2 - (double)ca - (double)cb;
             const bool mass = shift_d > -1.0e300 && shift_d < 1.0e300;
             const float shift = mass ? (float)shift_d : 0.0f;
+            // 2^-shift in double, for rows that hold values instead of logs (their range is a float's, times the offsets')
+            double pow_shift = 0.0;
+            if (any_lin && mass) {
+                const double t = fmin(fmax(-shift_d, -2000.0), 2000.0), ti = floor(t);
+                pow_shift = ldexp((double)fexp2((float)(t - ti)), (int)ti);
+            }
             float sum = 0.0f;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int q = u * MT + tid;
                 if (q * 4 < K0) {
                     float e[4];
-                    e[0] = fexp2((pa[u].x + pb[u].x) * G0.in_scale - shift); e[1] = fexp2((pa[u].y + pb[u].y) * G0.in_scale - shift);
-                    e[2] = fexp2((pa[u].z + pb[u].z) * G0.in_scale - shift); e[3] = fexp2((pa[u].w + pb[u].w) * G0.in_scale - shift);
+                    if (any_lin) {   // rows that hold the values themselves: the posterior is their product, formed in double
+                        e[0] = (float)(as_value(pa[u].x, lin_a) * as_value(pb[u].x, lin_b) * pow_shift);
+                        e[1] = (float)(as_value(pa[u].y, lin_a) * as_value(pb[u].y, lin_b) * pow_shift);
+                        e[2] = (float)(as_value(pa[u].z, lin_a) * as_value(pb[u].z, lin_b) * pow_shift);
+                        e[3] = (float)(as_value(pa[u].w, lin_a) * as_value(pb[u].w, lin_b) * pow_shift);
+                    } else {
+                        e[0] = fexp2((pa[u].x + pb[u].x) * G0.in_scale - shift); e[1] = fexp2((pa[u].y + pb[u].y) * G0.in_scale - shift);
+                        e[2] = fexp2((pa[u].z + pb[u].z) * G0.in_scale - shift); e[3] = fexp2((pa[u].w + pb[u].w) * G0.in_scale - shift);
+                    }
                     if (q * 4 + 3 >= K0) {   // the row's last piece when K0 is not a multiple of 4: padding counts as zero-bar
                         if (q * 4 + 1 >= K0) e[1] = 0.0f;
                         if (q * 4 + 2 >= K0) e[2] = 0.0f;
@@ -1418,10 +2028,13 @@ bool recursion_fixed_available()
     static const bool ok = [] {
         hipFuncAttributes attr{};
         hipFuncAttributes attr_lin{};
+        hipFuncAttributes attr_prob{};
         const hipError_t e = hipFuncGetAttributes(&attr, (const void *)fb_recursion_kernel<kNWShared, float, false, kXsFixed>);
         const hipError_t e_lin =
             hipFuncGetAttributes(&attr_lin, (const void *)fb_recursion_kernel<kNWShared, float, false, kXsFixed, true>);
-        return e == hipSuccess && attr.sharedSizeBytes == 0 && e_lin == hipSuccess && attr_lin.sharedSizeBytes == 0;
+        const hipError_t e_prob = hipFuncGetAttributes(&attr_prob, (const void *)fb_linear_kernel);
+        return e == hipSuccess && attr.sharedSizeBytes == 0 && e_lin == hipSuccess && attr_lin.sharedSizeBytes == 0 &&
+               e_prob == hipSuccess && attr_prob.sharedSizeBytes == 0;
     }();
     return ok;
 }
@@ -1430,6 +2043,15 @@ int launch_recursion(int nw, bool f64, bool tropical, const RecParams &p, size_t
 {
     if (p.xs_fixed) {   // fixed-length state buffers: large graphs with float vectors only
         if (p.xs_fixed != kXsFixed || nw != kNWShared || f64 || tropical) return fail(FB_EHIP, "internal error: fixed-buffer launch");
+        if (p.linear_p) {
+            if (!p.shared || !p.used_pdf || p.linear_w || p.D > 64 * kWave - 4) return fail(FB_EHIP, "internal error: probability-domain launch");
+            for (int i = 0; i < p.n_dir; ++i) {
+                if (!p.dir[i].prob.units) return fail(FB_EHIP, "internal error: probability-domain launch without its plan");
+                lds_bytes = std::max(lds_bytes, probability_lds_bytes(p.D, p.dir[i].backward != 0));
+            }
+            if (lds_bytes > kLdsBytes) return fail(FB_EHIP, "internal error: probability-domain launch beyond the on-chip memory");
+            return launch_rec(fb_linear_kernel, nw, p, lds_bytes, stream);
+        }
         if (p.linear_w) return launch_rec(fb_recursion_kernel<kNWShared, float, false, kXsFixed, true>, nw, p, lds_bytes, stream);
         return launch_rec(fb_recursion_kernel<kNWShared, float, false, kXsFixed>, nw, p, lds_bytes, stream);
     }
@@ -1446,6 +2068,18 @@ int launch_recursion(int nw, bool f64, bool tropical, const RecParams &p, size_t
                    : launch_rec(fb_recursion_kernel<kNWShared, float, false, 0>, nw, p, lds_bytes, stream);
     return f64 ? launch_rec(fb_recursion_kernel<kNWSmall, double, false, 0>, nw, p, lds_bytes, stream)
                : launch_rec(fb_recursion_kernel<kNWSmall, float, false, 0>, nw, p, lds_bytes, stream);
+}
+
+size_t probability_lds_bytes(int32_t D, bool backward)
+{
+    return (size_t)kXbStride + ((size_t)kXsFixed * (backward ? 3 : 1) + 64 + 3 * (((size_t)D + 1 + 3) & ~(size_t)3)) * 4;
+}
+
+unsigned int linear_restarts()
+{
+    unsigned int n = 0;
+    if (hipMemcpyFromSymbol(&n, HIP_SYMBOL(g_linear_restarts), sizeof(n)) != hipSuccess) return 0;
+    return n;
 }
 
 int launch_backtrace(const BacktraceParams &p, void *stream)
