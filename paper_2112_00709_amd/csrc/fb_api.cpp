@@ -95,8 +95,6 @@ int run_recursion(const fb_graph *g, const float *emis, const int32_t *lengths, 
     if (g->linear_p && !tropical) {
         if (!p.xs_fixed) return fail(FB_EHIP, "internal error: probability-domain kernel without fixed buffers");
         p.linear_p = 1;
-        p.used_pdf = g->used_pdf;
-        p.all_pdfs_used = g->all_pdfs_used ? 1 : 0;
     }
     // graphs whose streams carry weights as 2^w were found to fit the fixed buffers when they were created
     if (g->linear_w && !tropical) {

@@ -422,14 +422,6 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
                 else g->trop = g->fwd;
             }
             if (rc == FB_OK && g->linear_p) {
-                std::vector<uint64_t> used((size_t)kWave, 0);   // bit 4 j + c of entry l: pdf 4 (64 j + l) + c is tied to a state
-                std::vector<char> seen((size_t)D, 0);
-                for (int32_t k = 0; k < K; ++k) {
-                    const int32_t q = pdf[k] / 4, c = pdf[k] % 4;
-                    used[(size_t)(q % kWave)] |= (uint64_t)1 << (4 * (q / kWave) + c);
-                    seen[(size_t)pdf[k]] = 1;
-                }
-                g->all_pdfs_used = std::count(seen.begin(), seen.end(), (char)1) == (ptrdiff_t)D;
                 auto up = [&](const PStreamHost &h, PStreamDev &d) {
                     int r;
                     if ((r = upload(g, h.waves, &d.waves)) || (r = upload(g, h.units, &d.units)) ||
@@ -443,7 +435,7 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
                     d.dim = h.dim;
                     return (int)FB_OK;
                 };
-                if (!(rc = up(g->hp_fwd, g->pfwd)) && !(rc = up(g->hp_bwd, g->pbwd))) rc = upload(g, used, &g->used_pdf);
+                if (!(rc = up(g->hp_fwd, g->pfwd))) rc = up(g->hp_bwd, g->pbwd);
             }
             g->d_pdf = const_cast<int32_t *>(dp); g->d_init2 = const_cast<float *>(di); g->d_final2 = const_cast<float *>(df);
         }

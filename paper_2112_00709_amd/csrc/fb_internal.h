@@ -173,13 +173,44 @@ constexpr float kLinWeightSpan = 64.0f, kLinRowSumTop = 40.0f;   // log2 bounds 
 // emission byte offset << 16}.
 // ---------------------------------------------------------------------------
 constexpr int kPChunk = 32;       // arcs one lane walks at most for a row (longer rows take more lanes)
-constexpr int kPResident = 22;    // units per wave and step that stay in registers
+constexpr int kPResident = 20;    // units per wave and step that stay in registers
 constexpr int kPRing = 4;         // units of the streamed part in flight
-// A wave's units in the order it walks them: the first kPHead stay in registers, then come groups of three, two that
-// stay in registers and one that is re-read from L2 at every step (so the re-reading is spread over the step),
-// kPPatterned positions in all; what follows is all re-read.
-constexpr int kPHead = 2;
-constexpr int kPPatterned = kPHead + (kPResident - kPHead) / 2 * 3;
+// A wave's units in the order it walks them: of the first kPPatterned positions kPResident stay in registers and the
+// others are re-read from L2 at every step, spread evenly behind a head of kPHead that all stay (so that the re-reading
+// is spread over the step and each re-read unit can be asked for several positions ahead); what follows is all re-read.
+constexpr int kPHead = 4;
+constexpr int kPPatterned = 32;
+constexpr bool p_streamed(int u)   // position u < kPPatterned is re-read: three of every seven behind the head
+{
+    return u >= kPHead && ((u - kPHead) % 7 == 1 || (u - kPHead) % 7 == 4 || (u - kPHead) % 7 == 6);
+}
+constexpr int p_streamed_before(int u)   // re-read positions in front of position u <= kPPatterned
+{
+    int n = 0;
+    for (int i = 0; i < u; ++i) n += p_streamed(i) ? 1 : 0;
+    return n;
+}
+constexpr int p_streamed_pos(int m)   // position of the m-th re-read unit, m >= 0
+{
+    int n = 0;
+    for (int u = 0; u < kPPatterned; ++u)
+        if (p_streamed(u)) {
+            if (n == m) return u;
+            ++n;
+        }
+    return kPPatterned + (m - n);
+}
+constexpr int p_resident_pos(int q)   // position of the q-th unit that stays in registers, q < kPResident
+{
+    int n = 0;
+    for (int u = 0; u < kPPatterned; ++u)
+        if (!p_streamed(u)) {
+            if (n == q) return u;
+            ++n;
+        }
+    return -1;
+}
+static_assert(kPPatterned - p_streamed_before(kPPatterned) == kPResident, "the pattern keeps kPResident units");
 constexpr int kPMaxClose = 8;     // slices per wave and step
 constexpr int kPMaxUnits = 128;   // units per wave and step
 
@@ -268,8 +299,6 @@ struct fb_graph {
     bool linear_p = false;            // the recursions run in the probability domain (linear_run): the plans below exist
     fb::PStreamHost hp_fwd, hp_bwd;   // its plans, host
     fb::PStreamDev pfwd, pbwd;        // and device
-    const uint64_t *used_pdf = nullptr;   // device [64]: bit 4 j + c of entry l: pdf 4 (64 j + l) + c is tied to a state
-    bool all_pdfs_used = false;
     fb::PdfHost h_pdf;                // states grouped by pdf, for the posterior accumulation
     // device
     fb::StreamDev fwd, bwd, trop;     // trop = fwd unless own_trop
@@ -319,9 +348,7 @@ struct RecParams {
     int32_t Kcap, Ecap;
     int32_t xs_fixed;      // kXsFixed: launch the fixed-buffer instantiation; 0: buffers sized by the graph
     int32_t linear_w;      // the streams carry weights as 2^w (fixed-buffer instantiation only)
-    int32_t linear_p;      // launch the probability-domain kernel (dir[].prob, used_pdf)
-    const uint64_t *used_pdf;   // [64] bit 4 j + c of entry l: pdf 4 (64 j + l) + c is tied to a state of the (shared) graph
-    int32_t all_pdfs_used;      // every pdf is
+    int32_t linear_p;      // launch the probability-domain kernel (dir[].prob)
     // A launch may cover a range of the sequences in order of length: order[r] = the sequence of rank r
     // (longest first, written by launch_order), ranks [rank0, rank0 + n_launch).  order == nullptr: all B.
     const int32_t *order;

@@ -57,6 +57,12 @@ __device__ __forceinline__ float tmin(float a, float b)
     asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
     return r;
 }
+__device__ __forceinline__ float tmin3(float a, float b, float c)
+{
+    float r;
+    asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
 __device__ __forceinline__ float tmax3(float a, float b, float c)
 {
     float r;
@@ -873,7 +879,7 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
 // ---------------------------------------------------------------------------
 __device__ unsigned int g_linear_restarts;   // diagnostic: sequences (x directions) given up by linear_run since the library was loaded
 
-typedef uint32_t close_words_t __attribute__((ext_vector_type(kPMaxClose)));
+typedef uint32_t close_vector_t __attribute__((ext_vector_type(2 * kPMaxClose)));
 
 __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, const int which, double *lds_raw)
 {
@@ -901,6 +907,7 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
     float *red = bwd ? bh + 2 * XF : bh;
     float *er = red + 64;
     float *emaxw = red + 4;
+    float *espw = red + 8;                       // per frame: log2 of (smallest / largest) emission factor, less a margin
 
     const float *em_seq = P.emis + (size_t)b * P.N * P.D;
     const size_t out_ld = (size_t)(R_.out_ld ? R_.out_ld : K);
@@ -927,28 +934,32 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
     };
 
     // ---- duties of the data-moving wave
+    // a frame's emissions -> LDS, 16 bytes a lane where the row allows it; the lane's address is formed once and every
+    // piece but the last is loaded by all lanes
     auto stage = [&](int f, float *dst) {
         const float *row = em_seq + (size_t)f * P.D;
+        typedef const __attribute__((address_space(1))) void gvoid;
+        typedef __attribute__((address_space(3))) void lvoid;
         if ((P.D & 3) == 0 && ((uintptr_t)row & 15) == 0) {
-            for (int e0 = 0; e0 < nE; e0 += 4 * kWave)
-                if (e0 + 4 * lane < nE)
-                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(row + e0 + 4 * lane),
-                                                     (__attribute__((address_space(3))) void *)(dst + e0), 16, 0, 0);
+            const float *mine = row + 4 * lane;
+            int e0 = 0;
+            for (; e0 + 4 * kWave <= nE; e0 += 4 * kWave) __builtin_amdgcn_global_load_lds((gvoid *)(mine + e0), (lvoid *)(dst + e0), 16, 0, 0);
+            if (e0 + 4 * lane < nE) __builtin_amdgcn_global_load_lds((gvoid *)(mine + e0), (lvoid *)(dst + e0), 16, 0, 0);
         } else {
-            for (int e0 = 0; e0 < nE; e0 += kWave)
-                if (e0 + lane < nE)
-                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(row + e0 + lane),
-                                                     (__attribute__((address_space(3))) void *)(dst + e0), 4, 0, 0);
+            const float *mine = row + lane;
+            int e0 = 0;
+            for (; e0 + kWave <= nE; e0 += kWave) __builtin_amdgcn_global_load_lds((gvoid *)(mine + e0), (lvoid *)(dst + e0), 4, 0, 0);
+            if (e0 + lane < nE) __builtin_amdgcn_global_load_lds((gvoid *)(mine + e0), (lvoid *)(dst + e0), 4, 0, 0);
         }
     };
     auto staged_wait = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
-    // the largest emission (log2 units) among the pdfs the graph uses, of a staged frame; 0 if it has none above
-    // zero-bar.  16 bytes per lane and read (the compute waves keep the LDS queue full: few, wide reads); bit 4 j + c of
-    // a lane's mask: pdf 4 (64 j + lane) + c is used (what lies behind the row is never marked)
-    const uint64_t used = io_wave ? P.used_pdf[lane] : 0;
-    const uint32_t used_lo = (uint32_t)used, used_hi = (uint32_t)(used >> 32);
-    auto frame_emax = [&](const float *row) {
-        float m = -INFINITY;
+    // The largest emission of a staged frame, in log2 units (0 if there is none above zero-bar), and how far below it the
+    // smallest lies (rounded down by one; -inf if a pdf has probability zero).  Over all pdfs, whether a state of the graph
+    // is tied to them or not: any scale serves, and a bound that is too careful only makes a run give up early.  16 bytes
+    // per lane and read (the arc-walking waves keep the LDS queue full: few, wide reads).  The last group of four always
+    // holds an entry behind the row (-inf: staging never writes there), so there are n4 - 1 whole groups of pdfs.
+    auto emax_of = [&](const float *row, float &spread) {
+        float m = -INFINITY, mn = INFINITY;
         const float4 *r4 = (const float4 *)row;
         const int n4 = Es / 4;
         constexpr int U = 8;
@@ -958,39 +969,18 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
             for (int u = 0; u < U; ++u) v[u] = r4[min((j0 + u) * kWave + lane, n4 - 1)];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                // an entry the graph does not use counts as -inf: all bits of `keep` are the entry's bit of the mask
-                const uint32_t word = 4 * (j0 + u) < 32 ? used_lo : used_hi;
-                const int at = (4 * (j0 + u)) & 31;
-                auto pick = [&](float x, int c) {
-                    const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe((int)word, (uint32_t)(at + c), 1u);
-                    return __uint_as_float((__float_as_uint(x) & keep) | (0xff800000u & ~keep));
-                };
-                m = tmax3(m, pick(v[u].x, 0), pick(v[u].y, 1));
-                m = tmax3(m, pick(v[u].z, 2), pick(v[u].w, 3));
+                m = tmax3(tmax3(m, v[u].x, v[u].y), v[u].z, v[u].w);
+                const float c = tmin3(tmin3(mn, v[u].x, v[u].y), v[u].z, v[u].w);
+                mn = (j0 + u) * kWave + lane < n4 - 1 ? c : mn;
             }
         }
+        if (lane < (P.D & 3)) mn = tmin(mn, row[(P.D & ~3) + lane]);   // the pdfs of the last group
         m = wave_max(m) * (float)kLog2e;
-        return m > -INFINITY ? m : 0.0f;
+        mn = -wave_max(-mn);
+        const float em = m > -INFINITY ? m : 0.0f;
+        spread = mn < INFINITY ? fmaf(mn, (float)kLog2e, -em) - 1.0f : 0.0f;
+        return em;
     };
-    // the same when the graph uses every pdf (what lies behind the row in the last 16 bytes is -inf or belongs to no pdf:
-    // the caller has set it to -inf)
-    auto frame_emax_all = [&](const float *row) {
-        float m = -INFINITY;
-        const float4 *r4 = (const float4 *)row;
-        const int n4 = Es / 4;
-        constexpr int U = 8;
-        for (int j0 = 0; j0 * kWave < n4; j0 += U) {
-            float4 v[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) v[u] = r4[min((j0 + u) * kWave + lane, n4 - 1)];
-#pragma unroll
-            for (int u = 0; u < U; ++u) m = tmax3(tmax3(m, v[u].x, v[u].y), v[u].z, v[u].w);
-        }
-        m = wave_max(m) * (float)kLog2e;
-        return m > -INFINITY ? m : 0.0f;
-    };
-    const bool all_used = P.all_pdfs_used != 0;
-    auto emax_of = [&](const float *row) { return all_used ? frame_emax_all(row) : frame_emax(row); };
     const CloneDesc *cdesc = S.clones;
     // a finished vector -> global memory, coalesced; a cloned state leaves as the sum of its clones.  Either as it is
     // (RecDir::out_linear: the reader has the offsets and the scale) or as log2 of (entry x 2^-bias) x out_scale, the
@@ -1052,15 +1042,16 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
     if (tid < 12) er[(tid >> 2) * Es + Es - 4 + (tid & 3)] = -INFINITY;   // behind the rows (staging never writes there; the row's own last entries are rewritten)
     __syncthreads();
     if (tid < 3) er[tid * Es + P.D] = -INFINITY;   // what the dump slot "emits": its entry stays zero whatever the frame's scale
-    if (tid < 8) red[tid] = tid == 7 ? -INFINITY : 0.0f;
+    if (tid < 12) red[tid] = tid == 7 ? -INFINITY : 0.0f;
     __syncthreads();
     if (io_wave) {
         stage(frame(0), er);
         if (Tn > 1) stage(frame(1), er + Es);
         staged_wait();
-        const float e0 = emax_of(er);
-        const float e1 = Tn > 1 ? emax_of(er + Es) : 0.0f;
-        if (lane == 0) { emaxw[0] = e0; emaxw[1] = e1; }
+        float sp0 = 0.0f, sp1 = 0.0f;
+        const float e0 = emax_of(er, sp0);
+        const float e1 = Tn > 1 ? emax_of(er + Es, sp1) : 0.0f;
+        if (lane == 0) { emaxw[0] = e0; emaxw[1] = e1; espw[0] = sp0; espw[1] = sp1; }
         if (Tn > 2) stage(frame(2), er + 2 * Es);   // lands while step 1 runs
     }
     __syncthreads();
@@ -1119,8 +1110,9 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
             }
             staged_wait();   // frame i+1, requested a whole step ago, is in LDS
             if (i + 1 < Tn) {
-                const float en = emax_of(er + ((i + 1) % 3) * Es);
-                if (lane == 0) emaxw[(i + 1) % 3] = en;   // (the word of frame i - 2: read for the last time in step i - 1)
+                float sp;
+                const float en = emax_of(er + ((i + 1) % 3) * Es, sp);
+                if (lane == 0) { emaxw[(i + 1) % 3] = en; espw[(i + 1) % 3] = sp; }   // (the words of frame i - 2: read for the last time in step i - 1)
             }
             if (i + 2 < Tn) stage(frame(i + 2), er + ((i + 2) % 3) * Es);   // buffer of frame i-1: no longer read
             write_row(frame(i - 1), bwd ? bh + cur * XF : xb + cur * Xs);
@@ -1149,19 +1141,29 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
         // of its use; the first kPRing - 1 of a step when the step before ends.  Every place that asks does so whatever
         // the wave's unit count (for a unit that is not there, the last one again): the number of loads on their way
         // at any point of the code is then a constant, which is what the waits on them are counted by.
-        constexpr int NP = kPPatterned, H = kPHead, NG = (R - H) / 2;   // patterned positions, head, groups
-        static_assert((R - H) % 2 == 0 && NP <= 64 && NP % 4 == 0, "groups of two resident units and a streamed one; close bits of the patterned part in one 64-bit word; blocks of 4");
-        const int n_s = n_units_w <= H ? 0 : n_units_w <= NP ? (n_units_w - H) / 3 : NG + (n_units_w - NP);   // streamed units per step
+        constexpr int NP = kPPatterned, H = kPHead, NG = NP - R;   // patterned positions, head, re-read ones among them
+        static_assert(NP <= 64 && NP % 16 == 0 && NG >= kPRing - 1, "close bits of the patterned part in one 64-bit word; blocks of 4, a priority level for every quarter");
+        // the position of the wave's last re-read unit: what a request for a unit behind it asks for again (a wave
+        // without any asks for a unit behind its own: never folded, and the plan has room behind every wave)
+        int last_spos = p_streamed_pos(0);
+        unrolled([&](auto uc) __attribute__((always_inline)) {
+            constexpr int u = decltype(uc)::value;
+            if constexpr (p_streamed(u)) last_spos = u < n_units_w ? u : last_spos;
+        }, std::make_integer_sequence<int, NP>{});
+        if (n_units_w > NP) last_spos = n_units_w - 1;
         Unit res[R];   // (units behind the wave's last one are zero words or another wave's: never folded)
         unrolled([&](auto qc) __attribute__((always_inline)) {
             constexpr int q = decltype(qc)::value;
-            load_unit(res[q], ubase + (size_t)(q < H ? q : H + 3 * ((q - H) / 2) + (q - H) % 2) * (3 * kWave));
+            load_unit(res[q], ubase + (size_t)p_resident_pos(q) * (3 * kWave));
         }, std::make_integer_sequence<int, R>{});
-        close_words_t cwv;
-        unrolled([&](auto cc) __attribute__((always_inline)) {
-            constexpr int c = decltype(cc)::value;
-            cwv[c] = S.close_words[((size_t)wd.cw_base + c) * kWave + lane];
-        }, std::make_integer_sequence<int, kPMaxClose>{});
+        // The lane's close words and, behind them, the emission factors of the step in hand, both picked by the number
+        // of the close (uniform).  One vector of sixteen: picking from a vector of eight is compiled into a chain of seven
+        // selects, from a longer one into one indexed register move.
+        close_vector_t cwv;
+#pragma unroll
+        for (int c = 0; c < kPMaxClose; ++c) cwv[c] = S.close_words[((size_t)wd.cw_base + c) * kWave + lane];
+        // (everything asked for so far has arrived: the waits inside the loop then count the loop's own loads only)
+        __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
         Unit ring[kPRing];
         // streamed unit m -> its ring place (in the patterned part streamed unit m is position H + 3 m + 2; behind it, unit
         // NP + t is streamed unit NG + t)
@@ -1169,9 +1171,8 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
         // scalar base plus the lane's offset, while addresses kept over the whole loop, as the compiler would have them,
         // take a register pair each)
         uint32_t ub_lo = (uint32_t)(uintptr_t)ubase, ub_hi = (uint32_t)((uintptr_t)ubase >> 32);
-        auto request = [&](Unit &dst, int m) __attribute__((always_inline)) {
-            m = max(min(m, n_s - 1), 0);
-            const int u = m < NG ? H + 3 * m + 2 : NP + (m - NG);
+        auto request = [&](Unit &dst, int pos) __attribute__((always_inline)) {
+            const int u = min(pos, last_spos);
             typedef const __attribute__((address_space(1))) uint32_t global_u32;   // (an address built from integers: say that it is global memory)
             global_u32 *ub = (global_u32 *)((uintptr_t)ub_lo | ((uintptr_t)ub_hi << 32)) + (size_t)u * (3 * kWave);
             dst.s = ub[lane3];
@@ -1181,7 +1182,7 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
         };
         unrolled([&](auto mc) __attribute__((always_inline)) {
             constexpr int m = decltype(mc)::value;
-            request(ring[m], m);
+            request(ring[m], p_streamed_pos(m));
         }, std::make_integer_sequence<int, kPRing - 1>{});
 
         auto step = [&](int i) __attribute__((always_inline)) -> bool {
@@ -1196,14 +1197,16 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
             rescale(mx, sc, nls);
             const float emx = emaxw[i % 3];
             wmax = 0.0f;
-            float wlow = INFINITY;   // the smallest entry this lane has written for a state that is not zero
+            // the smallest row sum above zero this lane has seen, as its bit pattern less one (so that zero wraps to the
+            // largest key and the keys of positive floats keep their order)
+            uint32_t wlow = 0xffffffffu;
             float acc = 0.0f;
             // the wave's constants, opaque at every step: what is derived from them is computed where it is used (a
             // scalar instruction or two) instead of being kept in scalar registers that do not exist
             uint32_t m_lo = (uint32_t)mask0_w, m_hi = (uint32_t)(mask0_w >> 32), m1_lo = (uint32_t)mask1_w, m1_hi = (uint32_t)(mask1_w >> 32);
             uint32_t lg_lo = (uint32_t)lgs_w;
             int n_units = n_units_w;
-            asm volatile("" : "+s"(m_lo), "+s"(m_hi), "+s"(m1_lo), "+s"(m1_hi), "+s"(lg_lo), "+s"(n_units), "+s"(ub_lo), "+s"(ub_hi));
+            asm volatile("" : "+s"(m_lo), "+s"(m_hi), "+s"(m1_lo), "+s"(m1_hi), "+s"(lg_lo), "+s"(n_units), "+s"(ub_lo), "+s"(ub_hi), "+s"(last_spos));
             int nclose = 0;   // slices closed so far in this step (uniform)
             if (i <= 2)   // rows without arcs: zero from the second frame on, in both buffers
                 for (int z = tid; z < S.n_zero; z += NC * kWave) {
@@ -1227,40 +1230,38 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
             // a slice ends: the lanes of a row are added up, the row is rescaled, takes its emission, is stored.  The
             // emission of the slice that ends next is asked for as soon as the one before it has ended, so that it has
             // arrived when it is needed (LDS answers in order: asked for at the end, it would wait behind the gathers).
-            float e_next;
-            uint32_t cw_next;
-            auto ask_emission = [&]() __attribute__((always_inline)) {
-                cw_next = cwv[nclose];
-                e_next = *(const float *)(ern + (cw_next >> 16));
-            };
-            ask_emission();
+            // the emission factors of the wave's closes, relative to the frame's best: read and raised here, so that a
+            // close waits for nothing but its own arcs
+            typedef const __attribute__((address_space(3))) float lds_cf;
+            const uint32_t ern_a = (uint32_t)(uintptr_t)ern;
+#pragma unroll
+            for (int c = 0; c < kPMaxClose; ++c)
+                cwv[kPMaxClose + c] = __float_as_uint(fexp2(fmaf(*(lds_cf *)(uintptr_t)(ern_a + (cwv[c] >> 16)), (float)kLog2e, -emx)));
+            // a slice ends: the lanes of a row are added up, the row is rescaled, takes its emission, is stored
             auto close_slice = [&]() __attribute__((always_inline)) {
                 const int lg = (int)((lg_lo >> (3 * nclose)) & 7u);
-                const uint32_t cw = cw_next;
-                const float ep = fmaf(e_next, (float)kLog2e, -emx);   // log2 of the emission relative to the frame's best
+                const uint32_t tgt = cwv[nclose] & 0xffffu;
+                const float pe = __uint_as_float(cwv[kPMaxClose + nclose]);
                 ++nclose;
-                if (nclose < kPMaxClose) ask_emission();
                 for (int sft = 0; sft < lg; ++sft)   // the lanes of a row are neighbours: a butterfly over 2^lg lanes (few rows are that long)
                     acc += __uint_as_float((uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ (1 << sft)) << 2, (int)__float_as_uint(acc)));
                 const float pb = acc * sc;
-                const float px = pb * fexp2(ep);
-                *(float *)((char *)xn + (cw & 0xffffu)) = px;
-                if (bwd) *(float *)((char *)bn + (cw & 0xffffu)) = pb;
+                const float px = pb * pe;
+                *(float *)((char *)xn + tgt) = px;
+                if (bwd) *(float *)((char *)bn + tgt) = pb;
                 wmax = tmax(wmax, px);
-                // (an emission too small for a float gives px = 0: that counts as an entry that is too small)
-                wlow = tmin(wlow, (acc > 0.0f && ep > -INFINITY) ? px : INFINITY);
+                wlow = min(wlow, __float_as_uint(pb) - 1u);
                 acc = 0.0f;
             };
             // position u of the patterned part: which registers hold it
             auto unit_at = [&](auto uc) __attribute__((always_inline)) -> Unit {
                 constexpr int u = decltype(uc)::value;
-                if constexpr (u < H) return res[u];
-                else if constexpr ((u - H) % 3 == 2) return ring[((u - H) / 3) % kPRing];
-                else return res[H + 2 * ((u - H) / 3) + (u - H) % 3];
+                if constexpr (p_streamed(u)) return ring[p_streamed_before(u) % kPRing];
+                else return res[u - p_streamed_before(u)];
             };
             // gathered values of the unit being folded and of the next GD: under load a gather takes a few hundred cycles
             constexpr int GD = 3, NGB = GD + 1;
-            static_assert(kPRing % NGB == 0 && GD <= H + 1 && GD <= kPRing - 1, "buffer names repeat with the ring; the first gathers are of resident units");
+            static_assert(kPRing % NGB == 0 && NG % kPRing == 0 && GD <= H && GD <= kPRing - 1, "buffer names repeat with the ring; the first gathers are of resident units");
             float2 G[NGB];
             unrolled([&](auto uc) __attribute__((always_inline)) {
                 constexpr int u = decltype(uc)::value;
@@ -1268,25 +1269,20 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
             }, std::make_integer_sequence<int, GD>{});
             // Waves of equal priority are served oldest first, so with one fixed priority the younger waves of a SIMD
             // would do most of their step alone after the older ones have finished theirs.  A wave's priority therefore
-            // falls as its step advances, and the younger half of the waves stays one level above the older half.
-            const bool young = wave >= NW / 2;
-            auto prio = [&](auto level) __attribute__((always_inline)) {   // level: a compile-time constant 1..2
-                if (young) __builtin_amdgcn_s_setprio(decltype(level)::value);
-                else __builtin_amdgcn_s_setprio(decltype(level)::value - 1);
-            };
-            prio(std::integral_constant<int, 2>{});
+            // falls as its step advances, a level for every quarter: whoever has more left goes first.
+            __builtin_amdgcn_s_setprio(3);
             // (the units are in order, so nothing follows a unit that is not there; looked at every fourth position)
             auto block = [&](auto self, auto kc) __attribute__((always_inline)) -> void {
                 constexpr int u0 = decltype(kc)::value * 4;
                 if constexpr (u0 < NP) {
                     if (n_units > u0) {
-                        if constexpr (u0 == NP / 2) prio(std::integral_constant<int, 1>{});
+                        if constexpr (u0 % (NP / 4) == 0 && u0 > 0) __builtin_amdgcn_s_setprio(3 - u0 / (NP / 4));
                         unrolled([&](auto jc) __attribute__((always_inline)) {
                             constexpr int u = u0 + decltype(jc)::value;
                             // a streamed unit: the place of the one before it in the ring is free, the unit kPRing - 1 further on goes there
-                            if constexpr (u >= H && (u - H) % 3 == 2) {
-                                constexpr int m = (u - H) / 3;
-                                request(ring[(m + kPRing - 1) % kPRing], m + kPRing - 1);
+                            if constexpr (p_streamed(u)) {
+                                constexpr int m = p_streamed_before(u);
+                                request(ring[(m + kPRing - 1) % kPRing], p_streamed_pos(m + kPRing - 1));
                             }
                             // (gathered whether the wave has that unit or not - its registers hold valid sources either way -
                             // so that the number of gathers on their way is a constant too)
@@ -1311,7 +1307,7 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
                     const int t = t0 + tt;
                     if (NP + t < n_units) {
                         const int mr = NG + tt;   // (t0 is a multiple of kPRing: only tt names the buffers)
-                        request(ring[(mr + kPRing - 1) % kPRing], NG + t + kPRing - 1);
+                        request(ring[(mr + kPRing - 1) % kPRing], NP + t + kPRing - 1);
                         gather(G[(NP + tt + GD) % NGB], ring[(mr + GD) % kPRing].s);
                         acc = fmaf(G[(NP + tt) % NGB].x, ring[mr % kPRing].w0, acc);
                         acc = fmaf(G[(NP + tt) % NGB].y, ring[mr % kPRing].w1, acc);
@@ -1324,10 +1320,14 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
             // the first streamed units of the next step (every place of the ring is free now)
             unrolled([&](auto mc) __attribute__((always_inline)) {
                 constexpr int m = decltype(mc)::value;
-                request(ring[m], m);
+                request(ring[m], p_streamed_pos(m));
             }, std::make_integer_sequence<int, kPRing - 1>{});
-            // an entry below the range: the run gives up (see above)
-            put_max(i, wlow < kLinDimP ? INFINITY : wmax);
+            // An entry below the range: the run gives up (see above).  Judged by the smallest row sum and the frame's
+            // smallest emission factor together, which is at most the smallest entry: one test per lane and step instead
+            // of one per row, at the price of giving up a little early.  (A product too small for a float is zero or
+            // subnormal: below the range as well.)
+            const bool low = wlow != 0xffffffffu && __uint_as_float(wlow + 1u) * fexp2(espw[i % 3]) < kLinDimP;
+            put_max(i, low ? INFINITY : wmax);
             __syncthreads();
             return true;
         };
@@ -2044,7 +2044,7 @@ int launch_recursion(int nw, bool f64, bool tropical, const RecParams &p, size_t
     if (p.xs_fixed) {   // fixed-length state buffers: large graphs with float vectors only
         if (p.xs_fixed != kXsFixed || nw != kNWShared || f64 || tropical) return fail(FB_EHIP, "internal error: fixed-buffer launch");
         if (p.linear_p) {
-            if (!p.shared || !p.used_pdf || p.linear_w || p.D > 64 * kWave - 4) return fail(FB_EHIP, "internal error: probability-domain launch");
+            if (!p.shared || p.linear_w) return fail(FB_EHIP, "internal error: probability-domain launch");
             for (int i = 0; i < p.n_dir; ++i) {
                 if (!p.dir[i].prob.units) return fail(FB_EHIP, "internal error: probability-domain launch without its plan");
                 lds_bytes = std::max(lds_bytes, probability_lds_bytes(p.D, p.dir[i].backward != 0));

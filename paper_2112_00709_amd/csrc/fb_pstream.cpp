@@ -82,9 +82,86 @@ int half_cycles(const int32_t *addr, int n)
 
 // Lays out the arcs of one half of a slice.  lanes: for every lane of the half the arcs it has to walk (any order),
 // at most trip each.  Returns, per lane, the arcs in walking order, padded to trip with {-1, 0} entries (the caller
-// gives those an address that costs nothing).  Step by step, the banks that still have the most to serve are served
-// first; several lanes that read one address count once.
-void order_half(const std::vector<std::vector<std::pair<int32_t, float>>> &lanes, int trip,
+// gives those an address that costs nothing).  A gather is free of conflicts when its lanes read different banks, so
+// an order is an edge colouring of the bipartite multigraph lanes x banks (an arc = an edge from its lane to the bank
+// of its source, a colour = a step): with as many colours as the largest degree such a colouring always exists
+// (Koenig), and it is found edge by edge, an alternating path recoloured where the two ends have no free colour in
+// common.  A bank that serves more arcs than there are steps is split into as many nodes as it needs to bring every
+// node's degree down to the number of steps: then a step has at most that many arcs of the bank, which is the least
+// any order could do.
+void order_half_coloured(const std::vector<std::vector<std::pair<int32_t, float>>> &lanes, int trip,
+                         std::vector<std::vector<std::pair<int32_t, float>>> &out)
+{
+    const int nl = (int)lanes.size();
+    struct Edge { int lane, node, idx; };
+    std::vector<Edge> edges;
+    int bank_deg[kBanks] = {}, parts[kBanks], first_node[kBanks], seen[kBanks] = {};
+    for (int u = 0; u < nl; ++u)
+        for (const auto &a : lanes[u]) ++bank_deg[bank_of(a.first)];
+    int n_nodes = 0;
+    for (int bk = 0; bk < kBanks; ++bk) {
+        parts[bk] = std::max(1, (bank_deg[bk] + trip - 1) / trip);
+        first_node[bk] = n_nodes;
+        n_nodes += parts[bk];
+    }
+    for (int u = 0; u < nl; ++u)
+        for (int i = 0; i < (int)lanes[u].size(); ++i) {
+            const int bk = bank_of(lanes[u][i].first);
+            edges.push_back({u, first_node[bk] + seen[bk]++ / trip, i});   // (node after node filled: only the surplus shares a step)
+        }
+    // the arcs of the surplus nodes first: they take the lowest colours, so that the surplus of different banks meets in
+    // the same few steps instead of spoiling a step each
+    std::stable_sort(edges.begin(), edges.end(), [&](const Edge &x, const Edge &y) {
+        const bool sx = x.node != first_node[bank_of(lanes[(size_t)x.lane][(size_t)x.idx].first)];
+        const bool sy = y.node != first_node[bank_of(lanes[(size_t)y.lane][(size_t)y.idx].first)];
+        return sx && !sy;
+    });
+    const int n_col = trip;
+    std::vector<int> at_lane((size_t)nl * n_col, -1), at_node((size_t)n_nodes * n_col, -1), colour(edges.size(), -1);
+    auto free_at = [&](const std::vector<int> &tab, int v) {
+        for (int c = 0; c < n_col; ++c)
+            if (tab[(size_t)v * n_col + c] < 0) return c;
+        return -1;
+    };
+    for (int e = 0; e < (int)edges.size(); ++e) {
+        const int u = edges[e].lane, v = edges[e].node;
+        const int a = free_at(at_lane, u), b = free_at(at_node, v);   // (both exist: no degree is above n_col)
+        if (at_node[(size_t)v * n_col + a] >= 0) {
+            // a is taken at the bank: walk from the bank along colours a, b, a, ... and swap the two on that path (it
+            // cannot come back to lane u, which has no edge of colour a)
+            std::vector<int> path;
+            int x = v, c = a;
+            bool on_node = true;
+            for (;;) {
+                const int f = on_node ? at_node[(size_t)x * n_col + c] : at_lane[(size_t)x * n_col + c];
+                if (f < 0) break;
+                path.push_back(f);
+                x = on_node ? edges[f].lane : edges[f].node;
+                on_node = !on_node;
+                c = c == a ? b : a;
+            }
+            for (int f : path) {
+                at_lane[(size_t)edges[f].lane * n_col + colour[f]] = -1;
+                at_node[(size_t)edges[f].node * n_col + colour[f]] = -1;
+            }
+            for (int f : path) {
+                colour[f] = colour[f] == a ? b : a;
+                at_lane[(size_t)edges[f].lane * n_col + colour[f]] = f;
+                at_node[(size_t)edges[f].node * n_col + colour[f]] = f;
+            }
+        }
+        colour[e] = a;
+        at_lane[(size_t)u * n_col + a] = e;
+        at_node[(size_t)v * n_col + a] = e;
+    }
+    out.assign((size_t)nl, std::vector<std::pair<int32_t, float>>((size_t)trip, {-1, 0.0f}));
+    for (int e = 0; e < (int)edges.size(); ++e) out[(size_t)edges[e].lane][(size_t)colour[e]] = lanes[(size_t)edges[e].lane][(size_t)edges[e].idx];
+}
+
+// The same by a greedy rule: step by step, the banks that still have the most to serve are served first, and several
+// lanes that read one address count once (which the colouring does not know about: where many lanes read the same
+// states, this order is the better one).
+void order_half_greedy(const std::vector<std::vector<std::pair<int32_t, float>>> &lanes, int trip,
                 std::vector<std::vector<std::pair<int32_t, float>>> &out)
 {
     const int nl = (int)lanes.size();
@@ -139,6 +216,31 @@ void order_half(const std::vector<std::vector<std::pair<int32_t, float>>> &lanes
             }
         }
     }
+}
+
+// gather cycles of a laid-out half under the bank model (padding entries cost nothing)
+long laid_cycles(const std::vector<std::vector<std::pair<int32_t, float>>> &laid, int trip)
+{
+    long cyc = 0;
+    for (int t = 0; t < trip; ++t) {
+        int32_t addr[kHalf];
+        int n = 0;
+        for (const auto &l : laid)
+            if (l[(size_t)t].first >= 0) addr[n++] = l[(size_t)t].first;
+        cyc += half_cycles(addr, n);
+    }
+    return cyc;
+}
+
+// the better of the two orders
+void order_half(const std::vector<std::vector<std::pair<int32_t, float>>> &lanes, int trip,
+                std::vector<std::vector<std::pair<int32_t, float>>> &out)
+{
+    std::vector<std::vector<std::pair<int32_t, float>>> other;
+    order_half_coloured(lanes, trip, out);
+    if (laid_cycles(out, trip) == trip) return;   // (nothing to gain)
+    order_half_greedy(lanes, trip, other);
+    if (laid_cycles(other, trip) < laid_cycles(out, trip)) out.swap(other);
 }
 
 }  // namespace
@@ -245,7 +347,7 @@ bool pstream_build(int32_t K, const int64_t *ptr, const int32_t *col, const floa
         i += (size_t)count;
     }
 
-    // ---- trade rows between the halves of slices of equal shape until each half's arcs are spread evenly over the banks
+    // ---- trade rows between the halves of slices that both rows fit until each half's arcs are spread evenly over the banks
     // (one lane per row only: the rows of a slice of wider rows share their half anyway)
     {
         auto half_hist = [&](const PSlice &sl, int h, int *hist) {
@@ -266,25 +368,27 @@ bool pstream_build(int32_t K, const int64_t *ptr, const int32_t *col, const floa
         const int64_t tries = std::min<int64_t>(400000, 200 * (int64_t)items.size());
         for (int64_t it = 0; it < tries && halves.size() > 1; ++it) {
             const size_t a = (size_t)(next() % halves.size());
-            // a partner of the same trip: halves are in slice order, slices of equal trip are neighbours
+            // a partner nearby: halves are in slice order, slices of similar trips are neighbours
             const int span = 12;
             const size_t lo = a > (size_t)span ? a - span : 0, hi = std::min(halves.size() - 1, a + span);
             const size_t b2 = lo + (size_t)(next() % (hi - lo + 1));
             if (b2 == a) continue;
             PSlice &sa = slices[halves[a].first], &sb = slices[halves[b2].first];
-            if (sa.trip != sb.trip) continue;
             const int na = std::min<int>(kHalf, (int)sa.items.size() - halves[a].second * kHalf);
             const int nb = std::min<int>(kHalf, (int)sb.items.size() - halves[b2].second * kHalf);
             const int ia = halves[a].second * kHalf + (int)(next() % (uint64_t)na), ib = halves[b2].second * kHalf + (int)(next() % (uint64_t)nb);
             const PItem &ra = items[sa.items[ia]], &rb = items[sb.items[ib]];
-            // peaks before and after the swap
+            if ((int)ra.col.size() > sb.trip || (int)rb.col.size() > sa.trip) continue;   // each row must fit the other slice
+            // what the two halves cost before and after the swap: a half whose fullest bank serves no more arcs than
+            // the slice has steps can be walked without conflicts, the surplus is what counts
             std::vector<int> &ha = hist[a], &hb = hist[b2];
-            const int before = peak(ha.data()) + peak(hb.data());
+            auto cost = [&]() { return std::max(peak(ha.data()), sa.trip) + std::max(peak(hb.data()), sb.trip); };
+            const int before = cost();
             long sq_before = 0, sq_after = 0;
             for (int k = 0; k < kBanks; ++k) sq_before += (long)ha[k] * ha[k] + (long)hb[k] * hb[k];
             for (int32_t c : ra.col) { --ha[bank_of(c)]; ++hb[bank_of(c)]; }
             for (int32_t c : rb.col) { ++ha[bank_of(c)]; --hb[bank_of(c)]; }
-            const int after = peak(ha.data()) + peak(hb.data());
+            const int after = cost();
             for (int k = 0; k < kBanks; ++k) sq_after += (long)ha[k] * ha[k] + (long)hb[k] * hb[k];
             if (after < before || (after == before && sq_after < sq_before)) {
                 std::swap(sa.items[ia], sb.items[ib]);
