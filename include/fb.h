@@ -41,7 +41,8 @@
  * into a HIP graph by stream capture on `stream` (streams of the library's own
  * that a call uses are forked from and joined into `stream` with events; nothing
  * is cleared with a memset; the one step that cannot be recorded, a stream wait
- * on a value in lfmmi_loss_grad_ragged, is left out while `stream` is capturing).
+ * on a value in the LF-MMI calls, is replaced by waits on events while `stream` is
+ * capturing).
  *
  * Layouts (row-major, last index fastest):
  *   emis, pdf_post, grad   float [B][N][D]
@@ -233,11 +234,24 @@ size_t fb_lfmmi_workspace_bytes(const fb_graph *den, const fb_graph *num, int32_
  *   loss  out, device double [1]; logz_num, logz_den out, device double [B], nullable
  *   ws    device scratch of at least fb_lfmmi_workspace_bytes(), 256-byte aligned;
  *         its contents are undefined before and after the call
- * The numerator launch runs on a stream of the library's own that is forked from
- * `stream` and joined back into it with events before the gradient is formed, so
- * for the caller everything is ordered on `stream` as usual (FB_AMD_SERIAL=1 in the
- * environment keeps all launches on `stream`).  That stream and its two events belong to
- * the process: calls of lfmmi_loss_grad from several host threads must not overlap.
+ * Schedule.  For B >= 32 the batch is worked in order of length (the order is computed on
+ * the device from `lengths`; no host copy of the lengths is needed).  The denominator
+ * recursions of all sequences are one launch, longest sequences first; the ranks are cut
+ * into ranges, each with a progress counter its recursion workgroups increment when they
+ * are done, and every range has a gradient launch of its own, on the caller's stream and
+ * three of the library's, that waits for its counter (hipStreamWaitValue32) and runs on the
+ * compute units its sequences have left while the longest recursions are still going.  The
+ * numerator launch runs on one of those streams once the denominator workgroups hold their
+ * compute units.  Where the device cannot wait for a word, or while `stream` is being
+ * captured, every range has a denominator launch of its own instead and the waits are on
+ * events.  For B < 32 there is one launch per stage, the numerator launch on a stream of
+ * the library's beside the denominator launch.  The library's streams are forked from
+ * `stream` and joined back into it with events, so for the caller everything is ordered on
+ * `stream` as usual.  FB_AMD_SERIAL=1 in the environment keeps all launches on `stream`;
+ * FB_AMD_GROUPS=0 creates only one of the library's streams (with the caller's, the four
+ * take the hardware queues a process has) and so keeps to one launch per stage.  Those
+ * streams, their events and the stage timer belong to the process: LF-MMI calls from
+ * several host threads must not overlap.
  * FB_EINVAL: as fb_alpha, or ws too small / NULL, den packed, num shared.
  */
 int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths,
@@ -245,35 +259,22 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
                     float *grad, void *ws, size_t ws_bytes, fb_stream stream);
 
 /*
- * The same objective and derivative (Eq. 16-17), given a host copy of the lengths, from which
- * the library picks how the work of the call is scheduled:
+ * The same objective and derivative (Eq. 16-17), given a host copy of the lengths:
  *   lengths_host  host int32 [B], the values of `lengths`; used to decide how the work is
  *                 scheduled, never for the results (if it disagrees with `lengths` the call is
  *                 still correct, only possibly slower); NULL: exactly lfmmi_loss_grad
- * (a) Sequences that differ in length: when the shorter ones would leave more than 15 % of the
- * denominator recursion's compute-unit time idle (and B >= 32), the batch is cut into four ranges
- * of the sequences in order of length (the order is computed on the device from `lengths`);
- * every range has its own denominator and gradient launch on a stream of its own (the caller's
- * and three of the library's), and the gradient of the shorter ranges runs on the compute
- * units their sequences have left while the recursion of the longest range is still going
- * (for one range the numerators' share of the gradient is added by a launch of its own, as
- * in (b); the gradient of the shorter half of the longest range waits, with
- * hipStreamWaitValue32 where the device has it, for a counter that half's recursion
- * workgroups increment, not for the end of the launch).  Not used when FB_AMD_GROUPS=0 or
- * FB_AMD_SERIAL=1 is in the environment (the three streams are then not created: with the
- * caller's they take the four hardware queues a process has).
- * (b) Sequences of (nearly) equal length, a denominator graph large enough for the 16-wave
- * kernel and 2 B >= the number of compute units: no compute unit falls free before the
- * denominator recursion ends, so the numerator recursion cannot hide beside it.  The
- * denominator's share of the gradient is then formed while the numerator recursion runs (on
- * the library's side stream) and the numerators' share is added by a last small launch.
- * Not used when FB_AMD_SERIAL=1 is in the environment.
- * (c) Otherwise the call is lfmmi_loss_grad.
- * In every case the library's streams are forked from and joined back into `stream` with
- * events, so for the caller the call is ordered on `stream` as usual.  Same arguments,
- * workspace and errors as lfmmi_loss_grad, same loss and log Z bit for bit, the same
- * gradient to rounding (the launches of the schedules form the same sums in different
- * orders).  Calls from several host threads must not overlap.
+ * What the lengths decide: sequences that differ in length (the shorter ones would leave more
+ * than 15 % of the denominator recursion's compute-unit time idle) are scheduled as in
+ * lfmmi_loss_grad.  For sequences of (nearly) equal length, a denominator graph large enough
+ * for the 16-wave kernel and 2 B >= the number of compute units, no compute unit falls free
+ * before the denominator recursion ends: then there is one denominator launch, the
+ * denominator's share of the gradient is formed while the numerator recursion runs on the
+ * library's side stream, and the numerators' share is added by a last small launch - the same
+ * as lfmmi_loss_grad reaches with its counters, without them (so also under stream capture).
+ * Otherwise one launch per stage.  Same arguments, workspace and errors as lfmmi_loss_grad,
+ * same loss and log Z bit for bit, the same gradient to rounding (the launches of the
+ * schedules form the same sums in different orders).  Calls from several host threads must
+ * not overlap.
  */
 int lfmmi_loss_grad_ragged(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths,
                            const int32_t *lengths_host, int32_t B, int32_t N, int32_t D, double *loss,

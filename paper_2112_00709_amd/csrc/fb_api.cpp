@@ -52,11 +52,12 @@ struct RankRange {
 
 int run_recursion(const fb_graph *g, const float *emis, const int32_t *lengths, int32_t B, int32_t N, int32_t D,
                   const RecDir *dirs, int n_dir, fb_stream stream, bool tropical = false, RankRange range = RankRange(),
-                  uint32_t *done = nullptr, const int32_t *done_from = nullptr)
+                  uint32_t *done = nullptr, const int32_t *done_from = nullptr, bool count_started = false)
 {
     RecParams p{};
     p.done = done_from ? done : nullptr;
-    for (int i = 0; i < 3; ++i) p.done_from[i] = done_from ? done_from[i] : 0;
+    for (int i = 0; i < kDoneCuts; ++i) p.done_from[i] = done_from ? done_from[i] : 0;
+    p.started = (done && count_started) ? done + kDoneStarted : nullptr;
     p.order = range.order;
     p.rank0 = range.rank0;
     p.n_launch = range.count;
@@ -221,7 +222,7 @@ void mark(int i, hipStream_t stream)
 // also takes the numerator launch of a call too small for groups.  Setting FB_AMD_SERIAL=1 in the
 // environment keeps everything on the caller's stream.
 constexpr int kGroups = 4;
-constexpr int kRange0Parts = 2;   // at most 4: RecParams has three thresholds
+constexpr int kRange0Parts = 2;   // the longest range is cut once more (see lfmmi_run)
 struct SideStream {
     bool ok = false, tried = false;
     bool groups_ok = false;                     // the group streams exist (FB_AMD_GROUPS=0 in the environment: they do not)
@@ -459,18 +460,22 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
         q[0].fmt_b = fmt_b;
     }
 
-    if (in_groups && side.groups_ok && B >= 8 * kGroups) {
-        // Length groups.  A sequence's gradient needs only that sequence's vectors, and the sequences of a
-        // batch differ in length, so the compute units of the short ones would idle until the longest
-        // denominator recursion ends.  The batch is therefore cut into kGroups ranges of the sequences in
-        // order of length; every range has a denominator launch and a gradient launch of its own on a stream
-        // of its own, and the gradient of a range starts as soon as that range's recursions are done, on the
-        // compute units its sequences have left.  A denominator workgroup fills a compute unit (no other
-        // workgroup fits beside it), so none of this work shares a compute unit with the longest sequences,
-        // which set the time of the call.  The numerators of all sequences are one launch behind the
-        // denominator launch of the last range (a few very short sequences): launched at once it would take
-        // compute units before every denominator workgroup has one.  Range 0 (the longest sequences) runs on
-        // the caller's stream and is small: its gradient launch is all that is left when its recursion ends.
+    hipStreamCaptureStatus cap_state = hipStreamCaptureStatusNone;
+    const bool not_capturing = hipStreamIsCapturing(main_s, &cap_state) == hipSuccess && cap_state == hipStreamCaptureStatusNone;
+    if (in_groups && side.groups_ok && B >= 8 * kGroups && side.can_wait_value && not_capturing) {
+        // Length groups by progress counters.  A sequence's gradient needs only that sequence's vectors, and the
+        // sequences of a batch differ in length, so the compute units of the short ones would idle until the
+        // longest denominator recursion ends.  The denominator recursions of the whole batch are one launch with
+        // its workgroups in order of length, longest first; the batch is cut into kGroups ranges of ranks (the
+        // first once more in two), each with a progress counter that the recursion workgroups of the range
+        // increment when they are done, and every range has a gradient launch of its own that waits for its
+        // counter (a stream wait on the word) and then runs on the compute units its sequences have left.  Only
+        // the gradient of the very longest sequences waits for the launch itself and is all that is left when it
+        // ends.  Nothing here depends on the lengths themselves, only on ranks, which the device computes.
+        // A denominator workgroup fills a compute unit, so none of this work shares a compute unit with the
+        // longest sequences, which set the time of the call.  The numerators of all sequences are one launch that
+        // waits until the denominator workgroups hold their compute units (a word they add to when they begin):
+        // launched at once it would take compute units before every denominator workgroup has one.
         const bool fills = side.n_cu > 0 && 2 * (int64_t)B >= side.n_cu;
         const int32_t cut[kGroups + 1] = {0, group_cut(B, 0, fills), group_cut(B, 1, fills), group_cut(B, 2, fills), B};
         hipStream_t gs[kGroups] = {main_s, side.group[0], side.group[1], side.group[2]};
@@ -483,21 +488,72 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
         mark(1, main_s);
         // From here on the side streams hold work of this call: whatever happens, the caller's stream waits
         // for them before the call returns.
-        // Range 0 sets the end of the call: its gradient is the only work left when its recursion launch ends.
-        // Its sequences differ in length too, so it is cut once more, into kRange0Parts parts by rank, with a
-        // progress counter each that the recursion workgroups of the part increment when they are done; the
-        // gradient launches of the shorter parts wait for their counter (a stream wait on the word) on the last
-        // range's stream, which is idle by then, and run while the longest sequences are still going.  Only the
-        // gradient of part 0 waits for the launch itself.  (Measured: 2.94 instead of 3.03 ms per call with two
-        // parts; three or four parts give the same.)
-        // ranks [part_from[p], part_from[p + 1]); entries beyond n_part stay at B + 1 (never reached)
-        // (a stream wait on a value cannot be recorded into a graph: not while the caller's stream is being captured)
-        hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
-        const bool plain_stream = hipStreamIsCapturing(main_s, &capturing) == hipSuccess && capturing == hipStreamCaptureStatusNone;
-        const int n_part = (side.can_wait_value && plain_stream && cut[1] >= 4 * kRange0Parts) ? kRange0Parts : 1;
-        int32_t part_from[5] = {0, B + 1, B + 1, B + 1, B + 1};
-        for (int pt = 1; pt < n_part; ++pt) part_from[pt] = (int32_t)((int64_t)cut[1] * pt / n_part);
-        part_from[n_part] = cut[1];
+        const int32_t part1 = cut[1] >= 4 * kRange0Parts ? cut[1] / 2 : cut[1];   // the longest range, cut once more
+        const int32_t from[kDoneCuts] = {part1, cut[1], cut[2], cut[3]};
+        const int32_t upto[kDoneCuts] = {cut[1], cut[2], cut[3], B};
+        auto slot_range = [&](int slot) { return RankRange{order, from[slot - 1], upto[slot - 1] - from[slot - 1]}; };
+        auto wait_slot = [&](hipStream_t st, int slot) {   // every recursion workgroup (two per sequence) of the slot's ranks is done
+            const uint32_t n = 2u * (uint32_t)(upto[slot - 1] - from[slot - 1]);
+            return n == 0 || ok(hipStreamWaitValue32(st, done + slot, n, hipStreamWaitValueGte, 0xffffffffu));
+        };
+        auto stages = [&]() -> int {
+            int r;
+            if ((r = run_recursion(den, emis, lengths, B, N, D, dd, 2, main_s, false, RankRange{order, 0, B}, done, from, true))) return r;
+            mark(2, main_s);
+            hipStream_t ns = gs[kGroups - 1];
+            const uint32_t holding = side.n_cu > 0 ? (uint32_t)std::min<int64_t>(2 * (int64_t)B, side.n_cu) : 1u;
+            if (!ok(hipStreamWaitValue32(ns, done + kDoneStarted, holding, hipStreamWaitValueGte, 0xffffffffu)))
+                return fail(FB_EHIP, "lfmmi_loss_grad: stream wait on a value failed");
+            mark(5, ns);
+            if ((r = run_recursion(num, emis, lengths, B, N, D, dn, 2, ns, false, RankRange{order, 0, B}))) return r;
+            mark(6, ns);
+            if (!ok(hipEventRecord(side.num_done, ns))) return fail(FB_EHIP, "lfmmi_loss_grad: event record failed");
+            // the shortest range, on the numerators' stream
+            if (!wait_slot(ns, 4)) return fail(FB_EHIP, "lfmmi_loss_grad: stream wait on a value failed");
+            if ((r = run_posteriors(q, 2, lengths, B, N, D, grad, ns, slot_range(4), false, offs))) return r;
+            // The range before it: its recursions end before the numerator launch does (which only gets the compute
+            // units that finished sequences have left), so the denominator's share of its gradient does not wait for
+            // the numerators, whose share a small launch adds afterwards (as in the schedule for equal lengths below).
+            if (!wait_slot(gs[2], 3)) return fail(FB_EHIP, "lfmmi_loss_grad: stream wait on a value failed");
+            if ((r = run_posteriors(&q[0], 1, lengths, B, N, D, grad, gs[2], slot_range(3), false, offs))) return r;
+            if (!ok(hipStreamWaitEvent(gs[2], side.num_done, 0))) return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
+            if ((r = run_posteriors(&q[1], 1, lengths, B, N, D, grad, gs[2], slot_range(3), true))) return r;
+            // the longer ranges: the numerators are done long before them unless all lengths are (nearly) equal
+            if (!wait_slot(gs[1], 2) || !ok(hipStreamWaitEvent(gs[1], side.num_done, 0)))
+                return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
+            if ((r = run_posteriors(q, 2, lengths, B, N, D, grad, gs[1], slot_range(2), false, offs))) return r;
+            if (part1 < cut[1]) {
+                if (!wait_slot(ns, 1)) return fail(FB_EHIP, "lfmmi_loss_grad: stream wait on a value failed");
+                if ((r = run_posteriors(q, 2, lengths, B, N, D, grad, ns, slot_range(1), false, offs))) return r;
+            }
+            if (!ok(hipStreamWaitEvent(main_s, side.num_done, 0))) return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
+            return run_posteriors(q, 2, lengths, B, N, D, grad, main_s, RankRange{order, 0, part1}, false, offs);
+        };
+        rc = stages();
+        for (int g = 1; g < kGroups; ++g)
+            if ((!ok(hipEventRecord(side.group_done[g - 1], gs[g])) || !ok(hipStreamWaitEvent(main_s, side.group_done[g - 1], 0))) &&
+                rc == FB_OK)
+                rc = fail(FB_EHIP, "lfmmi_loss_grad: joining the group streams failed");
+        if (rc) return rc;
+        mark(3, main_s);
+    } else if (in_groups && side.groups_ok && B >= 8 * kGroups) {
+        // Length groups by launches: the same ranges where a stream cannot wait for a word, or while the caller's
+        // stream is being captured into a graph (such a wait cannot be recorded).  Every range has a denominator
+        // launch and a gradient launch of its own on a stream of its own, and the gradient of a range starts when
+        // that range's launch is done.  The numerators of all sequences are one launch behind the denominator launch
+        // of the last range (a few very short sequences).
+        const bool fills = side.n_cu > 0 && 2 * (int64_t)B >= side.n_cu;
+        const int32_t cut[kGroups + 1] = {0, group_cut(B, 0, fills), group_cut(B, 1, fills), group_cut(B, 2, fills), B};
+        hipStream_t gs[kGroups] = {main_s, side.group[0], side.group[1], side.group[2]};
+        auto ok = [](hipError_t e) { return e == hipSuccess; };
+        mark(0, main_s);
+        if ((rc = launch_order(lengths, B, N, order, done, main_s))) return rc;
+        if (!ok(hipEventRecord(side.fork, main_s))) return fail(FB_EHIP, "lfmmi_loss_grad: event record failed");
+        for (int g = 1; g < kGroups; ++g)
+            if (!ok(hipStreamWaitEvent(gs[g], side.fork, 0))) return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
+        mark(1, main_s);
+        // From here on the side streams hold work of this call: whatever happens, the caller's stream waits
+        // for them before the call returns.
         auto stages = [&]() -> int {
             int r;
             for (int g = 0; g < kGroups; ++g) {
@@ -507,10 +563,6 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
                 // would be dispatched at the same moment; an empty kernel in front of the others holds them
                 // back by a launch latency (measured: 0.1 ms per call).
                 if (g > 0 && (r = launch_delay(gs[g]))) return r;
-                if (g == 0 && n_part > 1) {
-                    if ((r = run_recursion(den, emis, lengths, B, N, D, dd, 2, gs[g], false, range, done, part_from + 1))) return r;
-                    continue;
-                }
                 if ((r = run_recursion(den, emis, lengths, B, N, D, dd, 2, gs[g], false, range))) return r;
             }
             mark(5, gs[kGroups - 1]);
@@ -532,17 +584,6 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
                 if (g < kGroups - 1 && !ok(hipStreamWaitEvent(gs[g], side.num_done, 0)))
                     return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
                 if (g == 0) mark(2, main_s);   // the longest sequences' recursions are done: the last gradient launch starts
-                if (g == 0 && n_part > 1) {
-                    hipStream_t s2 = gs[kGroups - 1];   // idle by now
-                    for (int pt = n_part - 1; pt >= 1; --pt) {   // the shorter parts first: they are done first
-                        const int32_t n_seq_pt = part_from[pt + 1] - part_from[pt];
-                        if (!ok(hipStreamWaitValue32(s2, done + pt, 2u * (uint32_t)n_seq_pt, hipStreamWaitValueGte, 0xffffffffu)))
-                            return fail(FB_EHIP, "lfmmi_loss_grad: stream wait on a value failed");
-                        if ((r = run_posteriors(q, 2, lengths, B, N, D, grad, s2, RankRange{order, part_from[pt], n_seq_pt}, false, offs))) return r;
-                    }
-                    if ((r = run_posteriors(q, 2, lengths, B, N, D, grad, gs[g], RankRange{order, 0, part_from[1]}, false, offs))) return r;
-                    continue;
-                }
                 if ((r = run_posteriors(q, 2, lengths, B, N, D, grad, gs[g], range, false, offs))) return r;
             }
             return FB_OK;
@@ -610,7 +651,9 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
                     int32_t N, int32_t D, double *loss, double *logz_num, double *logz_den, float *grad, void *ws,
                     size_t ws_bytes, fb_stream stream)
 {
-    return lfmmi_run(den, num, emis, lengths, B, N, D, loss, logz_num, logz_den, grad, ws, ws_bytes, stream, false, false);
+    // Without a host copy of the lengths nothing is known about them here; the schedule in length groups needs only
+    // ranks, which the device computes, and costs little when the lengths turn out to be equal.
+    return lfmmi_run(den, num, emis, lengths, B, N, D, loss, logz_num, logz_den, grad, ws, ws_bytes, stream, true, false);
 }
 
 int lfmmi_loss_grad_ragged(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths,

@@ -338,6 +338,9 @@ struct RecDir {
                            //     fell back to the log form)
 };
 
+constexpr int kDoneCuts = 4;       // progress counters of a recursion launch: kDoneCuts + 1 parts by rank, the first uncounted
+constexpr int kDoneStarted = 8;    // index of the `started` word in the counter block (which launch_order clears)
+
 struct RecParams {
     RecDir dir[2];
     int n_dir;
@@ -354,10 +357,12 @@ struct RecParams {
     const int32_t *order;
     int32_t rank0, n_launch;
     // Progress counters (nullptr: none): a workgroup that has written everything it writes adds one to done[i],
-    // i = how many of done_from[0..2] its rank (in order of length) has reached; i = 0 counts for nothing.
-    // A stream can wait for such a word (hipStreamWaitValue32) and so for part of a launch.
+    // i = how many of done_from[0..kDoneCuts-1] its rank (in order of length) has reached; i = 0 counts for nothing.
+    // A stream can wait for such a word (hipStreamWaitValue32) and so for part of a launch.  started (nullable):
+    // a word every workgroup adds one to when it begins, i.e. when it holds its compute unit.
     uint32_t *done;
-    int32_t done_from[3];
+    int32_t done_from[kDoneCuts];
+    uint32_t *started;
 };
 
 struct PostGraph {

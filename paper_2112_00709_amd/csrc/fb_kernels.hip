@@ -284,7 +284,9 @@ __device__ __forceinline__ void count_done(const RecParams &P)
 {
     if (P.done) {
         const int rank = P.rank0 + (int)blockIdx.x / P.n_dir;   // (launches with counters cover ranks in order)
-        const int slot = (rank >= P.done_from[0] ? 1 : 0) + (rank >= P.done_from[1] ? 1 : 0) + (rank >= P.done_from[2] ? 1 : 0);
+        int slot = 0;
+#pragma unroll
+        for (int i = 0; i < kDoneCuts; ++i) slot += rank >= P.done_from[i] ? 1 : 0;
         __syncthreads();
         if (threadIdx.x == 0 && slot > 0) {
             __threadfence();
@@ -1388,6 +1390,7 @@ __global__ __launch_bounds__(kNWShared * 64) void fb_linear_kernel(const RecPara
     __builtin_amdgcn_s_setprio(3);
     extern __shared__ double lds_raw[];
     int b, which;
+    if (P.started && threadIdx.x == 0) atomicAdd(P.started, 1u);   // this workgroup has its compute unit
     resolve_sequence<kNWShared>(P, lds_raw, b, which);
     if (!linear_run(P, b, which, lds_raw)) {
         recursion_run<kNWShared, float, false, kXsFixed, false>(P, b, which, lds_raw);
@@ -1405,6 +1408,7 @@ __global__ __launch_bounds__(NW * 64) void fb_recursion_kernel(const RecParams P
     if (NW == kNWShared) __builtin_amdgcn_s_setprio(3);
     extern __shared__ double lds_raw[];
     int b, which;
+    if (P.started && threadIdx.x == 0) atomicAdd(P.started, 1u);   // this workgroup has its compute unit
     resolve_sequence<NW>(P, lds_raw, b, which);
     recursion_run<NW, T, TROP, XF, LINW>(P, b, which, lds_raw);
     count_done(P);
@@ -1941,7 +1945,7 @@ __global__ __launch_bounds__(kWave) void fb_num_add_kernel(const PostParams P)
 __global__ __launch_bounds__(256) void fb_order_kernel(const int32_t *lengths, int32_t B, int32_t N, int32_t *order, uint32_t *done)
 {
     const int b = blockIdx.x * 256 + threadIdx.x;
-    if (done && b < 4) done[b] = 0u;   // the progress counters of the call start at zero
+    if (done && b <= kDoneStarted) done[b] = 0u;   // the progress counters of the call start at zero
     if (b >= B) return;
     const int lb = min(max(lengths[b], 0), N);
     int rank = 0;
