@@ -1,6 +1,6 @@
 """Benchmark of the LF-MMI hot path on one MI355X.
 
-A step is one lfmmi_loss_grad call on configuration 5 (the largest workload:
+A step is one lfmmi_loss_grad call (device lengths only) on configuration 5 (the largest workload:
 the 6000-state / ~60k-arc Zipf denominator graph shared by B=128 utterances,
 128 packed numerator chains, D=3000, N_b = round(3.6 L_b) frames): numerator
 and denominator alpha and beta recursions, log Z, state and pdf posteriors,
@@ -27,25 +27,41 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
-# plain (unpacked, non-fused) fp32 VALU issue rate: 256 CUs x 64 lanes x 2.4 GHz = 157.3 TFLOP/s / 4
-VALU_PEAK_PER_S = 256 * 64 * 2.4e9
 
-# HBM bytes per denominator-recursion launch on configuration 5 from rocprofv3 --pmc
-# (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on a plain copy kernel);
-# see profiles/.  None until measured for the workload being run.
-MEASURED_TRAFFIC_BYTES = {"config5": 532536 * 1024 * 2.00 + 2077684 * 1024 * 1.00}
+# LDS gather rate: 256 CUs x 128 bytes per clock x 2.4 GHz
+LDS_PEAK_GBS = 256 * 128 * 2.4
+# HBM bytes per denominator-recursion launch on configuration 5 from rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each
+# scaled by what the same counter reads for a plain copy of known size): written by
+# `python -m paper_2112_00709_amd.traffic_summary`, which names the kernel the figures belong to.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "lfmmi_config5_traffic.json")
+DOMINANT_KERNEL = "fb_linear_kernel"
+
+
+def measured_traffic(kernel: str):
+    """Bytes per launch from the committed counter summary; None when it is missing or names another kernel."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            t = json.load(f)
+    except (OSError, ValueError):
+        return None
+    if kernel not in t.get("kernel", ""):
+        return None
+    return float(t["traffic_bytes_per_launch"])
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def context_workloads(fb, wl, torch):
+def context_workloads(fb, wl, torch, everything=True):
     """fb_alpha + fb_beta + fb_posteriors (three calls, vectors through HBM) on the other workloads."""
     out = {}
     side = torch.cuda.Stream()   # one for all workloads: the box has few hardware queues to map streams onto
-    for name, make in (("config1", wl.config1), ("config2", wl.config2), ("config3", wl.config3),
-                       ("config4", wl.config4), ("paper_shape_den", wl.paper_shape_den)):
+    makers = (("config1", wl.config1), ("config2", wl.config2), ("config3", wl.config3),
+              ("config4", wl.config4), ("paper_shape_den", wl.paper_shape_den))
+    if not everything:
+        makers = makers[3:]
+    for name, make in makers:
         w = make()
         g = w.num if w.den is None else w.den
         t0 = time.time()
@@ -90,7 +106,7 @@ def context_workloads(fb, wl, torch):
             out[name]["paper_table1_s"] = 1.04
         log(f"[bench] {name}: {ms:.3f} ms, {upd / (ms * 1e-3):.3e} arc-updates/s, HBM fraction {out[name]['hbm_frac']:.3f}")
         G.destroy()
-        if name in ("config4", "paper_shape_den"):   # best path (tropical semiring) on the same inputs
+        if everything and name in ("config4", "paper_shape_den"):   # best path (tropical semiring) on the same inputs
             Gv = fb.graph_from(g, w.D)
             for _ in range(2):
                 fb.fb_viterbi(Gv, emis, lengths)
@@ -112,18 +128,27 @@ def context_workloads(fb, wl, torch):
     emis, lengths = torch.from_numpy(w.emis).cuda(), torch.from_numpy(w.lengths).cuda()
     ws = torch.empty((fb.fb_lfmmi_workspace_bytes(den, num, w.B, w.N, w.D),), dtype=torch.uint8, device="cuda")
     grad = torch.empty((w.B, w.N, w.D), dtype=torch.float32, device="cuda")
-    for _ in range(2):
-        fb.lfmmi_loss_grad(den, num, emis, lengths, ws=ws, grad=grad, lengths_host=w.lengths)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(5):
-        fb.lfmmi_loss_grad(den, num, emis, lengths, ws=ws, grad=grad, lengths_host=w.lengths)
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / 5
+    def timed(host_lengths):
+        for _ in range(2):
+            fb.lfmmi_loss_grad(den, num, emis, lengths, ws=ws, grad=grad, lengths_host=host_lengths)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            fb.lfmmi_loss_grad(den, num, emis, lengths, ws=ws, grad=grad, lengths_host=host_lengths)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / 5
+
+    ms = timed(None)
+    ms_ragged = timed(w.lengths)
     upd = w.arc_updates(w.den) + w.arc_updates(w.num)
+    frames = int(w.lengths.sum())
+    d_used = int(np.unique(w.den.pdf).size)
+    fused = frames * (8 * w.den.K + 8 * d_used + 4 * w.D)   # the fully fused model of the main line (whole_step_hbm)
     out["paper_shape_lfmmi"] = {"B": w.B, "N_max": w.N, "D": w.D, "den_states": w.den.K, "den_arcs": w.den.E,
-                                "num_states": w.num.K, "num_arcs": w.num.E, "ms": ms, "arc_updates": upd,
-                                "arc_updates_per_s": upd / (ms * 1e-3), "paper_table3_s": 0.220}
+                                "num_states": w.num.K, "num_arcs": w.num.E, "ms": ms,
+                                "lfmmi_loss_grad_ms": ms, "lfmmi_loss_grad_ragged_ms": ms_ragged, "arc_updates": upd,
+                                "arc_updates_per_s": upd / (ms * 1e-3), "algorithmic_bytes": fused,
+                                "hbm_frac": fused / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "paper_table3_s": 0.220}
     log(f"[bench] paper_shape_lfmmi: {ms:.3f} ms, {upd / (ms * 1e-3):.3e} arc-updates/s")
     den.destroy(); num.destroy()
     return out
@@ -138,9 +163,10 @@ def main() -> int:
     ap.add_argument("--cpu-sample", type=int, default=0, help="sequences the CPU oracle is timed on (0 = 2 per thread)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--context", action="store_true",
-                    help="also time fb_alpha + fb_beta + fb_posteriors on configurations 1-4 and on the paper-shaped "
-                         "denominator (context figures, added to the JSON line as other_workloads)")
-    ap.add_argument("--context-only", action="store_true", help=argparse.SUPPRESS)   # the child process of --context
+                    help="time every other workload (configurations 1-4, the paper-shaped denominator and LF-MMI, the best "
+                         "path) for other_workloads; without it: configuration 4 and the two paper-shaped ones")
+    ap.add_argument("--no-context", action="store_true", help="leave other_workloads out")
+    ap.add_argument("--context-only", choices=["all", "main"], default=None, help=argparse.SUPPRESS)   # the child process
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -158,7 +184,7 @@ def main() -> int:
     fb.lib()
     torch.cuda.set_device(0)
     if args.context_only:
-        print(json.dumps(context_workloads(fb, wl, torch)), flush=True)
+        print(json.dumps(context_workloads(fb, wl, torch, everything=args.context_only == "all")), flush=True)
         return 0
 
     t_gen = time.time()
@@ -175,7 +201,10 @@ def main() -> int:
     grad = torch.empty((w.B, w.N, w.D), dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
 
-    def step():   # the host knows the lengths (it made the batch): the entry point for ragged batches
+    def step():   # the call the benchmark is about: lengths on the device only
+        return fb.lfmmi_loss_grad(den, num, emis, lengths, ws=ws, grad=grad)
+
+    def step_ragged():   # its sibling for callers who have the lengths on the host
         return fb.lfmmi_loss_grad(den, num, emis, lengths, ws=ws, grad=grad, lengths_host=w.lengths)
 
     for _ in range(args.warmup):
@@ -193,6 +222,14 @@ def main() -> int:
         e0.record(); step(); e1.record()
     torch.cuda.synchronize()
     single = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    for _ in range(args.warmup):
+        step_ragged()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step_ragged()
+    torch.cuda.synchronize()
+    ms_ragged = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # stage times with HIP events recorded by the library on the launching stream
     fb.fb_profile_enable(True)
@@ -211,7 +248,9 @@ def main() -> int:
     # the emission entries the graph uses are read once and the state vector is written once
     algo_bytes = frames * 2 * (4 * d_used + 4 * w.den.K)
     achieved = algo_bytes / (stage_ms["den_recursion"] * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get("config5")
+    traffic = measured_traffic(DOMINANT_KERNEL)
+    plan_arcs = int(np.unique(w.den.src.astype(np.int64) * w.den.K + w.den.dst).size)
+    upd_plan = 2 * frames * plan_arcs + upd_num   # arcs the plans walk: parallel arcs (same source and destination) are merged
     result = {
         "metric": "log-semiring arc-updates/sec (B*N*E*2) + LF-MMI loss+grad ms/batch",
         "value": arc_updates / (ms_per_step * 1e-3),
@@ -224,30 +263,27 @@ def main() -> int:
                                "128 packed numerator chains, D=3000, N_b=round(3.6 L_b)",
                    "B": w.B, "N_max": w.N, "frames": frames, "D": w.D,
                    "den_states": w.den.K, "den_arcs": w.den.E, "num_states": w.num.K, "num_arcs": w.num.E,
-                   # arcs the compute plans walk per step: parallel arcs (same source and destination) are merged
-                   "den_plan_arcs": int(np.unique(w.den.src.astype(np.int64) * w.den.K + w.den.dst).size)},
+                   "den_plan_arcs": plan_arcs, "entry_point": "lfmmi_loss_grad"},
         "lfmmi_ms_per_batch": ms_per_step,
+        "lfmmi_loss_grad_ms": ms_per_step, "lfmmi_loss_grad_ragged_ms": ms_ragged,
+        "value_on_plan_arcs": upd_plan / (ms_per_step * 1e-3),
         "ms_per_step_median": single[len(single) // 2], "ms_per_step_min": single[0],
         "graph_create_s": graph_create_s,
         "arc_updates_per_step": arc_updates,
         "arc_updates_padded": 2 * w.B * w.N * w.den.E,
         "stage_ms": stage_ms,
         "loss": loss,
-        # the denominator recursion of a step is four launches of this kernel (one per length group, on four
-        # streams) that start together; achieved = the bytes of all four / the time from their start to the end
-        # of the last one (the longest sequences'), which is what den_recursion brackets
-        "roofline": {"kernel": "fb_recursion_kernel<16> (denominator alpha+beta; 4 concurrent launches, one per length group)",
+        # the denominator recursion of a step is one launch of this kernel (alpha and beta of every sequence, 2 B
+        # workgroups in order of length); den_recursion brackets it with events on the launching stream
+        "roofline": {"kernel": DOMINANT_KERNEL + " (denominator alpha+beta, one launch)",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes": algo_bytes, "launch_ms": stage_ms["den_recursion"]},
-        # the bound that applies to that launch: VALU issue.  The (+)-update of one arc needs at least an add
-        # (weight), a max, a subtract, an exponential and an add; the exponential runs at a quarter of the
-        # plain fp32 rate, so an arc-update is at least 4 + 4 = 8 lane-issue slots of the 256 x 64 x 2.4e9 per second
-        # (packed fp32 is not used in this build)
-        "roofline_alu": {"bound": "alu", "achieved": 8 * upd_den / (stage_ms["den_recursion"] * 1e-3) / 1e12,
-                         "peak": VALU_PEAK_PER_S / 1e12, "unit": "T fp32 lane-ops/s (8 per arc-update, the exp as 4)",
-                         "frac": 8 * upd_den / (stage_ms["den_recursion"] * 1e-3) / VALU_PEAK_PER_S,
-                         "exp_frac": upd_den / (stage_ms["den_recursion"] * 1e-3) / (VALU_PEAK_PER_S / 4)},
+        # what holds that launch back: every arc-update is one 4-byte gather from the state vector in LDS (plus the
+        # bank conflicts of 64 lanes reading 64 scattered words); the rate below counts the walked arcs only
+        "roofline_lds": {"bound": "lds", "achieved": 4 * 2 * frames * plan_arcs / (stage_ms["den_recursion"] * 1e-3) / 1e9,
+                         "peak": LDS_PEAK_GBS, "unit": "GB/s gathered (4 bytes per walked arc)",
+                         "frac": 4 * 2 * frames * plan_arcs / (stage_ms["den_recursion"] * 1e-3) / 1e9 / LDS_PEAK_GBS},
     }
 
     # the rate a plain device copy reaches on this machine (1 GiB read + 1 GiB written per copy), beside the published peak
@@ -270,12 +306,12 @@ def main() -> int:
     result["whole_step_hbm"] = {"model_bytes": fused_bytes, "achieved": fused_bytes / (ms_per_step * 1e-3) / 1e9,
                                 "unit": "GB/s", "frac": fused_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
-    if args.context:
-        # In a process of its own, without the library's three group streams: these workloads run fb_alpha and
-        # fb_beta on two streams of the caller's, and a process has only four hardware queues for all its streams.
+    if not args.no_context:
+        # In a process of its own: these workloads run fb_alpha and fb_beta on two streams of the caller's, and a
+        # process has only four hardware queues for all its streams (the LF-MMI calls use three of the library's).
         import subprocess
-        child = subprocess.run([sys.executable, os.path.abspath(__file__), "--context-only"], stdout=subprocess.PIPE,
-                               env=dict(os.environ, FB_AMD_GROUPS="0"), check=True, text=True)
+        child = subprocess.run([sys.executable, os.path.abspath(__file__), "--context-only", "all" if args.context else "main"],
+                               stdout=subprocess.PIPE, check=True, text=True)
         result["other_workloads"] = json.loads(child.stdout.strip().splitlines()[-1])
 
     if args.calibrate_copy:
