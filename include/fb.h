@@ -281,6 +281,28 @@ int lfmmi_loss_grad_ragged(const fb_graph *den, const fb_graph *num, const float
                            double *logz_num, double *logz_den, float *grad, void *ws, size_t ws_bytes,
                            fb_stream stream);
 
+/*
+ * lfmmi_loss_grad for callers that cannot allocate device memory or have none to spare for a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same results as lfmmi_loss_grad (same kernels, same schedule); the workspace is
+ * scratch memory built into the library's image, fb_static_scratch_bytes() = 16 MiB on every
+ * GPU the library runs on, held until the process ends.  The call allocates nothing and frees
+ * nothing (the address of the memory on a device is looked up when the first graph is created
+ * on it, else at the first call).
+ *   loss, logz_num, logz_den, grad   as in lfmmi_loss_grad, caller-owned device memory
+ * Sizes whose fb_lfmmi_workspace_bytes() exceeds fb_static_scratch_bytes() are refused with
+ * FB_EUNSUPPORTED (the message gives both figures); other errors as lfmmi_loss_grad.
+ * Every call on a GPU shares that GPU's scratch memory, which keeps the last call's contents
+ * (a call writes every word it reads, so nothing has to be cleared): calls that overlap on
+ * one GPU, on whatever streams, race with each other.
+ */
+int lfmmi_loss_grad_static(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths,
+                           int32_t B, int32_t N, int32_t D, double *loss, double *logz_num, double *logz_den,
+                           float *grad, fb_stream stream);
+
+/* Bytes of the scratch memory lfmmi_loss_grad_static works in. */
+size_t fb_static_scratch_bytes(void);
+
 /* Bytes of device workspace fb_viterbi needs for these sizes (0 on bad arguments). */
 size_t fb_viterbi_workspace_bytes(const fb_graph *g, int32_t B, int32_t N);
 

@@ -29,7 +29,7 @@ SYMBOLS = ["fb_graph_create", "fb_graph_destroy", "fb_graph_layout_size", "fb_gr
            "fb_alpha", "fb_beta", "fb_posteriors", "fb_lfmmi_workspace_bytes", "lfmmi_loss_grad", "lfmmi_loss_grad_ragged",
            "fb_limits_max_states", "fb_strerror", "fb_last_error", "fb_graph_schedule_apply_host",
            "fb_profile_enable", "fb_profile_read", "fb_viterbi_workspace_bytes", "fb_viterbi", "fb_graph_linear_weights",
-           "fb_debug_linear_restarts", "fb_graph_plan_cycles"]
+           "fb_debug_linear_restarts", "fb_graph_plan_cycles", "lfmmi_loss_grad_static", "fb_static_scratch_bytes"]
 
 
 class FBError(RuntimeError):
@@ -72,6 +72,10 @@ def lib() -> ctypes.CDLL:
         L.fb_posteriors.restype = ctypes.c_int
         L.fb_lfmmi_workspace_bytes.argtypes = [vp, vp, i32, i32, i32]
         L.fb_lfmmi_workspace_bytes.restype = sz
+        L.lfmmi_loss_grad_static.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp]
+        L.lfmmi_loss_grad_static.restype = ctypes.c_int
+        L.fb_static_scratch_bytes.argtypes = []
+        L.fb_static_scratch_bytes.restype = sz
         L.lfmmi_loss_grad.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.lfmmi_loss_grad.restype = ctypes.c_int
         L.lfmmi_loss_grad_ragged.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
@@ -302,6 +306,21 @@ def fb_viterbi(g: Graph, emis, lengths, ws=None):
     _check(lib().fb_viterbi(g.handle, _dp(emis), _dp(lengths), B, N, D, _dp(score), _dp(path), _dp(ws), int(ws.numel()),
                             _stream()))
     return score, path
+
+
+def fb_static_scratch_bytes() -> int:
+    """Bytes of the scratch memory built into the library (what lfmmi_loss_grad_static can use as workspace)."""
+    return int(lib().fb_static_scratch_bytes())
+
+
+def lfmmi_loss_grad_static(den: Graph, num: Graph, emis, lengths, loss, logz_num, logz_den, grad):
+    """lfmmi_loss_grad for callers that cannot allocate: the workspace is the library's built-in scratch memory and
+    every output is the caller's (loss [1] float64, logz_num / logz_den [B] float64, grad [B,N,D] float32, all on
+    the device).  Raises FBError(FB_EUNSUPPORTED) when the sizes need more than fb_static_scratch_bytes()."""
+    B, N, D = _dev_inputs(emis, lengths)
+    _check(lib().lfmmi_loss_grad_static(den.handle, num.handle, _dp(emis), _dp(lengths), B, N, D, _dp(loss), _dp(logz_num),
+                                        _dp(logz_den), _dp(grad), _stream()))
+    return loss, logz_num, logz_den, grad
 
 
 def lfmmi_loss_grad(den: Graph, num: Graph, emis, lengths, ws=None, grad=None, lengths_host=None):

@@ -1,8 +1,10 @@
 // The compute entry points of the C ABI: argument checks and kernel launches.
-#include <hip/hip_runtime_api.h>
+#include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <cstdlib>
+#include <mutex>
+#include <string>
 
 #include "fb_internal.h"
 
@@ -241,12 +243,46 @@ SideStream &side_stream()
     return s;
 }
 
+
+// Scratch memory of lfmmi_loss_grad_static: part of the library's image on every GPU it runs on, so a call needs no
+// allocation.  In host code the array's name only stands for the symbol; the address on a GPU is looked up once per
+// device, with that device current, and kept.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+struct StaticScratch {
+    std::mutex lock;
+    void *ptr[kMaxDevices] = {};
+} g_scratch;
+
+// The address of the scratch array on the current device (nullptr and an error message on failure).
+void *static_scratch()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        fail(FB_EHIP, "lfmmi_loss_grad_static: no current device");
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> hold(g_scratch.lock);
+    if (!g_scratch.ptr[dev]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            fail(FB_EHIP, std::string("lfmmi_loss_grad_static: hipGetSymbolAddress: ") + hipGetErrorString(e));
+            return nullptr;
+        }
+        g_scratch.ptr[dev] = p;
+    }
+    return g_scratch.ptr[dev];
+}
+
 }  // namespace
 
 namespace fb {
 
 void side_stream_init()
 {
+    (void)static_scratch();   // set-up time, this device current: later calls find the address
     SideStream &s = side_stream();
     if (s.tried) return;
     s.tried = true;
@@ -654,6 +690,27 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
     // Without a host copy of the lengths nothing is known about them here; the schedule in length groups needs only
     // ranks, which the device computes, and costs little when the lengths turn out to be equal.
     return lfmmi_run(den, num, emis, lengths, B, N, D, loss, logz_num, logz_den, grad, ws, ws_bytes, stream, true, false);
+}
+
+size_t fb_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int lfmmi_loss_grad_static(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths, int32_t B,
+                           int32_t N, int32_t D, double *loss, double *logz_num, double *logz_den, float *grad,
+                           fb_stream stream)
+{
+    int rc = check_common("lfmmi_loss_grad_static", den, emis, lengths, B, N, D);
+    if (rc) return rc;
+    if ((rc = check_common("lfmmi_loss_grad_static", num, emis, lengths, B, N, D))) return rc;
+    const size_t need = fb_lfmmi_workspace_bytes(den, num, B, N, D);
+    if (need == 0) return fail(FB_EINVAL, "lfmmi_loss_grad_static: these graphs and sizes have no workspace size");
+    if (need > kStaticScratchBytes)
+        return fail(FB_EUNSUPPORTED, "lfmmi_loss_grad_static: the call needs " + std::to_string(need) +
+                                         " bytes of workspace, the built-in scratch memory holds " +
+                                         std::to_string(kStaticScratchBytes) + " (use lfmmi_loss_grad with a workspace)");
+    void *ws = static_scratch();
+    if (!ws) return FB_EHIP;
+    // (every word of the workspace that a kernel reads is written earlier in the same call: nothing to clear)
+    return lfmmi_run(den, num, emis, lengths, B, N, D, loss, logz_num, logz_den, grad, ws, kStaticScratchBytes, stream, true, false);
 }
 
 int lfmmi_loss_grad_ragged(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths,
