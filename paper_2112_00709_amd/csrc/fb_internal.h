@@ -161,8 +161,11 @@ bool stream_apply_host(const StreamHost &S, int32_t sub, const double *x, double
 // The arc list of S with the weights of all batches but the stacked ones replaced by 2^w, for the kernel
 // instantiation that multiplies instead of adding in the exponent; arcs of weight zero-bar (padding included) get
 // weight 0 and the dump slot, which always holds zero-bar, as their source, so that they never raise a running
-// maximum.  False (out unspecified) if a finite weight lies outside [-kLinearSpan, kLinearSpan] (log2 units).
-constexpr float kLinearSpan = 64.0f;
+// maximum.  False (out unspecified) if a finite weight lies outside [-kLinearSpan, kLinearSpan] (log2 units): that
+// kernel normalises a row's terms by the largest gathered value alone and loses a term that lies more than 126 binary
+// orders below it; with weights inside the span such a term is below 2^(2 x 50 - 126) of the row's largest product,
+// i.e. below float rounding.
+constexpr float kLinearSpan = 50.0f;
 bool stream_linear_weights(const StreamHost &S, std::vector<Arc> &out);
 constexpr float kLinWeightSpan = 64.0f, kLinRowSumTop = 40.0f;   // log2 bounds on an arc weight for the probability-domain kernel
 

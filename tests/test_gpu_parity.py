@@ -524,6 +524,75 @@ def test_both_forms_of_the_arc_weights(fb):
     compare_fb(fb, g3, D, emis, lengths, name="a weight out of range: the adding form")
 
 
+def test_strong_weight_on_a_weak_source(fb):
+    """A row that mixes a strong weight (2^60) on an arc from a weak source with a tiny weight (2^-60) on an arc from
+    the source that dominates the frame: the two terms are of comparable size although the gathered values lie more
+    than a float's exponent range apart once normalised by their maximum.  Such weights are outside what the
+    instantiations that take weights as 2^w accept (the probability-domain kernel's row sums, the 2^w form's
+    span), so the graph runs in the adding form; every sequence against the oracle."""
+    rng = np.random.default_rng(78)
+    D, B, N = 60, 4, 16
+    g = wl.random_graph(rng, 1500, D, zipf_s=1.1, mean_extra_deg=6.0)
+    emis = (rng.standard_normal((B, N, D)) * 2.5).astype(np.float32)
+    emis[:, :, 7] += 40.0                                     # the states tied to pdf 7 dominate every frame
+    lengths = np.array([16, 9, 16, 2], dtype=np.int32)
+    strong = np.flatnonzero(g.pdf[g.src] == 7)
+    weak = np.flatnonzero(g.pdf[g.src] != 7)
+    w = g.logw.copy()
+    # rows (destinations) fed by both kinds of source
+    both = np.intersect1d(g.dst[strong], g.dst[weak])
+    assert both.size > 20
+    for d in both[:40]:
+        w[strong[g.dst[strong] == d][0]] = -60.0 * np.log(2.0)
+        w[weak[g.dst[weak] == d][0]] = 60.0 * np.log(2.0)
+    g2 = wl.Graph(g.K, g.src, g.dst, w, g.pdf, g.init, g.final)
+    G = fb.graph_from(g2, D)
+    assert fb.fb_graph_linear_weights(G) == 0
+    G.destroy()
+    compare_fb(fb, g2, D, emis, lengths, name="strong weights on weak sources: the adding form")
+
+
+def test_probability_domain_gives_up_and_falls_back(fb):
+    """The probability-domain recursion keeps a step's vector as floats scaled by a power of two; a run whose
+    entries could fall below that range gives up (judged by the smallest row sum and the frame's smallest emission
+    factor) and the sequence is redone in the log form.  Emissions that force this: a pdf far below the others in
+    every frame of every sequence; in a single frame in the middle of one sequence; a pdf of probability zero.  The
+    counter of given-up runs must move exactly where expected, and every sequence must match the oracle."""
+    rng = np.random.default_rng(79)
+    D, B, N = 60, 5, 18
+    g = wl.random_graph(rng, 1500, D, zipf_s=1.1, mean_extra_deg=6.0)
+    lengths = np.array([18, 7, 18, 1, 12], dtype=np.int32)
+    base = (rng.standard_normal((B, N, D)) * 2.0).astype(np.float32)
+    G = fb.graph_from(g, D)
+    assert fb.fb_graph_linear_weights(G) == 2
+    G.destroy()
+
+    r0 = fb.fb_debug_linear_restarts()
+    compare_fb(fb, g, D, base, lengths, name="probability domain, ordinary emissions")
+    r1 = fb.fb_debug_linear_restarts()
+    assert r1 == r0                                           # nothing gives up
+
+    e2 = base.copy()
+    e2[:, :, 11] = -400.0                                     # 2^-577 of the others: no float holds both
+    compare_fb(fb, g, D, e2, lengths, name="a pdf far below the others in every frame")
+    r2 = fb.fb_debug_linear_restarts()
+    assert r2 - r1 == 2 * B                                   # forward and backward of every sequence (the first vector already holds such an entry)
+
+    e3 = base.copy()
+    e3[2, 9, 23] = -400.0                                     # one frame in the middle of one sequence
+    compare_fb(fb, g, D, e3, lengths, name="a pdf far below the others in one frame")
+    r3 = fb.fb_debug_linear_restarts()
+    assert r3 - r2 == 2
+
+    e4 = base.copy()
+    e4[4, 5, :] = -np.inf
+    e4[4, 5, 3] = 0.0                                         # a frame in which only one pdf has probability above zero
+    e4[0, :, 40] = -np.inf
+    compare_fb(fb, g, D, e4, lengths, name="pdfs of probability zero")
+    r4 = fb.fb_debug_linear_restarts()
+    assert r4 - r3 == 4
+
+
 def test_lfmmi_call_replayed_from_a_graph(fb):
     """The LF-MMI call captured into a HIP graph (through torch) on a side stream and replayed: the library's own
     streams are forked from and joined into the capturing stream with events, it allocates nothing and clears its

@@ -176,7 +176,7 @@ def test_plans_with_weights_as_powers_of_two(seed):
                      np.concatenate([g0.logw, rng.normal(size=every.size).astype(np.float32)]), g0.pdf, g0.init, g0.final)
     logw = g.logw.copy()
     logw[rng.integers(0, logw.size, size=logw.size // 20)] = -np.inf     # zero-bar arcs
-    logw[rng.integers(0, logw.size, size=5)] = -40.0                      # tiny, in range
+    logw[rng.integers(0, logw.size, size=5)] = -30.0                      # 2^-43: tiny, in range
     g = wl.Graph(g.K, g.src, g.dst, logw, g.pdf, g.init, g.final, state_off=g.state_off if g.packed else None)
     h = _host_graph(g, 9)
     off = g.state_off if g.packed else np.array([0, g.K])
@@ -291,3 +291,57 @@ def test_check_lengths():
     fb.fb_check_lengths(np.array([1, 5, 3]), 5)
     _raises(fb.FB_EINVAL, fb.fb_check_lengths, np.array([1, 6, 3]), 5)
     _raises(fb.FB_EINVAL, fb.fb_check_lengths, np.array([0, 2]), 5)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_probability_domain_plans(seed):
+    """The plan the probability-domain kernel walks (two arcs per lane and unit, weights as 2^w, the lanes of a long
+    row added up, clones, padding that reads the dump slot or repeats an address), interpreted on the host in
+    ordinary arithmetic: y = A x for the forward (which = 5) and the backward (6) matrix, against the direct sparse
+    product.  Graphs with hubs over several lanes, clones, parallel arcs, zero-bar weights, states without arcs.  The
+    modelled gather cycles of a step are never below two per gather.  Graphs the kernel cannot take have no plan:
+    packed ones, small ones, weights far out of range."""
+    rng = np.random.default_rng(500 + seed)
+    kind = seed % 3
+    if kind == 0:
+        g = wl.random_graph(rng, int(rng.integers(1100, 3600)), 9, zipf_s=float(rng.uniform(1.0, 1.5)),
+                            mean_extra_deg=float(rng.uniform(2, 12)))
+    elif kind == 1:
+        g = wl.config4(K=3500, B=2, Nmin=3, Nmax=4, D=64).den               # hubs long enough for clones
+    else:
+        g0 = wl.random_graph(rng, 5200, 9, mean_extra_deg=1.0)              # one giant hub and parallel arcs into it
+        every = np.concatenate([np.arange(g0.K), np.arange(0, g0.K, 3)]).astype(np.int32)
+        g = wl.Graph(g0.K, np.concatenate([g0.src, every]), np.concatenate([g0.dst, np.full(every.size, 7, np.int32)]),
+                     np.concatenate([g0.logw, rng.normal(size=every.size).astype(np.float32)]), g0.pdf, g0.init, g0.final)
+    logw = g.logw.copy()
+    logw[rng.integers(0, logw.size, size=logw.size // 20)] = -np.inf        # zero-bar arcs
+    lonely = int(rng.integers(0, g.K))
+    logw[(g.src == lonely) | (g.dst == lonely)] = -np.inf                    # a state without arcs
+    g = wl.Graph(g.K, g.src, g.dst, logw, g.pdf, g.init, g.final)
+    D = int(g.pdf.max()) + 1
+    h = _host_graph(g, D)
+    assert fb.fb_graph_linear_weights(h) == 2
+    W = np.exp(g.logw.astype(np.float64))
+    x = rng.random(g.K)
+    x[rng.integers(0, g.K, size=g.K // 10)] = 0.0
+    for which, rows, cols in ((5, g.dst, g.src), (6, g.src, g.dst)):
+        want = np.zeros(g.K)
+        np.add.at(want, rows, W * x[cols])
+        y = fb.fb_graph_schedule_apply_host(h, which, 0, x, np.full(g.K, np.nan))
+        assert np.all(y[want == 0] == 0)
+        np.testing.assert_allclose(y, want, rtol=2e-6, atol=0)              # weights (parallel arcs merged) as floats, products in double
+        cycles, floor = fb.fb_graph_plan_cycles(h, which == 6)
+        assert floor > 0 and floor % 2 == 0 and cycles >= floor
+        assert cycles <= 2.5 * floor                                        # the order keeps most gathers free of conflicts
+    h.destroy()
+    small = wl.random_graph(rng, 300, 9)
+    h = _host_graph(small, 9)
+    assert fb.fb_graph_linear_weights(h) != 2                               # the 4-wave kernels' territory
+    with pytest.raises(fb.FBError):
+        fb.fb_graph_schedule_apply_host(h, 5, 0, np.zeros(small.K), np.zeros(small.K))
+    h.destroy()
+    far = g.logw.copy()
+    far[g.src == g.src[np.flatnonzero(np.isfinite(far))[0]]] = -70.0          # every arc out of one state 2^-101: beyond the weight span
+    h = _host_graph(wl.Graph(g.K, g.src, g.dst, far, g.pdf, g.init, g.final), D)
+    assert fb.fb_graph_linear_weights(h) != 2
+    h.destroy()
