@@ -218,7 +218,9 @@ void mark(int i, hipStream_t stream)
 }
 
 // Three further streams (default priority) and untimed events, created once per process by
-// side_stream_init, which fb_graph_create calls, so that compute calls themselves never allocate.
+// side_stream_init, which fb_graph_create calls when it makes a packed graph (the numerators of an LF-MMI call: only
+// those calls use the streams, and a process that runs recursions of a shared graph on streams of its own keeps the
+// hardware queues for them), so that compute calls themselves never allocate.
 // With the caller's stream that makes four, the number of hardware queues a process has: one per length
 // group of lfmmi_loss_grad (group 0, the longest sequences, on the caller's stream).  `stream` (= group[0])
 // also takes the numerator launch of a call too small for groups.  Setting FB_AMD_SERIAL=1 in the
@@ -280,9 +282,10 @@ void *static_scratch()
 
 namespace fb {
 
+void static_scratch_init() { (void)static_scratch(); }   // set-up time, this device current: later calls find the address
+
 void side_stream_init()
 {
-    (void)static_scratch();   // set-up time, this device current: later calls find the address
     SideStream &s = side_stream();
     if (s.tried) return;
     s.tried = true;

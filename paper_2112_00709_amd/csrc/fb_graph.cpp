@@ -408,7 +408,8 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
 
         // ---- upload
         if (rc == FB_OK && !g->host_only) {
-            side_stream_init();
+            static_scratch_init();
+            if (n_seq != 0) side_stream_init();
             std::vector<float> i2((size_t)K), f2((size_t)K);
             for (int32_t k = 0; k < K; ++k) { i2[k] = to_log2(init[k]); f2[k] = to_log2(final_[k]); }
             std::vector<int32_t> hp(pdf, pdf + K);

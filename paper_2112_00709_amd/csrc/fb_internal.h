@@ -315,7 +315,8 @@ struct fb_graph {
 namespace fb {
 
 void set_error(const std::string &msg);
-void side_stream_init();   // once per process: the stream lfmmi_loss_grad runs the numerator launch on
+void side_stream_init();   // once per process: the streams the LF-MMI calls use beside the caller's
+void static_scratch_init();   // once per device: the address of the library's built-in scratch memory
 int fail(int code, const std::string &msg);
 
 struct RecDir {
@@ -428,6 +429,6 @@ int launch_loss(const double *logz_num, const double *logz_den, const int32_t *l
 size_t recursion_lds_bytes(int32_t Kcap, int32_t Ccap, int32_t Ecap, bool backward, bool f64, bool shared,
                            bool tropical = false, int32_t xs_fixed = 0);
 size_t posterior_lds_bytes(const PostParams &p);
-size_t probability_lds_bytes(int32_t D, bool backward);   // the probability-domain kernel's own use (its launch takes the larger of this and the log form's)
+size_t probability_lds_bytes(int32_t D, bool staged);   // the probability-domain kernel's own use (its launch takes the larger of this and the log form's); staged: the direction keeps rows on their way out apart from the vector (backward, or rows that leave as logarithms)
 
 }  // namespace fb

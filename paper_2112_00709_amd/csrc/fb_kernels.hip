@@ -905,8 +905,13 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
     if (Tn <= 0) return false;                   // (nothing to run: the log form writes the empty results)
 
     float *xb = (float *)lds_raw;
-    float *bh = xb + Xs + XF;                    // (backward only; its two buffers follow each other)
-    float *red = bwd ? bh + 2 * XF : bh;
+    // rows on their way out that are not the vector itself: beta before the emissions are applied (backward), and
+    // either direction's rows as logarithms when that is the form they leave in; two buffers that follow each other,
+    // present only when used
+    const bool log_rows = R_.out != nullptr && R_.out_linear == 0;
+    const bool staged = bwd || log_rows;
+    float *bh = xb + Xs + XF;
+    float *red = staged ? bh + 2 * XF : bh;
     float *er = red + 64;
     float *emaxw = red + 4;
     float *espw = red + 8;                       // per frame: log2 of (smallest / largest) emission factor, less a margin
@@ -993,6 +998,7 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
         const float e = (float)(__builtin_amdgcn_frexp_expf(v) - kLinBias);   // (v = 0: -inf comes from the mantissa)
         return (e + flog2(__builtin_amdgcn_frexp_mantf(v))) * R_.out_scale;
     };
+    // (rows that leave as logarithms were staged in that form by the waves that formed them: a plain copy either way)
     auto write_row = [&](int f, const float *srcv) {
         if (!out_row0) return;
         float *orow = out_row0 + (size_t)f * out_ld;
@@ -1004,13 +1010,6 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
             float4 v[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) v[u] = s4[min(q0 + u * kWave + lane, n4 - 1)];
-            if (!out_lin) {
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    v[u].x = to_log(v[u].x); v[u].y = to_log(v[u].y);
-                    v[u].z = to_log(v[u].z); v[u].w = to_log(v[u].w);
-                }
-            }
 #pragma unroll
             for (int u = 0; u < U; ++u)   // every read and conversion stays in front of the stores
                 asm volatile("" : "+v"(v[u].x), "+v"(v[u].y), "+v"(v[u].z), "+v"(v[u].w));
@@ -1031,9 +1030,21 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
         }
         for (int j = lane; j < S.n_clones; j += kWave) {   // stores of one wave to one address keep their order
             const CloneDesc cd = cdesc[j];
-            float t = srcv[cd.state];
-            for (int i = 0; i < cd.count; ++i) t += srcv[K + cd.first + i];
-            orow[cd.state] = out_lin ? t : to_log(t);
+            if (out_lin) {
+                float t = srcv[cd.state];
+                for (int i = 0; i < cd.count; ++i) t += srcv[K + cd.first + i];
+                orow[cd.state] = t;
+            } else {   // logarithms (scaled by out_scale, which is positive): the (+)-sum of the clones
+                float m = srcv[cd.state];
+                for (int i = 0; i < cd.count; ++i) m = tmax(m, srcv[K + cd.first + i]);
+                float t = 0.0f;
+                if (m > -INFINITY) {
+                    const float inv = 1.0f / R_.out_scale;
+                    t = fexp2((srcv[cd.state] - m) * inv);
+                    for (int i = 0; i < cd.count; ++i) t += fexp2((srcv[K + cd.first + i] - m) * inv);
+                }
+                orow[cd.state] = m > -INFINITY ? m + flog2(t) * R_.out_scale : m;
+            }
         }
     };
     // what the readers of a row get beside it: log2 of the true row = log2 of the stored row + cum (in the linear
@@ -1073,13 +1084,14 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
         const float y = s + fmaf(er[P.pdf[k]], (float)kLog2e, -emx0) - base0;
         const float px = fexp2(y);
         xb[k] = px;
-        if (bwd) bh[k] = fexp2(s - base0);
+        if (log_rows) bh[k] = ((bwd ? s - base0 : y) - (float)kLinBias) * R_.out_scale;
+        else if (bwd) bh[k] = fexp2(s - base0);
         const bool dim = y > -INFINITY && px < kLinDimP;
         wmax = dim ? INFINITY : tmax(wmax, px);
     }
     for (int k = tid; k < nC; k += NT) {   // clones start empty: the state itself holds the start weight
         xb[K + k] = 0.0f;
-        if (bwd) bh[K + k] = 0.0f;
+        if (staged) bh[K + k] = log_rows ? -INFINITY : 0.0f;
     }
     if (tid == 0) xb[nX - 1] = xb[Xs + nX - 1] = 0.0f;   // the dump slot holds zero in both buffers, always
     put_max(0, wmax);
@@ -1117,7 +1129,7 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
                 if (lane == 0) { emaxw[(i + 1) % 3] = en; espw[(i + 1) % 3] = sp; }   // (the words of frame i - 2: read for the last time in step i - 1)
             }
             if (i + 2 < Tn) stage(frame(i + 2), er + ((i + 2) % 3) * Es);   // buffer of frame i-1: no longer read
-            write_row(frame(i - 1), bwd ? bh + cur * XF : xb + cur * Xs);
+            write_row(frame(i - 1), staged ? bh + cur * XF : xb + cur * Xs);
             if (lane == 0) red[(i + 1) % 3] = 0.0f;   // the word of step i + 1 starts empty
             __syncthreads();
         }
@@ -1214,7 +1226,7 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
                 for (int z = tid; z < S.n_zero; z += NC * kWave) {
                     const int k = S.zero_rows[z];
                     xn[k] = 0.0f;
-                    if (bwd) bn[k] = 0.0f;
+                    if (staged) bn[k] = log_rows ? -INFINITY : 0.0f;
                 }
             // the two values a unit gathers; sources are byte offsets, the workgroup's LDS starts at address 0
             auto gather = [&](float2 &g, uint32_t s) __attribute__((always_inline)) {
@@ -1250,7 +1262,10 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
                 const float pb = acc * sc;
                 const float px = pb * pe;
                 *(float *)((char *)xn + tgt) = px;
-                if (bwd) *(float *)((char *)bn + tgt) = pb;
+                if (staged) {   // (uniform) what leaves the kernel for this row
+                    const float o = bwd ? pb : px;
+                    *(float *)((char *)bn + tgt) = log_rows ? to_log(o) : o;
+                }
                 wmax = tmax(wmax, px);
                 wlow = min(wlow, __float_as_uint(pb) - 1u);
                 acc = 0.0f;
@@ -1350,7 +1365,7 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
     // ---- last frame: write it out, close log Z with the end weights
     const int last = (Tn - 1) & 1;
     const float *xl = xb + last * Xs;
-    if (io_wave) write_row(frame(Tn - 1), bwd ? bh + last * XF : xl);
+    if (io_wave) write_row(frame(Tn - 1), staged ? bh + last * XF : xl);
     if (R_.logz) {
         float m = kNegBig, s = 0.0f;
         for (int k = tid; k < K; k += NT) lse_add(m, s, flog2(xl[k] * unbias) + R_.obound[k]);
@@ -2051,7 +2066,7 @@ int launch_recursion(int nw, bool f64, bool tropical, const RecParams &p, size_t
             if (!p.shared || p.linear_w) return fail(FB_EHIP, "internal error: probability-domain launch");
             for (int i = 0; i < p.n_dir; ++i) {
                 if (!p.dir[i].prob.units) return fail(FB_EHIP, "internal error: probability-domain launch without its plan");
-                lds_bytes = std::max(lds_bytes, probability_lds_bytes(p.D, p.dir[i].backward != 0));
+                lds_bytes = std::max(lds_bytes, probability_lds_bytes(p.D, p.dir[i].backward != 0 || (p.dir[i].out && !p.dir[i].out_linear)));
             }
             if (lds_bytes > kLdsBytes) return fail(FB_EHIP, "internal error: probability-domain launch beyond the on-chip memory");
             return launch_rec(fb_linear_kernel, nw, p, lds_bytes, stream);
@@ -2074,9 +2089,9 @@ int launch_recursion(int nw, bool f64, bool tropical, const RecParams &p, size_t
                : launch_rec(fb_recursion_kernel<kNWSmall, float, false, 0>, nw, p, lds_bytes, stream);
 }
 
-size_t probability_lds_bytes(int32_t D, bool backward)
+size_t probability_lds_bytes(int32_t D, bool staged)
 {
-    return (size_t)kXbStride + ((size_t)kXsFixed * (backward ? 3 : 1) + 64 + 3 * (((size_t)D + 1 + 3) & ~(size_t)3)) * 4;
+    return (size_t)kXbStride + ((size_t)kXsFixed * (staged ? 3 : 1) + 64 + 3 * (((size_t)D + 1 + 3) & ~(size_t)3)) * 4;
 }
 
 unsigned int linear_restarts()
