@@ -1185,8 +1185,9 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
         // scalar base plus the lane's offset, while addresses kept over the whole loop, as the compiler would have them,
         // take a register pair each)
         uint32_t ub_lo = (uint32_t)(uintptr_t)ubase, ub_hi = (uint32_t)((uintptr_t)ubase >> 32);
-        auto request = [&](Unit &dst, int pos) __attribute__((always_inline)) {
-            const int u = min(pos, last_spos);
+        // (a position inside the patterned part is asked for as it is, whatever the wave's unit count: the plan has
+        // room for kPPatterned units behind every wave's first; positions behind it are held to the wave's last unit)
+        auto request_at = [&](Unit &dst, int u) __attribute__((always_inline)) {
             typedef const __attribute__((address_space(1))) uint32_t global_u32;   // (an address built from integers: say that it is global memory)
             global_u32 *ub = (global_u32 *)((uintptr_t)ub_lo | ((uintptr_t)ub_hi << 32)) + (size_t)u * (3 * kWave);
             dst.s = ub[lane3];
@@ -1194,9 +1195,10 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
             dst.w1 = __uint_as_float(ub[lane3 + 2]);
             __builtin_amdgcn_sched_barrier(0);   // keep the issue order: waits count loads in order
         };
+        auto request = [&](Unit &dst, int pos) __attribute__((always_inline)) { request_at(dst, min(pos, last_spos)); };
         unrolled([&](auto mc) __attribute__((always_inline)) {
             constexpr int m = decltype(mc)::value;
-            request(ring[m], p_streamed_pos(m));
+            request_at(ring[m], p_streamed_pos(m));
         }, std::make_integer_sequence<int, kPRing - 1>{});
 
         auto step = [&](int i) __attribute__((always_inline)) -> bool {
@@ -1299,13 +1301,16 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
                             // a streamed unit: the place of the one before it in the ring is free, the unit kPRing - 1 further on goes there
                             if constexpr (p_streamed(u)) {
                                 constexpr int m = p_streamed_before(u);
-                                request(ring[(m + kPRing - 1) % kPRing], p_streamed_pos(m + kPRing - 1));
+                                if constexpr (p_streamed_pos(m + kPRing - 1) < NP) request_at(ring[(m + kPRing - 1) % kPRing], p_streamed_pos(m + kPRing - 1));
+                                else request(ring[(m + kPRing - 1) % kPRing], p_streamed_pos(m + kPRing - 1));
                             }
                             // (gathered whether the wave has that unit or not - its registers hold valid sources either way -
                             // so that the number of gathers on their way is a constant too)
                             if constexpr (u + GD < NP) gather(G[(u + GD) % NGB], unit_at(std::integral_constant<int, u + GD>{}).s);
                             else gather(G[(u + GD) % NGB], ring[(NG + (u + GD - NP)) % kPRing].s);   // the first units behind the patterned part
                             const Unit me = unit_at(std::integral_constant<int, u>{});
+                            // (both values of the unit are taken at one point: one wait for the pair instead of one each)
+                            asm volatile("" : "+v"(G[u % NGB].x), "+v"(G[u % NGB].y));
                             acc = fmaf(G[u % NGB].x, me.w0, acc);
                             acc = fmaf(G[u % NGB].y, me.w1, acc);
                             if (((u < 32 ? m_lo : m_hi) >> (u & 31)) & 1u) close_slice();
@@ -1326,6 +1331,7 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
                         const int mr = NG + tt;   // (t0 is a multiple of kPRing: only tt names the buffers)
                         request(ring[(mr + kPRing - 1) % kPRing], NP + t + kPRing - 1);
                         gather(G[(NP + tt + GD) % NGB], ring[(mr + GD) % kPRing].s);
+                        asm volatile("" : "+v"(G[(NP + tt) % NGB].x), "+v"(G[(NP + tt) % NGB].y));
                         acc = fmaf(G[(NP + tt) % NGB].x, ring[mr % kPRing].w0, acc);
                         acc = fmaf(G[(NP + tt) % NGB].y, ring[mr % kPRing].w1, acc);
                         const int at = NP + t;
@@ -1337,7 +1343,7 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
             // the first streamed units of the next step (every place of the ring is free now)
             unrolled([&](auto mc) __attribute__((always_inline)) {
                 constexpr int m = decltype(mc)::value;
-                request(ring[m], p_streamed_pos(m));
+                request_at(ring[m], p_streamed_pos(m));
             }, std::make_integer_sequence<int, kPRing - 1>{});
             // An entry below the range: the run gives up (see above).  Judged by the smallest row sum and the frame's
             // smallest emission factor together, which is at most the smallest entry: one test per lane and step instead
