@@ -55,16 +55,17 @@
  *       shared graph       float [B][N][K]
  *       packed graphs      float [N][K]   (K = all states of all sequences;
  *                                          sequence b fills its own columns)
- *   alpha_off, beta_off    float [B][N]
+ *   alpha_cum, beta_cum    double [B][N]
  *   logz                   double [B]
  *
  * Normalised storage.  Stored alpha/beta rows are shifted so that single
  * precision keeps its resolution on long sequences:
- *   true alpha_n[k] = alpha[..n..][k] + sum_{m <= n} alpha_off[b][m]
- *   true beta_n[k]  = beta[..n..][k]  + sum_{m >= n} beta_off[b][m]
- * (sum the offsets in double).  The shifts cancel in Eq. 15, so posteriors do
- * not depend on them.  Rows of padded frames hold -inf (alpha, beta) or 0
- * (offsets, posteriors, grad).
+ *   true alpha_n[k] = alpha[..n..][k] + alpha_cum[b][n]
+ *   true beta_n[k]  = beta[..n..][k]  + beta_cum[b][n]
+ * (the shift of frame n, accumulated in double over the frames the recursion has passed: from
+ * the first frame for alpha, from the last for beta).  The shifts cancel in Eq. 15, so
+ * posteriors do not depend on them.  Rows of padded frames hold -inf (alpha, beta) or 0
+ * (shifts, posteriors, grad).
  *
  * Precision.  Exponentials and logarithms are single precision everywhere.
  * The normalised state vector of the recursions is carried either in single or
@@ -190,25 +191,25 @@ int fb_check_lengths(const int32_t *lengths_host, int32_t B, int32_t N);
 
 /*
  * Forward recursion, Eq. 13, for every sequence of the batch.
- *   alpha      out, nullable (then only the offsets and log Z are produced)
- *   alpha_off  out, float [B][N], nullable
+ *   alpha      out, nullable (then only the shifts and log Z are produced)
+ *   alpha_cum  out, double [B][N], nullable
  *   logz       out, double [B], nullable: log Z_b = (+)-sum_k alpha_{T-1}[k] (x) final[k]
  * FB_EINVAL: g NULL or host-only, emis / lengths NULL, B/N/D <= 0, D != the graph's D,
  *   packed graph with B != n_seq.  FB_EUNSUPPORTED: K and D together exceed the
  *   on-chip memory of a compute unit (fb_limits).
  */
 int fb_alpha(const fb_graph *g, const float *emis, const int32_t *lengths, int32_t B, int32_t N, int32_t D,
-             float *alpha, float *alpha_off, double *logz, fb_stream stream);
+             float *alpha, double *alpha_cum, double *logz, fb_stream stream);
 
 /*
  * Backward recursion, Eq. 14 (with v_{n+1}, as in the scalar Eq. 3).
- *   beta, beta_off  out, nullable, as for fb_alpha
+ *   beta, beta_cum  out, nullable, as for fb_alpha
  *   logz            out, nullable: log Z_b evaluated at the first frame,
  *                   (+)-sum_k init[k] (x) v_0[k] (x) beta_0[k]; equals fb_alpha's up to rounding
  * Errors as fb_alpha.
  */
 int fb_beta(const fb_graph *g, const float *emis, const int32_t *lengths, int32_t B, int32_t N, int32_t D,
-            float *beta, float *beta_off, double *logz, fb_stream stream);
+            float *beta, double *beta_cum, double *logz, fb_stream stream);
 
 /*
  * State and pdf posteriors, Eq. 15, from the normalised alpha and beta of

@@ -265,19 +265,20 @@ def _recursion(fn, g: Graph, emis, lengths, want_vectors: bool):
     torch = _torch()
     B, N, D = _dev_inputs(emis, lengths)
     vec = _new(_vec_shape(g, B, N), torch.float32, emis.device) if want_vectors else None
-    off = _new((B, N), torch.float32, emis.device)
+    off = _new((B, N), torch.float64, emis.device)
     logz = _new((B,), torch.float64, emis.device)
     _check(fn(g.handle, _dp(emis), _dp(lengths), B, N, D, _dp(vec), _dp(off), _dp(logz), _stream()))
     return vec, off, logz
 
 
 def fb_alpha(g: Graph, emis, lengths, want_vectors: bool = True):
-    """-> (alpha, alpha_off [B,N], logz [B]); alpha is [B,N,K] (shared) or [N,K] (packed)."""
+    """-> (alpha, alpha_cum [B,N] float64, logz [B]); alpha is [B,N,K] (shared) or [N,K] (packed); the true row of
+    frame n is alpha[.., n, :] + alpha_cum[b, n]."""
     return _recursion(lib().fb_alpha, g, emis, lengths, want_vectors)
 
 
 def fb_beta(g: Graph, emis, lengths, want_vectors: bool = True):
-    """-> (beta, beta_off [B,N], logz [B])."""
+    """-> (beta, beta_cum [B,N] float64, logz [B])."""
     return _recursion(lib().fb_beta, g, emis, lengths, want_vectors)
 
 

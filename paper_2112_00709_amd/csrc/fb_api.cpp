@@ -27,7 +27,7 @@ int check_common(const char *who, const fb_graph *g, const void *p1, const void 
     return FB_OK;
 }
 
-RecDir make_dir(const fb_graph *g, bool backward, void *out, bool out_carrier, float *off, double *logz,
+RecDir make_dir(const fb_graph *g, bool backward, void *out, bool out_carrier, double *off, double *logz,
                 float out_scale, bool fill_pad)
 {
     RecDir r{};
@@ -354,20 +354,20 @@ int fb_profile_read(float *ms)
 extern "C" {
 
 int fb_alpha(const fb_graph *g, const float *emis, const int32_t *lengths, int32_t B, int32_t N, int32_t D, float *alpha,
-             float *alpha_off, double *logz, fb_stream stream)
+             double *alpha_cum, double *logz, fb_stream stream)
 {
     int rc = check_common("fb_alpha", g, emis, lengths, B, N, D);
     if (rc) return rc;
-    const RecDir d = make_dir(g, false, alpha, false, alpha_off, logz, kLn2f, true);
+    const RecDir d = make_dir(g, false, alpha, false, alpha_cum, logz, kLn2f, true);
     return run_recursion(g, emis, lengths, B, N, D, &d, 1, stream);
 }
 
 int fb_beta(const fb_graph *g, const float *emis, const int32_t *lengths, int32_t B, int32_t N, int32_t D, float *beta,
-            float *beta_off, double *logz, fb_stream stream)
+            double *beta_cum, double *logz, fb_stream stream)
 {
     int rc = check_common("fb_beta", g, emis, lengths, B, N, D);
     if (rc) return rc;
-    const RecDir d = make_dir(g, true, beta, false, beta_off, logz, kLn2f, true);
+    const RecDir d = make_dir(g, true, beta, false, beta_cum, logz, kLn2f, true);
     return run_recursion(g, emis, lengths, B, N, D, &d, 1, stream);
 }
 

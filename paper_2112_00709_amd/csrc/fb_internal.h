@@ -325,7 +325,7 @@ struct RecDir {
     const float *obound;   // end weights, for log Z
     void *out;             // normalised vectors, nullable: float, or the carrier type if out_carrier
     int out_carrier;       // out holds carrier-type values (workspace), not float
-    float *off;            // [B][N] offsets, nullable
+    double *off;           // [B][N] the shift of every stored row (accumulated offsets x out_scale), nullable
     float *cum;            // [B][N] running sums of the offsets (log2 units: stored row + cum = the true row), nullable
     double *logz;          // [B], nullable
     float out_scale;       // ln 2 for natural-log output, 1 to keep log2 units

@@ -330,7 +330,7 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
     const size_t out_at = P.shared ? (size_t)b * P.N * out_ld : (size_t)k0;
     float *out_f = (R.out && !R.out_carrier) ? (float *)R.out + out_at : nullptr;
     T *out_t = (R.out && R.out_carrier) ? (T *)R.out + out_at : nullptr;
-    float *off_seq = R.off ? R.off + (size_t)b * P.N : nullptr;
+    double *off_seq = R.off ? R.off + (size_t)b * P.N : nullptr;
     auto frame = [&](int i) { return bwd ? Tn - 1 - i : i; };
     // the maximum over the workgroup of the vector of step i (the next step normalises by it)
     constexpr bool kAtomMax = sizeof(T) == 4;
@@ -464,7 +464,7 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
             if (Tn > 1) stage(frame(1), er + Es);
             staged_wait();
             if (Tn > 2) stage(frame(2), er + 2 * Es);   // lands while step 1 runs
-            if (off_seq && lane == 0) off_seq[frame(0)] = 0.0f;
+            if (off_seq && lane == 0) off_seq[frame(0)] = 0.0;
             if (R.cum && lane == 0) R.cum[(size_t)b * P.N + frame(0)] = 0.0f;
         }
         __syncthreads();
@@ -491,7 +491,7 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
                 const T M = get_max(i - 1);
                 const T c = (M == kNegInf) ? (T)0 : M;
                 csum += (double)c;
-                if (off_seq && lane == 0) off_seq[frame(i)] = (float)c * R.out_scale;
+                if (off_seq && lane == 0) off_seq[frame(i)] = csum * (double)R.out_scale;
                 if (R.cum && lane == 0) R.cum[(size_t)b * P.N + frame(i)] = (float)csum;
                 staged_wait();   // frame i+1, requested a whole step ago, is in LDS
                 if (i + 2 < Tn) stage(frame(i + 2), er + ((i + 2) % 3) * Es);   // buffer of frame i-1: no longer read
@@ -841,7 +841,7 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
                 for (int k = tid; k < K; k += NT) orow[k] = -INFINITY;
             }
         if (off_seq)
-            for (int f = Tn + tid; f < P.N; f += NT) off_seq[f] = 0.0f;
+            for (int f = Tn + tid; f < P.N; f += NT) off_seq[f] = 0.0;
     }
 
 }
@@ -919,7 +919,7 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
     const float *em_seq = P.emis + (size_t)b * P.N * P.D;
     const size_t out_ld = (size_t)(R_.out_ld ? R_.out_ld : K);
     float *out_row0 = R_.out ? (float *)R_.out + (size_t)b * P.N * out_ld : nullptr;
-    float *off_seq = R_.off ? R_.off + (size_t)b * P.N : nullptr;
+    double *off_seq = R_.off ? R_.off + (size_t)b * P.N : nullptr;
     auto frame = [&](int i) { return bwd ? Tn - 1 - i : i; };
     auto put_max = [&](int i, float wmax) {
         wmax = wave_max(wmax);
@@ -1107,7 +1107,7 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
         float c = base0 + (float)kLinBias + (bwd ? 0.0f : emx0);
         csum = (double)c;
         if (lane == 0) {
-            if (off_seq) off_seq[frame(0)] = c * R_.out_scale;
+            if (off_seq) off_seq[frame(0)] = csum * (double)R_.out_scale;
             if (R_.cum) R_.cum[(size_t)b * P.N + frame(0)] = (float)(csum - cum_shift);
         }
         for (int i = 1; i < Tn; ++i) {
@@ -1119,7 +1119,7 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
             c = nls + emaxw[(bwd ? i - 1 : i) % 3];
             csum += (double)c;
             if (lane == 0) {
-                if (off_seq) off_seq[frame(i)] = c * R_.out_scale;
+                if (off_seq) off_seq[frame(i)] = csum * (double)R_.out_scale;
                 if (R_.cum) R_.cum[(size_t)b * P.N + frame(i)] = (float)(csum - cum_shift);
             }
             staged_wait();   // frame i+1, requested a whole step ago, is in LDS
@@ -1400,7 +1400,7 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
                 for (int k = tid; k < K; k += NT) orow[k] = -INFINITY;
             }
         if (off_seq)
-            for (int f = Tn + tid; f < P.N; f += NT) off_seq[f] = 0.0f;
+            for (int f = Tn + tid; f < P.N; f += NT) off_seq[f] = 0.0;
     }
     if (R_.fmt && tid == 0) R_.fmt[b] = out_lin ? 1 : 0;   // which form this sequence's rows have
     return true;
