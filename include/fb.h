@@ -111,7 +111,11 @@ enum {
     FB_GRAPH_WIDE_STATE = 2, /* carry the state vectors in double (see "Precision" below) */
     FB_GRAPH_NARROW_STATE = 4 /* carry them in single; with neither flag the library chooses:
                                double for small (sub-)graphs (< 4096 arcs and <= 1024 states each),
-                               single otherwise */
+                               single otherwise.  Single precision on long left-to-right chains (the
+                               numerator graphs) does NOT meet the 1e-5 posterior tolerance: a state
+                               can matter while its alpha lies thousands below the frame's best, where
+                               a float log value is spaced 2e-4 apart (1.2e-5 measured on chains of
+                               150 phones); use it only where that is acceptable */
 };
 
 /* Arrays that fb_graph_layout can copy out (graph-layout step; integer work, one
@@ -251,8 +255,10 @@ size_t fb_lfmmi_workspace_bytes(const fb_graph *den, const fb_graph *num, int32_
  * `stream` as usual.  FB_AMD_SERIAL=1 in the environment keeps all launches on `stream`;
  * FB_AMD_GROUPS=0 creates only one of the library's streams (with the caller's, the four
  * take the hardware queues a process has) and so keeps to one launch per stage.  Those
- * streams, their events and the stage timer belong to the process: LF-MMI calls from
- * several host threads must not overlap.
+ * streams, their events and the stage timer belong to the process; a lock is held while a call
+ * enqueues its work, so LF-MMI calls from several host threads are safe and their work is
+ * ordered on the library's streams in the order of the calls (each call still uses only its
+ * own workspace and outputs).
  * FB_EINVAL: as fb_alpha, or ws too small / NULL, den packed, num shared.
  */
 int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths,
@@ -274,8 +280,7 @@ int lfmmi_loss_grad(const fb_graph *den, const fb_graph *num, const float *emis,
  * as lfmmi_loss_grad reaches with its counters, without them (so also under stream capture).
  * Otherwise one launch per stage.  Same arguments, workspace and errors as lfmmi_loss_grad,
  * same loss and log Z bit for bit, the same gradient to rounding (the launches of the
- * schedules form the same sums in different orders).  Calls from several host threads must
- * not overlap.
+ * schedules form the same sums in different orders).
  */
 int lfmmi_loss_grad_ragged(const fb_graph *den, const fb_graph *num, const float *emis, const int32_t *lengths,
                            const int32_t *lengths_host, int32_t B, int32_t N, int32_t D, double *loss,

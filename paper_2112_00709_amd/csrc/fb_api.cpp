@@ -451,6 +451,10 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
     const size_t need = fb_lfmmi_workspace_bytes(den, num, B, N, D);
     if (!ws || ws_bytes < need) return fail(FB_EINVAL, "lfmmi_loss_grad: workspace missing or too small");
     if (((uintptr_t)ws & 255) != 0) return fail(FB_EINVAL, "lfmmi_loss_grad: workspace must be 256-byte aligned");
+    // The library's streams, their events and the stage timer are the process's: one call at a time enqueues its
+    // work (events are recorded and waited for in pairs inside a call, so calls must not interleave there).
+    static std::mutex enqueue_lock;
+    std::lock_guard<std::mutex> hold(enqueue_lock);
 
     // workspace: forward and backward vectors of both graphs in log2 units, log Z when the caller keeps none, the
     // sequences in order of length, the running offsets of the denominator's forward and backward rows

@@ -592,6 +592,49 @@ def test_probability_domain_gives_up_and_falls_back(fb):
     assert r4 - r3 == 4
 
 
+def test_lfmmi_calls_from_two_host_threads(fb):
+    """Two host threads call lfmmi_loss_grad at the same time on the same graphs, each on its own inputs, workspace,
+    outputs and stream (the library's side streams and events are shared by the process and guarded by a lock
+    while a call enqueues): every call must give the bits a call made alone gives."""
+    import threading
+    import torch
+    w = wl.config5(K=1500, B=40, Lmin=3, Lmax=12, D=100)
+    Gd, Gn = fb.graph_from(w.den, w.D), fb.graph_from(w.num, w.D)
+    lengths = dev(w.lengths.astype(np.int32))
+    emis = [dev(w.emis), dev(np.ascontiguousarray(-w.emis[::-1]))]
+    need = fb.fb_lfmmi_workspace_bytes(Gd, Gn, w.B, w.N, w.D)
+    alone = []
+    for e in emis:
+        out = fb.lfmmi_loss_grad(Gd, Gn, e, lengths)
+        torch.cuda.synchronize()
+        alone.append([host(x).copy() for x in out])
+    results, errors = [None, None], []
+
+    def worker(i):
+        try:
+            stream = torch.cuda.Stream()
+            ws = torch.full((need,), 255, dtype=torch.uint8, device="cuda")
+            grad = torch.full((w.B, w.N, w.D), float("nan"), dtype=torch.float32, device="cuda")
+            with torch.cuda.stream(stream):
+                for _ in range(12):
+                    out = fb.lfmmi_loss_grad(Gd, Gn, emis[i], lengths, ws=ws, grad=grad)
+            stream.synchronize()
+            results[i] = [host(x).copy() for x in out]
+        except Exception as exc:   # noqa: BLE001 (reported by the main thread)
+            errors.append(exc)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for i in range(2):
+        for a, b in zip(alone[i], results[i]):
+            assert np.array_equal(a, b)
+    Gd.destroy(); Gn.destroy()
+
+
 def test_lfmmi_call_replayed_from_a_graph(fb):
     """The LF-MMI call captured into a HIP graph (through torch) on a side stream and replayed: the library's own
     streams are forked from and joined into the capturing stream with events, it allocates nothing and clears its
