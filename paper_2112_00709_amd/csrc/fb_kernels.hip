@@ -1018,7 +1018,11 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
                 const int q = q0 + u * kWave + lane;
                 if (q < n4) {
                     if (vec) {   // (the row's padding may take up to 3 values that lie behind the states)
-                        ((float4 *)orow)[q] = v[u];
+                        // (a streaming store: the row is read again much later, by another kernel, and what it would
+                        // push out of L2 is the arc plan every workgroup re-reads at every step)
+                        typedef float f4 __attribute__((ext_vector_type(4)));
+                        const f4 t = {v[u].x, v[u].y, v[u].z, v[u].w};
+                        __builtin_nontemporal_store(t, (f4 *)orow + q);
                     } else {
                         if (4 * q + 0 < K) orow[4 * q + 0] = v[u].x;
                         if (4 * q + 1 < K) orow[4 * q + 1] = v[u].y;
