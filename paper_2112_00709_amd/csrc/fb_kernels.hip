@@ -854,8 +854,8 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
 // arc costs one LDS gather and one multiply-add (the plan carries 2^w) and a row one exponential (its emission)
 // instead of one exponential per arc.  At every step the vector is rescaled by the power of two that brings the
 // previous step's largest entry to [2^bias, 2^(bias + 1)) (exact), and the emissions of a frame enter relative to
-// the largest emission the graph uses in that frame.  bias is chosen per graph and direction so that no row sum
-// can overflow (from the largest sum of weights of a row).
+// the frame's largest emission over all pdfs (any scale serves).  bias is chosen per graph and direction so that no
+// row sum can overflow (from the largest sum of weights of a row).
 //
 // The plan (fb_pstream.cpp).  Each arc-walking wave has a list of units - two arcs per lane in three registers - most
 // of which stay in registers for the whole time loop (the rest cycles through a small ring fed from L2), a bit per
@@ -863,21 +863,25 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
 // lane's sum goes and which emission it takes.  The order of the arcs in a lane and of the rows in a slice has been
 // chosen on the host so that the 32 lanes of half a wave gather from different banks.
 //
-// Range guard.  A float holds what lies within 2^-126 of the scale; the log form holds everything.  Whenever a
-// state that is not the semiring zero would come to lie below `dim` - the value under which its product with the
-// graph's smallest weight could be flushed to zero - or the step's largest entry falls too far for the next
-// rescaling to be a float, the workgroup gives the sequence up (returns false) and its caller runs it again from
-// the first frame in the log form.  Every sum a completed run has formed is therefore exact to rounding.  The
-// give-up travels through the step maximum the waves exchange anyway: a lane that sees such a state reports +inf
-// as its maximum.
+// Range guard.  A float holds what lies within 2^-126 of the scale; the log form holds everything.  An entry that is
+// not the semiring zero must not come to lie below `dim`, the value under which its product with the graph's smallest
+// weight could be flushed to zero.  A lane keeps the smallest row sum above zero it has formed in a step; at the
+// step's end that, times the frame's smallest emission factor (from the data-moving wave, over all pdfs, rounded
+// down), is at most the smallest entry the lane has written: if it is below `dim`, or if the step's largest entry
+// falls too far for the next rescaling to be a float, the workgroup gives the sequence up (returns false) and its
+// caller runs it again from the first frame in the log form.  The test errs on the side of giving up.  Every sum a
+// completed run has formed is therefore exact to rounding.  The give-up travels through the step maximum the waves
+// exchange anyway: a lane that sees such a state reports +inf as its maximum.
 //
 // What leaves the kernel: the vectors as they are kept (RecDir::out_linear, for the gradient kernel) or, in the
-// form of the other kernel, normalised rows in log2 units (the data-moving wave takes the logarithms as it copies
-// a vector out); offsets and log Z as there.
+// form of the other kernel, normalised rows as logarithms (the wave that closes a row stages its logarithm; the
+// data-moving wave copies rows out either way); shifts and log Z as there.
 // LDS: xb, the previous / current vector, kXsFixed floats each at addresses 0 and kXbStride; bh 2 x kXsFixed behind
-// them (backward only: beta before the emission is applied); red 64 floats (0-2 step maxima, 4-6 the frames' emission maxima in log2 units, 7
-// scratch, 32-63 the last reduction); er 3 x Es floats, Es = D + 1 rounded up to 4: the emissions as given of the
-// frame in use and of the next two, entry D = -inf (what the dump slot "emits").
+// them (rows on their way out that are not the vector itself: beta before the emission is applied, or either
+// direction's rows as logarithms; absent otherwise); red 64 floats (0-2 step maxima, 4-6 the frames' emission maxima
+// in log2 units, 7 scratch, 8-10 the frames' emission spreads, 32-63 the last reduction); er 3 x Es floats, Es = D + 1
+// rounded up to 4: the emissions as given of the frame in use and of the next two, entry D = -inf (what the dump
+// slot "emits").
 // ---------------------------------------------------------------------------
 __device__ unsigned int g_linear_restarts;   // diagnostic: sequences (x directions) given up by linear_run since the library was loaded
 
