@@ -14,8 +14,8 @@
 //   * Arcs travel in pairs: a unit is, per lane, three 32-bit words {source of arc 0 | source of arc 1 << 16,
 //     2^w of arc 0, 2^w of arc 1} (6 bytes per arc), sources being byte offsets into the state buffer.  A
 //     slice is a whole number of units (its lanes are padded with arcs of weight 0), and a wave's time step
-//     is the units of its slices one after the other.  The first kPResident units of a wave stay in
-//     registers for the whole time loop, the rest is re-read from L2 every step.
+//     is the units of its slices one after the other.  Of a wave's first kPPatterned units kPResident stay
+//     in registers for the whole time loop (which ones: p_streamed), the rest is re-read from L2 every step.
 //   * When a slice ends, every lane holds a row's sum (or a share of it) and needs to know where it goes and
 //     which emission it takes: one 32-bit "close word" per lane and slice {target byte offset | emission
 //     byte offset << 16}, kept in registers too (at most kPMaxClose slices per wave).  Which units end a
@@ -26,8 +26,9 @@
 // served as two halves of 32 lanes, each taking as many cycles as the busiest bank has distinct addresses.
 // With arcs in arbitrary order a gather takes about three times the two cycles it needs.  Which lane walks
 // which row, and in which order a lane walks its arcs, is free, so both are chosen to spread every half's
-// addresses of a step over the banks: rows are first traded between the halves of slices of equal shape
-// until every half's arcs are spread evenly over the banks, then each half's arcs are laid out step by step.
+// addresses of a step over the banks: rows are first traded between the halves of slices that both rows fit
+// until no bank of a half serves more arcs than the slice has steps (as far as that goes), then each half's
+// arcs are given their steps by an edge colouring of the graph lanes x banks (order_half).
 #include <algorithm>
 #include <cmath>
 #include <cstring>
