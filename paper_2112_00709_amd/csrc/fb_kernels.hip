@@ -57,12 +57,6 @@ __device__ __forceinline__ float tmin(float a, float b)
     asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
     return r;
 }
-__device__ __forceinline__ float tmin3(float a, float b, float c)
-{
-    float r;
-    asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-    return r;
-}
 __device__ __forceinline__ float tmax3(float a, float b, float c)
 {
     float r;
@@ -865,11 +859,10 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
 //
 // Range guard.  A float holds what lies within 2^-126 of the scale; the log form holds everything.  An entry that is
 // not the semiring zero must not come to lie below `dim`, the value under which its product with the graph's smallest
-// weight could be flushed to zero.  A lane keeps the smallest row sum above zero it has formed in a step; at the
-// step's end that, times the frame's smallest emission factor (from the data-moving wave, over all pdfs, rounded
-// down), is at most the smallest entry the lane has written: if it is below `dim`, or if the step's largest entry
-// falls too far for the next rescaling to be a float, the workgroup gives the sequence up (returns false) and its
-// caller runs it again from the first frame in the log form.  The test errs on the side of giving up.  Every sum a
+// weight could be flushed to zero.  A lane keeps the smallest entry it has written in a step for a row whose sum is
+// above zero (an entry that an emission factor too small for a float has turned into zero included); if that is
+// below `dim`, or if the step's largest entry falls too far for the next rescaling to be a float, the workgroup gives
+// the sequence up (returns false) and its caller runs it again from the first frame in the log form.  Every sum a
 // completed run has formed is therefore exact to rounding.  The give-up travels through the step maximum the waves
 // exchange anyway: a lane that sees such a state reports +inf as its maximum.
 //
@@ -879,7 +872,7 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
 // LDS: xb, the previous / current vector, kXsFixed floats each at addresses 0 and kXbStride; bh 2 x kXsFixed behind
 // them (rows on their way out that are not the vector itself: beta before the emission is applied, or either
 // direction's rows as logarithms; absent otherwise); red 64 floats (0-2 step maxima, 4-6 the frames' emission maxima
-// in log2 units, 7 scratch, 8-10 the frames' emission spreads, 32-63 the last reduction); er 3 x Es floats, Es = D + 1
+// in log2 units, 7 scratch, 32-63 the last reduction); er 3 x Es floats, Es = D + 1
 // rounded up to 4: the emissions as given of the frame in use and of the next two, entry D = -inf (what the dump
 // slot "emits").
 // ---------------------------------------------------------------------------
@@ -918,7 +911,6 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
     float *red = staged ? bh + 2 * XF : bh;
     float *er = red + 64;
     float *emaxw = red + 4;
-    float *espw = red + 8;                       // per frame: log2 of (smallest / largest) emission factor, less a margin
 
     const float *em_seq = P.emis + (size_t)b * P.N * P.D;
     const size_t out_ld = (size_t)(R_.out_ld ? R_.out_ld : K);
@@ -964,33 +956,23 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
         }
     };
     auto staged_wait = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
-    // The largest emission of a staged frame, in log2 units (0 if there is none above zero-bar), and how far below it the
-    // smallest lies (rounded down by one; -inf if a pdf has probability zero).  Over all pdfs, whether a state of the graph
-    // is tied to them or not: any scale serves, and a bound that is too careful only makes a run give up early.  16 bytes
-    // per lane and read (the arc-walking waves keep the LDS queue full: few, wide reads).  The last group of four always
-    // holds an entry behind the row (-inf: staging never writes there), so there are n4 - 1 whole groups of pdfs.
-    auto emax_of = [&](const float *row, float &spread) {
-        float m = -INFINITY, mn = INFINITY;
+    // The largest emission of a staged frame, in log2 units (0 if there is none above zero-bar).  Over all pdfs, whether
+    // a state of the graph is tied to them or not: any scale serves.  16 bytes per lane and read (the arc-walking waves
+    // keep the LDS queue full: few, wide reads); what lies behind the row in its last group is -inf.
+    auto emax_of = [&](const float *row) {
+        float m = -INFINITY;
         const float4 *r4 = (const float4 *)row;
-        const int n4 = Es / 4;
+        const int n4e = Es / 4;
         constexpr int U = 8;
-        for (int j0 = 0; j0 * kWave < n4; j0 += U) {
+        for (int j0 = 0; j0 * kWave < n4e; j0 += U) {
             float4 v[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) v[u] = r4[min((j0 + u) * kWave + lane, n4 - 1)];
+            for (int u = 0; u < U; ++u) v[u] = r4[min((j0 + u) * kWave + lane, n4e - 1)];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                m = tmax3(tmax3(m, v[u].x, v[u].y), v[u].z, v[u].w);
-                const float c = tmin3(tmin3(mn, v[u].x, v[u].y), v[u].z, v[u].w);
-                mn = (j0 + u) * kWave + lane < n4 - 1 ? c : mn;
-            }
+            for (int u = 0; u < U; ++u) m = tmax3(tmax3(m, v[u].x, v[u].y), v[u].z, v[u].w);
         }
-        if (lane < (P.D & 3)) mn = tmin(mn, row[(P.D & ~3) + lane]);   // the pdfs of the last group
         m = wave_max(m) * (float)kLog2e;
-        mn = -wave_max(-mn);
-        const float em = m > -INFINITY ? m : 0.0f;
-        spread = mn < INFINITY ? fmaf(mn, (float)kLog2e, -em) - 1.0f : 0.0f;
-        return em;
+        return m > -INFINITY ? m : 0.0f;
     };
     const CloneDesc *cdesc = S.clones;
     // a finished vector -> global memory, coalesced; a cloned state leaves as the sum of its clones.  Either as it is
@@ -1063,16 +1045,15 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
     if (tid < 12) er[(tid >> 2) * Es + Es - 4 + (tid & 3)] = -INFINITY;   // behind the rows (staging never writes there; the row's own last entries are rewritten)
     __syncthreads();
     if (tid < 3) er[tid * Es + P.D] = -INFINITY;   // what the dump slot "emits": its entry stays zero whatever the frame's scale
-    if (tid < 12) red[tid] = tid == 7 ? -INFINITY : 0.0f;
+    if (tid < 8) red[tid] = tid == 7 ? -INFINITY : 0.0f;
     __syncthreads();
     if (io_wave) {
         stage(frame(0), er);
         if (Tn > 1) stage(frame(1), er + Es);
         staged_wait();
-        float sp0 = 0.0f, sp1 = 0.0f;
-        const float e0 = emax_of(er, sp0);
-        const float e1 = Tn > 1 ? emax_of(er + Es, sp1) : 0.0f;
-        if (lane == 0) { emaxw[0] = e0; emaxw[1] = e1; espw[0] = sp0; espw[1] = sp1; }
+        const float e0 = emax_of(er);
+        const float e1 = Tn > 1 ? emax_of(er + Es) : 0.0f;
+        if (lane == 0) { emaxw[0] = e0; emaxw[1] = e1; }
         if (Tn > 2) stage(frame(2), er + 2 * Es);   // lands while step 1 runs
     }
     __syncthreads();
@@ -1132,9 +1113,8 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
             }
             staged_wait();   // frame i+1, requested a whole step ago, is in LDS
             if (i + 1 < Tn) {
-                float sp;
-                const float en = emax_of(er + ((i + 1) % 3) * Es, sp);
-                if (lane == 0) { emaxw[(i + 1) % 3] = en; espw[(i + 1) % 3] = sp; }   // (the words of frame i - 2: read for the last time in step i - 1)
+                const float en = emax_of(er + ((i + 1) % 3) * Es);
+                if (lane == 0) emaxw[(i + 1) % 3] = en;   // (the word of frame i - 2: read for the last time in step i - 1)
             }
             if (i + 2 < Tn) stage(frame(i + 2), er + ((i + 2) % 3) * Es);   // buffer of frame i-1: no longer read
             write_row(frame(i - 1), staged ? bh + cur * XF : xb + cur * Xs);
@@ -1221,9 +1201,9 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
             rescale(mx, sc, nls);
             const float emx = emaxw[i % 3];
             wmax = 0.0f;
-            // the smallest row sum above zero this lane has seen, as its bit pattern less one (so that zero wraps to the
-            // largest key and the keys of positive floats keep their order)
-            uint32_t wlow = 0xffffffffu;
+            // the smallest entry this lane has written for a row whose sum is above zero, as its bit pattern (which keeps
+            // the order of floats that are not negative)
+            uint32_t wlow = 0x7f800000u;
             float acc = 0.0f;
             // the wave's constants, opaque at every step: what is derived from them is computed where it is used (a
             // scalar instruction or two) instead of being kept in scalar registers that do not exist
@@ -1277,7 +1257,7 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
                     *(float *)((char *)bn + tgt) = log_rows ? to_log(o) : o;
                 }
                 wmax = tmax(wmax, px);
-                wlow = min(wlow, __float_as_uint(pb) - 1u);
+                wlow = min(wlow, __float_as_uint(pb > 0.0f ? px : INFINITY));
                 acc = 0.0f;
             };
             // position u of the patterned part: which registers hold it
@@ -1353,11 +1333,8 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
                 constexpr int m = decltype(mc)::value;
                 request_at(ring[m], p_streamed_pos(m));
             }, std::make_integer_sequence<int, kPRing - 1>{});
-            // An entry below the range: the run gives up (see above).  Judged by the smallest row sum and the frame's
-            // smallest emission factor together, which is at most the smallest entry: one test per lane and step instead
-            // of one per row, at the price of giving up a little early.  (A product too small for a float is zero or
-            // subnormal: below the range as well.)
-            const bool low = wlow != 0xffffffffu && __uint_as_float(wlow + 1u) * fexp2(espw[i % 3]) < kLinDimP;
+            // an entry below the range: the run gives up (see above)
+            const bool low = wlow < __float_as_uint(kLinDimP);
             put_max(i, low ? INFINITY : wmax);
             __syncthreads();
             return true;

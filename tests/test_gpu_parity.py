@@ -592,6 +592,64 @@ def test_probability_domain_gives_up_and_falls_back(fb):
     assert r4 - r3 == 4
 
 
+@pytest.mark.parametrize("case", ["odd_sizes", "clones", "one_frame", "big_emissions", "sparse_ends"])
+def test_probability_domain_shapes(fb, case):
+    """Shapes the probability-domain recursion has code paths of its own for, every sequence against the oracle:
+    a number of pdfs and of states that are not multiples of four (rows staged and stored entry by entry, the
+    emission row's last group); hub rows long enough for clones (a cloned state leaves as the sum of its clones, as
+    a logarithm here); sequences of one and two frames and a batch of one; emissions far from zero (only
+    differences to the frame's largest matter); few start and end states."""
+    rng = np.random.default_rng(90)
+    if case == "odd_sizes":
+        g = wl.random_graph(rng, 1501, 85, zipf_s=1.2, mean_extra_deg=5.0)
+        D, lengths = 85, np.array([9, 4, 12], dtype=np.int32)
+    elif case == "clones":
+        g = wl.config4(K=3500, B=2, Nmin=3, Nmax=4, D=64).den
+        D, lengths = 64, np.array([7, 10], dtype=np.int32)
+    elif case == "one_frame":
+        g = wl.random_graph(rng, 1500, 60, zipf_s=1.1, mean_extra_deg=6.0)
+        D, lengths = 60, np.array([1, 2, 1, 5], dtype=np.int32)
+    elif case == "big_emissions":
+        g = wl.random_graph(rng, 1500, 60, zipf_s=1.1, mean_extra_deg=6.0)
+        D, lengths = 60, np.array([8], dtype=np.int32)
+    else:
+        g0 = wl.random_graph(rng, 1500, 60, zipf_s=1.1, mean_extra_deg=6.0)
+        init = np.full(g0.K, -np.inf, dtype=np.float32); init[[3, 700]] = np.log(0.5)
+        final = np.full(g0.K, -np.inf, dtype=np.float32); final[rng.integers(0, g0.K, size=40)] = 0.0
+        g = wl.Graph(g0.K, g0.src, g0.dst, g0.logw, g0.pdf, init, final)
+        D, lengths = 60, np.array([10, 6], dtype=np.int32)
+    B, N = lengths.size, int(lengths.max()) + 1
+    emis = (rng.standard_normal((B, N, D)) * 2.0).astype(np.float32)
+    if case == "big_emissions":
+        emis += 700.0
+        emis[0, 3] -= 1500.0
+    G = fb.graph_from(g, D)
+    assert fb.fb_graph_linear_weights(G) == 2
+    G.destroy()
+    r0 = fb.fb_debug_linear_restarts()
+    compare_fb(fb, g, D, emis, lengths, name=f"probability domain, {case}")
+    assert fb.fb_debug_linear_restarts() == r0
+
+
+def test_lfmmi_with_sequences_that_fall_back(fb):
+    """Inside the LF-MMI call the denominator's rows reach the gradient kernel as the probability-domain kernel keeps
+    them, except those of a sequence (and direction) that gave up and was redone in the log form: a batch that mixes
+    both, every sequence against the oracle, both entry points.  Three causes of giving up are present: a pdf far
+    below the others in one frame, a pdf of probability zero throughout, and (in this small graph as drawn) states
+    that only feed one another, whose forward values fall below the range after some twenty frames."""
+    w = wl.config5(K=1500, B=36, Lmin=3, Lmax=10, D=100)
+    emis = w.emis.copy()
+    long_ones = np.argsort(-w.lengths)[:3]
+    emis[long_ones[0], 4, 17] = -400.0
+    emis[long_ones[1], :, 55] = -np.inf
+    r0 = fb.fb_debug_linear_restarts()
+    compare_lfmmi(fb, w, name="lfmmi with fallbacks, plain entry point", emis=emis)
+    r1 = fb.fb_debug_linear_restarts()
+    assert 4 <= r1 - r0 < w.B                                 # of 2 B runs: some fall back, most do not
+    compare_lfmmi(fb, w, name="lfmmi with fallbacks, ragged", ragged=True, emis=emis)
+    assert fb.fb_debug_linear_restarts() - r1 == r1 - r0      # the same sequences, whatever the entry point
+
+
 def test_lfmmi_calls_from_two_host_threads(fb):
     """Two host threads call lfmmi_loss_grad at the same time on the same graphs, each on its own inputs, workspace,
     outputs and stream (the library's side streams and events are shared by the process and guarded by a lock
