@@ -1644,8 +1644,10 @@ __global__ __launch_bounds__(kPostThreads) void fb_posterior_kernel(const PostPa
 // recursions also left the running sums of their offsets (PostParams::cum_a, cum_b:
 // A_n, B_n with alpha_n = stored row + A_n, beta_n = stored row + B_n, log2 units)
 // and log Z.  Same sums in the same order as fb_posterior_kernel, organised for speed:
-// grid = (ceil(N / frames_per_block), B), 9 waves, one workgroup barrier per frame.
-// Waves 0-7 work on the denominator: a thread keeps, for the whole block, the
+// grid = (ceil(N / frames_per_block), B), 8 waves, one workgroup barrier per frame.  (Eight, two per SIMD: two
+// workgroups then share a compute unit.  With nine - three on one SIMD - the second workgroup was never placed
+// beside the first, whatever the occupancy calculation says, and the kernel ran at 3/4 of its present rate.)
+// Waves 0-6 work on the denominator: a thread keeps, for the whole block, the
 // places of "its" states in pdf order and the state ranges of "its" pdfs in
 // registers, the rows of the next frame travel from HBM into registers while the
 // current frame is worked on, and the exponentials go to LDS in pdf order, so that a
@@ -1655,22 +1657,24 @@ __global__ __launch_bounds__(kPostThreads) void fb_posterior_kernel(const PostPa
 // behind it are needed (the values are still normalised by their own sum, so a drift
 // of the float recursions cancels).  The denominator waves store their pdf posteriors
 // straight from the sums (no staging of the row in LDS), adding the numerator's value
-// for the pdf, which wave 8 - it works on the numerator of the same frame at the same
+// for the pdf, which wave 7 - it works on the numerator of the same frame at the same
 // time, with wave-level reductions only - has left in a small list (two buffers, by
 // frame parity) before the frame's barrier; the exponentials in pdf order have two
 // buffers as well, so nothing of frame n + 1 overwrites what frame n still reads.
-// LDS: red [2][16] sums of waves 0-7; tb [2][K0 rounded to 4, + 4]; nval [2][Rcap] the numerator's pdf
+// LDS: red [2][16] sums of waves 0-6; tb [2][K0 rounded to 4, + kGradSlack]; nval [2][Rcap] the numerator's pdf
 // posteriors by pdf row; en [Kcap] numerator exponentials; nidx [D] 16-bit: pdf -> its row in
 // this sequence's numerator + 1, 0 = none; the numerator tables.
 // ---------------------------------------------------------------------------
-constexpr int kGradMain = 512, kGradThreads = kGradMain + kWave;
-constexpr int kGradU = 3;        // 16-byte pieces of a denominator row per thread: 6144 states
-constexpr int kGradPdf = 6;      // pdfs per thread: 3072 pdfs
+constexpr int kGradMain = 448, kGradThreads = kGradMain + kWave;
+constexpr int kGradU = 4;        // 16-byte pieces of a denominator row per thread: 7168 states
+constexpr int kGradPdf = 8;      // pdfs per thread: 3584 pdfs
 constexpr int kGradNumU = 8;     // numerator states (and pdf rows) per lane: 512
 constexpr int kGradNumK = kGradNumU * kWave;
+constexpr int kGradAhead = 8;    // states of a pdf whose exponentials are read at once, before any of them is added
+constexpr int kGradSlack = 4 + kGradAhead;   // floats behind a buffer of exponentials: reads ahead may pass the last state
 
 template <class NT>
-__global__ __launch_bounds__(kGradThreads, 5) void fb_grad_kernel(const PostParams P)
+__global__ __launch_bounds__(kGradThreads, 4) void fb_grad_kernel(const PostParams P)
 {
     extern __shared__ double lds_raw[];
     constexpr int MT = kGradMain, U = kGradU, NU = kGradNumU;
@@ -1681,10 +1685,10 @@ __global__ __launch_bounds__(kGradThreads, 5) void fb_grad_kernel(const PostPara
     const int T = min(max(P.lengths[b], 0), P.N);
     const int n0 = blockIdx.x * P.frames_per_block;
     const int n_end = min(min(n0 + P.frames_per_block, P.N), T);   // real frames of this chunk: [n0, n_end)
-    const bool has_num = P.n_graph == 2;   // one graph: the shared graph's share alone (no numerators: wave 8 only keeps the barriers)
+    const bool has_num = P.n_graph == 2;   // one graph: the shared graph's share alone (no numerators: wave 7 only keeps the barriers)
     const PostGraph &G0 = P.g[0], &G1 = P.g[1];
     const int K0 = G0.pdfs.sub[0].K, D = P.D;
-    const int K0r = ((K0 + 3) & ~3) + 4;
+    const int K0r = ((K0 + 3) & ~3) + kGradSlack;
     const PdfSub ps1 = has_num ? G1.pdfs.sub[b] : PdfSub{};
     const int K1 = ps1.K, R1 = ps1.n_rows;
 
@@ -1736,7 +1740,6 @@ __global__ __launch_bounds__(kGradThreads, 5) void fb_grad_kernel(const PostPara
             ca = P.cum_a[(size_t)b * P.N + n];
             cb = P.cum_b[(size_t)b * P.N + n];
         };
-        issue(n0);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int q = u * MT + tid;
@@ -1747,16 +1750,32 @@ __global__ __launch_bounds__(kGradThreads, 5) void fb_grad_kernel(const PostPara
             const int d = j * MT + tid;
             prange[j] = d < D ? (uint32_t)G0.pdfs.row_ptr[d] | ((uint32_t)G0.pdfs.row_ptr[d + 1] << 16) : 0u;
         }
+        // the most states any pdf of this wave has: how far the reads ahead below go is the same for all its lanes
+        float most = 0.0f;
+#pragma unroll
+        for (int j = 0; j < kGradPdf; ++j) most = tmax(most, (float)((prange[j] >> 16) - (prange[j] & 0xffffu)));
+        const int wcnt = __builtin_amdgcn_readfirstlane((int)wave_max(most));
+        // The frames of the block, for one form of the rows: 2 both hold values (every sequence the probability-domain
+        // recursion has carried through), 0 both hold logs, 1 one of each (a sequence that fell back in one direction).
+        auto frames = [&](auto form_c) {
+        constexpr int form = decltype(form_c)::value;
+        issue(n0);
         for (int n = n0; n < n_end; ++n) {
             const int par = (n - n0) & 1;
             float *tbn = tb + par * K0r;
+            // (the packed places and ranges stay packed between frames: unpacked once and for all they would not fit
+            // the registers)
+#pragma unroll
+            for (int u = 0; u < U; ++u) asm volatile("" : "+v"(posr[u].x), "+v"(posr[u].y));
+#pragma unroll
+            for (int j = 0; j < kGradPdf; ++j) asm volatile("" : "+v"(prange[j]));
             // log2 Z - A_n - B_n; a sequence without any path (log Z = -inf) has no posteriors
             const double shift_d = z2 - (double)ca - (double)cb;
             const bool mass = shift_d > -1.0e300 && shift_d < 1.0e300;
             const float shift = mass ? (float)shift_d : 0.0f;
             // 2^-shift in double, for rows that hold values instead of logs (their range is a float's, times the offsets')
             double pow_shift = 0.0;
-            if (any_lin && mass) {
+            if (form != 0 && mass) {
                 const double t = fmin(fmax(-shift_d, -2000.0), 2000.0), ti = floor(t);
                 pow_shift = ldexp((double)fexp2((float)(t - ti)), (int)ti);
             }
@@ -1766,7 +1785,12 @@ __global__ __launch_bounds__(kGradThreads, 5) void fb_grad_kernel(const PostPara
                 const int q = u * MT + tid;
                 if (q * 4 < K0) {
                     float e[4];
-                    if (any_lin) {   // rows that hold the values themselves: the posterior is their product, formed in double
+                    if (form == 2) {   // rows that hold the values themselves: the posterior is their product, formed in double
+                        e[0] = (float)((double)pa[u].x * (double)pb[u].x * pow_shift);
+                        e[1] = (float)((double)pa[u].y * (double)pb[u].y * pow_shift);
+                        e[2] = (float)((double)pa[u].z * (double)pb[u].z * pow_shift);
+                        e[3] = (float)((double)pa[u].w * (double)pb[u].w * pow_shift);
+                    } else if (form == 1) {
                         e[0] = (float)(as_value(pa[u].x, lin_a) * as_value(pb[u].x, lin_b) * pow_shift);
                         e[1] = (float)(as_value(pa[u].y, lin_a) * as_value(pb[u].y, lin_b) * pow_shift);
                         e[2] = (float)(as_value(pa[u].z, lin_a) * as_value(pb[u].z, lin_b) * pow_shift);
@@ -1785,6 +1809,7 @@ __global__ __launch_bounds__(kGradThreads, 5) void fb_grad_kernel(const PostPara
                     tbn[posr[u].x & 0xffffu] = e[0]; tbn[posr[u].x >> 16] = e[1];
                     tbn[posr[u].y & 0xffffu] = e[2]; tbn[posr[u].y >> 16] = e[3];
                 }
+                __builtin_amdgcn_sched_barrier(0);   // one piece at a time: the doubles of all at once would not fit the registers
             }
             if (n + 1 < n_end) issue(n + 1);   // the next frame starts its trip now
             sum = wave_sum(sum);
@@ -1796,19 +1821,47 @@ __global__ __launch_bounds__(kGradThreads, 5) void fb_grad_kernel(const PostPara
             const float scale = sum > 0.0f ? G0.sign / sum : 0.0f;
             float *prow = P.pdf_out + ((size_t)b * P.N + n) * D;
             const float *nv = nval + par * G1.Rcap;
+            // A pdf's exponentials are neighbours in the buffer.  The first kGradAhead of each of two pdfs are read
+            // at once (as far as the wave's longest pdf goes; what lies behind a pdf's own states is read and not
+            // used), so that a thread waits for LDS once per two pdfs and not once per state; they are added in
+            // ascending order of states as before, and what a pdf has beyond them in a loop of its own.
+            constexpr int H = 2;
+            static_assert(kGradPdf % H == 0, "pdfs per thread come in groups");
 #pragma unroll
-            for (int j = 0; j < kGradPdf; ++j) {
-                const int d = j * MT + tid;
-                if (d < D) {
+            for (int h = 0; h < kGradPdf; h += H) {
+                float t[H][kGradAhead];
+                uint32_t r[H];
+#pragma unroll
+                for (int jj = 0; jj < H; ++jj) {
+                    const float *seg = tbn + (prange[h + jj] & 0xffffu);
+#pragma unroll
+                    for (int i = 0; i < kGradAhead; i += 2)
+                        if (wcnt > i) { t[jj][i] = seg[i]; t[jj][i + 1] = seg[i + 1]; }
+                    r[jj] = nidx[min((h + jj) * MT + tid, D - 1)];
+                }
+                float nvv[H];
+#pragma unroll
+                for (int jj = 0; jj < H; ++jj) nvv[jj] = nv[r[jj] ? r[jj] - 1 : 0];   // (no numerators: never used)
+#pragma unroll
+                for (int jj = 0; jj < H; ++jj) {
+                    const int d = (h + jj) * MT + tid;
+                    const int begin = (int)(prange[h + jj] & 0xffffu), end = (int)(prange[h + jj] >> 16);
                     float acc = 0.0f;
-                    for (int i = (int)(prange[j] & 0xffffu); i < (int)(prange[j] >> 16); ++i) acc += tbn[i];   // ascending states
-                    const int r = nidx[d];
+#pragma unroll
+                    for (int i = 0; i < kGradAhead; ++i)
+                        if (wcnt > i) acc += begin + i < end ? t[jj][i] : 0.0f;
+                    if (wcnt > kGradAhead)
+                        for (int i = begin + kGradAhead; i < end; ++i) acc += tbn[i];
                     float v = acc * scale;
-                    if (r) v += nv[r - 1];
-                    prow[d] = v;
+                    if (r[jj]) v += nvv[jj];
+                    if (d < D) prow[d] = v;
                 }
             }
         }
+        };
+        if (lin_a && lin_b) frames(std::integral_constant<int, 2>());
+        else if (any_lin) frames(std::integral_constant<int, 1>());
+        else frames(std::integral_constant<int, 0>());
     } else {
         NT qa[NU], qb[NU];            // rows of the frame being prefetched / worked on
         auto issue = [&](int n) {
@@ -2130,7 +2183,7 @@ size_t gradient_lds_bytes(const PostParams &p)
 {
     const PostGraph &d = p.g[0], &n = p.g[1];
     const size_t nR = p.n_graph == 2 ? (size_t)n.Rcap : 0, nK = p.n_graph == 2 ? (size_t)n.Kcap : 0;   // one graph: no numerator tables
-    return 128 + (2 * ((size_t)((d.Kcap + 3) & ~3) + 4) + 2 * nR + nK) * 4 + ((size_t)((p.D + 1) & ~1) + nR * 2 + 1 + nK + 3) / 2 * 4;
+    return 128 + (2 * ((size_t)((d.Kcap + 3) & ~3) + kGradSlack) + 2 * nR + nK) * 4 + ((size_t)((p.D + 1) & ~1) + nR * 2 + 1 + nK + 3) / 2 * 4;
 }
 
 int launch_gradient(const PostParams &p, size_t lds_bytes, void *stream)
