@@ -1673,6 +1673,14 @@ constexpr int kGradNumK = kGradNumU * kWave;
 constexpr int kGradAhead = 8;    // states of a pdf whose exponentials are read at once, before any of them is added
 constexpr int kGradSlack = 4 + kGradAhead;   // floats behind a buffer of exponentials: reads ahead may pass the last state
 
+// a 16-byte load of data that is read once: it should not push the recursion kernel's arc plan out of L2
+__device__ __forceinline__ float4 nt_load4(const float4 *p)
+{
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const f4 v = __builtin_nontemporal_load((const f4 *)p);
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
 template <class NT>
 __global__ __launch_bounds__(kGradThreads, 4) void fb_grad_kernel(const PostParams P)
 {
@@ -1735,7 +1743,7 @@ __global__ __launch_bounds__(kGradThreads, 4) void fb_grad_kernel(const PostPara
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int q = u * MT + tid;
-                if (q * 4 < K0) { pa[u] = ar[q]; pb[u] = br[q]; }
+                if (q * 4 < K0) { pa[u] = nt_load4(ar + q); pb[u] = nt_load4(br + q); }
             }
             ca = P.cum_a[(size_t)b * P.N + n];
             cb = P.cum_b[(size_t)b * P.N + n];
@@ -1854,7 +1862,7 @@ __global__ __launch_bounds__(kGradThreads, 4) void fb_grad_kernel(const PostPara
                         for (int i = begin + kGradAhead; i < end; ++i) acc += tbn[i];
                     float v = acc * scale;
                     if (r[jj]) v += nvv[jj];
-                    if (d < D) prow[d] = v;
+                    if (d < D) __builtin_nontemporal_store(v, prow + d);
                 }
             }
         }
