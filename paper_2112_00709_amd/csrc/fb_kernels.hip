@@ -1700,8 +1700,8 @@ __global__ __launch_bounds__(kGradThreads, 4) void fb_grad_kernel(const PostPara
     const PdfSub ps1 = has_num ? G1.pdfs.sub[b] : PdfSub{};
     const int K1 = ps1.K, R1 = ps1.n_rows;
 
-    float *red = (float *)lds_raw;                       // [2][16]
-    float *tb = red + 32;                                // [2][K0r]
+    float *red = (float *)lds_raw;                       // [2][16] sums, [2][16] maxima
+    float *tb = red + 64;                                // [2][K0r]
     float *nval = tb + 2 * K0r;                          // [2][Rcap]
     float *en = nval + 2 * G1.Rcap;                      // [Kcap]
     uint16_t *nidx = (uint16_t *)(en + G1.Kcap);         // [D rounded to 2]
@@ -1726,6 +1726,7 @@ __global__ __launch_bounds__(kGradThreads, 4) void fb_grad_kernel(const PostPara
         uint2 posr[U];                // places (4 x 16 bit) of the thread's states in pdf order
         uint32_t prange[kGradPdf];    // state ranges (begin | end << 16) of the thread's pdfs tid, tid + MT, ...
         const double z2 = P.logz ? P.logz[b] * kLog2e : 0.0;   // log2 Z of the shared graph
+        const bool by_max = !P.cum_a;   // no offsets: the frame's exponentials are taken relative to its largest sum
         // the form of this sequence's rows: the values themselves (what the probability-domain recursion leaves), or logs
         const bool lin_a = G0.fmt_a && G0.fmt_a[b] != 0, lin_b = G0.fmt_b && G0.fmt_b[b] != 0;
         const bool any_lin = lin_a || lin_b;
@@ -1745,8 +1746,8 @@ __global__ __launch_bounds__(kGradThreads, 4) void fb_grad_kernel(const PostPara
                 const int q = u * MT + tid;
                 if (q * 4 < K0) { pa[u] = nt_load4(ar + q); pb[u] = nt_load4(br + q); }
             }
-            ca = P.cum_a[(size_t)b * P.N + n];
-            cb = P.cum_b[(size_t)b * P.N + n];
+            ca = by_max ? 0.0f : P.cum_a[(size_t)b * P.N + n];
+            cb = by_max ? 0.0f : P.cum_b[(size_t)b * P.N + n];
         };
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -1778,7 +1779,29 @@ __global__ __launch_bounds__(kGradThreads, 4) void fb_grad_kernel(const PostPara
 #pragma unroll
             for (int j = 0; j < kGradPdf; ++j) asm volatile("" : "+v"(prange[j]));
             // log2 Z - A_n - B_n; a sequence without any path (log Z = -inf) has no posteriors
-            const double shift_d = z2 - (double)ca - (double)cb;
+            double shift_d = z2 - (double)ca - (double)cb;
+            if (form == 0 && by_max) {
+                // Rows without offsets (normalised logs as fb_alpha / fb_beta return them): the largest sum of the
+                // frame takes the place of log2 Z - A_n - B_n, at the price of a second barrier per frame.
+                float mx = -INFINITY;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int q = u * MT + tid;
+                    if (q * 4 < K0) {
+                        mx = tmax(mx, pa[u].x + pb[u].x);
+                        if (q * 4 + 1 < K0) mx = tmax(mx, pa[u].y + pb[u].y);
+                        if (q * 4 + 2 < K0) mx = tmax(mx, pa[u].z + pb[u].z);
+                        if (q * 4 + 3 < K0) mx = tmax(mx, pa[u].w + pb[u].w);
+                    }
+                }
+                mx = wave_max(mx);
+                if (lane == 0) red[32 + par * 16 + wave] = mx;
+                __syncthreads();
+                mx = red[32 + par * 16];
+#pragma unroll
+                for (int w = 1; w < MT / kWave; ++w) mx = tmax(mx, red[32 + par * 16 + w]);
+                shift_d = mx > -INFINITY ? (double)(mx * G0.in_scale) : -INFINITY;
+            }
             const bool mass = shift_d > -1.0e300 && shift_d < 1.0e300;
             const float shift = mass ? (float)shift_d : 0.0f;
             // 2^-shift in double, for rows that hold values instead of logs (their range is a float's, times the offsets')
@@ -1881,7 +1904,11 @@ __global__ __launch_bounds__(kGradThreads, 4) void fb_grad_kernel(const PostPara
             }
         };
         if (!has_num) {
-            for (int n = n0; n < n_end; ++n) __syncthreads();
+            const bool two = !P.cum_a && !(G0.fmt_a && G0.fmt_a[b] != 0) && !(G0.fmt_b && G0.fmt_b[b] != 0);   // as the other waves decide
+            for (int n = n0; n < n_end; ++n) {
+                if (two) __syncthreads();
+                __syncthreads();
+            }
             return;
         }
         issue(n0);
@@ -2173,13 +2200,16 @@ int launch_posteriors(const PostParams &p, size_t lds_bytes, void *stream)
 
 bool gradient_kernel_applies(const PostParams &p)
 {
-    if (!p.cum_a || !p.cum_b || !p.logz || !p.pdf_out || p.accumulate) return false;
+    if (!p.pdf_out || p.accumulate) return false;
+    const bool offsets = p.cum_a && p.cum_b && p.logz;
     if (p.n_graph == 1) {   // the shared graph's share alone: no numerators
         const PostGraph &d = p.g[0];
+        // without the offsets of the rows only rows of logarithms (no format flags), relative to each frame's maximum
+        if (!offsets && (p.cum_a || p.cum_b || p.logz || d.fmt_a || d.fmt_b)) return false;
         return d.shared && !d.f64 && !d.state_post && d.pdfs.pos && (d.ld & 3) == 0 && d.ld >= ((d.Kcap + 3) & ~3) &&
                d.Kcap <= kGradMain * 4 * kGradU && (((uintptr_t)d.a | (uintptr_t)d.b) & 15) == 0 && p.D <= kGradMain * kGradPdf;
     }
-    if (p.n_graph != 2) return false;
+    if (p.n_graph != 2 || !offsets) return false;
     const PostGraph &d = p.g[0], &n = p.g[1];
     return d.shared && !d.f64 && !d.state_post && d.pdfs.pos && (d.ld & 3) == 0 && d.ld >= ((d.Kcap + 3) & ~3) &&
            d.Kcap <= kGradMain * 4 * kGradU &&
@@ -2191,7 +2221,7 @@ size_t gradient_lds_bytes(const PostParams &p)
 {
     const PostGraph &d = p.g[0], &n = p.g[1];
     const size_t nR = p.n_graph == 2 ? (size_t)n.Rcap : 0, nK = p.n_graph == 2 ? (size_t)n.Kcap : 0;   // one graph: no numerator tables
-    return 128 + (2 * ((size_t)((d.Kcap + 3) & ~3) + kGradSlack) + 2 * nR + nK) * 4 + ((size_t)((p.D + 1) & ~1) + nR * 2 + 1 + nK + 3) / 2 * 4;
+    return 256 + (2 * ((size_t)((d.Kcap + 3) & ~3) + kGradSlack) + 2 * nR + nK) * 4 + ((size_t)((p.D + 1) & ~1) + nR * 2 + 1 + nK + 3) / 2 * 4;
 }
 
 int launch_gradient(const PostParams &p, size_t lds_bytes, void *stream)

@@ -53,9 +53,11 @@ def gpu_forward_backward(fb, g, D, emis, lengths, state="auto"):
     a, acum, za = fb.fb_alpha(G, e, l)
     b, bcum, zb = fb.fb_beta(G, e, l)
     gam, rho = fb.fb_posteriors(G, a, b, l, B, N)
+    # the pdf posteriors alone: for a shared graph of fitting size another kernel than the one above
+    _, rho_only = fb.fb_posteriors(G, a, b, l, B, N, want_state=False)
     torch.cuda.synchronize()
     out = dict(alpha=host(a), beta=host(b), acum=host(acum), bcum=host(bcum),
-               logz=host(za), logz_b=host(zb), gamma=host(gam), rho=host(rho))
+               logz=host(za), logz_b=host(zb), gamma=host(gam), rho=host(rho), rho_only=host(rho_only))
     G.destroy()
     return out
 
@@ -103,6 +105,7 @@ def compare_fb(fb, g, D, emis, lengths, sel=None, name="", state="auto", post_to
                 assert abs(z - wz) <= TOL_LOGZ_REL * max(1.0, abs(wz)), f"{name} b={b}: logZ {z} vs {wz}"
         if np.isneginf(wz):
             assert np.all(seq_view(g, out["gamma"], b, T) == 0) and np.all(out["rho"][b] == 0)
+            assert np.all(out["rho_only"][b] == 0)
             continue
         check_log_rows(seq_view(g, out["alpha"], b, T), out["acum"][b, :T], ref.alpha[i], f"{name} alpha b={b}")
         check_log_rows(seq_view(g, out["beta"], b, T), out["bcum"][b, :T], ref.beta[i],
@@ -111,12 +114,14 @@ def compare_fb(fb, g, D, emis, lengths, sel=None, name="", state="auto", post_to
         dr = np.abs(out["rho"][b] - ref.rho[i]).max()
         assert dg <= post_tol, f"{name} b={b}: state posterior err {dg}"
         assert dr <= post_tol, f"{name} b={b}: pdf posterior err {dr}"
+        dr = np.abs(out["rho_only"][b] - ref.rho[i]).max()
+        assert dr <= post_tol, f"{name} b={b}: pdf posterior err {dr} (pdf posteriors alone)"
     # padded frames, every sequence
     N = emis.shape[1]
     for b in range(B):
         T = int(lengths[b])
         if T < N:
-            assert np.all(out["rho"][b, T:] == 0)
+            assert np.all(out["rho"][b, T:] == 0) and np.all(out["rho_only"][b, T:] == 0)
             pad = out["gamma"][T:, g.state_off[b]:g.state_off[b + 1]] if g.packed else out["gamma"][b, T:]
             assert np.all(pad == 0)
             assert np.all(out["acum"][b, T:] == 0) and np.all(out["bcum"][b, T:] == 0)
