@@ -1661,7 +1661,10 @@ __global__ __launch_bounds__(kPostThreads) void fb_posterior_kernel(const PostPa
 // time, with wave-level reductions only - has left in a small list (two buffers, by
 // frame parity) before the frame's barrier; the exponentials in pdf order have two
 // buffers as well, so nothing of frame n + 1 overwrites what frame n still reads.
-// LDS: red [2][16] sums of waves 0-6; tb [2][K0 rounded to 4, + kGradSlack]; nval [2][Rcap] the numerator's pdf
+// Without the offsets (the pdf posteriors of fb_posteriors: one shared graph, rows of logarithms as fb_alpha and
+// fb_beta return them) the frame's largest sum of a forward and a backward entry takes the place of
+// log2 Z - A_n - B_n: one more reduction over the workgroup and a second barrier per frame.
+// LDS: red [2][16] sums and [2][16] maxima of waves 0-6; tb [2][K0 rounded to 4, + kGradSlack]; nval [2][Rcap] the numerator's pdf
 // posteriors by pdf row; en [Kcap] numerator exponentials; nidx [D] 16-bit: pdf -> its row in
 // this sequence's numerator + 1, 0 = none; the numerator tables.
 // ---------------------------------------------------------------------------
