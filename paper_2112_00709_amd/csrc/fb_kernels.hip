@@ -1684,6 +1684,22 @@ __device__ __forceinline__ float4 nt_load4(const float4 *p)
     return make_float4(v.x, v.y, v.z, v.w);
 }
 
+// four consecutive floats of a row whose pieces need not be 16-byte aligned; have: how many of them exist (the
+// others come back as 0 and nothing behind the row is touched)
+__device__ __forceinline__ float4 nt_load4_any(const float *p, int have)
+{
+    typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+    if (have >= 4) {
+        const f4u v = __builtin_nontemporal_load((const f4u *)p);
+        return make_float4(v.x, v.y, v.z, v.w);
+    }
+    float4 r = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (have > 0) r.x = p[0];
+    if (have > 1) r.y = p[1];
+    if (have > 2) r.z = p[2];
+    return r;
+}
+
 template <class NT>
 __global__ __launch_bounds__(kGradThreads, 4) void fb_grad_kernel(const PostParams P)
 {
@@ -1729,6 +1745,8 @@ __global__ __launch_bounds__(kGradThreads, 4) void fb_grad_kernel(const PostPara
         uint2 posr[U];                // places (4 x 16 bit) of the thread's states in pdf order
         uint32_t prange[kGradPdf];    // state ranges (begin | end << 16) of the thread's pdfs tid, tid + MT, ...
         const double z2 = P.logz ? P.logz[b] * kLog2e : 0.0;   // log2 Z of the shared graph
+        // rows in whole 16-byte pieces (the workspace of an LF-MMI call; the caller's rows when K is a multiple of 4)
+        const bool pieces16 = (G0.ld & 3) == 0 && (((uintptr_t)G0.a | (uintptr_t)G0.b) & 15) == 0;
         const bool by_max = !P.cum_a;   // no offsets: the frame's exponentials are taken relative to its largest sum
         // the form of this sequence's rows: the values themselves (what the probability-domain recursion leaves), or logs
         const bool lin_a = G0.fmt_a && G0.fmt_a[b] != 0, lin_b = G0.fmt_b && G0.fmt_b[b] != 0;
@@ -1741,26 +1759,31 @@ __global__ __launch_bounds__(kGradThreads, 4) void fb_grad_kernel(const PostPara
             const float fl = floorf(x);
             return ldexp((double)fexp2(x - fl), (int)fl);
         };
-        auto issue = [&](int n) {
-            const float4 *ar = (const float4 *)((const float *)G0.a + ((size_t)b * P.N + n) * G0.ld);
-            const float4 *br = (const float4 *)((const float *)G0.b + ((size_t)b * P.N + n) * G0.ld);
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int q = u * MT + tid;
-                if (q * 4 < K0) { pa[u] = nt_load4(ar + q); pb[u] = nt_load4(br + q); }
-            }
-            ca = by_max ? 0.0f : P.cum_a[(size_t)b * P.N + n];
-            cb = by_max ? 0.0f : P.cum_b[(size_t)b * P.N + n];
-        };
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int q = u * MT + tid;
             posr[u] = q * 4 < K0 ? ((const uint2 *)G0.pdfs.pos)[q] : make_uint2(0u, 0u);
         }
+        // Few pdfs (the paper's own graphs: 84 pdfs for 3022 states): tpp threads, neighbours in a wave, share a pdf,
+        // each with a part of its states; their sums are added in a fixed order.  Otherwise a thread has up to
+        // kGradPdf whole pdfs: tid, tid + MT, ...
+        int tpp = 1;
+        while (tpp < kWave && D * tpp * 2 <= MT) tpp *= 2;
+        const int n_mine = tpp > 1 ? 1 : kGradPdf;   // pdfs (or parts of one) of a thread
 #pragma unroll
         for (int j = 0; j < kGradPdf; ++j) {
-            const int d = j * MT + tid;
-            prange[j] = d < D ? (uint32_t)G0.pdfs.row_ptr[d] | ((uint32_t)G0.pdfs.row_ptr[d + 1] << 16) : 0u;
+            const int d = tpp > 1 ? tid / tpp : j * MT + tid;
+            uint32_t lo = 0, hi = 0;
+            if (d < D && j < n_mine) {
+                lo = G0.pdfs.row_ptr[d];
+                hi = G0.pdfs.row_ptr[d + 1];
+                if (tpp > 1) {
+                    const uint32_t len = hi - lo, part = (uint32_t)(tid & (tpp - 1));
+                    hi = lo + len * (part + 1) / (uint32_t)tpp;
+                    lo = lo + len * part / (uint32_t)tpp;
+                }
+            }
+            prange[j] = lo | (hi << 16);
         }
         // the most states any pdf of this wave has: how far the reads ahead below go is the same for all its lanes
         float most = 0.0f;
@@ -1769,8 +1792,25 @@ __global__ __launch_bounds__(kGradThreads, 4) void fb_grad_kernel(const PostPara
         const int wcnt = __builtin_amdgcn_readfirstlane((int)wave_max(most));
         // The frames of the block, for one form of the rows: 2 both hold values (every sequence the probability-domain
         // recursion has carried through), 0 both hold logs, 1 one of each (a sequence that fell back in one direction).
-        auto frames = [&](auto form_c) {
+        auto frames = [&](auto form_c, auto few_c) {
         constexpr int form = decltype(form_c)::value;
+        constexpr bool few = decltype(few_c)::value;   // few pdfs: several threads share one (tpp > 1)
+        auto issue = [&](int n) {
+            const float *af = (const float *)G0.a + ((size_t)b * P.N + n) * G0.ld;
+            const float *bf = (const float *)G0.b + ((size_t)b * P.N + n) * G0.ld;
+            const float4 *ar = (const float4 *)af, *br = (const float4 *)bf;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int q = u * MT + tid;
+                if (q * 4 < K0) {
+                    // (rows that hold values are the workspace's: whole pieces)
+                    if (form != 0 || pieces16) { pa[u] = nt_load4(ar + q); pb[u] = nt_load4(br + q); }
+                    else { pa[u] = nt_load4_any(af + q * 4, K0 - q * 4); pb[u] = nt_load4_any(bf + q * 4, K0 - q * 4); }
+                }
+            }
+            ca = (form == 0 && by_max) ? 0.0f : P.cum_a[(size_t)b * P.N + n];   // (rows that hold values come with offsets)
+            cb = (form == 0 && by_max) ? 0.0f : P.cum_b[(size_t)b * P.N + n];
+        };
         issue(n0);
         for (int n = n0; n < n_end; ++n) {
             const int par = (n - n0) & 1;
@@ -1862,7 +1902,7 @@ __global__ __launch_bounds__(kGradThreads, 4) void fb_grad_kernel(const PostPara
             constexpr int H = 2;
             static_assert(kGradPdf % H == 0, "pdfs per thread come in groups");
 #pragma unroll
-            for (int h = 0; h < kGradPdf; h += H) {
+            for (int h = 0; h < (few ? 1 : kGradPdf); h += H) {
                 float t[H][kGradAhead];
                 uint32_t r[H];
 #pragma unroll
@@ -1871,14 +1911,14 @@ __global__ __launch_bounds__(kGradThreads, 4) void fb_grad_kernel(const PostPara
 #pragma unroll
                     for (int i = 0; i < kGradAhead; i += 2)
                         if (wcnt > i) { t[jj][i] = seg[i]; t[jj][i + 1] = seg[i + 1]; }
-                    r[jj] = nidx[min((h + jj) * MT + tid, D - 1)];
+                    r[jj] = nidx[min(few ? tid / tpp : (h + jj) * MT + tid, D - 1)];
                 }
                 float nvv[H];
 #pragma unroll
                 for (int jj = 0; jj < H; ++jj) nvv[jj] = nv[r[jj] ? r[jj] - 1 : 0];   // (no numerators: never used)
 #pragma unroll
                 for (int jj = 0; jj < H; ++jj) {
-                    const int d = (h + jj) * MT + tid;
+                    const int d = few ? tid / tpp : (h + jj) * MT + tid;
                     const int begin = (int)(prange[h + jj] & 0xffffu), end = (int)(prange[h + jj] >> 16);
                     float acc = 0.0f;
 #pragma unroll
@@ -1886,16 +1926,26 @@ __global__ __launch_bounds__(kGradThreads, 4) void fb_grad_kernel(const PostPara
                         if (wcnt > i) acc += begin + i < end ? t[jj][i] : 0.0f;
                     if (wcnt > kGradAhead)
                         for (int i = begin + kGradAhead; i < end; ++i) acc += tbn[i];
+                    if (few)
+                        for (int o = 1; o < tpp; o <<= 1) acc += __shfl_xor(acc, o, kWave);   // the parts of a pdf, in a fixed order
                     float v = acc * scale;
                     if (r[jj]) v += nvv[jj];
-                    if (d < D) __builtin_nontemporal_store(v, prow + d);
+                    if (few ? (d < D && (tid & (tpp - 1)) == 0 && jj == 0) : d < D) __builtin_nontemporal_store(v, prow + d);
                 }
             }
         }
         };
-        if (lin_a && lin_b) frames(std::integral_constant<int, 2>());
-        else if (any_lin) frames(std::integral_constant<int, 1>());
-        else frames(std::integral_constant<int, 0>());
+        const std::true_type yes;
+        const std::false_type no;
+        if (tpp > 1) {
+            if (lin_a && lin_b) frames(std::integral_constant<int, 2>(), yes);
+            else if (any_lin) frames(std::integral_constant<int, 1>(), yes);
+            else frames(std::integral_constant<int, 0>(), yes);
+        } else {
+            if (lin_a && lin_b) frames(std::integral_constant<int, 2>(), no);
+            else if (any_lin) frames(std::integral_constant<int, 1>(), no);
+            else frames(std::integral_constant<int, 0>(), no);
+        }
     } else {
         NT qa[NU], qb[NU];            // rows of the frame being prefetched / worked on
         auto issue = [&](int n) {
@@ -2209,8 +2259,11 @@ bool gradient_kernel_applies(const PostParams &p)
         const PostGraph &d = p.g[0];
         // without the offsets of the rows only rows of logarithms (no format flags), relative to each frame's maximum
         if (!offsets && (p.cum_a || p.cum_b || p.logz || d.fmt_a || d.fmt_b)) return false;
-        return d.shared && !d.f64 && !d.state_post && d.pdfs.pos && (d.ld & 3) == 0 && d.ld >= ((d.Kcap + 3) & ~3) &&
-               d.Kcap <= kGradMain * 4 * kGradU && (((uintptr_t)d.a | (uintptr_t)d.b) & 15) == 0 && p.D <= kGradMain * kGradPdf;
+        // (rows that are not in whole 16-byte pieces are read piece by piece and need no padding)
+        const bool pieces16 = (d.ld & 3) == 0 && d.ld >= ((d.Kcap + 3) & ~3) && (((uintptr_t)d.a | (uintptr_t)d.b) & 15) == 0;
+        const bool any_rows = d.ld >= d.Kcap && (((uintptr_t)d.a | (uintptr_t)d.b) & 3) == 0;
+        return d.shared && !d.f64 && !d.state_post && d.pdfs.pos && (pieces16 || any_rows) &&
+               d.Kcap <= kGradMain * 4 * kGradU && p.D <= kGradMain * kGradPdf;
     }
     if (p.n_graph != 2 || !offsets) return false;
     const PostGraph &d = p.g[0], &n = p.g[1];
