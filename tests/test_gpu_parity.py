@@ -439,6 +439,16 @@ def test_ragged_batch_with_fully_padded_tail(fb):
     compare_fb(fb, w.den, 30, emis, lengths, name="ragged + NaN padding")
 
 
+@pytest.mark.parametrize("K,D", [(501, 30), (503, 3), (1022, 500), (6001, 3000)])
+def test_pdf_posteriors_alone_rows_of_any_length(fb, K, D):
+    """fb_posteriors asked for the pdf posteriors only reads the rows of a shared graph in 16-byte pieces whatever
+    their length and alignment (the last piece of a row element by element), with one or several threads per pdf."""
+    B, N = (3, 9) if K < 2000 else (2, 4)
+    w = wl.config3(K=K, B=B, N=N, D=D)
+    lengths = np.array([N, 1, N - 2][:B], np.int32)
+    compare_fb(fb, w.den, D, w.emis, lengths, name=f"pdf posteriors alone, K={K} D={D}")
+
+
 def test_infeasible_and_semiring_zero_inputs(fb):
     rng = np.random.default_rng(3)
     g = wl.chain_graphs(rng, np.array([2, 3, 2]), 11)                 # 6, 9, 6 states
