@@ -105,6 +105,20 @@ def context_workloads(fb, wl, torch, everything=True):
         if name == "paper_shape_den":   # Table 1: 1.04 s for the denominator forward-backward on an RTX 2080 Ti
             out[name]["paper_table1_s"] = 1.04
         log(f"[bench] {name}: {ms:.3f} ms, {upd / (ms * 1e-3):.3e} arc-updates/s, HBM fraction {out[name]['hbm_frac']:.3f}")
+        if name in ("config4", "paper_shape_den"):
+            # comparison mode beside the exact path (Table 1's leaky-HMM rows): log Z and pdf posteriors of the
+            # leaky-HMM of the same graph in one call, a plain kernel (one workgroup per sequence, both sweeps)
+            lws = torch.empty((fb.fb_leaky_workspace_bytes(G, w.B, w.N),), dtype=torch.uint8, device="cuda")
+            fb.fb_leaky_posteriors(G, emis, lengths, 1e-5, ws=lws)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(3):
+                fb.fb_leaky_posteriors(G, emis, lengths, 1e-5, ws=lws)
+            torch.cuda.synchronize()
+            out[name]["leaky_hmm_ms"] = (time.perf_counter() - t0) * 1e3 / 3
+            out[name]["leaky_hmm_leak"] = 1e-5
+            log(f"[bench] {name}: leaky-HMM comparison mode {out[name]['leaky_hmm_ms']:.3f} ms")
+            del lws
         G.destroy()
         if everything and name in ("config4", "paper_shape_den"):   # best path (tropical semiring) on the same inputs
             Gv = fb.graph_from(g, w.D)

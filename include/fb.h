@@ -329,6 +329,28 @@ size_t fb_viterbi_workspace_bytes(const fb_graph *g, int32_t B, int32_t N);
 int fb_viterbi(const fb_graph *g, const float *emis, const int32_t *lengths, int32_t B, int32_t N, int32_t D,
                double *score, int32_t *path, void *ws, size_t ws_bytes, fb_stream stream);
 
+/*
+ * Comparison mode: the "leaky-HMM" denominator (Python and Julia recipes section and Table 1: the approximation the
+ * paper's comparison system makes, in the probability domain with a scale per frame).  The paper defines it only
+ * by reference; it is taken here as a model with a plain definition: before every transition a fraction `leak` of
+ * the total probability is handed out again over the states in proportion to pi = exp(init) / sum exp(init), i.e.
+ * the hidden Markov model with the transition matrix T' = (I + leak 1 pi^T) T and the graph's own initial and
+ * final weights.  log Z and the pdf posteriors (Eq. 13-15 for T') of every sequence, in one call; leak = 0 gives
+ * the graph itself.  Not part of lfmmi_loss_grad, and not tuned like it: a plain kernel, one workgroup per sequence.
+ *   g         a shared graph (n_seq == 0)
+ *   emis      device float [B][N][D];  lengths  device int32 [B]
+ *   leak      in [0, 1]
+ *   logz      out, device double [B] (-inf for a sequence without a path, whose posteriors are 0)
+ *   pdf_post  out, device float [B][N][D], 0 on padded frames
+ *   ws        device scratch of at least fb_leaky_workspace_bytes() (the forward vectors: 4 bytes per state and frame)
+ * FB_EINVAL: NULL arguments, a packed or host-only graph, sizes <= 0, D != the graph's D, leak outside [0, 1],
+ * workspace missing or too small.  FB_EUNSUPPORTED: more than 8192 states, or four state vectors and an emission row
+ * exceed the 160 KB of on-chip memory of a compute unit (16 K + 4 D bytes).
+ */
+size_t fb_leaky_workspace_bytes(const fb_graph *g, int32_t B, int32_t N);
+int fb_leaky_posteriors(const fb_graph *g, const float *emis, const int32_t *lengths, int32_t B, int32_t N, int32_t D,
+                        float leak, double *logz, float *pdf_post, void *ws, size_t ws_bytes, fb_stream stream);
+
 /* Limits of the kernels for a graph / batch shape: the largest number of states
  * one (sub-)graph may have so that its state vectors and one emission row of D
  * pdfs fit in the 160 KB of on-chip memory of a gfx950 compute unit.

@@ -29,7 +29,8 @@ SYMBOLS = ["fb_graph_create", "fb_graph_destroy", "fb_graph_layout_size", "fb_gr
            "fb_alpha", "fb_beta", "fb_posteriors", "fb_lfmmi_workspace_bytes", "lfmmi_loss_grad", "lfmmi_loss_grad_ragged",
            "fb_limits_max_states", "fb_strerror", "fb_last_error", "fb_graph_schedule_apply_host",
            "fb_profile_enable", "fb_profile_read", "fb_viterbi_workspace_bytes", "fb_viterbi", "fb_graph_linear_weights",
-           "fb_debug_linear_restarts", "fb_graph_plan_cycles", "lfmmi_loss_grad_static", "fb_static_scratch_bytes"]
+           "fb_debug_linear_restarts", "fb_graph_plan_cycles", "lfmmi_loss_grad_static", "fb_static_scratch_bytes",
+           "fb_leaky_workspace_bytes", "fb_leaky_posteriors"]
 
 
 class FBError(RuntimeError):
@@ -92,6 +93,10 @@ def lib() -> ctypes.CDLL:
         L.fb_viterbi_workspace_bytes.restype = sz
         L.fb_viterbi.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
         L.fb_viterbi.restype = ctypes.c_int
+        L.fb_leaky_workspace_bytes.argtypes = [vp, i32, i32]
+        L.fb_leaky_workspace_bytes.restype = sz
+        L.fb_leaky_posteriors.argtypes = [vp, vp, vp, i32, i32, i32, ctypes.c_float, vp, vp, vp, sz, vp]
+        L.fb_leaky_posteriors.restype = ctypes.c_int
         L.fb_profile_enable.argtypes = [ctypes.c_int]
         L.fb_profile_enable.restype = ctypes.c_int
         L.fb_profile_read.argtypes = [vp]
@@ -293,6 +298,24 @@ def fb_posteriors(g: Graph, alpha, beta, lengths, B: int, N: int, want_state: bo
 
 def fb_lfmmi_workspace_bytes(den: Graph, num: Graph, B: int, N: int, D: int) -> int:
     return int(lib().fb_lfmmi_workspace_bytes(den.handle, num.handle, B, N, D))
+
+
+def fb_leaky_workspace_bytes(g: Graph, B: int, N: int) -> int:
+    return int(lib().fb_leaky_workspace_bytes(g.handle, B, N))
+
+
+def fb_leaky_posteriors(g: Graph, emis, lengths, leak: float, ws=None):
+    """Leaky-HMM comparison mode -> (logz [B] float64, pdf_post [B,N,D]), on the device."""
+    torch = _torch()
+    B, N, D = _dev_inputs(emis, lengths)
+    need = int(lib().fb_leaky_workspace_bytes(g.handle, B, N))
+    if ws is None:
+        ws = _new((need,), torch.uint8, emis.device)
+    logz = _new((B,), torch.float64, emis.device)
+    post = _new((B, N, D), torch.float32, emis.device)
+    _check(lib().fb_leaky_posteriors(g.handle, _dp(emis), _dp(lengths), B, N, D, float(leak), _dp(logz), _dp(post), _dp(ws),
+                                     int(ws.numel()), _stream()))
+    return logz, post
 
 
 def fb_viterbi(g: Graph, emis, lengths, ws=None):

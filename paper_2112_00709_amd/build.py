@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfb_amd.so")
-SOURCES = ["fb_kernels.hip", "fb_graph.cpp", "fb_sell.cpp", "fb_stream.cpp", "fb_pstream.cpp", "fb_api.cpp"]
+SOURCES = ["fb_kernels.hip", "fb_graph.cpp", "fb_sell.cpp", "fb_stream.cpp", "fb_pstream.cpp", "fb_api.cpp", "fb_leaky.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",

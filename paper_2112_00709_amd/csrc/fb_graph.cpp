@@ -439,6 +439,7 @@ int fb_graph_create(fb_graph **out, int32_t K, int64_t E, const int32_t *src, co
                 if (!(rc = up(g->hp_fwd, g->pfwd))) rc = up(g->hp_bwd, g->pbwd);
             }
             g->d_pdf = const_cast<int32_t *>(dp); g->d_init2 = const_cast<float *>(di); g->d_final2 = const_cast<float *>(df);
+            if (rc == FB_OK && n_seq == 0) rc = leaky_prepare(g, init, final_);
         }
     } catch (const std::bad_alloc &) {
         rc = fail(FB_ENOMEM, "fb_graph_create: host allocation failed");
@@ -459,6 +460,7 @@ int fb_graph_destroy(fb_graph *g)
     int rc = FB_OK;
     for (void *p : g->allocs)
         if (hipFree(p) != hipSuccess) rc = FB_EHIP;
+    fb::leaky_release(g);
     delete g;
     return rc == FB_OK ? FB_OK : fail(FB_EHIP, "hipFree failed");
 }

@@ -309,6 +309,7 @@ struct fb_graph {
     int32_t *d_pdf = nullptr;         // [K]
     float *d_init2 = nullptr;         // [K] init * log2(e)
     float *d_final2 = nullptr;        // [K] final * log2(e)
+    void *leaky = nullptr;            // shared graphs: the row lists of the leaky-HMM comparison mode (fb_leaky.hip)
     std::vector<void *> allocs;       // everything to hipFree
 };
 
@@ -317,6 +318,8 @@ namespace fb {
 void set_error(const std::string &msg);
 void side_stream_init();   // once per process: the streams the LF-MMI calls use beside the caller's
 void static_scratch_init();   // once per device: the address of the library's built-in scratch memory
+int leaky_prepare(fb_graph *g, const float *init, const float *final_);   // device tables of the leaky-HMM mode (shared graphs)
+void leaky_release(fb_graph *g);
 int fail(int code, const std::string &msg);
 
 struct RecDir {
