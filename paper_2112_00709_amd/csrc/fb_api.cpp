@@ -387,7 +387,8 @@ int fb_posteriors(const fb_graph *g, const float *alpha, const float *beta, cons
 // its Ccap clone columns at K + b * Ccap).
 static size_t viterbi_bp_ld(const fb_graph *g)
 {
-    return (size_t)g->K + (size_t)(g->n_seq == 0 ? 1 : g->n_seq) * (size_t)(g->own_trop ? g->h_trop : g->h_fwd).Ccap;
+    // (a multiple of 8 entries: rows start on 16-byte boundaries, which the back-trace copies in 16-byte pieces)
+    return ((size_t)g->K + (size_t)(g->n_seq == 0 ? 1 : g->n_seq) * (size_t)(g->own_trop ? g->h_trop : g->h_fwd).Ccap + 7) & ~(size_t)7;
 }
 
 size_t fb_viterbi_workspace_bytes(const fb_graph *g, int32_t B, int32_t N)

@@ -413,6 +413,7 @@ struct BacktraceParams {
     const int32_t *lengths;
     StreamDev sched;         // the forward plan (sub-graphs, clones)
     int32_t B, N, shared, Ktot, Kcap, Ccap;
+    int32_t frames;          // back-pointer rows the kernel holds in LDS at a time (set by launch_backtrace)
     int32_t *path;           // [B][N]
 };
 int launch_backtrace(const BacktraceParams &p, void *stream);

@@ -2124,31 +2124,80 @@ __global__ __launch_bounds__(256) void fb_loss_kernel(const double *zn, const do
 // Best path from the back-pointers: one thread per sequence walks from the best end state to frame 0.
 // Indices are those of the state buffer (a state, or Kcap + slot for a clone of a very long row); a clone
 // is reported as the state it belongs to.
-__global__ __launch_bounds__(64) void fb_backtrace_kernel(const BacktraceParams P)
+// One workgroup per sequence.  A path is a chain of dependent reads (the back-pointer of frame n names the row
+// entry to read at frame n - 1), each a trip to HBM if taken one by one; so the workgroup copies the sequence's
+// back-pointer rows of kBtFrames frames at a time into LDS (whole rows: which entry is needed is only known once the
+// chain gets there), the next block travelling while one thread walks the frames of this one there.
+constexpr int kBtThreads = 256, kBtFrames = 8;
+
+__global__ __launch_bounds__(kBtThreads) void fb_backtrace_kernel(const BacktraceParams P)
 {
-    const int b = blockIdx.x * 64 + threadIdx.x;
-    if (b >= P.B) return;
+    extern __shared__ uint16_t bt_rows[];   // [frames][W]: the 16-byte pieces that hold the states' columns, then the clone slots'
+    const int b = blockIdx.x, tid = threadIdx.x;
     const SubDesc sd = P.sched.sub[P.shared ? 0 : b];
     const CloneDesc *cdesc = P.sched.clones + sd.clone0;
     const int T = min(max(P.lengths[b], 0), P.N);
     int32_t *prow = P.path + (size_t)b * P.N;
-    int s = T > 0 ? P.last[b] : -1;
-    for (int n = T; n < P.N; ++n) prow[n] = -1;
-    for (int n = T - 1; n >= 0; --n) {
-        if (s < 0) { prow[n] = -1; continue; }
-        int state = s;
-        int64_t col = (P.shared ? 0 : sd.k0) + s;
-        if (s >= P.Kcap) {   // a clone slot
-            const int slot = s - P.Kcap;
-            state = 0;
-            for (int j = 0; j < sd.n_cdesc; ++j)
-                if (slot >= cdesc[j].first && slot < cdesc[j].first + cdesc[j].count) state = cdesc[j].state;
-            col = (P.shared ? sd.K : (int64_t)P.Ktot + (int64_t)b * P.Ccap) + slot;
-        }
-        prow[n] = sd.k0 + state;
-        if (n > 0) s = P.bp[(P.shared ? ((size_t)b * P.N + n) : (size_t)n) * P.bp_ld + col];
+    for (int n = T + tid; n < P.N; n += kBtThreads) prow[n] = -1;
+    if (T == 0) return;
+    const int K = sd.K, F = P.frames;
+    // where the sequence's columns lie in a row of back-pointers, and the 16-byte pieces of the row that hold them
+    // (rows are a multiple of 8 entries long and start on 16-byte boundaries)
+    const int64_t col_states = P.shared ? 0 : sd.k0;
+    const int64_t col_clones = P.shared ? (int64_t)K : (int64_t)P.Ktot + (int64_t)b * P.Ccap;
+    const int64_t ps0 = col_states >> 3, ps1 = (col_states + K + 7) >> 3;
+    const int64_t pc0 = col_clones >> 3, pc1 = (col_clones + P.Ccap + 7) >> 3;
+    const int ns = (int)(ps1 - ps0), nc = P.Ccap > 0 ? (int)(pc1 - pc0) : 0;   // pieces
+    const int W = (ns + nc) * 8;
+    const int at_states = (int)(col_states - ps0 * 8), at_clones = ns * 8 + (int)(col_clones - pc0 * 8);
+    const int lane = tid & (kWave - 1), wave = tid >> 6;
+    int s = P.last[b];   // index in the kernel's index space: a state, or Kcap + a clone slot (thread 0 follows it)
+    if (s < 0) {
+        for (int n = tid; n < T; n += kBtThreads) prow[n] = -1;
+        return;
     }
+    auto state_of = [&](int idx) {
+        if (idx < P.Kcap) return idx;
+        const int slot = idx - P.Kcap;
+        int state = 0;
+        for (int j = 0; j < sd.n_cdesc; ++j)
+            if (slot >= cdesc[j].first && slot < cdesc[j].first + cdesc[j].count) state = cdesc[j].state;
+        return state;
+    };
+    // frames T-1 .. 1 take their predecessor from their own row; blocks of F rows, highest frame first, in two
+    // buffers: the next block is on its way from global memory while thread 0 walks this one
+    auto issue = [&](int hi, int buf) {   // rows hi, hi - 1, ..., straight into LDS, 16 bytes per lane, nothing waits in between
+        const int cnt = min(F, hi);
+        for (int f = 0; f < cnt; ++f) {
+            const uint4 *row = (const uint4 *)(P.bp + (P.shared ? ((size_t)b * P.N + (hi - f)) : (size_t)(hi - f)) * P.bp_ld);
+            uint4 *dst = (uint4 *)(bt_rows + ((size_t)buf * F + f) * W);
+            for (int i0 = wave * kWave; i0 < ns; i0 += kBtThreads)
+                if (i0 + lane < ns)
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(row + ps0 + i0 + lane),
+                                                     (__attribute__((address_space(3))) void *)(dst + i0), 16, 0, 0);
+            for (int i0 = wave * kWave; i0 < nc; i0 += kBtThreads)
+                if (i0 + lane < nc)
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(row + pc0 + i0 + lane),
+                                                     (__attribute__((address_space(3))) void *)(dst + ns + i0), 16, 0, 0);
+        }
+    };
+    if (T > 1) issue(T - 1, 0);
+    int buf = 0;
+    for (int hi = T - 1; hi >= 1; hi -= F, buf ^= 1) {
+        const int cnt = min(F, hi);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();   // this block is in LDS; thread 0 has left the other buffer
+        if (hi - F >= 1) issue(hi - F, buf ^ 1);
+        if (tid == 0) {
+            for (int f = 0; f < cnt; ++f) {
+                prow[hi - f] = sd.k0 + state_of(s);
+                s = bt_rows[((size_t)buf * F + f) * W + (s < P.Kcap ? at_states + s : at_clones + (s - P.Kcap))];
+            }
+        }
+    }
+    if (tid == 0) prow[0] = sd.k0 + state_of(s);
 }
+
 
 // ---------------------------------------------------------------------------
 // launchers
@@ -2235,7 +2284,18 @@ unsigned int linear_restarts()
 
 int launch_backtrace(const BacktraceParams &p, void *stream)
 {
-    hipLaunchKernelGGL(fb_backtrace_kernel, dim3((unsigned)((p.B + 63) / 64)), dim3(64), 0, (hipStream_t)stream, p);
+    // rows of the sequence with the most columns: its states and the clone slots
+    BacktraceParams q = p;
+    if ((p.bp_ld & 7) != 0 || ((uintptr_t)p.bp & 15) != 0) return fail(FB_EHIP, "internal error: back-pointer rows are not in 16-byte pieces");
+    const size_t row_bytes = ((size_t)p.Kcap + (size_t)p.Ccap + 32) * sizeof(uint16_t);   // both spans rounded out to whole pieces
+    q.frames = (int32_t)std::max<size_t>(1, std::min<size_t>(kBtFrames, (kLdsBytes - kLdsReserve) / (2 * std::max<size_t>(row_bytes, 1))));   // two buffers
+    const size_t lds_bytes = 2 * (size_t)q.frames * row_bytes;
+    if (lds_bytes > kLdsBytes) return fail(FB_EUNSUPPORTED, "backtrace: a row of back-pointers exceeds the on-chip memory");
+    if (lds_bytes > 64 * 1024) {
+        const hipError_t e = hipFuncSetAttribute((const void *)fb_backtrace_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return fail(FB_EHIP, std::string("hipFuncSetAttribute(LDS size): ") + hipGetErrorString(e));
+    }
+    hipLaunchKernelGGL(fb_backtrace_kernel, dim3((unsigned)p.B), dim3(kBtThreads), lds_bytes, (hipStream_t)stream, q);
     return check_launch("backtrace kernel launch");
 }
 
