@@ -872,7 +872,7 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
 // LDS: xb, the previous / current vector, kXsFixed floats each at addresses 0 and kXbStride; bh 2 x kXsFixed behind
 // them (rows on their way out that are not the vector itself: beta before the emission is applied, or either
 // direction's rows as logarithms; absent otherwise); red 64 floats (0-2 step maxima, 4-6 the frames' emission maxima
-// in log2 units, 7 scratch, 32-63 the last reduction); er 3 x Es floats, Es = D + 1
+// in log2 units, 3 and 7 scratch of the first frame, 32-63 the last reduction); er 3 x Es floats, Es = D + 1
 // rounded up to 4: the emissions as given of the frame in use and of the next two, entry D = -inf (what the dump
 // slot "emits").
 // ---------------------------------------------------------------------------
@@ -1045,7 +1045,7 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
     if (tid < 12) er[(tid >> 2) * Es + Es - 4 + (tid & 3)] = -INFINITY;   // behind the rows (staging never writes there; the row's own last entries are rewritten)
     __syncthreads();
     if (tid < 3) er[tid * Es + P.D] = -INFINITY;   // what the dump slot "emits": its entry stays zero whatever the frame's scale
-    if (tid < 8) red[tid] = tid == 7 ? -INFINITY : 0.0f;
+    if (tid < 8) red[tid] = (tid == 7 || tid == 3) ? -INFINITY : 0.0f;
     __syncthreads();
     if (io_wave) {
         stage(frame(0), er);
@@ -1059,14 +1059,27 @@ __device__ __forceinline__ bool linear_run(const RecParams &P, const int b, cons
     __syncthreads();
     const float emx0 = emaxw[0];
     {
-        float ymax = -INFINITY;
-        for (int k = tid; k < K; k += NT) ymax = tmax(ymax, R_.bound[k] + fmaf(er[P.pdf[k]], (float)kLog2e, -emx0));
+        float ymax = -INFINITY, smax = -INFINITY;
+        for (int k = tid; k < K; k += NT) {
+            const float s = R_.bound[k];
+            ymax = tmax(ymax, s + fmaf(er[P.pdf[k]], (float)kLog2e, -emx0));
+            smax = tmax(smax, s);
+        }
         ymax = wave_max(ymax);
-        if (lane == 0) __builtin_amdgcn_ds_fmaxf((__attribute__((address_space(3))) float *)(red + 7), ymax, 0, 0, false);
+        smax = wave_max(smax);
+        if (lane == 0) {
+            __builtin_amdgcn_ds_fmaxf((__attribute__((address_space(3))) float *)(red + 7), ymax, 0, 0, false);
+            __builtin_amdgcn_ds_fmaxf((__attribute__((address_space(3))) float *)(red + 3), smax, 0, 0, false);
+        }
     }
     __syncthreads();
     const float M0 = red[7];
-    const float base0 = M0 > -INFINITY ? M0 - (float)kLinBias : 0.0f;   // log2 of the first vector = log2 of its entries + base0 (+ the emission maximum)
+    // log2 of the first vector = log2 of its entries + base0 (+ the emission maximum).  The largest entry goes to
+    // 2^bias; backward, the row that leaves is the start weights before the frame's emissions, which lie above the
+    // vector by what the best state's emission lacks to the frame's largest: the scale is held back as far as that
+    // row needs to stay a float (the vector's entries are then smaller, and below the range the run gives up as ever).
+    float base0 = M0 > -INFINITY ? M0 - (float)kLinBias : 0.0f;
+    if (bwd && M0 > -INFINITY) base0 = tmax(base0, red[3] - 126.0f);
     float wmax = 0.0f;
     for (int k = tid; k < K; k += NT) {
         const float s = R_.bound[k];

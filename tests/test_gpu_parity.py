@@ -665,6 +665,22 @@ def test_lfmmi_with_sequences_that_fall_back(fb):
     assert fb.fb_debug_linear_restarts() - r1 == r1 - r0      # the same sequences, whatever the entry point
 
 
+def test_backward_start_row_stays_in_range(fb):
+    """The backward recursion's first row is the final weights, before the frame's emissions; the vector it continues
+    from carries them.  When every state's emission in the last frame lies far below the frame's largest (a pdf no
+    state is tied to), the scale that suits the vector would push that row beyond a float: it must stay finite, and
+    the gradient of the last frame with it."""
+    w = wl.config5(K=1500, B=6, Lmin=2, Lmax=6, D=100)
+    w.den.pdf[:] = w.den.pdf % 50
+    w.num.pdf[:] = w.num.pdf % 50
+    emis = w.emis.copy()
+    for b in range(w.B):
+        emis[b, int(w.lengths[b]) - 1, 99] = 60.0        # 87 binary orders above everything a state emits
+        emis[b, 0, 98] = 45.0
+    compare_lfmmi(fb, w, name="lfmmi, an unused pdf far above the others in the last frame", emis=emis)
+    compare_fb(fb, w.den, w.D, emis, w.lengths, name="the same through fb_alpha / fb_beta / fb_posteriors")
+
+
 def test_lfmmi_calls_from_two_host_threads(fb):
     """Two host threads call lfmmi_loss_grad at the same time on the same graphs, each on its own inputs, workspace,
     outputs and stream (the library's side streams and events are shared by the process and guarded by a lock
