@@ -337,6 +337,9 @@ int fb_viterbi(const fb_graph *g, const float *emis, const int32_t *lengths, int
  * the hidden Markov model with the transition matrix T' = (I + leak 1 pi^T) T and the graph's own initial and
  * final weights.  log Z and the pdf posteriors (Eq. 13-15 for T') of every sequence, in one call; leak = 0 gives
  * the graph itself.  Not part of lfmmi_loss_grad, and not tuned like it: a plain kernel, one workgroup per sequence.
+ * Vectors are float, rescaled to sum 1 in every frame, with no fallback: an entry below 2^-126 of its frame's total
+ * is taken as 0 (as in any implementation of this kind; harmless unless a later frame's emissions lift such a state
+ * by as much again, which takes emissions that differ by more than 87 nats between live states of one frame).
  *   g         a shared graph (n_seq == 0)
  *   emis      device float [B][N][D];  lengths  device int32 [B]
  *   leak      in [0, 1]

@@ -15,7 +15,9 @@
 // Vectors are float in LDS.  The sparse products walk plain row lists in global memory (they stay in L2): rows of
 // more than 64 arcs in pieces of 256 arcs by a wave each (their sums added in order afterwards), the others one per
 // thread, sorted by length in blocks of 1024 rows with the arcs of a block stored slot by slot, so that the threads
-// of a wave read neighbouring words.  This is a simple kernel for comparison, not tuned like the exact path: no
+// of a wave read neighbouring words.  There is no range guard and no fallback to logarithms: an entry below 2^-126 of
+// its frame's total is flushed to zero, which is this kind of method's own approximation (the exact path gives such
+// a sequence up and redoes it in the log form).  This is a simple kernel for comparison, not tuned like the exact path: no
 // arcs in registers, several barriers per frame, 8 bytes from L2 per arc and frame.
 
 #include <hip/hip_runtime.h>
@@ -278,19 +280,27 @@ __global__ __launch_bounds__(kLeakyThreads) void fb_leaky_kernel(const LeakyPara
             for (int u = 0; u < kPre; ++u) pe[u] = tid + u * NT < D ? em[(size_t)n * D + tid + u * NT] : -INFINITY;
         }
     };
-    // emissions of frame n (fetched before) -> er, returns the largest (0 if the frame has none above zero-bar);
-    // next: the frame to fetch now, or -1
+    // emissions of frame n (fetched before) -> er (in place after a barrier); next: the frame to fetch now, or -1
     auto stage = [&](int n, int next) {
-        float m = -INFINITY;
         if (pre) {
 #pragma unroll
             for (int u = 0; u < kPre; ++u)
-                if (tid + u * NT < D) { er[tid + u * NT] = pe[u]; m = fmaxf(m, pe[u]); }
+                if (tid + u * NT < D) er[tid + u * NT] = pe[u];
             if (next >= 0) fetch(next);
         } else {
-            for (int d = tid; d < D; d += NT) { const float e = em[(size_t)n * D + d]; er[d] = e; m = fmaxf(m, e); }
+            for (int d = tid; d < D; d += NT) er[d] = em[(size_t)n * D + d];
         }
-        m = block_reduce<true>(m, red, turn);   // (its barrier also puts er in place)
+        __syncthreads();
+    };
+    // The scale of a frame's emission factors: the largest emission among the states that carry probability in vec (0
+    // if there is none above zero-bar).  Not the largest of the row: a pdf that no state is tied to, or whose states are
+    // out of reach in this frame, may lie far above the others, and factors relative to it would leave a float's range.
+    auto frame_scale = [&](const float *vec) {
+        float m = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (tid + u * NT < K && vec[tid + u * NT] > 0.0f) m = fmaxf(m, er[kpp[u] & 0xffffu]);
+        m = block_reduce<true>(m, red, turn);
         if (!(m > -INFINITY)) m = 0.0f;
         return m;
     };
@@ -300,20 +310,25 @@ __global__ __launch_bounds__(kLeakyThreads) void fb_leaky_kernel(const LeakyPara
     float zl = 0.0f;
     fetch(0);
     for (int n = 0; n < T; ++n) {
-        const float m = stage(n, n + 1 < T ? n + 1 : -1);
+        stage(n, n + 1 < T ? n + 1 : -1);
         if (n > 0) {
             sparse_product(G.fwd, x, y, part);   // x = previous vector with the leak handed out
             __syncthreads();
             long_rows(G.fwd, y, part);
-            __syncthreads();
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (tid + u * NT < K) y[tid + u * NT] = G.initp[tid + u * NT];
         }
+        __syncthreads();
+        const float m = frame_scale(y);
         float s = 0.0f, v[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int k = tid + u * NT;
             v[u] = 0.0f;
             if (k < K) {
-                v[u] = (n == 0 ? G.initp[k] : y[k]) * __expf(er[kpp[u] & 0xffffu] - m);
+                v[u] = y[k] * __expf(er[kpp[u] & 0xffffu] - m);
                 s += v[u];
             }
         }
@@ -358,7 +373,8 @@ __global__ __launch_bounds__(kLeakyThreads) void fb_leaky_kernel(const LeakyPara
     __syncthreads();
     for (int n = T - 1; n >= 0; --n) {
         if (n < T - 1) {
-            const float m = stage(n + 1, n >= 1 ? n : -1);
+            stage(n + 1, n >= 1 ? n : -1);
+            const float m = frame_scale(x);
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 if (tid + u * NT < K) y[tid + u * NT] = x[tid + u * NT] * __expf(er[kpp[u] & 0xffffu] - m);

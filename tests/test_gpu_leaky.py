@@ -108,6 +108,18 @@ def test_a_frame_nobody_can_emit(fb):
     assert np.isneginf(logz[1]) and np.isfinite(logz[0]) and np.isfinite(logz[2])
 
 
+def test_a_pdf_no_state_is_tied_to_far_above_the_others(fb):
+    """The per-frame scale of the emissions is the largest emission a state has, not the largest of the row: an
+    unused pdf 130 binary orders above the rest must not flush the frame's factors to zero."""
+    rng = np.random.default_rng(8)
+    g = wl.random_graph(rng, 300, 40, mean_extra_deg=3.0)
+    g.pdf[:] = g.pdf % 20
+    emis = (rng.standard_normal((3, 10, 40)) * 2).astype(np.float32)
+    emis[:, ::2, 39] = 90.0
+    emis[1, 3, 30] = 200.0
+    compare(fb, g, 40, emis, np.array([10, 7, 10], np.int32), 1e-3, name="unused pdf far above the others")
+
+
 def test_config4_full_size_sampled(fb):
     w = wl.config4()
     order = np.argsort(w.lengths)
