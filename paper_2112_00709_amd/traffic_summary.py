@@ -3,11 +3,11 @@
 Usage (on the GPU machine, from the repository root; one counter per run):
 
     export FB_AMD_SERIAL=1
-    rocprofv3 --pmc FETCH_SIZE -d gpurun_out/pmc_fetch -o p --output-format csv -- \\
+    rocprofv3 --pmc FETCH_SIZE -d out/pmc_fetch -o p --output-format csv -- \\
         python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --no-context --calibrate-copy
-    rocprofv3 --pmc WRITE_SIZE -d gpurun_out/pmc_write -o p --output-format csv -- \\
+    rocprofv3 --pmc WRITE_SIZE -d out/pmc_write -o p --output-format csv -- \\
         python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --no-context --calibrate-copy
-    python3 -m paper_2112_00709_amd.traffic_summary gpurun_out/pmc_fetch gpurun_out/pmc_write \\
+    python3 -m paper_2112_00709_amd.traffic_summary out/pmc_fetch out/pmc_write \\
         profiles/lfmmi_config5_traffic.json
 
 FB_AMD_SERIAL=1 keeps every launch of a call on the caller's stream.  A counter run lets one kernel at a time onto
