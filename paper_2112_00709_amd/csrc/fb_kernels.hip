@@ -329,7 +329,10 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
     // the maximum over the workgroup of the vector of step i (the next step normalises by it)
     constexpr bool kAtomMax = sizeof(T) == 4;
     auto put_max = [&](int i, T wmax) {
-        wmax = wave_max(wmax);
+        // (a double carrier's maximum is reduced as a float rounded up: what the next step subtracts from every entry
+        // need only be near the largest, the same for all, and not below it by more than rounding)
+        if constexpr (sizeof(T) == 8) wmax = (T)wave_max(__double2float_ru((double)wmax));
+        else wmax = wave_max(wmax);
         if (lane == 0) {   // (one lane per wave: atomics of many lanes on one word are served one at a time)
             if constexpr (kAtomMax)
                 __builtin_amdgcn_ds_fmaxf((__attribute__((address_space(3))) float *)(red + i % 3), (float)wmax, 0, 0, false);
@@ -527,6 +530,11 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
             // iteration; kept in registers (word i in lane i) and read with v_readlane
             const uint32_t *fwp = S.flagwords + wd.flag_base;
             const uint32_t rflag0 = fwp[0], rflag1 = fwp[1];
+            // batches of the resident part that hold arcs (padding only follows them, and only when nothing is streamed)
+            int n_res = 0;
+            for (int q = 0; q < NRES; ++q)
+                if (!((((q < 4 ? rflag0 : rflag1) >> (8 * (q & 3))) & 0xffu) & kFlagSkip)) n_res = q + 1;
+            n_res = __builtin_amdgcn_readfirstlane(n_res);
             const uint32_t fwv0 = lane < n_iter ? fwp[2 + lane] : 0u;
             const uint32_t fwv1 = lane + kWave < n_iter ? fwp[2 + lane + kWave] : 0u;
             Arc ring[kRing][kBatchRows];
@@ -620,11 +628,26 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
                         // Stacked slices: every part of the lane is a row of its own with one or two terms, closed
                         // here; the running sums of the lane are not touched (stacked batches come first).
                         // val: the part's (+)-sum; parg: tropical semiring, where its best term came from
-                        auto close_part = [&](T val, int parg, uint32_t field) {
+                        // The emissions of the parts' targets first, all of them (two LDS reads in a row each, one
+                        // after the other per part they would be most of a small graph's time step).
+                        const bool quad = (f & kFlagQuad) != 0;
+                        uint32_t ptgt[kBatchRows];
+                        float pem[kBatchRows];
+#pragma unroll
+                        for (int r = 0; r < kBatchRows; ++r) {
+                            uint32_t field = (uint32_t)a[(quad || (r & 1)) ? r : r + 1].src;   // two parts: rows 1 and 3 name the targets
                             asm volatile("" : "+v"(field));
-                            const uint32_t tgt = field >> 16;
+                            ptgt[r] = field >> 16;
+                        }
+                        uint32_t pvi[kBatchRows];
+#pragma unroll
+                        for (int r = 0; r < kBatchRows; ++r) pvi[r] = vix[ptgt[r]];
+#pragma unroll
+                        for (int r = 0; r < kBatchRows; ++r) pem[r] = ern[pvi[r]];
+                        auto close_part = [&](T val, int parg, int r) {   // r: a row of the part that names its target
+                            const uint32_t tgt = ptgt[r];
                             const T pre = val - c;
-                            const T x = pre + (T)ern[vix[tgt]] * (T)kLog2e;
+                            const T x = pre + (T)pem[r] * (T)kLog2e;
                             xn[tgt] = x;
                             if constexpr (TROP) bpn[tgt] = (uint16_t)(parg >> kSrcShift);
                             else if (bwd) bn[tgt] = pre;
@@ -637,8 +660,8 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
 #pragma unroll
                             for (int r = 0; r < kBatchRows; ++r) {   // one term: the sum is the term
                                 const uint32_t field = (uint32_t)a[r].src;
-                                if constexpr (TROP) close_part(xs[r], xs[r] > kNegInf ? (int)(field & 0xffffu) : 0, field);
-                                else close_part(xs[r] > (T)kNegBig ? xs[r] : kNegInf, 0, field);   // (as the running sums treat it)
+                                if constexpr (TROP) close_part(xs[r], xs[r] > kNegInf ? (int)(field & 0xffffu) : 0, r);
+                                else close_part(xs[r] > (T)kNegBig ? xs[r] : kNegInf, 0, r);   // (as the running sums treat it)
                             }
                         } else {
 #pragma unroll
@@ -650,10 +673,10 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
                                     int parg = 0;
                                     if (u0 > pm) { pm = u0; parg = a[2 * p].src; }
                                     if (u1 > pm) { pm = u1; parg = (int)(field & 0xffffu); }
-                                    close_part(pm, parg, field);
+                                    close_part(pm, parg, 2 * p + 1);
                                 } else {
                                     const T pm = tmax3((T)kNegBig, u0, u1);
-                                    close_part(pm + (T)flog2(fexp2((float)(u0 - pm)) + fexp2((float)(u1 - pm))), 0, field);   // 0 -> -inf
+                                    close_part(pm + (T)flog2(fexp2((float)(u0 - pm)) + fexp2((float)(u1 - pm))), 0, 2 * p + 1);   // 0 -> -inf
                                 }
                             }
                         }
@@ -729,11 +752,13 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
                 gather(g[0], res[0], vbase, is_stacked(rflag(0)));
                 unrolled([&](auto qc) {
                     constexpr int q = decltype(qc)::value;
-                    if constexpr (q + 1 < NRES)
-                        fold(std::bool_constant<(q < kMaxStacked)>{}, rflag(q), res[q], g[q % GB], g[(q + 1) % GB], res[q + 1],
-                             q + 1 < kMaxStacked && is_stacked(rflag(q + 1)), true);
-                    else
-                        fold(std::bool_constant<(q < kMaxStacked)>{}, rflag(q), res[q], g[q % GB], g[(q + 1) % GB], ring[0], false, n_iter > 0);
+                    if (q < n_res) {   // (a small graph fills only the first of them: the padding behind is not walked)
+                        if constexpr (q + 1 < NRES)
+                            fold(std::bool_constant<(q < kMaxStacked)>{}, rflag(q), res[q], g[q % GB], g[(q + 1) % GB], res[q + 1],
+                                 q + 1 < kMaxStacked && is_stacked(rflag(q + 1)), q + 1 < n_res);
+                        else
+                            fold(std::bool_constant<(q < kMaxStacked)>{}, rflag(q), res[q], g[q % GB], g[(q + 1) % GB], ring[0], false, n_iter > 0);
+                    }
                 }, std::make_integer_sequence<int, NRES>{});
                 uint32_t fw = fw_first;
                 prio(std::integral_constant<int, 2>{});
