@@ -352,6 +352,12 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
     };
 
     // ---- duties of the data-moving wave (called by that wave only, all 64 lanes)
+    // Packed graphs: the pdf of the lane's states u * 64 + lane, in registers when a (sub-)graph has at most
+    // kPixRegs * 64 states (read once: looked up in LDS at every frame, each of a frame's loads would wait for a read)
+    // (the small-graph instantiations only: the others have no registers to spare)
+    constexpr int kPixRegs = NW == kNWSmall ? 8 : 0;
+    const bool pix_in_regs = kPixRegs > 0 && !P.shared && nE <= kPixRegs * kWave;
+    int32_t pixr[kPixRegs > 0 ? kPixRegs : 1] = {};
     // emissions of frame f -> dst, through the direct global->LDS path (no registers, any length)
     auto stage = [&](int f, float *dst) {
         const float *row = em_seq + (size_t)f * P.D;
@@ -367,6 +373,12 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
                         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(row + e0 + lane),
                                                          (__attribute__((address_space(3))) void *)(dst + e0), 4, 0, 0);
             }
+        } else if (kPixRegs > 0 && pix_in_regs) {
+#pragma unroll
+            for (int u = 0; u < kPixRegs; ++u)
+                if (u * kWave < nE && u * kWave + lane < nE)
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(row + pixr[u]),
+                                                     (__attribute__((address_space(3))) void *)(dst + u * kWave), 4, 0, 0);
         } else {
             for (int e0 = 0; e0 < nE; e0 += kWave)
                 if (e0 + lane < nE)
@@ -381,7 +393,7 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
     // can only be reused once the store has completed, so a read-one-store-one loop would pay a full HBM
     // round trip per piece)
     auto copy_out = [&](auto *orow, const auto *srcv, int n, auto cvt) {
-        constexpr int U = 16;
+        constexpr int U = NW == kNWShared ? 16 : 8;   // (small graphs: a row of up to 512 states is one group)
         for (int k0 = 0; k0 < n; k0 += U * kWave) {
             std::remove_cv_t<std::remove_reference_t<decltype(srcv[0])>> v[U];
 #pragma unroll
@@ -457,6 +469,10 @@ __device__ __forceinline__ void recursion_run(const RecParams &P, const int b, c
         if (kAtomMax && tid < 3) red[tid] = kNegInf;
         __syncthreads();
         if (io_wave) {
+            if (kPixRegs > 0 && pix_in_regs) {
+#pragma unroll
+                for (int u = 0; u < kPixRegs; ++u) pixr[u] = u * kWave + lane < nE ? pix[u * kWave + lane] : 0;
+            }
             stage(frame(0), er);
             if (Tn > 1) stage(frame(1), er + Es);
             staged_wait();
