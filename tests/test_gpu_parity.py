@@ -277,6 +277,22 @@ def test_carrier_precision_can_be_forced(fb):
     compare_fb(fb, c.num, c.D, c.emis, c.lengths, name="config2 wide state", state="wide")
 
 
+def test_long_chains_through_float_rows(fb):
+    """fb_alpha / fb_beta hand their rows over as float32 (relative to the frame's best state, the shift in double).
+    In a long left-to-right chain a state that matters can lie hundreds of units below its frame's best forward
+    entry (the backward entry makes up for it), and a float that large is rounded at 2e-5: state posteriors formed
+    from such rows by fb_posteriors are good to that, not to 1e-5.  (Inside lfmmi_loss_grad the numerators' rows stay
+    in the carrier's type, double; the config-5 and paper-shaped gradient tests hold 1e-5.)  Sub-graphs of 511 and
+    514 states also sit on both sides of the 512 states whose pdf offsets the data-moving wave keeps in registers."""
+    rng = np.random.default_rng(7)
+    D = 40
+    phones = np.array([170, 171, 2])
+    g = wl.chain_graphs(rng, phones, D)
+    lengths = np.array([546, 550, 9], dtype=np.int32)
+    emis = (rng.standard_normal((3, 551, D)) * 2.0).astype(np.float32)
+    compare_fb(fb, g, D, emis, lengths, name="chains of 511 / 514 / 7 states over 550 frames", post_tol=5e-5)
+
+
 def test_cloned_hub_rows_small(fb):
     """A 3500-state hub graph whose largest in-degree needs clones, every sequence checked in full."""
     w = wl.config4(K=3500, B=3, Nmin=10, Nmax=25, D=300)
