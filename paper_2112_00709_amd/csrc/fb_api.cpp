@@ -129,6 +129,7 @@ PostGraph make_post(const fb_graph *g, const void *a, const void *b, bool f64, f
 struct Offsets {
     const float *cum_a = nullptr, *cum_b = nullptr;
     const double *logz = nullptr;
+    const int32_t *fused = nullptr;   // PostParams::fused
 };
 
 int run_posteriors(const PostGraph *gs, int n_graph, const int32_t *lengths, int32_t B, int32_t N, int32_t D,
@@ -138,6 +139,7 @@ int run_posteriors(const PostGraph *gs, int n_graph, const int32_t *lengths, int
     PostParams p{};
     p.accumulate = accumulate ? 1 : 0;
     if (offs.cum_a && offs.cum_b && offs.logz) { p.cum_a = offs.cum_a; p.cum_b = offs.cum_b; p.logz = offs.logz; }
+    p.fused = offs.fused;
     p.order = range.order;
     p.rank0 = range.rank0;
     p.n_launch = range.count;
@@ -156,7 +158,9 @@ int run_posteriors(const PostGraph *gs, int n_graph, const int32_t *lengths, int
         if (glds <= kLdsBytes) return launch_gradient(p, glds, stream);
     }
     if (num_add_kernel_applies(p)) {
-        p.frames_per_block = 8;
+        // (a launch that may find nothing left to add, PostParams::fused, comes in few workgroups: they are all dispatched
+        // beside the call's last gradient launch before they can leave)
+        p.frames_per_block = p.fused ? 32 : 8;
         return launch_num_add(p, stream);
     }
     const size_t lds = posterior_lds_bytes(p);
@@ -540,6 +544,15 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
             const uint32_t n = 2u * (uint32_t)(upto[slot - 1] - from[slot - 1]);
             return n == 0 || ok(hipStreamWaitValue32(st, done + slot, n, hipStreamWaitValueGte, 0xffffffffu));
         };
+        bool decides_on_device = gradient_reads_denominator(q, lengths, B, N, D, grad);
+        {
+            PostParams pa{};
+            pa.n_graph = 1;
+            pa.g[0] = q[1];
+            pa.accumulate = 1;
+            pa.pdf_out = grad;
+            decides_on_device = decides_on_device && num_add_kernel_applies(pa);
+        }
         auto stages = [&]() -> int {
             int r;
             if ((r = run_recursion(den, emis, lengths, B, N, D, dd, 2, main_s, false, RankRange{order, 0, B}, done, from, true))) return r;
@@ -550,6 +563,11 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
                 return fail(FB_EHIP, "lfmmi_loss_grad: stream wait on a value failed");
             mark(5, ns);
             if ((r = run_recursion(num, emis, lengths, B, N, D, dn, 2, ns, false, RankRange{order, 0, B}))) return r;
+            // (a word on the device says that the launch has ended: see the second range below.  A launch of its own
+            // behind it, not a count by the numerator workgroups: each of those would have to push its rows out of
+            // its L2 before it counts, 256 times beside the denominator launch.)
+            uint32_t *num_ended = done + kDoneNum;
+            if (decides_on_device && (r = launch_mark(num_ended, ns))) return r;
             mark(6, ns);
             if (!ok(hipEventRecord(side.num_done, ns))) return fail(FB_EHIP, "lfmmi_loss_grad: event record failed");
             // the shortest range, on the numerators' stream
@@ -562,10 +580,25 @@ static int lfmmi_run(const fb_graph *den, const fb_graph *num, const float *emis
             if ((r = run_posteriors(&q[0], 1, lengths, B, N, D, grad, gs[2], slot_range(3), false, offs))) return r;
             if (!ok(hipStreamWaitEvent(gs[2], side.num_done, 0))) return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
             if ((r = run_posteriors(&q[1], 1, lengths, B, N, D, grad, gs[2], slot_range(3), true))) return r;
-            // the longer ranges: the numerators are done long before them unless all lengths are (nearly) equal
-            if (!wait_slot(gs[1], 2) || !ok(hipStreamWaitEvent(gs[1], side.num_done, 0)))
-                return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
-            if ((r = run_posteriors(q, 2, lengths, B, N, D, grad, gs[1], slot_range(2), false, offs))) return r;
+            // The second range: the numerators are done long before its recursions unless all lengths are (nearly)
+            // equal.  Then no compute unit falls free before the denominator launch ends, the numerator recursions
+            // only start there, and the range's gradient should not wait for them: a word written on the device when
+            // the range is released says which it is, and the gradient launch takes both graphs or the denominator's
+            // share alone, in which case the launch behind it adds the numerators' (same sums, same order either way).
+            // (Only the gradient kernel and the kernel that adds a packed graph's share read that word.)
+            if (!wait_slot(gs[1], 2)) return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
+            if (decides_on_device) {
+                int32_t *fused2 = (int32_t *)(done + kDoneFused);
+                Offsets offs2 = offs, add2;
+                offs2.fused = add2.fused = fused2;
+                if ((r = launch_decide(num_ended, 1u, fused2, gs[1]))) return r;
+                if ((r = run_posteriors(q, 2, lengths, B, N, D, grad, gs[1], slot_range(2), false, offs2))) return r;
+                if (!ok(hipStreamWaitEvent(gs[1], side.num_done, 0))) return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
+                if ((r = run_posteriors(&q[1], 1, lengths, B, N, D, grad, gs[1], slot_range(2), true, add2))) return r;
+            } else {
+                if (!ok(hipStreamWaitEvent(gs[1], side.num_done, 0))) return fail(FB_EHIP, "lfmmi_loss_grad: stream wait failed");
+                if ((r = run_posteriors(q, 2, lengths, B, N, D, grad, gs[1], slot_range(2), false, offs))) return r;
+            }
             if (part1 < cut[1]) {
                 if (!wait_slot(ns, 1)) return fail(FB_EHIP, "lfmmi_loss_grad: stream wait on a value failed");
                 if ((r = run_posteriors(q, 2, lengths, B, N, D, grad, ns, slot_range(1), false, offs))) return r;

@@ -347,6 +347,8 @@ struct RecDir {
 
 constexpr int kDoneCuts = 4;       // progress counters of a recursion launch: kDoneCuts + 1 parts by rank, the first uncounted
 constexpr int kDoneStarted = 8;    // index of the `started` word in the counter block (which launch_order clears)
+constexpr int kDoneNum = 6;        // ... of the word that is set when the numerator launch of an LF-MMI call has ended
+constexpr int kDoneFused = 16;     // ... of the word PostParams::fused of the call's second range (written before it is read)
 
 struct RecParams {
     RecDir dir[2];
@@ -401,6 +403,10 @@ struct PostParams {
     const double *logz;
     int32_t accumulate;    // one packed graph: its pdf posteriors are added to the rows pdf_out already holds (only the
                            // entries of pdfs the sequence's graph uses are touched; padded frames are left alone)
+    // A word on the device (nullable), written by launch_decide before the launch: whether the second graph's vectors
+    // were complete when the launch was released.  Gradient kernel over two graphs: 0 = leave the second graph's
+    // share out (a later launch in accumulate mode adds it); that later launch: not 0 = nothing is left to add.
+    const int32_t *fused;
 };
 
 int launch_recursion(int nw, bool f64, bool tropical, const RecParams &p, size_t lds_bytes, void *stream);
@@ -426,6 +432,8 @@ int launch_num_add(const PostParams &p, void *stream);
 // order[r] = index of the sequence of rank r when sorted by length (clamped to [0, N]), longest first, equal
 // lengths by index
 int launch_delay(void *stream);   // an empty kernel: what follows on the stream starts a launch latency later
+int launch_decide(const uint32_t *count, uint32_t need, int32_t *flag, void *stream);   // *flag = *count >= need, on the device
+int launch_mark(uint32_t *word, void *stream);   // *word = 1 when the stream gets there
 int launch_order(const int32_t *lengths, int32_t B, int32_t N, int32_t *order, uint32_t *done, void *stream);   // done: four words to clear, or nullptr
 int launch_loss(const double *logz_num, const double *logz_den, const int32_t *lengths, int32_t B, double *loss,
                 void *stream);

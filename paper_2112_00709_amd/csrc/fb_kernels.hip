@@ -1766,7 +1766,9 @@ __global__ __launch_bounds__(kGradThreads, 4) void fb_grad_kernel(const PostPara
     const int T = min(max(P.lengths[b], 0), P.N);
     const int n0 = blockIdx.x * P.frames_per_block;
     const int n_end = min(min(n0 + P.frames_per_block, P.N), T);   // real frames of this chunk: [n0, n_end)
-    const bool has_num = P.n_graph == 2;   // one graph: the shared graph's share alone (no numerators: wave 7 only keeps the barriers)
+    // one graph, or a second graph whose vectors were not complete when the launch was released (PostParams::fused):
+    // the shared graph's share alone (no numerators: wave 7 only keeps the barriers)
+    const bool has_num = P.n_graph == 2 && (!P.fused || *P.fused != 0);
     const PostGraph &G0 = P.g[0], &G1 = P.g[1];
     const int K0 = G0.pdfs.sub[0].K, D = P.D;
     const int K0r = ((K0 + 3) & ~3) + kGradSlack;
@@ -1982,7 +1984,10 @@ __global__ __launch_bounds__(kGradThreads, 4) void fb_grad_kernel(const PostPara
                         for (int i = begin + kGradAhead; i < end; ++i) acc += tbn[i];
                     if (few)
                         for (int o = 1; o < tpp; o <<= 1) acc += __shfl_xor(acc, o, kWave);   // the parts of a pdf, in a fixed order
+                    // (a product and a sum, each rounded: the bits a launch of the denominator's share followed by one
+                    // that adds the numerators' gives, whichever of the two ways a call takes)
                     float v = acc * scale;
+                    asm volatile("" : "+v"(v));   // (kept a product of its own: not merged with the sum into one rounding)
                     if (r[jj]) v += nvv[jj];
                     if (few ? (d < D && (tid & (tpp - 1)) == 0 && jj == 0) : d < D) __builtin_nontemporal_store(v, prow + d);
                 }
@@ -2081,6 +2086,7 @@ __global__ __launch_bounds__(kWave) void fb_num_add_kernel(const PostParams P)
     const int n0 = blockIdx.x * P.frames_per_block;
     const int n_end = min(n0 + P.frames_per_block, T);   // real frames of this chunk: [n0, n_end)
     if (n0 >= n_end) return;
+    if (P.fused && *P.fused != 0) return;   // the launch before this one has added this graph's share already
     const PostGraph &G1 = P.g[0];
     const PdfSub ps1 = G1.pdfs.sub[b];
     const int K1 = ps1.K, R1 = ps1.n_rows;
@@ -2135,7 +2141,9 @@ __global__ __launch_bounds__(kWave) void fb_num_add_kernel(const PostParams P)
             if (r < R1) {
                 float acc = 0.0f;
                 for (int i = nptr[r]; i < nptr[r + 1]; ++i) acc += en[nst[i]];
-                prow[npdf[r]] += acc * scale;
+                float share = acc * scale;
+                asm volatile("" : "+v"(share));   // (rounded as the gradient kernel's last wave rounds it, then added)
+                prow[npdf[r]] += share;
             }
         }
     }
@@ -2425,6 +2433,29 @@ int launch_num_add(const PostParams &p, void *stream)
 
 // Does nothing: a launch whose only effect is that what follows it on its stream starts one launch latency later.
 __global__ __launch_bounds__(64) void fb_delay_kernel() {}
+
+// *flag = whether the counter has reached `need` (a progress counter of a launch that may still be running)
+__global__ __launch_bounds__(64) void fb_decide_kernel(const uint32_t *count, uint32_t need, int32_t *flag)
+{
+    if (threadIdx.x == 0) *flag = *(const volatile uint32_t *)count >= need ? 1 : 0;
+}
+
+__global__ __launch_bounds__(64) void fb_mark_kernel(uint32_t *word)
+{
+    if (threadIdx.x == 0) *word = 1u;
+}
+
+int launch_mark(uint32_t *word, void *stream)
+{
+    hipLaunchKernelGGL(fb_mark_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, word);
+    return check_launch("mark kernel launch");
+}
+
+int launch_decide(const uint32_t *count, uint32_t need, int32_t *flag, void *stream)
+{
+    hipLaunchKernelGGL(fb_decide_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, count, need, flag);
+    return check_launch("decide kernel launch");
+}
 
 int launch_delay(void *stream)
 {
